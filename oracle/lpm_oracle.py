@@ -1,0 +1,448 @@
+"""fp64 CPU oracle for the partitioned training step (layers, loss, backward, update, plan, schedules).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the benchmark's
+cpu_baseline leg.  The product path never calls it, and it imports nothing from the GPU
+package.  It shares no code with the HIP sources.
+
+What it computes is plain mini-batch backpropagation plus SGD, re-organised in time:
+  * layers            a^{l+1} = g_l(a^l, p^l)                       (Problem Statement, eq. 1)
+  * loss              f(a^L, e), softmax cross-entropy              (Problem Statement, eq. 3; Results section)
+  * backward          chain rule for parameter/activation gradients (Problem Statement, eqs. 8-9)
+  * update            p <- p - alpha * omega                        (Problem Statement, eq. 6)
+  * partitions        stacks of consecutive layers (sub-modules)    (Layer-wise Partitioning and Merging)
+  * cost              additive over the F_{i,j}, B_{i,j} operations (Cost Model, eq. 10)
+  * schedules         locked F_1..F_n then B_n..B_1; overlapped F/B of different micro-batches,
+                      gradient accumulation and one update per mini-batch
+                      (Forward Pass and Backward Pass Parallelisation and Optimisation)
+
+Convolution and pooling loops are the C routines of lpm_oracle.c (direct fp64 loops);
+everything else is numpy in float64.  Layouts are logical: activations [N][C][H][W],
+weights [Cout][Cin][Kh][Kw].  Layers are the plain dicts of workloads.configs.
+
+Readings taken where the paper is silent are listed next to each function.
+"""
+import ctypes
+import itertools
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "liblpm_oracle.so")
+_SRC = os.path.join(_HERE, "lpm_oracle.c")
+
+
+def build(force=False):
+    """Compile lpm_oracle.c (gcc -O2 -fopenmp) into liblpm_oracle.so next to it."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-o", _SO, _SRC])
+    return _SO
+
+
+_lib = None
+
+
+def _c():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+# --------------------------------------------------------------------------- layers
+
+def _oshape(l):
+    k = l["kind"]
+    if k == "conv":
+        return (l["cout"], (l["h_in"] + 2 * l["pad"] - l["kh"]) // l["stride"] + 1,
+                (l["w_in"] + 2 * l["pad"] - l["kw"]) // l["stride"] + 1)
+    if k in ("fc",):
+        return (l["cout"], 1, 1)
+    if k == "maxpool2":
+        return (l["cin"], l["h_in"] // 2, l["w_in"] // 2)
+    return (l["cin"], 1, 1)          # gap, softmax_ce
+
+
+def _geom(l):
+    """(Cin,H,W,Cout,Kh,Kw,stride,pad); an fc layer is a conv whose kernel covers its whole input."""
+    if l["kind"] == "fc":
+        return l["cin"], l["h_in"], l["w_in"], l["cout"], l["h_in"], l["w_in"], 1, 0
+    return l["cin"], l["h_in"], l["w_in"], l["cout"], l["kh"], l["kw"], l["stride"], l["pad"]
+
+
+def conv_fwd(x, W, l):
+    Cin, H, Wd, Cout, Kh, Kw, s, p = _geom(l)
+    x = _f64(x).reshape(-1, Cin, H, Wd)
+    N = x.shape[0]
+    z = np.empty((N,) + _oshape(l))
+    _c().orc_conv_fwd(_p(x), _p(_f64(W)), _p(z), N, Cin, H, Wd, Cout, Kh, Kw, s, p)
+    return z
+
+
+def conv_bwd_data(dz, W, l):
+    Cin, H, Wd, Cout, Kh, Kw, s, p = _geom(l)
+    dz = _f64(dz)
+    N = dz.shape[0]
+    dx = np.empty((N, Cin, H, Wd))
+    _c().orc_conv_bwd_data(_p(dz), _p(_f64(W)), _p(dx), N, Cin, H, Wd, Cout, Kh, Kw, s, p)
+    return dx
+
+
+def conv_bwd_weight(x, dz, l):
+    Cin, H, Wd, Cout, Kh, Kw, s, p = _geom(l)
+    x = _f64(x).reshape(-1, Cin, H, Wd)
+    dz = _f64(dz)
+    dW = np.empty((Cout, Cin, Kh, Kw))
+    _c().orc_conv_bwd_weight(_p(x), _p(dz), _p(dW), x.shape[0], Cin, H, Wd, Cout, Kh, Kw, s, p)
+    return dW
+
+
+def maxpool2_fwd(x):
+    x = _f64(x)
+    N, C, H, W = x.shape
+    y = np.empty((N, C, H // 2, W // 2))
+    _c().orc_maxpool2_fwd(_p(x), _p(y), N, C, H, W)
+    return y
+
+
+def maxpool2_bwd(x, dy):
+    """Gradient goes to the first maximum of each window (row-major inside the window)."""
+    x, dy = _f64(x), _f64(dy)
+    N, C, H, W = x.shape
+    dx = np.empty_like(x)
+    _c().orc_maxpool2_bwd(_p(x), _p(dy), _p(dx), N, C, H, W)
+    return dx
+
+
+def softmax_ce(logits, labels, batch_total):
+    """Per-call partial of the mini-batch mean loss and its gradient.
+
+    loss_partial = (1/b) * sum_n -log softmax(logits_n)[e_n];  dlogits = (softmax - onehot)/b,
+    with b = batch_total, the size of the WHOLE mini-batch (reading: the loss is the mean over
+    the mini-batch b_t of eq. 7, so gradients of micro-batches add up to the mini-batch gradient).
+    """
+    z = _f64(logits).reshape(len(labels), -1)
+    zs = z - z.max(axis=1, keepdims=True)
+    lse = np.log(np.exp(zs).sum(axis=1))
+    rows = np.arange(z.shape[0])
+    loss = float((lse - zs[rows, labels]).sum() / batch_total)
+    d = np.exp(zs - lse[:, None])
+    d[rows, labels] -= 1.0
+    return loss, (d / batch_total).reshape(np.shape(logits))
+
+
+# --------------------------------------------------------------------------- a stage (sub-module)
+
+def stage_forward(layers, first, last, params, a_in, labels=None, batch_total=None):
+    """F_{z,j}: evaluate layers [first,last) on one micro-batch.
+
+    a_in is tensor first-1 (the activation handed over by the previous sub-module, or the
+    network input).  Returns (a_out, stash, loss_partial): the stash maps tensor index ->
+    value for every tensor backward needs (first-1 .. last-1); if the stage ends in the loss
+    layer, a_out is the logits and stash['dlogits'] holds the loss gradient.
+    """
+    T = {first - 1: _f64(a_in)}
+    loss = None
+    for i in range(first, last):
+        l = layers[i]
+        x = T[l["src"]]
+        k = l["kind"]
+        if k in ("conv", "fc"):
+            p = params[i]
+            z = conv_fwd(x, p["W"], l)
+            if l["scale"]:
+                z = z * p["s"][None, :, None, None]
+            if l["bias"]:
+                z = z + p["b"][None, :, None, None]
+            if l["add_src"] is not None:
+                z = z + T[l["add_src"]]
+            T[i] = np.maximum(z, 0.0) if l["relu"] else z
+        elif k == "maxpool2":
+            T[i] = maxpool2_fwd(x)
+        elif k == "gap":
+            T[i] = x.mean(axis=(2, 3), keepdims=True)
+        elif k == "softmax_ce":
+            loss, T["dlogits"] = softmax_ce(x, labels, batch_total)
+            T[i] = x
+        else:
+            raise ValueError(k)
+    return T[last - 1], T, loss
+
+
+def stage_backward(layers, first, last, params, stash, g_out, grads, input_grad=None):
+    """B_{z,j}: reverse pass over layers [first,last) for one micro-batch.
+
+    g_out is the gradient w.r.t. the stage output (None for a stage ending in the loss layer).
+    Parameter gradients are ADDED into grads[i]['W'|'b'] (gradient accumulation over
+    micro-batches).  Returns the gradient w.r.t. tensor first-1; by default None when first == 0
+    (the network input needs no gradient); input_grad=True forces it, for a partition whose input
+    is an upstream activation.  ReLU'(0) = 0 (mask is y > 0).
+    """
+    G = {}
+    if input_grad is None:
+        input_grad = first > 0
+
+    def acc(t, g):
+        G[t] = g if t not in G else G[t] + g
+
+    if layers[last - 1]["kind"] == "softmax_ce":
+        acc(last - 1, stash["dlogits"])
+    else:
+        acc(last - 1, _f64(g_out))
+    for i in range(last - 1, first - 1, -1):
+        l = layers[i]
+        g = G.pop(i)
+        k = l["kind"]
+        src = l["src"]
+        if k in ("conv", "fc"):
+            p = params[i]
+            gm = g * (stash[i] > 0.0) if l["relu"] else g
+            if l["add_src"] is not None:
+                acc(l["add_src"], gm)
+            if l["bias"]:
+                grads[i]["b"] += gm.sum(axis=(0, 2, 3))
+            dz = gm * p["s"][None, :, None, None] if l["scale"] else gm
+            grads[i]["W"] += conv_bwd_weight(stash[src], dz, l)
+            if src >= first or input_grad:
+                acc(src, conv_bwd_data(dz, p["W"], l).reshape(stash[src].shape))
+        elif k == "maxpool2":
+            acc(src, maxpool2_bwd(stash[src], g))
+        elif k == "gap":
+            x = stash[src]
+            acc(src, np.broadcast_to(g / (x.shape[2] * x.shape[3]), x.shape).copy())
+        elif k == "softmax_ce":
+            acc(src, g)
+    return G.get(first - 1) if input_grad else None
+
+
+def zero_grads(layers, params):
+    return {i: {k: np.zeros_like(v) for k, v in p.items() if k != "s"} for i, p in params.items()}
+
+
+def sgd_momentum(params, grads, momentum, lr, mu, first=0, last=None):
+    """v <- mu*v + g ; p <- p - lr*v  for the trainable tensors of layers [first,last), in place.
+
+    With mu = 0 this is eq. 6, p <- p - alpha*omega.  The momentum form (no dampening, no
+    Nesterov, no weight decay) is this build's reading: the paper's update has no momentum term.
+    The frozen per-channel scale 's' is never updated.
+    """
+    for i, p in params.items():
+        if i < first or (last is not None and i >= last):
+            continue
+        for k in ("W", "b"):
+            if k in p:
+                momentum[i][k] = mu * momentum[i][k] + grads[i][k]
+                p[k] = p[k] - lr * momentum[i][k]
+
+
+# --------------------------------------------------------------------------- schedules
+
+LOCKED, OVERLAPPED = 0, 1
+
+
+def schedule_ops(Z, M, mode, window=2):
+    """Operation set and dependency map of one mini-batch step.
+
+    Ops are ('F',z,j), ('B',z,j), ('U',z).  Returns {op: set(prerequisite ops)}.
+    LOCKED: a single chain  F_{0,j}..F_{Z-1,j}, B_{Z-1,j}..B_{0,j}  for j = 0..M-1, then U_0..U_{Z-1}
+    (the non-parallel schedule).  OVERLAPPED (reading of the parallel schedule):
+      F_{z,j} after F_{z-1,j} and F_{z,j-1};  B_{z,j} after B_{z+1,j} (or F_{Z-1,j} for the last
+      stage) and B_{z,j-1} (fixed accumulation order);  window: F_{z,j+window} after B_{z,j}
+      (with window 2 this is "B_{0,0} finishes before F_{0,2}");  U_z after B_{z,M-1}.
+    """
+    deps = {}
+    if mode == LOCKED:
+        chain = []
+        for j in range(M):
+            chain += [("F", z, j) for z in range(Z)] + [("B", z, j) for z in range(Z - 1, -1, -1)]
+        chain += [("U", z) for z in range(Z)]
+        for a, b in zip([None] + chain[:-1], chain):
+            deps[b] = set() if a is None else {a}
+        return deps
+    for j in range(M):
+        for z in range(Z):
+            d = set()
+            if z > 0:
+                d.add(("F", z - 1, j))
+            if j > 0:
+                d.add(("F", z, j - 1))
+            if j >= window:
+                d.add(("B", z, j - window))
+            deps[("F", z, j)] = d
+            d = {("B", z + 1, j)} if z < Z - 1 else {("F", Z - 1, j)}
+            if j > 0:
+                d.add(("B", z, j - 1))
+            deps[("B", z, j)] = d
+    for z in range(Z):
+        deps[("U", z)] = {("B", z, M - 1)}
+    return deps
+
+
+def legal_order(deps, rng=None):
+    """One topological order of deps; random among the ready ops when rng (numpy Generator) is given,
+    else the first ready op in sorted order."""
+    done, order = set(), []
+    remaining = dict(deps)
+    while remaining:
+        ready = sorted(op for op, d in remaining.items() if d <= done)
+        assert ready, "dependency cycle"
+        op = ready[int(rng.integers(len(ready)))] if rng is not None else ready[0]
+        order.append(op)
+        done.add(op)
+        del remaining[op]
+    return order
+
+
+def run_schedule(layers, starts, params, momentum, x, labels, g_up, M, lr, mu, mode=LOCKED, window=2,
+                 order_rng=None, keep=False, input_grad=False):
+    """Execute one mini-batch step under a schedule; returns dict(loss, grads, [acts, gins]).
+
+    The batch is split in order into M contiguous micro-batches; per-micro-batch gradients are
+    summed; every stage is updated once, after its last backward.  Ops run in a legal topological
+    order of schedule_ops (randomised when order_rng is given) and every dependency, the
+    in-flight window and the stash-slot discipline (slot j mod window is never overwritten while
+    its micro-batch is still awaiting backward) are asserted as they run.
+    params and momentum are updated in place.
+    """
+    Z = len(starts) - 1
+    b = x.shape[0]
+    assert b % M == 0
+    m = b // M
+    deps = schedule_ops(Z, M, mode, window)
+    order = legal_order(deps, order_rng)
+    grads = zero_grads(layers, params)
+    slots = [[None] * window for _ in range(Z)]          # slot -> (j, stash)
+    act = {}                                             # (z,j) -> activation handed to stage z+1
+    gin = {}                                             # (z,j) -> gradient handed to stage z-1
+    done = set()
+    loss = 0.0
+    acts_keep, gins_keep = {}, {}
+    for op in order:
+        assert deps[op] <= done, ("dependency violated", op)
+        if op[0] == "F":
+            _, z, j = op
+            a_in = x[j * m:(j + 1) * m] if z == 0 else act[(z - 1, j)]
+            lab = labels[j * m:(j + 1) * m] if (labels is not None and z == Z - 1) else None
+            a_out, stash, lp = stage_forward(layers, starts[z], starts[z + 1], params, a_in, lab, b)
+            s = j % window
+            assert slots[z][s] is None, ("stash slot overwritten while live", op)
+            assert sum(e is not None for e in slots[z]) < window
+            slots[z][s] = (j, stash)
+            act[(z, j)] = a_out
+            if lp is not None:
+                loss += lp
+            if keep:
+                acts_keep[(z, j)] = stash
+        elif op[0] == "B":
+            _, z, j = op
+            s = j % window
+            assert slots[z][s] is not None and slots[z][s][0] == j, ("stash missing", op)
+            if z == Z - 1:
+                g_out = None if labels is not None else g_up[j * m:(j + 1) * m]
+            else:
+                g_out = gin[(z + 1, j)]
+            g = stage_backward(layers, starts[z], starts[z + 1], params, slots[z][s][1], g_out, grads,
+                               input_grad=(z > 0 or input_grad))
+            slots[z][s] = None
+            gin[(z, j)] = g
+            if keep:
+                gins_keep[(z, j)] = g
+        else:
+            _, z = op
+            sgd_momentum(params, grads, momentum, lr, mu, starts[z], starts[z + 1])
+        done.add(op)
+    out = dict(loss=loss, grads=grads, order=order)
+    if keep:
+        out["stash"], out["gin"] = acts_keep, gins_keep
+    return out
+
+
+# --------------------------------------------------------------------------- cost model and plan
+
+def layer_cost(layers, i, m, M, elem_bytes, flop_per_us, hbm_byte_per_us):
+    """Integer cost (picoseconds) of F+B of layer i on one micro-batch of m images plus 1/M of its update.
+
+    Reading of the cost functions T(F_{i,j}), T(B_{i,j}) of eq. 10, which the paper leaves opaque:
+    the larger of arithmetic time and ideal memory-traffic time,
+        c = max( flop*1e6 // flop_per_us ,  (M*byte_fb + byte_upd)*1e6 // (M*hbm_byte_per_us) )
+    flop      = 2*MAC*m*(3 passes, or 2 if the layer reads the network input: no data gradient)
+    byte_fb   = forward (in + out [+ shortcut] + W) + backward (dout + stashed in + din [+ dshortcut]
+                + W + fp32 dW read and write)
+    byte_upd  = P*(20 [+2 for the low-precision weight copy])   (P = trainable parameters)
+    All quantities are integers derived from the descriptor, so plans are reproducible bit for bit.
+    """
+    l = layers[i]
+    e = elem_bytes
+    cin, h, w = l["cin"], l["h_in"], l["w_in"]
+    co, ho, wo = _oshape(l)
+    in_el, out_el = cin * h * w, co * ho * wo
+    has_w = l["kind"] in ("conv", "fc")
+    kh, kw = (l["h_in"], l["w_in"]) if l["kind"] == "fc" else (l["kh"], l["kw"])
+    w_el = co * cin * kh * kw if has_w else 0
+    p_el = w_el + (co if (has_w and l["bias"]) else 0)
+    mac = out_el * cin * kh * kw if has_w else 0
+    first = l["src"] < 0
+    flop = 2 * mac * m * (2 if first else 3)
+    sc = out_el if l.get("add_src") is not None else 0
+    fwd = (in_el + out_el + sc) * m * e + w_el * e
+    bwd = (out_el + in_el + (0 if first else in_el) + sc) * m * e + w_el * e + 8 * w_el
+    upd = p_el * (20 + (2 if e == 2 else 0))
+    t_flop = flop * 1000000 // flop_per_us
+    t_byte = ((fwd + bwd) * M + upd) * 1000000 // (M * hbm_byte_per_us)
+    return max(t_flop, t_byte)
+
+
+def boundary_bytes(layers, i, m, elem_bytes):
+    """Bytes of the activation crossing a cut placed after layer i, for one micro-batch."""
+    co, ho, wo = _oshape(layers[i])
+    return co * ho * wo * m * elem_bytes
+
+
+def plan_cost(layers, starts, cp):
+    """(per-stage costs, total boundary bytes) of a plan.  cp: dict with flop_per_us, hbm_byte_per_us,
+    link_byte_per_us (0 = ignore transfers), elem_bytes, microbatch, n_microbatch.
+    A stage's cost is the sum of its layers' costs (eq. 10 is additive) plus, when link_byte_per_us > 0,
+    2*bytes*1e6 // link for each of its boundaries (activation forward and gradient backward)."""
+    m, M, e = cp["microbatch"], cp["n_microbatch"], cp["elem_bytes"]
+    c = [layer_cost(layers, i, m, M, e, cp["flop_per_us"], cp["hbm_byte_per_us"]) for i in range(len(layers))]
+    Z = len(starts) - 1
+    costs, tot = [], 0
+    for z in range(Z):
+        sc = sum(c[starts[z]:starts[z + 1]])
+        for cut in ([starts[z] - 1] if z > 0 else []) + ([starts[z + 1] - 1] if z < Z - 1 else []):
+            bb = boundary_bytes(layers, cut, m, e)
+            if cp.get("link_byte_per_us", 0) > 0:
+                sc += 2 * bb * 1000000 // cp["link_byte_per_us"]
+        costs.append(sc)
+    for z in range(1, Z):
+        tot += boundary_bytes(layers, starts[z] - 1, m, e)
+    return costs, tot
+
+
+def plan_bruteforce(layers, Z, cp):
+    """The plan by exhaustive enumeration: among all ways of cutting the layer list into Z non-empty
+    contiguous stages at allowed cut points, the one minimising, lexicographically,
+    (largest stage cost, total boundary bytes, starts).  Reading of the partition-and-merge objective:
+    eq. 10's plain sum does not depend on the cuts, so the bottleneck stage (which bounds a pipelined
+    step) is minimised first, then the communication volume merging is meant to reduce."""
+    L = len(layers)
+    allowed = [i + 1 for i in range(L - 1) if layers[i]["cut_after"]]
+    best = None
+    for cuts in itertools.combinations(allowed, Z - 1):
+        starts = [0] + list(cuts) + [L]
+        costs, bb = plan_cost(layers, starts, cp)
+        key = (max(costs), bb, starts)
+        if best is None or key < best[0]:
+            best = (key, starts, costs)
+    if best is None:
+        raise ValueError("no plan with %d stages" % Z)
+    return best[1], best[2]

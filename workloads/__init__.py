@@ -1,0 +1,11 @@
+"""Seeded synthetic inputs and layer lists for the benchmark workloads.
+
+This package holds *data descriptions only*: layer lists (plain dicts) and a
+counter-based random generator.  It contains none of the method's arithmetic and
+is the only module imported by both the CPU oracle's tests and the GPU binding's
+tests, so that both sides see identical inputs.
+"""
+from .rng import normal, uniform, integers, round_to_bf16          # noqa: F401
+from .configs import (lenet, vgg16_cifar, resnet18_cifar, r50_conv4x, vgg16_224,   # noqa: F401
+                      tiny_lenet, tiny_resnet, tiny_vgg, CONFIGS, out_shape, in_shape,
+                      param_shapes, make_params, make_batch, tensor_shapes)
