@@ -142,8 +142,25 @@ def softmax_ce(logits, labels, batch_total):
 
 # --------------------------------------------------------------------------- a stage (sub-module)
 
-def stage_forward(layers, first, last, params, a_in, labels=None, batch_total=None):
+def round_bf16(a):
+    """Nearest bfloat16 (ties to even) of every element, returned as float64.  Models the STORAGE
+    precision of the bf16 workloads; arithmetic stays fp64."""
+    f = np.ascontiguousarray(a, dtype=np.float64).astype(np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    lsb = (u >> np.uint64(16)) & np.uint64(1)
+    u = ((u + np.uint64(0x7FFF) + lsb) >> np.uint64(16)) << np.uint64(16)
+    return u.astype(np.uint32).view(np.float32).astype(np.float64).reshape(np.shape(a))
+
+
+def stage_forward(layers, first, last, params, a_in, labels=None, batch_total=None, store=None):
     """F_{z,j}: evaluate layers [first,last) on one micro-batch.
+
+    store: optional function applied to every layer output as it is stored (e.g. round_bf16).  The
+    bf16 workloads keep activations in bfloat16, and two decisions of the backward pass are taken on
+    stored values: the ReLU mask (y > 0) and the position of a pooling window's maximum.  Both sides
+    of a comparison must take them in the same precision, so for those workloads the oracle rounds
+    each stored activation once, exactly where the device stores it, and computes everything else in
+    fp64.  With store=None the oracle is the unrounded textbook computation.
 
     a_in is tensor first-1 (the activation handed over by the previous sub-module, or the
     network input).  Returns (a_out, stash, loss_partial): the stash maps tensor index ->
@@ -175,6 +192,8 @@ def stage_forward(layers, first, last, params, a_in, labels=None, batch_total=No
             T[i] = x
         else:
             raise ValueError(k)
+        if store is not None and k != "softmax_ce":
+            T[i] = store(T[i])
     return T[last - 1], T, loss
 
 
@@ -303,7 +322,7 @@ def legal_order(deps, rng=None):
 
 
 def run_schedule(layers, starts, params, momentum, x, labels, g_up, M, lr, mu, mode=LOCKED, window=2,
-                 order_rng=None, keep=False, input_grad=False):
+                 order_rng=None, keep=False, input_grad=False, store=None):
     """Execute one mini-batch step under a schedule; returns dict(loss, grads, [acts, gins]).
 
     The batch is split in order into M contiguous micro-batches; per-micro-batch gradients are
@@ -332,7 +351,7 @@ def run_schedule(layers, starts, params, momentum, x, labels, g_up, M, lr, mu, m
             _, z, j = op
             a_in = x[j * m:(j + 1) * m] if z == 0 else act[(z - 1, j)]
             lab = labels[j * m:(j + 1) * m] if (labels is not None and z == Z - 1) else None
-            a_out, stash, lp = stage_forward(layers, starts[z], starts[z + 1], params, a_in, lab, b)
+            a_out, stash, lp = stage_forward(layers, starts[z], starts[z + 1], params, a_in, lab, b, store)
             s = j % window
             assert slots[z][s] is None, ("stash slot overwritten while live", op)
             assert sum(e is not None for e in slots[z]) < window

@@ -1,0 +1,424 @@
+"""ctypes binding of liblpm.so: same names as the C ABI, argument marshalling only.
+
+PyTorch is used for device memory and streams; no torch operator takes part in the training step.
+The library is required: importing this module fails if liblpm.so has not been built
+(python -m paper_2207_11019_amd.build or __graft_entry__.build()).
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+__all__ = ["LpmError", "lib", "lpm_layer", "lpm_cost_params", "lpm_stage_buffers", "layers_from_dicts",
+           "lpm_layer_cost", "lpm_partition", "Stage", "Schedule", "Net", "F32", "BF16", "LOCKED", "OVERLAPPED",
+           "GRAPH", "pack_act", "unpack_act", "pack_weight", "unpack_weight", "MI355X_COST"]
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = os.path.join(_HERE, "liblpm.so")
+if not os.path.exists(_LIB):
+    raise ImportError("liblpm.so is missing: build it with `python -m paper_2207_11019_amd.build`")
+lib = C.CDLL(_LIB)
+
+F32, BF16 = 0, 1
+LOCKED, OVERLAPPED, GRAPH = 0, 1, 16
+KINDS = {"conv": 0, "fc": 1, "maxpool2": 2, "gap": 3, "softmax_ce": 4}
+RELU, BIAS, SCALE = 1, 2, 4
+NONE = -2
+MAX_WINDOW = 4
+
+
+class LpmError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("lpm error %d: %s" % (code, text))
+        self.code = code
+
+
+class lpm_layer(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("kind", "cin", "cout", "kh", "kw", "stride", "pad", "h_in", "w_in", "flags",
+                                         "src", "add_src", "cut_allowed_after")]
+
+
+class lpm_cost_params(C.Structure):
+    _fields_ = [("flop_per_us", C.c_uint64), ("hbm_byte_per_us", C.c_uint64), ("link_byte_per_us", C.c_uint64),
+                ("elem_bytes", C.c_int32), ("microbatch", C.c_int32), ("n_microbatch", C.c_int32)]
+
+
+class lpm_stage_buffers(C.Structure):
+    _fields_ = [("params", C.c_void_p), ("lowp", C.c_void_p), ("grads", C.c_void_p), ("momentum", C.c_void_p),
+                ("stash", C.c_void_p * MAX_WINDOW), ("act_out", C.c_void_p * MAX_WINDOW), ("grad_in", C.c_void_p),
+                ("fwd_ws", C.c_void_p), ("bwd_ws", C.c_void_p)]
+
+
+lib.lpm_last_error.restype = C.c_char_p
+_vp, _i32, _sz = C.c_void_p, C.c_int32, C.c_size_t
+_psz = C.POINTER(C.c_size_t)
+lib.lpm_layer_cost.argtypes = [C.POINTER(lpm_layer), _i32, _i32, C.POINTER(lpm_cost_params), C.POINTER(C.c_uint64)]
+lib.lpm_partition.argtypes = [C.POINTER(lpm_layer), _i32, _i32, C.POINTER(lpm_cost_params), C.POINTER(_i32),
+                              C.POINTER(_i32), C.POINTER(C.c_uint64)]
+lib.lpm_stage_create.argtypes = [C.POINTER(lpm_layer), _i32, _i32, _i32, _i32, _i32, C.POINTER(_vp)]
+lib.lpm_stage_destroy.argtypes = [_vp]
+lib.lpm_stage_sizes.argtypes = [_vp] + [_psz] * 8
+lib.lpm_stage_param_offset.argtypes = [_vp, _i32, _i32, _psz, _psz]
+lib.lpm_stage_stash_offset.argtypes = [_vp, _i32, _psz, _psz]
+lib.lpm_stage_grad_offset.argtypes = [_vp, _i32, _psz, _psz]
+lib.lpm_stage_sync_lowp.argtypes = [_vp, _vp, _vp, _vp]
+lib.lpm_stage_forward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, C.c_float, _vp]
+lib.lpm_stage_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]
+lib.lpm_stage_update.argtypes = [_vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _i32, _vp]
+lib.lpm_schedule_create.argtypes = [C.POINTER(_vp), _i32, _i32, _i32, C.POINTER(_vp)]
+lib.lpm_schedule_destroy.argtypes = [_vp]
+lib.lpm_schedule_run.argtypes = [_vp, _i32, _vp, _vp, _vp, C.POINTER(lpm_stage_buffers), _i32, C.c_float, C.c_float,
+                                 _vp, _vp, _vp]
+for _f in ("lpm_layer_cost", "lpm_partition", "lpm_stage_create", "lpm_stage_destroy", "lpm_stage_sizes",
+           "lpm_stage_param_offset", "lpm_stage_stash_offset", "lpm_stage_grad_offset", "lpm_stage_sync_lowp",
+           "lpm_stage_forward", "lpm_stage_backward", "lpm_stage_update", "lpm_schedule_create",
+           "lpm_schedule_destroy", "lpm_schedule_run"):
+    getattr(lib, _f).restype = C.c_int32
+
+# public MI355X figures used as cost-model parameters: 2.5166 PFLOP/s bf16 MFMA, 157.3 TFLOP/s fp32, 8 TB/s HBM
+MI355X_COST = {"bf16": dict(flop_per_us=2_516_582_400, hbm_byte_per_us=8_000_000, elem_bytes=2),
+               "f32": dict(flop_per_us=157_286_400, hbm_byte_per_us=8_000_000, elem_bytes=4)}
+
+
+def _check(rc):
+    if rc != 0:
+        raise LpmError(rc, lib.lpm_last_error().decode())
+
+
+def layers_from_dicts(layers):
+    """list of layer dicts (see workloads.configs) -> ctypes array of lpm_layer."""
+    arr = (lpm_layer * len(layers))()
+    for i, l in enumerate(layers):
+        flags = (RELU if l.get("relu") else 0) | (BIAS if l.get("bias") else 0) | (SCALE if l.get("scale") else 0)
+        add = l.get("add_src")
+        arr[i] = lpm_layer(KINDS[l["kind"]], l["cin"], l["cout"], l["kh"], l["kw"], l["stride"], l["pad"], l["h_in"],
+                           l["w_in"], flags, l["src"], NONE if add is None else add, 1 if l.get("cut_after") else 0)
+    return arr
+
+
+def _as_layers(layers):
+    return layers if isinstance(layers, C.Array) else layers_from_dicts(layers)
+
+
+def _cp(cp):
+    return lpm_cost_params(cp["flop_per_us"], cp["hbm_byte_per_us"], cp.get("link_byte_per_us", 0), cp["elem_bytes"],
+                           cp["microbatch"], cp["n_microbatch"])
+
+
+def lpm_layer_cost(layers, i, cp):
+    arr = _as_layers(layers)
+    out = C.c_uint64()
+    c = _cp(cp)
+    _check(lib.lpm_layer_cost(arr, len(arr), i, C.byref(c), C.byref(out)))
+    return out.value
+
+
+def lpm_partition(layers, Z, cp, fixed_starts=None):
+    """-> (starts[Z+1], stage_cost[Z])"""
+    arr = _as_layers(layers)
+    c = _cp(cp)
+    starts = (C.c_int32 * (Z + 1))()
+    cost = (C.c_uint64 * Z)()
+    fixed = None
+    if fixed_starts is not None:
+        if len(fixed_starts) != Z + 1:
+            raise LpmError(-1, "fixed_starts needs Z+1 entries")
+        fixed = (C.c_int32 * (Z + 1))(*fixed_starts)
+    _check(lib.lpm_partition(arr, len(arr), Z, C.byref(c), fixed, starts, cost))
+    return list(starts), list(cost)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(s):
+    if s is None:
+        return None
+    return s if isinstance(s, int) else s.cuda_stream
+
+
+class Stage:
+    """lpm_stage handle; methods are the lpm_stage_* calls."""
+
+    def __init__(self, layers, first, last, microbatch, dtype):
+        self._arr = _as_layers(layers)
+        self.first, self.last, self.m, self.dtype = first, last, microbatch, dtype
+        h = C.c_void_p()
+        _check(lib.lpm_stage_create(self._arr, len(self._arr), first, last, microbatch, dtype, C.byref(h)))
+        self.h = h
+        v = [C.c_size_t() for _ in range(8)]
+        _check(lib.lpm_stage_sizes(self.h, *[C.byref(x) for x in v]))
+        (self.param_bytes, self.lowp_bytes, self.grad_bytes, self.stash_bytes, self.fwd_ws_bytes, self.bwd_ws_bytes,
+         self.in_bytes, self.out_bytes) = [x.value for x in v]
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib.lpm_stage_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+    def param_offset(self, layer, which):
+        o, n = C.c_size_t(), C.c_size_t()
+        _check(lib.lpm_stage_param_offset(self.h, layer, which, C.byref(o), C.byref(n)))
+        return o.value, n.value
+
+    def has_param(self, layer, which):
+        o, n = C.c_size_t(), C.c_size_t()
+        return lib.lpm_stage_param_offset(self.h, layer, which, C.byref(o), C.byref(n)) == 0
+
+    def stash_offset(self, t):
+        o, n = C.c_size_t(), C.c_size_t()
+        _check(lib.lpm_stage_stash_offset(self.h, t, C.byref(o), C.byref(n)))
+        return o.value, n.value
+
+    def grad_offset(self, t):
+        o, n = C.c_size_t(), C.c_size_t()
+        _check(lib.lpm_stage_grad_offset(self.h, t, C.byref(o), C.byref(n)))
+        return o.value, n.value
+
+    def sync_lowp(self, params, lowp, stream=None):
+        _check(lib.lpm_stage_sync_lowp(self.h, _ptr(params), _ptr(lowp), _stream(stream)))
+
+    def forward(self, x, y, labels, loss_accum, params, lowp, stash, fwd_ws, loss_scale, stream=None):
+        _check(lib.lpm_stage_forward(self.h, _ptr(x), _ptr(y), _ptr(labels), _ptr(loss_accum), _ptr(params), _ptr(lowp),
+                                     _ptr(stash), _ptr(fwd_ws), loss_scale, _stream(stream)))
+
+    def backward(self, x, y, dy, dx, params, lowp, stash, grads, accumulate, bwd_ws, stream=None):
+        _check(lib.lpm_stage_backward(self.h, _ptr(x), _ptr(y), _ptr(dy), _ptr(dx), _ptr(params), _ptr(lowp), _ptr(stash),
+                                      _ptr(grads), int(accumulate), _ptr(bwd_ws), _stream(stream)))
+
+    def update(self, params, lowp, grads, momentum, lr, mu, zero_grads=False, stream=None):
+        _check(lib.lpm_stage_update(self.h, _ptr(params), _ptr(lowp), _ptr(grads), _ptr(momentum), lr, mu,
+                                    int(zero_grads), _stream(stream)))
+
+
+class Schedule:
+    """lpm_schedule handle."""
+
+    def __init__(self, stages, n_microbatch, window=2):
+        self.stages = stages
+        arr = (C.c_void_p * len(stages))(*[s.h for s in stages])
+        h = C.c_void_p()
+        _check(lib.lpm_schedule_create(arr, len(stages), n_microbatch, window, C.byref(h)))
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib.lpm_schedule_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+    def run(self, mode, x_batch, labels, dy_batch, per_stage, dx_wanted, lr, mu, loss_out, stream_fwd, stream_bwd):
+        _check(lib.lpm_schedule_run(self.h, mode, _ptr(x_batch), _ptr(labels), _ptr(dy_batch), per_stage, int(dx_wanted),
+                                    lr, mu, _ptr(loss_out), _stream(stream_fwd), _stream(stream_bwd)))
+
+
+# ------------------------------------------------------------------------------------------ layouts
+# Logical tensors (numpy, [N][C][H][W] and [Cout][Cin][Kh][Kw]) <-> device layouts ([m][H][W][C],
+# [Cout][Kh][Kw][Cin]).  Pure data movement.
+
+def _torch():
+    import torch
+    return torch
+
+
+def pack_act(a, dtype, device="cuda:0"):
+    torch = _torch()
+    t = torch.from_numpy(np.ascontiguousarray(np.transpose(np.asarray(a, dtype=np.float32), (0, 2, 3, 1))))
+    return t.to(device=device, dtype=torch.bfloat16 if dtype == BF16 else torch.float32).contiguous()
+
+
+def unpack_act(t, shape_nchw):
+    n, c, h, w = shape_nchw
+    return np.transpose(t.float().cpu().numpy().reshape(n, h, w, c), (0, 3, 1, 2)).astype(np.float64)
+
+
+def pack_weight(w):
+    return np.ascontiguousarray(np.transpose(np.asarray(w, dtype=np.float32), (0, 2, 3, 1))).reshape(-1)
+
+
+def unpack_weight(flat, shape_oihw):
+    o, i, kh, kw = shape_oihw
+    return np.transpose(np.asarray(flat).reshape(o, kh, kw, i), (0, 3, 1, 2)).astype(np.float64)
+
+
+def _oshape(l):
+    k = l["kind"]
+    if k == "conv":
+        return (l["cout"], (l["h_in"] + 2 * l["pad"] - l["kh"]) // l["stride"] + 1,
+                (l["w_in"] + 2 * l["pad"] - l["kw"]) // l["stride"] + 1)
+    if k == "fc":
+        return (l["cout"], 1, 1)
+    if k == "maxpool2":
+        return (l["cin"], l["h_in"] // 2, l["w_in"] // 2)
+    return (l["cin"], 1, 1)
+
+
+def _wshape(l):
+    if l["kind"] == "fc":
+        return (l["cout"], l["cin"], l["h_in"], l["w_in"])
+    return (l["cout"], l["cin"], l["kh"], l["kw"])
+
+
+class Net:
+    """A partitioned network resident on one GPU: stages, their device buffers and a schedule.
+
+    layers: list of layer dicts; starts: plan (Z+1 entries); dtype F32/BF16.
+    """
+
+    def __init__(self, layers, starts, microbatch, n_microbatch, dtype, window=2, device="cuda:0", dx_wanted=False):
+        torch = _torch()
+        self.torch = torch
+        self.layers, self.starts, self.m, self.M, self.dtype, self.window = layers, list(starts), microbatch, n_microbatch, dtype, window
+        self.device = torch.device(device)
+        self.Z = len(starts) - 1
+        self.dx_wanted = dx_wanted
+        arr = layers_from_dicts(layers)
+        self.stages = [Stage(arr, starts[z], starts[z + 1], microbatch, dtype) for z in range(self.Z)]
+        self.schedule = Schedule(self.stages, n_microbatch, window)
+        self.tdtype = torch.bfloat16 if dtype == BF16 else torch.float32
+
+        def buf(nbytes, zero=True):
+            n = max(int(nbytes), 256)
+            t = torch.zeros(n, dtype=torch.uint8, device=self.device) if zero else torch.empty(n, dtype=torch.uint8, device=self.device)
+            assert t.data_ptr() % 256 == 0
+            return t
+
+        self.bufs = []
+        self.cbufs = (lpm_stage_buffers * self.Z)()
+        for z, s in enumerate(self.stages):
+            b = dict(params=buf(s.param_bytes), lowp=buf(s.lowp_bytes) if dtype == BF16 else None, grads=buf(s.grad_bytes),
+                     momentum=buf(s.grad_bytes), stash=[buf(s.stash_bytes) for _ in range(window)],
+                     act_out=[buf(s.out_bytes) for _ in range(window)],
+                     grad_in=buf(s.in_bytes) if (z > 0 or dx_wanted) else None,
+                     fwd_ws=buf(s.fwd_ws_bytes), bwd_ws=buf(s.bwd_ws_bytes))
+            self.bufs.append(b)
+            cb = self.cbufs[z]
+            cb.params, cb.lowp, cb.grads, cb.momentum = _ptr(b["params"]), _ptr(b["lowp"]), _ptr(b["grads"]), _ptr(b["momentum"])
+            for w in range(window):
+                cb.stash[w] = _ptr(b["stash"][w])
+                cb.act_out[w] = _ptr(b["act_out"][w])
+            cb.grad_in, cb.fwd_ws, cb.bwd_ws = _ptr(b["grad_in"]), _ptr(b["fwd_ws"]), _ptr(b["bwd_ws"])
+        self.loss = torch.zeros(64, dtype=torch.float32, device=self.device)
+        self.stream_fwd = torch.cuda.Stream(device=self.device)
+        self.stream_bwd = torch.cuda.Stream(device=self.device)
+
+    def stage_of(self, layer):
+        for z in range(self.Z):
+            if self.starts[z] <= layer < self.starts[z + 1]:
+                return z
+        raise IndexError(layer)
+
+    # ---- parameters: logical numpy dicts {layer: {'W','b','s'}} <-> packed device buffers
+    def _write(self, name, values, keys):
+        torch = self.torch
+        for z, s in enumerate(self.stages):
+            host = self.bufs[z][name].view(torch.float32).cpu().numpy().copy()
+            for i in range(s.first, s.last):
+                if i not in values:
+                    continue
+                for which, k in enumerate(("W", "b", "s")):
+                    if k in keys and k in values[i]:
+                        off, n = s.param_offset(i, which)
+                        v = pack_weight(values[i][k]) if k == "W" else np.asarray(values[i][k], dtype=np.float32)
+                        host[off:off + n] = v
+            self.bufs[z][name].view(torch.float32).copy_(torch.from_numpy(host))
+
+    def _read(self, name, keys):
+        torch = self.torch
+        out = {}
+        for z, s in enumerate(self.stages):
+            host = self.bufs[z][name].view(torch.float32).cpu().numpy()
+            for i in range(s.first, s.last):
+                l = self.layers[i]
+                if l["kind"] not in ("conv", "fc"):
+                    continue
+                d = {}
+                for which, k in enumerate(("W", "b", "s")):
+                    if k in keys and s.has_param(i, which):
+                        off, n = s.param_offset(i, which)
+                        d[k] = unpack_weight(host[off:off + n], _wshape(l)) if k == "W" else host[off:off + n].astype(np.float64)
+                out[i] = d
+        return out
+
+    def load_params(self, params, momentum=None):
+        self._write("params", params, ("W", "b", "s"))
+        if momentum is not None:
+            self._write("momentum", momentum, ("W", "b"))
+        if self.dtype == BF16:
+            for z, s in enumerate(self.stages):
+                s.sync_lowp(self.bufs[z]["params"], self.bufs[z]["lowp"], None)
+        self.torch.cuda.synchronize(self.device)
+
+    def read_params(self):
+        return self._read("params", ("W", "b", "s"))
+
+    def read_grads(self):
+        return self._read("grads", ("W", "b"))
+
+    def read_momentum(self):
+        return self._read("momentum", ("W", "b"))
+
+    # ---- tensors
+    def tensor_shape(self, t):
+        return _oshape(self.layers[t]) if t >= 0 else (self.layers[0]["cin"], self.layers[0]["h_in"], self.layers[0]["w_in"])
+
+    def read_stash(self, t, slot):
+        """Logical [m][C][H][W] value of internal tensor t from a stash slot."""
+        z = self.stage_of(t)
+        off, n = self.stages[z].stash_offset(t)
+        raw = self.bufs[z]["stash"][slot][off:off + n].view(self.tdtype)
+        return unpack_act(raw, (self.m,) + self.tensor_shape(t))
+
+    def read_act_out(self, z, slot):
+        s = self.stages[z]
+        t = s.last - 1 if self.layers[s.last - 1]["kind"] != "softmax_ce" else s.last - 2
+        n = s.out_bytes
+        return unpack_act(self.bufs[z]["act_out"][slot][:n].view(self.tdtype), (self.m,) + self.tensor_shape(t))
+
+    def _out_tensor(self, z):
+        s = self.stages[z]
+        return s.last - 1 if self.layers[s.last - 1]["kind"] != "softmax_ce" else s.last - 2
+
+    def write_stash(self, t, slot, value):
+        """Store a logical [m][C][H][W] array as internal tensor t of a stash slot (t = 'dlogits' for the
+        loss gradient).  For tests that hand a stage a prepared forward state."""
+        if t == "dlogits":
+            z = self.Z - 1
+            off, n = self.stages[z].stash_offset(-100)
+        else:
+            z = self.stage_of(t)
+            off, n = self.stages[z].stash_offset(t)
+        src = pack_act(value, self.dtype, self.device).reshape(-1).view(self.torch.uint8)
+        assert src.numel() == n, (src.numel(), n)
+        self.bufs[z]["stash"][slot][off:off + n].copy_(src)
+
+    def write_act_out(self, z, slot, value):
+        src = pack_act(value, self.dtype, self.device).reshape(-1).view(self.torch.uint8)
+        assert src.numel() == self.stages[z].out_bytes
+        self.bufs[z]["act_out"][slot][:src.numel()].copy_(src)
+
+    def read_grad_in(self, z):
+        s = self.stages[z]
+        return unpack_act(self.bufs[z]["grad_in"][:s.in_bytes].view(self.tdtype), (self.m,) + self.tensor_shape(s.first - 1))
+
+    # ---- one mini-batch step
+    def step(self, x_batch, labels, dy_batch, lr, mu, mode=OVERLAPPED):
+        """x_batch, labels, dy_batch: device tensors already in device layout (see pack_act)."""
+        torch = self.torch
+        cur = torch.cuda.current_stream(self.device)
+        self.stream_fwd.wait_stream(cur)
+        self.schedule.run(mode, x_batch, labels, dy_batch, self.cbufs, self.dx_wanted, lr, mu, self.loss,
+                          self.stream_fwd, self.stream_bwd)
+        cur.wait_stream(self.stream_fwd)
+
+    def loss_value(self):
+        self.torch.cuda.synchronize(self.device)
+        return float(self.loss[0].item())

@@ -1,0 +1,29 @@
+// Element load/store helpers: float or bfloat16 storage, float arithmetic.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+namespace lpm {
+
+struct bf16_t { uint16_t bits; };   // storage only
+
+__device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// round to nearest, ties to even; NaN stays NaN
+__device__ __forceinline__ uint16_t f2bf(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+}
+
+__device__ __forceinline__ float ld(const float* p, int64_t i) { return p[i]; }
+__device__ __forceinline__ float ld(const bf16_t* p, int64_t i) { return bf2f(p[i].bits); }
+__device__ __forceinline__ void st(float* p, int64_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void st(bf16_t* p, int64_t i, float v) { p[i].bits = f2bf(v); }
+
+}  // namespace lpm

@@ -1,0 +1,454 @@
+// Shape-generic kernels: every layer kind, any extent, float or bf16 elements.
+//
+// These are the fall-back contraction kernels (one thread per output element, fp32 accumulation)
+// used for the fp32 element type and for shapes the MFMA kernels do not cover, plus the
+// memory-bound kernels of the step: epilogue backward + bias gradient, pooling, loss, update.
+// Layouts: activations [m][H][W][C], weights [Cout][Kh][Kw][Cin].
+#include "lpm_internal.h"
+#include "elem.h"
+
+namespace lpm {
+
+#define LPM_DISPATCH(dtype, ...)                       \
+    do {                                               \
+        if ((dtype) == LPM_BF16) { typedef bf16_t T; __VA_ARGS__; } \
+        else { typedef float T; __VA_ARGS__; }         \
+    } while (0)
+
+static inline unsigned nblk(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
+
+// --------------------------------------------------------------------------------------------------
+// convolution forward, eq. 1 for a conv/FC layer:  y = relu?(scale*z + bias + add)
+template <typename T>
+__global__ void __launch_bounds__(256) conv_fwd_generic(ConvGeom g, const T* __restrict__ x, const T* __restrict__ w,
+                                                        const float* __restrict__ scale, const float* __restrict__ bias,
+                                                        const T* __restrict__ add, int relu, T* __restrict__ y) {
+    const int64_t total = g.rows_out() * g.Cout;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int co = (int)(idx % g.Cout);
+    const int64_t row = idx / g.Cout;
+    const int wo = (int)(row % g.Wo), ho = (int)((row / g.Wo) % g.Ho), n = (int)(row / ((int64_t)g.Wo * g.Ho));
+    float acc = 0.f;
+    for (int kh = 0; kh < g.Kh; ++kh) {
+        const int h = ho * g.stride + kh - g.pad;
+        if (h < 0 || h >= g.H) continue;
+        for (int kw = 0; kw < g.Kw; ++kw) {
+            const int ww = wo * g.stride + kw - g.pad;
+            if (ww < 0 || ww >= g.W) continue;
+            const T* xp = x + (((int64_t)n * g.H + h) * g.W + ww) * g.Cin;
+            const T* wp = w + (((int64_t)co * g.Kh + kh) * g.Kw + kw) * g.Cin;
+            for (int ci = 0; ci < g.Cin; ++ci) acc = fmaf(ld(xp, ci), ld(wp, ci), acc);
+        }
+    }
+    if (scale) acc *= scale[co];
+    if (bias) acc += bias[co];
+    if (add) acc += ld(add, idx);
+    if (relu) acc = fmaxf(acc, 0.f);
+    st(y, idx, acc);
+}
+
+hipError_t conv_fwd_generic_launch(int dtype, const ConvGeom& g, const void* x, const void* w, const float* scale,
+                                   const float* bias, const void* add, int relu, void* y, hipStream_t s) {
+    const int64_t total = g.rows_out() * g.Cout;
+    LPM_DISPATCH(dtype, hipLaunchKernelGGL(conv_fwd_generic<T>, dim3(nblk(total, 256)), dim3(256), 0, s, g, (const T*)x,
+                                           (const T*)w, scale, bias, (const T*)add, relu, (T*)y));
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------------------------
+// data gradient, eq. 9: dx[n,h,w,ci] (+)= sum_{kh,kw,co} dz[n,(h+p-kh)/s,(w+p-kw)/s,co] * w[co,kh,kw,ci]
+template <typename T>
+__global__ void __launch_bounds__(256) conv_dgrad_generic(ConvGeom g, const T* __restrict__ dz, const T* __restrict__ w,
+                                                          T* __restrict__ dx, int accumulate) {
+    const int64_t total = g.rows_in() * g.Cin;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int ci = (int)(idx % g.Cin);
+    const int64_t row = idx / g.Cin;
+    const int ww = (int)(row % g.W), h = (int)((row / g.W) % g.H), n = (int)(row / ((int64_t)g.W * g.H));
+    float acc = 0.f;
+    for (int kh = 0; kh < g.Kh; ++kh) {
+        const int hh = h + g.pad - kh;
+        if (hh < 0 || hh % g.stride) continue;
+        const int ho = hh / g.stride;
+        if (ho >= g.Ho) continue;
+        for (int kw = 0; kw < g.Kw; ++kw) {
+            const int wq = ww + g.pad - kw;
+            if (wq < 0 || wq % g.stride) continue;
+            const int wo = wq / g.stride;
+            if (wo >= g.Wo) continue;
+            const T* dp = dz + (((int64_t)n * g.Ho + ho) * g.Wo + wo) * g.Cout;
+            const T* wp = w + ((int64_t)kh * g.Kw + kw) * g.Cin + ci;
+            const int64_t wstride = (int64_t)g.Kh * g.Kw * g.Cin;
+            for (int co = 0; co < g.Cout; ++co) acc = fmaf(ld(dp, co), ld(wp, co * wstride), acc);
+        }
+    }
+    if (accumulate) acc += ld(dx, idx);
+    st(dx, idx, acc);
+}
+
+hipError_t conv_dgrad_generic_launch(int dtype, const ConvGeom& g, const void* dz, const void* w, void* dx,
+                                     int accumulate, hipStream_t s) {
+    const int64_t total = g.rows_in() * g.Cin;
+    LPM_DISPATCH(dtype, hipLaunchKernelGGL(conv_dgrad_generic<T>, dim3(nblk(total, 256)), dim3(256), 0, s, g,
+                                           (const T*)dz, (const T*)w, (T*)dx, accumulate));
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------------------------
+// weight gradient, eq. 8: dw[co,kh,kw,ci] (+)= sum_{n,ho,wo} dz[n,ho,wo,co] * x[n,ho*s+kh-p,wo*s+kw-p,ci]
+// The (n,ho) range is split into `chunks` slices (blockIdx.y); with more than one slice each writes a
+// partial to ws[chunk][Cout*K] and a second kernel adds the partials in slice order (no float atomics,
+// so the result does not depend on scheduling).
+template <typename T>
+__global__ void __launch_bounds__(256) conv_wgrad_generic(ConvGeom g, const T* __restrict__ x, const T* __restrict__ dz,
+                                                          float* __restrict__ out, int chunks, int accumulate) {
+    const int K = g.K();
+    const int64_t total = (int64_t)g.Cout * K;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int ci = (int)(idx % g.Cin);
+    const int kw = (int)((idx / g.Cin) % g.Kw), kh = (int)((idx / ((int64_t)g.Cin * g.Kw)) % g.Kh);
+    const int co = (int)(idx / K);
+    const int nho = g.m * g.Ho;
+    const int per = (nho + chunks - 1) / chunks;
+    const int r0 = blockIdx.y * per, r1 = min(nho, r0 + per);
+    float acc = 0.f;
+    for (int r = r0; r < r1; ++r) {
+        const int n = r / g.Ho, ho = r % g.Ho;
+        const int h = ho * g.stride + kh - g.pad;
+        if (h < 0 || h >= g.H) continue;
+        const T* dp = dz + ((int64_t)r * g.Wo) * g.Cout + co;
+        const T* xp = x + (((int64_t)n * g.H + h) * g.W) * g.Cin + ci;
+        for (int wo = 0; wo < g.Wo; ++wo) {
+            const int ww = wo * g.stride + kw - g.pad;
+            if (ww < 0 || ww >= g.W) continue;
+            acc = fmaf(ld(dp, (int64_t)wo * g.Cout), ld(xp, (int64_t)ww * g.Cin), acc);
+        }
+    }
+    if (chunks > 1) out[(int64_t)blockIdx.y * total + idx] = acc;
+    else out[idx] = accumulate ? out[idx] + acc : acc;
+}
+
+// dst[i] (+)= sum_{c<chunks} part[c][i], added in slice order
+__global__ void __launch_bounds__(256) reduce_partials(const float* __restrict__ part, float* __restrict__ dst,
+                                                       int64_t n, int chunks, int accumulate) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    float acc = part[i];
+    for (int c = 1; c < chunks; ++c) acc += part[(int64_t)c * n + i];
+    dst[i] = accumulate ? dst[i] + acc : acc;
+}
+
+hipError_t reduce_partials_launch(const float* part, float* dst, int64_t n, int chunks, int accumulate, hipStream_t s) {
+    hipLaunchKernelGGL(reduce_partials, dim3(nblk(n, 256)), dim3(256), 0, s, part, dst, n, chunks, accumulate);
+    return hipGetLastError();
+}
+
+static int wgrad_generic_chunks(const ConvGeom& g) {
+    const int64_t total = (int64_t)g.Cout * g.K();
+    int64_t c = ((int64_t)1 << 21) / total;
+    const int nho = g.m * g.Ho;
+    if (c > 32) c = 32;
+    if (c > nho) c = nho;
+    if (c < 1) c = 1;
+    return (int)c;
+}
+
+size_t wgrad_generic_ws_bytes(const ConvGeom& g) {
+    const int c = wgrad_generic_chunks(g);
+    return c > 1 ? (size_t)c * g.Cout * g.K() * sizeof(float) : 0;
+}
+
+hipError_t conv_wgrad_generic_launch(int dtype, const ConvGeom& g, const void* x, const void* dz, float* dw,
+                                     int accumulate, void* ws, hipStream_t s) {
+    const int64_t total = (int64_t)g.Cout * g.K();
+    const int chunks = wgrad_generic_chunks(g);
+    float* out = chunks > 1 ? (float*)ws : dw;
+    LPM_DISPATCH(dtype, hipLaunchKernelGGL(conv_wgrad_generic<T>, dim3(nblk(total, 256), chunks), dim3(256), 0, s, g,
+                                           (const T*)x, (const T*)dz, out, chunks, accumulate));
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || chunks == 1) return e;
+    return reduce_partials_launch((const float*)ws, dw, total, chunks, accumulate, s);
+}
+
+// --------------------------------------------------------------------------------------------------
+// epilogue backward (eqs. 8-9 through y = relu(scale*z + bias + add)):
+//   gm = dy * [y > 0];  dz = gm * scale_c;  gadd (+)= gm;  dbias_c (+)= sum_rows gm
+// Block = 64 channels x 4 row lanes; a block covers EPI_ROWS rows and leaves one partial per channel,
+// which bias_reduce adds in block order.
+#define EPI_ROWS 128
+template <typename T>
+__global__ void __launch_bounds__(256) epilogue_bwd_kernel(int64_t rows, int C, const T* __restrict__ dy,
+                                                           const T* __restrict__ y, const float* __restrict__ scale,
+                                                           T* __restrict__ dz, T* __restrict__ gadd, int gadd_acc,
+                                                           float* __restrict__ part) {
+    __shared__ float red[4][64];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + tx;
+    const int64_t r0 = (int64_t)blockIdx.y * EPI_ROWS;
+    const int64_t r1 = min(rows, r0 + EPI_ROWS);
+    float sum = 0.f;
+    if (c < C) {
+        const float sc = scale ? scale[c] : 1.f;
+        for (int64_t r = r0 + ty; r < r1; r += 4) {
+            const int64_t i = r * C + c;
+            float gm = ld(dy, i);
+            if (y && !(ld(y, i) > 0.f)) gm = 0.f;
+            if (dz) st(dz, i, gm * sc);
+            if (gadd) st(gadd, i, gadd_acc ? ld(gadd, i) + gm : gm);
+            sum += gm;
+        }
+    }
+    if (!part) return;
+    red[ty][tx] = sum;
+    __syncthreads();
+    if (ty == 0 && c < C) part[(int64_t)blockIdx.y * C + c] = (red[0][tx] + red[1][tx]) + (red[2][tx] + red[3][tx]);
+}
+
+__global__ void __launch_bounds__(256) bias_reduce(const float* __restrict__ part, float* __restrict__ db, int C,
+                                                   int nblocks, int accumulate) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= C) return;
+    float acc = 0.f;
+    for (int b = 0; b < nblocks; ++b) acc += part[(int64_t)b * C + c];
+    db[c] = accumulate ? db[c] + acc : acc;
+}
+
+size_t epi_bwd_ws_bytes(int64_t rows, int32_t C) { return (size_t)nblk(rows, EPI_ROWS) * C * sizeof(float); }
+
+hipError_t launch_epilogue_bwd(int dtype, int64_t rows, int32_t C, const void* dy, const void* y, const float* scale,
+                               void* dz, void* gadd, int gadd_acc, float* dbias, int db_acc, void* ws, hipStream_t s) {
+    const unsigned rb = nblk(rows, EPI_ROWS);
+    float* part = dbias ? (float*)ws : nullptr;
+    LPM_DISPATCH(dtype, hipLaunchKernelGGL(epilogue_bwd_kernel<T>, dim3(nblk(C, 64), rb), dim3(256), 0, s, rows, C,
+                                           (const T*)dy, (const T*)y, scale, (T*)dz, (T*)gadd, gadd_acc, part));
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || !dbias) return e;
+    hipLaunchKernelGGL(bias_reduce, dim3(nblk(C, 256)), dim3(256), 0, s, (const float*)part, dbias, C, (int)rb, db_acc);
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------------------------
+// 2x2/2 max pooling
+template <typename T>
+__global__ void __launch_bounds__(256) maxpool_fwd_kernel(int m, int H, int W, int C, const T* __restrict__ x,
+                                                          T* __restrict__ y) {
+    const int Ho = H / 2, Wo = W / 2;
+    const int64_t total = (int64_t)m * Ho * Wo * C;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int c = (int)(idx % C);
+    const int64_t r = idx / C;
+    const int wo = (int)(r % Wo), ho = (int)((r / Wo) % Ho), n = (int)(r / ((int64_t)Wo * Ho));
+    const T* p = x + (((int64_t)n * H + 2 * ho) * W + 2 * wo) * C + c;
+    const float a = ld(p, 0), b = ld(p, C), d = ld(p, (int64_t)W * C), e = ld(p, (int64_t)W * C + C);
+    st(y, idx, fmaxf(fmaxf(a, b), fmaxf(d, e)));
+}
+
+// gradient to the first element (row-major in the window) equal to the window maximum
+template <typename T>
+__global__ void __launch_bounds__(256) maxpool_bwd_kernel(int m, int H, int W, int C, const T* __restrict__ x,
+                                                          const T* __restrict__ y, const T* __restrict__ dy,
+                                                          T* __restrict__ dx, int accumulate) {
+    const int Ho = H / 2, Wo = W / 2;
+    const int64_t total = (int64_t)m * Ho * Wo * C;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int c = (int)(idx % C);
+    const int64_t r = idx / C;
+    const int wo = (int)(r % Wo), ho = (int)((r / Wo) % Ho), n = (int)(r / ((int64_t)Wo * Ho));
+    const int64_t base = (((int64_t)n * H + 2 * ho) * W + 2 * wo) * C + c;
+    const int64_t off[4] = {0, C, (int64_t)W * C, (int64_t)W * C + C};
+    const float mx = ld(y, idx), g = ld(dy, idx);
+    bool found = false;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const bool hit = !found && (ld(x, base + off[k]) == mx);
+        found = found || hit;
+        float v = hit ? g : 0.f;
+        if (accumulate) v += ld(dx, base + off[k]);
+        st(dx, base + off[k], v);
+    }
+}
+
+hipError_t launch_maxpool_fwd(int dtype, int32_t m, int32_t H, int32_t W, int32_t C, const void* x, void* y, hipStream_t s) {
+    const int64_t total = (int64_t)m * (H / 2) * (W / 2) * C;
+    LPM_DISPATCH(dtype, hipLaunchKernelGGL(maxpool_fwd_kernel<T>, dim3(nblk(total, 256)), dim3(256), 0, s, m, H, W, C,
+                                           (const T*)x, (T*)y));
+    return hipGetLastError();
+}
+
+hipError_t launch_maxpool_bwd(int dtype, int32_t m, int32_t H, int32_t W, int32_t C, const void* x, const void* y,
+                              const void* dy, void* dx, int accumulate, hipStream_t s) {
+    const int64_t total = (int64_t)m * (H / 2) * (W / 2) * C;
+    LPM_DISPATCH(dtype, hipLaunchKernelGGL(maxpool_bwd_kernel<T>, dim3(nblk(total, 256)), dim3(256), 0, s, m, H, W, C,
+                                           (const T*)x, (const T*)y, (const T*)dy, (T*)dx, accumulate));
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------------------------
+// global average pooling
+template <typename T>
+__global__ void __launch_bounds__(256) gap_fwd_kernel(int m, int HW, int C, const T* __restrict__ x, T* __restrict__ y) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)m * C) return;
+    const int c = (int)(idx % C), n = (int)(idx / C);
+    float acc = 0.f;
+    for (int i = 0; i < HW; ++i) acc += ld(x, ((int64_t)n * HW + i) * C + c);
+    st(y, idx, acc / (float)HW);
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) gap_bwd_kernel(int m, int HW, int C, const T* __restrict__ dy, T* __restrict__ dx,
+                                                      int accumulate) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)m * HW * C) return;
+    const int c = (int)(idx % C), n = (int)(idx / ((int64_t)HW * C));
+    float v = ld(dy, (int64_t)n * C + c) / (float)HW;
+    if (accumulate) v += ld(dx, idx);
+    st(dx, idx, v);
+}
+
+hipError_t launch_gap_fwd(int dtype, int32_t m, int32_t HW, int32_t C, const void* x, void* y, hipStream_t s) {
+    LPM_DISPATCH(dtype, hipLaunchKernelGGL(gap_fwd_kernel<T>, dim3(nblk((int64_t)m * C, 256)), dim3(256), 0, s, m, HW, C,
+                                           (const T*)x, (T*)y));
+    return hipGetLastError();
+}
+
+hipError_t launch_gap_bwd(int dtype, int32_t m, int32_t HW, int32_t C, const void* dy, void* dx, int accumulate, hipStream_t s) {
+    LPM_DISPATCH(dtype, hipLaunchKernelGGL(gap_bwd_kernel<T>, dim3(nblk((int64_t)m * HW * C, 256)), dim3(256), 0, s, m, HW,
+                                           C, (const T*)dy, (T*)dx, accumulate));
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------------------------
+// softmax cross-entropy (eq. 3 with the cross-entropy loss), one wavefront per row, one block in all:
+//   dlogits = (softmax(z) - onehot(label)) * loss_scale
+//   *loss_accum += loss_scale * sum_rows ( log sum exp(z - max) - (z[label] - max) )   (rows added in order)
+__device__ inline float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) softmax_ce_kernel(int m, int C, const T* __restrict__ z,
+                                                         const int32_t* __restrict__ labels, float loss_scale,
+                                                         T* __restrict__ dz, float* __restrict__ loss_accum) {
+    __shared__ float rowloss[256];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float total = 0.f;
+    for (int base = 0; base < m; base += 256) {
+        const int nrow = min(256, m - base);
+        for (int r = wave; r < nrow; r += 4) {
+            const T* zr = z + (int64_t)(base + r) * C;
+            T* dr = dz + (int64_t)(base + r) * C;
+            float mx = -INFINITY;
+            for (int c = lane; c < C; c += 64) mx = fmaxf(mx, ld(zr, c));
+            mx = wave_max(mx);
+            float se = 0.f;
+            for (int c = lane; c < C; c += 64) se += expf(ld(zr, c) - mx);
+            se = wave_sum(se);
+            const int lab = labels[base + r];
+            const float inv = 1.f / se;
+            for (int c = lane; c < C; c += 64) {
+                const float p = expf(ld(zr, c) - mx) * inv;
+                st(dr, c, (p - (c == lab ? 1.f : 0.f)) * loss_scale);
+            }
+            if (lane == 0) rowloss[r] = logf(se) - (ld(zr, lab) - mx);
+        }
+        __syncthreads();
+        if (threadIdx.x == 0)
+            for (int r = 0; r < nrow; ++r) total += rowloss[r];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) loss_accum[0] += loss_scale * total;
+}
+
+hipError_t launch_softmax_ce(int dtype, int32_t m, int32_t C, const void* logits, const int32_t* labels, float loss_scale,
+                             void* dlogits, float* loss_accum, hipStream_t s) {
+    LPM_DISPATCH(dtype, hipLaunchKernelGGL(softmax_ce_kernel<T>, dim3(1), dim3(256), 0, s, m, C, (const T*)logits, labels,
+                                           loss_scale, (T*)dlogits, loss_accum));
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------------------------
+// update, eq. 6 with momentum: v = mu*v + g; p = p - lr*v; bf16 copy; optional g = 0.  Pure streaming.
+__global__ void __launch_bounds__(256) sgd_kernel(float4* __restrict__ p, uint2* __restrict__ lowp, float4* __restrict__ g,
+                                                  float4* __restrict__ v, size_t n4, float lr, float mu, int zero_g) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
+        const float4 gg = g[i];
+        float4 vv = v[i], pp = p[i];
+        vv.x = fmaf(mu, vv.x, gg.x); vv.y = fmaf(mu, vv.y, gg.y); vv.z = fmaf(mu, vv.z, gg.z); vv.w = fmaf(mu, vv.w, gg.w);
+        pp.x = fmaf(-lr, vv.x, pp.x); pp.y = fmaf(-lr, vv.y, pp.y); pp.z = fmaf(-lr, vv.z, pp.z); pp.w = fmaf(-lr, vv.w, pp.w);
+        v[i] = vv;
+        p[i] = pp;
+        if (lowp) lowp[i] = make_uint2(pack_bf16x2(pp.x, pp.y), pack_bf16x2(pp.z, pp.w));
+        if (zero_g) g[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
+
+hipError_t launch_sgd(float* p, uint16_t* lowp, float* g, float* v, size_t n, float lr, float mu, int zero_g, hipStream_t s) {
+    const size_t n4 = n / 4;
+    if (n4 == 0) return hipSuccess;
+    unsigned blocks = (unsigned)((n4 + 255) / 256);
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    hipLaunchKernelGGL(sgd_kernel, dim3(blocks), dim3(256), 0, s, (float4*)p, (uint2*)lowp, (float4*)g, (float4*)v, n4, lr,
+                       mu, zero_g);
+    return hipGetLastError();
+}
+
+__global__ void __launch_bounds__(256) f32_to_bf16_kernel(const float4* __restrict__ src, uint2* __restrict__ dst, size_t n4) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
+        const float4 a = src[i];
+        dst[i] = make_uint2(pack_bf16x2(a.x, a.y), pack_bf16x2(a.z, a.w));
+    }
+}
+
+hipError_t launch_f32_to_bf16(const float* src, uint16_t* dst, size_t n, hipStream_t s) {
+    const size_t n4 = n / 4;
+    if (n4 == 0) return hipSuccess;
+    unsigned blocks = (unsigned)((n4 + 255) / 256);
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(blocks), dim3(256), 0, s, (const float4*)src, (uint2*)dst, n4);
+    return hipGetLastError();
+}
+
+// dst[ci][k][co] = bf16(src[co][k][ci])   (k = kh*Kw+kw)
+__global__ void __launch_bounds__(256) weight_transpose_kernel(const float* __restrict__ src, uint16_t* __restrict__ dst,
+                                                               int Cout, int KK, int Cin) {
+    const int64_t total = (int64_t)Cout * KK * Cin;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int co = (int)(idx % Cout);
+    const int k = (int)((idx / Cout) % KK);
+    const int ci = (int)(idx / ((int64_t)Cout * KK));
+    dst[idx] = f2bf(src[((int64_t)co * KK + k) * Cin + ci]);
+}
+
+hipError_t launch_weight_transpose_bf16(const float* src, uint16_t* dst, int32_t Cout, int32_t KhKw, int32_t Cin, hipStream_t s) {
+    const int64_t total = (int64_t)Cout * KhKw * Cin;
+    hipLaunchKernelGGL(weight_transpose_kernel, dim3(nblk(total, 256)), dim3(256), 0, s, src, dst, Cout, KhKw, Cin);
+    return hipGetLastError();
+}
+
+__global__ void __launch_bounds__(256) fill_kernel(float* p, size_t n, float v) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = v;
+}
+
+hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    unsigned blocks = (unsigned)((n + 255) / 256);
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(fill_kernel, dim3(blocks), dim3(256), 0, s, p, n, v);
+    return hipGetLastError();
+}
+
+}  // namespace lpm

@@ -1,0 +1,83 @@
+// Internal declarations shared by the host-side sources and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdarg>
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+#include "../../include/lpm.h"
+
+namespace lpm {
+
+// ---- error text (thread local) -------------------------------------------------------------------
+int32_t fail(int32_t code, const char* fmt, ...);
+int32_t hip_fail(hipError_t e, const char* what);
+#define LPM_HIP(call)                                            \
+    do {                                                         \
+        hipError_t e__ = (call);                                 \
+        if (e__ != hipSuccess) return lpm::hip_fail(e__, #call); \
+    } while (0)
+
+// ---- validated network description ---------------------------------------------------------------
+struct Shape { int32_t c, h, w; size_t elems() const { return (size_t)c * h * w; } };
+
+// Checks the whole list (kinds, extents, references, shapes) and returns per-tensor shapes:
+// shapes[0] is tensor -1 (the network input), shapes[t+1] the output of layer t.
+// FC layers are rewritten to their convolution form (kh=h_in, kw=w_in, stride 1, pad 0).
+int32_t validate_network(const lpm_layer* layers, int32_t L, std::vector<lpm_layer>& norm,
+                         std::vector<Shape>& shapes);
+
+inline bool has_weights(const lpm_layer& l) { return l.kind == LPM_CONV || l.kind == LPM_FC; }
+
+// ---- geometry handed to the kernel launchers -----------------------------------------------------
+struct ConvGeom {
+    int32_t m, H, W, Cin, Ho, Wo, Cout, Kh, Kw, stride, pad;
+    __host__ __device__ int64_t rows_out() const { return (int64_t)m * Ho * Wo; }
+    __host__ __device__ int64_t rows_in() const { return (int64_t)m * H * W; }
+    __host__ __device__ int32_t K() const { return Kh * Kw * Cin; }
+};
+
+// All launchers enqueue on `st` and return the launch status.  `dtype` selects the element type of
+// activations / activation gradients / low-precision weights (LPM_F32: float everywhere).
+
+// y = relu?( scale_c * conv(x, w) + bias_c + add )      (scale, bias, add may be NULL)
+hipError_t launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, const float* scale,
+                           const float* bias, const void* add, int relu, void* y, void* ws, hipStream_t st);
+// dx (+)= conv_transpose(dz, w)
+hipError_t launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dz, const void* w, const void* wt,
+                             void* dx, int accumulate, void* ws, hipStream_t st);
+// dw (+)= sum over pixels of dz (x) x         ws: split-reduction partials (wgrad_ws_bytes)
+hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const void* dz, float* dw,
+                             int accumulate, void* ws, hipStream_t st);
+size_t wgrad_ws_bytes(int dtype, const ConvGeom& g);
+size_t fwd_ws_bytes(int dtype, const ConvGeom& g);
+size_t dgrad_ws_bytes(int dtype, const ConvGeom& g);
+
+// gm = dy * [y>0] (y NULL: gm = dy);  dz = gm * scale_c;  gadd (+)= gm;  dbias (+)= sum_rows gm
+// ws: per-block bias partials (epi_bwd_ws_bytes)
+hipError_t launch_epilogue_bwd(int dtype, int64_t rows, int32_t C, const void* dy, const void* y,
+                               const float* scale, void* dz, void* gadd, int gadd_acc, float* dbias,
+                               int db_acc, void* ws, hipStream_t st);
+size_t epi_bwd_ws_bytes(int64_t rows, int32_t C);
+
+hipError_t launch_maxpool_fwd(int dtype, int32_t m, int32_t H, int32_t W, int32_t C, const void* x, void* y,
+                              hipStream_t st);
+// dx (+)= dy routed to the first maximum of each window (recomputed from x and y)
+hipError_t launch_maxpool_bwd(int dtype, int32_t m, int32_t H, int32_t W, int32_t C, const void* x,
+                              const void* y, const void* dy, void* dx, int accumulate, hipStream_t st);
+hipError_t launch_gap_fwd(int dtype, int32_t m, int32_t HW, int32_t C, const void* x, void* y, hipStream_t st);
+hipError_t launch_gap_bwd(int dtype, int32_t m, int32_t HW, int32_t C, const void* dy, void* dx, int accumulate,
+                          hipStream_t st);
+// dlogits = (softmax(logits) - onehot) * loss_scale;  *loss_accum += loss_scale * sum_n -log p_n[label_n]
+hipError_t launch_softmax_ce(int dtype, int32_t m, int32_t C, const void* logits, const int32_t* labels,
+                             float loss_scale, void* dlogits, float* loss_accum, hipStream_t st);
+// v = mu*v + g; p -= lr*v; lowp[i] = bf16(p[i]) (lowp may be NULL); optionally g = 0.   n % 4 == 0
+hipError_t launch_sgd(float* p, uint16_t* lowp, float* g, float* v, size_t n, float lr, float mu, int zero_g,
+                      hipStream_t st);
+hipError_t launch_f32_to_bf16(const float* src, uint16_t* dst, size_t n, hipStream_t st);
+// dst[ci][kh][kw][co] = bf16(src[co][kh][kw][ci])
+hipError_t launch_weight_transpose_bf16(const float* src, uint16_t* dst, int32_t Cout, int32_t KhKw, int32_t Cin,
+                                        hipStream_t st);
+hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t st);
+
+}  // namespace lpm

@@ -1,0 +1,220 @@
+// One mini-batch step of the whole partitioned network on one GPU.
+//
+// Forward Pass and Backward Pass Parallelisation and Optimisation: the mini-batch is split into M
+// micro-batches; F_{z,j} / B_{z,j} are the forward / backward operations of stage z on micro-batch j.
+//   LOCKED      F_{0,j}..F_{Z-1,j}, B_{Z-1,j}..B_{0,j} one after the other (non-parallel schedule)
+//   OVERLAPPED  the forward chain of micro-batch j+1 runs on one stream while the backward chain of
+//               micro-batch j runs on another; a stage holds at most `window` micro-batches in
+//               flight, i.e. F_{z,j+window} starts after B_{z,j} ("B_{0,0} finishes before F_{0,2}").
+// Gradients are accumulated over the micro-batches in the fixed order j = 0..M-1 and every stage is
+// updated once, right after its last backward, so both modes produce bit-identical results.
+#include "stage.h"
+
+#include <cstring>
+#include <new>
+
+using namespace lpm;
+
+namespace {
+struct GraphEntry {
+    std::vector<unsigned char> key;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+};
+}  // namespace
+
+struct lpm_schedule {
+    std::vector<lpm_stage*> st;
+    int32_t Z = 0, M = 0, window = 2;
+    std::vector<hipEvent_t> ev_f;   // [M]    F_{Z-1,j} done
+    std::vector<hipEvent_t> ev_b;   // [Z*M]  B_{z,j} done
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    std::vector<GraphEntry> graphs;
+};
+
+static void destroy_events(lpm_schedule* s) {
+    for (hipEvent_t e : s->ev_f) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : s->ev_b) if (e) (void)hipEventDestroy(e);
+    if (s->ev_fork) (void)hipEventDestroy(s->ev_fork);
+    if (s->ev_join) (void)hipEventDestroy(s->ev_join);
+    for (GraphEntry& g : s->graphs) {
+        if (g.exec) (void)hipGraphExecDestroy(g.exec);
+        if (g.graph) (void)hipGraphDestroy(g.graph);
+    }
+}
+
+extern "C" int32_t lpm_schedule_create(lpm_stage* const* stages, int32_t Z, int32_t n_microbatch, int32_t window,
+                                       lpm_schedule** out) {
+    if (!out) return fail(LPM_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (!stages || Z <= 0) return fail(LPM_EINVAL, "no stages");
+    if (n_microbatch <= 0) return fail(LPM_EINVAL, "n_microbatch must be positive");
+    if (window < 1 || window > LPM_MAX_WINDOW) return fail(LPM_EINVAL, "window must be in 1..%d", LPM_MAX_WINDOW);
+    for (int32_t z = 0; z < Z; ++z) {
+        if (!stages[z]) return fail(LPM_EINVAL, "stage %d is NULL", z);
+        if (stages[z]->m != stages[0]->m || stages[z]->dtype != stages[0]->dtype || stages[z]->L != stages[0]->L)
+            return fail(LPM_ESHAPE, "stage %d differs from stage 0 in micro-batch, element type or network", z);
+        if (z == 0 ? stages[z]->first != 0 : stages[z]->first != stages[z - 1]->last)
+            return fail(LPM_ESHAPE, "stage %d does not start where stage %d ends", z, z - 1);
+        if (stages[z]->loss && z != Z - 1) return fail(LPM_ESHAPE, "only the last stage may hold the loss");
+    }
+    if (stages[Z - 1]->last != stages[0]->L) return fail(LPM_ESHAPE, "the stages do not cover the whole network");
+    lpm_schedule* s = new (std::nothrow) lpm_schedule();
+    if (!s) return fail(LPM_ENOMEM, "out of host memory");
+    s->st.assign(stages, stages + Z);
+    s->Z = Z; s->M = n_microbatch; s->window = window;
+    s->ev_f.assign((size_t)n_microbatch, nullptr);
+    s->ev_b.assign((size_t)n_microbatch * Z, nullptr);
+    hipError_t e = hipSuccess;
+    for (hipEvent_t& ev : s->ev_f) if (e == hipSuccess) e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+    for (hipEvent_t& ev : s->ev_b) if (e == hipSuccess) e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&s->ev_fork, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&s->ev_join, hipEventDisableTiming);
+    if (e != hipSuccess) {
+        destroy_events(s);
+        delete s;
+        return hip_fail(e, "hipEventCreateWithFlags");
+    }
+    *out = s;
+    return LPM_OK;
+}
+
+extern "C" int32_t lpm_schedule_destroy(lpm_schedule* s) {
+    if (!s) return LPM_OK;
+    destroy_events(s);
+    delete s;
+    return LPM_OK;
+}
+
+namespace {
+
+struct RunArgs {
+    int32_t mode;
+    const void* x_batch; const int32_t* labels; const void* dy_batch;
+    const lpm_stage_buffers* bufs; int32_t dx_wanted; float lr, mu; float* loss_out;
+    hipStream_t sf, sb;
+};
+
+int32_t fwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStream_t st) {
+    lpm_stage* sg = s->st[(size_t)z];
+    const int32_t slot = j % s->window;
+    const lpm_stage_buffers& b = a.bufs[z];
+    const void* in = z == 0 ? (const void*)((const char*)a.x_batch + (size_t)j * sg->T(sg->first - 1).bytes)
+                            : (const void*)a.bufs[z - 1].act_out[slot];
+    const int32_t* lab = sg->loss ? a.labels + (size_t)j * sg->m : nullptr;
+    return lpm_stage_forward(sg, in, b.act_out[slot], lab, a.loss_out, b.params, b.lowp, b.stash[slot], b.fwd_ws,
+                             1.0f / (float)(s->M * sg->m), st);
+}
+
+int32_t bwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStream_t st) {
+    lpm_stage* sg = s->st[(size_t)z];
+    const int32_t slot = j % s->window;
+    const lpm_stage_buffers& b = a.bufs[z];
+    const void* in = z == 0 ? (const void*)((const char*)a.x_batch + (size_t)j * sg->T(sg->first - 1).bytes)
+                            : (const void*)a.bufs[z - 1].act_out[slot];
+    const void* dy = nullptr;
+    if (z < s->Z - 1) dy = a.bufs[z + 1].grad_in;
+    else if (!sg->loss) dy = (const char*)a.dy_batch + (size_t)j * sg->T(sg->t_out).bytes;
+    void* dx = z == 0 ? (a.dx_wanted ? b.grad_in : nullptr) : b.grad_in;
+    return lpm_stage_backward(sg, in, b.act_out[slot], dy, dx, b.params, b.lowp, b.stash[slot], b.grads, j > 0,
+                              b.bwd_ws, st);
+}
+
+int32_t upd_op(lpm_schedule* s, const RunArgs& a, int32_t z, hipStream_t st) {
+    const lpm_stage_buffers& b = a.bufs[z];
+    return lpm_stage_update(s->st[(size_t)z], b.params, b.lowp, b.grads, b.momentum, a.lr, a.mu, 0, st);
+}
+
+int32_t enqueue(lpm_schedule* s, const RunArgs& a) {
+    const int32_t Z = s->Z, M = s->M, W = s->window;
+    int32_t rc;
+    if (s->st[(size_t)Z - 1]->loss) LPM_HIP(launch_fill_f32(a.loss_out, 1, 0.f, a.sf));
+    if ((a.mode & 15) == LPM_LOCKED) {
+        for (int32_t j = 0; j < M; ++j) {
+            for (int32_t z = 0; z < Z; ++z) if ((rc = fwd_op(s, a, z, j, a.sf))) return rc;
+            for (int32_t z = Z - 1; z >= 0; --z) if ((rc = bwd_op(s, a, z, j, a.sf))) return rc;
+        }
+        for (int32_t z = 0; z < Z; ++z) if ((rc = upd_op(s, a, z, a.sf))) return rc;
+        return LPM_OK;
+    }
+    LPM_HIP(hipEventRecord(s->ev_fork, a.sf));
+    LPM_HIP(hipStreamWaitEvent(a.sb, s->ev_fork, 0));
+    for (int32_t j = 0; j < M; ++j) {
+        for (int32_t z = 0; z < Z; ++z) {
+            if (j >= W) LPM_HIP(hipStreamWaitEvent(a.sf, s->ev_b[(size_t)(j - W) * Z + z], 0));
+            if ((rc = fwd_op(s, a, z, j, a.sf))) return rc;
+        }
+        LPM_HIP(hipEventRecord(s->ev_f[(size_t)j], a.sf));
+        LPM_HIP(hipStreamWaitEvent(a.sb, s->ev_f[(size_t)j], 0));
+        for (int32_t z = Z - 1; z >= 0; --z) {
+            if ((rc = bwd_op(s, a, z, j, a.sb))) return rc;
+            if (j + W < M) LPM_HIP(hipEventRecord(s->ev_b[(size_t)j * Z + z], a.sb));
+            if (j == M - 1 && (rc = upd_op(s, a, z, a.sb))) return rc;
+        }
+    }
+    LPM_HIP(hipEventRecord(s->ev_join, a.sb));
+    LPM_HIP(hipStreamWaitEvent(a.sf, s->ev_join, 0));
+    return LPM_OK;
+}
+
+}  // namespace
+
+extern "C" int32_t lpm_schedule_run(lpm_schedule* s, int32_t mode, const void* x_batch, const int32_t* labels,
+                                    const void* dy_batch, const lpm_stage_buffers* per_stage, int32_t dx_wanted,
+                                    float lr, float mu, float* loss_out, void* stream_fwd, void* stream_bwd) {
+    if (!s || !x_batch || !per_stage) return fail(LPM_EINVAL, "NULL argument");
+    const int32_t base = mode & 15;
+    if ((base != LPM_LOCKED && base != LPM_OVERLAPPED) || (mode & ~(15 | LPM_GRAPH))) return fail(LPM_EINVAL, "unknown mode %d", mode);
+    const bool loss = s->st[(size_t)s->Z - 1]->loss;
+    if (loss && (!labels || !loss_out)) return fail(LPM_EINVAL, "the last stage holds the loss: labels and loss_out are required");
+    if (!loss && !dy_batch) return fail(LPM_EINVAL, "the last stage is not a loss stage: dy_batch is required");
+    if (base == LPM_OVERLAPPED && stream_fwd == stream_bwd) return fail(LPM_EINVAL, "LPM_OVERLAPPED needs two distinct streams");
+    if (((uintptr_t)x_batch & 255u) || (dy_batch && ((uintptr_t)dy_batch & 255u))) return fail(LPM_EALIGN, "x_batch / dy_batch must be 256-byte aligned");
+    for (int32_t z = 0; z < s->Z; ++z) {
+        const lpm_stage_buffers& b = per_stage[z];
+        if (!b.params || !b.grads || !b.momentum || !b.fwd_ws || !b.bwd_ws) return fail(LPM_EINVAL, "stage %d: NULL buffer", z);
+        for (int32_t w = 0; w < s->window; ++w)
+            if (!b.stash[w] || !b.act_out[w]) return fail(LPM_EINVAL, "stage %d: stash / act_out slot %d is NULL", z, w);
+        if ((z > 0 || dx_wanted) && !b.grad_in) return fail(LPM_EINVAL, "stage %d: grad_in is NULL", z);
+    }
+    RunArgs a{mode, x_batch, labels, dy_batch, per_stage, dx_wanted, lr, mu, loss_out, (hipStream_t)stream_fwd,
+              (hipStream_t)stream_bwd};
+    if (!(mode & LPM_GRAPH)) return enqueue(s, a);
+
+    // Captured replay: the graph is keyed by every argument value (pointers included).
+    std::vector<unsigned char> key;
+    auto put = [&](const void* p, size_t n) { key.insert(key.end(), (const unsigned char*)p, (const unsigned char*)p + n); };
+    put(&mode, sizeof mode); put(&x_batch, sizeof x_batch); put(&labels, sizeof labels); put(&dy_batch, sizeof dy_batch);
+    put(per_stage, sizeof(lpm_stage_buffers) * (size_t)s->Z); put(&dx_wanted, sizeof dx_wanted);
+    put(&lr, sizeof lr); put(&mu, sizeof mu); put(&loss_out, sizeof loss_out); put(&stream_bwd, sizeof stream_bwd);
+    for (GraphEntry& g : s->graphs)
+        if (g.key == key) {
+            LPM_HIP(hipGraphLaunch(g.exec, a.sf));
+            return LPM_OK;
+        }
+    LPM_HIP(hipStreamBeginCapture(a.sf, hipStreamCaptureModeRelaxed));
+    const int32_t rc = enqueue(s, a);
+    hipGraph_t graph = nullptr;
+    const hipError_t e = hipStreamEndCapture(a.sf, &graph);
+    if (rc) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return rc;
+    }
+    if (e != hipSuccess) return hip_fail(e, "hipStreamEndCapture");
+    GraphEntry ge;
+    ge.key = key;
+    ge.graph = graph;
+    const hipError_t ei = hipGraphInstantiate(&ge.exec, graph, nullptr, nullptr, 0);
+    if (ei != hipSuccess) {
+        (void)hipGraphDestroy(graph);
+        return hip_fail(ei, "hipGraphInstantiate");
+    }
+    if (s->graphs.size() >= 8) {      // bounded cache: drop the oldest
+        (void)hipGraphExecDestroy(s->graphs.front().exec);
+        (void)hipGraphDestroy(s->graphs.front().graph);
+        s->graphs.erase(s->graphs.begin());
+    }
+    s->graphs.push_back(ge);
+    LPM_HIP(hipGraphLaunch(ge.exec, a.sf));
+    return LPM_OK;
+}

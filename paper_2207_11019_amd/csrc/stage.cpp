@@ -1,0 +1,354 @@
+// A stage = one sub-module (a stack of consecutive layers) and its three operations
+// F_{z,j}, B_{z,j}, U_z.  Host code only: validates, lays out buffers, enqueues kernels.
+//
+// Layer-wise Partitioning and Merging: sub-module z takes the activation of z-1 in the forward
+// pass and the gradient of z+1 in the backward pass.  Problem Statement eqs. 1, 8, 9 define what
+// each layer computes in the two passes; eq. 6 the update.
+#include "lpm_internal.h"
+
+#include <algorithm>
+#include <new>
+
+#include "stage.h"
+
+using namespace lpm;
+
+static bool misaligned(const void* p) { return ((uintptr_t)p & 255u) != 0; }
+
+extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t first, int32_t last,
+                                    int32_t microbatch, int32_t dtype, lpm_stage** out) {
+    if (!out) return fail(LPM_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (dtype != LPM_F32 && dtype != LPM_BF16) return fail(LPM_EINVAL, "dtype must be LPM_F32 or LPM_BF16");
+    if (microbatch <= 0) return fail(LPM_EINVAL, "microbatch must be positive");
+    lpm_stage* s = new (std::nothrow) lpm_stage();
+    if (!s) return fail(LPM_ENOMEM, "out of host memory");
+    int32_t rc = validate_network(layers, L, s->net, s->shapes);
+    if (rc) { delete s; return rc; }
+    if (first < 0 || last > L || first >= last) { delete s; return fail(LPM_EINVAL, "stage range [%d,%d) is not inside the network", first, last); }
+    s->first = first; s->last = last; s->m = microbatch; s->dtype = dtype; s->L = L;
+    s->esz = dtype == LPM_BF16 ? 2 : 4;
+    s->loss = s->net[last - 1].kind == LPM_SOFTMAX_CE;
+    if (s->loss && last - first < 2) { delete s; return fail(LPM_ESHAPE, "the loss layer cannot form a stage on its own"); }
+    // every tensor read from outside must be the stage input
+    for (int32_t i = first; i < last; ++i) {
+        const lpm_layer& l = s->net[i];
+        if (l.src < first - 1 || (l.add_src != LPM_NONE && l.add_src < first - 1)) {
+            delete s;
+            return fail(LPM_ESHAPE, "layer %d reads a tensor produced before the stage input (%d)", i, first - 1);
+        }
+    }
+    // no tensor of this stage other than its output may be read by a later layer
+    for (int32_t i = last; i < L; ++i) {
+        const lpm_layer& l = s->net[i];
+        for (int32_t ref : {l.src, l.add_src}) {
+            if (ref != LPM_NONE && ref >= first && ref < last - 1) {
+                delete s;
+                return fail(LPM_ESHAPE, "layer %d reads tensor %d across the stage boundary", i, ref);
+            }
+        }
+    }
+
+    // tensors first-1 .. last-1
+    s->ten.resize((size_t)(last - first + 1));
+    s->t_out = s->loss ? last - 2 : last - 1;
+    size_t stash = 0, gws = 0;
+    for (int32_t t = first - 1; t < last; ++t) {
+        TensorRt& tr = s->T(t);
+        tr.shape = s->shapes[(size_t)t + 1];
+        tr.bytes = tr.shape.elems() * (size_t)microbatch * s->esz;
+        if (t == first - 1) tr.loc = LOC_X;
+        else if (t == s->t_out || (s->loss && t == last - 1)) tr.loc = LOC_Y;
+        else {
+            tr.loc = LOC_STASH;
+            tr.stash_off = stash;
+            stash += align_up(tr.bytes, 256);
+            tr.g_off = gws;
+            gws += align_up(tr.bytes, 256);
+        }
+    }
+    if (s->loss) {
+        s->dlogits_off = stash;
+        stash += align_up(s->T(last - 2).bytes, 256);
+    }
+    s->stash_bytes = stash;
+
+    // parameters: trainable (W, bias per layer) first, frozen scales after
+    s->lay.resize((size_t)(last - first));
+    size_t off = 0, lowp = 0, dz_max = 0, kws = 0, fws = 0;
+    for (int32_t i = first; i < last; ++i) {
+        LayerRt& lr = s->Ly(i);
+        lr.d = s->net[i];
+        const lpm_layer& l = lr.d;
+        const Shape o = s->shapes[(size_t)i + 1];
+        lr.g = ConvGeom{microbatch, l.h_in, l.w_in, l.cin, o.h, o.w, o.c, l.kh, l.kw, l.stride, l.pad};
+        if (!has_weights(l)) continue;
+        lr.w_count = (size_t)l.cout * l.kh * l.kw * l.cin;
+        lr.w_off = off;
+        off += align_up(lr.w_count, 64);
+        if (l.flags & LPM_BIAS) { lr.b_off = off; off += align_up((size_t)l.cout, 64); }
+        if (dtype == LPM_BF16) {
+            lr.lowp_w_off = lr.w_off * 2;      // the bf16 copies mirror the float layout element for element
+            const bool single_pixel = (o.h == 1 && o.w == 1 && l.kh == l.h_in && l.kw == l.w_in && l.pad == 0);
+            if (!single_pixel) { lr.lowp_wt_off = lowp; lowp += align_up(lr.w_count * 2, 256); }   // rebased below
+        }
+        dz_max = std::max(dz_max, align_up(o.elems() * (size_t)microbatch * s->esz, 256));
+        kws = std::max(kws, align_up(wgrad_ws_bytes(dtype, lr.g), 256));
+        kws = std::max(kws, align_up(dgrad_ws_bytes(dtype, lr.g), 256));
+        kws = std::max(kws, align_up(epi_bwd_ws_bytes(lr.g.rows_out(), l.cout), 256));
+        fws = std::max(fws, align_up(fwd_ws_bytes(dtype, lr.g), 256));
+    }
+    s->n_trainable = off;
+    if (dtype == LPM_BF16) {                   // transposed copies follow the mirrored region
+        const size_t base = align_up(off * 2, 256);
+        for (int32_t i = first; i < last; ++i)
+            if (s->Ly(i).lowp_wt_off != NO) s->Ly(i).lowp_wt_off += base;
+        lowp += base;
+    }
+    for (int32_t i = first; i < last; ++i) {
+        LayerRt& lr = s->Ly(i);
+        if (has_weights(lr.d) && (lr.d.flags & LPM_SCALE)) { lr.s_off = off; off += align_up((size_t)lr.d.cout, 64); }
+    }
+    s->n_params = off;
+    s->lowp_bytes = lowp;
+    s->dz_off = gws;
+    s->kws_off = gws + dz_max;
+    s->kws_bytes = kws;
+    s->bwd_ws = std::max<size_t>(gws + dz_max + kws, 256);
+    s->fwd_ws = std::max<size_t>(fws, 256);
+    *out = s;
+    return LPM_OK;
+}
+
+extern "C" int32_t lpm_stage_destroy(lpm_stage* s) {
+    delete s;
+    return LPM_OK;
+}
+
+extern "C" int32_t lpm_stage_sizes(const lpm_stage* s, size_t* param_bytes, size_t* lowp_bytes, size_t* grad_bytes,
+                                   size_t* stash_bytes, size_t* fwd_ws_bytes_, size_t* bwd_ws_bytes,
+                                   size_t* in_bytes, size_t* out_bytes) {
+    if (!s) return fail(LPM_EINVAL, "stage is NULL");
+    if (param_bytes) *param_bytes = std::max<size_t>(s->n_params * 4, 256);
+    if (lowp_bytes) *lowp_bytes = s->lowp_bytes;
+    if (grad_bytes) *grad_bytes = std::max<size_t>(s->n_trainable * 4, 256);
+    if (stash_bytes) *stash_bytes = std::max<size_t>(s->stash_bytes, 256);
+    if (fwd_ws_bytes_) *fwd_ws_bytes_ = s->fwd_ws;
+    if (bwd_ws_bytes) *bwd_ws_bytes = s->bwd_ws;
+    if (in_bytes) *in_bytes = s->T(s->first - 1).bytes;
+    if (out_bytes) *out_bytes = s->T(s->t_out).bytes;
+    return LPM_OK;
+}
+
+extern "C" int32_t lpm_stage_param_offset(const lpm_stage* s, int32_t layer, int32_t which, size_t* offset, size_t* count) {
+    if (!s || !offset || !count) return fail(LPM_EINVAL, "NULL argument");
+    if (layer < s->first || layer >= s->last) return fail(LPM_EINVAL, "layer %d is not in the stage", layer);
+    const LayerRt& lr = s->Ly(layer);
+    size_t o = NO, c = 0;
+    if (which == 0) { o = lr.w_off; c = lr.w_count; }
+    else if (which == 1) { o = lr.b_off; c = (size_t)lr.d.cout; }
+    else if (which == 2) { o = lr.s_off; c = (size_t)lr.d.cout; }
+    if (o == NO) return fail(LPM_EINVAL, "layer %d has no parameter tensor %d", layer, which);
+    *offset = o; *count = c;
+    return LPM_OK;
+}
+
+extern "C" int32_t lpm_stage_stash_offset(const lpm_stage* s, int32_t t, size_t* offset, size_t* bytes) {
+    if (!s || !offset || !bytes) return fail(LPM_EINVAL, "NULL argument");
+    if (t == -100) {
+        if (!s->loss) return fail(LPM_EINVAL, "not a loss stage");
+        *offset = s->dlogits_off; *bytes = s->T(s->last - 2).bytes;
+        return LPM_OK;
+    }
+    if (t < s->first - 1 || t >= s->last || s->T(t).loc != LOC_STASH) return fail(LPM_EINVAL, "tensor %d is not in the stash", t);
+    *offset = s->T(t).stash_off; *bytes = s->T(t).bytes;
+    return LPM_OK;
+}
+
+extern "C" int32_t lpm_stage_grad_offset(const lpm_stage* s, int32_t t, size_t* offset, size_t* bytes) {
+    if (!s || !offset || !bytes) return fail(LPM_EINVAL, "NULL argument");
+    if (t < s->first - 1 || t >= s->last || s->T(t).loc != LOC_STASH) return fail(LPM_EINVAL, "tensor %d has no gradient in the scratch", t);
+    *offset = s->T(t).g_off; *bytes = s->T(t).bytes;
+    return LPM_OK;
+}
+
+extern "C" int32_t lpm_stage_sync_lowp(lpm_stage* s, const float* params, void* lowp, void* stream) {
+    if (!s || !params) return fail(LPM_EINVAL, "NULL argument");
+    if (s->dtype != LPM_BF16) return LPM_OK;
+    if (!lowp) return fail(LPM_EINVAL, "lowp is NULL");
+    if (misaligned(params) || misaligned(lowp)) return fail(LPM_EALIGN, "buffers must be 256-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    LPM_HIP(launch_f32_to_bf16(params, (uint16_t*)lowp, s->n_trainable, st));
+    for (int32_t i = s->first; i < s->last; ++i) {
+        const LayerRt& lr = s->Ly(i);
+        if (lr.lowp_wt_off != NO)
+            LPM_HIP(launch_weight_transpose_bf16(params + lr.w_off, (uint16_t*)((char*)lowp + lr.lowp_wt_off), lr.d.cout,
+                                                 lr.d.kh * lr.d.kw, lr.d.cin, st));
+    }
+    return LPM_OK;
+}
+
+namespace {
+// Where tensor t lives for this call.
+inline const void* tptr(const lpm_stage* s, int32_t t, const void* x, const void* y, const void* stash) {
+    const TensorRt& tr = s->T(t);
+    if (tr.loc == LOC_X) return x;
+    if (tr.loc == LOC_Y) return y;
+    return (const char*)stash + tr.stash_off;
+}
+}  // namespace
+
+extern "C" int32_t lpm_stage_forward(lpm_stage* s, const void* x, void* y, const int32_t* labels, float* loss_accum,
+                                     const float* params, const void* lowp, void* stash, void* fwd_ws,
+                                     float loss_scale, void* stream) {
+    if (!s || !x || !y || !params || !stash || !fwd_ws) return fail(LPM_EINVAL, "NULL argument");
+    if (s->dtype == LPM_BF16 && !lowp) return fail(LPM_EINVAL, "lowp is NULL for a bf16 stage");
+    if (s->loss && (!labels || !loss_accum)) return fail(LPM_EINVAL, "a loss stage needs labels and loss_accum");
+    if (misaligned(x) || misaligned(y) || misaligned(params) || misaligned(stash) || misaligned(fwd_ws) ||
+        (lowp && misaligned(lowp)))
+        return fail(LPM_EALIGN, "device buffers must be 256-byte aligned");
+    if (s->loss && (((uintptr_t)labels & 3u) || ((uintptr_t)loss_accum & 3u))) return fail(LPM_EALIGN, "labels / loss_accum must be 4-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    for (int32_t i = s->first; i < s->last; ++i) {
+        const LayerRt& lr = s->Ly(i);
+        const lpm_layer& l = lr.d;
+        const void* in = tptr(s, l.src, x, y, stash);
+        void* outp = const_cast<void*>(tptr(s, i, x, y, stash));
+        switch (l.kind) {
+            case LPM_CONV:
+            case LPM_FC: {
+                const void* w = s->dtype == LPM_BF16 ? (const void*)((const char*)lowp + lr.lowp_w_off)
+                                                     : (const void*)(params + lr.w_off);
+                const float* sc = lr.s_off != NO ? params + lr.s_off : nullptr;
+                const float* bi = lr.b_off != NO ? params + lr.b_off : nullptr;
+                const void* add = l.add_src != LPM_NONE ? tptr(s, l.add_src, x, y, stash) : nullptr;
+                LPM_HIP(launch_conv_fwd(s->dtype, lr.g, in, w, sc, bi, add, (l.flags & LPM_RELU) != 0, outp, fwd_ws, st));
+                break;
+            }
+            case LPM_MAXPOOL2:
+                LPM_HIP(launch_maxpool_fwd(s->dtype, s->m, l.h_in, l.w_in, l.cin, in, outp, st));
+                break;
+            case LPM_GAP:
+                LPM_HIP(launch_gap_fwd(s->dtype, s->m, l.h_in * l.w_in, l.cin, in, outp, st));
+                break;
+            case LPM_SOFTMAX_CE:
+                LPM_HIP(launch_softmax_ce(s->dtype, s->m, l.cin, in, labels, loss_scale, (char*)stash + s->dlogits_off,
+                                          loss_accum, st));
+                break;
+        }
+    }
+    return LPM_OK;
+}
+
+extern "C" int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y, const void* dy, void* dx,
+                                      const float* params, const void* lowp, const void* stash, float* grads,
+                                      int32_t accumulate, void* bwd_ws, void* stream) {
+    if (!s || !x || !y || !params || !stash || !grads || !bwd_ws) return fail(LPM_EINVAL, "NULL argument");
+    if (!s->loss && !dy) return fail(LPM_EINVAL, "dy is NULL for a stage that is not a loss stage");
+    if (s->dtype == LPM_BF16 && !lowp) return fail(LPM_EINVAL, "lowp is NULL for a bf16 stage");
+    if (misaligned(x) || misaligned(y) || misaligned(params) || misaligned(stash) || misaligned(grads) ||
+        misaligned(bwd_ws) || (dy && misaligned(dy)) || (dx && misaligned(dx)) || (lowp && misaligned(lowp)))
+        return fail(LPM_EALIGN, "device buffers must be 256-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    const int32_t first = s->first, last = s->last;
+    const bool acc = accumulate != 0;
+    char* ws = (char*)bwd_ws;
+    void* dzbuf = ws + s->dz_off;
+    void* kws = ws + s->kws_off;
+
+    // gradient buffer of every tensor, and whether it already holds a contribution
+    std::vector<void*> G((size_t)(last - first + 1), nullptr);
+    std::vector<char> have((size_t)(last - first + 1), 0);
+    auto gi = [&](int32_t t) { return (size_t)(t - (first - 1)); };
+    for (int32_t t = first; t < last; ++t)
+        if (s->T(t).loc == LOC_STASH) G[gi(t)] = ws + s->T(t).g_off;
+    G[gi(first - 1)] = dx;
+    int32_t top = last - 1;
+    if (s->loss) {
+        top = last - 2;
+        G[gi(top)] = const_cast<char*>((const char*)stash) + s->dlogits_off;
+    } else {
+        G[gi(top)] = const_cast<void*>(dy);
+    }
+    have[gi(top)] = 1;
+
+    for (int32_t i = top; i >= first; --i) {
+        const LayerRt& lr = s->Ly(i);
+        const lpm_layer& l = lr.d;
+        const void* g = G[gi(i)];
+        if (!have[gi(i)]) return fail(LPM_ESHAPE, "internal: tensor %d has no consumer", i);
+        const bool want_src = (l.src >= first) || (dx != nullptr);
+        switch (l.kind) {
+            case LPM_CONV:
+            case LPM_FC: {
+                const void* yout = tptr(s, i, x, y, stash);
+                const float* sc = lr.s_off != NO ? params + lr.s_off : nullptr;
+                const bool relu = (l.flags & LPM_RELU) != 0;
+                void* gadd = nullptr;
+                int gadd_acc = 0;
+                if (l.add_src != LPM_NONE && ((l.add_src >= first) || dx != nullptr)) {
+                    gadd = G[gi(l.add_src)];
+                    gadd_acc = have[gi(l.add_src)];
+                    have[gi(l.add_src)] = 1;
+                }
+                const void* dz = g;
+                if (relu || sc || gadd || lr.b_off != NO) {
+                    const bool need_dz = relu || sc;
+                    LPM_HIP(launch_epilogue_bwd(s->dtype, lr.g.rows_out(), l.cout, g, relu ? yout : nullptr, sc,
+                                                need_dz ? dzbuf : nullptr, gadd, gadd_acc,
+                                                lr.b_off != NO ? grads + lr.b_off : nullptr, acc, kws, st));
+                    if (need_dz) dz = dzbuf;
+                }
+                const void* xin = tptr(s, l.src, x, y, stash);
+                LPM_HIP(launch_conv_wgrad(s->dtype, lr.g, xin, dz, grads + lr.w_off, acc, kws, st));
+                if (want_src) {
+                    const void* w = s->dtype == LPM_BF16 ? (const void*)((const char*)lowp + lr.lowp_w_off)
+                                                         : (const void*)(params + lr.w_off);
+                    const void* wt = (s->dtype == LPM_BF16 && lr.lowp_wt_off != NO)
+                                         ? (const void*)((const char*)lowp + lr.lowp_wt_off) : nullptr;
+                    LPM_HIP(launch_conv_dgrad(s->dtype, lr.g, dz, w, wt, G[gi(l.src)], have[gi(l.src)], kws, st));
+                    have[gi(l.src)] = 1;
+                }
+                break;
+            }
+            case LPM_MAXPOOL2:
+                if (want_src) {
+                    LPM_HIP(launch_maxpool_bwd(s->dtype, s->m, l.h_in, l.w_in, l.cin, tptr(s, l.src, x, y, stash),
+                                               tptr(s, i, x, y, stash), g, G[gi(l.src)], have[gi(l.src)], st));
+                    have[gi(l.src)] = 1;
+                }
+                break;
+            case LPM_GAP:
+                if (want_src) {
+                    LPM_HIP(launch_gap_bwd(s->dtype, s->m, l.h_in * l.w_in, l.cin, g, G[gi(l.src)], have[gi(l.src)], st));
+                    have[gi(l.src)] = 1;
+                }
+                break;
+            default:
+                return fail(LPM_ESHAPE, "internal: unexpected layer kind in backward");
+        }
+    }
+    return LPM_OK;
+}
+
+extern "C" int32_t lpm_stage_update(lpm_stage* s, float* params, void* lowp, float* grads, float* momentum,
+                                    float lr_, float mu, int32_t zero_grads, void* stream) {
+    if (!s || !params || !grads || !momentum) return fail(LPM_EINVAL, "NULL argument");
+    if (s->dtype == LPM_BF16 && !lowp) return fail(LPM_EINVAL, "lowp is NULL for a bf16 stage");
+    if (misaligned(params) || misaligned(grads) || misaligned(momentum) || (lowp && misaligned(lowp)))
+        return fail(LPM_EALIGN, "device buffers must be 256-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    if (s->n_trainable == 0) return LPM_OK;
+    if (s->dtype != LPM_BF16) {
+        LPM_HIP(launch_sgd(params, nullptr, grads, momentum, s->n_trainable, lr_, mu, zero_grads, st));
+        return LPM_OK;
+    }
+    LPM_HIP(launch_sgd(params, (uint16_t*)lowp, grads, momentum, s->n_trainable, lr_, mu, zero_grads, st));
+    for (int32_t i = s->first; i < s->last; ++i) {
+        const LayerRt& lr = s->Ly(i);
+        if (lr.lowp_wt_off != NO)
+            LPM_HIP(launch_weight_transpose_bf16(params + lr.w_off, (uint16_t*)((char*)lowp + lr.lowp_wt_off), lr.d.cout,
+                                                 lr.d.kh * lr.d.kw, lr.d.cin, st));
+    }
+    return LPM_OK;
+}

@@ -1,0 +1,50 @@
+// Host-side layout of a stage (shared by the stage and schedule sources).
+#pragma once
+#include "lpm_internal.h"
+
+namespace lpm {
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static const size_t NO = (size_t)-1;
+
+enum Loc { LOC_X = 0, LOC_Y = 1, LOC_STASH = 2 };
+
+struct TensorRt {
+    Shape shape{};
+    size_t bytes = 0;
+    int loc = LOC_STASH;
+    size_t stash_off = NO;   // byte offset in a stash slot
+    size_t g_off = NO;       // byte offset of its gradient in the backward scratch
+};
+
+struct LayerRt {
+    lpm_layer d{};
+    ConvGeom g{};
+    size_t w_off = NO, b_off = NO, s_off = NO;   // float offsets into params
+    size_t w_count = 0;
+    size_t lowp_w_off = NO, lowp_wt_off = NO;    // byte offsets into lowp
+};
+
+}  // namespace lpm
+
+struct lpm_stage {
+    // (fields use the lpm:: types declared above)
+    int32_t first = 0, last = 0, m = 0, dtype = 0, L = 0;
+    bool loss = false;
+    size_t esz = 4;
+    std::vector<lpm_layer> net;
+    std::vector<lpm::Shape> shapes;
+    std::vector<lpm::LayerRt> lay;         // indexed by network layer index - first
+    std::vector<lpm::TensorRt> ten;        // indexed by tensor index - (first-1)
+    int32_t t_out = 0;                // tensor written to y
+    size_t n_trainable = 0, n_params = 0;   // floats
+    size_t lowp_bytes = 0, stash_bytes = 0, fwd_ws = 0, bwd_ws = 0;
+    size_t dlogits_off = lpm::NO, dz_off = lpm::NO, kws_off = lpm::NO;   // stash / bwd-scratch offsets
+    size_t kws_bytes = 0;
+
+    lpm::TensorRt& T(int32_t t) { return ten[(size_t)(t - (first - 1))]; }
+    const lpm::TensorRt& T(int32_t t) const { return ten[(size_t)(t - (first - 1))]; }
+    lpm::LayerRt& Ly(int32_t i) { return lay[(size_t)(i - first)]; }
+    const lpm::LayerRt& Ly(int32_t i) const { return lay[(size_t)(i - first)]; }
+};
+

@@ -1,0 +1,161 @@
+"""Shared driver for the GPU parity tests: runs the oracle and the HIP library on the same seeded
+inputs and compares tensor by tensor.
+
+Error measure (both element types): max_i |gpu_i - ref_i| / max_i |ref_i| per tensor, i.e. the error
+relative to the tensor's infinity norm; an element-wise relative error is meaningless at the zeros a
+ReLU produces.  Bars: 1e-4 for the float path, 2e-2 for the bf16 path.
+"""
+import copy
+
+import numpy as np
+
+import workloads as wl
+from oracle import lpm_oracle as orc
+
+TOL = {0: 1e-4, 1: 2e-2}
+
+
+def rel_err(got, ref):
+    got, ref = np.asarray(got, dtype=np.float64), np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def oracle_step(layers, starts, batch, M, bf16, seed, lr, mu, dx_wanted=False, bias_std=0.05, momentum_std=1e-3, steps=1):
+    params, mom = wl.make_params(layers, seed, bf16=bf16, bias_std=bias_std, momentum_std=momentum_std)
+    x, labels, g = wl.make_batch(layers, batch, seed, bf16=bf16)
+    p0, m0 = copy.deepcopy(params), copy.deepcopy(mom)
+    ref = None
+    for _ in range(steps):
+        ref = orc.run_schedule(layers, starts, params, mom, x, labels, g, M, lr, mu, orc.LOCKED, keep=True,
+                               input_grad=dx_wanted, store=orc.round_bf16 if bf16 else None)
+    return dict(p0=p0, m0=m0, x=x, labels=labels, g=g, ref=ref, params=params, mom=mom)
+
+
+def gpu_step(lpm, layers, starts, batch, M, dtype, o, lr, mu, mode, window=2, dx_wanted=False, steps=1):
+    import torch
+    net = lpm.Net(layers, starts, batch // M, M, dtype, window=window, dx_wanted=dx_wanted)
+    net.load_params(o["p0"], o["m0"])
+    xd = lpm.pack_act(o["x"], dtype)
+    ld = torch.from_numpy(o["labels"]).to("cuda:0") if o["labels"] is not None else None
+    gd = lpm.pack_act(o["g"], dtype) if o["g"] is not None else None
+    for _ in range(steps):
+        net.step(xd, ld, gd, lr, mu, mode)
+    torch.cuda.synchronize()
+    return net
+
+
+def compare(net, layers, starts, M, dtype, o, dx_wanted=False, window=2, report=None, backward=True):
+    """Compares loss, gradients, updated weights, momentum, and the last micro-batch's activations
+    and boundary gradients.  Returns {name: error}; asserts every error is under the bar.
+    backward=False restricts the comparison to the forward quantities (activations and loss)."""
+    tol = TOL[dtype]
+    ref = o["ref"]
+    errs = {}
+    if o["labels"] is not None:
+        errs["loss"] = abs(net.loss_value() - ref["loss"]) / max(abs(ref["loss"]), 1e-30)
+    g, p, v = net.read_grads(), net.read_params(), net.read_momentum()
+    for i in (o["params"] if backward else []):
+        for k in ("W", "b"):
+            if k in o["params"][i]:
+                errs["grad%d.%s" % (i, k)] = rel_err(g[i][k], ref["grads"][i][k])
+                errs["param%d.%s" % (i, k)] = rel_err(p[i][k], o["params"][i][k])
+                errs["mom%d.%s" % (i, k)] = rel_err(v[i][k], o["mom"][i][k])
+        if "s" in o["params"][i]:
+            errs["scale%d" % i] = rel_err(p[i]["s"], o["params"][i]["s"])
+    Z = len(starts) - 1
+    j = M - 1
+    slot = j % window
+    for z in range(Z):
+        stash = ref["stash"][(z, j)]
+        s = net.stages[z]
+        for t in range(starts[z], starts[z + 1]):
+            if layers[t]["kind"] == "softmax_ce":
+                continue
+            try:
+                got = net.read_stash(t, slot)
+            except Exception:
+                got = net.read_act_out(z, slot)
+            errs["act%d" % t] = rel_err(got, stash[t])
+        if backward and (z > 0 or dx_wanted):
+            errs["gin%d" % z] = rel_err(net.read_grad_in(z), ref["gin"][(z, j)])
+    bad = {k: e for k, e in errs.items() if not (e <= tol)}
+    if report is not None:
+        report.update(errs)
+    assert not bad, "over the %g bar: %s" % (tol, sorted(bad.items(), key=lambda kv: -kv[1])[:8])
+    return errs
+
+
+def l2_err(got, ref):
+    got, ref = np.asarray(got, dtype=np.float64), np.asarray(ref, dtype=np.float64)
+    return float(np.linalg.norm((got - ref).ravel()) / max(np.linalg.norm(ref.ravel()), 1e-30))
+
+
+def stage_backward_isolated(lpm, layers, starts, m, batch_total, dtype, seed, dx_wanted=False, bias_std=0.05,
+                            grad_std=1e-3, report=None):
+    """B_{z,j} of every stage on its own, at full micro-batch size, from a forward state prepared by the oracle.
+
+    The backward pass takes two integer decisions on stored activations (ReLU mask, position of a pooling
+    maximum).  In a deep bf16 network an end-to-end comparison lets last-bit differences of the forward
+    pass flip a few of them, which moves gradients by far more than any arithmetic tolerance, on either
+    side.  Here both sides take every decision on identical values: the oracle runs the forward pass
+    (storing bf16-rounded activations for the bf16 element type), its stored tensors are written into
+    the device buffers, and only lpm_stage_backward runs on the device.  Data flows oracle -> device only.
+    """
+    bf16 = dtype == 1
+    q = orc.round_bf16 if bf16 else (lambda a: a)
+    store = orc.round_bf16 if bf16 else None
+    params, _ = wl.make_params(layers, seed, bf16=bf16, bias_std=bias_std)
+    x, labels, g_up = wl.make_batch(layers, m, seed, bf16=bf16, grad_std=grad_std)
+    Z = len(starts) - 1
+    stashes, a = [], x
+    for z in range(Z):
+        last = z == Z - 1
+        a, stash, _ = orc.stage_forward(layers, starts[z], starts[z + 1], params, a,
+                                        labels if (last and labels is not None) else None, batch_total, store)
+        if "dlogits" in stash:
+            stash["dlogits"] = q(stash["dlogits"])
+        stashes.append(stash)
+    net = lpm.Net(layers, starts, m, 1, dtype, dx_wanted=dx_wanted)
+    net.load_params(params, None)
+    xd = lpm.pack_act(x, dtype)
+    tol = TOL[dtype]
+    errs = {}
+    g_out = g_up
+    for z in range(Z - 1, -1, -1):
+        s0, s1 = starts[z], starts[z + 1]
+        loss_stage = layers[s1 - 1]["kind"] == "softmax_ce"
+        dy = None if loss_stage else q(g_out)
+        grads = orc.zero_grads(layers, params)
+        want = z > 0 or dx_wanted
+        g_out = orc.stage_backward(layers, s0, s1, params, stashes[z], dy, grads, input_grad=want)
+        # device: prepared forward state in slot 0
+        for t in range(s0, s1 - 1):
+            if layers[t]["kind"] == "softmax_ce" or (loss_stage and t == s1 - 2):
+                continue
+            net.write_stash(t, 0, stashes[z][t])
+        t_out = s1 - 2 if loss_stage else s1 - 1
+        net.write_act_out(z, 0, stashes[z][t_out])
+        if loss_stage:
+            net.write_stash("dlogits", 0, stashes[z]["dlogits"])
+        if z > 0:
+            net.write_act_out(z - 1, 0, stashes[z][s0 - 1])
+        b = net.bufs[z]
+        xin = xd if z == 0 else net.bufs[z - 1]["act_out"][0]
+        dyd = None if loss_stage else lpm.pack_act(dy, dtype)
+        print("isolated backward stage", z, "layers", s0, s1, flush=True)
+        net.stages[z].backward(xin, b["act_out"][0], dyd, b["grad_in"] if want else None, b["params"], b["lowp"],
+                               b["stash"][0], b["grads"], 0, b["bwd_ws"], None)
+        net.torch.cuda.synchronize()
+        gg = net.read_grads()
+        for i in range(s0, s1):
+            for k in ("W", "b"):
+                if i in grads and k in grads[i]:
+                    errs["z%d.grad%d.%s" % (z, i, k)] = rel_err(gg[i][k], grads[i][k])
+        if want:
+            errs["z%d.dx" % z] = rel_err(net.read_grad_in(z), g_out)
+    if report is not None:
+        report.update(errs)
+    bad = {k: e for k, e in errs.items() if not (e <= tol)}
+    assert not bad, "over the %g bar: %s" % (tol, sorted(bad.items(), key=lambda kv: -kv[1])[:8])
+    return errs

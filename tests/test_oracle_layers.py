@@ -257,3 +257,28 @@ def test_sgd_momentum_pins():
     np.testing.assert_array_equal(params[0]["W"], p0)
     np.testing.assert_array_equal(params[0]["s"], np.ones(3))
     np.testing.assert_array_equal(params[1]["W"], p0 - 0.1 * g)
+
+
+def test_round_bf16_pins():
+    """bfloat16 = top 16 bits of float32, round to nearest, ties to even (hand-picked bit patterns)."""
+    cases = {1.0: 1.0, 1.00390625: 1.0,            # 1 + 2^-8: exactly half way between 1 and 1+2^-7 -> even (1.0)
+             1.01171875: 1.015625,                 # 1 + 3*2^-8: half way, rounds to even mantissa (1+2^-6)
+             1.005: 1.0078125, -2.7: -2.703125, 0.0: 0.0}
+    got = orc.round_bf16(np.array(list(cases.keys())))
+    np.testing.assert_allclose(got, np.array(list(cases.values())), rtol=1e-7)
+    r = np.random.default_rng(0)
+    a = r.standard_normal(10000) * 10.0 ** r.integers(-3, 4, 10000)
+    b = orc.round_bf16(a)
+    assert np.all(np.abs(b - a) <= np.abs(a) * 2.0 ** -8)                       # half an ulp of an 8-bit mantissa
+    assert np.all((b.astype(np.float32).view(np.uint32) & 0xFFFF) == 0)          # representable
+    np.testing.assert_array_equal(orc.round_bf16(b), b)                          # idempotent
+    import torch                                                                 # library conversion, CPU
+    np.testing.assert_array_equal(b, torch.tensor(a, dtype=torch.float32).bfloat16().double().numpy())
+    # with store=round_bf16 every stored activation is representable, the rest of the step is unchanged
+    layers = wl.tiny_vgg()
+    params, _ = wl.make_params(layers, seed=2, bf16=True)
+    x, labels, _ = wl.make_batch(layers, 2, seed=2, bf16=True)
+    _, stash, _ = orc.stage_forward(layers, 0, len(layers), params, x, labels, 2, store=orc.round_bf16)
+    for t, v in stash.items():
+        if t != "dlogits":
+            assert np.all((np.asarray(v).astype(np.float32).view(np.uint32) & 0xFFFF) == 0), t
