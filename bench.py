@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Benchmark of the partitioned training step on one MI355X.
+
+A "step" is one mini-batch pass of the whole hot path: every F_{z,j}, B_{z,j} of the planned
+partitions plus one update per stage (lpm_schedule_run, overlapped schedule replayed as a HIP graph),
+on synthetic inputs already resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload vgg16_cifar]
+
+Only one GPU is used; --gpus N with N > 1 exits with a message.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK = {"mfma_bf16": 2516.6e12, "fp32": 157.3e12, "hbm": 8.0e12}
+
+
+def conv_ops(layers, m, first_needs_dgrad=False):
+    """[(layer index, op, geometry dict, flops, ideal bytes)] for every contraction of one micro-batch."""
+    ops = []
+    for i, l in enumerate(layers):
+        if l["kind"] not in ("conv", "fc"):
+            continue
+        kh, kw = (l["h_in"], l["w_in"]) if l["kind"] == "fc" else (l["kh"], l["kw"])
+        s, p = (1, 0) if l["kind"] == "fc" else (l["stride"], l["pad"])
+        g = dict(m=m, h=l["h_in"], w=l["w_in"], cin=l["cin"], cout=l["cout"], kh=kh, kw=kw, stride=s, pad=p)
+        ho, wo = (g["h"] + 2 * p - kh) // s + 1, (g["w"] + 2 * p - kw) // s + 1
+        flops = 2 * m * ho * wo * l["cout"] * l["cin"] * kh * kw
+        in_el, out_el, w_el = m * g["h"] * g["w"] * l["cin"], m * ho * wo * l["cout"], l["cout"] * kh * kw * l["cin"]
+        ops.append((i, "fwd", g, flops, 2 * (in_el + out_el + w_el)))
+        if l["src"] >= 0 or first_needs_dgrad:
+            ops.append((i, "dgrad", g, flops, 2 * (in_el + out_el + w_el)))
+        ops.append((i, "wgrad", g, flops, 2 * (in_el + out_el) + 8 * w_el))
+    return ops
+
+
+def time_stream(torch, fn, iters, warm=3):
+    """Average duration in seconds of fn() enqueued `iters` times on torch's current stream, by HIP events."""
+    for _ in range(warm):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / iters
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="vgg16_cifar")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-layer-table", action="store_true", help="skip the per-contraction timing table")
+    ap.add_argument("--eager", action="store_true", help="enqueue the step kernel by kernel instead of replaying a graph")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); got --gpus %d" % args.gpus,
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import workloads as wl
+    import paper_2207_11019_amd as lpm
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+
+    builder, batch, M, Z, dt, fixed = wl.CONFIGS[args.workload]
+    layers = builder()
+    m = batch // M
+    dtype = lpm.BF16 if dt == "bf16" else lpm.F32
+    cp = dict(lpm.MI355X_COST[dt], link_byte_per_us=0, microbatch=m, n_microbatch=M)
+    fixed_starts = None
+    if fixed == "stage_boundaries":
+        fixed_starts = [0, 5, 10, 15, len(layers)]
+    starts, stage_cost = lpm.lpm_partition(layers, Z, cp, fixed_starts)
+    dx_wanted = layers[-1]["kind"] != "softmax_ce"
+    net = lpm.Net(layers, starts, m, M, dtype, window=2, dx_wanted=dx_wanted)
+    params, mom = wl.make_params(layers, bf16=(dt == "bf16"))
+    net.load_params(params, mom)
+    x, labels, g_up = wl.make_batch(layers, batch, bf16=(dt == "bf16"))
+    xd = lpm.pack_act(x, dtype)
+    ld = torch.from_numpy(labels).cuda() if labels is not None else None
+    gd = lpm.pack_act(g_up, dtype) if g_up is not None else None
+    lr, mu = 0.01, 0.9
+    gflag = 0 if args.eager else lpm.GRAPH
+
+    def run(mode, steps):
+        for _ in range(steps):
+            net.step(xd, ld, gd, lr, mu, mode | gflag)
+
+    def timed(mode, steps):
+        run(mode, args.warmup)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(mode, steps)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    t_locked = timed(lpm.LOCKED, args.steps)
+    t_over = timed(lpm.OVERLAPPED, args.steps)
+    ms_step = t_over / args.steps * 1e3
+    value = batch * args.steps / t_over
+
+    # ---- per-partition throughput: F + B of every micro-batch + U of one stage alone, on one stream
+    part = []
+    cur = torch.cuda.current_stream()
+    for z, s in enumerate(net.stages):
+        b = net.bufs[z]
+        xin = xd if z == 0 else net.bufs[z - 1]["act_out"][0]
+        loss_stage = layers[s.last - 1]["kind"] == "softmax_ce"
+        dy = None if loss_stage else (gd if z == net.Z - 1 else net.bufs[z + 1]["grad_in"])
+        dxp = b["grad_in"] if (z > 0 or dx_wanted) else None
+
+        def one(s=s, b=b, xin=xin, dy=dy, dxp=dxp, loss_stage=loss_stage):
+            for j in range(M):
+                s.forward(xin, b["act_out"][0], ld if loss_stage else None, net.loss if loss_stage else None, b["params"],
+                          b["lowp"], b["stash"][0], b["fwd_ws"], 1.0 / batch, cur)
+                s.backward(xin, b["act_out"][0], dy, dxp, b["params"], b["lowp"], b["stash"][0], b["grads"], j > 0,
+                           b["bwd_ws"], cur)
+            s.update(b["params"], b["lowp"], b["grads"], b["momentum"], 0.0, mu, False, cur)   # lr 0: weights stay put
+
+        t = time_stream(torch, one, max(3, args.steps // 3))
+        part.append(dict(stage=z, layers=[starts[z], starts[z + 1]], images_per_s=round(batch / t, 1),
+                         ms=round(t * 1e3, 4), model_cost_ps=int(stage_cost[z])))
+
+    # ---- per-contraction table and the roofline of the dominant kernel
+    roof, table = None, []
+    if not args.no_layer_table:
+        ops = conv_ops(layers, m, dx_wanted)
+        cache = {}
+        for (i, op, g, flops, byts) in ops:
+            key = (op,) + tuple(sorted(g.items()))
+            if key not in cache:
+                ho = (g["h"] + 2 * g["pad"] - g["kh"]) // g["stride"] + 1
+                wo = (g["w"] + 2 * g["pad"] - g["kw"]) // g["stride"] + 1
+                tdt = torch.bfloat16 if dtype == lpm.BF16 else torch.float32
+                K = g["kh"] * g["kw"] * g["cin"]
+                xx = torch.randn(g["m"] * g["h"] * g["w"] * g["cin"], device="cuda").to(tdt)
+                yy = torch.randn(g["m"] * ho * wo * g["cout"], device="cuda").to(tdt) * 1e-2
+                ww = (torch.randn(g["cout"] * K, device="cuda") * (2.0 / K) ** 0.5).to(tdt)
+                wt = ww.clone()
+                dw = torch.zeros(g["cout"] * K, device="cuda")
+                wsb = lpm.lpm_conv_ws_bytes(g, dtype)
+                ws = torch.empty(max(max(wsb), 256), dtype=torch.uint8, device="cuda")
+                if op == "fwd":
+                    fn = lambda: lpm.lpm_conv_forward(g, dtype, xx, ww, None, None, None, True, yy, ws, cur)
+                elif op == "dgrad":
+                    fn = lambda: lpm.lpm_conv_dgrad(g, dtype, yy, ww, wt if dtype == lpm.BF16 else None, xx, False, ws, cur)
+                else:
+                    fn = lambda: lpm.lpm_conv_wgrad(g, dtype, xx, yy, dw, True, ws, cur)
+                cache[key] = time_stream(torch, fn, 20)
+            t = cache[key]
+            ai = flops / byts
+            peak_f = PEAK["mfma_bf16"] if dtype == lpm.BF16 else PEAK["fp32"]
+            bound = "mfma" if ai >= peak_f / PEAK["hbm"] else "hbm"
+            table.append(dict(layer=i, op=op, shape="m%d %dx%dx%d->%d k%d s%d" % (g["m"], g["h"], g["w"], g["cin"], g["cout"],
+                                                                                    g["kh"], g["stride"]),
+                              us=round(t * 1e6, 2), tflops=round(flops / t / 1e12, 2), gbps=round(byts / t / 1e9, 1),
+                              bound=bound, flops=flops, bytes=byts, per_step_us=round(t * 1e6 * M, 1)))
+        dom = max(table, key=lambda r: r["per_step_us"])
+        t = dom["us"] * 1e-6
+        if dom["bound"] == "mfma":
+            peak_f = PEAK["mfma_bf16"] if dtype == lpm.BF16 else PEAK["fp32"]
+            roof = dict(bound="mfma", achieved=round(dom["flops"] / t / 1e12, 3), peak=peak_f / 1e12, unit="TFLOP/s",
+                        frac=round(dom["flops"] / t / peak_f, 5), traffic=None)
+        else:
+            roof = dict(bound="hbm", achieved=round(dom["bytes"] / t / 1e9, 2), peak=PEAK["hbm"] / 1e9, unit="GB/s",
+                        frac=round(dom["bytes"] / t / PEAK["hbm"], 5), traffic=None)
+        roof["kernel"] = "conv %s, layer %d (%s)" % (dom["op"], dom["layer"], dom["shape"])
+        roof["avg_us"] = dom["us"]
+        tot_flops = sum(r["flops"] for r in table) * M
+        roof["step_contraction_flops"] = tot_flops
+        roof["step_frac_of_mfma_peak"] = round(tot_flops / (ms_step * 1e-3) / (PEAK["mfma_bf16"] if dtype == lpm.BF16 else PEAK["fp32"]), 5)
+
+    # ---- the oracle on the host cores, on a bounded sample of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import lpm_oracle as orc
+        import copy
+        n_mb = 2 if args.workload in ("vgg16_cifar", "lenet") else 1
+        if args.workload == "lenet":
+            n_mb = M
+        xs = x[: n_mb * m]
+        ls = labels[: n_mb * m] if labels is not None else None
+        gs = g_up[: n_mb * m] if g_up is not None else None
+        p2, m2 = copy.deepcopy(params), copy.deepcopy(mom)
+        orc.run_schedule(layers, starts, p2, m2, xs[:m], ls[:m] if ls is not None else None,
+                         gs[:m] if gs is not None else None, 1, lr, mu, orc.LOCKED, input_grad=dx_wanted)   # warm-up
+        t0 = time.perf_counter()
+        orc.run_schedule(layers, starts, p2, m2, xs, ls, gs, n_mb, lr, mu, orc.LOCKED, input_grad=dx_wanted)
+        tc = time.perf_counter() - t0
+        cpu = dict(value=round(n_mb * m / tc, 3), unit="images/s", cores=int(os.environ.get("OMP_NUM_THREADS", os.cpu_count())),
+                   kind="oracle", sample="%d of %d micro-batches (%d images), locked schedule, forward+backward+update, fp64"
+                   % (n_mb, M, n_mb * m), seconds=round(tc, 2))
+
+    out = {
+        "metric": "partition train images/s (fwd+bwd+update) + % bf16 MFMA peak, 1 GPU",
+        "value": round(value, 2), "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dt, "data": "synthetic",
+        "config": {"workload": args.workload, "global_batch": batch, "n_microbatch": M, "microbatch": m, "partitions": Z,
+                   "plan": starts, "schedule": "overlapped, 2 HIP streams, window 2" + ("" if args.eager else ", graph replay"),
+                   "lr": lr, "momentum": mu},
+        "locked_ms_per_step": round(t_locked / args.steps * 1e3, 4),
+        "overlap_speedup": round(t_locked / t_over, 4),
+        "partitions": part,
+        "roofline": roof,
+        "cpu_baseline": cpu,
+    }
+    if table:
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "layer_table_%s.json" % args.workload), "w") as f:
+            json.dump(table, f, indent=1)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -236,6 +236,32 @@ int32_t lpm_schedule_run(lpm_schedule* s, int32_t mode, const void* x_batch, con
                          const void* dy_batch, const lpm_stage_buffers* per_stage, int32_t dx_wanted,
                          float lr, float mu, float* loss_out, void* stream_fwd, void* stream_bwd);
 
+/* ---- single-layer contractions (the kernels inside F and B), for tests and measurement ---------- */
+
+/* Geometry of one convolution on a micro-batch of m samples: input [m][h][w][cin], weights
+ * [cout][kh][kw][cin], output [m][ho][wo][cout] with ho = (h + 2*pad - kh)/stride + 1 (same for wo).
+ * A fully connected layer is kh = h, kw = w, stride 1, pad 0. */
+typedef struct lpm_conv_geom {
+    int32_t m, h, w, cin, cout, kh, kw, stride, pad;
+} lpm_conv_geom;
+
+/* Scratch bytes the three contractions need for this geometry (host out-pointers, any may be NULL). */
+int32_t lpm_conv_ws_bytes(const lpm_conv_geom* g, int32_t dtype, size_t* fwd, size_t* dgrad, size_t* wgrad);
+
+/* y = relu?( scale_c * (w (*) x) + bias_c + add )  -- eq. 1 for a convolution / FC layer.
+ *   w: float weights for LPM_F32, bf16 weights for LPM_BF16; scale, bias, add may be NULL. */
+int32_t lpm_conv_forward(const lpm_conv_geom* g, int32_t dtype, const void* x, const void* w, const float* scale,
+                         const float* bias, const void* add, int32_t relu, void* y, void* ws, void* stream);
+
+/* dx (+)= gradient w.r.t. the layer input given dz, the gradient w.r.t. its pre-activation -- eq. 9.
+ *   wt: the same weights laid out [cin][kh][kw][cout] (bf16), or NULL when the caller has none. */
+int32_t lpm_conv_dgrad(const lpm_conv_geom* g, int32_t dtype, const void* dz, const void* w, const void* wt, void* dx,
+                       int32_t accumulate, void* ws, void* stream);
+
+/* dw (+)= gradient w.r.t. the weights, float [cout][kh][kw][cin] -- eq. 8. */
+int32_t lpm_conv_wgrad(const lpm_conv_geom* g, int32_t dtype, const void* x, const void* dz, float* dw,
+                       int32_t accumulate, void* ws, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -9,7 +9,7 @@ import os
 
 import numpy as np
 
-__all__ = ["LpmError", "lib", "lpm_layer", "lpm_cost_params", "lpm_stage_buffers", "layers_from_dicts",
+__all__ = ["LpmError", "lib", "lpm_conv_geom", "lpm_conv_ws_bytes", "lpm_conv_forward", "lpm_conv_dgrad", "lpm_conv_wgrad", "lpm_layer", "lpm_cost_params", "lpm_stage_buffers", "layers_from_dicts",
            "lpm_layer_cost", "lpm_partition", "Stage", "Schedule", "Net", "F32", "BF16", "LOCKED", "OVERLAPPED",
            "GRAPH", "pack_act", "unpack_act", "pack_weight", "unpack_weight", "MI355X_COST"]
 
@@ -49,6 +49,10 @@ class lpm_stage_buffers(C.Structure):
                 ("fwd_ws", C.c_void_p), ("bwd_ws", C.c_void_p)]
 
 
+class lpm_conv_geom(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("m", "h", "w", "cin", "cout", "kh", "kw", "stride", "pad")]
+
+
 lib.lpm_last_error.restype = C.c_char_p
 _vp, _i32, _sz = C.c_void_p, C.c_int32, C.c_size_t
 _psz = C.POINTER(C.c_size_t)
@@ -69,7 +73,11 @@ lib.lpm_schedule_create.argtypes = [C.POINTER(_vp), _i32, _i32, _i32, C.POINTER(
 lib.lpm_schedule_destroy.argtypes = [_vp]
 lib.lpm_schedule_run.argtypes = [_vp, _i32, _vp, _vp, _vp, C.POINTER(lpm_stage_buffers), _i32, C.c_float, C.c_float,
                                  _vp, _vp, _vp]
-for _f in ("lpm_layer_cost", "lpm_partition", "lpm_stage_create", "lpm_stage_destroy", "lpm_stage_sizes",
+lib.lpm_conv_ws_bytes.argtypes = [C.POINTER(lpm_conv_geom), _i32, _psz, _psz, _psz]
+lib.lpm_conv_forward.argtypes = [C.POINTER(lpm_conv_geom), _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]
+lib.lpm_conv_dgrad.argtypes = [C.POINTER(lpm_conv_geom), _i32, _vp, _vp, _vp, _vp, _i32, _vp, _vp]
+lib.lpm_conv_wgrad.argtypes = [C.POINTER(lpm_conv_geom), _i32, _vp, _vp, _vp, _i32, _vp, _vp]
+for _f in ("lpm_conv_ws_bytes", "lpm_conv_forward", "lpm_conv_dgrad", "lpm_conv_wgrad", "lpm_layer_cost", "lpm_partition", "lpm_stage_create", "lpm_stage_destroy", "lpm_stage_sizes",
            "lpm_stage_param_offset", "lpm_stage_stash_offset", "lpm_stage_grad_offset", "lpm_stage_sync_lowp",
            "lpm_stage_forward", "lpm_stage_backward", "lpm_stage_update", "lpm_schedule_create",
            "lpm_schedule_destroy", "lpm_schedule_run"):
@@ -126,6 +134,35 @@ def lpm_partition(layers, Z, cp, fixed_starts=None):
         fixed = (C.c_int32 * (Z + 1))(*fixed_starts)
     _check(lib.lpm_partition(arr, len(arr), Z, C.byref(c), fixed, starts, cost))
     return list(starts), list(cost)
+
+
+def _geom(g):
+    return g if isinstance(g, lpm_conv_geom) else lpm_conv_geom(*[g[k] for k in ("m", "h", "w", "cin", "cout", "kh", "kw", "stride", "pad")])
+
+
+def lpm_conv_ws_bytes(g, dtype):
+    """-> (fwd, dgrad, wgrad) scratch bytes"""
+    v = [C.c_size_t() for _ in range(3)]
+    gg = _geom(g)
+    _check(lib.lpm_conv_ws_bytes(C.byref(gg), dtype, *[C.byref(x) for x in v]))
+    return tuple(x.value for x in v)
+
+
+def lpm_conv_forward(g, dtype, x, w, scale, bias, add, relu, y, ws=None, stream=None):
+    gg = _geom(g)
+    _check(lib.lpm_conv_forward(C.byref(gg), dtype, _ptr(x), _ptr(w), _ptr(scale), _ptr(bias), _ptr(add), int(relu), _ptr(y),
+                                _ptr(ws), _stream(stream)))
+
+
+def lpm_conv_dgrad(g, dtype, dz, w, wt, dx, accumulate=False, ws=None, stream=None):
+    gg = _geom(g)
+    _check(lib.lpm_conv_dgrad(C.byref(gg), dtype, _ptr(dz), _ptr(w), _ptr(wt), _ptr(dx), int(accumulate), _ptr(ws),
+                              _stream(stream)))
+
+
+def lpm_conv_wgrad(g, dtype, x, dz, dw, accumulate=False, ws=None, stream=None):
+    gg = _geom(g)
+    _check(lib.lpm_conv_wgrad(C.byref(gg), dtype, _ptr(x), _ptr(dz), _ptr(dw), int(accumulate), _ptr(ws), _stream(stream)))
 
 
 def _ptr(t):

@@ -1,0 +1,68 @@
+// Single-layer entry points: the contractions of eq. 1 (forward), eq. 9 (data gradient) and eq. 8
+// (weight gradient) on their own, for layer-level tests and per-kernel measurement.
+#include "lpm_internal.h"
+
+using namespace lpm;
+
+static int32_t to_geom(const lpm_conv_geom* g, int32_t dtype, ConvGeom& out) {
+    if (!g) return fail(LPM_EINVAL, "geometry is NULL");
+    if (dtype != LPM_F32 && dtype != LPM_BF16) return fail(LPM_EINVAL, "dtype must be LPM_F32 or LPM_BF16");
+    if (g->m <= 0 || g->h <= 0 || g->w <= 0 || g->cin <= 0 || g->cout <= 0 || g->kh <= 0 || g->kw <= 0 || g->stride <= 0 ||
+        g->pad < 0 || g->pad >= g->kh || g->pad >= g->kw)
+        return fail(LPM_ESHAPE, "bad convolution geometry");
+    const int32_t ho = g->h + 2 * g->pad - g->kh, wo = g->w + 2 * g->pad - g->kw;
+    if (ho < 0 || wo < 0) return fail(LPM_ESHAPE, "kernel larger than padded input");
+    out = ConvGeom{g->m, g->h, g->w, g->cin, ho / g->stride + 1, wo / g->stride + 1, g->cout, g->kh, g->kw, g->stride, g->pad};
+    return LPM_OK;
+}
+
+static bool bad_align(std::initializer_list<const void*> ps) {
+    for (const void* p : ps) if (p && ((uintptr_t)p & 255u)) return true;
+    return false;
+}
+
+extern "C" int32_t lpm_conv_ws_bytes(const lpm_conv_geom* g, int32_t dtype, size_t* fwd, size_t* dgrad, size_t* wgrad) {
+    ConvGeom cg;
+    int32_t rc = to_geom(g, dtype, cg);
+    if (rc) return rc;
+    if (fwd) *fwd = fwd_ws_bytes(dtype, cg);
+    if (dgrad) *dgrad = dgrad_ws_bytes(dtype, cg);
+    if (wgrad) *wgrad = wgrad_ws_bytes(dtype, cg);
+    return LPM_OK;
+}
+
+extern "C" int32_t lpm_conv_forward(const lpm_conv_geom* g, int32_t dtype, const void* x, const void* w, const float* scale,
+                                    const float* bias, const void* add, int32_t relu, void* y, void* ws, void* stream) {
+    ConvGeom cg;
+    int32_t rc = to_geom(g, dtype, cg);
+    if (rc) return rc;
+    if (!x || !w || !y) return fail(LPM_EINVAL, "NULL argument");
+    if (fwd_ws_bytes(dtype, cg) && !ws) return fail(LPM_EINVAL, "scratch required");
+    if (bad_align({x, w, scale, bias, add, y, ws})) return fail(LPM_EALIGN, "device buffers must be 256-byte aligned");
+    LPM_HIP(launch_conv_fwd(dtype, cg, x, w, scale, bias, add, relu != 0, y, ws, (hipStream_t)stream));
+    return LPM_OK;
+}
+
+extern "C" int32_t lpm_conv_dgrad(const lpm_conv_geom* g, int32_t dtype, const void* dz, const void* w, const void* wt,
+                                  void* dx, int32_t accumulate, void* ws, void* stream) {
+    ConvGeom cg;
+    int32_t rc = to_geom(g, dtype, cg);
+    if (rc) return rc;
+    if (!dz || !w || !dx) return fail(LPM_EINVAL, "NULL argument");
+    if (dgrad_ws_bytes(dtype, cg) && !ws) return fail(LPM_EINVAL, "scratch required");
+    if (bad_align({dz, w, wt, dx, ws})) return fail(LPM_EALIGN, "device buffers must be 256-byte aligned");
+    LPM_HIP(launch_conv_dgrad(dtype, cg, dz, w, wt, dx, accumulate != 0, ws, (hipStream_t)stream));
+    return LPM_OK;
+}
+
+extern "C" int32_t lpm_conv_wgrad(const lpm_conv_geom* g, int32_t dtype, const void* x, const void* dz, float* dw,
+                                  int32_t accumulate, void* ws, void* stream) {
+    ConvGeom cg;
+    int32_t rc = to_geom(g, dtype, cg);
+    if (rc) return rc;
+    if (!x || !dz || !dw) return fail(LPM_EINVAL, "NULL argument");
+    if (wgrad_ws_bytes(dtype, cg) && !ws) return fail(LPM_EINVAL, "scratch required");
+    if (bad_align({x, dz, dw, ws})) return fail(LPM_EALIGN, "device buffers must be 256-byte aligned");
+    LPM_HIP(launch_conv_wgrad(dtype, cg, x, dz, dw, accumulate != 0, ws, (hipStream_t)stream));
+    return LPM_OK;
+}
