@@ -1,4 +1,6 @@
-// Chooses the contraction kernel for a convolution / FC shape.
+// Chooses the contraction kernel for a convolution / FC shape: bf16 MFMA implicit GEMM where the
+// channel counts allow 16-byte K chunks, the shape-generic kernels otherwise (float element type,
+// 3-channel first layer, 10-class head).
 #include "lpm_internal.h"
 
 namespace lpm {
@@ -11,22 +13,40 @@ hipError_t conv_wgrad_generic_launch(int dtype, const ConvGeom& g, const void* x
                                      int accumulate, void* ws, hipStream_t s);
 size_t wgrad_generic_ws_bytes(const ConvGeom& g);
 
-size_t fwd_ws_bytes(int, const ConvGeom&) { return 0; }
-size_t dgrad_ws_bytes(int, const ConvGeom&) { return 0; }
-size_t wgrad_ws_bytes(int, const ConvGeom& g) { return wgrad_generic_ws_bytes(g); }
+bool mfma_fwd_ok(const ConvGeom& g);
+bool mfma_dgrad_ok(const ConvGeom& g);
+bool mfma_wgrad_ok(const ConvGeom& g);
+size_t mfma_fwd_ws_bytes(const ConvGeom& g);
+size_t mfma_dgrad_ws_bytes(const ConvGeom& g);
+size_t mfma_wgrad_ws_bytes(const ConvGeom& g);
+hipError_t mfma_conv_fwd(const ConvGeom& g, const void* x, const void* w, const float* scale, const float* bias,
+                         const void* add, int relu, void* y, void* ws, hipStream_t st);
+hipError_t mfma_conv_dgrad(const ConvGeom& g, const void* dz, const void* wt, void* dx, int accumulate, void* ws,
+                           hipStream_t st);
+hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, int accumulate, void* ws,
+                           hipStream_t st);
+
+size_t fwd_ws_bytes(int dtype, const ConvGeom& g) { return (dtype == LPM_BF16 && mfma_fwd_ok(g)) ? mfma_fwd_ws_bytes(g) : 0; }
+size_t dgrad_ws_bytes(int dtype, const ConvGeom& g) { return (dtype == LPM_BF16 && mfma_dgrad_ok(g)) ? mfma_dgrad_ws_bytes(g) : 0; }
+size_t wgrad_ws_bytes(int dtype, const ConvGeom& g) {
+    return (dtype == LPM_BF16 && mfma_wgrad_ok(g)) ? mfma_wgrad_ws_bytes(g) : wgrad_generic_ws_bytes(g);
+}
 
 hipError_t launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, const float* scale,
-                           const float* bias, const void* add, int relu, void* y, void*, hipStream_t st) {
+                           const float* bias, const void* add, int relu, void* y, void* ws, hipStream_t st) {
+    if (dtype == LPM_BF16 && mfma_fwd_ok(g)) return mfma_conv_fwd(g, x, w, scale, bias, add, relu, y, ws, st);
     return conv_fwd_generic_launch(dtype, g, x, w, scale, bias, add, relu, y, st);
 }
 
-hipError_t launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dz, const void* w, const void*, void* dx,
-                             int accumulate, void*, hipStream_t st) {
+hipError_t launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dz, const void* w, const void* wt, void* dx,
+                             int accumulate, void* ws, hipStream_t st) {
+    if (dtype == LPM_BF16 && wt && mfma_dgrad_ok(g)) return mfma_conv_dgrad(g, dz, wt, dx, accumulate, ws, st);
     return conv_dgrad_generic_launch(dtype, g, dz, w, dx, accumulate, st);
 }
 
 hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const void* dz, float* dw, int accumulate,
                              void* ws, hipStream_t st) {
+    if (dtype == LPM_BF16 && mfma_wgrad_ok(g)) return mfma_conv_wgrad(g, x, dz, dw, accumulate, ws, st);
     return conv_wgrad_generic_launch(dtype, g, x, dz, dw, accumulate, ws, st);
 }
 

@@ -1,0 +1,463 @@
+// bf16 MFMA implicit-GEMM contractions for gfx950: convolution forward (eq. 1), data gradient (eq. 9)
+// and weight gradient (eq. 8), fp32 accumulation, LDS-staged 32-deep K tiles, 4 wavefronts per block.
+//
+// Forward / data gradient:  C[M][N] = A[M][K] * B[N][K]^T
+//   forward  rows = output pixels, A gathered from x [m][H][W][Cin],  B = w  [Cout][Kh][Kw][Cin]
+//   dgrad    rows = input pixels,  A gathered from dz [m][Ho][Wo][Cout], B = wt [Cin][Kh][Kw][Cout]
+//   K runs over (kh, kw, channel); a 32-wide K tile lies inside one filter tap (channels % 32 == 0).
+// Weight gradient:  dW[co][tap][ci] = sum_rows dz[row][co] * x[pixel(row,tap)][ci]
+//   both operands are stored with the reduction index (the pixel) outermost, so the loader transposes
+//   4 pixels x 8 channels in registers before writing K-contiguous rows to LDS.
+// The matrix instruction is v_mfma_f32_32x32x16_bf16: each lane supplies 8 consecutive K values of row
+// (lane % 32); lane holds D[(i/4)*8 + (lane/32)*4 + i%4][lane % 32] in accumulator element i.
+#include "lpm_internal.h"
+#include "elem.h"
+
+namespace lpm {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+constexpr int BK = 32;    // K tile
+constexpr int LDK = 40;   // LDS row stride in elements (80 bytes: 16-byte aligned, staggers banks)
+
+enum { MODE_FWD = 0, MODE_DGRAD = 1 };
+
+struct IgemmArgs {
+    const uint16_t* A;
+    const uint16_t* B;
+    uint16_t* C;          // bf16 output [M][N]
+    float* part;          // split-K: fp32 partials [split][M][N]; NULL otherwise
+    const float* scale;
+    const float* bias;
+    const uint16_t* add;
+    int relu, accumulate;
+    int M, N, Ktot;
+    int Hi, Wi, Ci;       // extent of the gathered tensor
+    int Hr, Wr;           // extent of the row space
+    int Kw, stride, pad;
+    int kt_total, kt_per_split;
+};
+
+// XCD-aware tile order: consecutive workgroup ids land on different XCDs (each with its own L2), so give
+// every XCD one contiguous range of tiles.
+__device__ __forceinline__ int xcd_remap(int bid, int nblocks) {
+    const int per = nblocks >> 3, rem = nblocks & 7;
+    const int xcd = bid & 7, idx = bid >> 3;
+    return xcd * per + min(xcd, rem) + idx;
+}
+
+template <int BM, int BN, int WGM, int WGN>
+struct TileCfg {
+    static constexpr int WTM = BM / WGM, WTN = BN / WGN, MI = WTM / 32, NI = WTN / 32;
+    static_assert(WGM * WGN == 4 && WTM % 32 == 0 && WTN % 32 == 0, "4 wavefronts, 32x32 MFMA tiles");
+};
+
+// acc[mi][ni] += A-tile(wave rows) * B-tile(wave cols) over one 32-deep K tile held in LDS
+template <int MI, int NI>
+__device__ __forceinline__ void mma_tile(const uint16_t* As, const uint16_t* Bs, int arow0, int brow0, int lane,
+                                         f32x16 (&acc)[MI][NI]) {
+    const int r = lane & 31, kq = (lane >> 5) * 8;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+        bf16x8 a[MI], b[NI];
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+            a[mi] = *reinterpret_cast<const bf16x8*>(As + (arow0 + mi * 32 + r) * LDK + ks * 16 + kq);
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+            b[ni] = *reinterpret_cast<const bf16x8*>(Bs + (brow0 + ni * 32 + r) * LDK + ks * 16 + kq);
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+    }
+}
+
+template <int BM, int BN, int WGM, int WGN, int MODE>
+__global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs p) {
+    typedef TileCfg<BM, BN, WGM, WGN> Cfg;
+    constexpr int A_CH = (BM * 4 + 255) / 256, B_CH = (BN * 4 + 255) / 256;
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][BM * LDK];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN * LDK];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nt = (p.N + BN - 1) / BN;
+    const int tile = xcd_remap(blockIdx.x, gridDim.x);
+    const int m0 = (tile / nt) * BM, n0 = (tile % nt) * BN;
+    const int kt0 = blockIdx.z * p.kt_per_split;
+    const int kt1 = min(p.kt_total, kt0 + p.kt_per_split);
+
+    // per-thread gather state of its A chunks (a chunk = 8 channels of one row = 16 bytes)
+    int a_nb[A_CH], a_h0[A_CH], a_w0[A_CH];
+    bool a_ok[A_CH];
+#pragma unroll
+    for (int c = 0; c < A_CH; ++c) {
+        const int id = tid + c * 256, row = m0 + (id >> 2);
+        a_ok[c] = (id < BM * 4) && row < p.M;
+        const int rr = a_ok[c] ? row : 0;
+        const int wq = rr % p.Wr, t = rr / p.Wr, hq = t % p.Hr, n = t / p.Hr;
+        a_nb[c] = n * p.Hi * p.Wi;
+        if (MODE == MODE_FWD) { a_h0[c] = hq * p.stride - p.pad; a_w0[c] = wq * p.stride - p.pad; }
+        else { a_h0[c] = hq + p.pad; a_w0[c] = wq + p.pad; }
+    }
+    uint4 ra[A_CH], rb[B_CH];
+
+    auto load_tile = [&](int kt) {
+        const int k0 = kt * BK;
+        const int tap = k0 / p.Ci, c0 = k0 - tap * p.Ci;
+        const int kh = tap / p.Kw, kw = tap - kh * p.Kw;
+#pragma unroll
+        for (int c = 0; c < A_CH; ++c) {
+            const int id = tid + c * 256, kc = id & 3;
+            int h, w;
+            bool ok = a_ok[c];
+            if (MODE == MODE_FWD) { h = a_h0[c] + kh; w = a_w0[c] + kw; }
+            else {
+                h = a_h0[c] - kh; w = a_w0[c] - kw;
+                if (p.stride != 1) {
+                    ok = ok && h >= 0 && w >= 0 && (h % p.stride) == 0 && (w % p.stride) == 0;
+                    h /= p.stride; w /= p.stride;
+                }
+            }
+            ok = ok && (unsigned)h < (unsigned)p.Hi && (unsigned)w < (unsigned)p.Wi;
+            ra[c] = make_uint4(0, 0, 0, 0);
+            if (ok) ra[c] = *reinterpret_cast<const uint4*>(p.A + ((size_t)(a_nb[c] + h * p.Wi + w) * p.Ci + c0 + kc * 8));
+        }
+#pragma unroll
+        for (int c = 0; c < B_CH; ++c) {
+            const int id = tid + c * 256, n = n0 + (id >> 2), kc = id & 3;
+            rb[c] = make_uint4(0, 0, 0, 0);
+            if (id < BN * 4 && n < p.N) rb[c] = *reinterpret_cast<const uint4*>(p.B + ((size_t)n * p.Ktot + k0 + kc * 8));
+        }
+    };
+    auto store_tile = [&](int buf) {
+#pragma unroll
+        for (int c = 0; c < A_CH; ++c) {
+            const int id = tid + c * 256;
+            if (id < BM * 4) *reinterpret_cast<uint4*>(&As[buf][(id >> 2) * LDK + (id & 3) * 8]) = ra[c];
+        }
+#pragma unroll
+        for (int c = 0; c < B_CH; ++c) {
+            const int id = tid + c * 256;
+            if (id < BN * 4) *reinterpret_cast<uint4*>(&Bs[buf][(id >> 2) * LDK + (id & 3) * 8]) = rb[c];
+        }
+    };
+
+    f32x16 acc[Cfg::MI][Cfg::NI];
+#pragma unroll
+    for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < Cfg::NI; ++ni)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+
+    const int wm = wave / WGN, wn = wave % WGN;
+    if (kt0 < kt1) {
+        load_tile(kt0);
+        store_tile(0);
+        __syncthreads();
+        for (int kt = kt0; kt < kt1; ++kt) {
+            const int buf = (kt - kt0) & 1;
+            if (kt + 1 < kt1) load_tile(kt + 1);
+            mma_tile<Cfg::MI, Cfg::NI>(As[buf], Bs[buf], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
+            if (kt + 1 < kt1) store_tile(buf ^ 1);
+            __syncthreads();
+        }
+    }
+
+    // epilogue
+    const int col_l = lane & 31, rq = (lane >> 5) * 4;
+#pragma unroll
+    for (int ni = 0; ni < Cfg::NI; ++ni) {
+        const int col = n0 + wn * Cfg::WTN + ni * 32 + col_l;
+        if (col >= p.N) continue;
+        const float sc = (p.scale && !p.part) ? p.scale[col] : 1.f;
+        const float bi = (p.bias && !p.part) ? p.bias[col] : 0.f;
+#pragma unroll
+        for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int row = m0 + wm * Cfg::WTM + mi * 32 + (i >> 2) * 8 + rq + (i & 3);
+                if (row >= p.M) continue;
+                const size_t o = (size_t)row * p.N + col;
+                float v = acc[mi][ni][i];
+                if (p.part) { p.part[(size_t)blockIdx.z * p.M * p.N + o] = v; continue; }
+                v = v * sc + bi;
+                if (p.add) v += bf2f(p.add[o]);
+                if (p.accumulate) v += bf2f(p.C[o]);
+                if (p.relu) v = fmaxf(v, 0.f);
+                p.C[o] = f2bf(v);
+            }
+    }
+}
+
+// sums split-K partials in split order and applies the epilogue
+__global__ void __launch_bounds__(256) splitk_epilogue(const float* __restrict__ part, int splits, int64_t MN, int N,
+                                                       const float* __restrict__ scale, const float* __restrict__ bias,
+                                                       const uint16_t* __restrict__ add, int relu, int accumulate,
+                                                       uint16_t* __restrict__ C) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= MN) return;
+    float v = part[i];
+    for (int s = 1; s < splits; ++s) v += part[(int64_t)s * MN + i];
+    const int col = (int)(i % N);
+    if (scale) v *= scale[col];
+    if (bias) v += bias[col];
+    if (add) v += bf2f(add[i]);
+    if (accumulate) v += bf2f(C[i]);
+    if (relu) v = fmaxf(v, 0.f);
+    C[i] = f2bf(v);
+}
+
+// --------------------------------------------------------------------------------------------------
+struct IgemmPlan { int big; int splits; int kt_total; int kt_per; };
+
+static IgemmPlan plan_igemm(int64_t M, int N, int Ktot) {
+    IgemmPlan pl{};
+    pl.kt_total = Ktot / BK;
+    const int64_t b128 = ((M + 127) / 128) * ((N + 127) / 128);
+    pl.big = b128 >= 160;
+    pl.splits = 1;
+    if (!pl.big) {
+        const int64_t b64 = ((M + 63) / 64) * ((N + 63) / 64);
+        int s = (int)((384 + b64 - 1) / b64);
+        const int smax = pl.kt_total / 4;
+        if (s > smax) s = smax;
+        if (s > 32) s = 32;
+        if (s < 1) s = 1;
+        pl.splits = s;
+    }
+    pl.kt_per = (pl.kt_total + pl.splits - 1) / pl.splits;
+    pl.splits = (pl.kt_total + pl.kt_per - 1) / pl.kt_per;
+    return pl;
+}
+
+static hipError_t run_igemm(int mode, IgemmArgs a, void* ws, hipStream_t st) {
+    const IgemmPlan pl = plan_igemm(a.M, a.N, a.Ktot);
+    a.kt_total = pl.kt_total;
+    a.kt_per_split = pl.kt_per;
+    a.part = pl.splits > 1 ? (float*)ws : nullptr;
+    if (pl.big) {
+        const dim3 grid((unsigned)(((a.M + 127) / 128) * ((a.N + 127) / 128)), 1, pl.splits);
+        if (mode == MODE_FWD) hipLaunchKernelGGL((igemm_kernel<128, 128, 2, 2, MODE_FWD>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((igemm_kernel<128, 128, 2, 2, MODE_DGRAD>), grid, dim3(256), 0, st, a);
+    } else {
+        const dim3 grid((unsigned)(((a.M + 63) / 64) * ((a.N + 63) / 64)), 1, pl.splits);
+        if (mode == MODE_FWD) hipLaunchKernelGGL((igemm_kernel<64, 64, 2, 2, MODE_FWD>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((igemm_kernel<64, 64, 2, 2, MODE_DGRAD>), grid, dim3(256), 0, st, a);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || pl.splits == 1) return e;
+    const int64_t MN = (int64_t)a.M * a.N;
+    hipLaunchKernelGGL(splitk_epilogue, dim3((unsigned)((MN + 255) / 256)), dim3(256), 0, st, (const float*)ws, pl.splits,
+                       MN, a.N, a.scale, a.bias, a.add, a.relu, a.accumulate, a.C);
+    return hipGetLastError();
+}
+
+bool mfma_fwd_ok(const ConvGeom& g) { return g.Cin % 32 == 0 && g.rows_out() < (1ll << 31) / 8; }
+bool mfma_dgrad_ok(const ConvGeom& g) { return g.Cout % 32 == 0 && g.rows_in() < (1ll << 31) / 8; }
+
+size_t mfma_fwd_ws_bytes(const ConvGeom& g) {
+    const IgemmPlan pl = plan_igemm(g.rows_out(), g.Cout, g.K());
+    return pl.splits > 1 ? (size_t)pl.splits * g.rows_out() * g.Cout * sizeof(float) : 0;
+}
+size_t mfma_dgrad_ws_bytes(const ConvGeom& g) {
+    const IgemmPlan pl = plan_igemm(g.rows_in(), g.Cin, g.Kh * g.Kw * g.Cout);
+    return pl.splits > 1 ? (size_t)pl.splits * g.rows_in() * g.Cin * sizeof(float) : 0;
+}
+
+hipError_t mfma_conv_fwd(const ConvGeom& g, const void* x, const void* w, const float* scale, const float* bias,
+                         const void* add, int relu, void* y, void* ws, hipStream_t st) {
+    IgemmArgs a{};
+    a.A = (const uint16_t*)x; a.B = (const uint16_t*)w; a.C = (uint16_t*)y;
+    a.scale = scale; a.bias = bias; a.add = (const uint16_t*)add; a.relu = relu; a.accumulate = 0;
+    a.M = (int)g.rows_out(); a.N = g.Cout; a.Ktot = g.K();
+    a.Hi = g.H; a.Wi = g.W; a.Ci = g.Cin; a.Hr = g.Ho; a.Wr = g.Wo; a.Kw = g.Kw; a.stride = g.stride; a.pad = g.pad;
+    return run_igemm(MODE_FWD, a, ws, st);
+}
+
+// wt: weights laid out [Cin][Kh][Kw][Cout]
+hipError_t mfma_conv_dgrad(const ConvGeom& g, const void* dz, const void* wt, void* dx, int accumulate, void* ws,
+                           hipStream_t st) {
+    IgemmArgs a{};
+    a.A = (const uint16_t*)dz; a.B = (const uint16_t*)wt; a.C = (uint16_t*)dx;
+    a.accumulate = accumulate;
+    a.M = (int)g.rows_in(); a.N = g.Cin; a.Ktot = g.Kh * g.Kw * g.Cout;
+    a.Hi = g.Ho; a.Wi = g.Wo; a.Ci = g.Cout; a.Hr = g.H; a.Wr = g.W; a.Kw = g.Kw; a.stride = g.stride; a.pad = g.pad;
+    return run_igemm(MODE_DGRAD, a, ws, st);
+}
+
+// --------------------------------------------------------------------------------------------------
+// weight gradient
+struct WgradArgs {
+    const uint16_t* X;
+    const uint16_t* DZ;
+    float* out;            // dW, or the partials base when splits > 1
+    int Cout, Cin, KhKw, Kw;
+    int H, W, Ho, Wo, stride, pad;
+    int R;                 // reduction length m*Ho*Wo
+    int rt_total, rt_per_split, splits;
+    int accumulate;
+    int co_tiles, ci_tiles;
+};
+
+__device__ __forceinline__ void transpose4x8_store(const uint4 (&q)[4], uint16_t* dst /* row 0 of the 8 channels */) {
+    const uint32_t d[4][4] = {{q[0].x, q[0].y, q[0].z, q[0].w}, {q[1].x, q[1].y, q[1].z, q[1].w},
+                              {q[2].x, q[2].y, q[2].z, q[2].w}, {q[3].x, q[3].y, q[3].z, q[3].w}};
+#pragma unroll
+    for (int pr = 0; pr < 4; ++pr) {
+        // channel 2*pr: low halves; channel 2*pr+1: high halves; 4 pixels -> 8 bytes, K-contiguous
+        const uint32_t lo0 = __builtin_amdgcn_perm(d[1][pr], d[0][pr], 0x05040100u);
+        const uint32_t lo1 = __builtin_amdgcn_perm(d[3][pr], d[2][pr], 0x05040100u);
+        const uint32_t hi0 = __builtin_amdgcn_perm(d[1][pr], d[0][pr], 0x07060302u);
+        const uint32_t hi1 = __builtin_amdgcn_perm(d[3][pr], d[2][pr], 0x07060302u);
+        *reinterpret_cast<uint2*>(dst + (2 * pr) * LDK) = make_uint2(lo0, lo1);
+        *reinterpret_cast<uint2*>(dst + (2 * pr + 1) * LDK) = make_uint2(hi0, hi1);
+    }
+}
+
+template <int BM, int BN>
+__global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs p) {
+    typedef TileCfg<BM, BN, 2, 2> Cfg;
+    static_assert(BM + BN <= 256, "one loader item per thread");
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][BM * LDK];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN * LDK];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    int tile = xcd_remap(blockIdx.x, gridDim.x);
+    const int ci_t = tile % p.ci_tiles; tile /= p.ci_tiles;
+    const int tap = tile % p.KhKw;
+    const int co_t = tile / p.KhKw;
+    const int co0 = co_t * BM, ci0 = ci_t * BN;
+    const int kh = tap / p.Kw, kw = tap - kh * p.Kw;
+    const int rt0 = blockIdx.z * p.rt_per_split, rt1 = min(p.rt_total, rt0 + p.rt_per_split);
+
+    // loader role: threads [0,BM) feed dz, [BM,BM+BN) feed x; an item = 4 pixels x 8 channels
+    const bool isA = tid < BM, isB = !isA && tid < BM + BN;
+    const int item = isA ? tid : tid - BM;
+    const int nchunk = (isA ? BM : BN) / 8;
+    const int cc = item % nchunk, rg = item / nchunk;      // channel chunk, pixel group (0..7)
+    const int ch = (isA ? co0 : ci0) + cc * 8;
+    const bool ch_ok = (isA || isB) && ch < (isA ? p.Cout : p.Cin);
+    uint4 q[4];
+
+    auto load_tile = [&](int rt) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            q[j] = make_uint4(0, 0, 0, 0);
+            const int r = rt * BK + rg * 4 + j;
+            if (!ch_ok || r >= p.R) continue;
+            if (isA) {
+                q[j] = *reinterpret_cast<const uint4*>(p.DZ + (size_t)r * p.Cout + ch);
+            } else {
+                const int wo = r % p.Wo, t = r / p.Wo, ho = t % p.Ho, n = t / p.Ho;
+                const int h = ho * p.stride + kh - p.pad, w = wo * p.stride + kw - p.pad;
+                if ((unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W)
+                    q[j] = *reinterpret_cast<const uint4*>(p.X + ((size_t)(n * p.H + h) * p.W + w) * p.Cin + ch);
+            }
+        }
+    };
+    auto store_tile = [&](int buf) {
+        if (isA) transpose4x8_store(q, &As[buf][(cc * 8) * LDK + rg * 4]);
+        else if (isB) transpose4x8_store(q, &Bs[buf][(cc * 8) * LDK + rg * 4]);
+    };
+
+    f32x16 acc[Cfg::MI][Cfg::NI];
+#pragma unroll
+    for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < Cfg::NI; ++ni)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+
+    const int wm = wave >> 1, wn = wave & 1;
+    if (rt0 < rt1) {
+        load_tile(rt0);
+        store_tile(0);
+        __syncthreads();
+        for (int rt = rt0; rt < rt1; ++rt) {
+            const int buf = (rt - rt0) & 1;
+            if (rt + 1 < rt1) load_tile(rt + 1);
+            mma_tile<Cfg::MI, Cfg::NI>(As[buf], Bs[buf], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
+            if (rt + 1 < rt1) store_tile(buf ^ 1);
+            __syncthreads();
+        }
+    }
+
+    const size_t total = (size_t)p.Cout * p.KhKw * p.Cin;
+    float* out = p.out + (p.splits > 1 ? (size_t)blockIdx.z * total : 0);
+    const int col_l = lane & 31, rq = (lane >> 5) * 4;
+#pragma unroll
+    for (int ni = 0; ni < Cfg::NI; ++ni) {
+        const int ci = ci0 + wn * Cfg::WTN + ni * 32 + col_l;
+        if (ci >= p.Cin) continue;
+#pragma unroll
+        for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int co = co0 + wm * Cfg::WTM + mi * 32 + (i >> 2) * 8 + rq + (i & 3);
+                if (co >= p.Cout) continue;
+                const size_t o = ((size_t)co * p.KhKw + tap) * p.Cin + ci;
+                float v = acc[mi][ni][i];
+                if (p.splits == 1 && p.accumulate) v += out[o];
+                out[o] = v;
+            }
+    }
+}
+
+hipError_t reduce_partials_launch(const float* part, float* dst, int64_t n, int chunks, int accumulate, hipStream_t s);
+
+struct WgradPlan { int big; int splits; int rt_total; int rt_per; int co_tiles, ci_tiles; };
+
+static WgradPlan plan_wgrad(const ConvGeom& g) {
+    WgradPlan pl{};
+    const int64_t R = g.rows_out();
+    pl.rt_total = (int)((R + BK - 1) / BK);
+    pl.big = (g.Cout >= 128 && g.Cin >= 128);
+    const int t = pl.big ? 128 : 64;
+    pl.co_tiles = (g.Cout + t - 1) / t;
+    pl.ci_tiles = (g.Cin + t - 1) / t;
+    const int64_t tiles = (int64_t)pl.co_tiles * pl.ci_tiles * g.Kh * g.Kw;
+    int s = (int)((512 + tiles - 1) / tiles);
+    const int smax = pl.rt_total / 4;
+    if (s > smax) s = smax;
+    if (s > 64) s = 64;
+    // the partials must stay modest for very large weight tensors
+    const int64_t wbytes = (int64_t)g.Cout * g.K() * 4;
+    while (s > 1 && wbytes * s > (256ll << 20)) --s;
+    if (s < 1) s = 1;
+    pl.rt_per = (pl.rt_total + s - 1) / s;
+    pl.splits = (pl.rt_total + pl.rt_per - 1) / pl.rt_per;
+    return pl;
+}
+
+bool mfma_wgrad_ok(const ConvGeom& g) { return g.Cin % 8 == 0 && g.Cout % 8 == 0 && g.rows_out() < (1ll << 31) / 8; }
+
+size_t mfma_wgrad_ws_bytes(const ConvGeom& g) {
+    const WgradPlan pl = plan_wgrad(g);
+    return pl.splits > 1 ? (size_t)pl.splits * g.Cout * g.K() * sizeof(float) : 0;
+}
+
+hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, int accumulate, void* ws,
+                           hipStream_t st) {
+    const WgradPlan pl = plan_wgrad(g);
+    WgradArgs a{};
+    a.X = (const uint16_t*)x; a.DZ = (const uint16_t*)dz;
+    a.out = pl.splits > 1 ? (float*)ws : dw;
+    a.Cout = g.Cout; a.Cin = g.Cin; a.KhKw = g.Kh * g.Kw; a.Kw = g.Kw;
+    a.H = g.H; a.W = g.W; a.Ho = g.Ho; a.Wo = g.Wo; a.stride = g.stride; a.pad = g.pad;
+    a.R = (int)g.rows_out();
+    a.rt_total = pl.rt_total; a.rt_per_split = pl.rt_per; a.splits = pl.splits;
+    a.accumulate = accumulate;
+    a.co_tiles = pl.co_tiles; a.ci_tiles = pl.ci_tiles;
+    const dim3 grid((unsigned)(pl.co_tiles * pl.ci_tiles * a.KhKw), 1, pl.splits);
+    if (pl.big) hipLaunchKernelGGL((wgrad_kernel<128, 128>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((wgrad_kernel<64, 64>), grid, dim3(256), 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || pl.splits == 1) return e;
+    return reduce_partials_launch((const float*)ws, dw, (int64_t)g.Cout * g.K(), pl.splits, accumulate, st);
+}
+
+}  // namespace lpm

@@ -148,9 +148,11 @@ hipError_t reduce_partials_launch(const float* part, float* dst, int64_t n, int 
 
 static int wgrad_generic_chunks(const ConvGeom& g) {
     const int64_t total = (int64_t)g.Cout * g.K();
-    int64_t c = ((int64_t)1 << 21) / total;
     const int nho = g.m * g.Ho;
-    if (c > 32) c = 32;
+    int64_t c = ((int64_t)1 << 22) / total;     // keep the partials within a few MB
+    const int64_t want = (nho + 3) / 4;          // a thread walks at most 4 (n,ho) lines
+    if (c > want) c = want;
+    if (c > 256) c = 256;
     if (c > nho) c = nho;
     if (c < 1) c = 1;
     return (int)c;
@@ -207,13 +209,74 @@ __global__ void __launch_bounds__(256) epilogue_bwd_kernel(int64_t rows, int C, 
     if (ty == 0 && c < C) part[(int64_t)blockIdx.y * C + c] = (red[0][tx] + red[1][tx]) + (red[2][tx] + red[3][tx]);
 }
 
+// bf16, C % 8 == 0: a thread owns 8 channels (16-byte accesses); block = 8 channel chunks x 32 row lanes.
+__global__ void __launch_bounds__(256) epilogue_bwd_bf16x8(int64_t rows, int C, const uint4* __restrict__ dy,
+                                                           const uint4* __restrict__ y, const float* __restrict__ scale,
+                                                           uint4* __restrict__ dz, uint4* __restrict__ gadd, int gadd_acc,
+                                                           float* __restrict__ part) {
+    __shared__ float red[32][65];
+    const int cx = threadIdx.x & 7, ty = threadIdx.x >> 3;
+    const int c0 = blockIdx.x * 64 + cx * 8;
+    const int64_t r0 = (int64_t)blockIdx.y * EPI_ROWS;
+    const int64_t r1 = min(rows, r0 + EPI_ROWS);
+    const int C8 = C >> 3;
+    float sum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (c0 < C) {
+        float sc[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) sc[k] = scale ? scale[c0 + k] : 1.f;
+        for (int64_t r = r0 + ty; r < r1; r += 32) {
+            const int64_t i = r * C8 + (c0 >> 3);
+            const uint4 g4 = dy[i];
+            uint4 y4 = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
+            if (y) y4 = y[i];
+            uint4 a4 = make_uint4(0, 0, 0, 0);
+            if (gadd && gadd_acc) a4 = gadd[i];
+            const uint32_t gw[4] = {g4.x, g4.y, g4.z, g4.w}, yw[4] = {y4.x, y4.y, y4.z, y4.w}, aw[4] = {a4.x, a4.y, a4.z, a4.w};
+            uint32_t zo[4], go[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                float g0 = bf2f((uint16_t)(gw[k] & 0xffffu)), g1 = bf2f((uint16_t)(gw[k] >> 16));
+                if (!(bf2f((uint16_t)(yw[k] & 0xffffu)) > 0.f)) g0 = 0.f;
+                if (!(bf2f((uint16_t)(yw[k] >> 16)) > 0.f)) g1 = 0.f;
+                sum[2 * k] += g0; sum[2 * k + 1] += g1;
+                zo[k] = pack_bf16x2(g0 * sc[2 * k], g1 * sc[2 * k + 1]);
+                go[k] = pack_bf16x2(g0 + bf2f((uint16_t)(aw[k] & 0xffffu)), g1 + bf2f((uint16_t)(aw[k] >> 16)));
+            }
+            if (dz) dz[i] = make_uint4(zo[0], zo[1], zo[2], zo[3]);
+            if (gadd) gadd[i] = make_uint4(go[0], go[1], go[2], go[3]);
+        }
+    }
+    if (!part) return;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) red[ty][cx * 8 + k] = sum[k];
+    __syncthreads();
+    if (threadIdx.x < 64 && blockIdx.x * 64 + threadIdx.x < C) {
+        float acc = 0.f;
+#pragma unroll
+        for (int r = 0; r < 32; ++r) acc += red[r][threadIdx.x];
+        part[(int64_t)blockIdx.y * C + blockIdx.x * 64 + threadIdx.x] = acc;
+    }
+}
+
+// db[c] (+)= sum over the row blocks' partials, added in block order; 4 lanes per channel
 __global__ void __launch_bounds__(256) bias_reduce(const float* __restrict__ part, float* __restrict__ db, int C,
                                                    int nblocks, int accumulate) {
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= C) return;
+    __shared__ float red[4][64];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + tx;
     float acc = 0.f;
-    for (int b = 0; b < nblocks; ++b) acc += part[(int64_t)b * C + c];
-    db[c] = accumulate ? db[c] + acc : acc;
+    if (c < C) {
+        const int per = (nblocks + 3) / 4;
+        const int b1 = min(nblocks, (ty + 1) * per);
+        for (int b = ty * per; b < b1; ++b) acc += part[(int64_t)b * C + c];
+    }
+    red[ty][tx] = acc;
+    __syncthreads();
+    if (ty == 0 && c < C) {
+        const float v = (red[0][tx] + red[1][tx]) + (red[2][tx] + red[3][tx]);
+        db[c] = accumulate ? db[c] + v : v;
+    }
 }
 
 size_t epi_bwd_ws_bytes(int64_t rows, int32_t C) { return (size_t)nblk(rows, EPI_ROWS) * C * sizeof(float); }
@@ -222,11 +285,16 @@ hipError_t launch_epilogue_bwd(int dtype, int64_t rows, int32_t C, const void* d
                                void* dz, void* gadd, int gadd_acc, float* dbias, int db_acc, void* ws, hipStream_t s) {
     const unsigned rb = nblk(rows, EPI_ROWS);
     float* part = dbias ? (float*)ws : nullptr;
-    LPM_DISPATCH(dtype, hipLaunchKernelGGL(epilogue_bwd_kernel<T>, dim3(nblk(C, 64), rb), dim3(256), 0, s, rows, C,
-                                           (const T*)dy, (const T*)y, scale, (T*)dz, (T*)gadd, gadd_acc, part));
+    if (dtype == LPM_BF16 && (C & 7) == 0) {
+        hipLaunchKernelGGL(epilogue_bwd_bf16x8, dim3(nblk(C, 64), rb), dim3(256), 0, s, rows, C, (const uint4*)dy,
+                           (const uint4*)y, scale, (uint4*)dz, (uint4*)gadd, gadd_acc, part);
+    } else {
+        LPM_DISPATCH(dtype, hipLaunchKernelGGL(epilogue_bwd_kernel<T>, dim3(nblk(C, 64), rb), dim3(256), 0, s, rows, C,
+                                               (const T*)dy, (const T*)y, scale, (T*)dz, (T*)gadd, gadd_acc, part));
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || !dbias) return e;
-    hipLaunchKernelGGL(bias_reduce, dim3(nblk(C, 256)), dim3(256), 0, s, (const float*)part, dbias, C, (int)rb, db_acc);
+    hipLaunchKernelGGL(bias_reduce, dim3(nblk(C, 64)), dim3(256), 0, s, (const float*)part, dbias, C, (int)rb, db_acc);
     return hipGetLastError();
 }
 
