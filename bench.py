@@ -156,7 +156,7 @@ def main():
                 wt = ww.clone()
                 dw = torch.zeros(g["cout"] * K, device="cuda")
                 wsb = lpm.lpm_conv_ws_bytes(g, dtype)
-                ws = torch.empty(max(max(wsb), 256), dtype=torch.uint8, device="cuda")
+                ws = torch.zeros(max(max(wsb), 256), dtype=torch.uint8, device="cuda")
                 if op == "fwd":
                     fn = lambda: lpm.lpm_conv_forward(g, dtype, xx, ww, None, None, None, True, yy, ws, cur)
                 elif op == "dgrad":

@@ -1,10 +1,10 @@
 // bf16 MFMA implicit-GEMM contractions for gfx950: convolution forward (eq. 1), data gradient (eq. 9)
-// and weight gradient (eq. 8), fp32 accumulation, LDS-staged 32-deep K tiles, 4 wavefronts per block.
+// and weight gradient (eq. 8), fp32 accumulation, LDS-staged K tiles of 32..128, 4 wavefronts per block.
 //
 // Forward / data gradient:  C[M][N] = A[M][K] * B[N][K]^T
 //   forward  rows = output pixels, A gathered from x [m][H][W][Cin],  B = w  [Cout][Kh][Kw][Cin]
 //   dgrad    rows = input pixels,  A gathered from dz [m][Ho][Wo][Cout], B = wt [Cin][Kh][Kw][Cout]
-//   K runs over (kh, kw, channel); a 32-wide K tile lies inside one filter tap (channels % 32 == 0).
+//   K runs over (kh, kw, channel); a K tile lies inside one filter tap (channels % tile depth == 0).
 // Weight gradient:  dW[co][tap][ci] = sum_rows dz[row][co] * x[pixel(row,tap)][ci]
 //   both operands are stored with the reduction index (the pixel) outermost, so the loader transposes
 //   4 pixels x 8 channels in registers before writing K-contiguous rows to LDS.
@@ -18,8 +18,8 @@ namespace lpm {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-constexpr int BK = 32;    // K tile
-constexpr int LDK = 40;   // LDS row stride in elements (80 bytes: 16-byte aligned, staggers banks)
+// A K tile of depth BK is stored in LDS as rows of BK + 8 elements (16-byte aligned, staggers banks).
+// Small-M shapes are bound by the latency of one global load per K tile, so they take deep tiles.
 
 enum { MODE_FWD = 0, MODE_DGRAD = 1 };
 
@@ -53,13 +53,14 @@ struct TileCfg {
     static_assert(WGM * WGN == 4 && WTM % 32 == 0 && WTN % 32 == 0, "4 wavefronts, 32x32 MFMA tiles");
 };
 
-// acc[mi][ni] += A-tile(wave rows) * B-tile(wave cols) over one 32-deep K tile held in LDS
-template <int MI, int NI>
+// acc[mi][ni] += A-tile(wave rows) * B-tile(wave cols) over one BK-deep K tile held in LDS
+template <int MI, int NI, int BK>
 __device__ __forceinline__ void mma_tile(const uint16_t* As, const uint16_t* Bs, int arow0, int brow0, int lane,
                                          f32x16 (&acc)[MI][NI]) {
+    constexpr int LDK = BK + 8;
     const int r = lane & 31, kq = (lane >> 5) * 8;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
+    for (int ks = 0; ks < BK / 16; ++ks) {
         bf16x8 a[MI], b[NI];
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
@@ -75,10 +76,11 @@ __device__ __forceinline__ void mma_tile(const uint16_t* As, const uint16_t* Bs,
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int MODE>
+template <int BM, int BN, int BK, int WGM, int WGN, int MODE>
 __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs p) {
     typedef TileCfg<BM, BN, WGM, WGN> Cfg;
-    constexpr int A_CH = (BM * 4 + 255) / 256, B_CH = (BN * 4 + 255) / 256;
+    constexpr int LDK = BK + 8, CPR = BK / 8;                 // chunks (16 bytes) per row
+    constexpr int A_CH = (BM * CPR + 255) / 256, B_CH = (BN * CPR + 255) / 256;
     __shared__ __attribute__((aligned(16))) uint16_t As[2][BM * LDK];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN * LDK];
 
@@ -94,8 +96,8 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs p) {
     bool a_ok[A_CH];
 #pragma unroll
     for (int c = 0; c < A_CH; ++c) {
-        const int id = tid + c * 256, row = m0 + (id >> 2);
-        a_ok[c] = (id < BM * 4) && row < p.M;
+        const int id = tid + c * 256, row = m0 + id / CPR;
+        a_ok[c] = (id < BM * CPR) && row < p.M;
         const int rr = a_ok[c] ? row : 0;
         const int wq = rr % p.Wr, t = rr / p.Wr, hq = t % p.Hr, n = t / p.Hr;
         a_nb[c] = n * p.Hi * p.Wi;
@@ -110,7 +112,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs p) {
         const int kh = tap / p.Kw, kw = tap - kh * p.Kw;
 #pragma unroll
         for (int c = 0; c < A_CH; ++c) {
-            const int id = tid + c * 256, kc = id & 3;
+            const int id = tid + c * 256, kc = id % CPR;
             int h, w;
             bool ok = a_ok[c];
             if (MODE == MODE_FWD) { h = a_h0[c] + kh; w = a_w0[c] + kw; }
@@ -127,21 +129,21 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs p) {
         }
 #pragma unroll
         for (int c = 0; c < B_CH; ++c) {
-            const int id = tid + c * 256, n = n0 + (id >> 2), kc = id & 3;
+            const int id = tid + c * 256, n = n0 + id / CPR, kc = id % CPR;
             rb[c] = make_uint4(0, 0, 0, 0);
-            if (id < BN * 4 && n < p.N) rb[c] = *reinterpret_cast<const uint4*>(p.B + ((size_t)n * p.Ktot + k0 + kc * 8));
+            if (id < BN * CPR && n < p.N) rb[c] = *reinterpret_cast<const uint4*>(p.B + ((size_t)n * p.Ktot + k0 + kc * 8));
         }
     };
     auto store_tile = [&](int buf) {
 #pragma unroll
         for (int c = 0; c < A_CH; ++c) {
             const int id = tid + c * 256;
-            if (id < BM * 4) *reinterpret_cast<uint4*>(&As[buf][(id >> 2) * LDK + (id & 3) * 8]) = ra[c];
+            if (id < BM * CPR) *reinterpret_cast<uint4*>(&As[buf][(id / CPR) * LDK + (id % CPR) * 8]) = ra[c];
         }
 #pragma unroll
         for (int c = 0; c < B_CH; ++c) {
             const int id = tid + c * 256;
-            if (id < BN * 4) *reinterpret_cast<uint4*>(&Bs[buf][(id >> 2) * LDK + (id & 3) * 8]) = rb[c];
+            if (id < BN * CPR) *reinterpret_cast<uint4*>(&Bs[buf][(id / CPR) * LDK + (id % CPR) * 8]) = rb[c];
         }
     };
 
@@ -161,7 +163,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs p) {
         for (int kt = kt0; kt < kt1; ++kt) {
             const int buf = (kt - kt0) & 1;
             if (kt + 1 < kt1) load_tile(kt + 1);
-            mma_tile<Cfg::MI, Cfg::NI>(As[buf], Bs[buf], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
+            mma_tile<Cfg::MI, Cfg::NI, BK>(As[buf], Bs[buf], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
             if (kt + 1 < kt1) store_tile(buf ^ 1);
             __syncthreads();
         }
@@ -212,19 +214,23 @@ __global__ void __launch_bounds__(256) splitk_epilogue(const float* __restrict__
 }
 
 // --------------------------------------------------------------------------------------------------
-struct IgemmPlan { int big; int splits; int kt_total; int kt_per; };
+struct IgemmPlan { int big; int bk; int splits; int kt_total; int kt_per; };
 
-static IgemmPlan plan_igemm(int64_t M, int N, int Ktot) {
+// ci: channel count of the gathered tensor (a K tile must not straddle a filter tap)
+static IgemmPlan plan_igemm(int64_t M, int N, int Ktot, int ci) {
     IgemmPlan pl{};
-    pl.kt_total = Ktot / BK;
     const int64_t b128 = ((M + 127) / 128) * ((N + 127) / 128);
     pl.big = b128 >= 160;
+    if (pl.big) pl.bk = (ci % 64 == 0) ? 64 : 32;
+    else pl.bk = (ci % 128 == 0) ? 128 : (ci % 64 == 0) ? 64 : 32;
+    pl.kt_total = Ktot / pl.bk;
     pl.splits = 1;
     if (!pl.big) {
         const int64_t b64 = ((M + 63) / 64) * ((N + 63) / 64);
         int s = (int)((384 + b64 - 1) / b64);
-        const int smax = pl.kt_total / 4;
+        const int smax = (Ktot / 32) / 8;          // at least 256 of K per split
         if (s > smax) s = smax;
+        if (s > pl.kt_total) s = pl.kt_total;
         if (s > 32) s = 32;
         if (s < 1) s = 1;
         pl.splits = s;
@@ -234,20 +240,27 @@ static IgemmPlan plan_igemm(int64_t M, int N, int Ktot) {
     return pl;
 }
 
+template <int MODE>
+static void launch_igemm_cfg(const IgemmPlan& pl, const IgemmArgs& a, hipStream_t st) {
+    if (pl.big) {
+        const dim3 grid((unsigned)(((a.M + 127) / 128) * ((a.N + 127) / 128)), 1, pl.splits);
+        if (pl.bk == 64) hipLaunchKernelGGL((igemm_kernel<128, 128, 64, 2, 2, MODE>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((igemm_kernel<128, 128, 32, 2, 2, MODE>), grid, dim3(256), 0, st, a);
+    } else {
+        const dim3 grid((unsigned)(((a.M + 63) / 64) * ((a.N + 63) / 64)), 1, pl.splits);
+        if (pl.bk == 128) hipLaunchKernelGGL((igemm_kernel<64, 64, 128, 2, 2, MODE>), grid, dim3(256), 0, st, a);
+        else if (pl.bk == 64) hipLaunchKernelGGL((igemm_kernel<64, 64, 64, 2, 2, MODE>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((igemm_kernel<64, 64, 32, 2, 2, MODE>), grid, dim3(256), 0, st, a);
+    }
+}
+
 static hipError_t run_igemm(int mode, IgemmArgs a, void* ws, hipStream_t st) {
-    const IgemmPlan pl = plan_igemm(a.M, a.N, a.Ktot);
+    const IgemmPlan pl = plan_igemm(a.M, a.N, a.Ktot, a.Ci);
     a.kt_total = pl.kt_total;
     a.kt_per_split = pl.kt_per;
     a.part = pl.splits > 1 ? (float*)ws : nullptr;
-    if (pl.big) {
-        const dim3 grid((unsigned)(((a.M + 127) / 128) * ((a.N + 127) / 128)), 1, pl.splits);
-        if (mode == MODE_FWD) hipLaunchKernelGGL((igemm_kernel<128, 128, 2, 2, MODE_FWD>), grid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((igemm_kernel<128, 128, 2, 2, MODE_DGRAD>), grid, dim3(256), 0, st, a);
-    } else {
-        const dim3 grid((unsigned)(((a.M + 63) / 64) * ((a.N + 63) / 64)), 1, pl.splits);
-        if (mode == MODE_FWD) hipLaunchKernelGGL((igemm_kernel<64, 64, 2, 2, MODE_FWD>), grid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((igemm_kernel<64, 64, 2, 2, MODE_DGRAD>), grid, dim3(256), 0, st, a);
-    }
+    if (mode == MODE_FWD) launch_igemm_cfg<MODE_FWD>(pl, a, st);
+    else launch_igemm_cfg<MODE_DGRAD>(pl, a, st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.splits == 1) return e;
     const int64_t MN = (int64_t)a.M * a.N;
@@ -260,11 +273,11 @@ bool mfma_fwd_ok(const ConvGeom& g) { return g.Cin % 32 == 0 && g.rows_out() < (
 bool mfma_dgrad_ok(const ConvGeom& g) { return g.Cout % 32 == 0 && g.rows_in() < (1ll << 31) / 8; }
 
 size_t mfma_fwd_ws_bytes(const ConvGeom& g) {
-    const IgemmPlan pl = plan_igemm(g.rows_out(), g.Cout, g.K());
+    const IgemmPlan pl = plan_igemm(g.rows_out(), g.Cout, g.K(), g.Cin);
     return pl.splits > 1 ? (size_t)pl.splits * g.rows_out() * g.Cout * sizeof(float) : 0;
 }
 size_t mfma_dgrad_ws_bytes(const ConvGeom& g) {
-    const IgemmPlan pl = plan_igemm(g.rows_in(), g.Cin, g.Kh * g.Kw * g.Cout);
+    const IgemmPlan pl = plan_igemm(g.rows_in(), g.Cin, g.Kh * g.Kw * g.Cout, g.Cout);
     return pl.splits > 1 ? (size_t)pl.splits * g.rows_in() * g.Cin * sizeof(float) : 0;
 }
 
@@ -303,6 +316,7 @@ struct WgradArgs {
     int co_tiles, ci_tiles;
 };
 
+template <int LDK>
 __device__ __forceinline__ void transpose4x8_store(const uint4 (&q)[4], uint16_t* dst /* row 0 of the 8 channels */) {
     const uint32_t d[4][4] = {{q[0].x, q[0].y, q[0].z, q[0].w}, {q[1].x, q[1].y, q[1].z, q[1].w},
                               {q[2].x, q[2].y, q[2].z, q[2].w}, {q[3].x, q[3].y, q[3].z, q[3].w}};
@@ -318,10 +332,12 @@ __device__ __forceinline__ void transpose4x8_store(const uint4 (&q)[4], uint16_t
     }
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int BK>
 __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs p) {
     typedef TileCfg<BM, BN, 2, 2> Cfg;
-    static_assert(BM + BN <= 256, "one loader item per thread");
+    constexpr int LDK = BK + 8;
+    constexpr int A_ITEMS = (BM / 8) * (BK / 4), B_ITEMS = (BN / 8) * (BK / 4);   // item = 4 pixels x 8 channels
+    constexpr int A_PT = (A_ITEMS + 255) / 256, B_PT = (B_ITEMS + 255) / 256;
     __shared__ __attribute__((aligned(16))) uint16_t As[2][BM * LDK];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN * LDK];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -334,34 +350,49 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs p) {
     const int kh = tap / p.Kw, kw = tap - kh * p.Kw;
     const int rt0 = blockIdx.z * p.rt_per_split, rt1 = min(p.rt_total, rt0 + p.rt_per_split);
 
-    // loader role: threads [0,BM) feed dz, [BM,BM+BN) feed x; an item = 4 pixels x 8 channels
-    const bool isA = tid < BM, isB = !isA && tid < BM + BN;
-    const int item = isA ? tid : tid - BM;
-    const int nchunk = (isA ? BM : BN) / 8;
-    const int cc = item % nchunk, rg = item / nchunk;      // channel chunk, pixel group (0..7)
-    const int ch = (isA ? co0 : ci0) + cc * 8;
-    const bool ch_ok = (isA || isB) && ch < (isA ? p.Cout : p.Cin);
-    uint4 q[4];
+    uint4 qa[A_PT][4], qb[B_PT][4];
 
     auto load_tile = [&](int rt) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            q[j] = make_uint4(0, 0, 0, 0);
-            const int r = rt * BK + rg * 4 + j;
-            if (!ch_ok || r >= p.R) continue;
-            if (isA) {
-                q[j] = *reinterpret_cast<const uint4*>(p.DZ + (size_t)r * p.Cout + ch);
-            } else {
-                const int wo = r % p.Wo, t = r / p.Wo, ho = t % p.Ho, n = t / p.Ho;
-                const int h = ho * p.stride + kh - p.pad, w = wo * p.stride + kw - p.pad;
-                if ((unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W)
-                    q[j] = *reinterpret_cast<const uint4*>(p.X + ((size_t)(n * p.H + h) * p.W + w) * p.Cin + ch);
+        for (int t = 0; t < A_PT; ++t) {
+            const int item = tid + t * 256, cc = item % (BM / 8), rg = item / (BM / 8);
+            const int ch = co0 + cc * 8;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                qa[t][j] = make_uint4(0, 0, 0, 0);
+                const int r = rt * BK + rg * 4 + j;
+                if (item < A_ITEMS && ch < p.Cout && r < p.R)
+                    qa[t][j] = *reinterpret_cast<const uint4*>(p.DZ + (size_t)r * p.Cout + ch);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < B_PT; ++t) {
+            const int item = tid + t * 256, cc = item % (BN / 8), rg = item / (BN / 8);
+            const int ch = ci0 + cc * 8;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                qb[t][j] = make_uint4(0, 0, 0, 0);
+                const int r = rt * BK + rg * 4 + j;
+                if (item < B_ITEMS && ch < p.Cin && r < p.R) {
+                    const int wo = r % p.Wo, q = r / p.Wo, ho = q % p.Ho, n = q / p.Ho;
+                    const int h = ho * p.stride + kh - p.pad, w = wo * p.stride + kw - p.pad;
+                    if ((unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W)
+                        qb[t][j] = *reinterpret_cast<const uint4*>(p.X + ((size_t)(n * p.H + h) * p.W + w) * p.Cin + ch);
+                }
             }
         }
     };
     auto store_tile = [&](int buf) {
-        if (isA) transpose4x8_store(q, &As[buf][(cc * 8) * LDK + rg * 4]);
-        else if (isB) transpose4x8_store(q, &Bs[buf][(cc * 8) * LDK + rg * 4]);
+#pragma unroll
+        for (int t = 0; t < A_PT; ++t) {
+            const int item = tid + t * 256, cc = item % (BM / 8), rg = item / (BM / 8);
+            if (item < A_ITEMS) transpose4x8_store<LDK>(qa[t], &As[buf][(cc * 8) * LDK + rg * 4]);
+        }
+#pragma unroll
+        for (int t = 0; t < B_PT; ++t) {
+            const int item = tid + t * 256, cc = item % (BN / 8), rg = item / (BN / 8);
+            if (item < B_ITEMS) transpose4x8_store<LDK>(qb[t], &Bs[buf][(cc * 8) * LDK + rg * 4]);
+        }
     };
 
     f32x16 acc[Cfg::MI][Cfg::NI];
@@ -380,7 +411,7 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs p) {
         for (int rt = rt0; rt < rt1; ++rt) {
             const int buf = (rt - rt0) & 1;
             if (rt + 1 < rt1) load_tile(rt + 1);
-            mma_tile<Cfg::MI, Cfg::NI>(As[buf], Bs[buf], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
+            mma_tile<Cfg::MI, Cfg::NI, BK>(As[buf], Bs[buf], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
             if (rt + 1 < rt1) store_tile(buf ^ 1);
             __syncthreads();
         }
@@ -409,19 +440,20 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs p) {
 
 hipError_t reduce_partials_launch(const float* part, float* dst, int64_t n, int chunks, int accumulate, hipStream_t s);
 
-struct WgradPlan { int big; int splits; int rt_total; int rt_per; int co_tiles, ci_tiles; };
+struct WgradPlan { int big; int bk; int splits; int rt_total; int rt_per; int co_tiles, ci_tiles; };
 
 static WgradPlan plan_wgrad(const ConvGeom& g) {
     WgradPlan pl{};
     const int64_t R = g.rows_out();
-    pl.rt_total = (int)((R + BK - 1) / BK);
-    pl.big = (g.Cout >= 128 && g.Cin >= 128);
+    pl.big = (g.Cout >= 128 && g.Cin >= 128 && R >= 512);
+    pl.bk = pl.big ? 64 : (R > 64 ? 128 : 64);
+    pl.rt_total = (int)((R + pl.bk - 1) / pl.bk);
     const int t = pl.big ? 128 : 64;
     pl.co_tiles = (g.Cout + t - 1) / t;
     pl.ci_tiles = (g.Cin + t - 1) / t;
     const int64_t tiles = (int64_t)pl.co_tiles * pl.ci_tiles * g.Kh * g.Kw;
     int s = (int)((512 + tiles - 1) / tiles);
-    const int smax = pl.rt_total / 4;
+    const int smax = (int)(R / 256);               // at least 256 pixels per split
     if (s > smax) s = smax;
     if (s > 64) s = 64;
     // the partials must stay modest for very large weight tensors
@@ -453,8 +485,9 @@ hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, flo
     a.accumulate = accumulate;
     a.co_tiles = pl.co_tiles; a.ci_tiles = pl.ci_tiles;
     const dim3 grid((unsigned)(pl.co_tiles * pl.ci_tiles * a.KhKw), 1, pl.splits);
-    if (pl.big) hipLaunchKernelGGL((wgrad_kernel<128, 128>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((wgrad_kernel<64, 64>), grid, dim3(256), 0, st, a);
+    if (pl.big) hipLaunchKernelGGL((wgrad_kernel<128, 128, 64>), grid, dim3(256), 0, st, a);
+    else if (pl.bk == 128) hipLaunchKernelGGL((wgrad_kernel<64, 64, 128>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((wgrad_kernel<64, 64, 64>), grid, dim3(256), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.splits == 1) return e;
     return reduce_partials_launch((const float*)ws, dw, (int64_t)g.Cout * g.K(), pl.splits, accumulate, st);
