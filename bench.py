@@ -97,11 +97,9 @@ def main():
     ld = torch.from_numpy(labels).cuda() if labels is not None else None
     gd = lpm.pack_act(g_up, dtype) if g_up is not None else None
     lr, mu = 0.01, 0.9
-    gflag = 0 if args.eager else lpm.GRAPH
-
     def run(mode, steps):
         for _ in range(steps):
-            net.step(xd, ld, gd, lr, mu, mode | gflag)
+            net.step(xd, ld, gd, lr, mu, mode)
 
     def timed(mode, steps):
         run(mode, args.warmup)
@@ -111,8 +109,14 @@ def main():
         torch.cuda.synchronize()
         return time.perf_counter() - t0
 
-    t_locked = timed(lpm.LOCKED, args.steps)
-    t_over = timed(lpm.OVERLAPPED, args.steps)
+    # the step is timed both enqueued kernel by kernel and replayed as a captured graph; the faster one is reported
+    res = {}
+    for name, gflag in (("eager", 0), ("graph", lpm.GRAPH)):
+        if args.eager and name == "graph":
+            continue
+        res[name] = (timed(lpm.LOCKED | gflag, args.steps), timed(lpm.OVERLAPPED | gflag, args.steps))
+    best = min(res, key=lambda k: res[k][1])
+    t_locked, t_over = res[best]
     ms_step = t_over / args.steps * 1e3
     value = batch * args.steps / t_over
 
@@ -157,13 +161,9 @@ def main():
                 dw = torch.zeros(g["cout"] * K, device="cuda")
                 wsb = lpm.lpm_conv_ws_bytes(g, dtype)
                 ws = torch.zeros(max(max(wsb), 256), dtype=torch.uint8, device="cuda")
-                if op == "fwd":
-                    fn = lambda: lpm.lpm_conv_forward(g, dtype, xx, ww, None, None, None, True, yy, ws, cur)
-                elif op == "dgrad":
-                    fn = lambda: lpm.lpm_conv_dgrad(g, dtype, yy, ww, wt if dtype == lpm.BF16 else None, xx, False, ws, cur)
-                else:
-                    fn = lambda: lpm.lpm_conv_wgrad(g, dtype, xx, yy, dw, True, ws, cur)
-                cache[key] = time_stream(torch, fn, 20)
+                opi = {"fwd": 0, "dgrad": 1, "wgrad": 2}[op]
+                us = lpm.lpm_conv_time(opi, g, dtype, xx, ww, wt if dtype == lpm.BF16 else None, yy, dw, ws, 3, 30, cur)
+                cache[key] = us * 1e-6
             t = cache[key]
             ai = flops / byts
             peak_f = PEAK["mfma_bf16"] if dtype == lpm.BF16 else PEAK["fp32"]
@@ -214,9 +214,11 @@ def main():
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dt, "data": "synthetic",
         "config": {"workload": args.workload, "global_batch": batch, "n_microbatch": M, "microbatch": m, "partitions": Z,
-                   "plan": starts, "schedule": "overlapped, 2 HIP streams, window 2" + ("" if args.eager else ", graph replay"),
+                   "plan": starts, "schedule": "overlapped, 2 HIP streams, window 2, " + ("graph replay" if best == "graph" else "eager enqueue"),
                    "lr": lr, "momentum": mu},
         "locked_ms_per_step": round(t_locked / args.steps * 1e3, 4),
+        "ms_per_step_by_launch_mode": {k: {"locked": round(v[0] / args.steps * 1e3, 4), "overlapped": round(v[1] / args.steps * 1e3, 4)}
+                                       for k, v in res.items()},
         "overlap_speedup": round(t_locked / t_over, 4),
         "partitions": part,
         "roofline": roof,

@@ -262,6 +262,14 @@ int32_t lpm_conv_dgrad(const lpm_conv_geom* g, int32_t dtype, const void* dz, co
 int32_t lpm_conv_wgrad(const lpm_conv_geom* g, int32_t dtype, const void* x, const void* dz, float* dw,
                        int32_t accumulate, void* ws, void* stream);
 
+/* Measurement helper: enqueues one of the three contractions `iters` times back to back on `stream`
+ * between two HIP events (after `warmup` untimed launches), waits for them, and returns the average
+ * duration of one launch in microseconds.  op: 0 = forward (x, w -> y, ReLU epilogue), 1 = data gradient
+ * (y as dz, w, wt -> x as dx), 2 = weight gradient (x, y as dz -> dw, accumulating).  Buffers as in the
+ * calls above; synchronises the stream.  Errors: as the calls above, LPM_EHIP. */
+int32_t lpm_conv_time(int32_t op, const lpm_conv_geom* g, int32_t dtype, void* x, const void* w, const void* wt,
+                      void* y, float* dw, void* ws, int32_t warmup, int32_t iters, void* stream, float* avg_us);
+
 #ifdef __cplusplus
 }
 #endif

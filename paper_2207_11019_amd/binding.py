@@ -9,7 +9,7 @@ import os
 
 import numpy as np
 
-__all__ = ["LpmError", "lib", "lpm_conv_geom", "lpm_conv_ws_bytes", "lpm_conv_forward", "lpm_conv_dgrad", "lpm_conv_wgrad", "lpm_layer", "lpm_cost_params", "lpm_stage_buffers", "layers_from_dicts",
+__all__ = ["LpmError", "lib", "lpm_conv_geom", "lpm_conv_ws_bytes", "lpm_conv_forward", "lpm_conv_dgrad", "lpm_conv_wgrad", "lpm_conv_time", "lpm_layer", "lpm_cost_params", "lpm_stage_buffers", "layers_from_dicts",
            "lpm_layer_cost", "lpm_partition", "Stage", "Schedule", "Net", "F32", "BF16", "LOCKED", "OVERLAPPED",
            "GRAPH", "pack_act", "unpack_act", "pack_weight", "unpack_weight", "MI355X_COST"]
 
@@ -77,7 +77,9 @@ lib.lpm_conv_ws_bytes.argtypes = [C.POINTER(lpm_conv_geom), _i32, _psz, _psz, _p
 lib.lpm_conv_forward.argtypes = [C.POINTER(lpm_conv_geom), _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]
 lib.lpm_conv_dgrad.argtypes = [C.POINTER(lpm_conv_geom), _i32, _vp, _vp, _vp, _vp, _i32, _vp, _vp]
 lib.lpm_conv_wgrad.argtypes = [C.POINTER(lpm_conv_geom), _i32, _vp, _vp, _vp, _i32, _vp, _vp]
-for _f in ("lpm_conv_ws_bytes", "lpm_conv_forward", "lpm_conv_dgrad", "lpm_conv_wgrad", "lpm_layer_cost", "lpm_partition", "lpm_stage_create", "lpm_stage_destroy", "lpm_stage_sizes",
+lib.lpm_conv_time.argtypes = [_i32, C.POINTER(lpm_conv_geom), _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp,
+                              C.POINTER(C.c_float)]
+for _f in ("lpm_conv_time", "lpm_conv_ws_bytes", "lpm_conv_forward", "lpm_conv_dgrad", "lpm_conv_wgrad", "lpm_layer_cost", "lpm_partition", "lpm_stage_create", "lpm_stage_destroy", "lpm_stage_sizes",
            "lpm_stage_param_offset", "lpm_stage_stash_offset", "lpm_stage_grad_offset", "lpm_stage_sync_lowp",
            "lpm_stage_forward", "lpm_stage_backward", "lpm_stage_update", "lpm_schedule_create",
            "lpm_schedule_destroy", "lpm_schedule_run"):
@@ -163,6 +165,15 @@ def lpm_conv_dgrad(g, dtype, dz, w, wt, dx, accumulate=False, ws=None, stream=No
 def lpm_conv_wgrad(g, dtype, x, dz, dw, accumulate=False, ws=None, stream=None):
     gg = _geom(g)
     _check(lib.lpm_conv_wgrad(C.byref(gg), dtype, _ptr(x), _ptr(dz), _ptr(dw), int(accumulate), _ptr(ws), _stream(stream)))
+
+
+def lpm_conv_time(op, g, dtype, x, w, wt, y, dw, ws, warmup=3, iters=20, stream=None):
+    """Average microseconds of one launch of contraction op (0 forward, 1 data gradient, 2 weight gradient)."""
+    gg = _geom(g)
+    out = C.c_float()
+    _check(lib.lpm_conv_time(op, C.byref(gg), dtype, _ptr(x), _ptr(w), _ptr(wt), _ptr(y), _ptr(dw), _ptr(ws), warmup, iters,
+                             _stream(stream), C.byref(out)))
+    return out.value
 
 
 def _ptr(t):

@@ -66,3 +66,29 @@ extern "C" int32_t lpm_conv_wgrad(const lpm_conv_geom* g, int32_t dtype, const v
     LPM_HIP(launch_conv_wgrad(dtype, cg, x, dz, dw, accumulate != 0, ws, (hipStream_t)stream));
     return LPM_OK;
 }
+
+extern "C" int32_t lpm_conv_time(int32_t op, const lpm_conv_geom* g, int32_t dtype, void* x, const void* w, const void* wt,
+                                 void* y, float* dw, void* ws, int32_t warmup, int32_t iters, void* stream, float* avg_us) {
+    if (op < 0 || op > 2 || iters <= 0 || warmup < 0 || !avg_us) return fail(LPM_EINVAL, "bad op / iteration count");
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    LPM_HIP(hipEventCreate(&e0));
+    hipError_t he = hipEventCreate(&e1);
+    if (he != hipSuccess) { (void)hipEventDestroy(e0); return hip_fail(he, "hipEventCreate"); }
+    int32_t rc = LPM_OK;
+    for (int32_t i = 0; i < warmup + iters && rc == LPM_OK; ++i) {
+        if (i == warmup) he = hipEventRecord(e0, (hipStream_t)stream);
+        if (op == 0) rc = lpm_conv_forward(g, dtype, x, w, nullptr, nullptr, nullptr, 1, y, ws, stream);
+        else if (op == 1) rc = lpm_conv_dgrad(g, dtype, y, w, wt, x, 0, ws, stream);
+        else rc = lpm_conv_wgrad(g, dtype, x, y, dw, 1, ws, stream);
+    }
+    if (rc == LPM_OK && he == hipSuccess) he = hipEventRecord(e1, (hipStream_t)stream);
+    if (rc == LPM_OK && he == hipSuccess) he = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (rc == LPM_OK && he == hipSuccess) he = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != LPM_OK) return rc;
+    if (he != hipSuccess) return hip_fail(he, "event timing");
+    *avg_us = ms * 1000.f / (float)iters;
+    return LPM_OK;
+}

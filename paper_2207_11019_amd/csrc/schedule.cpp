@@ -15,6 +15,8 @@
 
 using namespace lpm;
 
+int32_t lpm_stage_prepare(lpm_stage* s);
+
 namespace {
 struct GraphEntry {
     std::vector<unsigned char> key;
@@ -59,6 +61,10 @@ extern "C" int32_t lpm_schedule_create(lpm_stage* const* stages, int32_t Z, int3
         if (stages[z]->loss && z != Z - 1) return fail(LPM_ESHAPE, "only the last stage may hold the loss");
     }
     if (stages[Z - 1]->last != stages[0]->L) return fail(LPM_ESHAPE, "the stages do not cover the whole network");
+    for (int32_t z = 0; z < Z; ++z) {      // side streams and events exist before any capture starts
+        const int32_t rc = lpm_stage_prepare(stages[z]);
+        if (rc) return rc;
+    }
     lpm_schedule* s = new (std::nothrow) lpm_schedule();
     if (!s) return fail(LPM_ENOMEM, "out of host memory");
     s->st.assign(stages, stages + Z);

@@ -75,7 +75,7 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
 
     // parameters: trainable (W, bias per layer) first, frozen scales after
     s->lay.resize((size_t)(last - first));
-    size_t off = 0, lowp = 0, dz_max = 0, kws = 0, fws = 0;
+    size_t off = 0, lowp = 0, kws = 0, wws = 0, fws = 0;
     for (int32_t i = first; i < last; ++i) {
         LayerRt& lr = s->Ly(i);
         lr.d = s->net[i];
@@ -92,8 +92,11 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
             const bool single_pixel = (o.h == 1 && o.w == 1 && l.kh == l.h_in && l.kw == l.w_in && l.pad == 0);
             if (!single_pixel || lr.w_count <= ((size_t)4 << 20)) { lr.lowp_wt_off = lowp; lowp += align_up(lr.w_count * 2, 256); }   // rebased below
         }
-        dz_max = std::max(dz_max, align_up(o.elems() * (size_t)microbatch * s->esz, 256));
-        kws = std::max(kws, align_up(wgrad_ws_bytes(dtype, lr.g), 256));
+        if (l.flags & (LPM_RELU | LPM_SCALE)) {          // needs its own dz buffer (it outlives the layer's turn)
+            lr.dz_off = gws;
+            gws += align_up(o.elems() * (size_t)microbatch * s->esz, 256);
+        }
+        wws = std::max(wws, align_up(wgrad_ws_bytes(dtype, lr.g), 256));
         kws = std::max(kws, align_up(dgrad_ws_bytes(dtype, lr.g), 256));
         kws = std::max(kws, align_up(epi_bwd_ws_bytes(lr.g.rows_out(), l.cout), 256));
         fws = std::max(fws, align_up(fwd_ws_bytes(dtype, lr.g), 256));
@@ -111,12 +114,37 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
     }
     s->n_params = off;
     s->lowp_bytes = lowp;
-    s->dz_off = gws;
-    s->kws_off = gws + dz_max;
-    s->kws_bytes = kws;
-    s->bwd_ws = std::max<size_t>(gws + dz_max + kws, 256);
+    s->kws_off = gws;
+    s->wws_off = gws + kws;
+    s->bwd_ws = std::max<size_t>(gws + kws + wws, 256);
     s->fwd_ws = std::max<size_t>(fws, 256);
     *out = s;
+    return LPM_OK;
+}
+
+lpm_stage::~lpm_stage() {
+    for (LayerRt& lr : lay) if (lr.ev_dz) (void)hipEventDestroy(lr.ev_dz);
+    if (ev_join) (void)hipEventDestroy(ev_join);
+    if (side) (void)hipStreamDestroy(side);
+}
+
+// Creates the side stream and events on first use (needs a device; stage creation does not).
+int32_t lpm_stage_prepare(lpm_stage* s) {
+    if (s->side) return LPM_OK;
+    hipStream_t st = nullptr;
+    LPM_HIP(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
+    hipEvent_t ej = nullptr;
+    hipError_t e = hipEventCreateWithFlags(&ej, hipEventDisableTiming);
+    for (LayerRt& lr : s->lay)
+        if (e == hipSuccess && has_weights(lr.d)) e = hipEventCreateWithFlags(&lr.ev_dz, hipEventDisableTiming);
+    if (e != hipSuccess) {
+        (void)hipStreamDestroy(st);
+        if (ej) (void)hipEventDestroy(ej);
+        for (LayerRt& lr : s->lay) if (lr.ev_dz) { (void)hipEventDestroy(lr.ev_dz); lr.ev_dz = nullptr; }
+        return hip_fail(e, "hipEventCreateWithFlags");
+    }
+    s->ev_join = ej;
+    s->side = st;
     return LPM_OK;
 }
 
@@ -253,8 +281,26 @@ extern "C" int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y
     const int32_t first = s->first, last = s->last;
     const bool acc = accumulate != 0;
     char* ws = (char*)bwd_ws;
-    void* dzbuf = ws + s->dz_off;
     void* kws = ws + s->kws_off;
+    void* wws = ws + s->wws_off;
+    int32_t prc = lpm_stage_prepare(s);
+    if (prc) return prc;
+    bool forked = false;
+    // While the caller's stream is being captured into a graph no second stream is involved: the weight
+    // gradient nodes are taken out of the stream's dependency frontier instead (they depend on what came
+    // before them and on the previous weight gradient, nothing later depends on them until the join).
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    LPM_HIP(hipStreamIsCapturing(st, &cap));
+    const bool use_side = cap == hipStreamCaptureStatusNone;
+    std::vector<hipGraphNode_t> wtail;     // capture: frontier left by the last weight gradient
+    auto frontier = [&](std::vector<hipGraphNode_t>& out) -> hipError_t {
+        hipStreamCaptureStatus stt;
+        const hipGraphNode_t* deps = nullptr;
+        size_t nd = 0;
+        hipError_t e = hipStreamGetCaptureInfo_v2(st, &stt, nullptr, nullptr, &deps, &nd);
+        if (e == hipSuccess) out.assign(deps, deps + nd);
+        return e;
+    };
 
     // gradient buffer of every tensor, and whether it already holds a contribution
     std::vector<void*> G((size_t)(last - first + 1), nullptr);
@@ -295,12 +341,26 @@ extern "C" int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y
                 if (relu || sc || gadd || lr.b_off != NO) {
                     const bool need_dz = relu || sc;
                     LPM_HIP(launch_epilogue_bwd(s->dtype, lr.g.rows_out(), l.cout, g, relu ? yout : nullptr, sc,
-                                                need_dz ? dzbuf : nullptr, gadd, gadd_acc,
+                                                need_dz ? (void*)(ws + lr.dz_off) : nullptr, gadd, gadd_acc,
                                                 lr.b_off != NO ? grads + lr.b_off : nullptr, acc, kws, st));
-                    if (need_dz) dz = dzbuf;
+                    if (need_dz) dz = ws + lr.dz_off;
                 }
                 const void* xin = tptr(s, l.src, x, y, stash);
-                LPM_HIP(launch_conv_wgrad(s->dtype, lr.g, xin, dz, grads + lr.w_off, acc, kws, st));
+                // weight gradient on the side stream, once dz (and everything before it) is ready
+                if (use_side) {
+                    LPM_HIP(hipEventRecord(lr.ev_dz, st));
+                    LPM_HIP(hipStreamWaitEvent(s->side, lr.ev_dz, 0));
+                    LPM_HIP(launch_conv_wgrad(s->dtype, lr.g, xin, dz, grads + lr.w_off, acc, wws, s->side));
+                    forked = true;
+                } else {
+                    std::vector<hipGraphNode_t> before;
+                    LPM_HIP(frontier(before));
+                    if (!wtail.empty())       // weight gradients share one scratch area: keep them in a chain
+                        LPM_HIP(hipStreamUpdateCaptureDependencies(st, wtail.data(), wtail.size(), hipStreamAddCaptureDependencies));
+                    LPM_HIP(launch_conv_wgrad(s->dtype, lr.g, xin, dz, grads + lr.w_off, acc, wws, st));
+                    LPM_HIP(frontier(wtail));
+                    LPM_HIP(hipStreamUpdateCaptureDependencies(st, before.data(), before.size(), hipStreamSetCaptureDependencies));
+                }
                 if (want_src) {
                     const void* w = s->dtype == LPM_BF16 ? (const void*)((const char*)lowp + lr.lowp_w_off)
                                                          : (const void*)(params + lr.w_off);
@@ -327,6 +387,12 @@ extern "C" int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y
             default:
                 return fail(LPM_ESHAPE, "internal: unexpected layer kind in backward");
         }
+    }
+    if (!wtail.empty())
+        LPM_HIP(hipStreamUpdateCaptureDependencies(st, wtail.data(), wtail.size(), hipStreamAddCaptureDependencies));
+    if (forked) {      // join: the caller's stream is ordered after every weight gradient
+        LPM_HIP(hipEventRecord(s->ev_join, s->side));
+        LPM_HIP(hipStreamWaitEvent(st, s->ev_join, 0));
     }
     return LPM_OK;
 }

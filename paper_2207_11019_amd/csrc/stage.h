@@ -23,6 +23,8 @@ struct LayerRt {
     size_t w_off = NO, b_off = NO, s_off = NO;   // float offsets into params
     size_t w_count = 0;
     size_t lowp_w_off = NO, lowp_wt_off = NO;    // byte offsets into lowp
+    size_t dz_off = NO;                          // byte offset of its pre-activation gradient in the backward scratch
+    hipEvent_t ev_dz = nullptr;                  // dz of this layer is ready (backward, main stream)
 };
 
 }  // namespace lpm
@@ -39,8 +41,12 @@ struct lpm_stage {
     int32_t t_out = 0;                // tensor written to y
     size_t n_trainable = 0, n_params = 0;   // floats
     size_t lowp_bytes = 0, stash_bytes = 0, fwd_ws = 0, bwd_ws = 0;
-    size_t dlogits_off = lpm::NO, dz_off = lpm::NO, kws_off = lpm::NO;   // stash / bwd-scratch offsets
-    size_t kws_bytes = 0;
+    size_t dlogits_off = lpm::NO, kws_off = lpm::NO, wws_off = lpm::NO;   // stash / bwd-scratch offsets
+    // Weight gradients are off the critical path of B (nothing in the same pass reads them), so they run on
+    // a side stream owned by the stage, forked from and joined back into the caller's stream.
+    hipStream_t side = nullptr;
+    hipEvent_t ev_join = nullptr;
+    ~lpm_stage();
 
     lpm::TensorRt& T(int32_t t) { return ten[(size_t)(t - (first - 1))]; }
     const lpm::TensorRt& T(int32_t t) const { return ten[(size_t)(t - (first - 1))]; }
