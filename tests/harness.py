@@ -92,7 +92,7 @@ def l2_err(got, ref):
 
 
 def stage_backward_isolated(lpm, layers, starts, m, batch_total, dtype, seed, dx_wanted=False, bias_std=0.05,
-                            grad_std=1e-3, report=None):
+                            grad_std=1e-3, report=None, check_forward=False):
     """B_{z,j} of every stage on its own, at full micro-batch size, from a forward state prepared by the oracle.
 
     The backward pass takes two integer decisions on stored activations (ReLU mask, position of a pooling
@@ -101,6 +101,8 @@ def stage_backward_isolated(lpm, layers, starts, m, batch_total, dtype, seed, dx
     side.  Here both sides take every decision on identical values: the oracle runs the forward pass
     (storing bf16-rounded activations for the bf16 element type), its stored tensors are written into
     the device buffers, and only lpm_stage_backward runs on the device.  Data flows oracle -> device only.
+    check_forward=True first runs the device's own forward pass on the same micro-batch and compares every
+    activation and the loss with the oracle's forward pass.
     """
     bf16 = dtype == 1
     q = orc.round_bf16 if bf16 else (lambda a: a)
@@ -108,11 +110,13 @@ def stage_backward_isolated(lpm, layers, starts, m, batch_total, dtype, seed, dx
     params, _ = wl.make_params(layers, seed, bf16=bf16, bias_std=bias_std)
     x, labels, g_up = wl.make_batch(layers, m, seed, bf16=bf16, grad_std=grad_std)
     Z = len(starts) - 1
-    stashes, a = [], x
+    stashes, a, loss_ref = [], x, None
     for z in range(Z):
         last = z == Z - 1
-        a, stash, _ = orc.stage_forward(layers, starts[z], starts[z + 1], params, a,
-                                        labels if (last and labels is not None) else None, batch_total, store)
+        print("oracle forward stage", z, flush=True)
+        a, stash, lz = orc.stage_forward(layers, starts[z], starts[z + 1], params, a,
+                                         labels if (last and labels is not None) else None, batch_total, store)
+        loss_ref = lz if lz is not None else loss_ref
         if "dlogits" in stash:
             stash["dlogits"] = q(stash["dlogits"])
         stashes.append(stash)
@@ -121,6 +125,25 @@ def stage_backward_isolated(lpm, layers, starts, m, batch_total, dtype, seed, dx
     xd = lpm.pack_act(x, dtype)
     tol = TOL[dtype]
     errs = {}
+    if check_forward:
+        # the device's own forward pass (one LOCKED step with learning rate 0) against the oracle's
+        import torch
+        ld = torch.from_numpy(labels).to("cuda:0") if labels is not None else None
+        gd = lpm.pack_act(g_up, dtype) if g_up is not None else None
+        print("device forward", flush=True)
+        net.step(xd, ld, gd, 0.0, 0.0, 0)
+        torch.cuda.synchronize()
+        if labels is not None:
+            errs["loss"] = abs(net.loss_value() * (m / batch_total) - loss_ref) / max(abs(loss_ref), 1e-30)
+        for z in range(Z):
+            for t in range(starts[z], starts[z + 1]):
+                if layers[t]["kind"] == "softmax_ce":
+                    continue
+                try:
+                    got = net.read_stash(t, 0)
+                except Exception:
+                    got = net.read_act_out(z, 0)
+                errs["act%d" % t] = rel_err(got, stashes[z][t])
     g_out = g_up
     for z in range(Z - 1, -1, -1):
         s0, s1 = starts[z], starts[z + 1]

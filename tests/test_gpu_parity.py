@@ -113,3 +113,23 @@ def test_vgg16_cifar_config_bf16(lpm):
     rep = {}
     stage_backward_isolated(lpm, layers, starts, 16, 128, 1, seed=11, report=rep)
     print("isolated backward worst", sorted(rep.items(), key=lambda kv: -kv[1])[:5], flush=True)
+
+
+FULL = [
+    # name, builder, plan, micro-batch, mini-batch, upstream gradient wanted
+    ("resnet18_cifar", wl.resnet18_cifar, [0, 5, 10, 15, 23], 32, 256, False),
+    ("r50_conv4x", wl.r50_conv4x, [0, 19], 16, 64, True),
+    ("vgg16_224", wl.vgg16_224, [0, 10, 18, 19, 22], 4, 32, False),
+]
+
+
+@pytest.mark.parametrize("name,builder,plan,m,batch,dx", FULL, ids=[f[0] for f in FULL])
+def test_full_size_microbatch_bf16(lpm, name, builder, plan, m, batch, dx):
+    """One micro-batch of each remaining workload at its real shape: the device's forward pass against the
+    oracle's, then B of every stage from the oracle's forward state (element-wise, 2e-2 of each tensor's
+    infinity norm).  VGG-16/224 uses the described plan (conv1-3 | conv4-5 | FC1 | FC2-3)."""
+    layers = builder()
+    rep = {}
+    print("workload", name, "plan", plan, flush=True)
+    stage_backward_isolated(lpm, layers, plan, m, batch, 1, seed=17, dx_wanted=dx, report=rep, check_forward=True)
+    print(name, "worst", sorted(rep.items(), key=lambda kv: -kv[1])[:6], flush=True)
