@@ -8,7 +8,7 @@ namespace lpm {
 hipError_t conv_fwd_generic_launch(int dtype, const ConvGeom& g, const void* x, const void* w, const float* scale,
                                    const float* bias, const void* add, int relu, void* y, hipStream_t s);
 hipError_t conv_dgrad_generic_launch(int dtype, const ConvGeom& g, const void* dz, const void* w, void* dx,
-                                     int accumulate, hipStream_t s);
+                                     int accumulate, const void* mask, const float* mscale, hipStream_t s);
 hipError_t conv_wgrad_generic_launch(int dtype, const ConvGeom& g, const void* x, const void* dz, float* dw,
                                      int accumulate, void* ws, hipStream_t s);
 size_t wgrad_generic_ws_bytes(const ConvGeom& g);
@@ -21,32 +21,46 @@ size_t mfma_dgrad_ws_bytes(const ConvGeom& g);
 size_t mfma_wgrad_ws_bytes(const ConvGeom& g);
 hipError_t mfma_conv_fwd(const ConvGeom& g, const void* x, const void* w, const float* scale, const float* bias,
                          const void* add, int relu, void* y, void* ws, hipStream_t st);
-hipError_t mfma_conv_dgrad(const ConvGeom& g, const void* dz, const void* wt, void* dx, int accumulate, void* ws,
-                           hipStream_t st);
-hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, int accumulate, void* ws,
-                           hipStream_t st);
+hipError_t mfma_conv_dgrad(const ConvGeom& g, const void* dz, const void* wt, void* dx, int accumulate, const void* mask,
+                           const float* mscale, void* ws, hipStream_t st);
+hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* bscale,
+                           int accumulate, void* ws, hipStream_t st);
+
+bool smallk_ok(const ConvGeom& g);
+hipError_t smallk_conv_fwd(const ConvGeom& g, const void* x, const void* w, const float* scale, const float* bias,
+                           const void* add, int relu, void* y, hipStream_t st);
+size_t smallk_wgrad_ws_bytes(const ConvGeom& g);
+hipError_t smallk_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, int accumulate, void* ws,
+                             hipStream_t st);
 
 size_t fwd_ws_bytes(int dtype, const ConvGeom& g) { return (dtype == LPM_BF16 && mfma_fwd_ok(g)) ? mfma_fwd_ws_bytes(g) : 0; }
 size_t dgrad_ws_bytes(int dtype, const ConvGeom& g) { return (dtype == LPM_BF16 && mfma_dgrad_ok(g)) ? mfma_dgrad_ws_bytes(g) : 0; }
 size_t wgrad_ws_bytes(int dtype, const ConvGeom& g) {
-    return (dtype == LPM_BF16 && mfma_wgrad_ok(g)) ? mfma_wgrad_ws_bytes(g) : wgrad_generic_ws_bytes(g);
+    if (dtype == LPM_BF16 && mfma_wgrad_ok(g)) return mfma_wgrad_ws_bytes(g);
+    if (dtype == LPM_BF16 && smallk_ok(g)) return smallk_wgrad_ws_bytes(g);
+    return wgrad_generic_ws_bytes(g);
 }
 
 hipError_t launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, const float* scale,
                            const float* bias, const void* add, int relu, void* y, void* ws, hipStream_t st) {
     if (dtype == LPM_BF16 && mfma_fwd_ok(g)) return mfma_conv_fwd(g, x, w, scale, bias, add, relu, y, ws, st);
+    if (dtype == LPM_BF16 && smallk_ok(g)) return smallk_conv_fwd(g, x, w, scale, bias, add, relu, y, st);
     return conv_fwd_generic_launch(dtype, g, x, w, scale, bias, add, relu, y, st);
 }
 
+bool wgrad_fuses_bias(int dtype, const ConvGeom& g) { return dtype == LPM_BF16 && mfma_wgrad_ok(g); }
+
 hipError_t launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dz, const void* w, const void* wt, void* dx,
-                             int accumulate, void* ws, hipStream_t st) {
-    if (dtype == LPM_BF16 && wt && mfma_dgrad_ok(g)) return mfma_conv_dgrad(g, dz, wt, dx, accumulate, ws, st);
-    return conv_dgrad_generic_launch(dtype, g, dz, w, dx, accumulate, st);
+                             int accumulate, const void* mask, const float* mscale, void* ws, hipStream_t st) {
+    if (dtype == LPM_BF16 && wt && mfma_dgrad_ok(g)) return mfma_conv_dgrad(g, dz, wt, dx, accumulate, mask, mscale, ws, st);
+    return conv_dgrad_generic_launch(dtype, g, dz, w, dx, accumulate, mask, mscale, st);
 }
 
-hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const void* dz, float* dw, int accumulate,
-                             void* ws, hipStream_t st) {
-    if (dtype == LPM_BF16 && mfma_wgrad_ok(g)) return mfma_conv_wgrad(g, x, dz, dw, accumulate, ws, st);
+hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias,
+                             const float* bscale, int accumulate, void* ws, hipStream_t st) {
+    if (dtype == LPM_BF16 && mfma_wgrad_ok(g)) return mfma_conv_wgrad(g, x, dz, dw, dbias, bscale, accumulate, ws, st);
+    if (dbias) return hipErrorInvalidValue;      // callers ask wgrad_fuses_bias first
+    if (dtype == LPM_BF16 && smallk_ok(g)) return smallk_conv_wgrad(g, x, dz, dw, accumulate, ws, st);
     return conv_wgrad_generic_launch(dtype, g, x, dz, dw, accumulate, ws, st);
 }
 

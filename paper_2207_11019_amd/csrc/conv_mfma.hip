@@ -31,6 +31,8 @@ struct IgemmArgs {
     const float* scale;
     const float* bias;
     const uint16_t* add;
+    const uint16_t* mask;   // data gradient: zero the result where this tensor (the producer's output) is <= 0
+    const float* mscale;    // data gradient: then multiply by the producer's per-channel scale
     int relu, accumulate;
     int M, N, Ktot;
     int Hi, Wi, Ci;       // extent of the gathered tensor
@@ -190,6 +192,8 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs p) {
                 if (p.add) v += bf2f(p.add[o]);
                 if (p.accumulate) v += bf2f(p.C[o]);
                 if (p.relu) v = fmaxf(v, 0.f);
+                if (p.mask && !(bf2f(p.mask[o]) > 0.f)) v = 0.f;
+                if (p.mscale) v *= p.mscale[col];
                 p.C[o] = f2bf(v);
             }
     }
@@ -199,6 +203,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs p) {
 __global__ void __launch_bounds__(256) splitk_epilogue(const float* __restrict__ part, int splits, int64_t MN, int N,
                                                        const float* __restrict__ scale, const float* __restrict__ bias,
                                                        const uint16_t* __restrict__ add, int relu, int accumulate,
+                                                       const uint16_t* __restrict__ mask, const float* __restrict__ mscale,
                                                        uint16_t* __restrict__ C) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= MN) return;
@@ -210,6 +215,8 @@ __global__ void __launch_bounds__(256) splitk_epilogue(const float* __restrict__
     if (add) v += bf2f(add[i]);
     if (accumulate) v += bf2f(C[i]);
     if (relu) v = fmaxf(v, 0.f);
+    if (mask && !(bf2f(mask[i]) > 0.f)) v = 0.f;
+    if (mscale) v *= mscale[col];
     C[i] = f2bf(v);
 }
 
@@ -265,7 +272,7 @@ static hipError_t run_igemm(int mode, IgemmArgs a, void* ws, hipStream_t st) {
     if (e != hipSuccess || pl.splits == 1) return e;
     const int64_t MN = (int64_t)a.M * a.N;
     hipLaunchKernelGGL(splitk_epilogue, dim3((unsigned)((MN + 255) / 256)), dim3(256), 0, st, (const float*)ws, pl.splits,
-                       MN, a.N, a.scale, a.bias, a.add, a.relu, a.accumulate, a.C);
+                       MN, a.N, a.scale, a.bias, a.add, a.relu, a.accumulate, a.mask, a.mscale, a.C);
     return hipGetLastError();
 }
 
@@ -292,11 +299,11 @@ hipError_t mfma_conv_fwd(const ConvGeom& g, const void* x, const void* w, const 
 }
 
 // wt: weights laid out [Cin][Kh][Kw][Cout]
-hipError_t mfma_conv_dgrad(const ConvGeom& g, const void* dz, const void* wt, void* dx, int accumulate, void* ws,
-                           hipStream_t st) {
+hipError_t mfma_conv_dgrad(const ConvGeom& g, const void* dz, const void* wt, void* dx, int accumulate, const void* mask,
+                           const float* mscale, void* ws, hipStream_t st) {
     IgemmArgs a{};
     a.A = (const uint16_t*)dz; a.B = (const uint16_t*)wt; a.C = (uint16_t*)dx;
-    a.accumulate = accumulate;
+    a.accumulate = accumulate; a.mask = (const uint16_t*)mask; a.mscale = mscale;
     a.M = (int)g.rows_in(); a.N = g.Cin; a.Ktot = g.Kh * g.Kw * g.Cout;
     a.Hi = g.Ho; a.Wi = g.Wo; a.Ci = g.Cout; a.Hr = g.H; a.Wr = g.W; a.Kw = g.Kw; a.stride = g.stride; a.pad = g.pad;
     return run_igemm(MODE_DGRAD, a, ws, st);
@@ -308,6 +315,9 @@ struct WgradArgs {
     const uint16_t* X;
     const uint16_t* DZ;
     float* out;            // dW, or the partials base when splits > 1
+    float* db;             // bias gradient (column sums of dz, divided by bscale), or NULL
+    const float* bscale;   // per-channel scale the layer applied after the bias-free pre-activation, or NULL
+    size_t part_stride;    // floats between the partials of consecutive splits (>= Cout*K + Cout)
     int Cout, Cin, KhKw, Kw;
     int H, W, Ho, Wo, stride, pad;
     int R;                 // reduction length m*Ho*Wo
@@ -403,6 +413,10 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs p) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
 
+    // the blocks of filter tap 0 / Cin tile 0 also sum their dz tile over the pixels: the bias gradient
+    const bool do_bias = p.db != nullptr && tap == 0 && ci_t == 0;
+    float bsum = 0.f;
+
     const int wm = wave >> 1, wn = wave & 1;
     if (rt0 < rt1) {
         load_tile(rt0);
@@ -411,6 +425,17 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs p) {
         for (int rt = rt0; rt < rt1; ++rt) {
             const int buf = (rt - rt0) & 1;
             if (rt + 1 < rt1) load_tile(rt + 1);
+            if (do_bias && tid < BM) {
+                const uint4* rowp = reinterpret_cast<const uint4*>(&As[buf][tid * LDK]);
+#pragma unroll
+                for (int k = 0; k < BK / 8; ++k) {
+                    const uint4 v = rowp[k];
+                    bsum += (bf2f((uint16_t)(v.x & 0xffffu)) + bf2f((uint16_t)(v.x >> 16))) +
+                            (bf2f((uint16_t)(v.y & 0xffffu)) + bf2f((uint16_t)(v.y >> 16))) +
+                            (bf2f((uint16_t)(v.z & 0xffffu)) + bf2f((uint16_t)(v.z >> 16))) +
+                            (bf2f((uint16_t)(v.w & 0xffffu)) + bf2f((uint16_t)(v.w >> 16)));
+                }
+            }
             mma_tile<Cfg::MI, Cfg::NI, BK>(As[buf], Bs[buf], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
             if (rt + 1 < rt1) store_tile(buf ^ 1);
             __syncthreads();
@@ -418,7 +443,15 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs p) {
     }
 
     const size_t total = (size_t)p.Cout * p.KhKw * p.Cin;
-    float* out = p.out + (p.splits > 1 ? (size_t)blockIdx.z * total : 0);
+    float* out = p.out + (p.splits > 1 ? (size_t)blockIdx.z * p.part_stride : 0);
+    if (do_bias && tid < BM && co0 + tid < p.Cout) {
+        const int co = co0 + tid;
+        if (p.splits > 1) out[total + co] = bsum;
+        else {
+            const float v = p.bscale ? bsum / p.bscale[co] : bsum;
+            p.db[co] = p.accumulate ? p.db[co] + v : v;
+        }
+    }
     const int col_l = lane & 31, rq = (lane >> 5) * 4;
 #pragma unroll
     for (int ni = 0; ni < Cfg::NI; ++ni) {
@@ -438,7 +471,21 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs p) {
     }
 }
 
-hipError_t reduce_partials_launch(const float* part, float* dst, int64_t n, int chunks, int accumulate, hipStream_t s);
+// dst[i] (+)= sum over splits of part[s*stride + i] (i < n);  db[c] (+)= (sum over splits of part[s*stride + n + c]) / bscale[c]
+__global__ void __launch_bounds__(256) wgrad_reduce(const float* __restrict__ part, size_t stride, int splits,
+                                                    float* __restrict__ dst, int64_t n, float* __restrict__ db, int nb,
+                                                    const float* __restrict__ bscale, int accumulate) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n + nb) return;
+    float acc = part[i];
+    for (int s = 1; s < splits; ++s) acc += part[(size_t)s * stride + i];
+    if (i < n) dst[i] = accumulate ? dst[i] + acc : acc;
+    else {
+        const int c = (int)(i - n);
+        if (bscale) acc /= bscale[c];
+        db[c] = accumulate ? db[c] + acc : acc;
+    }
+}
 
 struct WgradPlan { int big; int bk; int splits; int rt_total; int rt_per; int co_tiles, ci_tiles; };
 
@@ -469,11 +516,12 @@ bool mfma_wgrad_ok(const ConvGeom& g) { return g.Cin % 8 == 0 && g.Cout % 8 == 0
 
 size_t mfma_wgrad_ws_bytes(const ConvGeom& g) {
     const WgradPlan pl = plan_wgrad(g);
-    return pl.splits > 1 ? (size_t)pl.splits * g.Cout * g.K() * sizeof(float) : 0;
+    return pl.splits > 1 ? (size_t)pl.splits * ((size_t)g.Cout * g.K() + g.Cout) * sizeof(float) : 0;
 }
 
-hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, int accumulate, void* ws,
-                           hipStream_t st) {
+// dbias (may be NULL): also produce the bias gradient, the per-channel sum of dz divided by bscale (may be NULL)
+hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* bscale,
+                           int accumulate, void* ws, hipStream_t st) {
     const WgradPlan pl = plan_wgrad(g);
     WgradArgs a{};
     a.X = (const uint16_t*)x; a.DZ = (const uint16_t*)dz;
@@ -481,6 +529,8 @@ hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, flo
     a.Cout = g.Cout; a.Cin = g.Cin; a.KhKw = g.Kh * g.Kw; a.Kw = g.Kw;
     a.H = g.H; a.W = g.W; a.Ho = g.Ho; a.Wo = g.Wo; a.stride = g.stride; a.pad = g.pad;
     a.R = (int)g.rows_out();
+    a.db = dbias; a.bscale = bscale;
+    a.part_stride = (size_t)g.Cout * g.K() + g.Cout;
     a.rt_total = pl.rt_total; a.rt_per_split = pl.rt_per; a.splits = pl.splits;
     a.accumulate = accumulate;
     a.co_tiles = pl.co_tiles; a.ci_tiles = pl.ci_tiles;
@@ -490,7 +540,11 @@ hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, flo
     else hipLaunchKernelGGL((wgrad_kernel<64, 64, 64>), grid, dim3(256), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.splits == 1) return e;
-    return reduce_partials_launch((const float*)ws, dw, (int64_t)g.Cout * g.K(), pl.splits, accumulate, st);
+    const int64_t n = (int64_t)g.Cout * g.K();
+    const int nb = dbias ? g.Cout : 0;
+    hipLaunchKernelGGL(wgrad_reduce, dim3((unsigned)((n + nb + 255) / 256)), dim3(256), 0, st, (const float*)ws,
+                       a.part_stride, pl.splits, dw, n, dbias, nb, bscale, accumulate);
+    return hipGetLastError();
 }
 
 }  // namespace lpm

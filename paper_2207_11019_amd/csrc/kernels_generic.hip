@@ -60,7 +60,8 @@ hipError_t conv_fwd_generic_launch(int dtype, const ConvGeom& g, const void* x, 
 // data gradient, eq. 9: dx[n,h,w,ci] (+)= sum_{kh,kw,co} dz[n,(h+p-kh)/s,(w+p-kw)/s,co] * w[co,kh,kw,ci]
 template <typename T>
 __global__ void __launch_bounds__(256) conv_dgrad_generic(ConvGeom g, const T* __restrict__ dz, const T* __restrict__ w,
-                                                          T* __restrict__ dx, int accumulate) {
+                                                          T* __restrict__ dx, int accumulate, const T* __restrict__ mask,
+                                                          const float* __restrict__ mscale) {
     const int64_t total = g.rows_in() * g.Cin;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
@@ -85,14 +86,16 @@ __global__ void __launch_bounds__(256) conv_dgrad_generic(ConvGeom g, const T* _
         }
     }
     if (accumulate) acc += ld(dx, idx);
+    if (mask && !(ld(mask, idx) > 0.f)) acc = 0.f;
+    if (mscale) acc *= mscale[ci];
     st(dx, idx, acc);
 }
 
 hipError_t conv_dgrad_generic_launch(int dtype, const ConvGeom& g, const void* dz, const void* w, void* dx,
-                                     int accumulate, hipStream_t s) {
+                                     int accumulate, const void* mask, const float* mscale, hipStream_t s) {
     const int64_t total = g.rows_in() * g.Cin;
     LPM_DISPATCH(dtype, hipLaunchKernelGGL(conv_dgrad_generic<T>, dim3(nblk(total, 256)), dim3(256), 0, s, g,
-                                           (const T*)dz, (const T*)w, (T*)dx, accumulate));
+                                           (const T*)dz, (const T*)w, (T*)dx, accumulate, (const T*)mask, mscale));
     return hipGetLastError();
 }
 
@@ -319,7 +322,8 @@ __global__ void __launch_bounds__(256) maxpool_fwd_kernel(int m, int H, int W, i
 template <typename T>
 __global__ void __launch_bounds__(256) maxpool_bwd_kernel(int m, int H, int W, int C, const T* __restrict__ x,
                                                           const T* __restrict__ y, const T* __restrict__ dy,
-                                                          T* __restrict__ dx, int accumulate) {
+                                                          T* __restrict__ dx, int accumulate, int mask,
+                                                          const float* __restrict__ mscale) {
     const int Ho = H / 2, Wo = W / 2;
     const int64_t total = (int64_t)m * Ho * Wo * C;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -329,7 +333,10 @@ __global__ void __launch_bounds__(256) maxpool_bwd_kernel(int m, int H, int W, i
     const int wo = (int)(r % Wo), ho = (int)((r / Wo) % Ho), n = (int)(r / ((int64_t)Wo * Ho));
     const int64_t base = (((int64_t)n * H + 2 * ho) * W + 2 * wo) * C + c;
     const int64_t off[4] = {0, C, (int64_t)W * C, (int64_t)W * C + C};
-    const float mx = ld(y, idx), g = ld(dy, idx);
+    const float mx = ld(y, idx);
+    float g = ld(dy, idx);
+    if (mask && !(mx > 0.f)) g = 0.f;        // the pooled tensor is a ReLU output: its mask at the maximum
+    if (mscale) g *= mscale[c];
     bool found = false;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -349,10 +356,10 @@ hipError_t launch_maxpool_fwd(int dtype, int32_t m, int32_t H, int32_t W, int32_
 }
 
 hipError_t launch_maxpool_bwd(int dtype, int32_t m, int32_t H, int32_t W, int32_t C, const void* x, const void* y,
-                              const void* dy, void* dx, int accumulate, hipStream_t s) {
+                              const void* dy, void* dx, int accumulate, int mask, const float* mscale, hipStream_t s) {
     const int64_t total = (int64_t)m * (H / 2) * (W / 2) * C;
     LPM_DISPATCH(dtype, hipLaunchKernelGGL(maxpool_bwd_kernel<T>, dim3(nblk(total, 256)), dim3(256), 0, s, m, H, W, C,
-                                           (const T*)x, (const T*)y, (const T*)dy, (T*)dx, accumulate));
+                                           (const T*)x, (const T*)y, (const T*)dy, (T*)dx, accumulate, mask, mscale));
     return hipGetLastError();
 }
 
@@ -370,12 +377,15 @@ __global__ void __launch_bounds__(256) gap_fwd_kernel(int m, int HW, int C, cons
 
 template <typename T>
 __global__ void __launch_bounds__(256) gap_bwd_kernel(int m, int HW, int C, const T* __restrict__ dy, T* __restrict__ dx,
-                                                      int accumulate) {
+                                                      int accumulate, const T* __restrict__ mask,
+                                                      const float* __restrict__ mscale) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (int64_t)m * HW * C) return;
     const int c = (int)(idx % C), n = (int)(idx / ((int64_t)HW * C));
     float v = ld(dy, (int64_t)n * C + c) / (float)HW;
     if (accumulate) v += ld(dx, idx);
+    if (mask && !(ld(mask, idx) > 0.f)) v = 0.f;
+    if (mscale) v *= mscale[c];
     st(dx, idx, v);
 }
 
@@ -385,9 +395,10 @@ hipError_t launch_gap_fwd(int dtype, int32_t m, int32_t HW, int32_t C, const voi
     return hipGetLastError();
 }
 
-hipError_t launch_gap_bwd(int dtype, int32_t m, int32_t HW, int32_t C, const void* dy, void* dx, int accumulate, hipStream_t s) {
+hipError_t launch_gap_bwd(int dtype, int32_t m, int32_t HW, int32_t C, const void* dy, void* dx, int accumulate,
+                          const void* mask, const float* mscale, hipStream_t s) {
     LPM_DISPATCH(dtype, hipLaunchKernelGGL(gap_bwd_kernel<T>, dim3(nblk((int64_t)m * HW * C, 256)), dim3(256), 0, s, m, HW,
-                                           C, (const T*)dy, (T*)dx, accumulate));
+                                           C, (const T*)dy, (T*)dx, accumulate, (const T*)mask, mscale));
     return hipGetLastError();
 }
 

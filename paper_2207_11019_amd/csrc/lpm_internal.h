@@ -43,12 +43,15 @@ struct ConvGeom {
 // y = relu?( scale_c * conv(x, w) + bias_c + add )      (scale, bias, add may be NULL)
 hipError_t launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, const float* scale,
                            const float* bias, const void* add, int relu, void* y, void* ws, hipStream_t st);
-// dx (+)= conv_transpose(dz, w)
+// dx (+)= conv_transpose(dz, w);  then, when given, dx = dx * [mask > 0] * mscale_c -- the epilogue backward of
+// the layer that produced the tensor dx belongs to (mask = that tensor, mscale = that layer's scale)
 hipError_t launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dz, const void* w, const void* wt,
-                             void* dx, int accumulate, void* ws, hipStream_t st);
+                             void* dx, int accumulate, const void* mask, const float* mscale, void* ws, hipStream_t st);
 // dw (+)= sum over pixels of dz (x) x         ws: split-reduction partials (wgrad_ws_bytes)
-hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const void* dz, float* dw,
-                             int accumulate, void* ws, hipStream_t st);
+// dbias (may be NULL, only when wgrad_fuses_bias): dbias (+)= (sum over pixels of dz) / bscale_c
+hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias,
+                             const float* bscale, int accumulate, void* ws, hipStream_t st);
+bool wgrad_fuses_bias(int dtype, const ConvGeom& g);
 size_t wgrad_ws_bytes(int dtype, const ConvGeom& g);
 size_t fwd_ws_bytes(int dtype, const ConvGeom& g);
 size_t dgrad_ws_bytes(int dtype, const ConvGeom& g);
@@ -64,10 +67,11 @@ hipError_t launch_maxpool_fwd(int dtype, int32_t m, int32_t H, int32_t W, int32_
                               hipStream_t st);
 // dx (+)= dy routed to the first maximum of each window (recomputed from x and y)
 hipError_t launch_maxpool_bwd(int dtype, int32_t m, int32_t H, int32_t W, int32_t C, const void* x,
-                              const void* y, const void* dy, void* dx, int accumulate, hipStream_t st);
+                              const void* y, const void* dy, void* dx, int accumulate, int mask, const float* mscale,
+                              hipStream_t st);
 hipError_t launch_gap_fwd(int dtype, int32_t m, int32_t HW, int32_t C, const void* x, void* y, hipStream_t st);
 hipError_t launch_gap_bwd(int dtype, int32_t m, int32_t HW, int32_t C, const void* dy, void* dx, int accumulate,
-                          hipStream_t st);
+                          const void* mask, const float* mscale, hipStream_t st);
 // dlogits = (softmax(logits) - onehot) * loss_scale;  *loss_accum += loss_scale * sum_n -log p_n[label_n]
 hipError_t launch_softmax_ce(int dtype, int32_t m, int32_t C, const void* logits, const int32_t* labels,
                              float loss_scale, void* dlogits, float* loss_accum, hipStream_t st);

@@ -51,7 +51,7 @@ extern "C" int32_t lpm_conv_dgrad(const lpm_conv_geom* g, int32_t dtype, const v
     if (!dz || !w || !dx) return fail(LPM_EINVAL, "NULL argument");
     if (dgrad_ws_bytes(dtype, cg) && !ws) return fail(LPM_EINVAL, "scratch required");
     if (bad_align({dz, w, wt, dx, ws})) return fail(LPM_EALIGN, "device buffers must be 256-byte aligned");
-    LPM_HIP(launch_conv_dgrad(dtype, cg, dz, w, wt, dx, accumulate != 0, ws, (hipStream_t)stream));
+    LPM_HIP(launch_conv_dgrad(dtype, cg, dz, w, wt, dx, accumulate != 0, nullptr, nullptr, ws, (hipStream_t)stream));
     return LPM_OK;
 }
 
@@ -63,7 +63,7 @@ extern "C" int32_t lpm_conv_wgrad(const lpm_conv_geom* g, int32_t dtype, const v
     if (!x || !dz || !dw) return fail(LPM_EINVAL, "NULL argument");
     if (wgrad_ws_bytes(dtype, cg) && !ws) return fail(LPM_EINVAL, "scratch required");
     if (bad_align({x, dz, dw, ws})) return fail(LPM_EALIGN, "device buffers must be 256-byte aligned");
-    LPM_HIP(launch_conv_wgrad(dtype, cg, x, dz, dw, accumulate != 0, ws, (hipStream_t)stream));
+    LPM_HIP(launch_conv_wgrad(dtype, cg, x, dz, dw, nullptr, nullptr, accumulate != 0, ws, (hipStream_t)stream));
     return LPM_OK;
 }
 

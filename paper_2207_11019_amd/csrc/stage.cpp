@@ -101,6 +101,24 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
         kws = std::max(kws, align_up(epi_bwd_ws_bytes(lr.g.rows_out(), l.cout), 256));
         fws = std::max(fws, align_up(fwd_ws_bytes(dtype, lr.g), 256));
     }
+    // Epilogue-backward fusion: when a layer's output feeds exactly one later layer through its `src` edge, that
+    // layer's backward kernel (data gradient / pooling backward) applies the ReLU mask and the scale itself and
+    // writes dz directly; the bias gradient then comes out of the weight-gradient kernel.
+    for (int32_t i = first; i < last; ++i) {
+        LayerRt& lr = s->Ly(i);
+        const lpm_layer& l = lr.d;
+        if (dtype != LPM_BF16 || !has_weights(l) || !(l.flags & (LPM_RELU | LPM_SCALE)) || l.add_src != LPM_NONE) continue;
+        if (i == s->t_out) continue;           // its gradient arrives from outside the stage
+        int n_src = 0, n_other = 0;
+        for (int32_t j = i + 1; j < last; ++j) {
+            const lpm_layer& c = s->net[j];
+            if (c.src == i) (c.kind == LPM_SOFTMAX_CE ? n_other : n_src)++;
+            if (c.add_src == i) ++n_other;
+        }
+        if (n_src != 1 || n_other != 0) continue;
+        if ((l.flags & LPM_BIAS) && !wgrad_fuses_bias(dtype, lr.g)) continue;
+        lr.fused_in = true;
+    }
     s->n_trainable = off;
     if (dtype == LPM_BF16) {                   // transposed copies follow the mirrored region
         const size_t base = align_up(off * 2, 256);
@@ -330,57 +348,90 @@ extern "C" int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y
                 const void* yout = tptr(s, i, x, y, stash);
                 const float* sc = lr.s_off != NO ? params + lr.s_off : nullptr;
                 const bool relu = (l.flags & LPM_RELU) != 0;
-                void* gadd = nullptr;
-                int gadd_acc = 0;
-                if (l.add_src != LPM_NONE && ((l.add_src >= first) || dx != nullptr)) {
-                    gadd = G[gi(l.add_src)];
-                    gadd_acc = have[gi(l.add_src)];
-                    have[gi(l.add_src)] = 1;
-                }
+                float* dbias = lr.b_off != NO ? grads + lr.b_off : nullptr;
+                const bool bias_in_wgrad = dbias && wgrad_fuses_bias(s->dtype, lr.g);
                 const void* dz = g;
-                if (relu || sc || gadd || lr.b_off != NO) {
+                if (lr.fused_in) {
+                    dz = ws + lr.dz_off;           // written by the consumer's backward kernel
+                } else {
+                    void* gadd = nullptr;
+                    int gadd_acc = 0;
+                    if (l.add_src != LPM_NONE && ((l.add_src >= first) || dx != nullptr)) {
+                        gadd = G[gi(l.add_src)];
+                        gadd_acc = have[gi(l.add_src)];
+                        have[gi(l.add_src)] = 1;
+                    }
                     const bool need_dz = relu || sc;
-                    LPM_HIP(launch_epilogue_bwd(s->dtype, lr.g.rows_out(), l.cout, g, relu ? yout : nullptr, sc,
-                                                need_dz ? (void*)(ws + lr.dz_off) : nullptr, gadd, gadd_acc,
-                                                lr.b_off != NO ? grads + lr.b_off : nullptr, acc, kws, st));
-                    if (need_dz) dz = ws + lr.dz_off;
+                    if (need_dz || gadd || (dbias && !bias_in_wgrad)) {
+                        LPM_HIP(launch_epilogue_bwd(s->dtype, lr.g.rows_out(), l.cout, g, relu ? yout : nullptr, sc,
+                                                    need_dz ? (void*)(ws + lr.dz_off) : nullptr, gadd, gadd_acc,
+                                                    bias_in_wgrad ? nullptr : dbias, acc, kws, st));
+                        if (need_dz) dz = ws + lr.dz_off;
+                    }
+                }
+                float* wdb = bias_in_wgrad ? dbias : nullptr;
+                // where the gradient w.r.t. this layer's input goes: the producer's dz (fused) or the tensor's gradient
+                void* gsrc = nullptr;
+                int gsrc_acc = 0;
+                const void* gmask = nullptr;
+                const float* gmscale = nullptr;
+                const bool want = (l.src >= first) || (dx != nullptr);
+                if (want) {
+                    if (l.src >= first && s->Ly(l.src).fused_in) {
+                        const LayerRt& pr = s->Ly(l.src);
+                        gsrc = ws + pr.dz_off;
+                        gmask = (pr.d.flags & LPM_RELU) ? tptr(s, l.src, x, y, stash) : nullptr;
+                        gmscale = pr.s_off != NO ? params + pr.s_off : nullptr;
+                    } else {
+                        gsrc = G[gi(l.src)];
+                        gsrc_acc = have[gi(l.src)];
+                    }
+                    have[gi(l.src)] = 1;
                 }
                 const void* xin = tptr(s, l.src, x, y, stash);
                 // weight gradient on the side stream, once dz (and everything before it) is ready
                 if (use_side) {
                     LPM_HIP(hipEventRecord(lr.ev_dz, st));
                     LPM_HIP(hipStreamWaitEvent(s->side, lr.ev_dz, 0));
-                    LPM_HIP(launch_conv_wgrad(s->dtype, lr.g, xin, dz, grads + lr.w_off, acc, wws, s->side));
+                    LPM_HIP(launch_conv_wgrad(s->dtype, lr.g, xin, dz, grads + lr.w_off, wdb, sc, acc, wws, s->side));
                     forked = true;
                 } else {
                     std::vector<hipGraphNode_t> before;
                     LPM_HIP(frontier(before));
                     if (!wtail.empty())       // weight gradients share one scratch area: keep them in a chain
                         LPM_HIP(hipStreamUpdateCaptureDependencies(st, wtail.data(), wtail.size(), hipStreamAddCaptureDependencies));
-                    LPM_HIP(launch_conv_wgrad(s->dtype, lr.g, xin, dz, grads + lr.w_off, acc, wws, st));
+                    LPM_HIP(launch_conv_wgrad(s->dtype, lr.g, xin, dz, grads + lr.w_off, wdb, sc, acc, wws, st));
                     LPM_HIP(frontier(wtail));
                     LPM_HIP(hipStreamUpdateCaptureDependencies(st, before.data(), before.size(), hipStreamSetCaptureDependencies));
                 }
-                if (want_src) {
+                if (want) {
                     const void* w = s->dtype == LPM_BF16 ? (const void*)((const char*)lowp + lr.lowp_w_off)
                                                          : (const void*)(params + lr.w_off);
                     const void* wt = (s->dtype == LPM_BF16 && lr.lowp_wt_off != NO)
                                          ? (const void*)((const char*)lowp + lr.lowp_wt_off) : nullptr;
-                    LPM_HIP(launch_conv_dgrad(s->dtype, lr.g, dz, w, wt, G[gi(l.src)], have[gi(l.src)], kws, st));
-                    have[gi(l.src)] = 1;
+                    LPM_HIP(launch_conv_dgrad(s->dtype, lr.g, dz, w, wt, gsrc, gsrc_acc, gmask, gmscale, kws, st));
                 }
                 break;
             }
             case LPM_MAXPOOL2:
-                if (want_src) {
-                    LPM_HIP(launch_maxpool_bwd(s->dtype, s->m, l.h_in, l.w_in, l.cin, tptr(s, l.src, x, y, stash),
-                                               tptr(s, i, x, y, stash), g, G[gi(l.src)], have[gi(l.src)], st));
-                    have[gi(l.src)] = 1;
-                }
-                break;
             case LPM_GAP:
                 if (want_src) {
-                    LPM_HIP(launch_gap_bwd(s->dtype, s->m, l.h_in * l.w_in, l.cin, g, G[gi(l.src)], have[gi(l.src)], st));
+                    void* gsrc = G[gi(l.src)];
+                    int gsrc_acc = have[gi(l.src)];
+                    const void* gmask = nullptr;
+                    const float* gmscale = nullptr;
+                    if (l.src >= first && s->Ly(l.src).fused_in) {
+                        const LayerRt& pr = s->Ly(l.src);
+                        gsrc = ws + pr.dz_off;
+                        gsrc_acc = 0;
+                        gmask = (pr.d.flags & LPM_RELU) ? tptr(s, l.src, x, y, stash) : nullptr;
+                        gmscale = pr.s_off != NO ? params + pr.s_off : nullptr;
+                    }
+                    if (l.kind == LPM_MAXPOOL2)
+                        LPM_HIP(launch_maxpool_bwd(s->dtype, s->m, l.h_in, l.w_in, l.cin, tptr(s, l.src, x, y, stash),
+                                                   tptr(s, i, x, y, stash), g, gsrc, gsrc_acc, gmask != nullptr, gmscale, st));
+                    else
+                        LPM_HIP(launch_gap_bwd(s->dtype, s->m, l.h_in * l.w_in, l.cin, g, gsrc, gsrc_acc, gmask, gmscale, st));
                     have[gi(l.src)] = 1;
                 }
                 break;

@@ -40,6 +40,8 @@ SHAPES = [
     G(5, 4, 4, 64, 72, 4, 1, 0),          # kernel covers the input: a fully connected layer
     G(16, 1, 1, 512, 10, 1, 1, 0),        # classifier head (Cout = 10)
     G(4, 16, 16, 3, 64, 3, 1, 1),         # 3-channel first layer (generic kernels)
+    G(3, 9, 11, 3, 40, 3, 2, 1),          # 3-channel first layer, stride 2, ragged
+    G(2, 12, 12, 1, 16, 5, 1, 0),         # 1 channel, 5x5 (25 terms)
     G(16, 32, 32, 64, 160, 3, 1, 1),      # large: 128x128 tiles
     G(2, 14, 14, 256, 256, 3, 1, 1),      # both >= 128 channels: large weight-gradient tiles
 ]
