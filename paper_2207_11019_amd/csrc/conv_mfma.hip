@@ -18,10 +18,24 @@ namespace lpm {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// Global operands are read through buffer resources: a 16-byte load whose byte offset lies outside the
+// buffer returns zeros, so padding taps, ragged tiles and strided gaps need no branch and no select --
+// the loader just hands such chunks the offset OOB.  (Buffers are below 4 GiB; the host checks.)
+constexpr unsigned OOB = 0xffffffffu;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, unsigned off) {
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // A K tile of depth BK is stored in LDS as rows of BK + 8 elements (16-byte aligned, staggers banks).
 // Small-M shapes are bound by the latency of one global load per K tile, so they take deep tiles.
 
-enum { MODE_FWD = 0, MODE_DGRAD = 1 };
+enum { MODE_FWD = 0, MODE_DGRAD = 1 /* stride 1 */, MODE_DGRAD_S = 2 /* any stride */ };
 
 struct IgemmArgs {
     const uint16_t* A;
@@ -39,6 +53,7 @@ struct IgemmArgs {
     int Hr, Wr;           // extent of the row space
     int Kw, stride, pad;
     int kt_total, kt_per_split;
+    unsigned a_bytes, b_bytes;   // extents of A and B for the buffer resources
 };
 
 // XCD-aware tile order: consecutive workgroup ids land on different XCDs (each with its own L2), so give
@@ -94,60 +109,67 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs p) {
     const int kt1 = min(p.kt_total, kt0 + p.kt_per_split);
 
     // per-thread gather state of its A chunks (a chunk = 8 channels of one row = 16 bytes)
+    const __amdgpu_buffer_rsrc_t rsA = make_rsrc(p.A, p.a_bytes), rsB = make_rsrc(p.B, p.b_bytes);
     int a_nb[A_CH], a_h0[A_CH], a_w0[A_CH];
     bool a_ok[A_CH];
+    unsigned b_off[B_CH];
 #pragma unroll
     for (int c = 0; c < A_CH; ++c) {
         const int id = tid + c * 256, row = m0 + id / CPR;
-        a_ok[c] = (id < BM * CPR) && row < p.M;
+        a_ok[c] = (id < BM * CPR) & (row < p.M);
         const int rr = a_ok[c] ? row : 0;
         const int wq = rr % p.Wr, t = rr / p.Wr, hq = t % p.Hr, n = t / p.Hr;
         a_nb[c] = n * p.Hi * p.Wi;
         if (MODE == MODE_FWD) { a_h0[c] = hq * p.stride - p.pad; a_w0[c] = wq * p.stride - p.pad; }
         else { a_h0[c] = hq + p.pad; a_w0[c] = wq + p.pad; }
     }
-    uint4 ra[A_CH], rb[B_CH];
+#pragma unroll
+    for (int c = 0; c < B_CH; ++c) {
+        const int id = tid + c * 256, n = n0 + id / CPR;
+        b_off[c] = ((id < BN * CPR) & (n < p.N)) ? (unsigned)(((size_t)n * p.Ktot + (id % CPR) * 8) * 2) : OOB;
+    }
+    // two K tiles in flight in registers
+    uint4 ra0[A_CH], rb0[B_CH], ra1[A_CH], rb1[B_CH];
 
-    auto load_tile = [&](int kt) {
-        const int k0 = kt * BK;
-        const int tap = k0 / p.Ci, c0 = k0 - tap * p.Ci;
-        const int kh = tap / p.Kw, kw = tap - kh * p.Kw;
-#pragma unroll
-        for (int c = 0; c < A_CH; ++c) {
-            const int id = tid + c * 256, kc = id % CPR;
-            int h, w;
-            bool ok = a_ok[c];
-            if (MODE == MODE_FWD) { h = a_h0[c] + kh; w = a_w0[c] + kw; }
-            else {
-                h = a_h0[c] - kh; w = a_w0[c] - kw;
-                if (p.stride != 1) {
-                    ok = ok && h >= 0 && w >= 0 && (h % p.stride) == 0 && (w % p.stride) == 0;
-                    h /= p.stride; w /= p.stride;
-                }
-            }
-            ok = ok && (unsigned)h < (unsigned)p.Hi && (unsigned)w < (unsigned)p.Wi;
-            ra[c] = make_uint4(0, 0, 0, 0);
-            if (ok) ra[c] = *reinterpret_cast<const uint4*>(p.A + ((size_t)(a_nb[c] + h * p.Wi + w) * p.Ci + c0 + kc * 8));
-        }
-#pragma unroll
-        for (int c = 0; c < B_CH; ++c) {
-            const int id = tid + c * 256, n = n0 + id / CPR, kc = id % CPR;
-            rb[c] = make_uint4(0, 0, 0, 0);
-            if (id < BN * CPR && n < p.N) rb[c] = *reinterpret_cast<const uint4*>(p.B + ((size_t)n * p.Ktot + k0 + kc * 8));
-        }
-    };
-    auto store_tile = [&](int buf) {
-#pragma unroll
-        for (int c = 0; c < A_CH; ++c) {
-            const int id = tid + c * 256;
-            if (id < BM * CPR) *reinterpret_cast<uint4*>(&As[buf][(id / CPR) * LDK + (id % CPR) * 8]) = ra[c];
-        }
-#pragma unroll
-        for (int c = 0; c < B_CH; ++c) {
-            const int id = tid + c * 256;
-            if (id < BN * CPR) *reinterpret_cast<uint4*>(&Bs[buf][(id / CPR) * LDK + (id % CPR) * 8]) = rb[c];
-        }
-    };
+#define LPM_LOAD_TILE(KT, RA, RB)                                                                            \
+    {                                                                                                        \
+        const int k0_ = (KT) * BK;                                                                           \
+        const bool live_ = (KT) < kt1;                                                                       \
+        const int tap_ = k0_ / p.Ci, c0_ = k0_ - tap_ * p.Ci;                                                \
+        const int kh_ = tap_ / p.Kw, kw_ = tap_ - kh_ * p.Kw;                                                \
+        _Pragma("unroll") for (int c = 0; c < A_CH; ++c) {                                                   \
+            const int kc_ = (tid + c * 256) % CPR;                                                           \
+            int h_, w_;                                                                                      \
+            bool ok_ = a_ok[c] & live_;                                                                      \
+            if (MODE == MODE_FWD) { h_ = a_h0[c] + kh_; w_ = a_w0[c] + kw_; }                                \
+            else {                                                                                           \
+                h_ = a_h0[c] - kh_; w_ = a_w0[c] - kw_;                                                      \
+                if (MODE == MODE_DGRAD_S) {                                                                  \
+                    const int hq_ = h_ / p.stride, wq_ = w_ / p.stride;                                      \
+                    ok_ = ok_ & (h_ >= 0) & (w_ >= 0) & (hq_ * p.stride == h_) & (wq_ * p.stride == w_);     \
+                    h_ = hq_; w_ = wq_;                                                                      \
+                }                                                                                            \
+            }                                                                                                \
+            ok_ = ok_ & ((unsigned)h_ < (unsigned)p.Hi) & ((unsigned)w_ < (unsigned)p.Wi);                   \
+            const unsigned off_ = (unsigned)((a_nb[c] + h_ * p.Wi + w_) * p.Ci + c0_ + kc_ * 8) * 2u;        \
+            RA[c] = buf_load16(rsA, ok_ ? off_ : OOB);                                                       \
+        }                                                                                                    \
+        _Pragma("unroll") for (int c = 0; c < B_CH; ++c)                                                     \
+            RB[c] = buf_load16(rsB, ((b_off[c] == OOB) | !live_) ? OOB : b_off[c] + (unsigned)k0_ * 2u);     \
+    }
+#define LPM_STORE_TILE(BUF, RA, RB)                                                                          \
+    {                                                                                                        \
+        _Pragma("unroll") for (int c = 0; c < A_CH; ++c) {                                                   \
+            const int id_ = tid + c * 256;                                                                   \
+            if (A_CH * 256 == BM * CPR || id_ < BM * CPR)                                                    \
+                *reinterpret_cast<uint4*>(&As[BUF][(id_ / CPR) * LDK + (id_ % CPR) * 8]) = RA[c];            \
+        }                                                                                                    \
+        _Pragma("unroll") for (int c = 0; c < B_CH; ++c) {                                                   \
+            const int id_ = tid + c * 256;                                                                   \
+            if (B_CH * 256 == BN * CPR || id_ < BN * CPR)                                                    \
+                *reinterpret_cast<uint4*>(&Bs[BUF][(id_ / CPR) * LDK + (id_ % CPR) * 8]) = RB[c];            \
+        }                                                                                                    \
+    }
 
     f32x16 acc[Cfg::MI][Cfg::NI];
 #pragma unroll
@@ -158,18 +180,30 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs p) {
             for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
 
     const int wm = wave / WGN, wn = wave % WGN;
-    if (kt0 < kt1) {
-        load_tile(kt0);
-        store_tile(0);
+    // Pipeline: LDS holds tile i (being multiplied) and receives tile i+1; registers hold tiles i+1 and i+2,
+    // so every global load has two iterations to arrive.
+    const int nk = kt1 - kt0;
+    if (nk > 0) {
+        // Loads are issued unconditionally (a tile index past the end loads zeros that are never stored), so the
+        // wait before an LDS store counts exactly the younger tile's loads and lets them stay in flight.
+        LPM_LOAD_TILE(kt0, ra0, rb0);
+        LPM_LOAD_TILE(kt0 + 1, ra1, rb1);
+        LPM_STORE_TILE(0, ra0, rb0);
         __syncthreads();
-        for (int kt = kt0; kt < kt1; ++kt) {
-            const int buf = (kt - kt0) & 1;
-            if (kt + 1 < kt1) load_tile(kt + 1);
-            mma_tile<Cfg::MI, Cfg::NI, BK>(As[buf], Bs[buf], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
-            if (kt + 1 < kt1) store_tile(buf ^ 1);
+        for (int i = 0; i < nk; i += 2) {
+            LPM_LOAD_TILE(kt0 + i + 2, ra0, rb0);
+            mma_tile<Cfg::MI, Cfg::NI, BK>(As[0], Bs[0], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
+            if (i + 1 < nk) LPM_STORE_TILE(1, ra1, rb1);
+            __syncthreads();
+            if (i + 1 >= nk) break;
+            LPM_LOAD_TILE(kt0 + i + 3, ra1, rb1);
+            mma_tile<Cfg::MI, Cfg::NI, BK>(As[1], Bs[1], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
+            if (i + 2 < nk) LPM_STORE_TILE(0, ra0, rb0);
             __syncthreads();
         }
     }
+#undef LPM_LOAD_TILE
+#undef LPM_STORE_TILE
 
     // epilogue
     const int col_l = lane & 31, rq = (lane >> 5) * 4;
@@ -267,7 +301,8 @@ static hipError_t run_igemm(int mode, IgemmArgs a, void* ws, hipStream_t st) {
     a.kt_per_split = pl.kt_per;
     a.part = pl.splits > 1 ? (float*)ws : nullptr;
     if (mode == MODE_FWD) launch_igemm_cfg<MODE_FWD>(pl, a, st);
-    else launch_igemm_cfg<MODE_DGRAD>(pl, a, st);
+    else if (a.stride == 1) launch_igemm_cfg<MODE_DGRAD>(pl, a, st);
+    else launch_igemm_cfg<MODE_DGRAD_S>(pl, a, st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.splits == 1) return e;
     const int64_t MN = (int64_t)a.M * a.N;
@@ -276,8 +311,13 @@ static hipError_t run_igemm(int mode, IgemmArgs a, void* ws, hipStream_t st) {
     return hipGetLastError();
 }
 
-bool mfma_fwd_ok(const ConvGeom& g) { return g.Cin % 32 == 0 && g.rows_out() < (1ll << 31) / 8; }
-bool mfma_dgrad_ok(const ConvGeom& g) { return g.Cout % 32 == 0 && g.rows_in() < (1ll << 31) / 8; }
+// 32-bit byte offsets into every operand, 32-bit element counts of the output
+static bool fits32(const ConvGeom& g) {
+    const int64_t lim = (int64_t)1 << 31;
+    return g.rows_in() * g.Cin < lim && g.rows_out() * g.Cout < lim && (int64_t)g.Cout * g.K() < lim;
+}
+bool mfma_fwd_ok(const ConvGeom& g) { return g.Cin % 32 == 0 && fits32(g); }
+bool mfma_dgrad_ok(const ConvGeom& g) { return g.Cout % 32 == 0 && fits32(g); }
 
 size_t mfma_fwd_ws_bytes(const ConvGeom& g) {
     const IgemmPlan pl = plan_igemm(g.rows_out(), g.Cout, g.K(), g.Cin);
@@ -295,6 +335,7 @@ hipError_t mfma_conv_fwd(const ConvGeom& g, const void* x, const void* w, const 
     a.scale = scale; a.bias = bias; a.add = (const uint16_t*)add; a.relu = relu; a.accumulate = 0;
     a.M = (int)g.rows_out(); a.N = g.Cout; a.Ktot = g.K();
     a.Hi = g.H; a.Wi = g.W; a.Ci = g.Cin; a.Hr = g.Ho; a.Wr = g.Wo; a.Kw = g.Kw; a.stride = g.stride; a.pad = g.pad;
+    a.a_bytes = (unsigned)(g.rows_in() * g.Cin * 2); a.b_bytes = (unsigned)((int64_t)g.Cout * g.K() * 2);
     return run_igemm(MODE_FWD, a, ws, st);
 }
 
@@ -306,6 +347,7 @@ hipError_t mfma_conv_dgrad(const ConvGeom& g, const void* dz, const void* wt, vo
     a.accumulate = accumulate; a.mask = (const uint16_t*)mask; a.mscale = mscale;
     a.M = (int)g.rows_in(); a.N = g.Cin; a.Ktot = g.Kh * g.Kw * g.Cout;
     a.Hi = g.Ho; a.Wi = g.Wo; a.Ci = g.Cout; a.Hr = g.H; a.Wr = g.W; a.Kw = g.Kw; a.stride = g.stride; a.pad = g.pad;
+    a.a_bytes = (unsigned)(g.rows_out() * g.Cout * 2); a.b_bytes = (unsigned)((int64_t)g.Cout * g.K() * 2);
     return run_igemm(MODE_DGRAD, a, ws, st);
 }
 
@@ -318,6 +360,7 @@ struct WgradArgs {
     float* db;             // bias gradient (column sums of dz, divided by bscale), or NULL
     const float* bscale;   // per-channel scale the layer applied after the bias-free pre-activation, or NULL
     size_t part_stride;    // floats between the partials of consecutive splits (>= Cout*K + Cout)
+    unsigned dz_bytes, x_bytes;   // extents of DZ and X for the buffer resources
     int Cout, Cin, KhKw, Kw;
     int H, W, Ho, Wo, stride, pad;
     int R;                 // reduction length m*Ho*Wo
@@ -360,50 +403,47 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs p) {
     const int kh = tap / p.Kw, kw = tap - kh * p.Kw;
     const int rt0 = blockIdx.z * p.rt_per_split, rt1 = min(p.rt_total, rt0 + p.rt_per_split);
 
-    uint4 qa[A_PT][4], qb[B_PT][4];
+    // Two pixel tiles in flight in registers; out-of-range items (ragged channels, pixels past the end, taps
+    // in the padding) load zeros through the buffer resources.
+    const __amdgpu_buffer_rsrc_t rsD = make_rsrc(p.DZ, p.dz_bytes), rsX = make_rsrc(p.X, p.x_bytes);
+    uint4 qa0[A_PT][4], qb0[B_PT][4], qa1[A_PT][4], qb1[B_PT][4];
 
-    auto load_tile = [&](int rt) {
-#pragma unroll
-        for (int t = 0; t < A_PT; ++t) {
-            const int item = tid + t * 256, cc = item % (BM / 8), rg = item / (BM / 8);
-            const int ch = co0 + cc * 8;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                qa[t][j] = make_uint4(0, 0, 0, 0);
-                const int r = rt * BK + rg * 4 + j;
-                if (item < A_ITEMS && ch < p.Cout && r < p.R)
-                    qa[t][j] = *reinterpret_cast<const uint4*>(p.DZ + (size_t)r * p.Cout + ch);
-            }
-        }
-#pragma unroll
-        for (int t = 0; t < B_PT; ++t) {
-            const int item = tid + t * 256, cc = item % (BN / 8), rg = item / (BN / 8);
-            const int ch = ci0 + cc * 8;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                qb[t][j] = make_uint4(0, 0, 0, 0);
-                const int r = rt * BK + rg * 4 + j;
-                if (item < B_ITEMS && ch < p.Cin && r < p.R) {
-                    const int wo = r % p.Wo, q = r / p.Wo, ho = q % p.Ho, n = q / p.Ho;
-                    const int h = ho * p.stride + kh - p.pad, w = wo * p.stride + kw - p.pad;
-                    if ((unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W)
-                        qb[t][j] = *reinterpret_cast<const uint4*>(p.X + ((size_t)(n * p.H + h) * p.W + w) * p.Cin + ch);
-                }
-            }
-        }
-    };
-    auto store_tile = [&](int buf) {
-#pragma unroll
-        for (int t = 0; t < A_PT; ++t) {
-            const int item = tid + t * 256, cc = item % (BM / 8), rg = item / (BM / 8);
-            if (item < A_ITEMS) transpose4x8_store<LDK>(qa[t], &As[buf][(cc * 8) * LDK + rg * 4]);
-        }
-#pragma unroll
-        for (int t = 0; t < B_PT; ++t) {
-            const int item = tid + t * 256, cc = item % (BN / 8), rg = item / (BN / 8);
-            if (item < B_ITEMS) transpose4x8_store<LDK>(qb[t], &Bs[buf][(cc * 8) * LDK + rg * 4]);
-        }
-    };
+#define LPM_LOAD_TILE(RT, QA, QB)                                                                            \
+    {                                                                                                        \
+        _Pragma("unroll") for (int t = 0; t < A_PT; ++t) {                                                   \
+            const int item_ = tid + t * 256, cc_ = item_ % (BM / 8), rg_ = item_ / (BM / 8);                 \
+            const int ch_ = co0 + cc_ * 8;                                                                   \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                  \
+                const int r_ = (RT) * BK + rg_ * 4 + j;                                                      \
+                const bool ok_ = (item_ < A_ITEMS) & (ch_ < p.Cout) & (r_ < p.R) & ((RT) < rt1);             \
+                QA[t][j] = buf_load16(rsD, ok_ ? (unsigned)(r_ * p.Cout + ch_) * 2u : OOB);                  \
+            }                                                                                                \
+        }                                                                                                    \
+        _Pragma("unroll") for (int t = 0; t < B_PT; ++t) {                                                   \
+            const int item_ = tid + t * 256, cc_ = item_ % (BN / 8), rg_ = item_ / (BN / 8);                 \
+            const int ch_ = ci0 + cc_ * 8;                                                                   \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                  \
+                const int r_ = (RT) * BK + rg_ * 4 + j;                                                      \
+                const int rr_ = r_ < p.R ? r_ : 0;                                                           \
+                const int wo_ = rr_ % p.Wo, q_ = rr_ / p.Wo, ho_ = q_ % p.Ho, n_ = q_ / p.Ho;                \
+                const int h_ = ho_ * p.stride + kh - p.pad, w_ = wo_ * p.stride + kw - p.pad;                \
+                const bool ok_ = (item_ < B_ITEMS) & (ch_ < p.Cin) & (r_ < p.R) & ((RT) < rt1) &             \
+                                 ((unsigned)h_ < (unsigned)p.H) & ((unsigned)w_ < (unsigned)p.W);            \
+                QB[t][j] = buf_load16(rsX, ok_ ? (unsigned)(((n_ * p.H + h_) * p.W + w_) * p.Cin + ch_) * 2u : OOB); \
+            }                                                                                                \
+        }                                                                                                    \
+    }
+#define LPM_STORE_TILE(BUF, QA, QB)                                                                          \
+    {                                                                                                        \
+        _Pragma("unroll") for (int t = 0; t < A_PT; ++t) {                                                   \
+            const int item_ = tid + t * 256, cc_ = item_ % (BM / 8), rg_ = item_ / (BM / 8);                 \
+            if (item_ < A_ITEMS) transpose4x8_store<LDK>(QA[t], &As[BUF][(cc_ * 8) * LDK + rg_ * 4]);        \
+        }                                                                                                    \
+        _Pragma("unroll") for (int t = 0; t < B_PT; ++t) {                                                   \
+            const int item_ = tid + t * 256, cc_ = item_ % (BN / 8), rg_ = item_ / (BN / 8);                 \
+            if (item_ < B_ITEMS) transpose4x8_store<LDK>(QB[t], &Bs[BUF][(cc_ * 8) * LDK + rg_ * 4]);        \
+        }                                                                                                    \
+    }
 
     f32x16 acc[Cfg::MI][Cfg::NI];
 #pragma unroll
@@ -418,29 +458,41 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs p) {
     float bsum = 0.f;
 
     const int wm = wave >> 1, wn = wave & 1;
-    if (rt0 < rt1) {
-        load_tile(rt0);
-        store_tile(0);
-        __syncthreads();
-        for (int rt = rt0; rt < rt1; ++rt) {
-            const int buf = (rt - rt0) & 1;
-            if (rt + 1 < rt1) load_tile(rt + 1);
-            if (do_bias && tid < BM) {
-                const uint4* rowp = reinterpret_cast<const uint4*>(&As[buf][tid * LDK]);
+    auto bias_tile = [&](int buf) __attribute__((always_inline)) {
+        if (do_bias && tid < BM) {
+            const uint4* rowp = reinterpret_cast<const uint4*>(&As[buf][tid * LDK]);
 #pragma unroll
-                for (int k = 0; k < BK / 8; ++k) {
-                    const uint4 v = rowp[k];
-                    bsum += (bf2f((uint16_t)(v.x & 0xffffu)) + bf2f((uint16_t)(v.x >> 16))) +
-                            (bf2f((uint16_t)(v.y & 0xffffu)) + bf2f((uint16_t)(v.y >> 16))) +
-                            (bf2f((uint16_t)(v.z & 0xffffu)) + bf2f((uint16_t)(v.z >> 16))) +
-                            (bf2f((uint16_t)(v.w & 0xffffu)) + bf2f((uint16_t)(v.w >> 16)));
-                }
+            for (int k = 0; k < BK / 8; ++k) {
+                const uint4 v = rowp[k];
+                bsum += (bf2f((uint16_t)(v.x & 0xffffu)) + bf2f((uint16_t)(v.x >> 16))) +
+                        (bf2f((uint16_t)(v.y & 0xffffu)) + bf2f((uint16_t)(v.y >> 16))) +
+                        (bf2f((uint16_t)(v.z & 0xffffu)) + bf2f((uint16_t)(v.z >> 16))) +
+                        (bf2f((uint16_t)(v.w & 0xffffu)) + bf2f((uint16_t)(v.w >> 16)));
             }
-            mma_tile<Cfg::MI, Cfg::NI, BK>(As[buf], Bs[buf], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
-            if (rt + 1 < rt1) store_tile(buf ^ 1);
+        }
+    };
+    const int nk = rt1 - rt0;
+    if (nk > 0) {
+        LPM_LOAD_TILE(rt0, qa0, qb0);
+        LPM_LOAD_TILE(rt0 + 1, qa1, qb1);
+        LPM_STORE_TILE(0, qa0, qb0);
+        __syncthreads();
+        for (int i = 0; i < nk; i += 2) {
+            LPM_LOAD_TILE(rt0 + i + 2, qa0, qb0);
+            bias_tile(0);
+            mma_tile<Cfg::MI, Cfg::NI, BK>(As[0], Bs[0], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
+            if (i + 1 < nk) LPM_STORE_TILE(1, qa1, qb1);
+            __syncthreads();
+            if (i + 1 >= nk) break;
+            LPM_LOAD_TILE(rt0 + i + 3, qa1, qb1);
+            bias_tile(1);
+            mma_tile<Cfg::MI, Cfg::NI, BK>(As[1], Bs[1], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
+            if (i + 2 < nk) LPM_STORE_TILE(0, qa0, qb0);
             __syncthreads();
         }
     }
+#undef LPM_LOAD_TILE
+#undef LPM_STORE_TILE
 
     const size_t total = (size_t)p.Cout * p.KhKw * p.Cin;
     float* out = p.out + (p.splits > 1 ? (size_t)blockIdx.z * p.part_stride : 0);
@@ -512,7 +564,7 @@ static WgradPlan plan_wgrad(const ConvGeom& g) {
     return pl;
 }
 
-bool mfma_wgrad_ok(const ConvGeom& g) { return g.Cin % 8 == 0 && g.Cout % 8 == 0 && g.rows_out() < (1ll << 31) / 8; }
+bool mfma_wgrad_ok(const ConvGeom& g) { return g.Cin % 8 == 0 && g.Cout % 8 == 0 && fits32(g); }
 
 size_t mfma_wgrad_ws_bytes(const ConvGeom& g) {
     const WgradPlan pl = plan_wgrad(g);
@@ -531,6 +583,7 @@ hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, flo
     a.R = (int)g.rows_out();
     a.db = dbias; a.bscale = bscale;
     a.part_stride = (size_t)g.Cout * g.K() + g.Cout;
+    a.dz_bytes = (unsigned)(g.rows_out() * g.Cout * 2); a.x_bytes = (unsigned)(g.rows_in() * g.Cin * 2);
     a.rt_total = pl.rt_total; a.rt_per_split = pl.rt_per; a.splits = pl.splits;
     a.accumulate = accumulate;
     a.co_tiles = pl.co_tiles; a.ci_tiles = pl.ci_tiles;
