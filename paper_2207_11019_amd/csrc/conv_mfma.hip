@@ -110,52 +110,67 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs p) {
 
     // per-thread gather state of its A chunks (a chunk = 8 channels of one row = 16 bytes)
     const __amdgpu_buffer_rsrc_t rsA = make_rsrc(p.A, p.a_bytes), rsB = make_rsrc(p.B, p.b_bytes);
-    int a_nb[A_CH], a_h0[A_CH], a_w0[A_CH];
+    // Per chunk: the byte offset of its row's pixel at filter tap (0,0) (a_base, may wrap below zero for rows
+    // that start in the padding; it is only used when the tap lands inside the image) and the pixel's
+    // coordinates at tap (0,0).  Per K tile only a wave-uniform tap offset is added.
+    int a_h0[A_CH], a_w0[A_CH];
+    unsigned a_base[A_CH];
     bool a_ok[A_CH];
     unsigned b_off[B_CH];
 #pragma unroll
     for (int c = 0; c < A_CH; ++c) {
-        const int id = tid + c * 256, row = m0 + id / CPR;
+        const int id = tid + c * 256, row = m0 + id / CPR, kc = id % CPR;
         a_ok[c] = (id < BM * CPR) & (row < p.M);
         const int rr = a_ok[c] ? row : 0;
         const int wq = rr % p.Wr, t = rr / p.Wr, hq = t % p.Hr, n = t / p.Hr;
-        a_nb[c] = n * p.Hi * p.Wi;
         if (MODE == MODE_FWD) { a_h0[c] = hq * p.stride - p.pad; a_w0[c] = wq * p.stride - p.pad; }
         else { a_h0[c] = hq + p.pad; a_w0[c] = wq + p.pad; }
+        if (MODE == MODE_DGRAD_S) a_base[c] = (unsigned)(n * p.Hi * p.Wi * p.Ci + kc * 8) * 2u;
+        else a_base[c] = (unsigned)(((n * p.Hi + a_h0[c]) * p.Wi + a_w0[c]) * p.Ci + kc * 8) * 2u;
     }
 #pragma unroll
     for (int c = 0; c < B_CH; ++c) {
         const int id = tid + c * 256, n = n0 + id / CPR;
         b_off[c] = ((id < BN * CPR) & (n < p.N)) ? (unsigned)(((size_t)n * p.Ktot + (id % CPR) * 8) * 2) : OOB;
     }
+    // cursor of the next K tile to load (tiles are loaded strictly in order): filter tap and channel offset
+    int cur_kt = kt0, cur_c0, cur_kh, cur_kw;
+    {
+        const int k0 = kt0 * BK, tap = k0 / p.Ci;
+        cur_c0 = k0 - tap * p.Ci; cur_kh = tap / p.Kw; cur_kw = tap - cur_kh * p.Kw;
+    }
     // two K tiles in flight in registers
     uint4 ra0[A_CH], rb0[B_CH], ra1[A_CH], rb1[B_CH];
 
-#define LPM_LOAD_TILE(KT, RA, RB)                                                                            \
+#define LPM_LOAD_TILE(RA, RB)                                                                                \
     {                                                                                                        \
-        const int k0_ = (KT) * BK;                                                                           \
-        const bool live_ = (KT) < kt1;                                                                       \
-        const int tap_ = k0_ / p.Ci, c0_ = k0_ - tap_ * p.Ci;                                                \
-        const int kh_ = tap_ / p.Kw, kw_ = tap_ - kh_ * p.Kw;                                                \
+        const bool live_ = cur_kt < kt1;                                                                     \
+        const int kh_ = cur_kh, kw_ = cur_kw;                                                                \
+        const unsigned tapoff_ = (MODE == MODE_FWD)                                                          \
+                                     ? (unsigned)((kh_ * p.Wi + kw_) * p.Ci + cur_c0) * 2u                   \
+                                     : (unsigned)(cur_c0 - (kh_ * p.Wi + kw_) * p.Ci) * 2u;                  \
         _Pragma("unroll") for (int c = 0; c < A_CH; ++c) {                                                   \
-            const int kc_ = (tid + c * 256) % CPR;                                                           \
             int h_, w_;                                                                                      \
             bool ok_ = a_ok[c] & live_;                                                                      \
-            if (MODE == MODE_FWD) { h_ = a_h0[c] + kh_; w_ = a_w0[c] + kw_; }                                \
+            unsigned off_;                                                                                   \
+            if (MODE == MODE_FWD) { h_ = a_h0[c] + kh_; w_ = a_w0[c] + kw_; off_ = a_base[c] + tapoff_; }    \
+            else if (MODE == MODE_DGRAD) { h_ = a_h0[c] - kh_; w_ = a_w0[c] - kw_; off_ = a_base[c] + tapoff_; } \
             else {                                                                                           \
                 h_ = a_h0[c] - kh_; w_ = a_w0[c] - kw_;                                                      \
-                if (MODE == MODE_DGRAD_S) {                                                                  \
-                    const int hq_ = h_ / p.stride, wq_ = w_ / p.stride;                                      \
-                    ok_ = ok_ & (h_ >= 0) & (w_ >= 0) & (hq_ * p.stride == h_) & (wq_ * p.stride == w_);     \
-                    h_ = hq_; w_ = wq_;                                                                      \
-                }                                                                                            \
+                const int hq_ = h_ / p.stride, wq_ = w_ / p.stride;                                          \
+                ok_ = ok_ & (h_ >= 0) & (w_ >= 0) & (hq_ * p.stride == h_) & (wq_ * p.stride == w_);         \
+                h_ = hq_; w_ = wq_;                                                                          \
+                off_ = a_base[c] + (unsigned)((h_ * p.Wi + w_) * p.Ci + cur_c0) * 2u;                        \
             }                                                                                                \
             ok_ = ok_ & ((unsigned)h_ < (unsigned)p.Hi) & ((unsigned)w_ < (unsigned)p.Wi);                   \
-            const unsigned off_ = (unsigned)((a_nb[c] + h_ * p.Wi + w_) * p.Ci + c0_ + kc_ * 8) * 2u;        \
             RA[c] = buf_load16(rsA, ok_ ? off_ : OOB);                                                       \
         }                                                                                                    \
+        const unsigned k0b_ = (unsigned)cur_kt * (BK * 2u);                                                  \
         _Pragma("unroll") for (int c = 0; c < B_CH; ++c)                                                     \
-            RB[c] = buf_load16(rsB, ((b_off[c] == OOB) | !live_) ? OOB : b_off[c] + (unsigned)k0_ * 2u);     \
+            RB[c] = buf_load16(rsB, ((b_off[c] == OOB) | !live_) ? OOB : b_off[c] + k0b_);                   \
+        ++cur_kt;                                                                                            \
+        cur_c0 += BK;                                                                                        \
+        if (cur_c0 >= p.Ci) { cur_c0 = 0; if (++cur_kw == p.Kw) { cur_kw = 0; ++cur_kh; } }                  \
     }
 #define LPM_STORE_TILE(BUF, RA, RB)                                                                          \
     {                                                                                                        \
@@ -186,17 +201,17 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs p) {
     if (nk > 0) {
         // Loads are issued unconditionally (a tile index past the end loads zeros that are never stored), so the
         // wait before an LDS store counts exactly the younger tile's loads and lets them stay in flight.
-        LPM_LOAD_TILE(kt0, ra0, rb0);
-        LPM_LOAD_TILE(kt0 + 1, ra1, rb1);
+        LPM_LOAD_TILE(ra0, rb0);
+        LPM_LOAD_TILE(ra1, rb1);
         LPM_STORE_TILE(0, ra0, rb0);
         __syncthreads();
         for (int i = 0; i < nk; i += 2) {
-            LPM_LOAD_TILE(kt0 + i + 2, ra0, rb0);
+            LPM_LOAD_TILE(ra0, rb0);
             mma_tile<Cfg::MI, Cfg::NI, BK>(As[0], Bs[0], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
             if (i + 1 < nk) LPM_STORE_TILE(1, ra1, rb1);
             __syncthreads();
             if (i + 1 >= nk) break;
-            LPM_LOAD_TILE(kt0 + i + 3, ra1, rb1);
+            LPM_LOAD_TILE(ra1, rb1);
             mma_tile<Cfg::MI, Cfg::NI, BK>(As[1], Bs[1], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
             if (i + 2 < nk) LPM_STORE_TILE(0, ra0, rb0);
             __syncthreads();
