@@ -94,7 +94,7 @@ __device__ __forceinline__ void mma_tile(const uint16_t* As, const uint16_t* Bs,
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, int MODE>
-__global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs p) {
+__global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
     typedef TileCfg<BM, BN, WGM, WGN> Cfg;
     constexpr int LDK = BK + 8, CPR = BK / 8;                 // chunks (16 bytes) per row
     constexpr int A_CH = (BM * CPR + 255) / 256, B_CH = (BN * CPR + 255) / 256;
@@ -205,15 +205,16 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs p) {
         LPM_LOAD_TILE(ra1, rb1);
         LPM_STORE_TILE(0, ra0, rb0);
         __syncthreads();
-        for (int i = 0; i < nk; i += 2) {
+        // Tiles are processed in pairs with no exit in between; an odd count is padded by one all-zero tile.
+        const int npair = (nk + 1) >> 1;
+        for (int it = 0; it < npair; ++it) {
             LPM_LOAD_TILE(ra0, rb0);
             mma_tile<Cfg::MI, Cfg::NI, BK>(As[0], Bs[0], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
-            if (i + 1 < nk) LPM_STORE_TILE(1, ra1, rb1);
+            LPM_STORE_TILE(1, ra1, rb1);
             __syncthreads();
-            if (i + 1 >= nk) break;
             LPM_LOAD_TILE(ra1, rb1);
             mma_tile<Cfg::MI, Cfg::NI, BK>(As[1], Bs[1], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
-            if (i + 2 < nk) LPM_STORE_TILE(0, ra0, rb0);
+            LPM_STORE_TILE(0, ra0, rb0);
             __syncthreads();
         }
     }
@@ -401,7 +402,7 @@ __device__ __forceinline__ void transpose4x8_store(const uint4 (&q)[4], uint16_t
 }
 
 template <int BM, int BN, int BK>
-__global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs p) {
+__global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
     typedef TileCfg<BM, BN, 2, 2> Cfg;
     constexpr int LDK = BK + 8;
     constexpr int A_ITEMS = (BM / 8) * (BK / 4), B_ITEMS = (BN / 8) * (BK / 4);   // item = 4 pixels x 8 channels
@@ -492,17 +493,19 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs p) {
         LPM_LOAD_TILE(rt0 + 1, qa1, qb1);
         LPM_STORE_TILE(0, qa0, qb0);
         __syncthreads();
-        for (int i = 0; i < nk; i += 2) {
+        // pixel tiles in pairs with no exit in between; an odd count is padded by one all-zero tile
+        const int npair = (nk + 1) >> 1;
+        for (int it = 0; it < npair; ++it) {
+            const int i = it * 2;
             LPM_LOAD_TILE(rt0 + i + 2, qa0, qb0);
             bias_tile(0);
             mma_tile<Cfg::MI, Cfg::NI, BK>(As[0], Bs[0], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
-            if (i + 1 < nk) LPM_STORE_TILE(1, qa1, qb1);
+            LPM_STORE_TILE(1, qa1, qb1);
             __syncthreads();
-            if (i + 1 >= nk) break;
             LPM_LOAD_TILE(rt0 + i + 3, qa1, qb1);
             bias_tile(1);
             mma_tile<Cfg::MI, Cfg::NI, BK>(As[1], Bs[1], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
-            if (i + 2 < nk) LPM_STORE_TILE(0, qa0, qb0);
+            LPM_STORE_TILE(0, qa0, qb0);
             __syncthreads();
         }
     }
