@@ -424,30 +424,61 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
     const __amdgpu_buffer_rsrc_t rsD = make_rsrc(p.DZ, p.dz_bytes), rsX = make_rsrc(p.X, p.x_bytes);
     uint4 qa0[A_PT][4], qb0[B_PT][4], qa1[A_PT][4], qb1[B_PT][4];
 
-#define LPM_LOAD_TILE(RT, QA, QB)                                                                            \
+    // Cursors of the next pixel tile to load (tiles are loaded strictly in order).  Per item: the first of its
+    // 4 pixels as (row index, wo, ho, image); a tile step adds BK pixels with carries, pixels 1..3 follow by +1.
+    const int step_wo = BK % p.Wo, step_q = BK / p.Wo, step_ho = step_q % p.Ho, step_n = step_q / p.Ho;
+    int cur_rt = rt0;
+    int a_r[A_PT];
+    unsigned a_off[A_PT];
+    bool a_chok[A_PT];
+    int b_r[B_PT], b_wo[B_PT], b_ho[B_PT], b_n[B_PT];
+    unsigned b_choff[B_PT];
+    bool b_chok[B_PT];
+#pragma unroll
+    for (int t = 0; t < A_PT; ++t) {
+        const int item = tid + t * 256, cc = item % (BM / 8), rg = item / (BM / 8);
+        const int ch = co0 + cc * 8;
+        a_chok[t] = (item < A_ITEMS) & (ch < p.Cout);
+        a_r[t] = rt0 * BK + rg * 4;
+        a_off[t] = (unsigned)(a_r[t] * p.Cout + ch) * 2u;
+    }
+#pragma unroll
+    for (int t = 0; t < B_PT; ++t) {
+        const int item = tid + t * 256, cc = item % (BN / 8), rg = item / (BN / 8);
+        const int ch = ci0 + cc * 8;
+        b_chok[t] = (item < B_ITEMS) & (ch < p.Cin);
+        b_choff[t] = (unsigned)ch * 2u;
+        b_r[t] = rt0 * BK + rg * 4;
+        const int q = b_r[t] / p.Wo;
+        b_wo[t] = b_r[t] - q * p.Wo; b_ho[t] = q % p.Ho; b_n[t] = q / p.Ho;
+    }
+
+#define LPM_LOAD_TILE(QA, QB)                                                                                \
     {                                                                                                        \
+        const bool live_ = cur_rt < rt1;                                                                     \
         _Pragma("unroll") for (int t = 0; t < A_PT; ++t) {                                                   \
-            const int item_ = tid + t * 256, cc_ = item_ % (BM / 8), rg_ = item_ / (BM / 8);                 \
-            const int ch_ = co0 + cc_ * 8;                                                                   \
             _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                  \
-                const int r_ = (RT) * BK + rg_ * 4 + j;                                                      \
-                const bool ok_ = (item_ < A_ITEMS) & (ch_ < p.Cout) & (r_ < p.R) & ((RT) < rt1);             \
-                QA[t][j] = buf_load16(rsD, ok_ ? (unsigned)(r_ * p.Cout + ch_) * 2u : OOB);                  \
+                const bool ok_ = a_chok[t] & live_ & (a_r[t] + j < p.R);                                     \
+                QA[t][j] = buf_load16(rsD, ok_ ? a_off[t] + (unsigned)(j * p.Cout) * 2u : OOB);              \
             }                                                                                                \
+            a_r[t] += BK; a_off[t] += (unsigned)(BK * p.Cout) * 2u;                                          \
         }                                                                                                    \
         _Pragma("unroll") for (int t = 0; t < B_PT; ++t) {                                                   \
-            const int item_ = tid + t * 256, cc_ = item_ % (BN / 8), rg_ = item_ / (BN / 8);                 \
-            const int ch_ = ci0 + cc_ * 8;                                                                   \
+            int wo_ = b_wo[t], ho_ = b_ho[t], n_ = b_n[t];                                                   \
             _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                  \
-                const int r_ = (RT) * BK + rg_ * 4 + j;                                                      \
-                const int rr_ = r_ < p.R ? r_ : 0;                                                           \
-                const int wo_ = rr_ % p.Wo, q_ = rr_ / p.Wo, ho_ = q_ % p.Ho, n_ = q_ / p.Ho;                \
                 const int h_ = ho_ * p.stride + kh - p.pad, w_ = wo_ * p.stride + kw - p.pad;                \
-                const bool ok_ = (item_ < B_ITEMS) & (ch_ < p.Cin) & (r_ < p.R) & ((RT) < rt1) &             \
-                                 ((unsigned)h_ < (unsigned)p.H) & ((unsigned)w_ < (unsigned)p.W);            \
-                QB[t][j] = buf_load16(rsX, ok_ ? (unsigned)(((n_ * p.H + h_) * p.W + w_) * p.Cin + ch_) * 2u : OOB); \
+                const bool ok_ = b_chok[t] & live_ & (b_r[t] + j < p.R) & ((unsigned)h_ < (unsigned)p.H) &   \
+                                 ((unsigned)w_ < (unsigned)p.W);                                             \
+                QB[t][j] = buf_load16(rsX, ok_ ? (unsigned)(((n_ * p.H + h_) * p.W + w_) * p.Cin) * 2u + b_choff[t] : OOB); \
+                ++wo_;                                                                                       \
+                if (wo_ == p.Wo) { wo_ = 0; ++ho_; if (ho_ == p.Ho) { ho_ = 0; ++n_; } }                     \
             }                                                                                                \
+            b_r[t] += BK;                                                                                    \
+            b_wo[t] += step_wo; b_ho[t] += step_ho; b_n[t] += step_n;                                        \
+            if (b_wo[t] >= p.Wo) { b_wo[t] -= p.Wo; ++b_ho[t]; }                                             \
+            if (b_ho[t] >= p.Ho) { b_ho[t] -= p.Ho; ++b_n[t]; }                                              \
         }                                                                                                    \
+        ++cur_rt;                                                                                            \
     }
 #define LPM_STORE_TILE(BUF, QA, QB)                                                                          \
     {                                                                                                        \
@@ -489,20 +520,19 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
     };
     const int nk = rt1 - rt0;
     if (nk > 0) {
-        LPM_LOAD_TILE(rt0, qa0, qb0);
-        LPM_LOAD_TILE(rt0 + 1, qa1, qb1);
+        LPM_LOAD_TILE(qa0, qb0);
+        LPM_LOAD_TILE(qa1, qb1);
         LPM_STORE_TILE(0, qa0, qb0);
         __syncthreads();
         // pixel tiles in pairs with no exit in between; an odd count is padded by one all-zero tile
         const int npair = (nk + 1) >> 1;
         for (int it = 0; it < npair; ++it) {
-            const int i = it * 2;
-            LPM_LOAD_TILE(rt0 + i + 2, qa0, qb0);
+            LPM_LOAD_TILE(qa0, qb0);
             bias_tile(0);
             mma_tile<Cfg::MI, Cfg::NI, BK>(As[0], Bs[0], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
             LPM_STORE_TILE(1, qa1, qb1);
             __syncthreads();
-            LPM_LOAD_TILE(rt0 + i + 3, qa1, qb1);
+            LPM_LOAD_TILE(qa1, qb1);
             bias_tile(1);
             mma_tile<Cfg::MI, Cfg::NI, BK>(As[1], Bs[1], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
             LPM_STORE_TILE(0, qa0, qb0);
