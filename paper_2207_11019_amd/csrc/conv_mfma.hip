@@ -70,21 +70,26 @@ struct TileCfg {
     static_assert(WGM * WGN == 4 && WTM % 32 == 0 && WTN % 32 == 0, "4 wavefronts, 32x32 MFMA tiles");
 };
 
-// acc[mi][ni] += A-tile(wave rows) * B-tile(wave cols) over one BK-deep K tile held in LDS
-template <int MI, int NI, int BK>
+// acc[mi][ni] += A-tile(wave rows) * B-tile(wave cols) over one BK-deep K tile held in LDS (rows of LDK elements).
+// HALF: the rows are only 8-byte aligned, fetch each operand as two 8-byte reads.
+template <int MI, int NI, int BK, int LDK, bool HALF>
 __device__ __forceinline__ void mma_tile(const uint16_t* As, const uint16_t* Bs, int arow0, int brow0, int lane,
                                          f32x16 (&acc)[MI][NI]) {
-    constexpr int LDK = BK + 8;
     const int r = lane & 31, kq = (lane >> 5) * 8;
+    auto fetch = [&](const uint16_t* ptr) __attribute__((always_inline)) -> bf16x8 {
+        if (HALF) {
+            const uint2 lo = *reinterpret_cast<const uint2*>(ptr), hi = *reinterpret_cast<const uint2*>(ptr + 4);
+            return __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+        }
+        return *reinterpret_cast<const bf16x8*>(ptr);
+    };
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
         bf16x8 a[MI], b[NI];
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-            a[mi] = *reinterpret_cast<const bf16x8*>(As + (arow0 + mi * 32 + r) * LDK + ks * 16 + kq);
+        for (int mi = 0; mi < MI; ++mi) a[mi] = fetch(As + (arow0 + mi * 32 + r) * LDK + ks * 16 + kq);
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-            b[ni] = *reinterpret_cast<const bf16x8*>(Bs + (brow0 + ni * 32 + r) * LDK + ks * 16 + kq);
+        for (int ni = 0; ni < NI; ++ni) b[ni] = fetch(Bs + (brow0 + ni * 32 + r) * LDK + ks * 16 + kq);
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -209,11 +214,11 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
         const int npair = (nk + 1) >> 1;
         for (int it = 0; it < npair; ++it) {
             LPM_LOAD_TILE(ra0, rb0);
-            mma_tile<Cfg::MI, Cfg::NI, BK>(As[0], Bs[0], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
+            mma_tile<Cfg::MI, Cfg::NI, BK, LDK, false>(As[0], Bs[0], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
             LPM_STORE_TILE(1, ra1, rb1);
             __syncthreads();
             LPM_LOAD_TILE(ra1, rb1);
-            mma_tile<Cfg::MI, Cfg::NI, BK>(As[1], Bs[1], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
+            mma_tile<Cfg::MI, Cfg::NI, BK, LDK, false>(As[1], Bs[1], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
             LPM_STORE_TILE(0, ra0, rb0);
             __syncthreads();
         }
@@ -404,7 +409,11 @@ __device__ __forceinline__ void transpose4x8_store(const uint4 (&q)[4], uint16_t
 template <int BM, int BN, int BK>
 __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
     typedef TileCfg<BM, BN, 2, 2> Cfg;
-    constexpr int LDK = BK + 8;
+    // LDS rows of BK + 12 elements: 8 rows apart is 192 bytes apart modulo the 256-byte bank period, so the 4
+    // channel chunks x 8 pixel groups a half-wavefront writes per step fall on distinct banks (an item mapping
+    // with all 16 chunks in one wavefront put 88 % of the LDS cycles into bank conflicts).
+    constexpr int LDK = BK + 12;
+    constexpr int RGS = BK / 4;       // pixel groups per tile
     constexpr int A_ITEMS = (BM / 8) * (BK / 4), B_ITEMS = (BN / 8) * (BK / 4);   // item = 4 pixels x 8 channels
     constexpr int A_PT = (A_ITEMS + 255) / 256, B_PT = (B_ITEMS + 255) / 256;
     __shared__ __attribute__((aligned(16))) uint16_t As[2][BM * LDK];
@@ -436,7 +445,7 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
     bool b_chok[B_PT];
 #pragma unroll
     for (int t = 0; t < A_PT; ++t) {
-        const int item = tid + t * 256, cc = item % (BM / 8), rg = item / (BM / 8);
+        const int item = tid + t * 256, rg = (item >> 2) % RGS, cc = (item & 3) + 4 * (item / (4 * RGS));
         const int ch = co0 + cc * 8;
         a_chok[t] = (item < A_ITEMS) & (ch < p.Cout);
         a_r[t] = rt0 * BK + rg * 4;
@@ -444,7 +453,7 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
     }
 #pragma unroll
     for (int t = 0; t < B_PT; ++t) {
-        const int item = tid + t * 256, cc = item % (BN / 8), rg = item / (BN / 8);
+        const int item = tid + t * 256, rg = (item >> 2) % RGS, cc = (item & 3) + 4 * (item / (4 * RGS));
         const int ch = ci0 + cc * 8;
         b_chok[t] = (item < B_ITEMS) & (ch < p.Cin);
         b_choff[t] = (unsigned)ch * 2u;
@@ -483,11 +492,11 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
 #define LPM_STORE_TILE(BUF, QA, QB)                                                                          \
     {                                                                                                        \
         _Pragma("unroll") for (int t = 0; t < A_PT; ++t) {                                                   \
-            const int item_ = tid + t * 256, cc_ = item_ % (BM / 8), rg_ = item_ / (BM / 8);                 \
+            const int item_ = tid + t * 256, rg_ = (item_ >> 2) % RGS, cc_ = (item_ & 3) + 4 * (item_ / (4 * RGS)); \
             if (item_ < A_ITEMS) transpose4x8_store<LDK>(QA[t], &As[BUF][(cc_ * 8) * LDK + rg_ * 4]);        \
         }                                                                                                    \
         _Pragma("unroll") for (int t = 0; t < B_PT; ++t) {                                                   \
-            const int item_ = tid + t * 256, cc_ = item_ % (BN / 8), rg_ = item_ / (BN / 8);                 \
+            const int item_ = tid + t * 256, rg_ = (item_ >> 2) % RGS, cc_ = (item_ & 3) + 4 * (item_ / (4 * RGS)); \
             if (item_ < B_ITEMS) transpose4x8_store<LDK>(QB[t], &Bs[BUF][(cc_ * 8) * LDK + rg_ * 4]);        \
         }                                                                                                    \
     }
@@ -507,14 +516,12 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
     const int wm = wave >> 1, wn = wave & 1;
     auto bias_tile = [&](int buf) __attribute__((always_inline)) {
         if (do_bias && tid < BM) {
-            const uint4* rowp = reinterpret_cast<const uint4*>(&As[buf][tid * LDK]);
+            const uint2* rowp = reinterpret_cast<const uint2*>(&As[buf][tid * LDK]);
 #pragma unroll
-            for (int k = 0; k < BK / 8; ++k) {
-                const uint4 v = rowp[k];
+            for (int k = 0; k < BK / 4; ++k) {
+                const uint2 v = rowp[k];
                 bsum += (bf2f((uint16_t)(v.x & 0xffffu)) + bf2f((uint16_t)(v.x >> 16))) +
-                        (bf2f((uint16_t)(v.y & 0xffffu)) + bf2f((uint16_t)(v.y >> 16))) +
-                        (bf2f((uint16_t)(v.z & 0xffffu)) + bf2f((uint16_t)(v.z >> 16))) +
-                        (bf2f((uint16_t)(v.w & 0xffffu)) + bf2f((uint16_t)(v.w >> 16)));
+                        (bf2f((uint16_t)(v.y & 0xffffu)) + bf2f((uint16_t)(v.y >> 16)));
             }
         }
     };
@@ -529,12 +536,12 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
         for (int it = 0; it < npair; ++it) {
             LPM_LOAD_TILE(qa0, qb0);
             bias_tile(0);
-            mma_tile<Cfg::MI, Cfg::NI, BK>(As[0], Bs[0], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
+            mma_tile<Cfg::MI, Cfg::NI, BK, LDK, true>(As[0], Bs[0], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
             LPM_STORE_TILE(1, qa1, qb1);
             __syncthreads();
             LPM_LOAD_TILE(qa1, qb1);
             bias_tile(1);
-            mma_tile<Cfg::MI, Cfg::NI, BK>(As[1], Bs[1], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
+            mma_tile<Cfg::MI, Cfg::NI, BK, LDK, true>(As[1], Bs[1], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
             LPM_STORE_TILE(0, qa0, qb0);
             __syncthreads();
         }
