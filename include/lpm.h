@@ -74,6 +74,8 @@ extern "C" {
 /* ---- schedule modes ---- */
 #define LPM_LOCKED      0   /* F_{0,j}..F_{Z-1,j}, B_{Z-1,j}..B_{0,j} for j=0..M-1 on one stream, then U_z */
 #define LPM_OVERLAPPED  1   /* forward chain of micro-batch j+1 runs beside the backward chain of j        */
+#define LPM_PIPELINED   2   /* as OVERLAPPED, and every stage runs on its own pair of streams (owned by the
+                               schedule): stages work on different micro-batches at the same time         */
 #define LPM_GRAPH       16  /* OR-ed into mode: replay the step as a captured HIP graph                    */
 
 /* One layer a^{l+1} = g_l(a^l, p^l).  Tensor index t means "output of layer t"; t = -1 is the
@@ -206,7 +208,7 @@ typedef struct lpm_stage_buffers {
     float* params;  void* lowp;  float* grads;  float* momentum;
     void*  stash[LPM_MAX_WINDOW];   /* one slot per in-flight micro-batch                            */
     void*  act_out[LPM_MAX_WINDOW]; /* stage output ring (logits for the loss stage), out_bytes each */
-    void*  grad_in;                 /* gradient w.r.t. the stage input, in_bytes; may be NULL for stage 0 */
+    void*  grad_in[LPM_MAX_WINDOW]; /* gradient w.r.t. the stage input, in_bytes each; may be NULL for stage 0 */
     void*  fwd_ws;  void* bwd_ws;
 } lpm_stage_buffers;
 
@@ -220,17 +222,20 @@ int32_t lpm_schedule_destroy(lpm_schedule* s);
 
 /* One mini-batch step: all F_{z,j}, B_{z,j}, then U_z for every stage (one update per mini-batch with
  * the accumulated gradient).
- *   mode       LPM_LOCKED or LPM_OVERLAPPED, optionally | LPM_GRAPH
+ *   mode       LPM_LOCKED or LPM_OVERLAPPED, optionally | LPM_GRAPH; or LPM_PIPELINED (LPM_PIPELINED | LPM_GRAPH
+ *              is refused with LPM_EINVAL)
  *   x_batch    [M*m][H][W][C] network input (micro-batch j is the j-th contiguous block of m samples)
  *   labels     int32 [M*m] when the last stage is a loss stage, else NULL
  *   dy_batch   upstream gradient [M*m][..] of the last stage's output when it is not a loss stage
  *   per_stage  host array of Z buffer sets
- *   dx_wanted  non-zero: stage 0 also produces the gradient w.r.t. x (into per_stage[0].grad_in, one
- *              micro-batch at a time; for partitions fed by an upstream activation)
+ *   dx_wanted  non-zero: stage 0 also produces the gradient w.r.t. x (micro-batch j into
+ *              per_stage[0].grad_in[j % window]; for partitions fed by an upstream activation)
  *   loss_out   device float; set to the mini-batch mean loss (loss stage only; may be NULL otherwise)
- *   stream_fwd, stream_bwd  two distinct streams for LPM_OVERLAPPED; LPM_LOCKED uses stream_fwd only.
+ *   stream_fwd, stream_bwd  two distinct streams for LPM_OVERLAPPED; LPM_LOCKED and LPM_PIPELINED use
+ *              stream_fwd only (PIPELINED forks its own streams from it and joins them back).
+ * Micro-batch j uses slot j % window of stash, act_out and grad_in in every mode.
  * On return all work is enqueued and stream_fwd is ordered after everything the call enqueued.
- * Results are bitwise identical between the two modes (fixed accumulation order, no float atomics).
+ * Results are bitwise identical between the modes (fixed accumulation order, no float atomics).
  * Errors: LPM_EINVAL, LPM_EALIGN, LPM_EHIP. */
 int32_t lpm_schedule_run(lpm_schedule* s, int32_t mode, const void* x_batch, const int32_t* labels,
                          const void* dy_batch, const lpm_stage_buffers* per_stage, int32_t dx_wanted,

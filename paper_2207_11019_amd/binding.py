@@ -10,7 +10,7 @@ import os
 import numpy as np
 
 __all__ = ["LpmError", "lib", "lpm_conv_geom", "lpm_conv_ws_bytes", "lpm_conv_forward", "lpm_conv_dgrad", "lpm_conv_wgrad", "lpm_conv_time", "lpm_layer", "lpm_cost_params", "lpm_stage_buffers", "layers_from_dicts",
-           "lpm_layer_cost", "lpm_partition", "Stage", "Schedule", "Net", "F32", "BF16", "LOCKED", "OVERLAPPED",
+           "lpm_layer_cost", "lpm_partition", "Stage", "Schedule", "Net", "F32", "BF16", "LOCKED", "OVERLAPPED", "PIPELINED",
            "GRAPH", "pack_act", "unpack_act", "pack_weight", "unpack_weight", "MI355X_COST"]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -20,7 +20,7 @@ if not os.path.exists(_LIB):
 lib = C.CDLL(_LIB)
 
 F32, BF16 = 0, 1
-LOCKED, OVERLAPPED, GRAPH = 0, 1, 16
+LOCKED, OVERLAPPED, PIPELINED, GRAPH = 0, 1, 2, 16
 KINDS = {"conv": 0, "fc": 1, "maxpool2": 2, "gap": 3, "softmax_ce": 4}
 RELU, BIAS, SCALE = 1, 2, 4
 NONE = -2
@@ -45,7 +45,7 @@ class lpm_cost_params(C.Structure):
 
 class lpm_stage_buffers(C.Structure):
     _fields_ = [("params", C.c_void_p), ("lowp", C.c_void_p), ("grads", C.c_void_p), ("momentum", C.c_void_p),
-                ("stash", C.c_void_p * MAX_WINDOW), ("act_out", C.c_void_p * MAX_WINDOW), ("grad_in", C.c_void_p),
+                ("stash", C.c_void_p * MAX_WINDOW), ("act_out", C.c_void_p * MAX_WINDOW), ("grad_in", C.c_void_p * MAX_WINDOW),
                 ("fwd_ws", C.c_void_p), ("bwd_ws", C.c_void_p)]
 
 
@@ -315,6 +315,17 @@ def _wshape(l):
     return (l["cout"], l["cin"], l["kh"], l["kw"])
 
 
+_NET_STREAMS = {}
+
+
+def _net_streams(torch, device):
+    """One pair of streams per device, shared by every Net of the process."""
+    key = str(device)
+    if key not in _NET_STREAMS:
+        _NET_STREAMS[key] = (torch.cuda.Stream(device=device), torch.cuda.Stream(device=device))
+    return _NET_STREAMS[key]
+
+
 class Net:
     """A partitioned network resident on one GPU: stages, their device buffers and a schedule.
 
@@ -345,7 +356,7 @@ class Net:
             b = dict(params=buf(s.param_bytes), lowp=buf(s.lowp_bytes) if dtype == BF16 else None, grads=buf(s.grad_bytes),
                      momentum=buf(s.grad_bytes), stash=[buf(s.stash_bytes) for _ in range(window)],
                      act_out=[buf(s.out_bytes) for _ in range(window)],
-                     grad_in=buf(s.in_bytes) if (z > 0 or dx_wanted) else None,
+                     grad_in=[buf(s.in_bytes) if (z > 0 or dx_wanted) else None for _ in range(window)],
                      fwd_ws=buf(s.fwd_ws_bytes), bwd_ws=buf(s.bwd_ws_bytes))
             self.bufs.append(b)
             cb = self.cbufs[z]
@@ -353,10 +364,10 @@ class Net:
             for w in range(window):
                 cb.stash[w] = _ptr(b["stash"][w])
                 cb.act_out[w] = _ptr(b["act_out"][w])
-            cb.grad_in, cb.fwd_ws, cb.bwd_ws = _ptr(b["grad_in"]), _ptr(b["fwd_ws"]), _ptr(b["bwd_ws"])
+                cb.grad_in[w] = _ptr(b["grad_in"][w])
+            cb.fwd_ws, cb.bwd_ws = _ptr(b["fwd_ws"]), _ptr(b["bwd_ws"])
         self.loss = torch.zeros(64, dtype=torch.float32, device=self.device)
-        self.stream_fwd = torch.cuda.Stream(device=self.device)
-        self.stream_bwd = torch.cuda.Stream(device=self.device)
+        self.stream_fwd, self.stream_bwd = _net_streams(torch, self.device)
 
     def stage_of(self, layer):
         for z in range(self.Z):
@@ -453,9 +464,9 @@ class Net:
         assert src.numel() == self.stages[z].out_bytes
         self.bufs[z]["act_out"][slot][:src.numel()].copy_(src)
 
-    def read_grad_in(self, z):
+    def read_grad_in(self, z, slot=0):
         s = self.stages[z]
-        return unpack_act(self.bufs[z]["grad_in"][:s.in_bytes].view(self.tdtype), (self.m,) + self.tensor_shape(s.first - 1))
+        return unpack_act(self.bufs[z]["grad_in"][slot][:s.in_bytes].view(self.tdtype), (self.m,) + self.tensor_shape(s.first - 1))
 
     # ---- one mini-batch step
     def step(self, x_batch, labels, dy_batch, lr, mu, mode=OVERLAPPED):

@@ -18,6 +18,12 @@ int32_t hip_fail(hipError_t e, const char* what);
         if (e__ != hipSuccess) return lpm::hip_fail(e__, #call); \
     } while (0)
 
+// ---- pooled worker streams (per device, created on first use, alive until the process ends) --------
+constexpr int LPM_POOL_SCHEDULE_STREAMS = 8;    // indices 0..7: forward / backward stream of stage z at 2z, 2z+1 (mod 8)
+constexpr int LPM_POOL_STREAMS = 12;            // indices 8..11: weight-gradient side streams, handed out round-robin
+hipError_t pooled_stream(int index, hipStream_t* out);
+int next_side_stream_index();
+
 // ---- validated network description ---------------------------------------------------------------
 struct Shape { int32_t c, h, w; size_t elems() const { return (size_t)c * h * w; } };
 

@@ -6,6 +6,12 @@
 //   OVERLAPPED  the forward chain of micro-batch j+1 runs on one stream while the backward chain of
 //               micro-batch j runs on another; a stage holds at most `window` micro-batches in
 //               flight, i.e. F_{z,j+window} starts after B_{z,j} ("B_{0,0} finishes before F_{0,2}").
+//   PIPELINED   the same dependency set, but every stage owns a forward and a backward stream (the
+//               one-device-per-sub-module layout of the method's figure, with streams standing in for
+//               devices): F_{z,j+1} also overlaps F_{z+1,j}, and B_{z,j} overlaps B_{z+1,j+1}.
+// Every buffer that belongs to a micro-batch (stash, stage output, input gradient) lives in slot
+// j % window.  Micro-batch j + window starts at stage 0 only after B_{0,j}, the last operation of
+// micro-batch j, so a slot is never rewritten while an operation of its previous owner is pending.
 // Gradients are accumulated over the micro-batches in the fixed order j = 0..M-1 and every stage is
 // updated once, right after its last backward, so both modes produce bit-identical results.
 #include "stage.h"
@@ -28,9 +34,11 @@ struct GraphEntry {
 struct lpm_schedule {
     std::vector<lpm_stage*> st;
     int32_t Z = 0, M = 0, window = 2;
-    std::vector<hipEvent_t> ev_f;   // [M]    F_{Z-1,j} done
-    std::vector<hipEvent_t> ev_b;   // [Z*M]  B_{z,j} done
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    std::vector<hipEvent_t> ev_f;   // [Z*M]  F_{z,j} done (index j*Z + z)
+    std::vector<hipEvent_t> ev_b;   // [Z*M]  data phase of B_{z,j} done
+    std::vector<hipEvent_t> ev_w;   // [Z*M]  all of B_{z,j} done (weight phase included)
+    hipEvent_t ev_fork = nullptr;
+    std::vector<hipStream_t> sf, sb;     // PIPELINED: per-stage forward / backward streams (borrowed from the pool)
     std::vector<GraphEntry> graphs;
 };
 
@@ -38,7 +46,7 @@ static void destroy_events(lpm_schedule* s) {
     for (hipEvent_t e : s->ev_f) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : s->ev_b) if (e) (void)hipEventDestroy(e);
     if (s->ev_fork) (void)hipEventDestroy(s->ev_fork);
-    if (s->ev_join) (void)hipEventDestroy(s->ev_join);
+    for (hipEvent_t e : s->ev_w) if (e) (void)hipEventDestroy(e);
     for (GraphEntry& g : s->graphs) {
         if (g.exec) (void)hipGraphExecDestroy(g.exec);
         if (g.graph) (void)hipGraphDestroy(g.graph);
@@ -69,17 +77,24 @@ extern "C" int32_t lpm_schedule_create(lpm_stage* const* stages, int32_t Z, int3
     if (!s) return fail(LPM_ENOMEM, "out of host memory");
     s->st.assign(stages, stages + Z);
     s->Z = Z; s->M = n_microbatch; s->window = window;
-    s->ev_f.assign((size_t)n_microbatch, nullptr);
+    s->ev_f.assign((size_t)n_microbatch * Z, nullptr);
     s->ev_b.assign((size_t)n_microbatch * Z, nullptr);
+    s->ev_w.assign((size_t)n_microbatch * Z, nullptr);
+    s->sf.assign((size_t)Z, nullptr);
+    s->sb.assign((size_t)Z, nullptr);
     hipError_t e = hipSuccess;
+    for (int32_t z = 0; z < Z; ++z) {
+        if (e == hipSuccess) e = pooled_stream((2 * z) % LPM_POOL_SCHEDULE_STREAMS, &s->sf[(size_t)z]);
+        if (e == hipSuccess) e = pooled_stream((2 * z + 1) % LPM_POOL_SCHEDULE_STREAMS, &s->sb[(size_t)z]);
+    }
+    for (hipEvent_t& ev : s->ev_w) if (e == hipSuccess) e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
     for (hipEvent_t& ev : s->ev_f) if (e == hipSuccess) e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
     for (hipEvent_t& ev : s->ev_b) if (e == hipSuccess) e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&s->ev_fork, hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&s->ev_join, hipEventDisableTiming);
     if (e != hipSuccess) {
         destroy_events(s);
         delete s;
-        return hip_fail(e, "hipEventCreateWithFlags");
+        return hip_fail(e, "creating the schedule's streams and events");
     }
     *out = s;
     return LPM_OK;
@@ -112,18 +127,19 @@ int32_t fwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStrea
                              1.0f / (float)(s->M * sg->m), st);
 }
 
-int32_t bwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStream_t st) {
+// wst: stream of the weight phase (see lpm_stage_backward_on)
+int32_t bwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStream_t st, hipStream_t wst) {
     lpm_stage* sg = s->st[(size_t)z];
     const int32_t slot = j % s->window;
     const lpm_stage_buffers& b = a.bufs[z];
     const void* in = z == 0 ? (const void*)((const char*)a.x_batch + (size_t)j * sg->T(sg->first - 1).bytes)
                             : (const void*)a.bufs[z - 1].act_out[slot];
     const void* dy = nullptr;
-    if (z < s->Z - 1) dy = a.bufs[z + 1].grad_in;
+    if (z < s->Z - 1) dy = a.bufs[z + 1].grad_in[slot];
     else if (!sg->loss) dy = (const char*)a.dy_batch + (size_t)j * sg->T(sg->t_out).bytes;
-    void* dx = z == 0 ? (a.dx_wanted ? b.grad_in : nullptr) : b.grad_in;
-    return lpm_stage_backward(sg, in, b.act_out[slot], dy, dx, b.params, b.lowp, b.stash[slot], b.grads, j > 0,
-                              b.bwd_ws, st);
+    void* dx = (z > 0 || a.dx_wanted) ? b.grad_in[slot] : nullptr;
+    return lpm_stage_backward_on(sg, in, b.act_out[slot], dy, dx, b.params, b.lowp, b.stash[slot], b.grads, j > 0,
+                                 b.bwd_ws, st, wst, j & 1);
 }
 
 int32_t upd_op(lpm_schedule* s, const RunArgs& a, int32_t z, hipStream_t st) {
@@ -131,35 +147,74 @@ int32_t upd_op(lpm_schedule* s, const RunArgs& a, int32_t z, hipStream_t st) {
     return lpm_stage_update(s->st[(size_t)z], b.params, b.lowp, b.grads, b.momentum, a.lr, a.mu, 0, st);
 }
 
+// The dz area of a stage's backward scratch has two copies (micro-batch parity), so the weight phase of
+// micro-batch j may still run while the data phase of j + 1 writes; the data phase of j + 2 follows the
+// forward pass of j + 2, which the window rule places after micro-batch j when window <= 2.  A wider
+// window needs the explicit wait below.
 int32_t enqueue(lpm_schedule* s, const RunArgs& a) {
     const int32_t Z = s->Z, M = s->M, W = s->window;
+    const bool capturing = (a.mode & LPM_GRAPH) != 0;
     int32_t rc;
     if (s->st[(size_t)Z - 1]->loss) LPM_HIP(launch_fill_f32(a.loss_out, 1, 0.f, a.sf));
     if ((a.mode & 15) == LPM_LOCKED) {
         for (int32_t j = 0; j < M; ++j) {
             for (int32_t z = 0; z < Z; ++z) if ((rc = fwd_op(s, a, z, j, a.sf))) return rc;
-            for (int32_t z = Z - 1; z >= 0; --z) if ((rc = bwd_op(s, a, z, j, a.sf))) return rc;
+            for (int32_t z = Z - 1; z >= 0; --z) if ((rc = bwd_op(s, a, z, j, a.sf, a.sf))) return rc;
         }
         for (int32_t z = 0; z < Z; ++z) if ((rc = upd_op(s, a, z, a.sf))) return rc;
         return LPM_OK;
     }
     LPM_HIP(hipEventRecord(s->ev_fork, a.sf));
+    if ((a.mode & 15) == LPM_PIPELINED) {
+        // stage z: forward stream sf[z], backward (data phase) stream sb[z], weight phase and update on the
+        // stage's side stream.  ev_b[j*Z+z]: data phase of B_{z,j} done; ev_w[j*Z+z]: all of B_{z,j} done.
+        for (int32_t z = 0; z < Z; ++z) {
+            LPM_HIP(hipStreamWaitEvent(s->sf[(size_t)z], s->ev_fork, 0));
+            LPM_HIP(hipStreamWaitEvent(s->sb[(size_t)z], s->ev_fork, 0));
+        }
+        for (int32_t j = 0; j < M; ++j) {
+            for (int32_t z = 0; z < Z; ++z) {
+                hipStream_t f = s->sf[(size_t)z];
+                if (j >= W) LPM_HIP(hipStreamWaitEvent(f, s->ev_w[(size_t)(j - W) * Z + z], 0));
+                if (z > 0) LPM_HIP(hipStreamWaitEvent(f, s->ev_f[(size_t)j * Z + z - 1], 0));
+                if ((rc = fwd_op(s, a, z, j, f))) return rc;
+                LPM_HIP(hipEventRecord(s->ev_f[(size_t)j * Z + z], f));
+            }
+            for (int32_t z = Z - 1; z >= 0; --z) {
+                hipStream_t b = s->sb[(size_t)z], w = s->st[(size_t)z]->side;
+                // B_{z,j} follows F_{z,j}: directly for the last stage, through B_{z+1,j} for the others
+                if (z == Z - 1) LPM_HIP(hipStreamWaitEvent(b, s->ev_f[(size_t)j * Z + z], 0));
+                else LPM_HIP(hipStreamWaitEvent(b, s->ev_b[(size_t)j * Z + z + 1], 0));
+                if (W > 2 && j >= 2) LPM_HIP(hipStreamWaitEvent(b, s->ev_w[(size_t)(j - 2) * Z + z], 0));
+                if ((rc = bwd_op(s, a, z, j, b, w))) return rc;
+                if (z > 0) LPM_HIP(hipEventRecord(s->ev_b[(size_t)j * Z + z], b));
+                if (j == M - 1 && (rc = upd_op(s, a, z, w))) return rc;
+                if (j + W < M || j == M - 1 || W > 2) LPM_HIP(hipEventRecord(s->ev_w[(size_t)j * Z + z], w));
+            }
+        }
+        for (int32_t z = 0; z < Z; ++z)      // the weight stream's last event is ordered after all work of its stage
+            LPM_HIP(hipStreamWaitEvent(a.sf, s->ev_w[(size_t)(M - 1) * Z + z], 0));
+        return LPM_OK;
+    }
+    // OVERLAPPED: forward chains on sf, data phases of the backward chains on sb, weight phases and updates on
+    // one weight stream (stage 0's side stream; the data phases stay on sb alone while a graph is captured).
+    // ev_w[j*Z]: everything of micro-batch j done.
+    hipStream_t sw = capturing ? a.sb : s->st[0]->side;
     LPM_HIP(hipStreamWaitEvent(a.sb, s->ev_fork, 0));
     for (int32_t j = 0; j < M; ++j) {
-        for (int32_t z = 0; z < Z; ++z) {
-            if (j >= W) LPM_HIP(hipStreamWaitEvent(a.sf, s->ev_b[(size_t)(j - W) * Z + z], 0));
-            if ((rc = fwd_op(s, a, z, j, a.sf))) return rc;
-        }
-        LPM_HIP(hipEventRecord(s->ev_f[(size_t)j], a.sf));
-        LPM_HIP(hipStreamWaitEvent(a.sb, s->ev_f[(size_t)j], 0));
+        // F_{0,j} after B_{0,j-W}, the last operation of micro-batch j-W; the other stages follow in stream order
+        if (j >= W) LPM_HIP(hipStreamWaitEvent(a.sf, s->ev_w[(size_t)(j - W) * Z], 0));
+        for (int32_t z = 0; z < Z; ++z) if ((rc = fwd_op(s, a, z, j, a.sf))) return rc;
+        LPM_HIP(hipEventRecord(s->ev_f[(size_t)j * Z + Z - 1], a.sf));
+        LPM_HIP(hipStreamWaitEvent(a.sb, s->ev_f[(size_t)j * Z + Z - 1], 0));
+        if (W > 2 && j >= 2 && !capturing) LPM_HIP(hipStreamWaitEvent(a.sb, s->ev_w[(size_t)(j - 2) * Z], 0));
         for (int32_t z = Z - 1; z >= 0; --z) {
-            if ((rc = bwd_op(s, a, z, j, a.sb))) return rc;
-            if (j + W < M) LPM_HIP(hipEventRecord(s->ev_b[(size_t)j * Z + z], a.sb));
-            if (j == M - 1 && (rc = upd_op(s, a, z, a.sb))) return rc;
+            if ((rc = bwd_op(s, a, z, j, a.sb, capturing ? nullptr : sw))) return rc;
+            if (j == M - 1 && (rc = upd_op(s, a, z, sw))) return rc;
         }
+        if (j + W < M || j == M - 1 || W > 2) LPM_HIP(hipEventRecord(s->ev_w[(size_t)j * Z], sw));
     }
-    LPM_HIP(hipEventRecord(s->ev_join, a.sb));
-    LPM_HIP(hipStreamWaitEvent(a.sf, s->ev_join, 0));
+    LPM_HIP(hipStreamWaitEvent(a.sf, s->ev_w[(size_t)(M - 1) * Z], 0));
     return LPM_OK;
 }
 
@@ -170,7 +225,11 @@ extern "C" int32_t lpm_schedule_run(lpm_schedule* s, int32_t mode, const void* x
                                     float lr, float mu, float* loss_out, void* stream_fwd, void* stream_bwd) {
     if (!s || !x_batch || !per_stage) return fail(LPM_EINVAL, "NULL argument");
     const int32_t base = mode & 15;
-    if ((base != LPM_LOCKED && base != LPM_OVERLAPPED) || (mode & ~(15 | LPM_GRAPH))) return fail(LPM_EINVAL, "unknown mode %d", mode);
+    if ((base != LPM_LOCKED && base != LPM_OVERLAPPED && base != LPM_PIPELINED) || (mode & ~(15 | LPM_GRAPH))) return fail(LPM_EINVAL, "unknown mode %d", mode);
+    // Capturing the per-stage streams (many streams forked from and cross-joined inside one capture, plus the
+    // backward pass's edits of the capture frontier) ended in a crash inside the runtime's capture code; the
+    // combination is refused.  Replay is no faster than enqueueing for a multi-branch graph anyway.
+    if (base == LPM_PIPELINED && (mode & LPM_GRAPH)) return fail(LPM_EINVAL, "LPM_PIPELINED cannot be combined with LPM_GRAPH");
     const bool loss = s->st[(size_t)s->Z - 1]->loss;
     if (loss && (!labels || !loss_out)) return fail(LPM_EINVAL, "the last stage holds the loss: labels and loss_out are required");
     if (!loss && !dy_batch) return fail(LPM_EINVAL, "the last stage is not a loss stage: dy_batch is required");
@@ -180,8 +239,8 @@ extern "C" int32_t lpm_schedule_run(lpm_schedule* s, int32_t mode, const void* x
         const lpm_stage_buffers& b = per_stage[z];
         if (!b.params || !b.grads || !b.momentum || !b.fwd_ws || !b.bwd_ws) return fail(LPM_EINVAL, "stage %d: NULL buffer", z);
         for (int32_t w = 0; w < s->window; ++w)
-            if (!b.stash[w] || !b.act_out[w]) return fail(LPM_EINVAL, "stage %d: stash / act_out slot %d is NULL", z, w);
-        if ((z > 0 || dx_wanted) && !b.grad_in) return fail(LPM_EINVAL, "stage %d: grad_in is NULL", z);
+            if (!b.stash[w] || !b.act_out[w] || ((z > 0 || dx_wanted) && !b.grad_in[w]))
+                return fail(LPM_EINVAL, "stage %d: stash / act_out / grad_in slot %d is NULL", z, w);
     }
     RunArgs a{mode, x_batch, labels, dy_batch, per_stage, dx_wanted, lr, mu, loss_out, (hipStream_t)stream_fwd,
               (hipStream_t)stream_bwd};

@@ -132,36 +132,36 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
     }
     s->n_params = off;
     s->lowp_bytes = lowp;
-    s->kws_off = gws;
-    s->wws_off = gws + kws;
-    s->bwd_ws = std::max<size_t>(gws + kws + wws, 256);
+    // backward scratch: two copies of the gradient / dz area (a schedule alternates between them so the weight
+    // phase of one micro-batch may still read its dz while the next data phase writes), then kernel scratch
+    s->gws_bytes = gws;
+    s->kws_off = 2 * gws;
+    s->wws_off = 2 * gws + kws;
+    s->bwd_ws = std::max<size_t>(2 * gws + kws + wws, 256);
     s->fwd_ws = std::max<size_t>(fws, 256);
     *out = s;
     return LPM_OK;
 }
 
 lpm_stage::~lpm_stage() {
-    for (LayerRt& lr : lay) if (lr.ev_dz) (void)hipEventDestroy(lr.ev_dz);
+    if (ev_fork) (void)hipEventDestroy(ev_fork);
     if (ev_join) (void)hipEventDestroy(ev_join);
-    if (side) (void)hipStreamDestroy(side);
 }
 
-// Creates the side stream and events on first use (needs a device; stage creation does not).
+// Borrows the side stream and creates the events on first use (needs a device; stage creation does not).
 int32_t lpm_stage_prepare(lpm_stage* s) {
     if (s->side) return LPM_OK;
     hipStream_t st = nullptr;
-    LPM_HIP(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
-    hipEvent_t ej = nullptr;
+    LPM_HIP(pooled_stream(next_side_stream_index(), &st));
+    hipEvent_t ej = nullptr, ef = nullptr;
     hipError_t e = hipEventCreateWithFlags(&ej, hipEventDisableTiming);
-    for (LayerRt& lr : s->lay)
-        if (e == hipSuccess && has_weights(lr.d)) e = hipEventCreateWithFlags(&lr.ev_dz, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ef, hipEventDisableTiming);
     if (e != hipSuccess) {
-        (void)hipStreamDestroy(st);
         if (ej) (void)hipEventDestroy(ej);
-        for (LayerRt& lr : s->lay) if (lr.ev_dz) { (void)hipEventDestroy(lr.ev_dz); lr.ev_dz = nullptr; }
         return hip_fail(e, "hipEventCreateWithFlags");
     }
     s->ev_join = ej;
+    s->ev_fork = ef;
     s->side = st;
     return LPM_OK;
 }
@@ -289,6 +289,21 @@ extern "C" int32_t lpm_stage_forward(lpm_stage* s, const void* x, void* y, const
 extern "C" int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y, const void* dy, void* dx,
                                       const float* params, const void* lowp, const void* stash, float* grads,
                                       int32_t accumulate, void* bwd_ws, void* stream) {
+    return lpm_stage_backward_on(s, x, y, dy, dx, params, lowp, stash, grads, accumulate, bwd_ws, stream, nullptr, 0);
+}
+
+// B_{z,j} in two phases.  Data phase (on `stream`): everything the next stage down waits for -- epilogue
+// backward, pooling backward, data gradients -- leaving every layer's dz in the backward scratch.  Weight
+// phase: the weight (and fused bias) gradients, which nothing in the same pass reads, enqueued after the
+// data phase on `wstream` behind a single event.  wstream == stream: no event at all (fully serial);
+// wstream == NULL: the stage's own side stream, joined back into `stream` before returning (the
+// contract of lpm_stage_backward); any other stream: the caller orders later work after it.
+// parity (0 / 1) selects the copy of the gradient / dz area in bwd_ws this pass uses.
+// While `stream` is being captured the weight gradients stay on it and are taken out of its dependency
+// frontier instead.
+int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const void* dy, void* dx,
+                              const float* params, const void* lowp, const void* stash, float* grads,
+                              int32_t accumulate, void* bwd_ws, void* stream, void* wstream, int32_t parity) {
     if (!s || !x || !y || !params || !stash || !grads || !bwd_ws) return fail(LPM_EINVAL, "NULL argument");
     if (!s->loss && !dy) return fail(LPM_EINVAL, "dy is NULL for a stage that is not a loss stage");
     if (s->dtype == LPM_BF16 && !lowp) return fail(LPM_EINVAL, "lowp is NULL for a bf16 stage");
@@ -301,15 +316,17 @@ extern "C" int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y
     char* ws = (char*)bwd_ws;
     void* kws = ws + s->kws_off;
     void* wws = ws + s->wws_off;
+    char* gw = ws + (parity ? s->gws_bytes : 0);
     int32_t prc = lpm_stage_prepare(s);
     if (prc) return prc;
-    bool forked = false;
     // While the caller's stream is being captured into a graph no second stream is involved: the weight
     // gradient nodes are taken out of the stream's dependency frontier instead (they depend on what came
     // before them and on the previous weight gradient, nothing later depends on them until the join).
     hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
     LPM_HIP(hipStreamIsCapturing(st, &cap));
-    const bool use_side = cap == hipStreamCaptureStatusNone;
+    const bool deferred = cap == hipStreamCaptureStatusNone;
+    struct WgradJob { const LayerRt* lr; const void* xin; const void* dz; float* wdb; const float* sc; };
+    std::vector<WgradJob> jobs;            // eager: the weight phase, in layer order (last layer first)
     std::vector<hipGraphNode_t> wtail;     // capture: frontier left by the last weight gradient
     auto frontier = [&](std::vector<hipGraphNode_t>& out) -> hipError_t {
         hipStreamCaptureStatus stt;
@@ -325,7 +342,7 @@ extern "C" int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y
     std::vector<char> have((size_t)(last - first + 1), 0);
     auto gi = [&](int32_t t) { return (size_t)(t - (first - 1)); };
     for (int32_t t = first; t < last; ++t)
-        if (s->T(t).loc == LOC_STASH) G[gi(t)] = ws + s->T(t).g_off;
+        if (s->T(t).loc == LOC_STASH) G[gi(t)] = gw + s->T(t).g_off;
     G[gi(first - 1)] = dx;
     int32_t top = last - 1;
     if (s->loss) {
@@ -352,7 +369,7 @@ extern "C" int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y
                 const bool bias_in_wgrad = dbias && wgrad_fuses_bias(s->dtype, lr.g);
                 const void* dz = g;
                 if (lr.fused_in) {
-                    dz = ws + lr.dz_off;           // written by the consumer's backward kernel
+                    dz = gw + lr.dz_off;           // written by the consumer's backward kernel
                 } else {
                     void* gadd = nullptr;
                     int gadd_acc = 0;
@@ -364,9 +381,9 @@ extern "C" int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y
                     const bool need_dz = relu || sc;
                     if (need_dz || gadd || (dbias && !bias_in_wgrad)) {
                         LPM_HIP(launch_epilogue_bwd(s->dtype, lr.g.rows_out(), l.cout, g, relu ? yout : nullptr, sc,
-                                                    need_dz ? (void*)(ws + lr.dz_off) : nullptr, gadd, gadd_acc,
+                                                    need_dz ? (void*)(gw + lr.dz_off) : nullptr, gadd, gadd_acc,
                                                     bias_in_wgrad ? nullptr : dbias, acc, kws, st));
-                        if (need_dz) dz = ws + lr.dz_off;
+                        if (need_dz) dz = gw + lr.dz_off;
                     }
                 }
                 float* wdb = bias_in_wgrad ? dbias : nullptr;
@@ -379,7 +396,7 @@ extern "C" int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y
                 if (want) {
                     if (l.src >= first && s->Ly(l.src).fused_in) {
                         const LayerRt& pr = s->Ly(l.src);
-                        gsrc = ws + pr.dz_off;
+                        gsrc = gw + pr.dz_off;
                         gmask = (pr.d.flags & LPM_RELU) ? tptr(s, l.src, x, y, stash) : nullptr;
                         gmscale = pr.s_off != NO ? params + pr.s_off : nullptr;
                     } else {
@@ -389,12 +406,8 @@ extern "C" int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y
                     have[gi(l.src)] = 1;
                 }
                 const void* xin = tptr(s, l.src, x, y, stash);
-                // weight gradient on the side stream, once dz (and everything before it) is ready
-                if (use_side) {
-                    LPM_HIP(hipEventRecord(lr.ev_dz, st));
-                    LPM_HIP(hipStreamWaitEvent(s->side, lr.ev_dz, 0));
-                    LPM_HIP(launch_conv_wgrad(s->dtype, lr.g, xin, dz, grads + lr.w_off, wdb, sc, acc, wws, s->side));
-                    forked = true;
+                if (deferred) {
+                    jobs.push_back(WgradJob{&lr, xin, dz, wdb, sc});
                 } else {
                     std::vector<hipGraphNode_t> before;
                     LPM_HIP(frontier(before));
@@ -422,7 +435,7 @@ extern "C" int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y
                     const float* gmscale = nullptr;
                     if (l.src >= first && s->Ly(l.src).fused_in) {
                         const LayerRt& pr = s->Ly(l.src);
-                        gsrc = ws + pr.dz_off;
+                        gsrc = gw + pr.dz_off;
                         gsrc_acc = 0;
                         gmask = (pr.d.flags & LPM_RELU) ? tptr(s, l.src, x, y, stash) : nullptr;
                         gmscale = pr.s_off != NO ? params + pr.s_off : nullptr;
@@ -441,9 +454,18 @@ extern "C" int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y
     }
     if (!wtail.empty())
         LPM_HIP(hipStreamUpdateCaptureDependencies(st, wtail.data(), wtail.size(), hipStreamAddCaptureDependencies));
-    if (forked) {      // join: the caller's stream is ordered after every weight gradient
-        LPM_HIP(hipEventRecord(s->ev_join, s->side));
-        LPM_HIP(hipStreamWaitEvent(st, s->ev_join, 0));
+    if (!jobs.empty() || (wstream && wstream != stream && deferred)) {
+        hipStream_t wst = wstream ? (hipStream_t)wstream : s->side;
+        if (wst != st) {
+            LPM_HIP(hipEventRecord(s->ev_fork, st));
+            LPM_HIP(hipStreamWaitEvent(wst, s->ev_fork, 0));
+        }
+        for (const WgradJob& j : jobs)
+            LPM_HIP(launch_conv_wgrad(s->dtype, j.lr->g, j.xin, j.dz, grads + j.lr->w_off, j.wdb, j.sc, acc, wws, wst));
+        if (!wstream) {      // join: the caller's stream is ordered after every weight gradient
+            LPM_HIP(hipEventRecord(s->ev_join, s->side));
+            LPM_HIP(hipStreamWaitEvent(st, s->ev_join, 0));
+        }
     }
     return LPM_OK;
 }

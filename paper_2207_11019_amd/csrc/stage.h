@@ -25,7 +25,6 @@ struct LayerRt {
     size_t lowp_w_off = NO, lowp_wt_off = NO;    // byte offsets into lowp
     size_t dz_off = NO;                          // byte offset of its pre-activation gradient in the backward scratch
     bool fused_in = false;                       // its consumer's backward kernel writes dz directly (mask and scale fused)
-    hipEvent_t ev_dz = nullptr;                  // dz of this layer is ready (backward, main stream)
 };
 
 }  // namespace lpm
@@ -43,10 +42,11 @@ struct lpm_stage {
     size_t n_trainable = 0, n_params = 0;   // floats
     size_t lowp_bytes = 0, stash_bytes = 0, fwd_ws = 0, bwd_ws = 0;
     size_t dlogits_off = lpm::NO, kws_off = lpm::NO, wws_off = lpm::NO;   // stash / bwd-scratch offsets
+    size_t gws_bytes = 0;             // size of one copy of the gradient / dz area at the head of the backward scratch
     // Weight gradients are off the critical path of B (nothing in the same pass reads them), so they run on
-    // a side stream owned by the stage, forked from and joined back into the caller's stream.
+    // a side stream (borrowed from the library's pool), forked from and joined back into the caller's stream.
     hipStream_t side = nullptr;
-    hipEvent_t ev_join = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     ~lpm_stage();
 
     lpm::TensorRt& T(int32_t t) { return ten[(size_t)(t - (first - 1))]; }
@@ -55,3 +55,7 @@ struct lpm_stage {
     const lpm::LayerRt& Ly(int32_t i) const { return lay[(size_t)(i - first)]; }
 };
 
+// B_{z,j} with the weight phase on a stream of the caller's choice (see stage.cpp).
+int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const void* dy, void* dx,
+                              const float* params, const void* lowp, const void* stash, float* grads,
+                              int32_t accumulate, void* bwd_ws, void* stream, void* wstream, int32_t parity);

@@ -78,7 +78,7 @@ def compare(net, layers, starts, M, dtype, o, dx_wanted=False, window=2, report=
                 got = net.read_act_out(z, slot)
             errs["act%d" % t] = rel_err(got, stash[t])
         if backward and (z > 0 or dx_wanted):
-            errs["gin%d" % z] = rel_err(net.read_grad_in(z), ref["gin"][(z, j)])
+            errs["gin%d" % z] = rel_err(net.read_grad_in(z, slot), ref["gin"][(z, j)])
     bad = {k: e for k, e in errs.items() if not (e <= tol)}
     if report is not None:
         report.update(errs)
@@ -167,7 +167,7 @@ def stage_backward_isolated(lpm, layers, starts, m, batch_total, dtype, seed, dx
         xin = xd if z == 0 else net.bufs[z - 1]["act_out"][0]
         dyd = None if loss_stage else lpm.pack_act(dy, dtype)
         print("isolated backward stage", z, "layers", s0, s1, flush=True)
-        net.stages[z].backward(xin, b["act_out"][0], dyd, b["grad_in"] if want else None, b["params"], b["lowp"],
+        net.stages[z].backward(xin, b["act_out"][0], dyd, b["grad_in"][0] if want else None, b["params"], b["lowp"],
                                b["stash"][0], b["grads"], 0, b["bwd_ws"], None)
         net.torch.cuda.synchronize()
         gg = net.read_grads()

@@ -34,7 +34,7 @@ CASES = [
 
 
 @pytest.mark.parametrize("name,builder,batch,M,Z,dtype", CASES, ids=[c[0] for c in CASES])
-@pytest.mark.parametrize("mode", [0, 1, 17], ids=["locked", "overlapped", "overlapped_graph"])
+@pytest.mark.parametrize("mode", [0, 1, 17, 2], ids=["locked", "overlapped", "overlapped_graph", "pipelined"])
 def test_small_networks(lpm, name, builder, batch, M, Z, dtype, mode):
     layers = builder()
     starts = _starts(layers, Z)
@@ -42,6 +42,17 @@ def test_small_networks(lpm, name, builder, batch, M, Z, dtype, mode):
     o = oracle_step(layers, starts, batch, M, dtype == 1, seed=101, lr=0.05, mu=0.9)
     net = gpu_step(lpm, layers, starts, batch, M, dtype, o, 0.05, 0.9, mode)
     compare(net, layers, starts, M, dtype, o)
+
+
+def test_pipelined_graph_is_refused(lpm):
+    """Stage-parallel streams are not captured into a graph: the call fails before anything is enqueued."""
+    layers = wl.tiny_lenet()
+    starts = _starts(layers, 2)
+    import torch
+    net = lpm.Net(layers, starts, 2, 2, 0)
+    x = torch.zeros(4096, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(Exception, match="LPM_GRAPH"):
+        net.step(x, None, None, 0.1, 0.0, lpm.PIPELINED | lpm.GRAPH)
 
 
 def test_lenet_config_f32(lpm):
@@ -52,16 +63,18 @@ def test_lenet_config_f32(lpm):
     assert starts == [0, 4, 8]
     o = oracle_step(layers, starts, 32, 4, False, seed=7, lr=0.01, mu=0.9)
     nets = {}
-    for mode in (lpm.LOCKED, lpm.OVERLAPPED):
+    for mode in (lpm.LOCKED, lpm.OVERLAPPED, lpm.PIPELINED):
         print("lenet mode", mode, flush=True)
         nets[mode] = gpu_step(lpm, layers, starts, 32, 4, 0, o, 0.01, 0.9, mode)
         compare(nets[mode], layers, starts, 4, 0, o)
-    # the two schedules are bitwise identical
-    a, b = nets[lpm.LOCKED].read_params(), nets[lpm.OVERLAPPED].read_params()
-    for i in a:
-        for k in a[i]:
-            np.testing.assert_array_equal(a[i][k], b[i][k])
-    assert nets[lpm.LOCKED].loss_value() == nets[lpm.OVERLAPPED].loss_value()
+    # the schedules are bitwise identical
+    a = nets[lpm.LOCKED].read_params()
+    for mode in (lpm.OVERLAPPED, lpm.PIPELINED):
+        b = nets[mode].read_params()
+        for i in a:
+            for k in a[i]:
+                np.testing.assert_array_equal(a[i][k], b[i][k])
+        assert nets[lpm.LOCKED].loss_value() == nets[mode].loss_value()
 
 
 def test_two_steps_with_momentum(lpm):
@@ -96,14 +109,16 @@ def test_vgg16_cifar_config_bf16(lpm):
     print("oracle done", flush=True)
     rep = {}
     nets = {}
-    for mode in (lpm.LOCKED, lpm.OVERLAPPED | lpm.GRAPH):
+    for mode in (lpm.LOCKED, lpm.OVERLAPPED | lpm.GRAPH, lpm.PIPELINED):
         nets[mode] = gpu_step(lpm, layers, starts, 128, 8, 1, o, 0.01, 0.9, mode)
         compare(nets[mode], layers, starts, 8, 1, o, report=rep, backward=False)
         print("mode", mode, "worst", sorted(rep.items(), key=lambda kv: -kv[1])[:5], flush=True)
-    a, b = nets[lpm.LOCKED].read_params(), nets[lpm.OVERLAPPED | lpm.GRAPH].read_params()
-    for i in a:
-        for k in a[i]:
-            np.testing.assert_array_equal(a[i][k], b[i][k])
+    a = nets[lpm.LOCKED].read_params()
+    for mode in nets:
+        b = nets[mode].read_params()
+        for i in a:
+            for k in a[i]:
+                np.testing.assert_array_equal(a[i][k], b[i][k])
     # end-to-end gradients: sanity only (2-norm), the element-wise bar is applied per stage below
     g = nets[lpm.LOCKED].read_grads()
     worst = max(l2_err(g[i]["W"], o["ref"]["grads"][i]["W"]) for i in g)
