@@ -63,6 +63,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-layer-table", action="store_true", help="skip the per-contraction timing table")
     ap.add_argument("--eager", action="store_true", help="enqueue the step kernel by kernel instead of replaying a graph")
+    ap.add_argument("--only", choices=["locked", "overlapped", "pipelined"], default=None,
+                    help="profiling aid: run just this schedule (eager enqueue) for --steps steps and print its time")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); got --gpus %d" % args.gpus,
@@ -108,6 +110,12 @@ def main():
         run(mode, steps)
         torch.cuda.synchronize()
         return time.perf_counter() - t0
+
+    if args.only:
+        mode = {"locked": lpm.LOCKED, "overlapped": lpm.OVERLAPPED, "pipelined": lpm.PIPELINED}[args.only]
+        t = timed(mode, args.steps)
+        print(json.dumps({"workload": args.workload, "schedule": args.only, "ms_per_step": round(t / args.steps * 1e3, 4)}))
+        return 0
 
     # the step is timed both enqueued kernel by kernel and replayed as a captured graph; the faster one is reported
     res = {}

@@ -12,6 +12,10 @@
 // (lane % 32); lane holds D[(i/4)*8 + (lane/32)*4 + i%4][lane % 32] in accumulator element i.
 #include "lpm_internal.h"
 #include "elem.h"
+#include <algorithm>
+#ifdef LPM_TUNE
+#include <cstdlib>
+#endif
 
 namespace lpm {
 
@@ -278,25 +282,32 @@ __global__ void __launch_bounds__(256) splitk_epilogue(const float* __restrict__
 // --------------------------------------------------------------------------------------------------
 struct IgemmPlan { int big; int bk; int splits; int kt_total; int kt_per; };
 
-// ci: channel count of the gathered tensor (a K tile must not straddle a filter tap)
+// ci: channel count of the gathered tensor (a K tile must not straddle a filter tap).
+// Measured on MI355X over the layer shapes of the CIFAR, ResNet and 224x224 VGG workloads: 64x64 tiles with
+// 64-deep K tiles (four blocks per CU) are never behind the other variants by more than a few per cent, and
+// splitting K pays only while the tiles alone leave CUs idle and the K loop is long -- every split costs a
+// second kernel that sums fp32 partials.
 static IgemmPlan plan_igemm(int64_t M, int N, int Ktot, int ci) {
     IgemmPlan pl{};
-    const int64_t b128 = ((M + 127) / 128) * ((N + 127) / 128);
-    pl.big = b128 >= 160;
-    if (pl.big) pl.bk = (ci % 64 == 0) ? 64 : 32;
-    else pl.bk = (ci % 128 == 0) ? 128 : (ci % 64 == 0) ? 64 : 32;
+    pl.big = 0;
+    pl.bk = (ci % 64 == 0) ? 64 : 32;
     pl.kt_total = Ktot / pl.bk;
-    pl.splits = 1;
-    if (!pl.big) {
-        const int64_t b64 = ((M + 63) / 64) * ((N + 63) / 64);
-        int s = (int)((384 + b64 - 1) / b64);
-        const int smax = (Ktot / 32) / 8;          // at least 256 of K per split
-        if (s > smax) s = smax;
-        if (s > pl.kt_total) s = pl.kt_total;
-        if (s > 32) s = 32;
-        if (s < 1) s = 1;
-        pl.splits = s;
-    }
+    const int64_t tiles = ((M + 63) / 64) * ((N + 63) / 64);
+    const int kt64 = Ktot / 64;                                   // K depth in units of 64
+    int s = std::max(1, (kt64 + 7) / 14);                         // about 14 K tiles per block
+    // no more blocks than fill the chip once -- except for a single row of tiles (a small-batch FC layer), which
+    // only streams weights and needs many blocks in flight to cover the memory latency
+    const int64_t cap = (M <= 64 ? 1024 : 320) / tiles;
+    s = (int)std::min<int64_t>(s, std::max<int64_t>(1, cap));
+    s = std::min(s, pl.kt_total);
+    pl.splits = std::max(1, s);
+#ifdef LPM_TUNE      // measurement builds only: override the plan from the environment
+    if (const char* e = getenv("LPM_T_BIG")) { pl.big = atoi(e); }
+    if (const char* e = getenv("LPM_T_BK")) { if (ci % atoi(e) == 0) pl.bk = atoi(e); }
+    if (pl.big && pl.bk > 64) pl.bk = 64;
+    pl.kt_total = Ktot / pl.bk;
+    if (const char* e = getenv("LPM_T_SPLITS")) { pl.splits = std::max(1, std::min(atoi(e), pl.kt_total)); }
+#endif
     pl.kt_per = (pl.kt_total + pl.splits - 1) / pl.splits;
     pl.splits = (pl.kt_total + pl.kt_per - 1) / pl.kt_per;
     return pl;
@@ -304,14 +315,20 @@ static IgemmPlan plan_igemm(int64_t M, int N, int Ktot, int ci) {
 
 template <int MODE>
 static void launch_igemm_cfg(const IgemmPlan& pl, const IgemmArgs& a, hipStream_t st) {
+#ifdef LPM_TUNE
     if (pl.big) {
         const dim3 grid((unsigned)(((a.M + 127) / 128) * ((a.N + 127) / 128)), 1, pl.splits);
         if (pl.bk == 64) hipLaunchKernelGGL((igemm_kernel<128, 128, 64, 2, 2, MODE>), grid, dim3(256), 0, st, a);
         else hipLaunchKernelGGL((igemm_kernel<128, 128, 32, 2, 2, MODE>), grid, dim3(256), 0, st, a);
-    } else {
+    } else
+#endif
+    {
         const dim3 grid((unsigned)(((a.M + 63) / 64) * ((a.N + 63) / 64)), 1, pl.splits);
+#ifdef LPM_TUNE
         if (pl.bk == 128) hipLaunchKernelGGL((igemm_kernel<64, 64, 128, 2, 2, MODE>), grid, dim3(256), 0, st, a);
-        else if (pl.bk == 64) hipLaunchKernelGGL((igemm_kernel<64, 64, 64, 2, 2, MODE>), grid, dim3(256), 0, st, a);
+        else
+#endif
+        if (pl.bk == 64) hipLaunchKernelGGL((igemm_kernel<64, 64, 64, 2, 2, MODE>), grid, dim3(256), 0, st, a);
         else hipLaunchKernelGGL((igemm_kernel<64, 64, 32, 2, 2, MODE>), grid, dim3(256), 0, st, a);
     }
 }
@@ -596,24 +613,38 @@ __global__ void __launch_bounds__(256) wgrad_reduce(const float* __restrict__ pa
 
 struct WgradPlan { int big; int bk; int splits; int rt_total; int rt_per; int co_tiles, ci_tiles; };
 
+// Measured on the same shapes: 128x128 tiles win once the contraction is large (about 6e9 multiply-adds), the
+// 64x64 tile otherwise, with 128-pixel tiles when there are at least 1024 pixels; the pixel range is split
+// until one wave of blocks (two per CU) is full, keeping at least four pixel tiles per block.
 static WgradPlan plan_wgrad(const ConvGeom& g) {
     WgradPlan pl{};
     const int64_t R = g.rows_out();
-    pl.big = (g.Cout >= 128 && g.Cin >= 128 && R >= 512);
-    pl.bk = pl.big ? 64 : (R > 64 ? 128 : 64);
+    const double macs = (double)R * g.Cout * g.K();
+    pl.big = (g.Cout >= 128 && g.Cin >= 128 && macs >= 6e9);
+    pl.bk = pl.big ? 64 : (R >= 1024 ? 128 : 64);
     pl.rt_total = (int)((R + pl.bk - 1) / pl.bk);
     const int t = pl.big ? 128 : 64;
     pl.co_tiles = (g.Cout + t - 1) / t;
     pl.ci_tiles = (g.Cin + t - 1) / t;
     const int64_t tiles = (int64_t)pl.co_tiles * pl.ci_tiles * g.Kh * g.Kw;
-    int s = (int)((512 + tiles - 1) / tiles);
-    const int smax = (int)(R / 256);               // at least 256 pixels per split
-    if (s > smax) s = smax;
+    int s = (int)std::min<int64_t>(512 / std::max<int64_t>(tiles, 1), std::max(1, pl.rt_total / 4));
     if (s > 64) s = 64;
     // the partials must stay modest for very large weight tensors
     const int64_t wbytes = (int64_t)g.Cout * g.K() * 4;
     while (s > 1 && wbytes * s > (256ll << 20)) --s;
     if (s < 1) s = 1;
+#ifdef LPM_TUNE
+    if (const char* e = getenv("LPM_T_BIG")) {
+        pl.big = atoi(e);
+        pl.bk = pl.big ? 64 : (R > 64 ? 128 : 64);
+        if (const char* b = getenv("LPM_T_BK")) if (!pl.big) pl.bk = atoi(b) >= 128 ? 128 : 64;
+        pl.rt_total = (int)((R + pl.bk - 1) / pl.bk);
+        const int t2 = pl.big ? 128 : 64;
+        pl.co_tiles = (g.Cout + t2 - 1) / t2;
+        pl.ci_tiles = (g.Cin + t2 - 1) / t2;
+    }
+    if (const char* e = getenv("LPM_T_SPLITS")) s = std::max(1, std::min(atoi(e), pl.rt_total));
+#endif
     pl.rt_per = (pl.rt_total + s - 1) / s;
     pl.splits = (pl.rt_total + pl.rt_per - 1) / pl.rt_per;
     return pl;

@@ -8,7 +8,8 @@
 //               flight, i.e. F_{z,j+window} starts after B_{z,j} ("B_{0,0} finishes before F_{0,2}").
 //   PIPELINED   the same dependency set, but every stage owns a forward and a backward stream (the
 //               one-device-per-sub-module layout of the method's figure, with streams standing in for
-//               devices): F_{z,j+1} also overlaps F_{z+1,j}, and B_{z,j} overlaps B_{z+1,j+1}.
+//               devices): F_{z,j+1} also overlaps F_{z+1,j}, and B_{z,j} overlaps B_{z+1,j+1}.  Each stage
+//               is enqueued by a host thread of its own (launching is what bounds small micro-batches).
 // Every buffer that belongs to a micro-batch (stash, stage output, input gradient) lives in slot
 // j % window.  Micro-batch j + window starts at stage 0 only after B_{0,j}, the last operation of
 // micro-batch j, so a slot is never rewritten while an operation of its previous owner is pending.
@@ -16,8 +17,15 @@
 // updated once, right after its last backward, so both modes produce bit-identical results.
 #include "stage.h"
 
+#include <algorithm>
+#include <atomic>
+#include <condition_variable>
 #include <cstring>
+#include <memory>
+#include <mutex>
 #include <new>
+#include <string>
+#include <thread>
 
 using namespace lpm;
 
@@ -40,6 +48,24 @@ struct lpm_schedule {
     hipEvent_t ev_fork = nullptr;
     std::vector<hipStream_t> sf, sb;     // PIPELINED: per-stage forward / backward streams (borrowed from the pool)
     std::vector<GraphEntry> graphs;
+
+    // PIPELINED: one enqueue thread per stage, started at the first such run.  An event may only be waited
+    // on once its record has been enqueued, so each record is published to the other threads by storing the
+    // run's epoch in rec_*[j*Z+z]; a thread spins on that before it enqueues the matching wait.
+    int device = 0;
+    std::vector<std::thread> workers;
+    std::mutex mu;
+    std::condition_variable cv_go, cv_done;
+    uint64_t epoch = 0;
+    int pending = 0;
+    bool quit = false;
+    const void* job = nullptr;             // RunArgs of the current run
+    void* job_fn = nullptr;                // what every participating worker runs (RoleFn)
+    int32_t job_roles = 0;                 // workers 0..job_roles-1 take part
+    std::atomic<bool> abort{false};
+    std::vector<int32_t> wrc;              // per worker: status and error text of the current run
+    std::vector<std::string> werr;
+    std::unique_ptr<std::atomic<uint64_t>[]> rec_f, rec_b, rec_w;
 };
 
 static void destroy_events(lpm_schedule* s) {
@@ -82,7 +108,11 @@ extern "C" int32_t lpm_schedule_create(lpm_stage* const* stages, int32_t Z, int3
     s->ev_w.assign((size_t)n_microbatch * Z, nullptr);
     s->sf.assign((size_t)Z, nullptr);
     s->sb.assign((size_t)Z, nullptr);
-    hipError_t e = hipSuccess;
+    s->rec_f.reset(new std::atomic<uint64_t>[(size_t)n_microbatch * Z]);
+    s->rec_b.reset(new std::atomic<uint64_t>[(size_t)n_microbatch * Z]);
+    s->rec_w.reset(new std::atomic<uint64_t>[(size_t)n_microbatch * Z]);
+    for (size_t i = 0; i < (size_t)n_microbatch * Z; ++i) { s->rec_f[i].store(0); s->rec_b[i].store(0); s->rec_w[i].store(0); }
+    hipError_t e = hipGetDevice(&s->device);
     for (int32_t z = 0; z < Z; ++z) {
         if (e == hipSuccess) e = pooled_stream((2 * z) % LPM_POOL_SCHEDULE_STREAMS, &s->sf[(size_t)z]);
         if (e == hipSuccess) e = pooled_stream((2 * z + 1) % LPM_POOL_SCHEDULE_STREAMS, &s->sb[(size_t)z]);
@@ -102,6 +132,14 @@ extern "C" int32_t lpm_schedule_create(lpm_stage* const* stages, int32_t Z, int3
 
 extern "C" int32_t lpm_schedule_destroy(lpm_schedule* s) {
     if (!s) return LPM_OK;
+    if (!s->workers.empty()) {
+        {
+            std::lock_guard<std::mutex> lk(s->mu);
+            s->quit = true;
+        }
+        s->cv_go.notify_all();
+        for (std::thread& t : s->workers) t.join();
+    }
     destroy_events(s);
     delete s;
     return LPM_OK;
@@ -128,7 +166,8 @@ int32_t fwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStrea
 }
 
 // wst: stream of the weight phase (see lpm_stage_backward_on)
-int32_t bwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStream_t st, hipStream_t wst) {
+int32_t bwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStream_t st, hipStream_t wst,
+               int32_t phases = LPM_PHASE_DATA | LPM_PHASE_WEIGHTS) {
     lpm_stage* sg = s->st[(size_t)z];
     const int32_t slot = j % s->window;
     const lpm_stage_buffers& b = a.bufs[z];
@@ -139,12 +178,195 @@ int32_t bwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStrea
     else if (!sg->loss) dy = (const char*)a.dy_batch + (size_t)j * sg->T(sg->t_out).bytes;
     void* dx = (z > 0 || a.dx_wanted) ? b.grad_in[slot] : nullptr;
     return lpm_stage_backward_on(sg, in, b.act_out[slot], dy, dx, b.params, b.lowp, b.stash[slot], b.grads, j > 0,
-                                 b.bwd_ws, st, wst, j & 1);
+                                 b.bwd_ws, st, wst, j & 1, phases);
 }
 
 int32_t upd_op(lpm_schedule* s, const RunArgs& a, int32_t z, hipStream_t st) {
     const lpm_stage_buffers& b = a.bufs[z];
     return lpm_stage_update(s->st[(size_t)z], b.params, b.lowp, b.grads, b.momentum, a.lr, a.mu, 0, st);
+}
+
+// ---- enqueue threads.  Launching, not the GPU, bounds a step of small micro-batches, so the decoupled
+// schedules are enqueued by several host threads, each feeding streams of its own.  An event may only be
+// waited on once its record has been enqueued: every record another thread waits for is published by storing
+// the run's epoch in a rec_* slot, and the waiting thread spins on that slot before it enqueues the wait.
+// Each thread's sequence is the restriction of one topological order of the dependency graph to its
+// streams, so no thread waits for a record that can never be enqueued.
+
+int32_t await_record(lpm_schedule* s, const std::atomic<uint64_t>& rec, uint64_t epoch) {
+    unsigned spins = 0;
+    while (rec.load(std::memory_order_acquire) != epoch) {
+        if (s->abort.load(std::memory_order_relaxed)) return fail(LPM_EHIP, "another enqueue thread failed");
+        if (++spins > 2000) std::this_thread::yield();
+    }
+    return LPM_OK;
+}
+inline void publish(std::atomic<uint64_t>& rec, uint64_t epoch) { rec.store(epoch, std::memory_order_release); }
+
+// PIPELINED, worker z: stage z on sf[z] (forward), sb[z] (data phase of backward) and the stage's side stream
+// (weight phase, update).  ev_f / ev_b: F_{z,j} / data phase of B_{z,j} done; ev_w: all of B_{z,j} done.
+// Order: F_{z,0..W-1}, then B_{z,j}, F_{z,j+W} for j = 0..M-1 -- the restriction to stage z of
+// "B_{Z-1,j}..B_{0,j}, F_{0,j+W}..F_{Z-1,j+W}".
+int32_t pipelined_role(lpm_schedule* s, const RunArgs& a, int32_t z, uint64_t epoch) {
+    const int32_t Z = s->Z, M = s->M, W = s->window;
+    hipStream_t f = s->sf[(size_t)z], b = s->sb[(size_t)z], w = s->st[(size_t)z]->side;
+    int32_t rc;
+    LPM_HIP(hipStreamWaitEvent(f, s->ev_fork, 0));
+    LPM_HIP(hipStreamWaitEvent(b, s->ev_fork, 0));
+    auto F = [&](int32_t j) -> int32_t {
+        if (j >= W) LPM_HIP(hipStreamWaitEvent(f, s->ev_w[(size_t)(j - W) * Z + z], 0));
+        if (z > 0) {
+            const size_t i = (size_t)j * Z + z - 1;
+            if ((rc = await_record(s, s->rec_f[i], epoch))) return rc;
+            LPM_HIP(hipStreamWaitEvent(f, s->ev_f[i], 0));
+        }
+        if ((rc = fwd_op(s, a, z, j, f))) return rc;
+        LPM_HIP(hipEventRecord(s->ev_f[(size_t)j * Z + z], f));
+        publish(s->rec_f[(size_t)j * Z + z], epoch);
+        return LPM_OK;
+    };
+    auto B = [&](int32_t j) -> int32_t {
+        const size_t me = (size_t)j * Z + z;
+        // B_{z,j} follows F_{z,j}: directly for the last stage, through B_{z+1,j} for the others
+        if (z == Z - 1) {
+            LPM_HIP(hipStreamWaitEvent(b, s->ev_f[me], 0));
+        } else {
+            if ((rc = await_record(s, s->rec_b[me + 1], epoch))) return rc;
+            LPM_HIP(hipStreamWaitEvent(b, s->ev_b[me + 1], 0));
+        }
+        if (W > 2 && j >= 2) LPM_HIP(hipStreamWaitEvent(b, s->ev_w[(size_t)(j - 2) * Z + z], 0));
+        if ((rc = bwd_op(s, a, z, j, b, w, LPM_PHASE_DATA))) return rc;
+        LPM_HIP(hipEventRecord(s->ev_b[me], b));
+        publish(s->rec_b[me], epoch);
+        LPM_HIP(hipStreamWaitEvent(w, s->ev_b[me], 0));
+        if ((rc = bwd_op(s, a, z, j, b, w, LPM_PHASE_WEIGHTS))) return rc;
+        if (j == M - 1 && (rc = upd_op(s, a, z, w))) return rc;
+        LPM_HIP(hipEventRecord(s->ev_w[me], w));
+        return LPM_OK;
+    };
+    for (int32_t j = 0; j < W && j < M; ++j) if ((rc = F(j))) return rc;
+    for (int32_t j = 0; j < M; ++j) {
+        if ((rc = B(j))) return rc;
+        if (j + W < M && (rc = F(j + W))) return rc;
+    }
+    publish(s->rec_w[(size_t)(M - 1) * Z + z], epoch);
+    return LPM_OK;
+}
+
+// OVERLAPPED, three workers: 0 enqueues the forward chains on sf, 1 the data phases of the backward chains
+// on sb, 2 the weight phases and the updates on the weight stream (stage 0's side stream).
+// ev_f[j*Z+Z-1]: forward chain j done; ev_b[j*Z+z]: data phase of B_{z,j} done; ev_w[j*Z]: micro-batch j done.
+int32_t overlapped_role(lpm_schedule* s, const RunArgs& a, int32_t role, uint64_t epoch) {
+    const int32_t Z = s->Z, M = s->M, W = s->window;
+    hipStream_t sw = s->st[0]->side;
+    int32_t rc;
+    if (role == 0) {
+        for (int32_t j = 0; j < M; ++j) {
+            // F_{0,j} after B_{0,j-W}, the last operation of micro-batch j-W; the other stages follow in stream order
+            if (j >= W) {
+                const size_t i = (size_t)(j - W) * Z;
+                if ((rc = await_record(s, s->rec_w[i], epoch))) return rc;
+                LPM_HIP(hipStreamWaitEvent(a.sf, s->ev_w[i], 0));
+            }
+            for (int32_t z = 0; z < Z; ++z) if ((rc = fwd_op(s, a, z, j, a.sf))) return rc;
+            LPM_HIP(hipEventRecord(s->ev_f[(size_t)j * Z + Z - 1], a.sf));
+            publish(s->rec_f[(size_t)j * Z + Z - 1], epoch);
+        }
+    } else if (role == 1) {
+        LPM_HIP(hipStreamWaitEvent(a.sb, s->ev_fork, 0));
+        for (int32_t j = 0; j < M; ++j) {
+            const size_t i = (size_t)j * Z + Z - 1;
+            if ((rc = await_record(s, s->rec_f[i], epoch))) return rc;
+            LPM_HIP(hipStreamWaitEvent(a.sb, s->ev_f[i], 0));
+            if (W > 2 && j >= 2) {
+                if ((rc = await_record(s, s->rec_w[(size_t)(j - 2) * Z], epoch))) return rc;
+                LPM_HIP(hipStreamWaitEvent(a.sb, s->ev_w[(size_t)(j - 2) * Z], 0));
+            }
+            for (int32_t z = Z - 1; z >= 0; --z) {
+                if ((rc = bwd_op(s, a, z, j, a.sb, sw, LPM_PHASE_DATA))) return rc;
+                LPM_HIP(hipEventRecord(s->ev_b[(size_t)j * Z + z], a.sb));
+                publish(s->rec_b[(size_t)j * Z + z], epoch);
+            }
+        }
+    } else {
+        for (int32_t j = 0; j < M; ++j) {
+            for (int32_t z = Z - 1; z >= 0; --z) {
+                const size_t i = (size_t)j * Z + z;
+                if ((rc = await_record(s, s->rec_b[i], epoch))) return rc;
+                LPM_HIP(hipStreamWaitEvent(sw, s->ev_b[i], 0));
+                if ((rc = bwd_op(s, a, z, j, a.sb, sw, LPM_PHASE_WEIGHTS))) return rc;
+                if (j == M - 1 && (rc = upd_op(s, a, z, sw))) return rc;
+            }
+            LPM_HIP(hipEventRecord(s->ev_w[(size_t)j * Z], sw));
+            publish(s->rec_w[(size_t)j * Z], epoch);
+        }
+    }
+    return LPM_OK;
+}
+
+typedef int32_t (*RoleFn)(lpm_schedule*, const RunArgs&, int32_t, uint64_t);
+
+void enqueue_worker(lpm_schedule* s, int32_t idx) {
+    (void)hipSetDevice(s->device);
+    uint64_t seen = 0;
+    for (;;) {
+        RunArgs a;
+        RoleFn fn;
+        bool mine;
+        {
+            std::unique_lock<std::mutex> lk(s->mu);
+            s->cv_go.wait(lk, [&] { return s->quit || s->epoch != seen; });
+            if (s->quit) return;
+            seen = s->epoch;
+            a = *(const RunArgs*)s->job;
+            fn = (RoleFn)s->job_fn;
+            mine = idx < s->job_roles;
+        }
+        if (!mine) continue;
+        const int32_t rc = fn(s, a, idx, seen);
+        if (rc) {
+            s->abort.store(true);
+            s->wrc[(size_t)idx] = rc;
+            s->werr[(size_t)idx] = lpm_last_error();
+        }
+        {
+            std::lock_guard<std::mutex> lk(s->mu);
+            if (--s->pending == 0) s->cv_done.notify_one();
+        }
+    }
+}
+
+// Runs fn(s, a, role, epoch) for role = 0..roles-1 on the schedule's enqueue threads and waits for all of them.
+int32_t run_roles(lpm_schedule* s, const RunArgs& a, RoleFn fn, int32_t roles) {
+    const int32_t want = std::max(s->Z, 3);
+    if (s->workers.empty()) {
+        s->wrc.assign((size_t)want, LPM_OK);
+        s->werr.assign((size_t)want, std::string());
+        try {
+            for (int32_t i = 0; i < want; ++i) s->workers.emplace_back(enqueue_worker, s, i);
+        } catch (...) {
+            return fail(LPM_ENOMEM, "cannot start the enqueue threads");
+        }
+    }
+    if ((int32_t)s->workers.size() < roles) return fail(LPM_ENOMEM, "enqueue threads are missing");
+    {
+        std::lock_guard<std::mutex> lk(s->mu);
+        s->abort.store(false);
+        for (int32_t& r : s->wrc) r = LPM_OK;
+        s->job = &a;
+        s->job_fn = (void*)fn;
+        s->job_roles = roles;
+        s->pending = roles;
+        ++s->epoch;
+    }
+    s->cv_go.notify_all();
+    {
+        std::unique_lock<std::mutex> lk(s->mu);
+        s->cv_done.wait(lk, [&] { return s->pending == 0; });
+    }
+    for (int32_t i = 0; i < roles; ++i)
+        if (s->wrc[(size_t)i]) return fail(s->wrc[(size_t)i], "enqueue thread %d: %s", i, s->werr[(size_t)i].c_str());
+    return LPM_OK;
 }
 
 // The dz area of a stage's backward scratch has two copies (micro-batch parity), so the weight phase of
@@ -166,53 +388,29 @@ int32_t enqueue(lpm_schedule* s, const RunArgs& a) {
     }
     LPM_HIP(hipEventRecord(s->ev_fork, a.sf));
     if ((a.mode & 15) == LPM_PIPELINED) {
-        // stage z: forward stream sf[z], backward (data phase) stream sb[z], weight phase and update on the
-        // stage's side stream.  ev_b[j*Z+z]: data phase of B_{z,j} done; ev_w[j*Z+z]: all of B_{z,j} done.
-        for (int32_t z = 0; z < Z; ++z) {
-            LPM_HIP(hipStreamWaitEvent(s->sf[(size_t)z], s->ev_fork, 0));
-            LPM_HIP(hipStreamWaitEvent(s->sb[(size_t)z], s->ev_fork, 0));
-        }
-        for (int32_t j = 0; j < M; ++j) {
-            for (int32_t z = 0; z < Z; ++z) {
-                hipStream_t f = s->sf[(size_t)z];
-                if (j >= W) LPM_HIP(hipStreamWaitEvent(f, s->ev_w[(size_t)(j - W) * Z + z], 0));
-                if (z > 0) LPM_HIP(hipStreamWaitEvent(f, s->ev_f[(size_t)j * Z + z - 1], 0));
-                if ((rc = fwd_op(s, a, z, j, f))) return rc;
-                LPM_HIP(hipEventRecord(s->ev_f[(size_t)j * Z + z], f));
-            }
-            for (int32_t z = Z - 1; z >= 0; --z) {
-                hipStream_t b = s->sb[(size_t)z], w = s->st[(size_t)z]->side;
-                // B_{z,j} follows F_{z,j}: directly for the last stage, through B_{z+1,j} for the others
-                if (z == Z - 1) LPM_HIP(hipStreamWaitEvent(b, s->ev_f[(size_t)j * Z + z], 0));
-                else LPM_HIP(hipStreamWaitEvent(b, s->ev_b[(size_t)j * Z + z + 1], 0));
-                if (W > 2 && j >= 2) LPM_HIP(hipStreamWaitEvent(b, s->ev_w[(size_t)(j - 2) * Z + z], 0));
-                if ((rc = bwd_op(s, a, z, j, b, w))) return rc;
-                if (z > 0) LPM_HIP(hipEventRecord(s->ev_b[(size_t)j * Z + z], b));
-                if (j == M - 1 && (rc = upd_op(s, a, z, w))) return rc;
-                if (j + W < M || j == M - 1 || W > 2) LPM_HIP(hipEventRecord(s->ev_w[(size_t)j * Z + z], w));
-            }
-        }
+        if ((rc = run_roles(s, a, pipelined_role, Z))) return rc;
         for (int32_t z = 0; z < Z; ++z)      // the weight stream's last event is ordered after all work of its stage
             LPM_HIP(hipStreamWaitEvent(a.sf, s->ev_w[(size_t)(M - 1) * Z + z], 0));
         return LPM_OK;
     }
-    // OVERLAPPED: forward chains on sf, data phases of the backward chains on sb, weight phases and updates on
-    // one weight stream (stage 0's side stream; the data phases stay on sb alone while a graph is captured).
-    // ev_w[j*Z]: everything of micro-batch j done.
-    hipStream_t sw = capturing ? a.sb : s->st[0]->side;
+    if (!capturing) {
+        if ((rc = run_roles(s, a, overlapped_role, 3))) return rc;
+        LPM_HIP(hipStreamWaitEvent(a.sf, s->ev_w[(size_t)(M - 1) * Z], 0));
+        return LPM_OK;
+    }
+    // OVERLAPPED while a graph is captured: one thread, forward chains on sf, backward chains on sb (the weight
+    // gradients are branches of the graph, see lpm_stage_backward_on).  ev_w[j*Z]: micro-batch j done.
     LPM_HIP(hipStreamWaitEvent(a.sb, s->ev_fork, 0));
     for (int32_t j = 0; j < M; ++j) {
-        // F_{0,j} after B_{0,j-W}, the last operation of micro-batch j-W; the other stages follow in stream order
         if (j >= W) LPM_HIP(hipStreamWaitEvent(a.sf, s->ev_w[(size_t)(j - W) * Z], 0));
         for (int32_t z = 0; z < Z; ++z) if ((rc = fwd_op(s, a, z, j, a.sf))) return rc;
         LPM_HIP(hipEventRecord(s->ev_f[(size_t)j * Z + Z - 1], a.sf));
         LPM_HIP(hipStreamWaitEvent(a.sb, s->ev_f[(size_t)j * Z + Z - 1], 0));
-        if (W > 2 && j >= 2 && !capturing) LPM_HIP(hipStreamWaitEvent(a.sb, s->ev_w[(size_t)(j - 2) * Z], 0));
         for (int32_t z = Z - 1; z >= 0; --z) {
-            if ((rc = bwd_op(s, a, z, j, a.sb, capturing ? nullptr : sw))) return rc;
-            if (j == M - 1 && (rc = upd_op(s, a, z, sw))) return rc;
+            if ((rc = bwd_op(s, a, z, j, a.sb, nullptr))) return rc;
+            if (j == M - 1 && (rc = upd_op(s, a, z, a.sb))) return rc;
         }
-        if (j + W < M || j == M - 1 || W > 2) LPM_HIP(hipEventRecord(s->ev_w[(size_t)j * Z], sw));
+        if (j + W < M || j == M - 1) LPM_HIP(hipEventRecord(s->ev_w[(size_t)j * Z], a.sb));
     }
     LPM_HIP(hipStreamWaitEvent(a.sf, s->ev_w[(size_t)(M - 1) * Z], 0));
     return LPM_OK;

@@ -289,7 +289,7 @@ extern "C" int32_t lpm_stage_forward(lpm_stage* s, const void* x, void* y, const
 extern "C" int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y, const void* dy, void* dx,
                                       const float* params, const void* lowp, const void* stash, float* grads,
                                       int32_t accumulate, void* bwd_ws, void* stream) {
-    return lpm_stage_backward_on(s, x, y, dy, dx, params, lowp, stash, grads, accumulate, bwd_ws, stream, nullptr, 0);
+    return lpm_stage_backward_on(s, x, y, dy, dx, params, lowp, stash, grads, accumulate, bwd_ws, stream, nullptr, 0, LPM_PHASE_DATA | LPM_PHASE_WEIGHTS);
 }
 
 // B_{z,j} in two phases.  Data phase (on `stream`): everything the next stage down waits for -- epilogue
@@ -298,12 +298,16 @@ extern "C" int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y
 // data phase on `wstream` behind a single event.  wstream == stream: no event at all (fully serial);
 // wstream == NULL: the stage's own side stream, joined back into `stream` before returning (the
 // contract of lpm_stage_backward); any other stream: the caller orders later work after it.
+// phases: LPM_PHASE_DATA | LPM_PHASE_WEIGHTS as described; LPM_PHASE_DATA alone enqueues only the data
+// phase; LPM_PHASE_WEIGHTS alone only the weight phase on wstream, with no event -- the caller has ordered
+// wstream after the data phase (separate enqueue threads for the two).
 // parity (0 / 1) selects the copy of the gradient / dz area in bwd_ws this pass uses.
 // While `stream` is being captured the weight gradients stay on it and are taken out of its dependency
 // frontier instead.
 int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const void* dy, void* dx,
                               const float* params, const void* lowp, const void* stash, float* grads,
-                              int32_t accumulate, void* bwd_ws, void* stream, void* wstream, int32_t parity) {
+                              int32_t accumulate, void* bwd_ws, void* stream, void* wstream, int32_t parity,
+                              int32_t phases) {
     if (!s || !x || !y || !params || !stash || !grads || !bwd_ws) return fail(LPM_EINVAL, "NULL argument");
     if (!s->loss && !dy) return fail(LPM_EINVAL, "dy is NULL for a stage that is not a loss stage");
     if (s->dtype == LPM_BF16 && !lowp) return fail(LPM_EINVAL, "lowp is NULL for a bf16 stage");
@@ -325,6 +329,9 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
     hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
     LPM_HIP(hipStreamIsCapturing(st, &cap));
     const bool deferred = cap == hipStreamCaptureStatusNone;
+    const bool do_data = (phases & LPM_PHASE_DATA) != 0, do_weights = (phases & LPM_PHASE_WEIGHTS) != 0;
+    if (!deferred && !(do_data && do_weights)) return fail(LPM_EINVAL, "a captured backward pass cannot be split into phases");
+    if (!do_data && (!do_weights || !wstream)) return fail(LPM_EINVAL, "internal: bad phase selection");
     struct WgradJob { const LayerRt* lr; const void* xin; const void* dz; float* wdb; const float* sc; };
     std::vector<WgradJob> jobs;            // eager: the weight phase, in layer order (last layer first)
     std::vector<hipGraphNode_t> wtail;     // capture: frontier left by the last weight gradient
@@ -380,7 +387,7 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                     }
                     const bool need_dz = relu || sc;
                     if (need_dz || gadd || (dbias && !bias_in_wgrad)) {
-                        LPM_HIP(launch_epilogue_bwd(s->dtype, lr.g.rows_out(), l.cout, g, relu ? yout : nullptr, sc,
+                        if (do_data) LPM_HIP(launch_epilogue_bwd(s->dtype, lr.g.rows_out(), l.cout, g, relu ? yout : nullptr, sc,
                                                     need_dz ? (void*)(gw + lr.dz_off) : nullptr, gadd, gadd_acc,
                                                     bias_in_wgrad ? nullptr : dbias, acc, kws, st));
                         if (need_dz) dz = gw + lr.dz_off;
@@ -422,7 +429,7 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                                                          : (const void*)(params + lr.w_off);
                     const void* wt = (s->dtype == LPM_BF16 && lr.lowp_wt_off != NO)
                                          ? (const void*)((const char*)lowp + lr.lowp_wt_off) : nullptr;
-                    LPM_HIP(launch_conv_dgrad(s->dtype, lr.g, dz, w, wt, gsrc, gsrc_acc, gmask, gmscale, kws, st));
+                    if (do_data) LPM_HIP(launch_conv_dgrad(s->dtype, lr.g, dz, w, wt, gsrc, gsrc_acc, gmask, gmscale, kws, st));
                 }
                 break;
             }
@@ -440,10 +447,10 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                         gmask = (pr.d.flags & LPM_RELU) ? tptr(s, l.src, x, y, stash) : nullptr;
                         gmscale = pr.s_off != NO ? params + pr.s_off : nullptr;
                     }
-                    if (l.kind == LPM_MAXPOOL2)
+                    if (do_data && l.kind == LPM_MAXPOOL2)
                         LPM_HIP(launch_maxpool_bwd(s->dtype, s->m, l.h_in, l.w_in, l.cin, tptr(s, l.src, x, y, stash),
                                                    tptr(s, i, x, y, stash), g, gsrc, gsrc_acc, gmask != nullptr, gmscale, st));
-                    else
+                    else if (do_data)
                         LPM_HIP(launch_gap_bwd(s->dtype, s->m, l.h_in * l.w_in, l.cin, g, gsrc, gsrc_acc, gmask, gmscale, st));
                     have[gi(l.src)] = 1;
                 }
@@ -454,9 +461,9 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
     }
     if (!wtail.empty())
         LPM_HIP(hipStreamUpdateCaptureDependencies(st, wtail.data(), wtail.size(), hipStreamAddCaptureDependencies));
-    if (!jobs.empty() || (wstream && wstream != stream && deferred)) {
+    if (do_weights && (!jobs.empty() || (wstream && wstream != stream && deferred))) {
         hipStream_t wst = wstream ? (hipStream_t)wstream : s->side;
-        if (wst != st) {
+        if (wst != st && do_data) {
             LPM_HIP(hipEventRecord(s->ev_fork, st));
             LPM_HIP(hipStreamWaitEvent(wst, s->ev_fork, 0));
         }

@@ -58,4 +58,6 @@ struct lpm_stage {
 // B_{z,j} with the weight phase on a stream of the caller's choice (see stage.cpp).
 int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const void* dy, void* dx,
                               const float* params, const void* lowp, const void* stash, float* grads,
-                              int32_t accumulate, void* bwd_ws, void* stream, void* wstream, int32_t parity);
+                              int32_t accumulate, void* bwd_ws, void* stream, void* wstream, int32_t parity,
+                              int32_t phases);
+enum { LPM_PHASE_DATA = 1, LPM_PHASE_WEIGHTS = 2 };
