@@ -2,6 +2,7 @@
 // channel counts allow 16-byte K chunks, the shape-generic kernels otherwise (float element type,
 // 3-channel first layer, 10-class head).
 #include "lpm_internal.h"
+#include <algorithm>
 
 namespace lpm {
 
@@ -26,6 +27,13 @@ hipError_t mfma_conv_dgrad(const ConvGeom& g, const void* dz, const void* wt, vo
 hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* bscale,
                            int accumulate, void* ws, hipStream_t st);
 
+bool fc_skinny_ok(const ConvGeom& g);
+size_t fc_dgrad_ws_bytes(const ConvGeom& g);
+hipError_t fc_dgrad(const ConvGeom& g, const void* dz, const void* w, void* dx, int accumulate, const void* mask,
+                    const float* mscale, void* ws, hipStream_t st);
+hipError_t fc_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* bscale,
+                    int accumulate, hipStream_t st);
+
 bool smallk_ok(const ConvGeom& g);
 hipError_t smallk_conv_fwd(const ConvGeom& g, const void* x, const void* w, const float* scale, const float* bias,
                            const void* add, int relu, void* y, hipStream_t st);
@@ -34,8 +42,12 @@ hipError_t smallk_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, f
                              hipStream_t st);
 
 size_t fwd_ws_bytes(int dtype, const ConvGeom& g) { return (dtype == LPM_BF16 && mfma_fwd_ok(g)) ? mfma_fwd_ws_bytes(g) : 0; }
-size_t dgrad_ws_bytes(int dtype, const ConvGeom& g) { return (dtype == LPM_BF16 && mfma_dgrad_ok(g)) ? mfma_dgrad_ws_bytes(g) : 0; }
+size_t dgrad_ws_bytes(int dtype, const ConvGeom& g) {
+    if (dtype == LPM_BF16 && fc_skinny_ok(g)) return std::max(fc_dgrad_ws_bytes(g), mfma_dgrad_ok(g) ? mfma_dgrad_ws_bytes(g) : 0);
+    return (dtype == LPM_BF16 && mfma_dgrad_ok(g)) ? mfma_dgrad_ws_bytes(g) : 0;
+}
 size_t wgrad_ws_bytes(int dtype, const ConvGeom& g) {
+    if (dtype == LPM_BF16 && fc_skinny_ok(g)) return 0;
     if (dtype == LPM_BF16 && mfma_wgrad_ok(g)) return mfma_wgrad_ws_bytes(g);
     if (dtype == LPM_BF16 && smallk_ok(g)) return smallk_wgrad_ws_bytes(g);
     return wgrad_generic_ws_bytes(g);
@@ -48,16 +60,21 @@ hipError_t launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const vo
     return conv_fwd_generic_launch(dtype, g, x, w, scale, bias, add, relu, y, st);
 }
 
-bool wgrad_fuses_bias(int dtype, const ConvGeom& g) { return dtype == LPM_BF16 && mfma_wgrad_ok(g); }
+bool wgrad_fuses_bias(int dtype, const ConvGeom& g) { return dtype == LPM_BF16 && (fc_skinny_ok(g) || mfma_wgrad_ok(g)); }
+
+// whether the data gradient wants the [Cin][Kh][Kw][Cout] copy of the weights
+bool dgrad_uses_wt(int dtype, const ConvGeom& g) { return dtype == LPM_BF16 && !fc_skinny_ok(g) && mfma_dgrad_ok(g); }
 
 hipError_t launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dz, const void* w, const void* wt, void* dx,
                              int accumulate, const void* mask, const float* mscale, void* ws, hipStream_t st) {
+    if (dtype == LPM_BF16 && fc_skinny_ok(g)) return fc_dgrad(g, dz, w, dx, accumulate, mask, mscale, ws, st);
     if (dtype == LPM_BF16 && wt && mfma_dgrad_ok(g)) return mfma_conv_dgrad(g, dz, wt, dx, accumulate, mask, mscale, ws, st);
     return conv_dgrad_generic_launch(dtype, g, dz, w, dx, accumulate, mask, mscale, st);
 }
 
 hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias,
                              const float* bscale, int accumulate, void* ws, hipStream_t st) {
+    if (dtype == LPM_BF16 && fc_skinny_ok(g)) return fc_wgrad(g, x, dz, dw, dbias, bscale, accumulate, st);
     if (dtype == LPM_BF16 && mfma_wgrad_ok(g)) return mfma_conv_wgrad(g, x, dz, dw, dbias, bscale, accumulate, ws, st);
     if (dbias) return hipErrorInvalidValue;      // callers ask wgrad_fuses_bias first
     if (dtype == LPM_BF16 && smallk_ok(g)) return smallk_conv_wgrad(g, x, dz, dw, accumulate, ws, st);

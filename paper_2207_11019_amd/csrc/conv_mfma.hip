@@ -279,6 +279,14 @@ __global__ void __launch_bounds__(256) splitk_epilogue(const float* __restrict__
     C[i] = f2bf(v);
 }
 
+hipError_t launch_splitk_epilogue(const float* part, int splits, int64_t MN, int N, const float* scale, const float* bias,
+                                  const void* add, int relu, int accumulate, const void* mask, const float* mscale,
+                                  void* C, hipStream_t st) {
+    hipLaunchKernelGGL(splitk_epilogue, dim3((unsigned)((MN + 255) / 256)), dim3(256), 0, st, part, splits, MN, N, scale, bias,
+                       (const uint16_t*)add, relu, accumulate, (const uint16_t*)mask, mscale, (uint16_t*)C);
+    return hipGetLastError();
+}
+
 // --------------------------------------------------------------------------------------------------
 struct IgemmPlan { int big; int bk; int splits; int kt_total; int kt_per; };
 

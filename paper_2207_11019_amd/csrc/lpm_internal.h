@@ -58,6 +58,7 @@ hipError_t launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dz, const
 hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias,
                              const float* bscale, int accumulate, void* ws, hipStream_t st);
 bool wgrad_fuses_bias(int dtype, const ConvGeom& g);
+bool dgrad_uses_wt(int dtype, const ConvGeom& g);
 size_t wgrad_ws_bytes(int dtype, const ConvGeom& g);
 size_t fwd_ws_bytes(int dtype, const ConvGeom& g);
 size_t dgrad_ws_bytes(int dtype, const ConvGeom& g);

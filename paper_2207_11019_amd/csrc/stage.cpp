@@ -89,8 +89,7 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
         if (l.flags & LPM_BIAS) { lr.b_off = off; off += align_up((size_t)l.cout, 64); }
         if (dtype == LPM_BF16) {
             lr.lowp_w_off = lr.w_off * 2;      // the bf16 copies mirror the float layout element for element
-            const bool single_pixel = (o.h == 1 && o.w == 1 && l.kh == l.h_in && l.kw == l.w_in && l.pad == 0);
-            if (!single_pixel || lr.w_count <= ((size_t)4 << 20)) { lr.lowp_wt_off = lowp; lowp += align_up(lr.w_count * 2, 256); }   // rebased below
+            if (dgrad_uses_wt(dtype, lr.g)) { lr.lowp_wt_off = lowp; lowp += align_up(lr.w_count * 2, 256); }   // rebased below
         }
         if (l.flags & (LPM_RELU | LPM_SCALE)) {          // needs its own dz buffer (it outlives the layer's turn)
             lr.dz_off = gws;

@@ -39,6 +39,9 @@ SHAPES = [
     G(16, 2, 2, 512, 512, 3, 1, 1),       # deep, few pixels: split reduction
     G(5, 4, 4, 64, 72, 4, 1, 0),          # kernel covers the input: a fully connected layer
     G(16, 1, 1, 512, 10, 1, 1, 0),        # classifier head (Cout = 10)
+    G(4, 7, 7, 64, 520, 7, 1, 0),         # FC over a 7x7 map, 4 samples: weight-streaming kernels, ragged channel split
+    G(13, 1, 1, 1032, 200, 1, 1, 0),      # FC, 13 samples, K not a multiple of the column block
+    G(7, 2, 2, 24, 48, 2, 1, 0),          # FC, 7 samples, one partial column block
     G(4, 16, 16, 3, 64, 3, 1, 1),         # 3-channel first layer (generic kernels)
     G(3, 9, 11, 3, 40, 3, 2, 1),          # 3-channel first layer, stride 2, ragged
     G(2, 12, 12, 1, 16, 5, 1, 0),         # 1 channel, 5x5 (25 terms)
