@@ -34,12 +34,14 @@ hipError_t fc_dgrad(const ConvGeom& g, const void* dz, const void* w, void* dx, 
 hipError_t fc_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* bscale,
                     int accumulate, hipStream_t st);
 
+bool mfma_wgrad_flat_ok(const ConvGeom& g);
+size_t mfma_wgrad_flat_ws_bytes(const ConvGeom& g);
+hipError_t mfma_conv_wgrad_flat(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias,
+                                const float* bscale, int accumulate, void* ws, hipStream_t st);
+
 bool smallk_ok(const ConvGeom& g);
 hipError_t smallk_conv_fwd(const ConvGeom& g, const void* x, const void* w, const float* scale, const float* bias,
                            const void* add, int relu, void* y, hipStream_t st);
-size_t smallk_wgrad_ws_bytes(const ConvGeom& g);
-hipError_t smallk_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, int accumulate, void* ws,
-                             hipStream_t st);
 
 size_t fwd_ws_bytes(int dtype, const ConvGeom& g) { return (dtype == LPM_BF16 && mfma_fwd_ok(g)) ? mfma_fwd_ws_bytes(g) : 0; }
 size_t dgrad_ws_bytes(int dtype, const ConvGeom& g) {
@@ -49,7 +51,7 @@ size_t dgrad_ws_bytes(int dtype, const ConvGeom& g) {
 size_t wgrad_ws_bytes(int dtype, const ConvGeom& g) {
     if (dtype == LPM_BF16 && fc_skinny_ok(g)) return 0;
     if (dtype == LPM_BF16 && mfma_wgrad_ok(g)) return mfma_wgrad_ws_bytes(g);
-    if (dtype == LPM_BF16 && smallk_ok(g)) return smallk_wgrad_ws_bytes(g);
+    if (dtype == LPM_BF16 && mfma_wgrad_flat_ok(g)) return mfma_wgrad_flat_ws_bytes(g);
     return wgrad_generic_ws_bytes(g);
 }
 
@@ -60,7 +62,7 @@ hipError_t launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const vo
     return conv_fwd_generic_launch(dtype, g, x, w, scale, bias, add, relu, y, st);
 }
 
-bool wgrad_fuses_bias(int dtype, const ConvGeom& g) { return dtype == LPM_BF16 && (fc_skinny_ok(g) || mfma_wgrad_ok(g)); }
+bool wgrad_fuses_bias(int dtype, const ConvGeom& g) { return dtype == LPM_BF16 && (fc_skinny_ok(g) || mfma_wgrad_ok(g) || mfma_wgrad_flat_ok(g)); }
 
 // whether the data gradient wants the [Cin][Kh][Kw][Cout] copy of the weights
 bool dgrad_uses_wt(int dtype, const ConvGeom& g) { return dtype == LPM_BF16 && !fc_skinny_ok(g) && mfma_dgrad_ok(g); }
@@ -76,8 +78,8 @@ hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const 
                              const float* bscale, int accumulate, void* ws, hipStream_t st) {
     if (dtype == LPM_BF16 && fc_skinny_ok(g)) return fc_wgrad(g, x, dz, dw, dbias, bscale, accumulate, st);
     if (dtype == LPM_BF16 && mfma_wgrad_ok(g)) return mfma_conv_wgrad(g, x, dz, dw, dbias, bscale, accumulate, ws, st);
+    if (dtype == LPM_BF16 && mfma_wgrad_flat_ok(g)) return mfma_conv_wgrad_flat(g, x, dz, dw, dbias, bscale, accumulate, ws, st);
     if (dbias) return hipErrorInvalidValue;      // callers ask wgrad_fuses_bias first
-    if (dtype == LPM_BF16 && smallk_ok(g)) return smallk_conv_wgrad(g, x, dz, dw, accumulate, ws, st);
     return conv_wgrad_generic_launch(dtype, g, x, dz, dw, accumulate, ws, st);
 }
 

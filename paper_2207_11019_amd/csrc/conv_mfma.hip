@@ -36,6 +36,10 @@ __device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, unsigned o
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+__device__ __forceinline__ unsigned short buf_load2(__amdgpu_buffer_rsrc_t r, unsigned off) {
+    return (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r, off, 0, 0);
+}
+
 // A K tile of depth BK is stored in LDS as rows of BK + 8 elements (16-byte aligned, staggers banks).
 // Small-M shapes are bound by the latency of one global load per K tile, so they take deep tiles.
 
@@ -413,6 +417,7 @@ struct WgradArgs {
     int rt_total, rt_per_split, splits;
     int accumulate;
     int co_tiles, ci_tiles;
+    int x_cin, x_taps;     // flattened mode (see wgrad_kernel): channels and filter taps of the real input
 };
 
 template <int LDK>
@@ -431,7 +436,10 @@ __device__ __forceinline__ void transpose4x8_store(const uint4 (&q)[4], uint16_t
     }
 }
 
-template <int BM, int BN, int BK>
+// FLAT: for an input of very few channels (an image: Cin*Kh*Kw <= BN) the N dimension of the tile is the
+// flattened (tap, channel) index instead of the channels of one tap; its operand is gathered 2 bytes at a time.
+// There p.Cin holds Cin*Kh*Kw and p.KhKw is 1, so the output index is the same expression in both modes.
+template <int BM, int BN, int BK, bool FLAT>
 __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
     typedef TileCfg<BM, BN, 2, 2> Cfg;
     // LDS rows of BK + 12 elements: 8 rows apart is 192 bytes apart modulo the 256-byte bank period, so the 4
@@ -457,6 +465,7 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
     // in the padding) load zeros through the buffer resources.
     const __amdgpu_buffer_rsrc_t rsD = make_rsrc(p.DZ, p.dz_bytes), rsX = make_rsrc(p.X, p.x_bytes);
     uint4 qa0[A_PT][4], qb0[B_PT][4], qa1[A_PT][4], qb1[B_PT][4];
+    unsigned short qs0[B_PT][4][8], qs1[B_PT][4][8];      // FLAT: the raw 2-byte gathers of the B items
 
     // Cursors of the next pixel tile to load (tiles are loaded strictly in order).  Per item: the first of its
     // 4 pixels as (row index, wo, ho, image); a tile step adds BK pixels with carries, pixels 1..3 follow by +1.
@@ -486,8 +495,24 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
         const int q = b_r[t] / p.Wo;
         b_wo[t] = b_r[t] - q * p.Wo; b_ho[t] = q % p.Ho; b_n[t] = q / p.Ho;
     }
+    // FLAT: the 8 (tap, channel) indices of an item -- element offset from the pixel at tap (0,0), and the tap
+    int f_off[B_PT][8], f_hw[B_PT][8];        // f_hw = kh << 16 | kw, or -1 when the index is past Cin*Kh*Kw
+    if (FLAT) {
+#pragma unroll
+        for (int t = 0; t < B_PT; ++t) {
+            const int item = tid + t * 256, cc = (item & 3) + 4 * (item / (4 * RGS));
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int k = ci0 + cc * 8 + e;
+                const int tp = k / p.x_cin, ci = k - tp * p.x_cin, th = tp / p.Kw, tw = tp - th * p.Kw;
+                const bool ok = (item < B_ITEMS) & (k < p.Cin);
+                f_off[t][e] = (th * p.W + tw) * p.x_cin + ci;
+                f_hw[t][e] = ok ? ((th << 16) | tw) : -1;
+            }
+        }
+    }
 
-#define LPM_LOAD_TILE(QA, QB)                                                                                \
+#define LPM_LOAD_TILE(QA, QB, QS)                                                                            \
     {                                                                                                        \
         const bool live_ = cur_rt < rt1;                                                                     \
         _Pragma("unroll") for (int t = 0; t < A_PT; ++t) {                                                   \
@@ -500,10 +525,22 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
         _Pragma("unroll") for (int t = 0; t < B_PT; ++t) {                                                   \
             int wo_ = b_wo[t], ho_ = b_ho[t], n_ = b_n[t];                                                   \
             _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                  \
-                const int h_ = ho_ * p.stride + kh - p.pad, w_ = wo_ * p.stride + kw - p.pad;                \
-                const bool ok_ = b_chok[t] & live_ & (b_r[t] + j < p.R) & ((unsigned)h_ < (unsigned)p.H) &   \
-                                 ((unsigned)w_ < (unsigned)p.W);                                             \
-                QB[t][j] = buf_load16(rsX, ok_ ? (unsigned)(((n_ * p.H + h_) * p.W + w_) * p.Cin) * 2u + b_choff[t] : OOB); \
+                if (FLAT) {                                                                                  \
+                    const int h0_ = ho_ * p.stride - p.pad, w0_ = wo_ * p.stride - p.pad;                    \
+                    const int base_ = ((n_ * p.H + h0_) * p.W + w0_) * p.x_cin;                              \
+                    const bool pix_ = live_ & (b_r[t] + j < p.R);                                            \
+                    _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                          \
+                        const int hw_ = f_hw[t][e];                                                          \
+                        const bool ok_ = pix_ & (hw_ >= 0) & ((unsigned)(h0_ + (hw_ >> 16)) < (unsigned)p.H) & \
+                                         ((unsigned)(w0_ + (hw_ & 0xffff)) < (unsigned)p.W);                 \
+                        QS[t][j][e] = buf_load2(rsX, ok_ ? (unsigned)(base_ + f_off[t][e]) * 2u : OOB);      \
+                    }                                                                                        \
+                } else {                                                                                     \
+                    const int h_ = ho_ * p.stride + kh - p.pad, w_ = wo_ * p.stride + kw - p.pad;            \
+                    const bool ok_ = b_chok[t] & live_ & (b_r[t] + j < p.R) & ((unsigned)h_ < (unsigned)p.H) & \
+                                     ((unsigned)w_ < (unsigned)p.W);                                         \
+                    QB[t][j] = buf_load16(rsX, ok_ ? (unsigned)(((n_ * p.H + h_) * p.W + w_) * p.Cin) * 2u + b_choff[t] : OOB); \
+                }                                                                                            \
                 ++wo_;                                                                                       \
                 if (wo_ == p.Wo) { wo_ = 0; ++ho_; if (ho_ == p.Ho) { ho_ = 0; ++n_; } }                     \
             }                                                                                                \
@@ -514,7 +551,7 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
         }                                                                                                    \
         ++cur_rt;                                                                                            \
     }
-#define LPM_STORE_TILE(BUF, QA, QB)                                                                          \
+#define LPM_STORE_TILE(BUF, QA, QB, QS)                                                                      \
     {                                                                                                        \
         _Pragma("unroll") for (int t = 0; t < A_PT; ++t) {                                                   \
             const int item_ = tid + t * 256, rg_ = (item_ >> 2) % RGS, cc_ = (item_ & 3) + 4 * (item_ / (4 * RGS)); \
@@ -522,6 +559,11 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
         }                                                                                                    \
         _Pragma("unroll") for (int t = 0; t < B_PT; ++t) {                                                   \
             const int item_ = tid + t * 256, rg_ = (item_ >> 2) % RGS, cc_ = (item_ & 3) + 4 * (item_ / (4 * RGS)); \
+            if (FLAT) {                                                                                      \
+                _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                \
+                    QB[t][j] = make_uint4(QS[t][j][0] | ((uint32_t)QS[t][j][1] << 16), QS[t][j][2] | ((uint32_t)QS[t][j][3] << 16), \
+                                          QS[t][j][4] | ((uint32_t)QS[t][j][5] << 16), QS[t][j][6] | ((uint32_t)QS[t][j][7] << 16)); \
+            }                                                                                                \
             if (item_ < B_ITEMS) transpose4x8_store<LDK>(QB[t], &Bs[BUF][(cc_ * 8) * LDK + rg_ * 4]);        \
         }                                                                                                    \
     }
@@ -552,22 +594,22 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
     };
     const int nk = rt1 - rt0;
     if (nk > 0) {
-        LPM_LOAD_TILE(qa0, qb0);
-        LPM_LOAD_TILE(qa1, qb1);
-        LPM_STORE_TILE(0, qa0, qb0);
+        LPM_LOAD_TILE(qa0, qb0, qs0);
+        LPM_LOAD_TILE(qa1, qb1, qs1);
+        LPM_STORE_TILE(0, qa0, qb0, qs0);
         __syncthreads();
         // pixel tiles in pairs with no exit in between; an odd count is padded by one all-zero tile
         const int npair = (nk + 1) >> 1;
         for (int it = 0; it < npair; ++it) {
-            LPM_LOAD_TILE(qa0, qb0);
+            LPM_LOAD_TILE(qa0, qb0, qs0);
             bias_tile(0);
             mma_tile<Cfg::MI, Cfg::NI, BK, LDK, true>(As[0], Bs[0], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
-            LPM_STORE_TILE(1, qa1, qb1);
+            LPM_STORE_TILE(1, qa1, qb1, qs1);
             __syncthreads();
-            LPM_LOAD_TILE(qa1, qb1);
+            LPM_LOAD_TILE(qa1, qb1, qs1);
             bias_tile(1);
             mma_tile<Cfg::MI, Cfg::NI, BK, LDK, true>(As[1], Bs[1], wm * Cfg::WTM, wn * Cfg::WTN, lane, acc);
-            LPM_STORE_TILE(0, qa0, qb0);
+            LPM_STORE_TILE(0, qa0, qb0, qs0);
             __syncthreads();
         }
     }
@@ -682,14 +724,92 @@ hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, flo
     a.accumulate = accumulate;
     a.co_tiles = pl.co_tiles; a.ci_tiles = pl.ci_tiles;
     const dim3 grid((unsigned)(pl.co_tiles * pl.ci_tiles * a.KhKw), 1, pl.splits);
-    if (pl.big) hipLaunchKernelGGL((wgrad_kernel<128, 128, 64>), grid, dim3(256), 0, st, a);
-    else if (pl.bk == 128) hipLaunchKernelGGL((wgrad_kernel<64, 64, 128>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((wgrad_kernel<64, 64, 64>), grid, dim3(256), 0, st, a);
+    if (pl.big) hipLaunchKernelGGL((wgrad_kernel<128, 128, 64, false>), grid, dim3(256), 0, st, a);
+    else if (pl.bk == 128) hipLaunchKernelGGL((wgrad_kernel<64, 64, 128, false>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((wgrad_kernel<64, 64, 64, false>), grid, dim3(256), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.splits == 1) return e;
     const int64_t n = (int64_t)g.Cout * g.K();
     const int nb = dbias ? g.Cout : 0;
     hipLaunchKernelGGL(wgrad_reduce, dim3((unsigned)((n + nb + 255) / 256)), dim3(256), 0, st, (const float*)ws,
+                       a.part_stride, pl.splits, dw, n, dbias, nb, bscale, accumulate);
+    return hipGetLastError();
+}
+
+// The same reduction for a short output vector (a first layer's few thousand weights) and many partials:
+// 8 lanes share one output, each adds a contiguous eighth of the partials in order, and the eight sums are
+// added in lane order -- a fixed order, with 8 loads in flight per output instead of one.
+__global__ void __launch_bounds__(256) wgrad_reduce_short(const float* __restrict__ part, size_t stride, int splits,
+                                                          float* __restrict__ dst, int64_t n, float* __restrict__ db, int nb,
+                                                          const float* __restrict__ bscale, int accumulate) {
+    __shared__ float red[8][32];
+    const int o = threadIdx.x & 31, l = threadIdx.x >> 5;
+    const int64_t i = (int64_t)blockIdx.x * 32 + o;
+    float acc = 0.f;
+    if (i < n + nb) {
+        const int per = (splits + 7) / 8;
+        const int s1 = min(splits, (l + 1) * per);
+        for (int s = l * per; s < s1; ++s) acc += part[(size_t)s * stride + i];
+    }
+    red[l][o] = acc;
+    __syncthreads();
+    if (l != 0 || i >= n + nb) return;
+    float v = red[0][o];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) v += red[k][o];
+    if (i < n) dst[i] = accumulate ? dst[i] + v : v;
+    else {
+        const int c = (int)(i - n);
+        if (bscale) v /= bscale[c];
+        db[c] = accumulate ? db[c] + v : v;
+    }
+}
+
+// Weight gradient of an image-input layer (Cin*Kh*Kw <= 64): one N tile holds every (tap, channel) index.
+bool mfma_wgrad_flat_ok(const ConvGeom& g) { return g.K() <= 64 && g.Cout % 8 == 0 && fits32(g); }
+
+static WgradPlan plan_wgrad_flat(const ConvGeom& g) {
+    WgradPlan pl{};
+    const int64_t R = g.rows_out();
+    pl.bk = R >= 1024 ? 128 : 64;
+    pl.rt_total = (int)((R + pl.bk - 1) / pl.bk);
+    pl.co_tiles = (g.Cout + 63) / 64;
+    pl.ci_tiles = 1;
+    int s = std::min(std::min(512 / pl.co_tiles, std::max(1, pl.rt_total / 4)), 256);
+    pl.rt_per = (pl.rt_total + s - 1) / s;
+    pl.splits = (pl.rt_total + pl.rt_per - 1) / pl.rt_per;
+    return pl;
+}
+
+size_t mfma_wgrad_flat_ws_bytes(const ConvGeom& g) {
+    const WgradPlan pl = plan_wgrad_flat(g);
+    return pl.splits > 1 ? (size_t)pl.splits * ((size_t)g.Cout * g.K() + g.Cout) * sizeof(float) : 0;
+}
+
+hipError_t mfma_conv_wgrad_flat(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias,
+                                const float* bscale, int accumulate, void* ws, hipStream_t st) {
+    const WgradPlan pl = plan_wgrad_flat(g);
+    WgradArgs a{};
+    a.X = (const uint16_t*)x; a.DZ = (const uint16_t*)dz;
+    a.out = pl.splits > 1 ? (float*)ws : dw;
+    a.Cout = g.Cout; a.Cin = g.K(); a.KhKw = 1; a.Kw = g.Kw;
+    a.x_cin = g.Cin; a.x_taps = g.Kh * g.Kw;
+    a.H = g.H; a.W = g.W; a.Ho = g.Ho; a.Wo = g.Wo; a.stride = g.stride; a.pad = g.pad;
+    a.R = (int)g.rows_out();
+    a.db = dbias; a.bscale = bscale;
+    a.part_stride = (size_t)g.Cout * g.K() + g.Cout;
+    a.dz_bytes = (unsigned)(g.rows_out() * g.Cout * 2); a.x_bytes = (unsigned)(g.rows_in() * g.Cin * 2);
+    a.rt_total = pl.rt_total; a.rt_per_split = pl.rt_per; a.splits = pl.splits;
+    a.accumulate = accumulate;
+    a.co_tiles = pl.co_tiles; a.ci_tiles = 1;
+    const dim3 grid((unsigned)pl.co_tiles, 1, pl.splits);
+    if (pl.bk == 128) hipLaunchKernelGGL((wgrad_kernel<64, 64, 128, true>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((wgrad_kernel<64, 64, 64, true>), grid, dim3(256), 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || pl.splits == 1) return e;
+    const int64_t n = (int64_t)g.Cout * g.K();
+    const int nb = dbias ? g.Cout : 0;
+    hipLaunchKernelGGL(wgrad_reduce_short, dim3((unsigned)((n + nb + 31) / 32)), dim3(256), 0, st, (const float*)ws,
                        a.part_stride, pl.splits, dw, n, dbias, nb, bscale, accumulate);
     return hipGetLastError();
 }

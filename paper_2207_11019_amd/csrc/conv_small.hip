@@ -1,7 +1,8 @@
 // Convolutions whose whole reduction fits a few dozen terms (an image-input first layer: Cin*Kh*Kw <= 32,
 // e.g. 3 channels x 3x3): too short for MFMA K tiles, and bound by activation traffic (about 26 flop/B).
-// Forward (eq. 1) and weight gradient (eq. 8) on the vector ALU with the filter bank / the patch matrix in
-// LDS.  bf16 activations, fp32 accumulation.  No data gradient: such a layer reads the network input.
+// Forward (eq. 1) on the vector ALU with the filter bank in LDS.  bf16 activations, fp32 accumulation.
+// (The weight gradient has a long reduction over the pixels and runs on the matrix cores; no data gradient:
+// such a layer reads the network input.)
 #include "lpm_internal.h"
 #include "elem.h"
 
@@ -63,78 +64,6 @@ hipError_t smallk_conv_fwd(const ConvGeom& g, const void* x, const void* w, cons
     hipLaunchKernelGGL(conv_fwd_smallk, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, g, (const uint16_t*)x,
                        (const uint16_t*)w, scale, bias, (const uint16_t*)add, relu, (uint16_t*)y);
     return hipGetLastError();
-}
-
-// A block reduces SK_ROWS output pixels: stages dz [rows][Cout] and the patch matrix [rows][K] in LDS as
-// floats, then every thread owns a few (co, k) entries.  One partial per block; a second kernel adds the
-// partials in block order.
-constexpr int SK_ROWS = 64;
-constexpr int SK_PER_BLOCK = 2;     // sub-iterations of SK_ROWS
-
-__global__ void __launch_bounds__(256) conv_wgrad_smallk(ConvGeom g, const uint16_t* __restrict__ x,
-                                                         const uint16_t* __restrict__ dz, float* __restrict__ part) {
-    __shared__ float dzs[SK_ROWS][SK_MAXCO + 1];
-    __shared__ float ps[SK_ROWS][SK_MAXK + 1];
-    const int K = g.K(), total = g.Cout * K;
-    const int64_t R = g.rows_out();
-    float acc[(SK_MAXCO * SK_MAXK + 255) / 256];
-#pragma unroll
-    for (int i = 0; i < (SK_MAXCO * SK_MAXK + 255) / 256; ++i) acc[i] = 0.f;
-    for (int it = 0; it < SK_PER_BLOCK; ++it) {
-        const int64_t r0 = ((int64_t)blockIdx.x * SK_PER_BLOCK + it) * SK_ROWS;
-        __syncthreads();
-        for (int i = threadIdx.x; i < SK_ROWS * g.Cout; i += 256) {
-            const int r = i / g.Cout, c = i % g.Cout;
-            dzs[r][c] = (r0 + r < R) ? bf2f(dz[(r0 + r) * g.Cout + c]) : 0.f;
-        }
-        for (int i = threadIdx.x; i < SK_ROWS * K; i += 256) {
-            const int r = i / K, k = i % K;
-            float v = 0.f;
-            if (r0 + r < R) {
-                const int64_t row = r0 + r;
-                const int wo = (int)(row % g.Wo), ho = (int)((row / g.Wo) % g.Ho), n = (int)(row / ((int64_t)g.Wo * g.Ho));
-                const int ci = k % g.Cin, kw = (k / g.Cin) % g.Kw, kh = k / (g.Cin * g.Kw);
-                const int h = ho * g.stride + kh - g.pad, ww = wo * g.stride + kw - g.pad;
-                if ((unsigned)h < (unsigned)g.H && (unsigned)ww < (unsigned)g.W)
-                    v = bf2f(x[(((int64_t)n * g.H + h) * g.W + ww) * g.Cin + ci]);
-            }
-            ps[r][k] = v;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < (SK_MAXCO * SK_MAXK + 255) / 256; ++i) {
-            const int o = threadIdx.x + i * 256;
-            if (o < total) {
-                const int co = o / K, k = o % K;
-                float a = acc[i];
-#pragma unroll 8
-                for (int r = 0; r < SK_ROWS; ++r) a = fmaf(dzs[r][co], ps[r][k], a);
-                acc[i] = a;
-            }
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < (SK_MAXCO * SK_MAXK + 255) / 256; ++i) {
-        const int o = threadIdx.x + i * 256;
-        if (o < total) part[(int64_t)blockIdx.x * total + o] = acc[i];
-    }
-}
-
-hipError_t reduce_partials_launch(const float* part, float* dst, int64_t n, int chunks, int accumulate, hipStream_t s);
-
-static int smallk_blocks(const ConvGeom& g) {
-    return (int)((g.rows_out() + SK_ROWS * SK_PER_BLOCK - 1) / (SK_ROWS * SK_PER_BLOCK));
-}
-
-size_t smallk_wgrad_ws_bytes(const ConvGeom& g) { return (size_t)smallk_blocks(g) * g.Cout * g.K() * sizeof(float); }
-
-hipError_t smallk_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, int accumulate, void* ws,
-                             hipStream_t st) {
-    const int nb = smallk_blocks(g);
-    hipLaunchKernelGGL(conv_wgrad_smallk, dim3(nb), dim3(256), 0, st, g, (const uint16_t*)x, (const uint16_t*)dz, (float*)ws);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    return reduce_partials_launch((const float*)ws, dw, (int64_t)g.Cout * g.K(), nb, accumulate, st);
 }
 
 }  // namespace lpm
