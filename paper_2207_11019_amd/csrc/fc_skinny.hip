@@ -13,7 +13,7 @@ hipError_t launch_splitk_epilogue(const float* part, int splits, int64_t MN, int
                                   const void* add, int relu, int accumulate, const void* mask, const float* mscale,
                                   void* C, hipStream_t st);
 
-constexpr int FC_MAX_M = 16;
+constexpr int FC_MAX_M = 8;       // beyond this the per-lane accumulators no longer fit the register file
 
 bool fc_skinny_ok(const ConvGeom& g) {
     return g.Ho == 1 && g.Wo == 1 && g.Kh == g.H && g.Kw == g.W && g.pad == 0 && g.m <= FC_MAX_M && g.K() % 8 == 0 &&
@@ -133,8 +133,7 @@ hipError_t fc_dgrad(const ConvGeom& g, const void* dz, const void* w, void* dx, 
 #define LPM_FCD(MB) hipLaunchKernelGGL((fc_dgrad_skinny<MB>), grid, dim3(256), 0, st, (const uint16_t*)dz, (const uint16_t*)w, \
                                        (float*)ws, g.m, g.Cout, K, p.cps)
     if (g.m <= 4) LPM_FCD(4);
-    else if (g.m <= 8) LPM_FCD(8);
-    else LPM_FCD(16);
+    else LPM_FCD(8);
 #undef LPM_FCD
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -214,8 +213,7 @@ hipError_t fc_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw,
 #define LPM_FCW(MB) hipLaunchKernelGGL((fc_wgrad_skinny<MB>), grid, dim3(threads), 0, st, (const uint16_t*)x, (const uint16_t*)dz, \
                                        dw, dbias, bscale, g.m, g.Cout, K, accumulate)
     if (g.m <= 4) LPM_FCW(4);
-    else if (g.m <= 8) LPM_FCW(8);
-    else LPM_FCW(16);
+    else LPM_FCW(8);
 #undef LPM_FCW
     return hipGetLastError();
 }

@@ -11,8 +11,10 @@
 //               devices): F_{z,j+1} also overlaps F_{z+1,j}, and B_{z,j} overlaps B_{z+1,j+1}.  Each stage
 //               is enqueued by a host thread of its own (launching is what bounds small micro-batches).
 // Every buffer that belongs to a micro-batch (stash, stage output, input gradient) lives in slot
-// j % window.  Micro-batch j + window starts at stage 0 only after B_{0,j}, the last operation of
-// micro-batch j, so a slot is never rewritten while an operation of its previous owner is pending.
+// j % window.  In LOCKED and OVERLAPPED micro-batch j + window starts at stage 0 only after all of
+// micro-batch j, so a slot is never rewritten while an operation of its previous owner is pending; in
+// PIPELINED F_{z,j+window} waits for every reader of the slots it rewrites (B_{z,j} and the weight phase of
+// B_{z+1,j}).
 // Gradients are accumulated over the micro-batches in the fixed order j = 0..M-1 and every stage is
 // updated once, right after its last backward, so both modes produce bit-identical results.
 #include "stage.h"
@@ -214,7 +216,16 @@ int32_t pipelined_role(lpm_schedule* s, const RunArgs& a, int32_t z, uint64_t ep
     LPM_HIP(hipStreamWaitEvent(f, s->ev_fork, 0));
     LPM_HIP(hipStreamWaitEvent(b, s->ev_fork, 0));
     auto F = [&](int32_t j) -> int32_t {
-        if (j >= W) LPM_HIP(hipStreamWaitEvent(f, s->ev_w[(size_t)(j - W) * Z + z], 0));
+        if (j >= W) {
+            // the slot's previous owner is done: this stage's B_{z,j-W}, and the weight phase of B_{z+1,j-W},
+            // which reads this stage's output (the input of stage z+1's first layer)
+            LPM_HIP(hipStreamWaitEvent(f, s->ev_w[(size_t)(j - W) * Z + z], 0));
+            if (z < Z - 1) {
+                const size_t i = (size_t)(j - W) * Z + z + 1;
+                if ((rc = await_record(s, s->rec_w[i], epoch))) return rc;
+                LPM_HIP(hipStreamWaitEvent(f, s->ev_w[i], 0));
+            }
+        }
         if (z > 0) {
             const size_t i = (size_t)j * Z + z - 1;
             if ((rc = await_record(s, s->rec_f[i], epoch))) return rc;
@@ -242,6 +253,7 @@ int32_t pipelined_role(lpm_schedule* s, const RunArgs& a, int32_t z, uint64_t ep
         if ((rc = bwd_op(s, a, z, j, b, w, LPM_PHASE_WEIGHTS))) return rc;
         if (j == M - 1 && (rc = upd_op(s, a, z, w))) return rc;
         LPM_HIP(hipEventRecord(s->ev_w[me], w));
+        publish(s->rec_w[me], epoch);
         return LPM_OK;
     };
     for (int32_t j = 0; j < W && j < M; ++j) if ((rc = F(j))) return rc;
@@ -249,7 +261,6 @@ int32_t pipelined_role(lpm_schedule* s, const RunArgs& a, int32_t z, uint64_t ep
         if ((rc = B(j))) return rc;
         if (j + W < M && (rc = F(j + W))) return rc;
     }
-    publish(s->rec_w[(size_t)(M - 1) * Z + z], epoch);
     return LPM_OK;
 }
 
