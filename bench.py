@@ -40,6 +40,43 @@ def conv_ops(layers, m, first_needs_dgrad=False):
     return ops
 
 
+def conv_buffers(torch, lpm, g, dtype):
+    """Synthetic device operands of one contraction: x, dz-shaped y, w, transposed-shaped wt, dW, scratch."""
+    ho = (g["h"] + 2 * g["pad"] - g["kh"]) // g["stride"] + 1
+    wo = (g["w"] + 2 * g["pad"] - g["kw"]) // g["stride"] + 1
+    tdt = torch.bfloat16 if dtype == lpm.BF16 else torch.float32
+    K = g["kh"] * g["kw"] * g["cin"]
+    xx = torch.randn(g["m"] * g["h"] * g["w"] * g["cin"], device="cuda").to(tdt)
+    yy = torch.randn(g["m"] * ho * wo * g["cout"], device="cuda").to(tdt) * 1e-2
+    ww = (torch.randn(g["cout"] * K, device="cuda") * (2.0 / K) ** 0.5).to(tdt)
+    wt = ww.clone() if dtype == lpm.BF16 else None
+    dw = torch.zeros(g["cout"] * K, device="cuda")
+    ws = torch.zeros(max(max(lpm.lpm_conv_ws_bytes(g, dtype)), 256), dtype=torch.uint8, device="cuda")
+    return xx, ww, wt, yy, dw, ws
+
+
+OPI = {"fwd": 0, "dgrad": 1, "wgrad": 2}
+
+
+def stored_traffic(workload, kernel):
+    """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    (profiles/hbm_traffic_<workload>.md); None when that file is missing or describes another kernel."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.md" % workload)
+    if not os.path.exists(path):
+        return None
+    kv = {}
+    for line in open(path):
+        if line.startswith("- ") and ": " in line:
+            k, v = line[2:].split(": ", 1)
+            kv[k.strip()] = v.strip()
+    if kv.get("kernel") != kernel:
+        return None
+    try:
+        return int(float(kv["traffic_bytes_per_launch"]))
+    except (KeyError, ValueError):
+        return None
+
+
 def time_stream(torch, fn, iters, warm=3):
     """Average duration in seconds of fn() enqueued `iters` times on torch's current stream, by HIP events."""
     for _ in range(warm):
@@ -63,6 +100,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-layer-table", action="store_true", help="skip the per-contraction timing table")
     ap.add_argument("--eager", action="store_true", help="enqueue the step kernel by kernel instead of replaying a graph")
+    ap.add_argument("--pmc-probe", default=None, metavar="LAYER:OP",
+                    help="counter-collection aid: launch one contraction (e.g. 1:wgrad) and a 256 MiB copy, nothing else")
     ap.add_argument("--only", choices=["locked", "overlapped", "pipelined"], default=None,
                     help="profiling aid: run just this schedule (eager enqueue) for --steps steps and print its time")
     args = ap.parse_args()
@@ -110,6 +149,23 @@ def main():
         run(mode, steps)
         torch.cuda.synchronize()
         return time.perf_counter() - t0
+
+    if args.pmc_probe:
+        # counter-collection aid: 20 launches of one contraction, then 10 device copies of 256 MiB (the known-size
+        # kernel the FETCH_SIZE / WRITE_SIZE readings are scaled by); run under rocprofv3 --pmc
+        li, op = args.pmc_probe.split(":")
+        g = [o for o in conv_ops(layers, m, dx_wanted) if o[0] == int(li) and o[1] == op][0][2]
+        xx, ww, wt, yy, dw, ws = conv_buffers(torch, lpm, g, dtype)
+        st = torch.cuda.Stream()
+        us = lpm.lpm_conv_time(OPI[op], g, dtype, xx, ww, wt, yy, dw, ws, 0, 20, st)
+        a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        b = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
+        for _ in range(10):
+            a.copy_(b)
+        torch.cuda.synchronize()
+        print(json.dumps({"workload": args.workload, "probe": args.pmc_probe, "geometry": g, "avg_us": round(us, 2),
+                          "copy_bytes": 256 << 20}))
+        return 0
 
     if args.only:
         mode = {"locked": lpm.LOCKED, "overlapped": lpm.OVERLAPPED, "pipelined": lpm.PIPELINED}[args.only]
@@ -163,19 +219,8 @@ def main():
         for (i, op, g, flops, byts) in ops:
             key = (op,) + tuple(sorted(g.items()))
             if key not in cache:
-                ho = (g["h"] + 2 * g["pad"] - g["kh"]) // g["stride"] + 1
-                wo = (g["w"] + 2 * g["pad"] - g["kw"]) // g["stride"] + 1
-                tdt = torch.bfloat16 if dtype == lpm.BF16 else torch.float32
-                K = g["kh"] * g["kw"] * g["cin"]
-                xx = torch.randn(g["m"] * g["h"] * g["w"] * g["cin"], device="cuda").to(tdt)
-                yy = torch.randn(g["m"] * ho * wo * g["cout"], device="cuda").to(tdt) * 1e-2
-                ww = (torch.randn(g["cout"] * K, device="cuda") * (2.0 / K) ** 0.5).to(tdt)
-                wt = ww.clone()
-                dw = torch.zeros(g["cout"] * K, device="cuda")
-                wsb = lpm.lpm_conv_ws_bytes(g, dtype)
-                ws = torch.zeros(max(max(wsb), 256), dtype=torch.uint8, device="cuda")
-                opi = {"fwd": 0, "dgrad": 1, "wgrad": 2}[op]
-                us = lpm.lpm_conv_time(opi, g, dtype, xx, ww, wt if dtype == lpm.BF16 else None, yy, dw, ws, 10, 100, cur)
+                xx, ww, wt, yy, dw, ws = conv_buffers(torch, lpm, g, dtype)
+                us = lpm.lpm_conv_time(OPI[op], g, dtype, xx, ww, wt, yy, dw, ws, 10, 100, cur)
                 cache[key] = us * 1e-6
             t = cache[key]
             ai = flops / byts
@@ -195,6 +240,7 @@ def main():
             roof = dict(bound="hbm", achieved=round(dom["bytes"] / t / 1e9, 2), peak=PEAK["hbm"] / 1e9, unit="GB/s",
                         frac=round(dom["bytes"] / t / PEAK["hbm"], 5), traffic=None)
         roof["kernel"] = "conv %s, layer %d (%s)" % (dom["op"], dom["layer"], dom["shape"])
+        roof["traffic"] = stored_traffic(args.workload, roof["kernel"])
         roof["avg_us"] = dom["us"]
         tot_flops = sum(r["flops"] for r in table) * M
         roof["step_contraction_flops"] = tot_flops

@@ -453,13 +453,18 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
     __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN * LDK];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-    int tile = xcd_remap(blockIdx.x, gridDim.x);
+    // Workgroups go to the 8 XCDs round-robin in launch order (x fastest, then z).  All tiles of one pixel range
+    // read the same dz and x rows (each filter tap a shifted copy), so they are given to one XCD, whose L2 then
+    // serves the repeats: virtual index = position in the XCD's contiguous share, pixel range outermost.
+    const int v_id = xcd_remap((int)(blockIdx.z * gridDim.x + blockIdx.x), (int)(gridDim.x * gridDim.z));
+    const int split = v_id / (int)gridDim.x;
+    int tile = v_id - split * (int)gridDim.x;
     const int ci_t = tile % p.ci_tiles; tile /= p.ci_tiles;
     const int tap = tile % p.KhKw;
     const int co_t = tile / p.KhKw;
     const int co0 = co_t * BM, ci0 = ci_t * BN;
     const int kh = tap / p.Kw, kw = tap - kh * p.Kw;
-    const int rt0 = blockIdx.z * p.rt_per_split, rt1 = min(p.rt_total, rt0 + p.rt_per_split);
+    const int rt0 = split * p.rt_per_split, rt1 = min(p.rt_total, rt0 + p.rt_per_split);
 
     // Two pixel tiles in flight in registers; out-of-range items (ragged channels, pixels past the end, taps
     // in the padding) load zeros through the buffer resources.
@@ -617,7 +622,7 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
 #undef LPM_STORE_TILE
 
     const size_t total = (size_t)p.Cout * p.KhKw * p.Cin;
-    float* out = p.out + (p.splits > 1 ? (size_t)blockIdx.z * p.part_stride : 0);
+    float* out = p.out + (p.splits > 1 ? (size_t)split * p.part_stride : 0);
     if (do_bias && tid < BM && co0 + tid < p.Cout) {
         const int co = co0 + tid;
         if (p.splits > 1) out[total + co] = bsum;
@@ -678,7 +683,7 @@ static WgradPlan plan_wgrad(const ConvGeom& g) {
     pl.ci_tiles = (g.Cin + t - 1) / t;
     const int64_t tiles = (int64_t)pl.co_tiles * pl.ci_tiles * g.Kh * g.Kw;
     int s = (int)std::min<int64_t>(512 / std::max<int64_t>(tiles, 1), std::max(1, pl.rt_total / 4));
-    if (s > 64) s = 64;
+    if (s > 24) s = 24;          // beyond this the partial sums cost more than the shorter pixel loops save
     // the partials must stay modest for very large weight tensors
     const int64_t wbytes = (int64_t)g.Cout * g.K() * 4;
     while (s > 1 && wbytes * s > (256ll << 20)) --s;

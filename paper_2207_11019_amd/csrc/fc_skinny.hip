@@ -117,6 +117,7 @@ static FcDgradPlan plan_fc_dgrad(const ConvGeom& g) {
     p.colblocks = (g.K() + FCD_COLS - 1) / FCD_COLS;
     int s = (1536 + p.colblocks - 1) / p.colblocks;          // enough blocks to cover the memory latency
     s = std::min(s, std::max(1, g.Cout / 32));                // at least 32 channels per block
+    s = std::min(s, 32);                                      // the reduction kernel adds the partials one after the other
     s = std::max(s, (g.Cout + FCD_MAX_CPS - 1) / FCD_MAX_CPS);
     p.cps = (g.Cout + s - 1) / s;
     p.splits = (g.Cout + p.cps - 1) / p.cps;
