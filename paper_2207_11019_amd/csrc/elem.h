@@ -21,6 +21,28 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
 }
 
+// Streaming accesses: data touched once per kernel (parameters in the update, the fp32 gradient of a large FC
+// layer) is read and written with the non-temporal hint so it does not displace reusable lines from the caches.
+typedef float lpm_f4 __attribute__((ext_vector_type(4)));
+typedef unsigned int lpm_u2 __attribute__((ext_vector_type(2)));
+typedef unsigned int lpm_u4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 ld_stream(const float4* a) {
+    const lpm_f4 t = __builtin_nontemporal_load(reinterpret_cast<const lpm_f4*>(a));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ uint4 ld_stream(const uint4* a) {
+    const lpm_u4 t = __builtin_nontemporal_load(reinterpret_cast<const lpm_u4*>(a));
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ void st_stream(float4* a, float4 x) {
+    const lpm_f4 t = {x.x, x.y, x.z, x.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<lpm_f4*>(a));
+}
+__device__ __forceinline__ void st_stream(uint2* a, uint2 x) {
+    const lpm_u2 t = {x.x, x.y};
+    __builtin_nontemporal_store(t, reinterpret_cast<lpm_u2*>(a));
+}
+
 __device__ __forceinline__ float ld(const float* p, int64_t i) { return p[i]; }
 __device__ __forceinline__ float ld(const bf16_t* p, int64_t i) { return bf2f(p[i].bits); }
 __device__ __forceinline__ void st(float* p, int64_t i, float v) { p[i] = v; }
