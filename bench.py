@@ -246,6 +246,27 @@ def main():
         roof["step_contraction_flops"] = tot_flops
         roof["step_frac_of_mfma_peak"] = round(tot_flops / (ms_step * 1e-3) / (PEAK["mfma_bf16"] if dtype == lpm.BF16 else PEAK["fp32"]), 5)
 
+    # ---- cost-model feedback (eq. 10 with measured operation times): re-plan from the measured contraction
+    # times (layers without a contraction keep their analytic cost) and time the step under that plan
+    replan = None
+    if table and fixed != "stage_boundaries" and Z > 1:
+        meas = [0] * len(layers)
+        for r in table:
+            meas[r["layer"]] += int(round(r["us"] * 1e6))
+        costs = [meas[i] if meas[i] > 0 else lpm.lpm_layer_cost(layers, i, cp) for i in range(len(layers))]
+        starts2, cost2 = lpm.lpm_partition_costs(layers, Z, cp, costs)
+        replan = {"plan": starts2, "stage_cost_ps": [int(c) for c in cost2],
+                  "model_plan_stage_cost_ps": [int(c) for c in lpm.lpm_partition_costs(layers, Z, cp, costs, starts)[1]]}
+        if starts2 != starts:
+            del net
+            torch.cuda.empty_cache()
+            net = lpm.Net(layers, starts2, m, M, dtype, window=2, dx_wanted=dx_wanted)
+            net.load_params(params, mom)
+            mode = lpm.OVERLAPPED if sched == "overlapped" else lpm.PIPELINED
+            replan["ms_per_step"] = round(timed(mode | (lpm.GRAPH if best == "graph" else 0), args.steps) / args.steps * 1e3, 4)
+        else:
+            replan["ms_per_step"] = round(ms_step, 4)
+
     # ---- the oracle on the host cores, on a bounded sample of the same workload
     cpu = None
     if not args.no_cpu_baseline:
@@ -280,6 +301,7 @@ def main():
         "ms_per_step_by_launch_mode": {k: {m: round(t / args.steps * 1e3, 4) for m, t in v.items()} for k, v in res.items()},
         "overlap_speedup": round(t_locked / t_over, 4),
         "partitions": part,
+        "plan_from_measured_costs": replan,
         "roofline": roof,
         "cpu_baseline": cpu,
     }

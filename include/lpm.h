@@ -130,6 +130,15 @@ int32_t lpm_layer_cost(const lpm_layer* layers, int32_t L, int32_t i, const lpm_
 int32_t lpm_partition(const lpm_layer* layers, int32_t L, int32_t Z, const lpm_cost_params* cp,
                       const int32_t* fixed_starts, int32_t* out_starts, uint64_t* out_stage_cost);
 
+/* The same plan from per-layer costs the caller supplies -- the cost model (eq. 10) asks for the times
+ * T(F_ij), T(B_ij) of the operations; here they can be measured ones.  layer_cost_ps: host array of L
+ * costs in picoseconds (forward + backward of one micro-batch, plus the layer's share of the update),
+ * used in place of the analytic per-layer cost; cp still supplies the micro-batch size, element size and
+ * link rate for the boundary terms.  Everything else as lpm_partition.  Errors: as lpm_partition. */
+int32_t lpm_partition_costs(const lpm_layer* layers, int32_t L, int32_t Z, const lpm_cost_params* cp,
+                            const uint64_t* layer_cost_ps, const int32_t* fixed_starts, int32_t* out_starts,
+                            uint64_t* out_stage_cost);
+
 /* Create the stage that owns layers [first, last) of the network for micro-batches of `microbatch`
  * samples (a sub-module z of Layer-wise Partitioning and Merging).
  *   layers  host, the WHOLE network (L entries); copied.

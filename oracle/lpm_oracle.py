@@ -426,13 +426,19 @@ def boundary_bytes(layers, i, m, elem_bytes):
     return co * ho * wo * m * elem_bytes
 
 
-def plan_cost(layers, starts, cp):
+def plan_cost(layers, starts, cp, layer_costs=None):
     """(per-stage costs, total boundary bytes) of a plan.  cp: dict with flop_per_us, hbm_byte_per_us,
     link_byte_per_us (0 = ignore transfers), elem_bytes, microbatch, n_microbatch.
     A stage's cost is the sum of its layers' costs (eq. 10 is additive) plus, when link_byte_per_us > 0,
-    2*bytes*1e6 // link for each of its boundaries (activation forward and gradient backward)."""
+    2*bytes*1e6 // link for each of its boundaries (activation forward and gradient backward).
+    layer_costs: per-layer costs given by the caller (eq. 10's T(F), T(B) as measured times, integer
+    picoseconds) in place of the analytic per-layer model."""
     m, M, e = cp["microbatch"], cp["n_microbatch"], cp["elem_bytes"]
-    c = [layer_cost(layers, i, m, M, e, cp["flop_per_us"], cp["hbm_byte_per_us"]) for i in range(len(layers))]
+    if layer_costs is not None:
+        c = [int(v) for v in layer_costs]
+        assert len(c) == len(layers)
+    else:
+        c = [layer_cost(layers, i, m, M, e, cp["flop_per_us"], cp["hbm_byte_per_us"]) for i in range(len(layers))]
     Z = len(starts) - 1
     costs, tot = [], 0
     for z in range(Z):
@@ -447,7 +453,7 @@ def plan_cost(layers, starts, cp):
     return costs, tot
 
 
-def plan_bruteforce(layers, Z, cp):
+def plan_bruteforce(layers, Z, cp, layer_costs=None):
     """The plan by exhaustive enumeration: among all ways of cutting the layer list into Z non-empty
     contiguous stages at allowed cut points, the one minimising, lexicographically,
     (largest stage cost, total boundary bytes, starts).  Reading of the partition-and-merge objective:
@@ -458,7 +464,7 @@ def plan_bruteforce(layers, Z, cp):
     best = None
     for cuts in itertools.combinations(allowed, Z - 1):
         starts = [0] + list(cuts) + [L]
-        costs, bb = plan_cost(layers, starts, cp)
+        costs, bb = plan_cost(layers, starts, cp, layer_costs)
         key = (max(costs), bb, starts)
         if best is None or key < best[0]:
             best = (key, starts, costs)

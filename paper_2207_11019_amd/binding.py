@@ -10,7 +10,7 @@ import os
 import numpy as np
 
 __all__ = ["LpmError", "lib", "lpm_conv_geom", "lpm_conv_ws_bytes", "lpm_conv_forward", "lpm_conv_dgrad", "lpm_conv_wgrad", "lpm_conv_time", "lpm_layer", "lpm_cost_params", "lpm_stage_buffers", "layers_from_dicts",
-           "lpm_layer_cost", "lpm_partition", "Stage", "Schedule", "Net", "F32", "BF16", "LOCKED", "OVERLAPPED", "PIPELINED",
+           "lpm_layer_cost", "lpm_partition", "lpm_partition_costs", "Stage", "Schedule", "Net", "F32", "BF16", "LOCKED", "OVERLAPPED", "PIPELINED",
            "GRAPH", "pack_act", "unpack_act", "pack_weight", "unpack_weight", "MI355X_COST"]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -59,6 +59,8 @@ _psz = C.POINTER(C.c_size_t)
 lib.lpm_layer_cost.argtypes = [C.POINTER(lpm_layer), _i32, _i32, C.POINTER(lpm_cost_params), C.POINTER(C.c_uint64)]
 lib.lpm_partition.argtypes = [C.POINTER(lpm_layer), _i32, _i32, C.POINTER(lpm_cost_params), C.POINTER(_i32),
                               C.POINTER(_i32), C.POINTER(C.c_uint64)]
+lib.lpm_partition_costs.argtypes = [C.POINTER(lpm_layer), _i32, _i32, C.POINTER(lpm_cost_params), C.POINTER(C.c_uint64),
+                                    C.POINTER(_i32), C.POINTER(_i32), C.POINTER(C.c_uint64)]
 lib.lpm_stage_create.argtypes = [C.POINTER(lpm_layer), _i32, _i32, _i32, _i32, _i32, C.POINTER(_vp)]
 lib.lpm_stage_destroy.argtypes = [_vp]
 lib.lpm_stage_sizes.argtypes = [_vp] + [_psz] * 8
@@ -79,7 +81,7 @@ lib.lpm_conv_dgrad.argtypes = [C.POINTER(lpm_conv_geom), _i32, _vp, _vp, _vp, _v
 lib.lpm_conv_wgrad.argtypes = [C.POINTER(lpm_conv_geom), _i32, _vp, _vp, _vp, _i32, _vp, _vp]
 lib.lpm_conv_time.argtypes = [_i32, C.POINTER(lpm_conv_geom), _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp,
                               C.POINTER(C.c_float)]
-for _f in ("lpm_conv_time", "lpm_conv_ws_bytes", "lpm_conv_forward", "lpm_conv_dgrad", "lpm_conv_wgrad", "lpm_layer_cost", "lpm_partition", "lpm_stage_create", "lpm_stage_destroy", "lpm_stage_sizes",
+for _f in ("lpm_conv_time", "lpm_conv_ws_bytes", "lpm_conv_forward", "lpm_conv_dgrad", "lpm_conv_wgrad", "lpm_layer_cost", "lpm_partition", "lpm_partition_costs", "lpm_stage_create", "lpm_stage_destroy", "lpm_stage_sizes",
            "lpm_stage_param_offset", "lpm_stage_stash_offset", "lpm_stage_grad_offset", "lpm_stage_sync_lowp",
            "lpm_stage_forward", "lpm_stage_backward", "lpm_stage_update", "lpm_schedule_create",
            "lpm_schedule_destroy", "lpm_schedule_run"):
@@ -135,6 +137,24 @@ def lpm_partition(layers, Z, cp, fixed_starts=None):
             raise LpmError(-1, "fixed_starts needs Z+1 entries")
         fixed = (C.c_int32 * (Z + 1))(*fixed_starts)
     _check(lib.lpm_partition(arr, len(arr), Z, C.byref(c), fixed, starts, cost))
+    return list(starts), list(cost)
+
+
+def lpm_partition_costs(layers, Z, cp, layer_cost_ps, fixed_starts=None):
+    """The plan from caller-supplied per-layer costs (integer picoseconds) -> (starts[Z+1], stage_cost[Z])"""
+    arr = _as_layers(layers)
+    c = _cp(cp)
+    if len(layer_cost_ps) != len(arr):
+        raise LpmError(-1, "layer_cost_ps needs one entry per layer")
+    costs = (C.c_uint64 * len(arr))(*[int(v) for v in layer_cost_ps])
+    starts = (C.c_int32 * (Z + 1))()
+    cost = (C.c_uint64 * Z)()
+    fixed = None
+    if fixed_starts is not None:
+        if len(fixed_starts) != Z + 1:
+            raise LpmError(-1, "fixed_starts needs Z+1 entries")
+        fixed = (C.c_int32 * (Z + 1))(*fixed_starts)
+    _check(lib.lpm_partition_costs(arr, len(arr), Z, C.byref(c), costs, fixed, starts, cost))
     return list(starts), list(cost)
 
 

@@ -313,11 +313,7 @@ static IgemmPlan plan_igemm(int64_t M, int N, int Ktot, int ci) {
     s = (int)std::min<int64_t>(s, std::max<int64_t>(1, cap));
     s = std::min(s, pl.kt_total);
     pl.splits = std::max(1, s);
-#ifdef LPM_TUNE      // measurement builds only: override the plan from the environment
-    if (const char* e = getenv("LPM_T_BIG")) { pl.big = atoi(e); }
-    if (const char* e = getenv("LPM_T_BK")) { if (ci % atoi(e) == 0) pl.bk = atoi(e); }
-    if (pl.big && pl.bk > 64) pl.bk = 64;
-    pl.kt_total = Ktot / pl.bk;
+#ifdef LPM_TUNE      // measurement builds only: override the split count from the environment
     if (const char* e = getenv("LPM_T_SPLITS")) { pl.splits = std::max(1, std::min(atoi(e), pl.kt_total)); }
 #endif
     pl.kt_per = (pl.kt_total + pl.splits - 1) / pl.splits;
@@ -327,22 +323,33 @@ static IgemmPlan plan_igemm(int64_t M, int N, int Ktot, int ci) {
 
 template <int MODE>
 static void launch_igemm_cfg(const IgemmPlan& pl, const IgemmArgs& a, hipStream_t st) {
-#ifdef LPM_TUNE
-    if (pl.big) {
-        const dim3 grid((unsigned)(((a.M + 127) / 128) * ((a.N + 127) / 128)), 1, pl.splits);
-        if (pl.bk == 64) hipLaunchKernelGGL((igemm_kernel<128, 128, 64, 2, 2, MODE>), grid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((igemm_kernel<128, 128, 32, 2, 2, MODE>), grid, dim3(256), 0, st, a);
-    } else
-#endif
-    {
-        const dim3 grid((unsigned)(((a.M + 63) / 64) * ((a.N + 63) / 64)), 1, pl.splits);
-#ifdef LPM_TUNE
-        if (pl.bk == 128) hipLaunchKernelGGL((igemm_kernel<64, 64, 128, 2, 2, MODE>), grid, dim3(256), 0, st, a);
-        else
-#endif
-        if (pl.bk == 64) hipLaunchKernelGGL((igemm_kernel<64, 64, 64, 2, 2, MODE>), grid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((igemm_kernel<64, 64, 32, 2, 2, MODE>), grid, dim3(256), 0, st, a);
+#ifdef LPM_TUNE      // measurement builds only: other block / wavefront tile shapes, chosen from the environment
+    if (MODE != MODE_DGRAD_S && a.Ci % 64 == 0) {
+        const int cfg = getenv("LPM_T_CFG") ? atoi(getenv("LPM_T_CFG")) : 0;
+#define LPM_CFG(ID, BM_, BN_, BK_, WGM_, WGN_)                                                                      \
+        if (cfg == ID) {                                                                                            \
+            const dim3 grid((unsigned)(((a.M + BM_ - 1) / BM_) * ((a.N + BN_ - 1) / BN_)), 1, pl.splits);           \
+            IgemmArgs b = a;                                                                                        \
+            b.kt_total = a.Ktot / BK_;                                                                              \
+            b.kt_per_split = (b.kt_total + pl.splits - 1) / pl.splits;                                              \
+            hipLaunchKernelGGL((igemm_kernel<BM_, BN_, BK_, WGM_, WGN_, MODE>), grid, dim3(256), 0, st, b);          \
+            return;                                                                                                 \
+        }
+        LPM_CFG(1, 128, 64, 64, 4, 1)
+        LPM_CFG(2, 128, 64, 64, 2, 2)
+        LPM_CFG(3, 64, 128, 64, 1, 4)
+        LPM_CFG(4, 128, 128, 64, 2, 2)
+        LPM_CFG(5, 128, 128, 32, 2, 2)
+        LPM_CFG(6, 256, 64, 32, 4, 1)
+        LPM_CFG(7, 128, 128, 64, 4, 1)
+        LPM_CFG(8, 256, 128, 32, 4, 1)
+        LPM_CFG(9, 256, 128, 32, 2, 2)
+#undef LPM_CFG
     }
+#endif
+    const dim3 grid((unsigned)(((a.M + 63) / 64) * ((a.N + 63) / 64)), 1, pl.splits);
+    if (pl.bk == 64) hipLaunchKernelGGL((igemm_kernel<64, 64, 64, 2, 2, MODE>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((igemm_kernel<64, 64, 32, 2, 2, MODE>), grid, dim3(256), 0, st, a);
 }
 
 static hipError_t run_igemm(int mode, IgemmArgs a, void* ws, hipStream_t st) {

@@ -154,8 +154,8 @@ extern "C" int32_t lpm_layer_cost(const lpm_layer* layers, int32_t L, int32_t i,
     return LPM_OK;
 }
 
-extern "C" int32_t lpm_partition(const lpm_layer* layers, int32_t L, int32_t Z, const lpm_cost_params* cp,
-                                 const int32_t* fixed_starts, int32_t* out_starts, uint64_t* out_stage_cost) {
+static int32_t plan(const lpm_layer* layers, int32_t L, int32_t Z, const lpm_cost_params* cp, const uint64_t* given_cost,
+                    const int32_t* fixed_starts, int32_t* out_starts, uint64_t* out_stage_cost) {
     std::vector<lpm_layer> net;
     std::vector<Shape> shapes;
     int32_t rc = validate_network(layers, L, net, shapes);
@@ -169,7 +169,9 @@ extern "C" int32_t lpm_partition(const lpm_layer* layers, int32_t L, int32_t Z, 
     P.prefix.assign((size_t)L + 1, 0);
     P.cut_bytes.assign(L, 0); P.cut_time.assign(L, 0); P.allowed.assign(L, 0);
     for (int32_t i = 0; i < L; ++i) {
-        P.prefix[i + 1] = P.prefix[i] + layer_cost(net, shapes, i, *cp);
+        const uint64_t c = given_cost ? given_cost[i] : layer_cost(net, shapes, i, *cp);
+        if (P.prefix[i] + c < P.prefix[i]) return fail(LPM_EINVAL, "layer costs overflow 64 bits");
+        P.prefix[i + 1] = P.prefix[i] + c;
         P.cut_bytes[i] = (uint64_t)shapes[(size_t)i + 1].elems() * (uint64_t)cp->microbatch * (uint64_t)cp->elem_bytes;
         if (cp->link_byte_per_us > 0)
             P.cut_time[i] = (uint64_t)((u128)2 * P.cut_bytes[i] * 1000000u / cp->link_byte_per_us);
@@ -235,4 +237,16 @@ extern "C" int32_t lpm_partition(const lpm_layer* layers, int32_t L, int32_t Z, 
     if (out_stage_cost)
         for (int32_t z = 0; z < Z; ++z) out_stage_cost[z] = P.stage_cost(starts[z], starts[z + 1]);
     return LPM_OK;
+}
+
+extern "C" int32_t lpm_partition(const lpm_layer* layers, int32_t L, int32_t Z, const lpm_cost_params* cp,
+                                 const int32_t* fixed_starts, int32_t* out_starts, uint64_t* out_stage_cost) {
+    return plan(layers, L, Z, cp, nullptr, fixed_starts, out_starts, out_stage_cost);
+}
+
+extern "C" int32_t lpm_partition_costs(const lpm_layer* layers, int32_t L, int32_t Z, const lpm_cost_params* cp,
+                                       const uint64_t* layer_cost_ps, const int32_t* fixed_starts, int32_t* out_starts,
+                                       uint64_t* out_stage_cost) {
+    if (!layer_cost_ps) return fail(LPM_EINVAL, "layer_cost_ps is NULL");
+    return plan(layers, L, Z, cp, layer_cost_ps, fixed_starts, out_starts, out_stage_cost);
 }

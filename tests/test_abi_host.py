@@ -82,6 +82,35 @@ def test_plans_on_random_chains(lpm):
         assert e.value.code in (-6, -1)
 
 
+def test_plans_from_supplied_costs(lpm):
+    """The cost model with caller-supplied (measured) per-layer costs: the library's DP equals the oracle's
+    enumeration with the same costs; a hand case pins the oracle itself (costs 5,1,1,1,5,1 into 3 stages:
+    the two heavy layers must be separated, bottleneck 6; ties go to the smallest starts)."""
+    L = [dict(kind="conv", cin=8, cout=8, kh=1, kw=1, stride=1, pad=0, h_in=2, w_in=2, relu=False, bias=False,
+              scale=False, src=i - 1, add_src=None, cut_after=True) for i in range(6)]
+    cp = _cp("bf16", 1, 1, 0)
+    costs = [5, 1, 1, 1, 5, 1]
+    so, co_ = orc.plan_bruteforce(L, 3, cp, layer_costs=costs)
+    assert so == [0, 1, 4, 6] and co_ == [5, 3, 6]
+    starts, sc = lpm.lpm_partition_costs(L, 3, cp, costs)
+    assert starts == so and sc == co_
+    # given costs equal to the analytic ones reproduce lpm_partition
+    an = [lpm.lpm_layer_cost(L, i, cp) for i in range(6)]
+    assert lpm.lpm_partition_costs(L, 3, cp, an) == lpm.lpm_partition(L, 3, cp)
+    r = np.random.default_rng(1)
+    for name in ("lenet", "vgg16_cifar", "resnet18_cifar"):
+        builder, batch, M, Z, dt, _ = wl.CONFIGS[name]
+        layers = builder()
+        cpn = _cp(dt, batch // M, M, 0)
+        for trial in range(3):
+            costs = [int(v) for v in r.integers(1, 1000, len(layers))]
+            starts, sc = lpm.lpm_partition_costs(layers, Z, cpn, costs)
+            so, co_ = orc.plan_bruteforce(layers, Z, cpn, layer_costs=costs)
+            assert starts == so and sc == co_, (name, trial)
+    with pytest.raises(lpm.LpmError):
+        lpm.lpm_partition_costs(L, 3, cp, [1, 2, 3])
+
+
 def test_error_codes(lpm):
     L = wl.lenet()
     cp = _cp("f32", 8, 4)
