@@ -385,6 +385,119 @@ def run_schedule(layers, starts, params, momentum, x, labels, g_up, M, lr, mu, m
     return out
 
 
+# --------------------------------------------------------------------------- asynchronous update
+
+def weight_version_read_by_forward(j, window):
+    """Index of the weight version F_{z,j} reads under the asynchronous update.
+
+    Reading of "asynchronous parameter update" (Forward Pass and Backward Pass Parallelisation and
+    Optimisation): every micro-batch updates the weights, U_{z,j} right after B_{z,j}; version 0 is the
+    state at the start of the step and U_{z,j} turns version j into version j+1.  A forward pass that
+    overlaps the backward pass of the previous micro-batch cannot see that micro-batch's update, so
+    with `window` micro-batches in flight F_{z,j} reads version max(0, j - (window - 1)): no delay
+    for window 1 (plain per-micro-batch SGD), one update behind for window 2.  B_{z,j} runs after
+    U_{z,j-1} and reads version j for its data gradients (no weight stashing), its activations are
+    the ones F_{z,j} stored."""
+    return max(0, j - (window - 1))
+
+
+def schedule_ops_async(Z, M, window=2, locked=False):
+    """Operation set and dependencies with one update per micro-batch: ('F',z,j), ('B',z,j), ('U',z,j).
+    locked: the single chain F_{0,j}..F_{Z-1,j}, then B_{z,j}, U_{z,j} for z = Z-1..0, for j = 0..M-1.
+    Otherwise F_{z,j} after F_{z-1,j}, F_{z,j-1} and U_{z,j-window}; B_{z,j} after B_{z+1,j} (F_{Z-1,j} for
+    the last stage) and U_{z,j-1}; U_{z,j} after B_{z,j}."""
+    deps = {}
+    if locked:
+        chain = []
+        for j in range(M):
+            chain += [("F", z, j) for z in range(Z)]
+            for z in range(Z - 1, -1, -1):
+                chain += [("B", z, j), ("U", z, j)]
+        for a, b in zip([None] + chain[:-1], chain):
+            deps[b] = set() if a is None else {a}
+        return deps
+    for j in range(M):
+        for z in range(Z):
+            d = set()
+            if z > 0:
+                d.add(("F", z - 1, j))
+            if j > 0:
+                d.add(("F", z, j - 1))
+            if j >= window:
+                d.add(("U", z, j - window))
+            deps[("F", z, j)] = d
+            d = {("B", z + 1, j)} if z < Z - 1 else {("F", Z - 1, j)}
+            if j > 0:
+                d.add(("U", z, j - 1))
+            deps[("B", z, j)] = d
+            deps[("U", z, j)] = {("B", z, j)}
+    return deps
+
+
+def run_schedule_async(layers, starts, params, momentum, x, labels, g_up, M, lr, mu, window=2, locked=False,
+                       order_rng=None, input_grad=False, store=None):
+    """One pass over the mini-batch with an update after every micro-batch (see
+    weight_version_read_by_forward).  Each micro-batch is a mini-batch of its own: its loss is the mean
+    over its m samples.  At most two weight versions of a stage are alive at any time (asserted: an
+    older one is dropped when a new one is made, and reading a dropped version fails).  Ops run in a
+    legal order of schedule_ops_async (randomised when order_rng is given); the result does not
+    depend on it.  params and momentum are updated in place to the final version; returns
+    dict(loss = sum of the micro-batches' mean losses, grads = gradient of the last micro-batch)."""
+    import copy
+    Z = len(starts) - 1
+    b = x.shape[0]
+    assert b % M == 0
+    m = b // M
+    w_eff = 1 if locked else window
+    deps = schedule_ops_async(Z, M, window, locked)
+    order = legal_order(deps, order_rng)
+    ver = [{0: {i: copy.deepcopy(params[i]) for i in range(starts[z], starts[z + 1]) if i in params}} for z in range(Z)]
+    slots = [[None] * max(window, 1) for _ in range(Z)]
+    act, gin, gr = {}, {}, {}
+    done = set()
+    loss = 0.0
+    for op in order:
+        assert deps[op] <= done, ("dependency violated", op)
+        _, z, j = op
+        first, last = starts[z], starts[z + 1]
+        if op[0] == "F":
+            P = ver[z][weight_version_read_by_forward(j, w_eff)]
+            a_in = x[j * m:(j + 1) * m] if z == 0 else act[(z - 1, j)]
+            lab = labels[j * m:(j + 1) * m] if (labels is not None and z == Z - 1) else None
+            a_out, stash, lp = stage_forward(layers, first, last, P, a_in, lab, m, store)
+            s = j % len(slots[z])
+            assert slots[z][s] is None, ("stash slot overwritten while live", op)
+            slots[z][s] = (j, stash)
+            act[(z, j)] = a_out
+            if lp is not None:
+                loss += lp
+        elif op[0] == "B":
+            P = ver[z][j]
+            s = j % len(slots[z])
+            assert slots[z][s] is not None and slots[z][s][0] == j, ("stash missing", op)
+            if z == Z - 1:
+                g_out = None if labels is not None else g_up[j * m:(j + 1) * m]
+            else:
+                g_out = gin[(z + 1, j)]
+            g = zero_grads(layers, P)
+            gin[(z, j)] = stage_backward(layers, first, last, P, slots[z][s][1], g_out, g, input_grad=(z > 0 or input_grad))
+            slots[z][s] = None
+            gr[(z, j)] = g
+        else:
+            new = copy.deepcopy(ver[z][j])
+            sgd_momentum(new, gr[(z, j)], momentum, lr, mu, first, last)
+            ver[z][j + 1] = new
+            ver[z].pop(j - 1, None)          # two versions alive: j and j+1
+            assert len(ver[z]) <= 2
+        done.add(op)
+    grads = {}
+    for z in range(Z):
+        for i, p in ver[z][M].items():
+            params[i] = p
+        grads.update(gr[(z, M - 1)])
+    return dict(loss=loss, grads=grads, order=order)
+
+
 # --------------------------------------------------------------------------- cost model and plan
 
 def layer_cost(layers, i, m, M, elem_bytes, flop_per_us, hbm_byte_per_us):
