@@ -76,6 +76,7 @@ extern "C" {
 #define LPM_OVERLAPPED  1   /* forward chain of micro-batch j+1 runs beside the backward chain of j        */
 #define LPM_PIPELINED   2   /* as OVERLAPPED, and every stage runs on its own pair of streams (owned by the
                                schedule): stages work on different micro-batches at the same time         */
+#define LPM_ASYNC_UPDATE 32  /* OR-ed into LOCKED or OVERLAPPED: one update per micro-batch (see lpm_schedule_run) */
 #define LPM_GRAPH       16  /* OR-ed into mode: replay the step as a captured HIP graph                    */
 
 /* One layer a^{l+1} = g_l(a^l, p^l).  Tensor index t means "output of layer t"; t = -1 is the
@@ -219,6 +220,8 @@ typedef struct lpm_stage_buffers {
     void*  act_out[LPM_MAX_WINDOW]; /* stage output ring (logits for the loss stage), out_bytes each */
     void*  grad_in[LPM_MAX_WINDOW]; /* gradient w.r.t. the stage input, in_bytes each; may be NULL for stage 0 */
     void*  fwd_ws;  void* bwd_ws;
+    float* params_alt;  void* lowp_alt;   /* second weight version (same sizes as params / lowp) for
+                                             LPM_ASYNC_UPDATE, frozen scales filled in like params; else NULL */
 } lpm_stage_buffers;
 
 /* A schedule over Z stages that form one network, M micro-batches per mini-batch, at most `window`
@@ -243,6 +246,14 @@ int32_t lpm_schedule_destroy(lpm_schedule* s);
  *   stream_fwd, stream_bwd  two distinct streams for LPM_OVERLAPPED; LPM_LOCKED and LPM_PIPELINED use
  *              stream_fwd only (PIPELINED forks its own streams from it and joins them back).
  * Micro-batch j uses slot j % window of stash, act_out and grad_in in every mode.
+ * mode | LPM_ASYNC_UPDATE (with LPM_LOCKED or LPM_OVERLAPPED, window <= 2, not with LPM_GRAPH): the
+ *   asynchronous parameter update.  Every micro-batch is a mini-batch of its own (loss = mean over its m
+ *   samples) and U_{z,j} follows B_{z,j}; version 0 of a stage's weights is the state at the start of the call
+ *   and U_{z,j} turns version j into version j+1.  B_{z,j} reads version j.  F_{z,j} reads version j when
+ *   nothing overlaps (LPM_LOCKED, or window 1) and version max(0, j-1) with window 2, where it runs beside
+ *   B_{z,j-1}: one update behind.  Even versions live in params / lowp, odd ones in params_alt / lowp_alt;
+ *   on return the final version (n_microbatch) is in params / lowp (copied there if n_microbatch is odd),
+ *   grads holds the gradient of the last micro-batch and loss_out the sum of the micro-batches' mean losses.
  * On return all work is enqueued and stream_fwd is ordered after everything the call enqueued.
  * Results are bitwise identical between the modes (fixed accumulation order, no float atomics).
  * Errors: LPM_EINVAL, LPM_EALIGN, LPM_EHIP. */

@@ -435,14 +435,17 @@ def schedule_ops_async(Z, M, window=2, locked=False):
 
 
 def run_schedule_async(layers, starts, params, momentum, x, labels, g_up, M, lr, mu, window=2, locked=False,
-                       order_rng=None, input_grad=False, store=None):
+                       order_rng=None, input_grad=False, store=None, wstore=None):
     """One pass over the mini-batch with an update after every micro-batch (see
     weight_version_read_by_forward).  Each micro-batch is a mini-batch of its own: its loss is the mean
     over its m samples.  At most two weight versions of a stage are alive at any time (asserted: an
     older one is dropped when a new one is made, and reading a dropped version fails).  Ops run in a
     legal order of schedule_ops_async (randomised when order_rng is given); the result does not
     depend on it.  params and momentum are updated in place to the final version; returns
-    dict(loss = sum of the micro-batches' mean losses, grads = gradient of the last micro-batch)."""
+    dict(loss = sum of the micro-batches' mean losses, grads = gradient of the last micro-batch).
+    wstore: optional function applied to the weight tensors 'W' the layers compute with (e.g. round_bf16:
+    the bf16 workloads compute from a bfloat16 copy of the full-precision master weights, which the update
+    refreshes; within the synchronous step that copy never changes, here it does after every update)."""
     import copy
     Z = len(starts) - 1
     b = x.shape[0]
@@ -461,7 +464,7 @@ def run_schedule_async(layers, starts, params, momentum, x, labels, g_up, M, lr,
         _, z, j = op
         first, last = starts[z], starts[z + 1]
         if op[0] == "F":
-            P = ver[z][weight_version_read_by_forward(j, w_eff)]
+            P = _compute_copy(ver[z][weight_version_read_by_forward(j, w_eff)], wstore)
             a_in = x[j * m:(j + 1) * m] if z == 0 else act[(z - 1, j)]
             lab = labels[j * m:(j + 1) * m] if (labels is not None and z == Z - 1) else None
             a_out, stash, lp = stage_forward(layers, first, last, P, a_in, lab, m, store)
@@ -472,7 +475,7 @@ def run_schedule_async(layers, starts, params, momentum, x, labels, g_up, M, lr,
             if lp is not None:
                 loss += lp
         elif op[0] == "B":
-            P = ver[z][j]
+            P = _compute_copy(ver[z][j], wstore)
             s = j % len(slots[z])
             assert slots[z][s] is not None and slots[z][s][0] == j, ("stash missing", op)
             if z == Z - 1:
@@ -496,6 +499,13 @@ def run_schedule_async(layers, starts, params, momentum, x, labels, g_up, M, lr,
             params[i] = p
         grads.update(gr[(z, M - 1)])
     return dict(loss=loss, grads=grads, order=order)
+
+
+def _compute_copy(P, wstore):
+    """The weights the layers compute with: the master version, or its stored (rounded) copy."""
+    if wstore is None:
+        return P
+    return {i: {k: (wstore(v) if k == "W" else v) for k, v in p.items()} for i, p in P.items()}
 
 
 # --------------------------------------------------------------------------- cost model and plan

@@ -10,7 +10,7 @@ import os
 import numpy as np
 
 __all__ = ["LpmError", "lib", "lpm_conv_geom", "lpm_conv_ws_bytes", "lpm_conv_forward", "lpm_conv_dgrad", "lpm_conv_wgrad", "lpm_conv_time", "lpm_layer", "lpm_cost_params", "lpm_stage_buffers", "layers_from_dicts",
-           "lpm_layer_cost", "lpm_partition", "lpm_partition_costs", "Stage", "Schedule", "Net", "F32", "BF16", "LOCKED", "OVERLAPPED", "PIPELINED",
+           "lpm_layer_cost", "lpm_partition", "lpm_partition_costs", "Stage", "Schedule", "Net", "F32", "BF16", "LOCKED", "OVERLAPPED", "PIPELINED", "ASYNC_UPDATE",
            "GRAPH", "pack_act", "unpack_act", "pack_weight", "unpack_weight", "MI355X_COST"]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -20,7 +20,7 @@ if not os.path.exists(_LIB):
 lib = C.CDLL(_LIB)
 
 F32, BF16 = 0, 1
-LOCKED, OVERLAPPED, PIPELINED, GRAPH = 0, 1, 2, 16
+LOCKED, OVERLAPPED, PIPELINED, GRAPH, ASYNC_UPDATE = 0, 1, 2, 16, 32
 KINDS = {"conv": 0, "fc": 1, "maxpool2": 2, "gap": 3, "softmax_ce": 4}
 RELU, BIAS, SCALE = 1, 2, 4
 NONE = -2
@@ -46,7 +46,7 @@ class lpm_cost_params(C.Structure):
 class lpm_stage_buffers(C.Structure):
     _fields_ = [("params", C.c_void_p), ("lowp", C.c_void_p), ("grads", C.c_void_p), ("momentum", C.c_void_p),
                 ("stash", C.c_void_p * MAX_WINDOW), ("act_out", C.c_void_p * MAX_WINDOW), ("grad_in", C.c_void_p * MAX_WINDOW),
-                ("fwd_ws", C.c_void_p), ("bwd_ws", C.c_void_p)]
+                ("fwd_ws", C.c_void_p), ("bwd_ws", C.c_void_p), ("params_alt", C.c_void_p), ("lowp_alt", C.c_void_p)]
 
 
 class lpm_conv_geom(C.Structure):
@@ -352,7 +352,9 @@ class Net:
     layers: list of layer dicts; starts: plan (Z+1 entries); dtype F32/BF16.
     """
 
-    def __init__(self, layers, starts, microbatch, n_microbatch, dtype, window=2, device="cuda:0", dx_wanted=False):
+    def __init__(self, layers, starts, microbatch, n_microbatch, dtype, window=2, device="cuda:0", dx_wanted=False,
+                 async_update=False):
+        """async_update: also allocate the second weight version the ASYNC_UPDATE schedules need."""
         torch = _torch()
         self.torch = torch
         self.layers, self.starts, self.m, self.M, self.dtype, self.window = layers, list(starts), microbatch, n_microbatch, dtype, window
@@ -386,6 +388,9 @@ class Net:
                 cb.act_out[w] = _ptr(b["act_out"][w])
                 cb.grad_in[w] = _ptr(b["grad_in"][w])
             cb.fwd_ws, cb.bwd_ws = _ptr(b["fwd_ws"]), _ptr(b["bwd_ws"])
+            b["params_alt"] = buf(s.param_bytes) if async_update else None
+            b["lowp_alt"] = buf(s.lowp_bytes) if (async_update and dtype == BF16) else None
+            cb.params_alt, cb.lowp_alt = _ptr(b["params_alt"]), _ptr(b["lowp_alt"])
         self.loss = torch.zeros(64, dtype=torch.float32, device=self.device)
         self.stream_fwd, self.stream_bwd = _net_streams(torch, self.device)
 
@@ -434,6 +439,11 @@ class Net:
         if self.dtype == BF16:
             for z, s in enumerate(self.stages):
                 s.sync_lowp(self.bufs[z]["params"], self.bufs[z]["lowp"], None)
+        for b in self.bufs:                       # the second weight version starts as a copy (frozen scales included)
+            if b["params_alt"] is not None:
+                b["params_alt"].copy_(b["params"])
+            if b["lowp_alt"] is not None:
+                b["lowp_alt"].copy_(b["lowp"])
         self.torch.cuda.synchronize(self.device)
 
     def read_params(self):

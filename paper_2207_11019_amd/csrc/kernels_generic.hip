@@ -462,12 +462,13 @@ hipError_t launch_softmax_ce(int dtype, int32_t m, int32_t C, const void* logits
 // update, eq. 6 with momentum: v = mu*v + g; p = p - lr*v; bf16 copy; optional g = 0.  Pure streaming: one
 // float4 per thread, consecutive threads on consecutive addresses, non-temporal accesses (measured at 103 M
 // parameters: 5.9 TB/s against 4.3 TB/s for a grid-stride loop over 4096 blocks).
-__global__ void __launch_bounds__(256) sgd_kernel(float4* __restrict__ p, uint2* __restrict__ lowp, float4* __restrict__ g,
+// (p_in and p_out may be the same buffer: every element is read and written by one thread)
+__global__ void __launch_bounds__(256) sgd_kernel(const float4* p_in, float4* p, uint2* __restrict__ lowp, float4* __restrict__ g,
                                                   float4* __restrict__ v, size_t n4, float lr, float mu, int zero_g) {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n4) return;
     const float4 gg = ld_stream(&g[i]);
-    float4 vv = ld_stream(&v[i]), pp = ld_stream(&p[i]);
+    float4 vv = ld_stream(&v[i]), pp = ld_stream(&p_in[i]);
     vv.x = fmaf(mu, vv.x, gg.x); vv.y = fmaf(mu, vv.y, gg.y); vv.z = fmaf(mu, vv.z, gg.z); vv.w = fmaf(mu, vv.w, gg.w);
     pp.x = fmaf(-lr, vv.x, pp.x); pp.y = fmaf(-lr, vv.y, pp.y); pp.z = fmaf(-lr, vv.z, pp.z); pp.w = fmaf(-lr, vv.w, pp.w);
     st_stream(&v[i], vv);
@@ -476,10 +477,11 @@ __global__ void __launch_bounds__(256) sgd_kernel(float4* __restrict__ p, uint2*
     if (zero_g) st_stream(&g[i], make_float4(0.f, 0.f, 0.f, 0.f));
 }
 
-hipError_t launch_sgd(float* p, uint16_t* lowp, float* g, float* v, size_t n, float lr, float mu, int zero_g, hipStream_t s) {
+hipError_t launch_sgd(const float* p_in, float* p, uint16_t* lowp, float* g, float* v, size_t n, float lr, float mu, int zero_g,
+                      hipStream_t s) {
     const size_t n4 = n / 4;
     if (n4 == 0) return hipSuccess;
-    hipLaunchKernelGGL(sgd_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, (float4*)p, (uint2*)lowp, (float4*)g,
+    hipLaunchKernelGGL(sgd_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, (const float4*)p_in, (float4*)p, (uint2*)lowp, (float4*)g,
                        (float4*)v, n4, lr, mu, zero_g);
     return hipGetLastError();
 }

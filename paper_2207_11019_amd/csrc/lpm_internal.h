@@ -82,8 +82,8 @@ hipError_t launch_gap_bwd(int dtype, int32_t m, int32_t HW, int32_t C, const voi
 // dlogits = (softmax(logits) - onehot) * loss_scale;  *loss_accum += loss_scale * sum_n -log p_n[label_n]
 hipError_t launch_softmax_ce(int dtype, int32_t m, int32_t C, const void* logits, const int32_t* labels,
                              float loss_scale, void* dlogits, float* loss_accum, hipStream_t st);
-// v = mu*v + g; p -= lr*v; lowp[i] = bf16(p[i]) (lowp may be NULL); optionally g = 0.   n % 4 == 0
-hipError_t launch_sgd(float* p, uint16_t* lowp, float* g, float* v, size_t n, float lr, float mu, int zero_g,
+// v = mu*v + g; p = p_in - lr*v (p_in may be p); lowp[i] = bf16(p[i]) (lowp may be NULL); optionally g = 0.   n % 4 == 0
+hipError_t launch_sgd(const float* p_in, float* p, uint16_t* lowp, float* g, float* v, size_t n, float lr, float mu, int zero_g,
                       hipStream_t st);
 hipError_t launch_f32_to_bf16(const float* src, uint16_t* dst, size_t n, hipStream_t st);
 // dst[ci][kh][kw][co] = bf16(src[co][kh][kw][ci])

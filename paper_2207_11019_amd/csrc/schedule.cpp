@@ -156,20 +156,27 @@ struct RunArgs {
     hipStream_t sf, sb;
 };
 
-int32_t fwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStream_t st) {
+// Weight version `ver` of a stage: -1 = the synchronous step (one version, in params / lowp); otherwise even
+// versions live in params / lowp and odd ones in params_alt / lowp_alt (LPM_ASYNC_UPDATE).
+inline float* ver_params(const lpm_stage_buffers& b, int32_t ver) { return (ver > 0 && (ver & 1)) ? b.params_alt : b.params; }
+inline void* ver_lowp(const lpm_stage_buffers& b, int32_t ver) { return (ver > 0 && (ver & 1)) ? b.lowp_alt : b.lowp; }
+
+int32_t fwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStream_t st, int32_t ver = -1) {
     lpm_stage* sg = s->st[(size_t)z];
     const int32_t slot = j % s->window;
     const lpm_stage_buffers& b = a.bufs[z];
     const void* in = z == 0 ? (const void*)((const char*)a.x_batch + (size_t)j * sg->T(sg->first - 1).bytes)
                             : (const void*)a.bufs[z - 1].act_out[slot];
     const int32_t* lab = sg->loss ? a.labels + (size_t)j * sg->m : nullptr;
-    return lpm_stage_forward(sg, in, b.act_out[slot], lab, a.loss_out, b.params, b.lowp, b.stash[slot], b.fwd_ws,
-                             1.0f / (float)(s->M * sg->m), st);
+    // synchronous step: the loss is the mean over the mini-batch; asynchronous update: over the micro-batch
+    const float loss_scale = 1.0f / (float)(ver < 0 ? s->M * sg->m : sg->m);
+    return lpm_stage_forward(sg, in, b.act_out[slot], lab, a.loss_out, ver_params(b, ver), ver_lowp(b, ver), b.stash[slot],
+                             b.fwd_ws, loss_scale, st);
 }
 
 // wst: stream of the weight phase (see lpm_stage_backward_on)
 int32_t bwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStream_t st, hipStream_t wst,
-               int32_t phases = LPM_PHASE_DATA | LPM_PHASE_WEIGHTS) {
+               int32_t phases = LPM_PHASE_DATA | LPM_PHASE_WEIGHTS, int32_t ver = -1) {
     lpm_stage* sg = s->st[(size_t)z];
     const int32_t slot = j % s->window;
     const lpm_stage_buffers& b = a.bufs[z];
@@ -179,14 +186,32 @@ int32_t bwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStrea
     if (z < s->Z - 1) dy = a.bufs[z + 1].grad_in[slot];
     else if (!sg->loss) dy = (const char*)a.dy_batch + (size_t)j * sg->T(sg->t_out).bytes;
     void* dx = (z > 0 || a.dx_wanted) ? b.grad_in[slot] : nullptr;
-    return lpm_stage_backward_on(sg, in, b.act_out[slot], dy, dx, b.params, b.lowp, b.stash[slot], b.grads, j > 0,
-                                 b.bwd_ws, st, wst, j & 1, phases);
+    return lpm_stage_backward_on(sg, in, b.act_out[slot], dy, dx, ver_params(b, ver), ver_lowp(b, ver), b.stash[slot], b.grads,
+                                 ver < 0 ? j > 0 : 0, b.bwd_ws, st, wst, j & 1, phases);
 }
 
-int32_t upd_op(lpm_schedule* s, const RunArgs& a, int32_t z, hipStream_t st) {
+// ver < 0: the one update of the synchronous step; else U_{z,ver}: version ver -> version ver + 1
+int32_t upd_op(lpm_schedule* s, const RunArgs& a, int32_t z, hipStream_t st, int32_t ver = -1) {
     const lpm_stage_buffers& b = a.bufs[z];
-    return lpm_stage_update(s->st[(size_t)z], b.params, b.lowp, b.grads, b.momentum, a.lr, a.mu, 0, st);
+    if (ver < 0) return lpm_stage_update(s->st[(size_t)z], b.params, b.lowp, b.grads, b.momentum, a.lr, a.mu, 0, st);
+    return lpm_stage_update_to(s->st[(size_t)z], ver_params(b, ver), ver_params(b, ver + 1), ver_lowp(b, ver + 1), b.grads,
+                               b.momentum, a.lr, a.mu, 0, st);
 }
+
+// LPM_ASYNC_UPDATE with an odd number of micro-batches leaves the final version in the alternate buffers
+int32_t copy_final_version(lpm_schedule* s, const RunArgs& a, int32_t z, hipStream_t st) {
+    if (!(s->M & 1)) return LPM_OK;
+    lpm_stage* sg = s->st[(size_t)z];
+    const lpm_stage_buffers& b = a.bufs[z];
+    if (sg->n_trainable == 0) return LPM_OK;
+    LPM_HIP(hipMemcpyAsync(b.params, b.params_alt, sg->n_trainable * sizeof(float), hipMemcpyDeviceToDevice, st));
+    if (sg->dtype == LPM_BF16 && sg->lowp_bytes)
+        LPM_HIP(hipMemcpyAsync(b.lowp, b.lowp_alt, sg->lowp_bytes, hipMemcpyDeviceToDevice, st));
+    return LPM_OK;
+}
+
+// version F_{z,j} reads under LPM_ASYNC_UPDATE: one update behind when it overlaps B_{z,j-1}
+inline int32_t forward_version(int32_t j, int32_t overlap_window) { return std::max(0, j - (overlap_window - 1)); }
 
 // ---- enqueue threads.  Launching, not the GPU, bounds a step of small micro-batches, so the decoupled
 // schedules are enqueued by several host threads, each feeding streams of its own.  An event may only be
@@ -269,6 +294,7 @@ int32_t pipelined_role(lpm_schedule* s, const RunArgs& a, int32_t z, uint64_t ep
 // ev_f[j*Z+Z-1]: forward chain j done; ev_b[j*Z+z]: data phase of B_{z,j} done; ev_w[j*Z]: micro-batch j done.
 int32_t overlapped_role(lpm_schedule* s, const RunArgs& a, int32_t role, uint64_t epoch) {
     const int32_t Z = s->Z, M = s->M, W = s->window;
+    const bool async = (a.mode & LPM_ASYNC_UPDATE) != 0;
     hipStream_t sw = s->st[0]->side;
     int32_t rc;
     if (role == 0) {
@@ -279,7 +305,7 @@ int32_t overlapped_role(lpm_schedule* s, const RunArgs& a, int32_t role, uint64_
                 if ((rc = await_record(s, s->rec_w[i], epoch))) return rc;
                 LPM_HIP(hipStreamWaitEvent(a.sf, s->ev_w[i], 0));
             }
-            for (int32_t z = 0; z < Z; ++z) if ((rc = fwd_op(s, a, z, j, a.sf))) return rc;
+            for (int32_t z = 0; z < Z; ++z) if ((rc = fwd_op(s, a, z, j, a.sf, async ? forward_version(j, W) : -1))) return rc;
             LPM_HIP(hipEventRecord(s->ev_f[(size_t)j * Z + Z - 1], a.sf));
             publish(s->rec_f[(size_t)j * Z + Z - 1], epoch);
         }
@@ -294,7 +320,12 @@ int32_t overlapped_role(lpm_schedule* s, const RunArgs& a, int32_t role, uint64_
                 LPM_HIP(hipStreamWaitEvent(a.sb, s->ev_w[(size_t)(j - 2) * Z], 0));
             }
             for (int32_t z = Z - 1; z >= 0; --z) {
-                if ((rc = bwd_op(s, a, z, j, a.sb, sw, LPM_PHASE_DATA))) return rc;
+                if (async && j > 0) {      // B_{z,j} reads version j: after U_{z,j-1} (which has also consumed the bias gradients)
+                    const size_t u = (size_t)(j - 1) * Z + z;
+                    if ((rc = await_record(s, s->rec_w[u], epoch))) return rc;
+                    LPM_HIP(hipStreamWaitEvent(a.sb, s->ev_w[u], 0));
+                }
+                if ((rc = bwd_op(s, a, z, j, a.sb, sw, LPM_PHASE_DATA, async ? j : -1))) return rc;
                 LPM_HIP(hipEventRecord(s->ev_b[(size_t)j * Z + z], a.sb));
                 publish(s->rec_b[(size_t)j * Z + z], epoch);
             }
@@ -305,8 +336,15 @@ int32_t overlapped_role(lpm_schedule* s, const RunArgs& a, int32_t role, uint64_
                 const size_t i = (size_t)j * Z + z;
                 if ((rc = await_record(s, s->rec_b[i], epoch))) return rc;
                 LPM_HIP(hipStreamWaitEvent(sw, s->ev_b[i], 0));
-                if ((rc = bwd_op(s, a, z, j, a.sb, sw, LPM_PHASE_WEIGHTS))) return rc;
-                if (j == M - 1 && (rc = upd_op(s, a, z, sw))) return rc;
+                if ((rc = bwd_op(s, a, z, j, a.sb, sw, LPM_PHASE_WEIGHTS, async ? j : -1))) return rc;
+                if (async) {
+                    if ((rc = upd_op(s, a, z, sw, j))) return rc;
+                    if (j == M - 1 && (rc = copy_final_version(s, a, z, sw))) return rc;
+                    if (z > 0) {           // ev_w[j*Z+z], z > 0: U_{z,j} done (the entry of stage 0 closes the micro-batch below)
+                        LPM_HIP(hipEventRecord(s->ev_w[i], sw));
+                        publish(s->rec_w[i], epoch);
+                    }
+                } else if (j == M - 1 && (rc = upd_op(s, a, z, sw))) return rc;
             }
             LPM_HIP(hipEventRecord(s->ev_w[(size_t)j * Z], sw));
             publish(s->rec_w[(size_t)j * Z], epoch);
@@ -389,6 +427,17 @@ int32_t enqueue(lpm_schedule* s, const RunArgs& a) {
     const bool capturing = (a.mode & LPM_GRAPH) != 0;
     int32_t rc;
     if (s->st[(size_t)Z - 1]->loss) LPM_HIP(launch_fill_f32(a.loss_out, 1, 0.f, a.sf));
+    if ((a.mode & 15) == LPM_LOCKED && (a.mode & LPM_ASYNC_UPDATE)) {      // plain per-micro-batch SGD
+        for (int32_t j = 0; j < M; ++j) {
+            for (int32_t z = 0; z < Z; ++z) if ((rc = fwd_op(s, a, z, j, a.sf, j))) return rc;
+            for (int32_t z = Z - 1; z >= 0; --z) {
+                if ((rc = bwd_op(s, a, z, j, a.sf, a.sf, LPM_PHASE_DATA | LPM_PHASE_WEIGHTS, j))) return rc;
+                if ((rc = upd_op(s, a, z, a.sf, j))) return rc;
+                if (j == M - 1 && (rc = copy_final_version(s, a, z, a.sf))) return rc;
+            }
+        }
+        return LPM_OK;
+    }
     if ((a.mode & 15) == LPM_LOCKED) {
         for (int32_t j = 0; j < M; ++j) {
             for (int32_t z = 0; z < Z; ++z) if ((rc = fwd_op(s, a, z, j, a.sf))) return rc;
@@ -434,7 +483,17 @@ extern "C" int32_t lpm_schedule_run(lpm_schedule* s, int32_t mode, const void* x
                                     float lr, float mu, float* loss_out, void* stream_fwd, void* stream_bwd) {
     if (!s || !x_batch || !per_stage) return fail(LPM_EINVAL, "NULL argument");
     const int32_t base = mode & 15;
-    if ((base != LPM_LOCKED && base != LPM_OVERLAPPED && base != LPM_PIPELINED) || (mode & ~(15 | LPM_GRAPH))) return fail(LPM_EINVAL, "unknown mode %d", mode);
+    if ((base != LPM_LOCKED && base != LPM_OVERLAPPED && base != LPM_PIPELINED) || (mode & ~(15 | LPM_GRAPH | LPM_ASYNC_UPDATE)))
+        return fail(LPM_EINVAL, "unknown mode %d", mode);
+    if (mode & LPM_ASYNC_UPDATE) {
+        if (base == LPM_PIPELINED || (mode & LPM_GRAPH)) return fail(LPM_EINVAL, "LPM_ASYNC_UPDATE goes with LPM_LOCKED or LPM_OVERLAPPED, without LPM_GRAPH");
+        if (s->window > 2) return fail(LPM_EINVAL, "LPM_ASYNC_UPDATE keeps two weight versions: window must be 1 or 2");
+        for (int32_t z = 0; z < s->Z; ++z) {
+            const lpm_stage_buffers& b = per_stage[z];
+            if (!b.params_alt || (s->st[(size_t)z]->dtype == LPM_BF16 && !b.lowp_alt) || ((uintptr_t)b.params_alt & 255u) || ((uintptr_t)b.lowp_alt & 255u))
+                return fail(LPM_EINVAL, "stage %d: LPM_ASYNC_UPDATE needs 256-byte aligned params_alt (and lowp_alt for bf16)", z);
+        }
+    }
     // Capturing the per-stage streams (many streams forked from and cross-joined inside one capture, plus the
     // backward pass's edits of the capture frontier) ended in a crash inside the runtime's capture code; the
     // combination is refused.  Replay is no faster than enqueueing for a multi-branch graph anyway.

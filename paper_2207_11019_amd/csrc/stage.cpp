@@ -478,17 +478,24 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
 
 extern "C" int32_t lpm_stage_update(lpm_stage* s, float* params, void* lowp, float* grads, float* momentum,
                                     float lr_, float mu, int32_t zero_grads, void* stream) {
-    if (!s || !params || !grads || !momentum) return fail(LPM_EINVAL, "NULL argument");
+    return lpm_stage_update_to(s, params, params, lowp, grads, momentum, lr_, mu, zero_grads, stream);
+}
+
+// U with the new weights written to another buffer than the one they are read from (params_out may equal
+// params_in): the asynchronous update keeps two versions of a stage's weights.  Frozen scales are not touched.
+int32_t lpm_stage_update_to(lpm_stage* s, const float* params_in, float* params, void* lowp, float* grads, float* momentum,
+                            float lr_, float mu, int32_t zero_grads, void* stream) {
+    if (!s || !params_in || !params || !grads || !momentum) return fail(LPM_EINVAL, "NULL argument");
     if (s->dtype == LPM_BF16 && !lowp) return fail(LPM_EINVAL, "lowp is NULL for a bf16 stage");
-    if (misaligned(params) || misaligned(grads) || misaligned(momentum) || (lowp && misaligned(lowp)))
+    if (misaligned(params_in) || misaligned(params) || misaligned(grads) || misaligned(momentum) || (lowp && misaligned(lowp)))
         return fail(LPM_EALIGN, "device buffers must be 256-byte aligned");
     hipStream_t st = (hipStream_t)stream;
     if (s->n_trainable == 0) return LPM_OK;
     if (s->dtype != LPM_BF16) {
-        LPM_HIP(launch_sgd(params, nullptr, grads, momentum, s->n_trainable, lr_, mu, zero_grads, st));
+        LPM_HIP(launch_sgd(params_in, params, nullptr, grads, momentum, s->n_trainable, lr_, mu, zero_grads, st));
         return LPM_OK;
     }
-    LPM_HIP(launch_sgd(params, (uint16_t*)lowp, grads, momentum, s->n_trainable, lr_, mu, zero_grads, st));
+    LPM_HIP(launch_sgd(params_in, params, (uint16_t*)lowp, grads, momentum, s->n_trainable, lr_, mu, zero_grads, st));
     for (int32_t i = s->first; i < s->last; ++i) {
         const LayerRt& lr = s->Ly(i);
         if (lr.lowp_wt_off != NO)

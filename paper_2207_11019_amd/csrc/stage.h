@@ -61,3 +61,7 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                               int32_t accumulate, void* bwd_ws, void* stream, void* wstream, int32_t parity,
                               int32_t phases);
 enum { LPM_PHASE_DATA = 1, LPM_PHASE_WEIGHTS = 2 };
+
+// U_z reading one weight version and writing another (see stage.cpp).
+int32_t lpm_stage_update_to(lpm_stage* s, const float* params_in, float* params_out, void* lowp_out, float* grads,
+                            float* momentum, float lr, float mu, int32_t zero_grads, void* stream);

@@ -32,9 +32,37 @@ def oracle_step(layers, starts, batch, M, bf16, seed, lr, mu, dx_wanted=False, b
     return dict(p0=p0, m0=m0, x=x, labels=labels, g=g, ref=ref, params=params, mom=mom)
 
 
+def oracle_step_async(layers, starts, batch, M, bf16, seed, lr, mu, window, locked, bias_std=0.05, momentum_std=1e-3):
+    """One pass with an update per micro-batch (oracle.run_schedule_async)."""
+    params, mom = wl.make_params(layers, seed, bf16=bf16, bias_std=bias_std, momentum_std=momentum_std)
+    x, labels, g = wl.make_batch(layers, batch, seed, bf16=bf16)
+    p0, m0 = copy.deepcopy(params), copy.deepcopy(mom)
+    ref = orc.run_schedule_async(layers, starts, params, mom, x, labels, g, M, lr, mu, window=window, locked=locked,
+                                 store=orc.round_bf16 if bf16 else None, wstore=orc.round_bf16 if bf16 else None)
+    return dict(p0=p0, m0=m0, x=x, labels=labels, g=g, ref=ref, params=params, mom=mom)
+
+
+def compare_async(net, dtype, o, tol=None):
+    """Loss, last micro-batch's gradient, final weights and momentum against the oracle."""
+    tol = TOL[dtype] if tol is None else tol
+    ref = o["ref"]
+    errs = {"loss": abs(net.loss_value() - ref["loss"]) / max(abs(ref["loss"]), 1e-30)}
+    g, p, v = net.read_grads(), net.read_params(), net.read_momentum()
+    for i in o["params"]:
+        for k in ("W", "b"):
+            if k in o["params"][i]:
+                errs["grad%d.%s" % (i, k)] = rel_err(g[i][k], ref["grads"][i][k])
+                errs["param%d.%s" % (i, k)] = rel_err(p[i][k], o["params"][i][k])
+                errs["mom%d.%s" % (i, k)] = rel_err(v[i][k], o["mom"][i][k])
+    bad = {k: e for k, e in errs.items() if not (e <= tol)}
+    assert not bad, "over the %g bar: %s" % (tol, sorted(bad.items(), key=lambda kv: -kv[1])[:8])
+    return errs
+
+
 def gpu_step(lpm, layers, starts, batch, M, dtype, o, lr, mu, mode, window=2, dx_wanted=False, steps=1):
     import torch
-    net = lpm.Net(layers, starts, batch // M, M, dtype, window=window, dx_wanted=dx_wanted)
+    net = lpm.Net(layers, starts, batch // M, M, dtype, window=window, dx_wanted=dx_wanted,
+                  async_update=bool(mode & lpm.ASYNC_UPDATE))
     net.load_params(o["p0"], o["m0"])
     xd = lpm.pack_act(o["x"], dtype)
     ld = torch.from_numpy(o["labels"]).to("cuda:0") if o["labels"] is not None else None

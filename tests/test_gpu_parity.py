@@ -55,6 +55,33 @@ def test_pipelined_graph_is_refused(lpm):
         net.step(x, None, None, 0.1, 0.0, lpm.PIPELINED | lpm.GRAPH)
 
 
+ASYNC = [
+    # name, builder, batch, M, Z, dtype
+    ("tiny_lenet_f32", wl.tiny_lenet, 8, 4, 3, 0),
+    ("tiny_resnet_f32_odd", wl.tiny_resnet, 6, 3, 2, 0),
+    # bf16: a network without ReLU / max-pooling.  After an update the bf16 weight copies of the two sides differ
+    # in a few last bits, and with a handful of samples per micro-batch the sign / maximum decisions of a ReLU
+    # network turn that into 10-50 % changes of the next gradient (measured on the oracle against itself).
+    ("tiny_linear_bf16", wl.tiny_linear, 8, 4, 2, 1),
+]
+
+
+@pytest.mark.parametrize("name,builder,batch,M,Z,dtype", ASYNC, ids=[c[0] for c in ASYNC])
+@pytest.mark.parametrize("sched", ["locked", "overlapped_w1", "overlapped_w2"])
+def test_async_update(lpm, name, builder, batch, M, Z, dtype, sched):
+    """One update per micro-batch: plain per-micro-batch SGD when nothing overlaps, forward passes one update
+    behind with two micro-batches in flight."""
+    from harness import oracle_step_async, compare_async
+    layers = builder()
+    starts = _starts(layers, Z)
+    window = 1 if sched == "overlapped_w1" else 2
+    mode = (lpm.LOCKED if sched == "locked" else lpm.OVERLAPPED) | lpm.ASYNC_UPDATE
+    print("async case", name, sched, "starts", starts, flush=True)
+    o = oracle_step_async(layers, starts, batch, M, dtype == 1, seed=23, lr=0.05, mu=0.9, window=window, locked=sched == "locked")
+    net = gpu_step(lpm, layers, starts, batch, M, dtype, o, 0.05, 0.9, mode, window=window)
+    compare_async(net, dtype, o)
+
+
 def test_lenet_config_f32(lpm):
     """The LeNet workload at its full size: batch 32, 4 micro-batches of 8, 2 partitions, lr 0.01, momentum 0.9."""
     layers = wl.lenet()

@@ -180,6 +180,14 @@ def tiny_lenet():
     return b.finish()
 
 
+def tiny_linear():
+    """Two convolutions without ReLU, global average pooling and an FC head: the only non-linearity is the loss,
+    so no result hinges on a sign or a maximum taken on rounded values (bf16 runs of several dependent steps)."""
+    b = _Builder(3, 8, 8)
+    b.conv(32, 3, pad=1, relu=False); b.conv(32, 3, pad=1, relu=False); b.gap(); b.fc(5, relu=False); b.loss()
+    return b.finish()
+
+
 def tiny_resnet(hw=8, widths=(4, 6), n_classes=5):
     """Stem + one identity block + one strided projection block + GAP + FC."""
     return resnet18_cifar(widths=widths, blocks=1, hw=hw, n_classes=n_classes)
