@@ -44,6 +44,32 @@ def test_small_networks(lpm, name, builder, batch, M, Z, dtype, mode):
     compare(net, layers, starts, M, dtype, o)
 
 
+@pytest.mark.parametrize("window", [1, 3, 4])
+@pytest.mark.parametrize("mode", [1, 2, 17], ids=["overlapped", "pipelined", "overlapped_graph"])
+def test_other_windows(lpm, window, mode):
+    """Window 1 (no overlap), and windows wider than the two copies of the backward scratch (the explicit
+    wait on micro-batch j-2), with more micro-batches than slots and fewer."""
+    layers = wl.tiny_vgg()
+    starts = _starts(layers, 3)
+    for batch, M in ((12, 6), (4, 2)):
+        print("window", window, "mode", mode, "M", M, flush=True)
+        o = oracle_step(layers, starts, batch, M, False, seed=31, lr=0.05, mu=0.9)
+        net = gpu_step(lpm, layers, starts, batch, M, 0, o, 0.05, 0.9, mode, window=window)
+        compare(net, layers, starts, M, 0, o, window=window)
+
+
+def test_stage_without_parameters(lpm):
+    """A partition made of a pooling layer alone: nothing to update, no weight gradient, gradients pass through."""
+    layers = wl.tiny_vgg()
+    pool = [i for i, l in enumerate(layers) if l["kind"] == "maxpool2"][0]
+    starts = [0, pool, pool + 1, len(layers)]
+    for dtype in (0, 1):
+        o = oracle_step(layers, starts, 8, 2, dtype == 1, seed=37, lr=0.05, mu=0.9)
+        for mode in (lpm.LOCKED, lpm.OVERLAPPED, lpm.PIPELINED):
+            net = gpu_step(lpm, layers, starts, 8, 2, dtype, o, 0.05, 0.9, mode)
+            compare(net, layers, starts, 2, dtype, o)
+
+
 def test_pipelined_graph_is_refused(lpm):
     """Stage-parallel streams are not captured into a graph: the call fails before anything is enqueued."""
     layers = wl.tiny_lenet()
