@@ -43,7 +43,7 @@ __device__ __forceinline__ unsigned short buf_load2(__amdgpu_buffer_rsrc_t r, un
 // A K tile of depth BK is stored in LDS as rows of BK + 8 elements (16-byte aligned, staggers banks).
 // Small-M shapes are bound by the latency of one global load per K tile, so they take deep tiles.
 
-enum { MODE_FWD = 0, MODE_DGRAD = 1 /* stride 1 */, MODE_DGRAD_S = 2 /* any stride */ };
+enum { MODE_FWD = 0, MODE_DGRAD = 1 /* stride 1 */, MODE_DGRAD_S = 2 /* stride 2..4, by residue class */ };
 
 struct IgemmArgs {
     const uint16_t* A;
@@ -62,6 +62,12 @@ struct IgemmArgs {
     int Kw, stride, pad;
     int kt_total, kt_per_split;
     unsigned a_bytes, b_bytes;   // extents of A and B for the buffer resources
+    // strided data gradient: the input pixels are processed by residue class (h % stride, w % stride); a class
+    // only meets the filter taps of matching parity.  cls_tile0[c] = first row tile of class c (c = ph*stride+pw).
+    int Kh;
+    int cls_tile0[17];
+    int m_tiles;                 // host only: row tiles to launch (0: ceil(M / 64)); K the plan is made for (0: Ktot)
+    int plan_K;
 };
 
 // XCD-aware tile order: consecutive workgroup ids land on different XCDs (each with its own L2), so give
@@ -116,16 +122,40 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nt = (p.N + BN - 1) / BN;
-    const int tile = xcd_remap(blockIdx.x, gridDim.x);
-    const int m0 = (tile / nt) * BM, n0 = (tile % nt) * BN;
-    const int kt0 = blockIdx.z * p.kt_per_split;
-    const int kt1 = min(p.kt_total, kt0 + p.kt_per_split);
+    // (strided data gradient: the residue classes differ in work -- 1, 2, 2 and 4 taps of a 3x3 filter, one
+    // class in four for a 1x1 filter -- so their tiles stay in launch order, which deals them round-robin to the XCDs)
+    const int tile = MODE == MODE_DGRAD_S ? (int)blockIdx.x : xcd_remap(blockIdx.x, gridDim.x);
+    int m0 = (tile / nt) * BM;
+    const int n0 = (tile % nt) * BN;
+    int kt0 = blockIdx.z * p.kt_per_split;
+    int kt1 = min(p.kt_total, kt0 + p.kt_per_split);
+    // filter taps visited: all of them in steps of 1, or (strided data gradient) those of the block's residue class
+    int kstep = 1, kh_first = 0, kw_first = 0;
+    int ph = 0, pw = 0, Hc = p.Hr, Wc = p.Wr, rows = p.M;     // residue class of the block's rows and its extent
+    if (MODE == MODE_DGRAD_S) {
+        const int s_ = p.stride, mt = tile / nt;
+        int c = 0;
+        while (c + 1 < s_ * s_ && mt >= p.cls_tile0[c + 1]) ++c;
+        ph = c / s_; pw = c - ph * s_;
+        Hc = (p.Hr - ph + s_ - 1) / s_; Wc = (p.Wr - pw + s_ - 1) / s_;
+        rows = (p.M / (p.Hr * p.Wr)) * Hc * Wc;
+        m0 = (mt - p.cls_tile0[c]) * BM;
+        kstep = s_;
+        kh_first = (ph + p.pad) % s_; kw_first = (pw + p.pad) % s_;
+        const int nkh = kh_first < p.Kh ? (p.Kh - kh_first + s_ - 1) / s_ : 0;
+        const int nkw = kw_first < p.Kw ? (p.Kw - kw_first + s_ - 1) / s_ : 0;
+        const int kt_cls = nkh * nkw * (p.Ci / BK);
+        const int per = (kt_cls + (int)gridDim.z - 1) / (int)gridDim.z;
+        kt0 = blockIdx.z * per;
+        kt1 = min(kt_cls, kt0 + per);
+    }
 
     // per-thread gather state of its A chunks (a chunk = 8 channels of one row = 16 bytes)
     const __amdgpu_buffer_rsrc_t rsA = make_rsrc(p.A, p.a_bytes), rsB = make_rsrc(p.B, p.b_bytes);
     // Per chunk: the byte offset of its row's pixel at filter tap (0,0) (a_base, may wrap below zero for rows
     // that start in the padding; it is only used when the tap lands inside the image) and the pixel's
     // coordinates at tap (0,0).  Per K tile only a wave-uniform tap offset is added.
+    // (Strided data gradient: the row's coordinates inside its residue class and the image's base offset.)
     int a_h0[A_CH], a_w0[A_CH];
     unsigned a_base[A_CH];
     bool a_ok[A_CH];
@@ -133,11 +163,12 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
 #pragma unroll
     for (int c = 0; c < A_CH; ++c) {
         const int id = tid + c * 256, row = m0 + id / CPR, kc = id % CPR;
-        a_ok[c] = (id < BM * CPR) & (row < p.M);
+        a_ok[c] = (id < BM * CPR) & (row < rows);
         const int rr = a_ok[c] ? row : 0;
-        const int wq = rr % p.Wr, t = rr / p.Wr, hq = t % p.Hr, n = t / p.Hr;
+        const int wq = rr % Wc, t = rr / Wc, hq = t % Hc, n = t / Hc;
         if (MODE == MODE_FWD) { a_h0[c] = hq * p.stride - p.pad; a_w0[c] = wq * p.stride - p.pad; }
-        else { a_h0[c] = hq + p.pad; a_w0[c] = wq + p.pad; }
+        else if (MODE == MODE_DGRAD) { a_h0[c] = hq + p.pad; a_w0[c] = wq + p.pad; }
+        else { a_h0[c] = hq; a_w0[c] = wq; }
         if (MODE == MODE_DGRAD_S) a_base[c] = (unsigned)(n * p.Hi * p.Wi * p.Ci + kc * 8) * 2u;
         else a_base[c] = (unsigned)(((n * p.Hi + a_h0[c]) * p.Wi + a_w0[c]) * p.Ci + kc * 8) * 2u;
     }
@@ -150,7 +181,11 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
     int cur_kt = kt0, cur_c0, cur_kh, cur_kw;
     {
         const int k0 = kt0 * BK, tap = k0 / p.Ci;
-        cur_c0 = k0 - tap * p.Ci; cur_kh = tap / p.Kw; cur_kw = tap - cur_kh * p.Kw;
+        cur_c0 = k0 - tap * p.Ci;
+        if (MODE == MODE_DGRAD_S) {
+            const int nkw = kw_first < p.Kw ? (p.Kw - kw_first + kstep - 1) / kstep : 1;
+            cur_kh = kh_first + (tap / nkw) * kstep; cur_kw = kw_first + (tap % nkw) * kstep;
+        } else { cur_kh = tap / p.Kw; cur_kw = tap - cur_kh * p.Kw; }
     }
     // two K tiles in flight in registers
     uint4 ra0[A_CH], rb0[B_CH], ra1[A_CH], rb1[B_CH];
@@ -162,6 +197,9 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
         const unsigned tapoff_ = (MODE == MODE_FWD)                                                          \
                                      ? (unsigned)((kh_ * p.Wi + kw_) * p.Ci + cur_c0) * 2u                   \
                                      : (unsigned)(cur_c0 - (kh_ * p.Wi + kw_) * p.Ci) * 2u;                  \
+        /* strided data gradient: output pixel = class coordinate + (ph + pad - kh) / stride, an exact quotient */ \
+        const int dh_ = (MODE == MODE_DGRAD_S) ? (ph + p.pad - kh_) / kstep : 0;                             \
+        const int dw_ = (MODE == MODE_DGRAD_S) ? (pw + p.pad - kw_) / kstep : 0;                             \
         _Pragma("unroll") for (int c = 0; c < A_CH; ++c) {                                                   \
             int h_, w_;                                                                                      \
             bool ok_ = a_ok[c] & live_;                                                                      \
@@ -169,21 +207,22 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
             if (MODE == MODE_FWD) { h_ = a_h0[c] + kh_; w_ = a_w0[c] + kw_; off_ = a_base[c] + tapoff_; }    \
             else if (MODE == MODE_DGRAD) { h_ = a_h0[c] - kh_; w_ = a_w0[c] - kw_; off_ = a_base[c] + tapoff_; } \
             else {                                                                                           \
-                h_ = a_h0[c] - kh_; w_ = a_w0[c] - kw_;                                                      \
-                const int hq_ = h_ / p.stride, wq_ = w_ / p.stride;                                          \
-                ok_ = ok_ & (h_ >= 0) & (w_ >= 0) & (hq_ * p.stride == h_) & (wq_ * p.stride == w_);         \
-                h_ = hq_; w_ = wq_;                                                                          \
+                h_ = a_h0[c] + dh_; w_ = a_w0[c] + dw_;                                                      \
                 off_ = a_base[c] + (unsigned)((h_ * p.Wi + w_) * p.Ci + cur_c0) * 2u;                        \
             }                                                                                                \
             ok_ = ok_ & ((unsigned)h_ < (unsigned)p.Hi) & ((unsigned)w_ < (unsigned)p.Wi);                   \
             RA[c] = buf_load16(rsA, ok_ ? off_ : OOB);                                                       \
         }                                                                                                    \
-        const unsigned k0b_ = (unsigned)cur_kt * (BK * 2u);                                                  \
+        const unsigned k0b_ = (unsigned)((kh_ * p.Kw + kw_) * p.Ci + cur_c0) * 2u;                           \
         _Pragma("unroll") for (int c = 0; c < B_CH; ++c)                                                     \
             RB[c] = buf_load16(rsB, ((b_off[c] == OOB) | !live_) ? OOB : b_off[c] + k0b_);                   \
         ++cur_kt;                                                                                            \
         cur_c0 += BK;                                                                                        \
-        if (cur_c0 >= p.Ci) { cur_c0 = 0; if (++cur_kw == p.Kw) { cur_kw = 0; ++cur_kh; } }                  \
+        if (cur_c0 >= p.Ci) {                                                                                \
+            cur_c0 = 0;                                                                                      \
+            cur_kw += kstep;                                                                                 \
+            if (cur_kw >= p.Kw) { cur_kw = kw_first; cur_kh += kstep; }                                      \
+        }                                                                                                    \
     }
 #define LPM_STORE_TILE(BUF, RA, RB)                                                                          \
     {                                                                                                        \
@@ -247,8 +286,12 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int row = m0 + wm * Cfg::WTM + mi * 32 + (i >> 2) * 8 + rq + (i & 3);
-                if (row >= p.M) continue;
-                const size_t o = (size_t)row * p.N + col;
+                if (row >= rows) continue;
+                size_t o = (size_t)row * p.N + col;
+                if (MODE == MODE_DGRAD_S) {      // class row -> pixel of the full image
+                    const int wq = row % Wc, t = row / Wc, hq = t % Hc, n = t / Hc;
+                    o = ((size_t)(n * p.Hr + hq * p.stride + ph) * p.Wr + wq * p.stride + pw) * p.N + col;
+                }
                 float v = acc[mi][ni][i];
                 if (p.part) { p.part[(size_t)blockIdx.z * p.M * p.N + o] = v; continue; }
                 v = v * sc + bi;
@@ -347,13 +390,14 @@ static void launch_igemm_cfg(const IgemmPlan& pl, const IgemmArgs& a, hipStream_
 #undef LPM_CFG
     }
 #endif
-    const dim3 grid((unsigned)(((a.M + 63) / 64) * ((a.N + 63) / 64)), 1, pl.splits);
+    const int mt = a.m_tiles ? a.m_tiles : (a.M + 63) / 64;
+    const dim3 grid((unsigned)(mt * ((a.N + 63) / 64)), 1, pl.splits);
     if (pl.bk == 64) hipLaunchKernelGGL((igemm_kernel<64, 64, 64, 2, 2, MODE>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((igemm_kernel<64, 64, 32, 2, 2, MODE>), grid, dim3(256), 0, st, a);
 }
 
 static hipError_t run_igemm(int mode, IgemmArgs a, void* ws, hipStream_t st) {
-    const IgemmPlan pl = plan_igemm(a.M, a.N, a.Ktot, a.Ci);
+    const IgemmPlan pl = plan_igemm(a.M, a.N, a.plan_K ? a.plan_K : a.Ktot, a.Ci);
     a.kt_total = pl.kt_total;
     a.kt_per_split = pl.kt_per;
     a.part = pl.splits > 1 ? (float*)ws : nullptr;
@@ -374,14 +418,20 @@ static bool fits32(const ConvGeom& g) {
     return g.rows_in() * g.Cin < lim && g.rows_out() * g.Cout < lim && (int64_t)g.Cout * g.K() < lim;
 }
 bool mfma_fwd_ok(const ConvGeom& g) { return g.Cin % 32 == 0 && fits32(g); }
-bool mfma_dgrad_ok(const ConvGeom& g) { return g.Cout % 32 == 0 && fits32(g); }
+bool mfma_dgrad_ok(const ConvGeom& g) { return g.Cout % 32 == 0 && g.stride <= 4 && fits32(g); }
 
 size_t mfma_fwd_ws_bytes(const ConvGeom& g) {
     const IgemmPlan pl = plan_igemm(g.rows_out(), g.Cout, g.K(), g.Cin);
     return pl.splits > 1 ? (size_t)pl.splits * g.rows_out() * g.Cout * sizeof(float) : 0;
 }
+// K a residue class of a strided data gradient runs over at most: the taps of matching parity
+static int dgrad_plan_K(const ConvGeom& g) {
+    const int s = g.stride;
+    return ((g.Kh + s - 1) / s) * ((g.Kw + s - 1) / s) * g.Cout;
+}
+
 size_t mfma_dgrad_ws_bytes(const ConvGeom& g) {
-    const IgemmPlan pl = plan_igemm(g.rows_in(), g.Cin, g.Kh * g.Kw * g.Cout, g.Cout);
+    const IgemmPlan pl = plan_igemm(g.rows_in(), g.Cin, dgrad_plan_K(g), g.Cout);
     return pl.splits > 1 ? (size_t)pl.splits * g.rows_in() * g.Cin * sizeof(float) : 0;
 }
 
@@ -405,6 +455,19 @@ hipError_t mfma_conv_dgrad(const ConvGeom& g, const void* dz, const void* wt, vo
     a.M = (int)g.rows_in(); a.N = g.Cin; a.Ktot = g.Kh * g.Kw * g.Cout;
     a.Hi = g.Ho; a.Wi = g.Wo; a.Ci = g.Cout; a.Hr = g.H; a.Wr = g.W; a.Kw = g.Kw; a.stride = g.stride; a.pad = g.pad;
     a.a_bytes = (unsigned)(g.rows_out() * g.Cout * 2); a.b_bytes = (unsigned)((int64_t)g.Cout * g.K() * 2);
+    a.Kh = g.Kh;
+    a.plan_K = dgrad_plan_K(g);
+    if (g.stride > 1) {          // row tiles per residue class (h % stride, w % stride)
+        const int s = g.stride;
+        int t = 0;
+        for (int c = 0; c < s * s; ++c) {
+            a.cls_tile0[c] = t;
+            const int64_t Hc = (g.H - c / s + s - 1) / s, Wc = (g.W - c % s + s - 1) / s;
+            t += (int)(((int64_t)g.m * Hc * Wc + 63) / 64);
+        }
+        for (int c = s * s; c <= 16; ++c) a.cls_tile0[c] = t;
+        a.m_tiles = t;
+    }
     return run_igemm(MODE_DGRAD, a, ws, st);
 }
 

@@ -33,6 +33,11 @@ SHAPES = [
     G(3, 9, 7, 64, 96, 3, 1, 1),          # ragged M and N
     G(2, 12, 12, 64, 40, 3, 2, 1),        # stride 2, N below a tile
     G(2, 11, 11, 32, 64, 3, 2, 1),        # stride 2, odd extent
+    G(4, 28, 28, 64, 64, 3, 2, 1),        # stride 2, several row tiles per residue class
+    G(2, 13, 13, 32, 32, 5, 2, 2),        # stride 2, 5x5: classes with 9, 6, 6 and 4 taps
+    G(2, 13, 11, 32, 64, 3, 3, 1),        # stride 3: one tap per class
+    G(1, 17, 17, 32, 32, 7, 4, 3),        # stride 4, 7x7
+    G(2, 9, 9, 256, 64, 3, 2, 1),         # stride 2, long K: split reduction over the taps of a class
     G(4, 6, 6, 128, 256, 1, 1, 0),        # 1x1
     G(2, 8, 8, 64, 128, 1, 2, 0),         # 1x1 stride 2 (projection shortcut)
     G(2, 10, 10, 32, 32, 5, 1, 0),        # 5x5 valid
