@@ -25,7 +25,7 @@ hipError_t mfma_conv_fwd(const ConvGeom& g, const void* x, const void* w, const 
 hipError_t mfma_conv_dgrad(const ConvGeom& g, const void* dz, const void* wt, void* dx, int accumulate, const void* mask,
                            const float* mscale, void* ws, hipStream_t st);
 hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* bscale,
-                           int accumulate, void* ws, hipStream_t st);
+                           int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred);
 
 bool fc_skinny_ok(const ConvGeom& g);
 size_t fc_dgrad_ws_bytes(const ConvGeom& g);
@@ -75,9 +75,10 @@ hipError_t launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dz, const
 }
 
 hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias,
-                             const float* bscale, int accumulate, void* ws, hipStream_t st) {
+                             const float* bscale, int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred) {
+    if (deferred) deferred->splits = 0;
     if (dtype == LPM_BF16 && fc_skinny_ok(g)) return fc_wgrad(g, x, dz, dw, dbias, bscale, accumulate, st);
-    if (dtype == LPM_BF16 && mfma_wgrad_ok(g)) return mfma_conv_wgrad(g, x, dz, dw, dbias, bscale, accumulate, ws, st);
+    if (dtype == LPM_BF16 && mfma_wgrad_ok(g)) return mfma_conv_wgrad(g, x, dz, dw, dbias, bscale, accumulate, ws, st, deferred);
     if (dtype == LPM_BF16 && mfma_wgrad_flat_ok(g)) return mfma_conv_wgrad_flat(g, x, dz, dw, dbias, bscale, accumulate, ws, st);
     if (dbias) return hipErrorInvalidValue;      // callers ask wgrad_fuses_bias first
     return conv_wgrad_generic_launch(dtype, g, x, dz, dw, accumulate, ws, st);

@@ -783,8 +783,54 @@ size_t mfma_wgrad_ws_bytes(const ConvGeom& g) {
 }
 
 // dbias (may be NULL): also produce the bias gradient, the per-channel sum of dz divided by bscale (may be NULL)
+struct ReduceBatchArgs {
+    ReduceDesc d[LPM_REDUCE_BATCH];
+    int64_t first[LPM_REDUCE_BATCH + 1];     // first global element of every reduction (elements = n + nb)
+    int count;
+};
+
+__global__ void __launch_bounds__(256) wgrad_reduce_batch(ReduceBatchArgs a) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= a.first[a.count]) return;
+    int k = 0;
+    while (k + 1 < a.count && e >= a.first[k + 1]) ++k;
+    const ReduceDesc& d = a.d[k];
+    const int64_t i = e - a.first[k];
+    if (i >= d.n + d.nb) return;              // padding up to a whole block
+    float acc = d.part[i];
+    for (int s = 1; s < d.splits; ++s) acc += d.part[(size_t)s * d.stride + i];
+    if (i < d.n) d.dst[i] = d.accumulate ? d.dst[i] + acc : acc;
+    else {
+        const int c = (int)(i - d.n);
+        if (d.bscale) acc /= d.bscale[c];
+        d.db[c] = d.accumulate ? d.db[c] + acc : acc;
+    }
+}
+
+hipError_t launch_reduce_batch(const ReduceDesc* d, int count, hipStream_t st) {
+    for (int done = 0; done < count;) {
+        ReduceBatchArgs a{};
+        int64_t tot = 0;
+        int k = 0;
+        for (; k < LPM_REDUCE_BATCH && done + k < count; ++k) {
+            a.d[k] = d[done + k];
+            a.first[k] = tot;
+            // whole blocks per reduction: a block never straddles two of them
+            tot += ((a.d[k].n + a.d[k].nb + 255) / 256) * 256;
+        }
+        a.first[k] = tot;
+        a.count = k;
+        done += k;
+        if (tot == 0) continue;
+        hipLaunchKernelGGL(wgrad_reduce_batch, dim3((unsigned)(tot / 256)), dim3(256), 0, st, a);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* bscale,
-                           int accumulate, void* ws, hipStream_t st) {
+                           int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred) {
     const WgradPlan pl = plan_wgrad(g);
     WgradArgs a{};
     a.X = (const uint16_t*)x; a.DZ = (const uint16_t*)dz;
@@ -806,6 +852,10 @@ hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, flo
     if (e != hipSuccess || pl.splits == 1) return e;
     const int64_t n = (int64_t)g.Cout * g.K();
     const int nb = dbias ? g.Cout : 0;
+    if (deferred) {
+        *deferred = ReduceDesc{(const float*)ws, a.part_stride, pl.splits, dw, n, dbias, nb, bscale, accumulate};
+        return hipSuccess;
+    }
     hipLaunchKernelGGL(wgrad_reduce, dim3((unsigned)((n + nb + 255) / 256)), dim3(256), 0, st, (const float*)ws,
                        a.part_stride, pl.splits, dw, n, dbias, nb, bscale, accumulate);
     return hipGetLastError();

@@ -55,8 +55,19 @@ hipError_t launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dz, const
                              void* dx, int accumulate, const void* mask, const float* mscale, void* ws, hipStream_t st);
 // dw (+)= sum over pixels of dz (x) x         ws: split-reduction partials (wgrad_ws_bytes)
 // dbias (may be NULL, only when wgrad_fuses_bias): dbias (+)= (sum over pixels of dz) / bscale_c
+// deferred (may be NULL): when the kernel leaves split partials, describe their reduction there instead of launching
+// it (deferred->splits stays 0 when nothing is left to do); the caller runs launch_reduce_batch later on the stream.
+struct ReduceDesc {
+    const float* part; size_t stride; int splits;      // partial s of output i at part[s*stride + i]
+    float* dst; int64_t n;                              // dst[i] (+)= sum_s part, i < n
+    float* db; int nb; const float* bscale;             // db[c] (+)= (sum_s part[s*stride + n + c]) / bscale[c], c < nb
+    int accumulate;
+};
 hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias,
-                             const float* bscale, int accumulate, void* ws, hipStream_t st);
+                             const float* bscale, int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred = nullptr);
+constexpr int LPM_REDUCE_BATCH = 24;
+// the reductions of up to LPM_REDUCE_BATCH weight gradients in one launch (each in its fixed split order)
+hipError_t launch_reduce_batch(const ReduceDesc* d, int count, hipStream_t st);
 bool wgrad_fuses_bias(int dtype, const ConvGeom& g);
 bool dgrad_uses_wt(int dtype, const ConvGeom& g);
 size_t wgrad_ws_bytes(int dtype, const ConvGeom& g);

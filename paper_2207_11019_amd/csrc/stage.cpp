@@ -95,7 +95,8 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
             lr.dz_off = gws;
             gws += align_up(o.elems() * (size_t)microbatch * s->esz, 256);
         }
-        wws = std::max(wws, align_up(wgrad_ws_bytes(dtype, lr.g), 256));
+        lr.wws_off = wws;                        // every layer its own area: the reductions of a pass run in one launch
+        wws += align_up(wgrad_ws_bytes(dtype, lr.g), 256);
         kws = std::max(kws, align_up(dgrad_ws_bytes(dtype, lr.g), 256));
         kws = std::max(kws, align_up(epi_bwd_ws_bytes(lr.g.rows_out(), l.cout), 256));
         fws = std::max(fws, align_up(fwd_ws_bytes(dtype, lr.g), 256));
@@ -419,7 +420,7 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                     LPM_HIP(frontier(before));
                     if (!wtail.empty())       // weight gradients share one scratch area: keep them in a chain
                         LPM_HIP(hipStreamUpdateCaptureDependencies(st, wtail.data(), wtail.size(), hipStreamAddCaptureDependencies));
-                    LPM_HIP(launch_conv_wgrad(s->dtype, lr.g, xin, dz, grads + lr.w_off, wdb, sc, acc, wws, st));
+                    LPM_HIP(launch_conv_wgrad(s->dtype, lr.g, xin, dz, grads + lr.w_off, wdb, sc, acc, (char*)wws + lr.wws_off, st));
                     LPM_HIP(frontier(wtail));
                     LPM_HIP(hipStreamUpdateCaptureDependencies(st, before.data(), before.size(), hipStreamSetCaptureDependencies));
                 }
@@ -466,8 +467,15 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
             LPM_HIP(hipEventRecord(s->ev_fork, st));
             LPM_HIP(hipStreamWaitEvent(wst, s->ev_fork, 0));
         }
-        for (const WgradJob& j : jobs)
-            LPM_HIP(launch_conv_wgrad(s->dtype, j.lr->g, j.xin, j.dz, grads + j.lr->w_off, j.wdb, j.sc, acc, wws, wst));
+        std::vector<ReduceDesc> red;
+        red.reserve(jobs.size());
+        for (const WgradJob& j : jobs) {
+            ReduceDesc d{};
+            LPM_HIP(launch_conv_wgrad(s->dtype, j.lr->g, j.xin, j.dz, grads + j.lr->w_off, j.wdb, j.sc, acc,
+                                      (char*)wws + j.lr->wws_off, wst, &d));
+            if (d.splits > 0) red.push_back(d);
+        }
+        if (!red.empty()) LPM_HIP(launch_reduce_batch(red.data(), (int)red.size(), wst));
         if (!wstream) {      // join: the caller's stream is ordered after every weight gradient
             LPM_HIP(hipEventRecord(s->ev_join, s->side));
             LPM_HIP(hipStreamWaitEvent(st, s->ev_join, 0));

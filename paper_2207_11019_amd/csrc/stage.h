@@ -24,6 +24,7 @@ struct LayerRt {
     size_t w_count = 0;
     size_t lowp_w_off = NO, lowp_wt_off = NO;    // byte offsets into lowp
     size_t dz_off = NO;                          // byte offset of its pre-activation gradient in the backward scratch
+    size_t wws_off = 0;                          // this layer's weight-gradient partials inside the backward scratch
     bool fused_in = false;                       // its consumer's backward kernel writes dz directly (mask and scale fused)
 };
 
