@@ -27,6 +27,11 @@ hipError_t mfma_conv_dgrad(const ConvGeom& g, const void* dz, const void* wt, vo
 hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* bscale,
                            int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred);
 
+bool wgrad_tr_ok(const ConvGeom& g);
+size_t wgrad_tr_ws_bytes(const ConvGeom& g);
+hipError_t wgrad_tr(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* bscale,
+                    int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred);
+
 bool fc_skinny_ok(const ConvGeom& g);
 size_t fc_dgrad_ws_bytes(const ConvGeom& g);
 hipError_t fc_dgrad(const ConvGeom& g, const void* dz, const void* w, void* dx, int accumulate, const void* mask,
@@ -50,6 +55,7 @@ size_t dgrad_ws_bytes(int dtype, const ConvGeom& g) {
 }
 size_t wgrad_ws_bytes(int dtype, const ConvGeom& g) {
     if (dtype == LPM_BF16 && fc_skinny_ok(g)) return 0;
+    if (dtype == LPM_BF16 && wgrad_tr_ok(g)) return wgrad_tr_ws_bytes(g);
     if (dtype == LPM_BF16 && mfma_wgrad_ok(g)) return mfma_wgrad_ws_bytes(g);
     if (dtype == LPM_BF16 && mfma_wgrad_flat_ok(g)) return mfma_wgrad_flat_ws_bytes(g);
     return wgrad_generic_ws_bytes(g);
@@ -78,6 +84,7 @@ hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const 
                              const float* bscale, int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred) {
     if (deferred) deferred->splits = 0;
     if (dtype == LPM_BF16 && fc_skinny_ok(g)) return fc_wgrad(g, x, dz, dw, dbias, bscale, accumulate, st);
+    if (dtype == LPM_BF16 && wgrad_tr_ok(g)) return wgrad_tr(g, x, dz, dw, dbias, bscale, accumulate, ws, st, deferred);
     if (dtype == LPM_BF16 && mfma_wgrad_ok(g)) return mfma_conv_wgrad(g, x, dz, dw, dbias, bscale, accumulate, ws, st, deferred);
     if (dtype == LPM_BF16 && mfma_wgrad_flat_ok(g)) return mfma_conv_wgrad_flat(g, x, dz, dw, dbias, bscale, accumulate, ws, st);
     if (dbias) return hipErrorInvalidValue;      // callers ask wgrad_fuses_bias first

@@ -70,14 +70,6 @@ struct IgemmArgs {
     int plan_K;
 };
 
-// XCD-aware tile order: consecutive workgroup ids land on different XCDs (each with its own L2), so give
-// every XCD one contiguous range of tiles.
-__device__ __forceinline__ int xcd_remap(int bid, int nblocks) {
-    const int per = nblocks >> 3, rem = nblocks & 7;
-    const int xcd = bid & 7, idx = bid >> 3;
-    return xcd * per + min(xcd, rem) + idx;
-}
-
 template <int BM, int BN, int WGM, int WGN>
 struct TileCfg {
     static constexpr int WTM = BM / WGM, WTN = BN / WGN, MI = WTM / 32, NI = WTN / 32;

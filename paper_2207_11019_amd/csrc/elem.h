@@ -43,6 +43,14 @@ __device__ __forceinline__ void st_stream(uint2* a, uint2 x) {
     __builtin_nontemporal_store(t, reinterpret_cast<lpm_u2*>(a));
 }
 
+// XCD-aware tile order: consecutive workgroup ids land on different XCDs (each with its own L2), so give
+// every XCD one contiguous range of tiles.
+__device__ __forceinline__ int xcd_remap(int bid, int nblocks) {
+    const int per = nblocks >> 3, rem = nblocks & 7;
+    const int xcd = bid & 7, idx = bid >> 3;
+    return xcd * per + min(xcd, rem) + idx;
+}
+
 __device__ __forceinline__ float ld(const float* p, int64_t i) { return p[i]; }
 __device__ __forceinline__ float ld(const bf16_t* p, int64_t i) { return bf2f(p[i].bits); }
 __device__ __forceinline__ void st(float* p, int64_t i, float v) { p[i] = v; }
