@@ -712,22 +712,6 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
     }
 }
 
-// dst[i] (+)= sum over splits of part[s*stride + i] (i < n);  db[c] (+)= (sum over splits of part[s*stride + n + c]) / bscale[c]
-__global__ void __launch_bounds__(256) wgrad_reduce(const float* __restrict__ part, size_t stride, int splits,
-                                                    float* __restrict__ dst, int64_t n, float* __restrict__ db, int nb,
-                                                    const float* __restrict__ bscale, int accumulate) {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n + nb) return;
-    float acc = part[i];
-    for (int s = 1; s < splits; ++s) acc += part[(size_t)s * stride + i];
-    if (i < n) dst[i] = accumulate ? dst[i] + acc : acc;
-    else {
-        const int c = (int)(i - n);
-        if (bscale) acc /= bscale[c];
-        db[c] = accumulate ? db[c] + acc : acc;
-    }
-}
-
 struct WgradPlan { int big; int bk; int splits; int rt_total; int rt_per; int co_tiles, ci_tiles; };
 
 // Measured on the same shapes: 128x128 tiles win once the contraction is large (about 6e9 multiply-adds), the
@@ -777,25 +761,56 @@ size_t mfma_wgrad_ws_bytes(const ConvGeom& g) {
 // dbias (may be NULL): also produce the bias gradient, the per-channel sum of dz divided by bscale (may be NULL)
 struct ReduceBatchArgs {
     ReduceDesc d[LPM_REDUCE_BATCH];
-    int64_t first[LPM_REDUCE_BATCH + 1];     // first global element of every reduction (elements = n + nb)
+    int64_t first[LPM_REDUCE_BATCH + 1];     // first thread of every reduction (a thread sums four outputs)
     int count;
 };
 
+// A thread sums four consecutive outputs over the splits with 16-byte loads, four splits in flight (split s goes to
+// chain s % 4, the chains are added pairwise at the end: a fixed order); the bias part and ragged ends go one by one.
 __global__ void __launch_bounds__(256) wgrad_reduce_batch(ReduceBatchArgs a) {
-    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= a.first[a.count]) return;
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= a.first[a.count]) return;
     int k = 0;
-    while (k + 1 < a.count && e >= a.first[k + 1]) ++k;
+    while (k + 1 < a.count && t >= a.first[k + 1]) ++k;
     const ReduceDesc& d = a.d[k];
-    const int64_t i = e - a.first[k];
+    const int64_t i = (t - a.first[k]) * 4;
     if (i >= d.n + d.nb) return;              // padding up to a whole block
-    float acc = d.part[i];
-    for (int s = 1; s < d.splits; ++s) acc += d.part[(size_t)s * d.stride + i];
-    if (i < d.n) d.dst[i] = d.accumulate ? d.dst[i] + acc : acc;
-    else {
-        const int c = (int)(i - d.n);
-        if (d.bscale) acc /= d.bscale[c];
-        d.db[c] = d.accumulate ? d.db[c] + acc : acc;
+    if (i + 4 <= d.n && (d.stride & 3) == 0) {
+        float4 c[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) c[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        const float* p = d.part + i;
+        int s = 0;
+        for (; s + 4 <= d.splits; s += 4) {
+            float4 v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = *reinterpret_cast<const float4*>(p + (size_t)(s + j) * d.stride);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { c[j].x += v[j].x; c[j].y += v[j].y; c[j].z += v[j].z; c[j].w += v[j].w; }
+        }
+#pragma unroll
+        for (int j = 0; j < 3; ++j) {             // the last one to three splits (static chain index: registers)
+            if (s + j < d.splits) {
+                const float4 v = *reinterpret_cast<const float4*>(p + (size_t)(s + j) * d.stride);
+                c[j].x += v.x; c[j].y += v.y; c[j].z += v.z; c[j].w += v.w;
+            }
+        }
+        float4 r = make_float4((c[0].x + c[1].x) + (c[2].x + c[3].x), (c[0].y + c[1].y) + (c[2].y + c[3].y),
+                               (c[0].z + c[1].z) + (c[2].z + c[3].z), (c[0].w + c[1].w) + (c[2].w + c[3].w));
+        float4* o = reinterpret_cast<float4*>(d.dst + i);
+        if (d.accumulate) { const float4 q = *o; r.x += q.x; r.y += q.y; r.z += q.z; r.w += q.w; }
+        *o = r;
+        return;
+    }
+    for (int64_t e = i; e < i + 4 && e < d.n + d.nb; ++e) {
+        float acc = d.part[e];
+        for (int s = 1; s < d.splits; ++s) acc += d.part[(size_t)s * d.stride + e];
+        if (e < d.n) d.dst[e] = d.accumulate ? d.dst[e] + acc : acc;
+        else {
+            const int c = (int)(e - d.n);
+            if (d.bscale) acc /= d.bscale[c];
+            d.db[c] = d.accumulate ? d.db[c] + acc : acc;
+        }
     }
 }
 
@@ -807,8 +822,8 @@ hipError_t launch_reduce_batch(const ReduceDesc* d, int count, hipStream_t st) {
         for (; k < LPM_REDUCE_BATCH && done + k < count; ++k) {
             a.d[k] = d[done + k];
             a.first[k] = tot;
-            // whole blocks per reduction: a block never straddles two of them
-            tot += ((a.d[k].n + a.d[k].nb + 255) / 256) * 256;
+            // a thread per four outputs, whole blocks per reduction: a block never straddles two of them
+            tot += (((a.d[k].n + a.d[k].nb + 3) / 4 + 255) / 256) * 256;
         }
         a.first[k] = tot;
         a.count = k;
@@ -844,13 +859,10 @@ hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, flo
     if (e != hipSuccess || pl.splits == 1) return e;
     const int64_t n = (int64_t)g.Cout * g.K();
     const int nb = dbias ? g.Cout : 0;
-    if (deferred) {
-        *deferred = ReduceDesc{(const float*)ws, a.part_stride, pl.splits, dw, n, dbias, nb, bscale, accumulate};
-        return hipSuccess;
-    }
-    hipLaunchKernelGGL(wgrad_reduce, dim3((unsigned)((n + nb + 255) / 256)), dim3(256), 0, st, (const float*)ws,
-                       a.part_stride, pl.splits, dw, n, dbias, nb, bscale, accumulate);
-    return hipGetLastError();
+    // one reduction kernel whether it runs now or batched with the stage's other layers: the same summation order
+    const ReduceDesc d{(const float*)ws, a.part_stride, pl.splits, dw, n, dbias, nb, bscale, accumulate};
+    if (deferred) { *deferred = d; return hipSuccess; }
+    return launch_reduce_batch(&d, 1, st);
 }
 
 // The same reduction for a short output vector (a first layer's few thousand weights) and many partials:

@@ -219,4 +219,108 @@ hipError_t fc_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw,
     return hipGetLastError();
 }
 
+// ---- the same weight gradient contracted once per mini-batch ----------------------------------------------
+// Accumulating dW micro-batch by micro-batch reads and writes the whole fp32 gradient matrix every time (822 MB
+// per micro-batch for a 25088 x 4096 layer).  A schedule that knows all M micro-batches of the mini-batch can
+// instead keep the layer's inputs and output gradients -- a few rows each -- and contract over all M*m rows at
+// the last one: dW is written once.  (The sum over the rows is the same; only its rounding order differs.)
+bool fc_staged_ok(const ConvGeom& g) {
+    return fc_skinny_ok(g) && ((int64_t)g.m * g.Cout) % 8 == 0 && (int64_t)g.Cout * g.K() >= 32768;
+}
+size_t fc_stage_x_bytes(const ConvGeom& g) { return (size_t)LPM_FC_STAGE_SLOTS * g.m * g.K() * 2; }
+size_t fc_stage_dz_bytes(const ConvGeom& g) { return (size_t)LPM_FC_STAGE_SLOTS * g.m * g.Cout * 2; }
+
+__global__ void __launch_bounds__(256) fc_stage_copy(const uint4* __restrict__ x, uint4* __restrict__ xs, int nx,
+                                                     const uint4* __restrict__ dz, uint4* __restrict__ dzs, int nd) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < nx) xs[i] = x[i];
+    else if (i - nx < nd) dzs[i - nx] = dz[i - nx];
+}
+
+// rows of micro-batch `slot` into the staging areas (xs [slots][m][K], dzs [slots][m][Cout], bf16)
+hipError_t fc_stage_rows(const ConvGeom& g, const void* x, const void* dz, void* xs, void* dzs, int slot, hipStream_t st) {
+    const int nx = (int)((size_t)g.m * g.K() * 2 / 16), nd = (int)((size_t)g.m * g.Cout * 2 / 16);
+    hipLaunchKernelGGL(fc_stage_copy, dim3((unsigned)((nx + nd + 255) / 256)), dim3(256), 0, st, (const uint4*)x,
+                       (uint4*)xs + (size_t)slot * nx, nx, (const uint4*)dz, (uint4*)dzs + (size_t)slot * nd, nd);
+    return hipGetLastError();
+}
+
+// dW[co][k] (+)= sum over R rows of dz[r][co] * x[r][k]: a thread owns 8 columns of 16 output channels and walks the
+// rows 8 at a time (dz of the block's channels sits in LDS as floats, read as broadcasts).
+constexpr int FCR_CPB = 16;
+__global__ void __launch_bounds__(256) fc_wgrad_rows(const uint16_t* __restrict__ x, const uint16_t* __restrict__ dz,
+                                                     float* __restrict__ dw, float* __restrict__ db,
+                                                     const float* __restrict__ bscale, int R, int Cout, int K, int accumulate) {
+    extern __shared__ float dzr[];               // [R rounded up to 8][FCR_CPB]
+    const int tid = threadIdx.x;
+    const int k0 = (blockIdx.x * blockDim.x + tid) * 8;
+    const int c0 = blockIdx.y * FCR_CPB, cn = min(FCR_CPB, Cout - c0);
+    const int R8 = (R + 7) & ~7;
+    for (int i = tid; i < R8 * FCR_CPB; i += blockDim.x) {
+        const int r = i / FCR_CPB, c = i % FCR_CPB;
+        dzr[i] = (r < R && c < cn) ? bf2f(dz[(size_t)r * Cout + c0 + c]) : 0.f;
+    }
+    __syncthreads();
+    if (db && blockIdx.x == 0 && tid < cn) {
+        float sum = 0.f;
+        for (int r = 0; r < R; ++r) sum += dzr[r * FCR_CPB + tid];
+        const int co = c0 + tid;
+        if (bscale) sum /= bscale[co];
+        db[co] = accumulate ? db[co] + sum : sum;
+    }
+    if (k0 >= K) return;
+    float acc[FCR_CPB][8];
+#pragma unroll
+    for (int c = 0; c < FCR_CPB; ++c)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[c][j] = 0.f;
+    for (int rg = 0; rg < R8; rg += 8) {
+        float xr[8][8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            if (rg + r < R) unpack8(*reinterpret_cast<const uint4*>(x + (size_t)(rg + r) * K + k0), xr[r]);
+            else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) xr[r][j] = 0.f;
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+#pragma unroll
+            for (int c = 0; c < FCR_CPB; ++c) {
+                const float d = dzr[(rg + r) * FCR_CPB + c];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[c][j] = fmaf(d, xr[r][j], acc[c][j]);
+            }
+    }
+    const size_t rs = (size_t)K / 4;
+    float4* row = reinterpret_cast<float4*>(dw + (size_t)c0 * K + k0);
+#pragma unroll
+    for (int c = 0; c < FCR_CPB; ++c) {
+        if (c < cn) {        // (no early exit: the unrolled loop keeps the accumulators in registers)
+            float4 a0 = make_float4(acc[c][0], acc[c][1], acc[c][2], acc[c][3]);
+            float4 a1 = make_float4(acc[c][4], acc[c][5], acc[c][6], acc[c][7]);
+            if (accumulate) {
+                const float4 o0 = row[(size_t)c * rs], o1 = row[(size_t)c * rs + 1];
+                a0.x += o0.x; a0.y += o0.y; a0.z += o0.z; a0.w += o0.w;
+                a1.x += o1.x; a1.y += o1.y; a1.z += o1.z; a1.w += o1.w;
+            }
+            row[(size_t)c * rs] = a0;
+            row[(size_t)c * rs + 1] = a1;
+        }
+    }
+}
+
+// contraction over the first `slots` staged micro-batches
+hipError_t fc_wgrad_staged(const ConvGeom& g, const void* xs, const void* dzs, int slots, float* dw, float* dbias,
+                           const float* bscale, int accumulate, hipStream_t st) {
+    const int K = g.K(), R = slots * g.m;
+    const int threads = std::min(256, ((K / 8 + 63) / 64) * 64);
+    const dim3 grid((unsigned)((K / 8 + threads - 1) / threads), (unsigned)((g.Cout + FCR_CPB - 1) / FCR_CPB));
+    const size_t lds = (size_t)((R + 7) & ~7) * FCR_CPB * sizeof(float);
+    hipLaunchKernelGGL(fc_wgrad_rows, grid, dim3(threads), lds, st, (const uint16_t*)xs, (const uint16_t*)dzs, dw, dbias,
+                       bscale, R, g.Cout, K, accumulate);
+    return hipGetLastError();
+}
+
 }  // namespace lpm

@@ -186,8 +186,12 @@ int32_t bwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStrea
     if (z < s->Z - 1) dy = a.bufs[z + 1].grad_in[slot];
     else if (!sg->loss) dy = (const char*)a.dy_batch + (size_t)j * sg->T(sg->t_out).bytes;
     void* dx = (z > 0 || a.dx_wanted) ? b.grad_in[slot] : nullptr;
+    // synchronous step over few enough micro-batches: large fully connected layers file their operands per micro-batch and
+    // contract the weight gradient once, at the last one (the weight phases of a stage run in micro-batch order)
+    const bool staged = ver < 0 && s->M <= LPM_FC_STAGE_SLOTS;
     return lpm_stage_backward_on(sg, in, b.act_out[slot], dy, dx, ver_params(b, ver), ver_lowp(b, ver), b.stash[slot], b.grads,
-                                 ver < 0 ? j > 0 : 0, b.bwd_ws, st, wst, j & 1, phases);
+                                 ver < 0 ? j > 0 : 0, b.bwd_ws, st, wst, j & 1, phases, staged ? j : -1,
+                                 staged && j == s->M - 1 ? s->M : 0);
 }
 
 // ver < 0: the one update of the synchronous step; else U_{z,ver}: version ver -> version ver + 1

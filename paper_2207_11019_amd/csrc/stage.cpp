@@ -75,7 +75,7 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
 
     // parameters: trainable (W, bias per layer) first, frozen scales after
     s->lay.resize((size_t)(last - first));
-    size_t off = 0, lowp = 0, kws = 0, wws = 0, fws = 0;
+    size_t off = 0, lowp = 0, kws = 0, wws = 0, fws = 0, fcs = 0;
     for (int32_t i = first; i < last; ++i) {
         LayerRt& lr = s->Ly(i);
         lr.d = s->net[i];
@@ -97,6 +97,10 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
         }
         lr.wws_off = wws;                        // every layer its own area: the reductions of a pass run in one launch
         wws += align_up(wgrad_ws_bytes(dtype, lr.g), 256);
+        if (dtype == LPM_BF16 && fc_staged_ok(lr.g)) {
+            lr.fcs_x_off = fcs;  fcs += align_up(fc_stage_x_bytes(lr.g), 256);
+            lr.fcs_dz_off = fcs; fcs += align_up(fc_stage_dz_bytes(lr.g), 256);
+        }
         kws = std::max(kws, align_up(dgrad_ws_bytes(dtype, lr.g), 256));
         kws = std::max(kws, align_up(epi_bwd_ws_bytes(lr.g.rows_out(), l.cout), 256));
         fws = std::max(fws, align_up(fwd_ws_bytes(dtype, lr.g), 256));
@@ -137,7 +141,11 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
     s->gws_bytes = gws;
     s->kws_off = 2 * gws;
     s->wws_off = 2 * gws + kws;
-    s->bwd_ws = std::max<size_t>(2 * gws + kws + wws, 256);
+    for (int32_t i = first; i < last; ++i) {     // the staging areas follow the kernel scratch
+        LayerRt& lr = s->Ly(i);
+        if (lr.fcs_x_off != NO) { lr.fcs_x_off += 2 * gws + kws + wws; lr.fcs_dz_off += 2 * gws + kws + wws; }
+    }
+    s->bwd_ws = std::max<size_t>(2 * gws + kws + wws + fcs, 256);
     s->fwd_ws = std::max<size_t>(fws, 256);
     *out = s;
     return LPM_OK;
@@ -307,7 +315,8 @@ extern "C" int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y
 int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const void* dy, void* dx,
                               const float* params, const void* lowp, const void* stash, float* grads,
                               int32_t accumulate, void* bwd_ws, void* stream, void* wstream, int32_t parity,
-                              int32_t phases) {
+                              int32_t phases, int32_t fc_slot, int32_t fc_flush) {
+    if (fc_slot >= LPM_FC_STAGE_SLOTS || fc_flush > LPM_FC_STAGE_SLOTS) return fail(LPM_EINVAL, "internal: staging slot out of range");
     if (!s || !x || !y || !params || !stash || !grads || !bwd_ws) return fail(LPM_EINVAL, "NULL argument");
     if (!s->loss && !dy) return fail(LPM_EINVAL, "dy is NULL for a stage that is not a loss stage");
     if (s->dtype == LPM_BF16 && !lowp) return fail(LPM_EINVAL, "lowp is NULL for a bf16 stage");
@@ -333,6 +342,19 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
     if (!deferred && !(do_data && do_weights)) return fail(LPM_EINVAL, "a captured backward pass cannot be split into phases");
     if (!do_data && (!do_weights || !wstream)) return fail(LPM_EINVAL, "internal: bad phase selection");
     struct WgradJob { const LayerRt* lr; const void* xin; const void* dz; float* wdb; const float* sc; };
+    // One weight gradient on stream q.  fc_slot >= 0: a fully connected layer with staging areas only files its
+    // operands under that micro-batch slot; fc_flush = M > 0 then contracts slots 0..M-1 (the whole mini-batch, so
+    // the result overwrites the accumulator).
+    auto one_wgrad = [&](const WgradJob& j, hipStream_t q, ReduceDesc* d) -> hipError_t {
+        const LayerRt& lr = *j.lr;
+        if (fc_slot >= 0 && lr.fcs_x_off != NO) {
+            if (d) d->splits = 0;
+            hipError_t e = fc_stage_rows(lr.g, j.xin, j.dz, ws + lr.fcs_x_off, ws + lr.fcs_dz_off, fc_slot, q);
+            if (e != hipSuccess || fc_flush <= 0) return e;
+            return fc_wgrad_staged(lr.g, ws + lr.fcs_x_off, ws + lr.fcs_dz_off, fc_flush, grads + lr.w_off, j.wdb, j.sc, 0, q);
+        }
+        return launch_conv_wgrad(s->dtype, lr.g, j.xin, j.dz, grads + lr.w_off, j.wdb, j.sc, acc, (char*)wws + lr.wws_off, q, d);
+    };
     std::vector<WgradJob> jobs;            // eager: the weight phase, in layer order (last layer first)
     std::vector<hipGraphNode_t> wtail;     // capture: frontier left by the last weight gradient
     auto frontier = [&](std::vector<hipGraphNode_t>& out) -> hipError_t {
@@ -420,7 +442,7 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                     LPM_HIP(frontier(before));
                     if (!wtail.empty())       // weight gradients share one scratch area: keep them in a chain
                         LPM_HIP(hipStreamUpdateCaptureDependencies(st, wtail.data(), wtail.size(), hipStreamAddCaptureDependencies));
-                    LPM_HIP(launch_conv_wgrad(s->dtype, lr.g, xin, dz, grads + lr.w_off, wdb, sc, acc, (char*)wws + lr.wws_off, st));
+                    LPM_HIP(one_wgrad(WgradJob{&lr, xin, dz, wdb, sc}, st, nullptr));
                     LPM_HIP(frontier(wtail));
                     LPM_HIP(hipStreamUpdateCaptureDependencies(st, before.data(), before.size(), hipStreamSetCaptureDependencies));
                 }
@@ -471,8 +493,7 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
         red.reserve(jobs.size());
         for (const WgradJob& j : jobs) {
             ReduceDesc d{};
-            LPM_HIP(launch_conv_wgrad(s->dtype, j.lr->g, j.xin, j.dz, grads + j.lr->w_off, j.wdb, j.sc, acc,
-                                      (char*)wws + j.lr->wws_off, wst, &d));
+            LPM_HIP(one_wgrad(j, wst, &d));
             if (d.splits > 0) red.push_back(d);
         }
         if (!red.empty()) LPM_HIP(launch_reduce_batch(red.data(), (int)red.size(), wst));

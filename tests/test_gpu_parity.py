@@ -30,6 +30,9 @@ CASES = [
     ("tiny_lenet_bf16", wl.tiny_lenet, 8, 4, 3, 1),
     ("tiny_resnet_bf16", wl.tiny_resnet, 6, 3, 2, 1),
     ("tiny_vgg_bf16", wl.tiny_vgg, 8, 2, 3, 1),
+    # a 512 x 64 fully connected layer at 2 samples per micro-batch: its weight gradient is contracted once per mini-batch
+    ("tiny_fc_bf16", wl.tiny_fc, 8, 4, 2, 1),
+    ("tiny_fc_bf16_one_stage", wl.tiny_fc, 6, 3, 1, 1),
 ]
 
 

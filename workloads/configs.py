@@ -188,6 +188,14 @@ def tiny_linear():
     return b.finish()
 
 
+def tiny_fc():
+    """One convolution, then a fully connected layer of 512 x 64 weights and a 10-class head: large enough for the
+    kernels that stream a weight matrix at a few samples per micro-batch."""
+    b = _Builder(3, 8, 8)
+    b.conv(8, 3, pad=1); b.fc(64); b.fc(10, relu=False); b.loss()
+    return b.finish()
+
+
 def tiny_resnet(hw=8, widths=(4, 6), n_classes=5):
     """Stem + one identity block + one strided projection block + GAP + FC."""
     return resnet18_cifar(widths=widths, blocks=1, hw=hw, n_classes=n_classes)
