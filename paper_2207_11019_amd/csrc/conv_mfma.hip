@@ -904,7 +904,12 @@ static WgradPlan plan_wgrad_flat(const ConvGeom& g) {
     pl.rt_total = (int)((R + pl.bk - 1) / pl.bk);
     pl.co_tiles = (g.Cout + 63) / 64;
     pl.ci_tiles = 1;
-    int s = std::min(std::min(512 / pl.co_tiles, std::max(1, pl.rt_total / 4)), 256);
+    // the 2-byte gathers make a pixel tile slow (about 2 us), so blocks take as few as two of them
+    int s = std::min(std::min(512 / pl.co_tiles, std::max(1, pl.rt_total / 2)), 256);
+#ifdef LPM_TUNE
+    if (const char* e = getenv("LPM_T_SPLITS")) s = std::max(1, std::min(atoi(e), pl.rt_total));
+    if (const char* e = getenv("LPM_T_BK")) { pl.bk = atoi(e) >= 128 ? 128 : 64; pl.rt_total = (int)((R + pl.bk - 1) / pl.bk); }
+#endif
     pl.rt_per = (pl.rt_total + s - 1) / s;
     pl.splits = (pl.rt_total + pl.rt_per - 1) / pl.rt_per;
     return pl;

@@ -500,22 +500,56 @@ hipError_t launch_f32_to_bf16(const float* src, uint16_t* dst, size_t n, hipStre
     return hipGetLastError();
 }
 
-// dst[ci][k][co] = bf16(src[co][k][ci])   (k = kh*Kw+kw)
-__global__ void __launch_bounds__(256) weight_transpose_kernel(const float* __restrict__ src, uint16_t* __restrict__ dst,
-                                                               int Cout, int KK, int Cin) {
-    const int64_t total = (int64_t)Cout * KK * Cin;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
-    const int co = (int)(idx % Cout);
-    const int k = (int)((idx / Cout) % KK);
-    const int ci = (int)(idx / ((int64_t)Cout * KK));
-    dst[idx] = f2bf(src[((int64_t)co * KK + k) * Cin + ci]);
+// dst[ci][k][co] = bf16(src[co][k][ci])   (k = kh*Kw+kw), for up to LPM_TRANSPOSE_BATCH weight tensors in one launch.
+// A block moves a 32 (co) x 32 (ci) tile of one filter tap through LDS: reads run along ci, writes along co.
+struct TransposeBatchArgs {
+    TransposeDesc d[LPM_TRANSPOSE_BATCH];
+    int first[LPM_TRANSPOSE_BATCH + 1];      // first block of every tensor
+    int count;
+};
+
+__global__ void __launch_bounds__(256) weight_transpose_batch(TransposeBatchArgs a) {
+    __shared__ float tile[32][33];
+    int k = 0;
+    while (k + 1 < a.count && (int)blockIdx.x >= a.first[k + 1]) ++k;
+    const TransposeDesc& d = a.d[k];
+    int t = (int)blockIdx.x - a.first[k];
+    const int cit = (d.Cin + 31) / 32, cot = (d.Cout + 31) / 32;
+    const int ci0 = (t % cit) * 32; t /= cit;
+    const int co0 = (t % cot) * 32;
+    const int kk = t / cot;
+    const int lx = threadIdx.x & 31, ly = threadIdx.x >> 5;      // 32 x 8
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int co = co0 + ly + r * 8, ci = ci0 + lx;
+        tile[ly + r * 8][lx] = (co < d.Cout && ci < d.Cin) ? d.src[((size_t)co * d.KK + kk) * d.Cin + ci] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int ci = ci0 + ly + r * 8, co = co0 + lx;
+        if (ci < d.Cin && co < d.Cout) d.dst[((size_t)ci * d.KK + kk) * d.Cout + co] = f2bf(tile[lx][ly + r * 8]);
+    }
 }
 
-hipError_t launch_weight_transpose_bf16(const float* src, uint16_t* dst, int32_t Cout, int32_t KhKw, int32_t Cin, hipStream_t s) {
-    const int64_t total = (int64_t)Cout * KhKw * Cin;
-    hipLaunchKernelGGL(weight_transpose_kernel, dim3(nblk(total, 256)), dim3(256), 0, s, src, dst, Cout, KhKw, Cin);
-    return hipGetLastError();
+hipError_t launch_weight_transpose_batch(const TransposeDesc* d, int count, hipStream_t s) {
+    for (int done = 0; done < count;) {
+        TransposeBatchArgs a{};
+        int tot = 0, k = 0;
+        for (; k < LPM_TRANSPOSE_BATCH && done + k < count; ++k) {
+            a.d[k] = d[done + k];
+            a.first[k] = tot;
+            tot += ((a.d[k].Cin + 31) / 32) * ((a.d[k].Cout + 31) / 32) * a.d[k].KK;
+        }
+        a.first[k] = tot;
+        a.count = k;
+        done += k;
+        if (tot == 0) continue;
+        hipLaunchKernelGGL(weight_transpose_batch, dim3((unsigned)tot), dim3(256), 0, s, a);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 __global__ void __launch_bounds__(256) fill_kernel(float* p, size_t n, float v) {

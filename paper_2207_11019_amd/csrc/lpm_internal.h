@@ -106,9 +106,10 @@ hipError_t launch_softmax_ce(int dtype, int32_t m, int32_t C, const void* logits
 hipError_t launch_sgd(const float* p_in, float* p, uint16_t* lowp, float* g, float* v, size_t n, float lr, float mu, int zero_g,
                       hipStream_t st);
 hipError_t launch_f32_to_bf16(const float* src, uint16_t* dst, size_t n, hipStream_t st);
-// dst[ci][kh][kw][co] = bf16(src[co][kh][kw][ci])
-hipError_t launch_weight_transpose_bf16(const float* src, uint16_t* dst, int32_t Cout, int32_t KhKw, int32_t Cin,
-                                        hipStream_t st);
+// dst[ci][kh][kw][co] = bf16(src[co][kh][kw][ci]) for a list of weight tensors, one launch per LPM_TRANSPOSE_BATCH of them
+struct TransposeDesc { const float* src; uint16_t* dst; int32_t Cout, KK, Cin; };
+constexpr int LPM_TRANSPOSE_BATCH = 24;
+hipError_t launch_weight_transpose_batch(const TransposeDesc* d, int count, hipStream_t st);
 hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t st);
 
 }  // namespace lpm

@@ -226,6 +226,17 @@ extern "C" int32_t lpm_stage_grad_offset(const lpm_stage* s, int32_t t, size_t* 
     return LPM_OK;
 }
 
+// the [Cin][Kh][Kw][Cout] copies of every layer whose data gradient reads one, all in one launch
+static hipError_t transpose_copies(const lpm_stage* s, const float* params, void* lowp, hipStream_t st) {
+    std::vector<TransposeDesc> d;
+    for (int32_t i = s->first; i < s->last; ++i) {
+        const LayerRt& lr = s->Ly(i);
+        if (lr.lowp_wt_off != NO)
+            d.push_back(TransposeDesc{params + lr.w_off, (uint16_t*)((char*)lowp + lr.lowp_wt_off), lr.d.cout, lr.d.kh * lr.d.kw, lr.d.cin});
+    }
+    return d.empty() ? hipSuccess : launch_weight_transpose_batch(d.data(), (int)d.size(), st);
+}
+
 extern "C" int32_t lpm_stage_sync_lowp(lpm_stage* s, const float* params, void* lowp, void* stream) {
     if (!s || !params) return fail(LPM_EINVAL, "NULL argument");
     if (s->dtype != LPM_BF16) return LPM_OK;
@@ -233,12 +244,7 @@ extern "C" int32_t lpm_stage_sync_lowp(lpm_stage* s, const float* params, void* 
     if (misaligned(params) || misaligned(lowp)) return fail(LPM_EALIGN, "buffers must be 256-byte aligned");
     hipStream_t st = (hipStream_t)stream;
     LPM_HIP(launch_f32_to_bf16(params, (uint16_t*)lowp, s->n_trainable, st));
-    for (int32_t i = s->first; i < s->last; ++i) {
-        const LayerRt& lr = s->Ly(i);
-        if (lr.lowp_wt_off != NO)
-            LPM_HIP(launch_weight_transpose_bf16(params + lr.w_off, (uint16_t*)((char*)lowp + lr.lowp_wt_off), lr.d.cout,
-                                                 lr.d.kh * lr.d.kw, lr.d.cin, st));
-    }
+    LPM_HIP(transpose_copies(s, params, lowp, st));
     return LPM_OK;
 }
 
@@ -525,11 +531,6 @@ int32_t lpm_stage_update_to(lpm_stage* s, const float* params_in, float* params,
         return LPM_OK;
     }
     LPM_HIP(launch_sgd(params_in, params, (uint16_t*)lowp, grads, momentum, s->n_trainable, lr_, mu, zero_grads, st));
-    for (int32_t i = s->first; i < s->last; ++i) {
-        const LayerRt& lr = s->Ly(i);
-        if (lr.lowp_wt_off != NO)
-            LPM_HIP(launch_weight_transpose_bf16(params + lr.w_off, (uint16_t*)((char*)lowp + lr.lowp_wt_off), lr.d.cout,
-                                                 lr.d.kh * lr.d.kw, lr.d.cin, st));
-    }
+    LPM_HIP(transpose_copies(s, params, lowp, st));
     return LPM_OK;
 }
