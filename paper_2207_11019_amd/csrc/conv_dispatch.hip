@@ -39,6 +39,10 @@ hipError_t fc_dgrad(const ConvGeom& g, const void* dz, const void* w, void* dx, 
 hipError_t fc_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* bscale,
                     int accumulate, hipStream_t st);
 
+bool fc_staged_ok(const ConvGeom& g);
+hipError_t fc_wgrad_staged(const ConvGeom& g, const void* xs, const void* dzs, int slots, float* dw, float* dbias,
+                           const float* bscale, int accumulate, hipStream_t st);
+
 bool mfma_wgrad_flat_ok(const ConvGeom& g);
 size_t mfma_wgrad_flat_ws_bytes(const ConvGeom& g);
 hipError_t mfma_conv_wgrad_flat(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias,
@@ -89,6 +93,32 @@ hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const 
     if (dtype == LPM_BF16 && mfma_wgrad_flat_ok(g)) return mfma_conv_wgrad_flat(g, x, dz, dw, dbias, bscale, accumulate, ws, st);
     if (dbias) return hipErrorInvalidValue;      // callers ask wgrad_fuses_bias first
     return conv_wgrad_generic_launch(dtype, g, x, dz, dw, accumulate, ws, st);
+}
+
+// Staging pays when one read-modify-write pass over dW moves several times the bytes of the staged operands.
+bool wgrad_staged_ok(int dtype, const ConvGeom& g) {
+    if (dtype != LPM_BF16) return false;
+    if (fc_staged_ok(g)) return true;
+    if (fc_skinny_ok(g) || !mfma_wgrad_ok(g)) return false;
+    const int64_t dw_rmw = (int64_t)g.Cout * g.K() * 8, staged = (g.rows_in() * g.Cin + g.rows_out() * g.Cout) * 2;
+    return (int64_t)g.Cout * g.K() >= 32768 && dw_rmw >= 6 * staged;
+}
+
+static ConvGeom staged_geom(const ConvGeom& g, int slots) { ConvGeom b = g; b.m = g.m * slots; return b; }
+
+size_t wgrad_staged_ws_bytes(int dtype, const ConvGeom& g) {
+    if (!wgrad_staged_ok(dtype, g) || fc_staged_ok(g)) return 0;
+    size_t b = 0;
+    for (int s = 1; s <= LPM_FC_STAGE_SLOTS; ++s) b = std::max(b, wgrad_ws_bytes(dtype, staged_geom(g, s)));
+    return b;
+}
+
+hipError_t launch_wgrad_staged(int dtype, const ConvGeom& g, const void* xs, const void* dzs, int slots, float* dw, float* dbias,
+                               const float* bscale, void* ws, hipStream_t st, ReduceDesc* deferred) {
+    if (deferred) deferred->splits = 0;
+    if (fc_staged_ok(g)) return fc_wgrad_staged(g, xs, dzs, slots, dw, dbias, bscale, 0, st);
+    // the staged micro-batches are one larger batch in the same layout
+    return launch_conv_wgrad(dtype, staged_geom(g, slots), xs, dzs, dw, dbias, bscale, 0, ws, st, deferred);
 }
 
 }  // namespace lpm

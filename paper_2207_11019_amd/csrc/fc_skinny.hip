@@ -227,8 +227,6 @@ hipError_t fc_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw,
 bool fc_staged_ok(const ConvGeom& g) {
     return fc_skinny_ok(g) && ((int64_t)g.m * g.Cout) % 8 == 0 && (int64_t)g.Cout * g.K() >= 32768;
 }
-size_t fc_stage_x_bytes(const ConvGeom& g) { return (size_t)LPM_FC_STAGE_SLOTS * g.m * g.K() * 2; }
-size_t fc_stage_dz_bytes(const ConvGeom& g) { return (size_t)LPM_FC_STAGE_SLOTS * g.m * g.Cout * 2; }
 
 __global__ void __launch_bounds__(256) fc_stage_copy(const uint4* __restrict__ x, uint4* __restrict__ xs, int nx,
                                                      const uint4* __restrict__ dz, uint4* __restrict__ dzs, int nd) {
@@ -237,9 +235,10 @@ __global__ void __launch_bounds__(256) fc_stage_copy(const uint4* __restrict__ x
     else if (i - nx < nd) dzs[i - nx] = dz[i - nx];
 }
 
-// rows of micro-batch `slot` into the staging areas (xs [slots][m][K], dzs [slots][m][Cout], bf16)
-hipError_t fc_stage_rows(const ConvGeom& g, const void* x, const void* dz, void* xs, void* dzs, int slot, hipStream_t st) {
-    const int nx = (int)((size_t)g.m * g.K() * 2 / 16), nd = (int)((size_t)g.m * g.Cout * 2 / 16);
+// a layer's input and output gradient of micro-batch `slot` into the staging areas (xs [slots][m][H][W][Cin],
+// dzs [slots][m][Ho][Wo][Cout], bf16; both sizes are multiples of 16 bytes)
+hipError_t stage_operands(const ConvGeom& g, const void* x, const void* dz, void* xs, void* dzs, int slot, hipStream_t st) {
+    const int nx = (int)((size_t)g.rows_in() * g.Cin * 2 / 16), nd = (int)((size_t)g.rows_out() * g.Cout * 2 / 16);
     hipLaunchKernelGGL(fc_stage_copy, dim3((unsigned)((nx + nd + 255) / 256)), dim3(256), 0, st, (const uint4*)x,
                        (uint4*)xs + (size_t)slot * nx, nx, (const uint4*)dz, (uint4*)dzs + (size_t)slot * nd, nd);
     return hipGetLastError();

@@ -68,15 +68,17 @@ hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const 
 constexpr int LPM_REDUCE_BATCH = 24;
 // the reductions of up to LPM_REDUCE_BATCH weight gradients in one launch (each in its fixed split order)
 hipError_t launch_reduce_batch(const ReduceDesc* d, int count, hipStream_t st);
-// Fully connected layers at a few samples per micro-batch: the schedule may keep the operands of every micro-batch
-// (slot j) and contract the weight gradient once per mini-batch instead of accumulating it M times.
+// Layers whose fp32 gradient matrix is much larger than their activations (fully connected layers at a few samples
+// per micro-batch, 512-channel convolutions over 2x2 or 4x4 images): accumulating dW micro-batch by micro-batch
+// reads and writes the whole matrix M times.  A schedule may instead file the layer's input and output gradient of
+// every micro-batch under slot j and contract over the whole mini-batch once, at the last one.
 constexpr int LPM_FC_STAGE_SLOTS = 32;
-bool fc_staged_ok(const ConvGeom& g);
-size_t fc_stage_x_bytes(const ConvGeom& g);
-size_t fc_stage_dz_bytes(const ConvGeom& g);
-hipError_t fc_stage_rows(const ConvGeom& g, const void* x, const void* dz, void* xs, void* dzs, int slot, hipStream_t st);
-hipError_t fc_wgrad_staged(const ConvGeom& g, const void* xs, const void* dzs, int slots, float* dw, float* dbias,
-                           const float* bscale, int accumulate, hipStream_t st);
+bool wgrad_staged_ok(int dtype, const ConvGeom& g);
+size_t wgrad_staged_ws_bytes(int dtype, const ConvGeom& g);      // split partials of the contraction, any slot count
+hipError_t stage_operands(const ConvGeom& g, const void* x, const void* dz, void* xs, void* dzs, int slot, hipStream_t st);
+// dw = (not +=) the gradient over the first `slots` staged micro-batches; `deferred` as for launch_conv_wgrad
+hipError_t launch_wgrad_staged(int dtype, const ConvGeom& g, const void* xs, const void* dzs, int slots, float* dw, float* dbias,
+                               const float* bscale, void* ws, hipStream_t st, ReduceDesc* deferred);
 bool wgrad_fuses_bias(int dtype, const ConvGeom& g);
 bool dgrad_uses_wt(int dtype, const ConvGeom& g);
 size_t wgrad_ws_bytes(int dtype, const ConvGeom& g);

@@ -175,8 +175,9 @@ int32_t fwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStrea
 }
 
 // wst: stream of the weight phase (see lpm_stage_backward_on)
+// by_layer: the two phases come as separate calls and the weight phase follows the data phase layer by layer
 int32_t bwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStream_t st, hipStream_t wst,
-               int32_t phases = LPM_PHASE_DATA | LPM_PHASE_WEIGHTS, int32_t ver = -1) {
+               int32_t phases = LPM_PHASE_DATA | LPM_PHASE_WEIGHTS, int32_t ver = -1, bool by_layer = false) {
     lpm_stage* sg = s->st[(size_t)z];
     const int32_t slot = j % s->window;
     const lpm_stage_buffers& b = a.bufs[z];
@@ -191,7 +192,7 @@ int32_t bwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStrea
     const bool staged = ver < 0 && s->M <= LPM_FC_STAGE_SLOTS;
     return lpm_stage_backward_on(sg, in, b.act_out[slot], dy, dx, ver_params(b, ver), ver_lowp(b, ver), b.stash[slot], b.grads,
                                  ver < 0 ? j > 0 : 0, b.bwd_ws, st, wst, j & 1, phases, staged ? j : -1,
-                                 staged && j == s->M - 1 ? s->M : 0);
+                                 staged && j == s->M - 1 ? s->M : 0, by_layer ? j % LPM_MAX_WINDOW : -1);
 }
 
 // ver < 0: the one update of the synchronous step; else U_{z,ver}: version ver -> version ver + 1
@@ -329,7 +330,7 @@ int32_t overlapped_role(lpm_schedule* s, const RunArgs& a, int32_t role, uint64_
                     if ((rc = await_record(s, s->rec_w[u], epoch))) return rc;
                     LPM_HIP(hipStreamWaitEvent(a.sb, s->ev_w[u], 0));
                 }
-                if ((rc = bwd_op(s, a, z, j, a.sb, sw, LPM_PHASE_DATA, async ? j : -1))) return rc;
+                if ((rc = bwd_op(s, a, z, j, a.sb, sw, LPM_PHASE_DATA, async ? j : -1, z == 0 && !async))) return rc;
                 LPM_HIP(hipEventRecord(s->ev_b[(size_t)j * Z + z], a.sb));
                 publish(s->rec_b[(size_t)j * Z + z], epoch);
             }
@@ -339,8 +340,14 @@ int32_t overlapped_role(lpm_schedule* s, const RunArgs& a, int32_t role, uint64_
             for (int32_t z = Z - 1; z >= 0; --z) {
                 const size_t i = (size_t)j * Z + z;
                 if ((rc = await_record(s, s->rec_b[i], epoch))) return rc;
-                LPM_HIP(hipStreamWaitEvent(sw, s->ev_b[i], 0));
-                if ((rc = bwd_op(s, a, z, j, a.sb, sw, LPM_PHASE_WEIGHTS, async ? j : -1))) return rc;
+                // Stage 0 closes the micro-batch, and the next forward chain but one waits for it: there the weight
+                // gradients follow the data phase layer by layer (the events were recorded before rec_b was published)
+                const bool by_layer = z == 0 && !async;
+                if (!by_layer) LPM_HIP(hipStreamWaitEvent(sw, s->ev_b[i], 0));
+                if ((rc = bwd_op(s, a, z, j, a.sb, sw, LPM_PHASE_WEIGHTS, async ? j : -1, by_layer))) return rc;
+                // whatever follows on this stream (the update, the record that closes the micro-batch) is still ordered
+                // after the whole data phase
+                if (by_layer) LPM_HIP(hipStreamWaitEvent(sw, s->ev_b[i], 0));
                 if (async) {
                     if ((rc = upd_op(s, a, z, sw, j))) return rc;
                     if (j == M - 1 && (rc = copy_final_version(s, a, z, sw))) return rc;

@@ -96,10 +96,10 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
             gws += align_up(o.elems() * (size_t)microbatch * s->esz, 256);
         }
         lr.wws_off = wws;                        // every layer its own area: the reductions of a pass run in one launch
-        wws += align_up(wgrad_ws_bytes(dtype, lr.g), 256);
-        if (dtype == LPM_BF16 && fc_staged_ok(lr.g)) {
-            lr.fcs_x_off = fcs;  fcs += align_up(fc_stage_x_bytes(lr.g), 256);
-            lr.fcs_dz_off = fcs; fcs += align_up(fc_stage_dz_bytes(lr.g), 256);
+        wws += align_up(std::max(wgrad_ws_bytes(dtype, lr.g), wgrad_staged_ws_bytes(dtype, lr.g)), 256);
+        if (wgrad_staged_ok(dtype, lr.g)) {
+            lr.fcs_x_off = fcs;  fcs += align_up((size_t)LPM_FC_STAGE_SLOTS * lr.g.rows_in() * lr.g.Cin * 2, 256);
+            lr.fcs_dz_off = fcs; fcs += align_up((size_t)LPM_FC_STAGE_SLOTS * lr.g.rows_out() * lr.g.Cout * 2, 256);
         }
         kws = std::max(kws, align_up(dgrad_ws_bytes(dtype, lr.g), 256));
         kws = std::max(kws, align_up(epi_bwd_ws_bytes(lr.g.rows_out(), l.cout), 256));
@@ -154,6 +154,7 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
 lpm_stage::~lpm_stage() {
     if (ev_fork) (void)hipEventDestroy(ev_fork);
     if (ev_join) (void)hipEventDestroy(ev_join);
+    for (hipEvent_t v : ev_layer) if (v) (void)hipEventDestroy(v);
 }
 
 // Borrows the side stream and creates the events on first use (needs a device; stage creation does not).
@@ -168,6 +169,18 @@ int32_t lpm_stage_prepare(lpm_stage* s) {
         if (ej) (void)hipEventDestroy(ej);
         return hip_fail(e, "hipEventCreateWithFlags");
     }
+    std::vector<hipEvent_t> evl((size_t)(s->last - s->first) * LPM_MAX_WINDOW, nullptr);
+    for (int32_t i = s->first; i < s->last && e == hipSuccess; ++i) {
+        if (!has_weights(s->Ly(i).d)) continue;
+        for (int k = 0; k < LPM_MAX_WINDOW && e == hipSuccess; ++k)
+            e = hipEventCreateWithFlags(&evl[(size_t)(i - s->first) * LPM_MAX_WINDOW + k], hipEventDisableTiming);
+    }
+    if (e != hipSuccess) {
+        for (hipEvent_t v : evl) if (v) (void)hipEventDestroy(v);
+        (void)hipEventDestroy(ej); (void)hipEventDestroy(ef);
+        return hip_fail(e, "hipEventCreateWithFlags");
+    }
+    s->ev_layer = std::move(evl);
     s->ev_join = ej;
     s->ev_fork = ef;
     s->side = st;
@@ -321,7 +334,8 @@ extern "C" int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y
 int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const void* dy, void* dx,
                               const float* params, const void* lowp, const void* stash, float* grads,
                               int32_t accumulate, void* bwd_ws, void* stream, void* wstream, int32_t parity,
-                              int32_t phases, int32_t fc_slot, int32_t fc_flush) {
+                              int32_t phases, int32_t fc_slot, int32_t fc_flush, int32_t layer_slot) {
+    if (layer_slot >= LPM_MAX_WINDOW) return fail(LPM_EINVAL, "internal: layer event slot out of range");
     if (fc_slot >= LPM_FC_STAGE_SLOTS || fc_flush > LPM_FC_STAGE_SLOTS) return fail(LPM_EINVAL, "internal: staging slot out of range");
     if (!s || !x || !y || !params || !stash || !grads || !bwd_ws) return fail(LPM_EINVAL, "NULL argument");
     if (!s->loss && !dy) return fail(LPM_EINVAL, "dy is NULL for a stage that is not a loss stage");
@@ -347,17 +361,22 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
     const bool do_data = (phases & LPM_PHASE_DATA) != 0, do_weights = (phases & LPM_PHASE_WEIGHTS) != 0;
     if (!deferred && !(do_data && do_weights)) return fail(LPM_EINVAL, "a captured backward pass cannot be split into phases");
     if (!do_data && (!do_weights || !wstream)) return fail(LPM_EINVAL, "internal: bad phase selection");
+    // layer_slot >= 0 (the two phases come as separate calls with the same slot): the data phase records, per weight
+    // layer, the point in its stream where that layer's output gradient is final, and the weight phase waits for
+    // that point before the layer's weight gradient instead of for the end of the data phase
+    const bool by_layer = layer_slot >= 0 && deferred && (do_data != do_weights);
     struct WgradJob { const LayerRt* lr; const void* xin; const void* dz; float* wdb; const float* sc; };
-    // One weight gradient on stream q.  fc_slot >= 0: a fully connected layer with staging areas only files its
+    // One weight gradient on stream q.  fc_slot >= 0: a layer with staging areas only files its
     // operands under that micro-batch slot; fc_flush = M > 0 then contracts slots 0..M-1 (the whole mini-batch, so
     // the result overwrites the accumulator).
     auto one_wgrad = [&](const WgradJob& j, hipStream_t q, ReduceDesc* d) -> hipError_t {
         const LayerRt& lr = *j.lr;
         if (fc_slot >= 0 && lr.fcs_x_off != NO) {
             if (d) d->splits = 0;
-            hipError_t e = fc_stage_rows(lr.g, j.xin, j.dz, ws + lr.fcs_x_off, ws + lr.fcs_dz_off, fc_slot, q);
+            hipError_t e = stage_operands(lr.g, j.xin, j.dz, ws + lr.fcs_x_off, ws + lr.fcs_dz_off, fc_slot, q);
             if (e != hipSuccess || fc_flush <= 0) return e;
-            return fc_wgrad_staged(lr.g, ws + lr.fcs_x_off, ws + lr.fcs_dz_off, fc_flush, grads + lr.w_off, j.wdb, j.sc, 0, q);
+            return launch_wgrad_staged(s->dtype, lr.g, ws + lr.fcs_x_off, ws + lr.fcs_dz_off, fc_flush, grads + lr.w_off, j.wdb,
+                                       j.sc, (char*)wws + lr.wws_off, q, d);
         }
         return launch_conv_wgrad(s->dtype, lr.g, j.xin, j.dz, grads + lr.w_off, j.wdb, j.sc, acc, (char*)wws + lr.wws_off, q, d);
     };
@@ -421,6 +440,7 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                         if (need_dz) dz = gw + lr.dz_off;
                     }
                 }
+                if (by_layer && do_data) LPM_HIP(hipEventRecord(s->ev_layer[(size_t)(i - first) * LPM_MAX_WINDOW + layer_slot], st));
                 float* wdb = bias_in_wgrad ? dbias : nullptr;
                 // where the gradient w.r.t. this layer's input goes: the producer's dz (fused) or the tensor's gradient
                 void* gsrc = nullptr;
@@ -499,6 +519,8 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
         red.reserve(jobs.size());
         for (const WgradJob& j : jobs) {
             ReduceDesc d{};
+            if (by_layer)
+                LPM_HIP(hipStreamWaitEvent(wst, s->ev_layer[(size_t)(j.lr - &s->lay[0]) * LPM_MAX_WINDOW + layer_slot], 0));
             LPM_HIP(one_wgrad(j, wst, &d));
             if (d.splits > 0) red.push_back(d);
         }

@@ -25,8 +25,8 @@ struct LayerRt {
     size_t lowp_w_off = NO, lowp_wt_off = NO;    // byte offsets into lowp
     size_t dz_off = NO;                          // byte offset of its pre-activation gradient in the backward scratch
     size_t wws_off = 0;                          // this layer's weight-gradient partials inside the backward scratch
-    size_t fcs_x_off = NO, fcs_dz_off = NO;      // staging areas of a fully connected layer whose weight gradient a
-                                                 // schedule contracts once per mini-batch (byte offsets in the backward scratch)
+    size_t fcs_x_off = NO, fcs_dz_off = NO;      // staging areas of a layer whose weight gradient a schedule contracts
+                                                 // once per mini-batch (byte offsets in the backward scratch)
     bool fused_in = false;                       // its consumer's backward kernel writes dz directly (mask and scale fused)
 };
 
@@ -50,6 +50,9 @@ struct lpm_stage {
     // a side stream (borrowed from the library's pool), forked from and joined back into the caller's stream.
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    // per weight layer and micro-batch slot: "this layer's output gradient is final" in the data phase's stream
+    // order, for schedules that let the weight phase follow the data phase layer by layer
+    std::vector<hipEvent_t> ev_layer;      // [(layer - first) * LPM_MAX_WINDOW + slot]
     ~lpm_stage();
 
     lpm::TensorRt& T(int32_t t) { return ten[(size_t)(t - (first - 1))]; }
@@ -62,7 +65,7 @@ struct lpm_stage {
 int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const void* dy, void* dx,
                               const float* params, const void* lowp, const void* stash, float* grads,
                               int32_t accumulate, void* bwd_ws, void* stream, void* wstream, int32_t parity,
-                              int32_t phases, int32_t fc_slot = -1, int32_t fc_flush = 0);
+                              int32_t phases, int32_t fc_slot = -1, int32_t fc_flush = 0, int32_t layer_slot = -1);
 enum { LPM_PHASE_DATA = 1, LPM_PHASE_WEIGHTS = 2 };
 
 // U_z reading one weight version and writing another (see stage.cpp).

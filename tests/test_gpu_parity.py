@@ -33,6 +33,8 @@ CASES = [
     # a 512 x 64 fully connected layer at 2 samples per micro-batch: its weight gradient is contracted once per mini-batch
     ("tiny_fc_bf16", wl.tiny_fc, 8, 4, 2, 1),
     ("tiny_fc_bf16_one_stage", wl.tiny_fc, 6, 3, 1, 1),
+    # 64-channel convolutions over 4x4 and 2x2 images: the same for convolutions
+    ("tiny_wide_bf16", wl.tiny_wide, 8, 4, 2, 1),
 ]
 
 

@@ -196,6 +196,14 @@ def tiny_fc():
     return b.finish()
 
 
+def tiny_wide():
+    """64-channel 3x3 convolutions over 4x4 and 2x2 images: gradient matrices far larger than the activations."""
+    b = _Builder(3, 8, 8)
+    b.conv(64, 3, pad=1); b.pool(); b.conv(64, 3, pad=1); b.pool(); b.conv(64, 3, pad=1); b.gap()
+    b.fc(5, relu=False); b.loss()
+    return b.finish()
+
+
 def tiny_resnet(hw=8, widths=(4, 6), n_classes=5):
     """Stem + one identity block + one strided projection block + GAP + FC."""
     return resnet18_cifar(widths=widths, blocks=1, hw=hw, n_classes=n_classes)
