@@ -114,11 +114,11 @@ size_t wgrad_staged_ws_bytes(int dtype, const ConvGeom& g) {
 }
 
 hipError_t launch_wgrad_staged(int dtype, const ConvGeom& g, const void* xs, const void* dzs, int slots, float* dw, float* dbias,
-                               const float* bscale, void* ws, hipStream_t st, ReduceDesc* deferred) {
+                               const float* bscale, int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred) {
     if (deferred) deferred->splits = 0;
-    if (fc_staged_ok(g)) return fc_wgrad_staged(g, xs, dzs, slots, dw, dbias, bscale, 0, st);
+    if (fc_staged_ok(g)) return fc_wgrad_staged(g, xs, dzs, slots, dw, dbias, bscale, accumulate, st);
     // the staged micro-batches are one larger batch in the same layout
-    return launch_conv_wgrad(dtype, staged_geom(g, slots), xs, dzs, dw, dbias, bscale, 0, ws, st, deferred);
+    return launch_conv_wgrad(dtype, staged_geom(g, slots), xs, dzs, dw, dbias, bscale, accumulate, ws, st, deferred);
 }
 
 }  // namespace lpm

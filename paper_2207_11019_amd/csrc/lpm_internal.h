@@ -76,9 +76,9 @@ constexpr int LPM_FC_STAGE_SLOTS = 32;
 bool wgrad_staged_ok(int dtype, const ConvGeom& g);
 size_t wgrad_staged_ws_bytes(int dtype, const ConvGeom& g);      // split partials of the contraction, any slot count
 hipError_t stage_operands(const ConvGeom& g, const void* x, const void* dz, void* xs, void* dzs, int slot, hipStream_t st);
-// dw = (not +=) the gradient over the first `slots` staged micro-batches; `deferred` as for launch_conv_wgrad
+// dw (+)= the gradient over `slots` staged micro-batches starting at xs / dzs; `deferred` as for launch_conv_wgrad
 hipError_t launch_wgrad_staged(int dtype, const ConvGeom& g, const void* xs, const void* dzs, int slots, float* dw, float* dbias,
-                               const float* bscale, void* ws, hipStream_t st, ReduceDesc* deferred);
+                               const float* bscale, int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred);
 bool wgrad_fuses_bias(int dtype, const ConvGeom& g);
 bool dgrad_uses_wt(int dtype, const ConvGeom& g);
 size_t wgrad_ws_bytes(int dtype, const ConvGeom& g);

@@ -366,17 +366,24 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
     // that point before the layer's weight gradient instead of for the end of the data phase
     const bool by_layer = layer_slot >= 0 && deferred && (do_data != do_weights);
     struct WgradJob { const LayerRt* lr; const void* xin; const void* dz; float* wdb; const float* sc; };
-    // One weight gradient on stream q.  fc_slot >= 0: a layer with staging areas only files its
-    // operands under that micro-batch slot; fc_flush = M > 0 then contracts slots 0..M-1 (the whole mini-batch, so
-    // the result overwrites the accumulator).
+    // One weight gradient on stream q.  fc_slot = j >= 0 (of fc_flush = M micro-batches): a layer with staging areas
+    // files its operands under slot j and contracts a group of slots at a time; the first group overwrites the accumulator.
     auto one_wgrad = [&](const WgradJob& j, hipStream_t q, ReduceDesc* d) -> hipError_t {
         const LayerRt& lr = *j.lr;
         if (fc_slot >= 0 && lr.fcs_x_off != NO) {
             if (d) d->splits = 0;
             hipError_t e = stage_operands(lr.g, j.xin, j.dz, ws + lr.fcs_x_off, ws + lr.fcs_dz_off, fc_slot, q);
-            if (e != hipSuccess || fc_flush <= 0) return e;
-            return launch_wgrad_staged(s->dtype, lr.g, ws + lr.fcs_x_off, ws + lr.fcs_dz_off, fc_flush, grads + lr.w_off, j.wdb,
-                                       j.sc, (char*)wws + lr.wws_off, q, d);
+            if (e != hipSuccess) return e;
+            // Contract in groups of G micro-batches.  One group (G = M) touches dW once, but all of that work then sits
+            // behind the last micro-batch, where nothing overlaps it; two groups leave half of it there.  Gradient
+            // matrices of 64 MiB and more are bound by their own traffic and keep the single pass.
+            const int32_t M = fc_flush;
+            const int32_t G = ((size_t)lr.w_count * 4 >= ((size_t)64 << 20)) ? M : std::max(1, (M + 1) / 2);
+            if ((fc_slot + 1) % G != 0 && fc_slot != M - 1) return hipSuccess;
+            const int32_t j0 = (fc_slot / G) * G;
+            const size_t xb = (size_t)lr.g.rows_in() * lr.g.Cin * 2, db = (size_t)lr.g.rows_out() * lr.g.Cout * 2;
+            return launch_wgrad_staged(s->dtype, lr.g, ws + lr.fcs_x_off + (size_t)j0 * xb, ws + lr.fcs_dz_off + (size_t)j0 * db,
+                                       fc_slot - j0 + 1, grads + lr.w_off, j.wdb, j.sc, j0 > 0, (char*)wws + lr.wws_off, q, d);
         }
         return launch_conv_wgrad(s->dtype, lr.g, j.xin, j.dz, grads + lr.w_off, j.wdb, j.sc, acc, (char*)wws + lr.wws_off, q, d);
     };
