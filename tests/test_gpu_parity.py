@@ -191,6 +191,7 @@ def test_vgg16_cifar_config_bf16(lpm):
 FULL = [
     # name, builder, plan, micro-batch, mini-batch, upstream gradient wanted
     ("resnet18_cifar", wl.resnet18_cifar, [0, 5, 10, 15, 23], 32, 256, False),
+    ("resnet34_cifar", wl.resnet34_cifar, [0, 7, 16, 29, 39], 32, 256, False),
     ("r50_conv4x", wl.r50_conv4x, [0, 19], 16, 64, True),
     ("vgg16_224", wl.vgg16_224, [0, 10, 18, 19, 22], 4, 32, False),
 ]

@@ -140,15 +140,22 @@ def _basic_block(b, cout, stride):
 
 
 def resnet18_cifar(widths=(64, 128, 256, 512), blocks=2, hw=32, n_classes=10):
+    """blocks: basic blocks per stage, one number for all stages or one per stage."""
     b = _Builder(3, hw, hw)
     b.conv(widths[0], 3, pad=1, scale=True)
+    per_stage = [blocks] * len(widths) if isinstance(blocks, int) else list(blocks)
     for i, wd in enumerate(widths):
-        for j in range(blocks):
+        for j in range(per_stage[i]):
             _basic_block(b, wd, 2 if (i > 0 and j == 0) else 1)
     b.gap()
     b.fc(n_classes, relu=False)
     b.loss()
     return b.finish()
+
+
+def resnet34_cifar():
+    """The deeper basic-block network of the paper's second use case: 3, 4, 6, 3 blocks per stage."""
+    return resnet18_cifar(blocks=(3, 4, 6, 3))
 
 
 def _bottleneck(b, mid, cout, stride, project):
@@ -213,11 +220,12 @@ def tiny_vgg(hw=8, n_classes=10):
     return _vgg(3, hw, [8, 8, "M", 16, "M", 16, 16, "M"], [24], n_classes)
 
 
-# name -> (builder, batch, n_microbatch, Z, dtype, fixed plan or None)
+# name -> (builder, batch, n_microbatch, Z, dtype, fixed plan (list of stage starts) or None)
 CONFIGS = {
     "lenet":          (lenet, 32, 4, 2, "f32", None),
     "vgg16_cifar":    (vgg16_cifar, 128, 8, 4, "bf16", None),
-    "resnet18_cifar": (resnet18_cifar, 256, 8, 4, "bf16", "stage_boundaries"),
+    "resnet18_cifar": (resnet18_cifar, 256, 8, 4, "bf16", [0, 5, 10, 15, 23]),      # cuts at the stage boundaries
+    "resnet34_cifar": (resnet34_cifar, 256, 8, 4, "bf16", [0, 7, 16, 29, 39]),      # (not a BASELINE config: same shapes, more depth)
     "r50_conv4x":     (r50_conv4x, 64, 4, 1, "bf16", None),
     "vgg16_224":      (vgg16_224, 32, 8, 4, "bf16", None),
 }
