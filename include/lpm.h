@@ -232,6 +232,14 @@ int32_t lpm_schedule_create(lpm_stage* const* stages, int32_t Z, int32_t n_micro
                             lpm_schedule** out);
 int32_t lpm_schedule_destroy(lpm_schedule* s);
 
+/* What per_stage[z].grad_in holds after a run (F/B parallelisation section: the gradient a sub-module hands to
+ * its neighbour).  0: the gradient w.r.t. the input of stage z (eq. 9).  1: that gradient with the ReLU
+ * derivative of the previous stage's last layer already applied (zero where the stage input is <= 0), i.e. the
+ * pre-activation gradient of that layer: when stage z-1 ends in conv/FC + ReLU without scale or shortcut and
+ * stage z's input has a single consumer, the schedule lets stage z's backward kernel apply the mask instead of
+ * running a separate kernel in stage z-1.  Always 0 for z = 0 and for the float path.  Negative: LPM_EINVAL. */
+int32_t lpm_schedule_cut_fused(const lpm_schedule* s, int32_t z);
+
 /* One mini-batch step: all F_{z,j}, B_{z,j}, then U_z for every stage (one update per mini-batch with
  * the accumulated gradient).
  *   mode       LPM_LOCKED or LPM_OVERLAPPED, optionally | LPM_GRAPH; or LPM_PIPELINED (LPM_PIPELINED | LPM_GRAPH

@@ -73,6 +73,7 @@ lib.lpm_stage_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, 
 lib.lpm_stage_update.argtypes = [_vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _i32, _vp]
 lib.lpm_schedule_create.argtypes = [C.POINTER(_vp), _i32, _i32, _i32, C.POINTER(_vp)]
 lib.lpm_schedule_destroy.argtypes = [_vp]
+lib.lpm_schedule_cut_fused.argtypes = [_vp, _i32]
 lib.lpm_schedule_run.argtypes = [_vp, _i32, _vp, _vp, _vp, C.POINTER(lpm_stage_buffers), _i32, C.c_float, C.c_float,
                                  _vp, _vp, _vp]
 lib.lpm_conv_ws_bytes.argtypes = [C.POINTER(lpm_conv_geom), _i32, _psz, _psz, _psz]
@@ -84,7 +85,7 @@ lib.lpm_conv_time.argtypes = [_i32, C.POINTER(lpm_conv_geom), _i32, _vp, _vp, _v
 for _f in ("lpm_conv_time", "lpm_conv_ws_bytes", "lpm_conv_forward", "lpm_conv_dgrad", "lpm_conv_wgrad", "lpm_layer_cost", "lpm_partition", "lpm_partition_costs", "lpm_stage_create", "lpm_stage_destroy", "lpm_stage_sizes",
            "lpm_stage_param_offset", "lpm_stage_stash_offset", "lpm_stage_grad_offset", "lpm_stage_sync_lowp",
            "lpm_stage_forward", "lpm_stage_backward", "lpm_stage_update", "lpm_schedule_create",
-           "lpm_schedule_destroy", "lpm_schedule_run"):
+           "lpm_schedule_destroy", "lpm_schedule_cut_fused", "lpm_schedule_run"):
     getattr(lib, _f).restype = C.c_int32
 
 # public MI355X figures used as cost-model parameters: 2.5166 PFLOP/s bf16 MFMA, 157.3 TFLOP/s fp32, 8 TB/s HBM
@@ -275,6 +276,13 @@ class Schedule:
         h = C.c_void_p()
         _check(lib.lpm_schedule_create(arr, len(stages), n_microbatch, window, C.byref(h)))
         self.h = h
+
+    def cut_fused(self, z):
+        """True when grad_in of stage z holds the gradient with the previous stage's ReLU mask applied."""
+        r = lib.lpm_schedule_cut_fused(self.h, z)
+        if r < 0:
+            _check(r)
+        return bool(r)
 
     def close(self):
         if getattr(self, "h", None):

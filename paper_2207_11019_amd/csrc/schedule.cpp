@@ -84,6 +84,7 @@ struct lpm_schedule {
     std::vector<hipEvent_t> ev_w;   // [Z*M]  all of B_{z,j} done (weight phase included)
     hipEvent_t ev_fork = nullptr;
     std::vector<hipStream_t> sf, sb;     // PIPELINED: per-stage forward / backward streams (borrowed from the pool)
+    std::vector<char> cut_fused;         // [Z] the ReLU backward of stage z-1's last layer runs inside stage z's backward kernel
     std::vector<GraphEntry> graphs;
 
     // PIPELINED: one enqueue thread per stage, started at the first such run.  An event may only be waited
@@ -145,6 +146,8 @@ extern "C" int32_t lpm_schedule_create(lpm_stage* const* stages, int32_t Z, int3
     s->ev_w.assign((size_t)n_microbatch * Z, nullptr);
     s->sf.assign((size_t)Z, nullptr);
     s->sb.assign((size_t)Z, nullptr);
+    s->cut_fused.assign((size_t)Z, 0);
+    for (int32_t z = 1; z < Z; ++z) s->cut_fused[(size_t)z] = lpm_stage_takes_dz(stages[z - 1]) && lpm_stage_can_mask_dx(stages[z]);
     s->rec_f.reset(new std::atomic<uint64_t>[(size_t)n_microbatch * Z]);
     s->rec_b.reset(new std::atomic<uint64_t>[(size_t)n_microbatch * Z]);
     s->rec_w.reset(new std::atomic<uint64_t>[(size_t)n_microbatch * Z]);
@@ -165,6 +168,11 @@ extern "C" int32_t lpm_schedule_create(lpm_stage* const* stages, int32_t Z, int3
     }
     *out = s;
     return LPM_OK;
+}
+
+extern "C" int32_t lpm_schedule_cut_fused(const lpm_schedule* s, int32_t z) {
+    if (!s || z < 0 || z >= s->Z) return fail(LPM_EINVAL, "bad schedule or stage index");
+    return s->cut_fused[(size_t)z] ? 1 : 0;
 }
 
 extern "C" int32_t lpm_schedule_destroy(lpm_schedule* s) {
@@ -227,7 +235,8 @@ int32_t bwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStrea
     const bool staged = ver < 0 && s->M <= LPM_FC_STAGE_SLOTS;
     return lpm_stage_backward_on(sg, in, b.act_out[slot], dy, dx, ver_params(b, ver), ver_lowp(b, ver), b.stash[slot], b.grads,
                                  ver < 0 ? j > 0 : 0, b.bwd_ws, st, wst, j & 1, phases, staged ? j : -1,
-                                 staged ? s->M : 0, by_layer ? j % LPM_MAX_WINDOW : -1);
+                                 staged ? s->M : 0, by_layer ? j % LPM_MAX_WINDOW : -1,
+                                 (s->cut_fused[(size_t)z] ? LPM_MASK_DX : 0) | (z + 1 < s->Z && s->cut_fused[(size_t)z + 1] ? LPM_DY_IS_DZ : 0));
 }
 
 // ver < 0: the one update of the synchronous step; else U_{z,ver}: version ver -> version ver + 1

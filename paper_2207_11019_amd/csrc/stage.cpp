@@ -334,7 +334,9 @@ extern "C" int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y
 int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const void* dy, void* dx,
                               const float* params, const void* lowp, const void* stash, float* grads,
                               int32_t accumulate, void* bwd_ws, void* stream, void* wstream, int32_t parity,
-                              int32_t phases, int32_t fc_slot, int32_t fc_flush, int32_t layer_slot) {
+                              int32_t phases, int32_t fc_slot, int32_t fc_flush, int32_t layer_slot, int32_t boundary) {
+    if ((boundary & LPM_MASK_DX) && !lpm_stage_can_mask_dx(s)) return fail(LPM_EINVAL, "internal: this stage cannot mask its input gradient");
+    if ((boundary & LPM_DY_IS_DZ) && !lpm_stage_takes_dz(s)) return fail(LPM_EINVAL, "internal: this stage needs the gradient of its output");
     if (layer_slot >= LPM_MAX_WINDOW) return fail(LPM_EINVAL, "internal: layer event slot out of range");
     if (fc_slot >= LPM_FC_STAGE_SLOTS || fc_flush > LPM_FC_STAGE_SLOTS) return fail(LPM_EINVAL, "internal: staging slot out of range");
     if (!s || !x || !y || !params || !stash || !grads || !bwd_ws) return fail(LPM_EINVAL, "NULL argument");
@@ -431,6 +433,8 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                 const void* dz = g;
                 if (lr.fused_in) {
                     dz = gw + lr.dz_off;           // written by the consumer's backward kernel
+                } else if (i == s->t_out && (boundary & LPM_DY_IS_DZ)) {
+                    dz = g;                        // the next stage applied this layer's ReLU mask to what it handed down
                 } else {
                     void* gadd = nullptr;
                     int gadd_acc = 0;
@@ -464,6 +468,7 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                     } else {
                         gsrc = G[gi(l.src)];
                         gsrc_acc = have[gi(l.src)];
+                        if (l.src == first - 1 && (boundary & LPM_MASK_DX)) gmask = x;      // ReLU backward of the previous stage's last layer
                     }
                     have[gi(l.src)] = 1;
                 }
@@ -501,6 +506,8 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                         gsrc_acc = 0;
                         gmask = (pr.d.flags & LPM_RELU) ? tptr(s, l.src, x, y, stash) : nullptr;
                         gmscale = pr.s_off != NO ? params + pr.s_off : nullptr;
+                    } else if (l.src == first - 1 && (boundary & LPM_MASK_DX)) {
+                        gmask = x;
                     }
                     if (do_data && l.kind == LPM_MAXPOOL2)
                         LPM_HIP(launch_maxpool_bwd(s->dtype, s->m, l.h_in, l.w_in, l.cin, tptr(s, l.src, x, y, stash),
@@ -538,6 +545,29 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
         }
     }
     return LPM_OK;
+}
+
+bool lpm_stage_can_mask_dx(const lpm_stage* s) {
+    if (!s || s->dtype != LPM_BF16 || s->first == 0) return false;
+    int n = 0;
+    for (int32_t i = s->first; i < s->last; ++i) {
+        const lpm_layer& l = s->net[(size_t)i];
+        if (l.add_src == s->first - 1) return false;
+        if (l.src != s->first - 1) continue;
+        if (l.kind != LPM_CONV && l.kind != LPM_FC && l.kind != LPM_MAXPOOL2 && l.kind != LPM_GAP) return false;
+        ++n;
+    }
+    return n == 1;
+}
+
+bool lpm_stage_takes_dz(const lpm_stage* s) {
+    if (!s || s->dtype != LPM_BF16 || s->loss) return false;
+    const int32_t i = s->t_out;
+    if (i != s->last - 1) return false;
+    const LayerRt& lr = s->Ly(i);
+    const lpm_layer& l = lr.d;
+    if (!has_weights(l) || !(l.flags & LPM_RELU) || (l.flags & LPM_SCALE) || l.add_src != LPM_NONE) return false;
+    return !(l.flags & LPM_BIAS) || wgrad_fuses_bias(s->dtype, lr.g);
 }
 
 extern "C" int32_t lpm_stage_update(lpm_stage* s, float* params, void* lowp, float* grads, float* momentum,

@@ -65,7 +65,15 @@ struct lpm_stage {
 int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const void* dy, void* dx,
                               const float* params, const void* lowp, const void* stash, float* grads,
                               int32_t accumulate, void* bwd_ws, void* stream, void* wstream, int32_t parity,
-                              int32_t phases, int32_t fc_slot = -1, int32_t fc_flush = 0, int32_t layer_slot = -1);
+                              int32_t phases, int32_t fc_slot = -1, int32_t fc_flush = 0, int32_t layer_slot = -1,
+                              int32_t boundary = 0);
+// boundary: a schedule may move the ReLU backward of a stage's last layer into the next stage, whose kernel that
+// writes the gradient w.r.t. its input then masks it with that input (the producer's output) -- one kernel less
+// per cut and micro-batch.  LPM_MASK_DX: this stage masks its dx; LPM_DY_IS_DZ: the gradient this stage receives
+// already is the pre-activation gradient of its last layer.  Both sides must agree (see the two predicates).
+enum { LPM_MASK_DX = 1, LPM_DY_IS_DZ = 2 };
+bool lpm_stage_can_mask_dx(const lpm_stage* s);        // its input tensor has exactly one consumer, a layer whose backward kernel can mask
+bool lpm_stage_takes_dz(const lpm_stage* s);           // its last layer is conv/FC + ReLU (no scale, no shortcut), bias gradient from the weight-gradient kernel
 enum { LPM_PHASE_DATA = 1, LPM_PHASE_WEIGHTS = 2 };
 
 // U_z reading one weight version and writing another (see stage.cpp).

@@ -103,10 +103,10 @@ __device__ __forceinline__ u32x2_ tr_words(const unsigned char* p) {
     return __builtin_bit_cast(u32x2_, __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4_*)(p)));
 }
 
-// NST: stages of the LDS ring.  A load takes of the order of a microsecond to land and a patch a fifth of that to
-// multiply, so the loads run NST - 1 patches ahead: few stages when two blocks share a CU, many when a block has it alone.
+// NST: stages of the LDS ring; the loads run NST - 1 patches ahead.  Four stages leave room for two blocks per CU;
+// a ring of eight for a block alone on its CU measured no faster.
 template <int TAPS, int NST>
-__global__ void __launch_bounds__(256, NST <= 4 ? 2 : 1) wgrad_tr_kernel(WgradTrArgs p) {
+__global__ void __launch_bounds__(256, 2) wgrad_tr_kernel(WgradTrArgs p) {
     typedef TrCfg<TAPS> C;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];      // NST stages of C::STAGE bytes + 256 (a filter row's third fetch reaches 2 pixels past its halo tile)
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -351,8 +351,6 @@ hipError_t wgrad_tr(const ConvGeom& g, const void* x, const void* dz, float* dw,
     a.accumulate = accumulate;
     a.co_tiles = pl.co_tiles; a.ci_tiles = pl.ci_tiles; a.tap_groups = pl.groups;
     const dim3 grid((unsigned)(pl.co_tiles * pl.ci_tiles * pl.groups), 1, pl.splits);
-    // a block that has its CU to itself (no more blocks than CUs) takes the deep ring
-    const bool deep = (int64_t)grid.x * grid.z <= 256;
     hipError_t e = hipSuccess;
 #define LPM_TR_LAUNCH(TAPS, NST)                                                                              \
     {                                                                                                         \
@@ -363,10 +361,10 @@ hipError_t wgrad_tr(const ConvGeom& g, const void* x, const void* dz, float* dw,
         hipLaunchKernelGGL((wgrad_tr_kernel<TAPS, NST>), grid, dim3(256), bytes, st, a);                      \
     }
 #ifdef LPM_TUNE      // all nine taps per block: measured slower than a filter row per block on every shape tried
-    if (pl.taps == 9) { if (deep) LPM_TR_LAUNCH(9, 7) else LPM_TR_LAUNCH(9, 3) } else
+    if (pl.taps == 9) LPM_TR_LAUNCH(9, 3) else
 #endif
-    if (pl.taps == 3) { if (deep) LPM_TR_LAUNCH(3, 8) else LPM_TR_LAUNCH(3, 4) }
-    else { if (deep) LPM_TR_LAUNCH(1, 8) else LPM_TR_LAUNCH(1, 4) }
+    if (pl.taps == 3) LPM_TR_LAUNCH(3, 4)
+    else LPM_TR_LAUNCH(1, 4)
 #undef LPM_TR_LAUNCH
     e = hipGetLastError();
     if (e != hipSuccess || pl.splits == 1) return e;

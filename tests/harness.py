@@ -106,7 +106,11 @@ def compare(net, layers, starts, M, dtype, o, dx_wanted=False, window=2, report=
                 got = net.read_act_out(z, slot)
             errs["act%d" % t] = rel_err(got, stash[t])
         if backward and (z > 0 or dx_wanted):
-            errs["gin%d" % z] = rel_err(net.read_grad_in(z, slot), ref["gin"][(z, j)])
+            want = ref["gin"][(z, j)]
+            if z > 0 and net.schedule.cut_fused(z):
+                # the cut hands down the previous stage's pre-activation gradient: ReLU derivative of the stage input applied
+                want = want * (ref["stash"][(z - 1, j)][starts[z] - 1] > 0)
+            errs["gin%d" % z] = rel_err(net.read_grad_in(z, slot), want)
     bad = {k: e for k, e in errs.items() if not (e <= tol)}
     if report is not None:
         report.update(errs)

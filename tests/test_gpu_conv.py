@@ -55,10 +55,10 @@ SHAPES = [
     G(2, 15, 15, 512, 512, 3, 1, 1),      # 512 channels, images just below two patches
     G(3, 24, 15, 64, 128, 3, 1, 1),       # ragged in x only
     # large images: the weight gradient by 8x8 pixel patches (LDS transpose reads)
-    G(1, 56, 56, 64, 64, 3, 1, 1),        # one tap per block, a block alone on its CU (deep LDS ring)
-    G(2, 64, 64, 64, 128, 3, 1, 1),       # one tap per block, more blocks than CUs (short ring)
+    G(1, 56, 56, 64, 64, 3, 1, 1),        # one tap per block, few patches per block
+    G(2, 64, 64, 64, 128, 3, 1, 1),       # one tap per block, more blocks than CUs
     G(1, 57, 59, 128, 128, 3, 1, 1),      # a filter row per block, patches over the edge in both directions
-    G(4, 64, 64, 128, 128, 3, 1, 0),      # a filter row per block, no padding, short ring
+    G(4, 64, 64, 128, 128, 3, 1, 0),      # a filter row per block, no padding
     G(1, 60, 60, 72, 136, 3, 1, 1),       # channel counts that are not multiples of the 64-channel tile
 ]
 
