@@ -23,7 +23,7 @@ size_t mfma_wgrad_ws_bytes(const ConvGeom& g);
 hipError_t mfma_conv_fwd(const ConvGeom& g, const void* x, const void* w, const float* scale, const float* bias,
                          const void* add, int relu, void* y, void* ws, hipStream_t st);
 hipError_t mfma_conv_dgrad(const ConvGeom& g, const void* dz, const void* wt, void* dx, int accumulate, const void* mask,
-                           const float* mscale, void* ws, hipStream_t st);
+                           const float* mscale, void* ws, hipStream_t st, const UnpoolDesc* unpool);
 hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* bscale,
                            int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred);
 
@@ -77,10 +77,20 @@ bool wgrad_fuses_bias(int dtype, const ConvGeom& g) { return dtype == LPM_BF16 &
 // whether the data gradient wants the [Cin][Kh][Kw][Cout] copy of the weights
 bool dgrad_uses_wt(int dtype, const ConvGeom& g) { return dtype == LPM_BF16 && !fc_skinny_ok(g) && mfma_dgrad_ok(g); }
 
+// the stride-1 MFMA data gradient can route its result through a following (in forward order: preceding) max-pooling
+// (worth it while the kernel is bound by its launch: measured on the 224x224 VGG layers the scattered 2-byte stores
+// in the contraction's epilogue cost more than the separate pooling kernel, so large gradients keep that kernel)
+bool dgrad_can_unpool(int dtype, const ConvGeom& g) {
+    return dtype == LPM_BF16 && !fc_skinny_ok(g) && mfma_dgrad_ok(g) && g.stride == 1 &&
+           (int64_t)g.rows_in() * g.Cin <= ((int64_t)1 << 20);
+}
+
 hipError_t launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dz, const void* w, const void* wt, void* dx,
-                             int accumulate, const void* mask, const float* mscale, void* ws, hipStream_t st) {
+                             int accumulate, const void* mask, const float* mscale, void* ws, hipStream_t st,
+                             const UnpoolDesc* unpool) {
+    if (unpool && !(dgrad_can_unpool(dtype, g) && wt)) return hipErrorInvalidValue;      // callers ask dgrad_can_unpool first
     if (dtype == LPM_BF16 && fc_skinny_ok(g)) return fc_dgrad(g, dz, w, dx, accumulate, mask, mscale, ws, st);
-    if (dtype == LPM_BF16 && wt && mfma_dgrad_ok(g)) return mfma_conv_dgrad(g, dz, wt, dx, accumulate, mask, mscale, ws, st);
+    if (dtype == LPM_BF16 && wt && mfma_dgrad_ok(g)) return mfma_conv_dgrad(g, dz, wt, dx, accumulate, mask, mscale, ws, st, unpool);
     return conv_dgrad_generic_launch(dtype, g, dz, w, dx, accumulate, mask, mscale, st);
 }
 

@@ -68,7 +68,36 @@ struct IgemmArgs {
     int cls_tile0[17];
     int m_tiles;                 // host only: row tiles to launch (0: ceil(M / 64)); K the plan is made for (0: Ktot)
     int plan_K;
+    // stride-1 data gradient routed through a 2x2 max-pooling (see UnpoolDesc): the rows are pooled pixels
+    const uint16_t* pool_x;      // pooling input [m][2*Hr][2*Wr][N], NULL: plain output
+    uint16_t* pool_dst;
+    int pool_acc, pool_mask;     // (the per-channel factor is mscale)
 };
+
+// One element v of the gradient of a 2x2 max-pooling output at pooled pixel `row`, channel `col`: goes to the first
+// maximum of the window (row-major), times the ReLU derivative at the maximum and a per-channel factor when asked.
+__device__ __forceinline__ void unpool_store(float v, int row, int col, int Hr, int Wr, int N, const uint16_t* __restrict__ pool_x,
+                                             uint16_t* __restrict__ dst, int acc, int mask, const float* __restrict__ mscale) {
+    const int wq = row % Wr, t = row / Wr, hq = t % Hr, n = t / Hr;
+    const size_t base = ((size_t)(n * 2 * Hr + 2 * hq) * (2 * Wr) + 2 * wq) * N + col;
+    const size_t off[4] = {0, (size_t)N, (size_t)2 * Wr * N, (size_t)2 * Wr * N + N};
+    float a[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) a[k] = bf2f(pool_x[base + off[k]]);
+    const float mx = fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3]));
+    float g = bf2f(f2bf(v));             // the value a stored bf16 gradient of the pooling output would have had
+    if (mask && !(mx > 0.f)) g = 0.f;
+    if (mscale) g *= mscale[col];
+    bool found = false;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const bool hit = !found && (a[k] == mx);
+        found = found || hit;
+        float o = hit ? g : 0.f;
+        if (acc) o += bf2f(dst[base + off[k]]);
+        dst[base + off[k]] = f2bf(o);
+    }
+}
 
 template <int BM, int BN, int WGM, int WGN>
 struct TileCfg {
@@ -286,6 +315,10 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
                 }
                 float v = acc[mi][ni][i];
                 if (p.part) { p.part[(size_t)blockIdx.z * p.M * p.N + o] = v; continue; }
+                if (MODE == MODE_DGRAD && p.pool_x) {
+                    unpool_store(v, row, col, p.Hr, p.Wr, p.N, p.pool_x, p.pool_dst, p.pool_acc, p.pool_mask, p.mscale);
+                    continue;
+                }
                 v = v * sc + bi;
                 if (p.add) v += bf2f(p.add[o]);
                 if (p.accumulate) v += bf2f(p.C[o]);
@@ -316,6 +349,18 @@ __global__ void __launch_bounds__(256) splitk_epilogue(const float* __restrict__
     if (mask && !(bf2f(mask[i]) > 0.f)) v = 0.f;
     if (mscale) v *= mscale[col];
     C[i] = f2bf(v);
+}
+
+// the same sum routed through a 2x2 max-pooling (see unpool_store)
+__global__ void __launch_bounds__(256) splitk_epilogue_unpool(const float* __restrict__ part, int splits, int64_t MN, int N,
+                                                              int Hr, int Wr, const uint16_t* __restrict__ pool_x,
+                                                              uint16_t* __restrict__ dst, int acc, int mask,
+                                                              const float* __restrict__ mscale) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= MN) return;
+    float v = part[i];
+    for (int s = 1; s < splits; ++s) v += part[(int64_t)s * MN + i];
+    unpool_store(v, (int)(i / N), (int)(i % N), Hr, Wr, N, pool_x, dst, acc, mask, mscale);
 }
 
 hipError_t launch_splitk_epilogue(const float* part, int splits, int64_t MN, int N, const float* scale, const float* bias,
@@ -399,8 +444,12 @@ static hipError_t run_igemm(int mode, IgemmArgs a, void* ws, hipStream_t st) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.splits == 1) return e;
     const int64_t MN = (int64_t)a.M * a.N;
-    hipLaunchKernelGGL(splitk_epilogue, dim3((unsigned)((MN + 255) / 256)), dim3(256), 0, st, (const float*)ws, pl.splits,
-                       MN, a.N, a.scale, a.bias, a.add, a.relu, a.accumulate, a.mask, a.mscale, a.C);
+    if (a.pool_x)
+        hipLaunchKernelGGL(splitk_epilogue_unpool, dim3((unsigned)((MN + 255) / 256)), dim3(256), 0, st, (const float*)ws,
+                           pl.splits, MN, a.N, a.Hr, a.Wr, a.pool_x, a.pool_dst, a.pool_acc, a.pool_mask, a.mscale);
+    else
+        hipLaunchKernelGGL(splitk_epilogue, dim3((unsigned)((MN + 255) / 256)), dim3(256), 0, st, (const float*)ws, pl.splits,
+                           MN, a.N, a.scale, a.bias, a.add, a.relu, a.accumulate, a.mask, a.mscale, a.C);
     return hipGetLastError();
 }
 
@@ -440,10 +489,15 @@ hipError_t mfma_conv_fwd(const ConvGeom& g, const void* x, const void* w, const 
 
 // wt: weights laid out [Cin][Kh][Kw][Cout]
 hipError_t mfma_conv_dgrad(const ConvGeom& g, const void* dz, const void* wt, void* dx, int accumulate, const void* mask,
-                           const float* mscale, void* ws, hipStream_t st) {
+                           const float* mscale, void* ws, hipStream_t st, const UnpoolDesc* unpool) {
     IgemmArgs a{};
     a.A = (const uint16_t*)dz; a.B = (const uint16_t*)wt; a.C = (uint16_t*)dx;
     a.accumulate = accumulate; a.mask = (const uint16_t*)mask; a.mscale = mscale;
+    if (unpool) {
+        a.C = nullptr; a.accumulate = 0; a.mask = nullptr;
+        a.pool_x = (const uint16_t*)unpool->pool_x; a.pool_dst = (uint16_t*)unpool->dst;
+        a.pool_acc = unpool->accumulate; a.pool_mask = unpool->mask; a.mscale = unpool->mscale;
+    }
     a.M = (int)g.rows_in(); a.N = g.Cin; a.Ktot = g.Kh * g.Kw * g.Cout;
     a.Hi = g.Ho; a.Wi = g.Wo; a.Ci = g.Cout; a.Hr = g.H; a.Wr = g.W; a.Kw = g.Kw; a.stride = g.stride; a.pad = g.pad;
     a.a_bytes = (unsigned)(g.rows_out() * g.Cout * 2); a.b_bytes = (unsigned)((int64_t)g.Cout * g.K() * 2);

@@ -51,8 +51,15 @@ hipError_t launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const vo
                            const float* bias, const void* add, int relu, void* y, void* ws, hipStream_t st);
 // dx (+)= conv_transpose(dz, w);  then, when given, dx = dx * [mask > 0] * mscale_c -- the epilogue backward of
 // the layer that produced the tensor dx belongs to (mask = that tensor, mscale = that layer's scale)
+// unpool (may be NULL; only when dgrad_can_unpool): dx is the gradient of a 2x2 max-pooling output that nothing else
+// reads -- it is not stored; the kernel routes each element straight to the first maximum of its pooling window
+// (found in pool_x, the pooling input [m][2H][2W][Cin]) and writes the four window positions of dst (same shape):
+// dst (+)= route(dx) * [max > 0 if mask] * mscale_c.  dx, accumulate, mask, mscale of the plain form are then unused.
+struct UnpoolDesc { const void* pool_x; void* dst; int accumulate; int mask; const float* mscale; };
 hipError_t launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dz, const void* w, const void* wt,
-                             void* dx, int accumulate, const void* mask, const float* mscale, void* ws, hipStream_t st);
+                             void* dx, int accumulate, const void* mask, const float* mscale, void* ws, hipStream_t st,
+                             const UnpoolDesc* unpool = nullptr);
+bool dgrad_can_unpool(int dtype, const ConvGeom& g);
 // dw (+)= sum over pixels of dz (x) x         ws: split-reduction partials (wgrad_ws_bytes)
 // dbias (may be NULL, only when wgrad_fuses_bias): dbias (+)= (sum over pixels of dz) / bscale_c
 // deferred (may be NULL): when the kernel leaves split partials, describe their reduction there instead of launching

@@ -123,6 +123,22 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
         if ((l.flags & LPM_BIAS) && !wgrad_fuses_bias(dtype, lr.g)) continue;
         lr.fused_in = true;
     }
+    // Pooling-backward fusion: a 2x2 max-pooling (even input extent) whose output feeds exactly one layer, a
+    // convolution whose data gradient runs on the stride-1 MFMA kernel: that kernel routes its result to the
+    // window maxima itself and the gradient of the pooling output is never stored.
+    for (int32_t i = first; i < last; ++i) {
+        LayerRt& lr = s->Ly(i);
+        const lpm_layer& l = lr.d;
+        if (!has_weights(l) || l.src < first || s->net[(size_t)l.src].kind != LPM_MAXPOOL2) continue;
+        const int32_t p = l.src;
+        const lpm_layer& pl = s->net[(size_t)p];
+        if (p == s->t_out || (pl.h_in & 1) || (pl.w_in & 1) || !dgrad_can_unpool(dtype, lr.g) || !dgrad_uses_wt(dtype, lr.g)) continue;
+        int n_cons = 0;
+        for (int32_t j = p + 1; j < last; ++j) n_cons += (s->net[(size_t)j].src == p) + (s->net[(size_t)j].add_src == p);
+        if (n_cons != 1) continue;
+        lr.unpool_of = p;
+        s->Ly(p).unpooled = true;
+    }
     s->n_trainable = off;
     if (dtype == LPM_BF16) {                   // transposed copies follow the mirrored region
         const size_t base = align_up(off * 2, 256);
@@ -459,7 +475,29 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                 const void* gmask = nullptr;
                 const float* gmscale = nullptr;
                 const bool want = (l.src >= first) || (dx != nullptr);
-                if (want) {
+                UnpoolDesc unpool{};
+                if (lr.unpool_of >= 0) {
+                    // this layer's input is a max-pooling output nobody else reads: route the data gradient through the
+                    // pooling to where the pooling backward would have written (the same choices as in the pooling case below)
+                    const int32_t p = lr.unpool_of, q = s->Ly(p).d.src;
+                    have[gi(p)] = 1;
+                    if (q >= first || dx != nullptr) {
+                        unpool.pool_x = tptr(s, q, x, y, stash);
+                        unpool.dst = G[gi(q)];
+                        unpool.accumulate = have[gi(q)];
+                        if (q >= first && s->Ly(q).fused_in) {
+                            const LayerRt& pr = s->Ly(q);
+                            unpool.dst = gw + pr.dz_off;
+                            unpool.accumulate = 0;
+                            unpool.mask = (pr.d.flags & LPM_RELU) != 0;
+                            unpool.mscale = pr.s_off != NO ? params + pr.s_off : nullptr;
+                        } else if (q == first - 1 && (boundary & LPM_MASK_DX)) {
+                            unpool.mask = 1;
+                        }
+                        have[gi(q)] = 1;
+                    }
+                }
+                if (want && lr.unpool_of < 0) {
                     if (l.src >= first && s->Ly(l.src).fused_in) {
                         const LayerRt& pr = s->Ly(l.src);
                         gsrc = gw + pr.dz_off;
@@ -489,12 +527,17 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                                                          : (const void*)(params + lr.w_off);
                     const void* wt = (s->dtype == LPM_BF16 && lr.lowp_wt_off != NO)
                                          ? (const void*)((const char*)lowp + lr.lowp_wt_off) : nullptr;
-                    if (do_data) LPM_HIP(launch_conv_dgrad(s->dtype, lr.g, dz, w, wt, gsrc, gsrc_acc, gmask, gmscale, kws, st));
+                    if (lr.unpool_of >= 0) {
+                        if (do_data && unpool.dst) LPM_HIP(launch_conv_dgrad(s->dtype, lr.g, dz, w, wt, nullptr, 0, nullptr, nullptr, kws, st, &unpool));
+                    } else if (do_data) {
+                        LPM_HIP(launch_conv_dgrad(s->dtype, lr.g, dz, w, wt, gsrc, gsrc_acc, gmask, gmscale, kws, st));
+                    }
                 }
                 break;
             }
             case LPM_MAXPOOL2:
             case LPM_GAP:
+                if (lr.unpooled) break;          // done by the consumer's data gradient
                 if (want_src) {
                     void* gsrc = G[gi(l.src)];
                     int gsrc_acc = have[gi(l.src)];
