@@ -386,7 +386,13 @@ static IgemmPlan plan_igemm(int64_t M, int N, int Ktot, int ci) {
     pl.kt_total = Ktot / pl.bk;
     const int64_t tiles = ((M + 63) / 64) * ((N + 63) / 64);
     const int kt64 = Ktot / 64;                                   // K depth in units of 64
-    int s = std::max(1, (kt64 + 7) / 14);                         // about 14 K tiles per block
+    // about 8 K tiles per block: timed alone a contraction is fastest at about 14, but inside a step, where two or
+    // three kernels share the GPU and a K tile takes longer, shorter loops win (VGG-16/CIFAR: -5 % locked, -2 % overlapped)
+    int kpb = 8;
+#ifdef LPM_TUNE
+    if (const char* e = getenv("LPM_T_KPB")) kpb = std::max(1, atoi(e));
+#endif
+    int s = std::max(1, (kt64 + kpb / 2) / kpb);
     // no more blocks than fill the chip once -- except for a single row of tiles (a small-batch FC layer), which
     // only streams weights and needs many blocks in flight to cover the memory latency
     const int64_t cap = (M <= 64 ? 1024 : 320) / tiles;
