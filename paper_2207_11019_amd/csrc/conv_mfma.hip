@@ -12,6 +12,7 @@
 // (lane % 32); lane holds D[(i/4)*8 + (lane/32)*4 + i%4][lane % 32] in accumulator element i.
 #include "lpm_internal.h"
 #include "elem.h"
+#include "lds_dma.h"
 #include <algorithm>
 #ifdef LPM_TUNE
 #include <cstdlib>
@@ -130,6 +131,77 @@ __device__ __forceinline__ void mma_tile(const uint16_t* As, const uint16_t* Bs,
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
                 acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+    }
+}
+
+// Writes a block's accumulators: split-K partials, the max-pooling route of a data gradient, or the fused epilogue.
+// The optional terms of the epilogue (shortcut, accumulation, mask) are the same for the whole launch; each of the
+// eight combinations gets its own straight-line copy of the store loop instead of three branches per element.
+template <int MI, int NI, int WTM, int WTN, int MODE, bool ADD, bool ACC, bool MASK>
+__device__ __forceinline__ void igemm_store(const IgemmArgs& p, const f32x16 (&acc)[MI][NI], int ni, int col, int m0, int wm, int rq,
+                                            int rows, int Hc, int Wc, int ph, int pw) {
+    const float sc = p.scale ? p.scale[col] : 1.f, bi = p.bias ? p.bias[col] : 0.f, ms = p.mscale ? p.mscale[col] : 1.f;
+    const bool relu = p.relu != 0;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int row = m0 + wm * WTM + mi * 32 + (i >> 2) * 8 + rq + (i & 3);
+            if (row >= rows) continue;
+            size_t o = (size_t)(unsigned)(row * p.N + col);            // (the host checked that the output has fewer than 2^31 elements)
+            if (MODE == MODE_DGRAD_S) {      // class row -> pixel of the full image
+                const int wq = row % Wc, t = row / Wc, hq = t % Hc, n = t / Hc;
+                o = (size_t)(unsigned)(((n * p.Hr + hq * p.stride + ph) * p.Wr + wq * p.stride + pw) * p.N + col);
+            }
+            float v = acc[mi][ni][i] * sc + bi;
+            if (ADD) v += bf2f(p.add[o]);
+            if (ACC) v += bf2f(p.C[o]);
+            const float r = fmaxf(v, 0.f);
+            v = relu ? r : v;
+            if (MASK) v = bf2f(p.mask[o]) > 0.f ? v : 0.f;
+            p.C[o] = f2bf(v * ms);
+        }
+}
+
+template <int MI, int NI, int WTM, int WTN, int MODE>
+__device__ __forceinline__ void igemm_epilogue(const IgemmArgs& p, f32x16 (&acc)[MI][NI], int m0, int n0, int wm, int wn, int lane,
+                                               int rows, int Hc, int Wc, int ph, int pw) {
+    const int col_l = lane & 31, rq = (lane >> 5) * 4;
+    const int variant = (p.add ? 1 : 0) | (p.accumulate ? 2 : 0) | (p.mask ? 4 : 0);
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+        const int col = n0 + wn * WTN + ni * 32 + col_l;
+        if (col >= p.N) continue;
+        if (p.part || (MODE == MODE_DGRAD && p.pool_x)) {
+            float* part = p.part ? p.part + (size_t)blockIdx.z * p.M * p.N : nullptr;
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int row = m0 + wm * WTM + mi * 32 + (i >> 2) * 8 + rq + (i & 3);
+                    if (row >= rows) continue;
+                    size_t o = (size_t)(unsigned)(row * p.N + col);
+                    if (MODE == MODE_DGRAD_S) {
+                        const int wq = row % Wc, t = row / Wc, hq = t % Hc, n = t / Hc;
+                        o = (size_t)(unsigned)(((n * p.Hr + hq * p.stride + ph) * p.Wr + wq * p.stride + pw) * p.N + col);
+                    }
+                    if (part) part[o] = acc[mi][ni][i];
+                    else unpool_store(acc[mi][ni][i], row, col, p.Hr, p.Wr, p.N, p.pool_x, p.pool_dst, p.pool_acc, p.pool_mask, p.mscale);
+                }
+            continue;
+        }
+#define LPM_STORE(A, B, C) igemm_store<MI, NI, WTM, WTN, MODE, A, B, C>(p, acc, ni, col, m0, wm, rq, rows, Hc, Wc, ph, pw)
+        switch (variant) {
+            case 0: LPM_STORE(false, false, false); break;
+            case 1: LPM_STORE(true, false, false); break;
+            case 2: LPM_STORE(false, true, false); break;
+            case 3: LPM_STORE(true, true, false); break;
+            case 4: LPM_STORE(false, false, true); break;
+            case 5: LPM_STORE(true, false, true); break;
+            case 6: LPM_STORE(false, true, true); break;
+            default: LPM_STORE(true, true, true); break;
+        }
+#undef LPM_STORE
     }
 }
 
@@ -294,41 +366,119 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
 #undef LPM_LOAD_TILE
 #undef LPM_STORE_TILE
 
-    // epilogue
-    const int col_l = lane & 31, rq = (lane >> 5) * 4;
-#pragma unroll
-    for (int ni = 0; ni < Cfg::NI; ++ni) {
-        const int col = n0 + wn * Cfg::WTN + ni * 32 + col_l;
-        if (col >= p.N) continue;
-        const float sc = (p.scale && !p.part) ? p.scale[col] : 1.f;
-        const float bi = (p.bias && !p.part) ? p.bias[col] : 0.f;
-#pragma unroll
-        for (int mi = 0; mi < Cfg::MI; ++mi)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int row = m0 + wm * Cfg::WTM + mi * 32 + (i >> 2) * 8 + rq + (i & 3);
-                if (row >= rows) continue;
-                size_t o = (size_t)row * p.N + col;
-                if (MODE == MODE_DGRAD_S) {      // class row -> pixel of the full image
-                    const int wq = row % Wc, t = row / Wc, hq = t % Hc, n = t / Hc;
-                    o = ((size_t)(n * p.Hr + hq * p.stride + ph) * p.Wr + wq * p.stride + pw) * p.N + col;
-                }
-                float v = acc[mi][ni][i];
-                if (p.part) { p.part[(size_t)blockIdx.z * p.M * p.N + o] = v; continue; }
-                if (MODE == MODE_DGRAD && p.pool_x) {
-                    unpool_store(v, row, col, p.Hr, p.Wr, p.N, p.pool_x, p.pool_dst, p.pool_acc, p.pool_mask, p.mscale);
-                    continue;
-                }
-                v = v * sc + bi;
-                if (p.add) v += bf2f(p.add[o]);
-                if (p.accumulate) v += bf2f(p.C[o]);
-                if (p.relu) v = fmaxf(v, 0.f);
-                if (p.mask && !(bf2f(p.mask[o]) > 0.f)) v = 0.f;
-                if (p.mscale) v *= p.mscale[col];
-                p.C[o] = f2bf(v);
-            }
-    }
+    igemm_epilogue<Cfg::MI, Cfg::NI, Cfg::WTM, Cfg::WTN, MODE>(p, acc, m0, n0, wm, wn, lane, rows, Hc, Wc, ph, pw);
 }
+
+#ifdef LPM_TUNE
+// Measurement builds only.  On MI355X this variant is behind the register-staged kernel above on the workloads' layer
+// shapes (3x3 filters, K loops of 8 tiles: 12.6 against 11.1 us on 32x32x128->256; a 224x224 VGG-16 step 9.73 against
+// 9.51 ms) and ahead only on long 1x1 contractions with thousands of blocks (38.7 against 42.0 us), so product
+// launches do not use it.
+// The same contraction with the K tiles copied by loads that write LDS directly, through a ring of four stages
+// (three tiles in flight), for forward and stride-1 data gradient when the gathered tensor's channel count is a
+// multiple of 64 and the filter has at most 64 taps.  LDS rows are 64 elements (128 bytes) without padding; chunk c
+// (16 bytes) of tile row r sits at position c ^ ((r >> 1) & 7), which makes the operand fetches (32 rows x one
+// chunk per half-wavefront) conflict-free -- the loader simply asks for the chunk that belongs at its lane's place.
+// Per row, the filter taps that fall inside the image are a 64-bit mask computed once; per K tile a lane spends a
+// shift and a select.  One workgroup barrier per K tile, no staging registers, no LDS stores.
+constexpr int DL_TILE_BYTES = 64 * 128, DL_STAGE = 2 * DL_TILE_BYTES;
+
+template <int MODE, int DL_NST>
+__global__ void __launch_bounds__(256, 2) igemm_dl_kernel(IgemmArgs p) {
+    static_assert(MODE == MODE_FWD || MODE == MODE_DGRAD, "forward or stride-1 data gradient");
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];      // DL_NST stages of A tile + B tile
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nt = (p.N + 63) / 64;
+    const int tile = xcd_remap(blockIdx.x, gridDim.x);
+    const int m0 = (tile / nt) * 64, n0 = (tile % nt) * 64;
+    const int kt0 = blockIdx.z * p.kt_per_split, nk = min(p.kt_total, kt0 + p.kt_per_split) - kt0;
+    const u32x4_ rsA = buffer_words(p.A, p.a_bytes), rsB = buffer_words(p.B, p.b_bytes);
+    const int taps = p.Kh * p.Kw;
+
+    // loader: load wl (0..7) of an operand fills tile rows wl*8 .. wl*8+7; lane = row * 8 + position; this wavefront takes wl = wave, wave + 4
+    const int l_row = lane >> 3, l_pos = lane & 7;
+    unsigned a_base[2], b_off[2];
+    unsigned long long a_mask[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int row = (wave + 4 * i) * 8 + l_row, c = l_pos ^ ((row >> 1) & 7);
+        const int grow = m0 + row;
+        const bool ok = grow < p.M;
+        const int rr = ok ? grow : 0;
+        const int wq = rr % p.Wr, t = rr / p.Wr, hq = t % p.Hr, n = t / p.Hr;
+        const int h0 = MODE == MODE_FWD ? hq * p.stride - p.pad : hq + p.pad;
+        const int w0 = MODE == MODE_FWD ? wq * p.stride - p.pad : wq + p.pad;
+        a_base[i] = (unsigned)(((n * p.Hi + h0) * p.Wi + w0) * p.Ci + c * 8) * 2u;     // may wrap below zero; used only for taps inside
+        unsigned long long mk = 0;
+        for (int tp = 0; tp < taps; ++tp) {
+            const int kh = tp / p.Kw, kw = tp - kh * p.Kw;
+            const int h = MODE == MODE_FWD ? h0 + kh : h0 - kh, w = MODE == MODE_FWD ? w0 + kw : w0 - kw;
+            if (ok & ((unsigned)h < (unsigned)p.Hi) & ((unsigned)w < (unsigned)p.Wi)) mk |= 1ull << tp;
+        }
+        a_mask[i] = mk;
+        const int nn = n0 + row;
+        b_off[i] = nn < p.N ? (unsigned)(((size_t)nn * p.Ktot + c * 8) * 2) : 0xffffffffu;
+    }
+    // cursor of the next K tile to load: filter tap and channel offset
+    int c_tap, c_c0, c_kh, c_kw;
+    {
+        const int k0 = kt0 * 64;
+        c_tap = k0 / p.Ci; c_c0 = k0 - c_tap * p.Ci;
+        c_kh = c_tap / p.Kw; c_kw = c_tap - c_kh * p.Kw;
+    }
+#define LPM_DL_ISSUE(ST)                                                                                      \
+    {                                                                                                         \
+        unsigned char* st_ = lds + (ST) * DL_STAGE;                                                           \
+        const unsigned tapoff_ = MODE == MODE_FWD ? (unsigned)((c_kh * p.Wi + c_kw) * p.Ci + c_c0) * 2u        \
+                                                  : (unsigned)(c_c0 - (c_kh * p.Wi + c_kw) * p.Ci) * 2u;       \
+        const unsigned kb_ = (unsigned)(c_tap * p.Ci + c_c0) * 2u;                                            \
+        _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                       \
+            const bool in_ = (a_mask[i] >> c_tap) & 1ull;                                                     \
+            load_to_lds16(rsA, st_ + (wave + 4 * i) * 1024, in_ ? a_base[i] + tapoff_ : 0xffffffffu);         \
+        }                                                                                                     \
+        _Pragma("unroll") for (int i = 0; i < 2; ++i)                                                         \
+            load_to_lds16(rsB, st_ + DL_TILE_BYTES + (wave + 4 * i) * 1024,                                   \
+                          b_off[i] == 0xffffffffu ? 0xffffffffu : b_off[i] + kb_);                            \
+        c_c0 += 64;                                                                                           \
+        if (c_c0 >= p.Ci) {                                                                                   \
+            c_c0 = 0; ++c_tap;                                                                                \
+            if (++c_kw == p.Kw) { c_kw = 0; ++c_kh; }                                                         \
+        }                                                                                                     \
+    }
+
+    f32x16 acc[1][1];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[0][0][i] = 0.f;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int r = lane & 31, kq = lane >> 5, sw = (r >> 1) & 7;
+#pragma unroll
+    for (int i = 0; i < DL_NST - 1; ++i)
+        if (i < nk) LPM_DL_ISSUE(i);
+    int st = 0;
+    for (int it = 0; it < nk; ++it) {
+        wait_tiles_behind<4, (DL_NST > 2 ? DL_NST - 2 : 1)>(DL_NST > 2 ? nk - 1 - it : 0);      // tile `it` has landed: only the tiles behind it are outstanding
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();      // every wavefront's part has landed, and all are done reading the stage loaded next
+        asm volatile("" ::: "memory");
+        if (it + DL_NST - 1 < nk) {
+            const int st2 = st == 0 ? DL_NST - 1 : st - 1;
+            LPM_DL_ISSUE(st2);
+        }
+        const unsigned char* as = lds + st * DL_STAGE + (wm * 32 + r) * 128;
+        const unsigned char* bs = lds + st * DL_STAGE + DL_TILE_BYTES + (wn * 32 + r) * 128;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int po = ((ks * 2 + kq) ^ sw) * 16;
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(as + po);
+            const bf16x8 b = *reinterpret_cast<const bf16x8*>(bs + po);
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[0][0], 0, 0, 0);
+        }
+        st = st == DL_NST - 1 ? 0 : st + 1;
+    }
+#undef LPM_DL_ISSUE
+    igemm_epilogue<1, 1, 32, 32, MODE>(p, acc, m0, n0, wm, wn, lane, p.M, p.Hr, p.Wr, 0, 0);
+}
+#endif   // LPM_TUNE
 
 // sums split-K partials in split order and applies the epilogue
 __global__ void __launch_bounds__(256) splitk_epilogue(const float* __restrict__ part, int splits, int64_t MN, int N,
@@ -407,6 +557,33 @@ static IgemmPlan plan_igemm(int64_t M, int N, int Ktot, int ci) {
     return pl;
 }
 
+#ifdef LPM_TUNE
+template <int MODE>
+static bool igemm_dl_ok(const IgemmPlan& pl, const IgemmArgs& a) {
+    if (MODE == MODE_DGRAD_S || pl.bk != 64 || a.Kh * a.Kw > 64 || a.Kh * a.Kw < 1) return false;
+    const char* e = getenv("LPM_T_DL");
+    return e && atoi(e) != 0;
+}
+
+template <int MODE, int NST>
+static void launch_igemm_dl_n(const dim3& grid, const IgemmArgs& a, hipStream_t st) {
+    constexpr int M2 = MODE == MODE_DGRAD_S ? MODE_DGRAD : MODE;     // (never launched for the strided form)
+    const int bytes = NST * DL_STAGE;
+    static const hipError_t attr = hipFuncSetAttribute((const void*)igemm_dl_kernel<M2, NST>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    (void)attr;
+    hipLaunchKernelGGL((igemm_dl_kernel<M2, NST>), grid, dim3(256), bytes, st, a);
+}
+template <int MODE>
+static void launch_igemm_dl(const dim3& grid, const IgemmArgs& a, hipStream_t st) {
+    if (const char* e = getenv("LPM_T_NST")) {
+        if (atoi(e) == 3) { launch_igemm_dl_n<MODE, 3>(grid, a, st); return; }
+        if (atoi(e) == 4) { launch_igemm_dl_n<MODE, 4>(grid, a, st); return; }
+    }
+    launch_igemm_dl_n<MODE, 2>(grid, a, st);
+}
+
+#endif   // LPM_TUNE
+
 template <int MODE>
 static void launch_igemm_cfg(const IgemmPlan& pl, const IgemmArgs& a, hipStream_t st) {
 #ifdef LPM_TUNE      // measurement builds only: other block / wavefront tile shapes, chosen from the environment
@@ -435,6 +612,9 @@ static void launch_igemm_cfg(const IgemmPlan& pl, const IgemmArgs& a, hipStream_
 #endif
     const int mt = a.m_tiles ? a.m_tiles : (a.M + 63) / 64;
     const dim3 grid((unsigned)(mt * ((a.N + 63) / 64)), 1, pl.splits);
+#ifdef LPM_TUNE
+    if (igemm_dl_ok<MODE>(pl, a)) { launch_igemm_dl<MODE>(grid, a, st); return; }
+#endif
     if (pl.bk == 64) hipLaunchKernelGGL((igemm_kernel<64, 64, 64, 2, 2, MODE>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((igemm_kernel<64, 64, 32, 2, 2, MODE>), grid, dim3(256), 0, st, a);
 }
@@ -489,6 +669,7 @@ hipError_t mfma_conv_fwd(const ConvGeom& g, const void* x, const void* w, const 
     a.scale = scale; a.bias = bias; a.add = (const uint16_t*)add; a.relu = relu; a.accumulate = 0;
     a.M = (int)g.rows_out(); a.N = g.Cout; a.Ktot = g.K();
     a.Hi = g.H; a.Wi = g.W; a.Ci = g.Cin; a.Hr = g.Ho; a.Wr = g.Wo; a.Kw = g.Kw; a.stride = g.stride; a.pad = g.pad;
+    a.Kh = g.Kh;
     a.a_bytes = (unsigned)(g.rows_in() * g.Cin * 2); a.b_bytes = (unsigned)((int64_t)g.Cout * g.K() * 2);
     return run_igemm(MODE_FWD, a, ws, st);
 }
