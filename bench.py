@@ -249,6 +249,38 @@ def main():
         roof["step_contraction_flops"] = tot_flops
         roof["step_frac_of_mfma_peak"] = round(tot_flops / (ms_step * 1e-3) / (PEAK["mfma_bf16"] if dtype == lpm.BF16 else PEAK["fp32"]), 5)
 
+    # ---- layer-wise partitioning without merging ("Layer-wise Partitioning and Merging" section, fig. 1a): every layer
+    # as n = Z sub-layers on n streams with concatenation / re-partition / summation, against the merged layer
+    layerwise = None
+    if table:
+        n_sub = Z if 2 <= Z <= 8 else 4
+        merged_us = lw_us = 0.0
+        used = skipped = 0
+        lcache = {}
+        for i, l in enumerate(layers):
+            mine = [r for r in table if r["layer"] == i]
+            if not mine:
+                continue
+            if l["cout"] % (8 * n_sub):
+                skipped += 1
+                continue
+            g = next(g for (j, op, g, _, _) in ops if j == i)
+            key = tuple(sorted(g.items()))
+            if key not in lcache:
+                xx, ww, wt, yy, dw, _ = conv_buffers(torch, lpm, g, dtype)
+                lw = lpm.Layerwise(g, dtype, n_sub)
+                ws = torch.zeros(max(lw.fwd_ws_bytes, lw.bwd_ws_bytes, 256), dtype=torch.uint8, device="cuda")
+                want_dx = any(r["op"] == "dgrad" for r in mine)
+                dxx = torch.empty_like(xx) if want_dx else None
+                lcache[key] = lw.time(0, xx, ww, wt, yy, None, dw, ws, 5, 50, cur) + lw.time(1, xx, ww, wt, yy, dxx, dw, ws, 5, 50, cur)
+                lw.close()
+            used += 1
+            merged_us += sum(r["us"] for r in mine)
+            lw_us += lcache[key]
+        if used:
+            layerwise = dict(n=n_sub, layers=used, layers_skipped=skipped, merged_us_per_step=round(merged_us * M, 1),
+                             layerwise_us_per_step=round(lw_us * M, 1), overhead=round(lw_us / merged_us, 3))
+
     # ---- cost-model feedback (eq. 10 with measured operation times): re-plan from the measured contraction
     # times (layers without a contraction keep their analytic cost) and time the step under that plan
     replan = None
@@ -316,6 +348,7 @@ def main():
         "overlapped_ms_per_step_by_window": by_window,
         "partitions": part,
         "plan_from_measured_costs": replan,
+        "layerwise_unmerged": layerwise,
         "roofline": roof,
         "cpu_baseline": cpu,
     }

@@ -305,6 +305,43 @@ int32_t lpm_conv_wgrad(const lpm_conv_geom* g, int32_t dtype, const void* x, con
 int32_t lpm_conv_time(int32_t op, const lpm_conv_geom* g, int32_t dtype, void* x, const void* w, const void* wt,
                       void* y, float* dw, void* ws, int32_t warmup, int32_t iters, void* stream, float* avg_us);
 
+/* ---- layer-wise partitioning of one layer ("Layer-wise Partitioning and Merging" section, fig. 1a) ---- */
+
+/* The un-merged form of the method: a layer's output channels are split into n equal sub-layers (n = the paper's
+ * number of devices), each sub-layer is computed by its own launch on its own stream of the library's pool (the
+ * stand-in for a device) with its slice of the weights, and the outputs are concatenated for the next layer.
+ * Backward, the incoming gradient is re-partitioned by channel, each sub-layer produces its slice of the weight
+ * gradient and a full-size partial input gradient, and the partials are added in sub-layer order.  The results are
+ * those of the merged layer (lpm_conv_*); the difference in time is the overhead that merging removes.
+ * Geometry as lpm_conv_geom; cout must be divisible by n with cout / n a multiple of 8; 2 <= n <= 8.
+ * The handle owns host objects only (events).  Errors: LPM_EINVAL, LPM_ESHAPE, LPM_ENOMEM, LPM_EHIP. */
+typedef struct lpm_layerwise lpm_layerwise;
+int32_t lpm_layerwise_create(const lpm_conv_geom* g, int32_t dtype, int32_t n, lpm_layerwise** out);
+int32_t lpm_layerwise_destroy(lpm_layerwise* lw);
+
+/* Device scratch (caller-owned, 256-byte aligned) the two calls below need: the sub-layer outputs / the
+ * re-partitioned gradient and partial input gradients, plus each sub-layer's own contraction scratch. */
+int32_t lpm_layerwise_ws_bytes(const lpm_layerwise* lw, size_t* forward, size_t* backward);
+
+/* y = relu?( scale_c * (w (*) x) + bias_c ), computed as n sub-layers and one concatenation (eq. 1 per sub-layer).
+ *   x [m][h][w][cin], w [cout][kh][kw][cin] (sub-layer i owns rows i*cout/n ...), y [m][ho][wo][cout]; scale, bias
+ *   (float [cout]) may be NULL.  Enqueues on `stream` and on n pooled streams that fork from and join back into it;
+ *   calls on one handle must not overlap (they share its events and the scratch). */
+int32_t lpm_layerwise_forward(lpm_layerwise* lw, const void* x, const void* w, const float* scale, const float* bias,
+                              int32_t relu, void* y, void* ws, void* stream);
+
+/* dw (+)= weight gradient (float [cout][kh][kw][cin], eq. 8), dx = input gradient (eq. 9; NULL: not computed) from dz,
+ * the gradient w.r.t. the pre-activation [m][ho][wo][cout].
+ *   wt: for LPM_BF16, the n sub-layers' weights transposed one after the other, each [cin][kh][kw][cout/n] (what
+ *   each device would keep beside its slice of w), or NULL (slower kernels). */
+int32_t lpm_layerwise_backward(lpm_layerwise* lw, const void* x, const void* dz, const void* w, const void* wt, void* dx,
+                               float* dw, int32_t accumulate, void* ws, void* stream);
+
+/* Measurement helper, as lpm_conv_time: op 0 = lpm_layerwise_forward (ReLU epilogue), op 1 = lpm_layerwise_backward
+ * (y as dz, accumulating into dw; dx may be NULL).  Returns the average microseconds of one call; synchronises. */
+int32_t lpm_layerwise_time(lpm_layerwise* lw, int32_t op, const void* x, const void* w, const void* wt, void* y, void* dx,
+                           float* dw, void* ws, int32_t warmup, int32_t iters, void* stream, float* avg_us);
+
 #ifdef __cplusplus
 }
 #endif

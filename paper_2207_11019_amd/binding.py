@@ -9,7 +9,7 @@ import os
 
 import numpy as np
 
-__all__ = ["LpmError", "lib", "lpm_conv_geom", "lpm_conv_ws_bytes", "lpm_conv_forward", "lpm_conv_dgrad", "lpm_conv_wgrad", "lpm_conv_time", "lpm_layer", "lpm_cost_params", "lpm_stage_buffers", "layers_from_dicts",
+__all__ = ["LpmError", "lib", "lpm_conv_geom", "lpm_conv_ws_bytes", "lpm_conv_forward", "lpm_conv_dgrad", "lpm_conv_wgrad", "lpm_conv_time", "Layerwise", "lpm_layer", "lpm_cost_params", "lpm_stage_buffers", "layers_from_dicts",
            "lpm_layer_cost", "lpm_partition", "lpm_partition_costs", "Stage", "Schedule", "Net", "F32", "BF16", "LOCKED", "OVERLAPPED", "PIPELINED", "ASYNC_UPDATE",
            "GRAPH", "pack_act", "unpack_act", "pack_weight", "unpack_weight", "MI355X_COST"]
 
@@ -82,7 +82,14 @@ lib.lpm_conv_dgrad.argtypes = [C.POINTER(lpm_conv_geom), _i32, _vp, _vp, _vp, _v
 lib.lpm_conv_wgrad.argtypes = [C.POINTER(lpm_conv_geom), _i32, _vp, _vp, _vp, _i32, _vp, _vp]
 lib.lpm_conv_time.argtypes = [_i32, C.POINTER(lpm_conv_geom), _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp,
                               C.POINTER(C.c_float)]
-for _f in ("lpm_conv_time", "lpm_conv_ws_bytes", "lpm_conv_forward", "lpm_conv_dgrad", "lpm_conv_wgrad", "lpm_layer_cost", "lpm_partition", "lpm_partition_costs", "lpm_stage_create", "lpm_stage_destroy", "lpm_stage_sizes",
+lib.lpm_layerwise_create.argtypes = [C.POINTER(lpm_conv_geom), _i32, _i32, C.POINTER(_vp)]
+lib.lpm_layerwise_destroy.argtypes = [_vp]
+lib.lpm_layerwise_ws_bytes.argtypes = [_vp, _psz, _psz]
+lib.lpm_layerwise_forward.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]
+lib.lpm_layerwise_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]
+lib.lpm_layerwise_time.argtypes = [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, C.POINTER(C.c_float)]
+for _f in ("lpm_layerwise_create", "lpm_layerwise_destroy", "lpm_layerwise_ws_bytes", "lpm_layerwise_forward",
+           "lpm_layerwise_backward", "lpm_layerwise_time", "lpm_conv_time", "lpm_conv_ws_bytes", "lpm_conv_forward", "lpm_conv_dgrad", "lpm_conv_wgrad", "lpm_layer_cost", "lpm_partition", "lpm_partition_costs", "lpm_stage_create", "lpm_stage_destroy", "lpm_stage_sizes",
            "lpm_stage_param_offset", "lpm_stage_stash_offset", "lpm_stage_grad_offset", "lpm_stage_sync_lowp",
            "lpm_stage_forward", "lpm_stage_backward", "lpm_stage_update", "lpm_schedule_create",
            "lpm_schedule_destroy", "lpm_schedule_cut_fused", "lpm_schedule_run"):
@@ -195,6 +202,43 @@ def lpm_conv_time(op, g, dtype, x, w, wt, y, dw, ws, warmup=3, iters=20, stream=
     _check(lib.lpm_conv_time(op, C.byref(gg), dtype, _ptr(x), _ptr(w), _ptr(wt), _ptr(y), _ptr(dw), _ptr(ws), warmup, iters,
                              _stream(stream), C.byref(out)))
     return out.value
+
+
+class Layerwise:
+    """lpm_layerwise handle (one layer computed as n sub-layers); methods are the lpm_layerwise_* calls."""
+
+    def __init__(self, g, dtype, n):
+        self.h = None
+        gg = _geom(g)
+        h = C.c_void_p()
+        _check(lib.lpm_layerwise_create(C.byref(gg), dtype, n, C.byref(h)))
+        self.h, self.n, self.dtype = h, n, dtype
+        f, b = C.c_size_t(), C.c_size_t()
+        _check(lib.lpm_layerwise_ws_bytes(self.h, C.byref(f), C.byref(b)))
+        self.fwd_ws_bytes, self.bwd_ws_bytes = f.value, b.value
+
+    def forward(self, x, w, scale, bias, relu, y, ws, stream=None):
+        _check(lib.lpm_layerwise_forward(self.h, _ptr(x), _ptr(w), _ptr(scale), _ptr(bias), int(relu), _ptr(y), _ptr(ws),
+                                         _stream(stream)))
+
+    def backward(self, x, dz, w, wt, dx, dw, accumulate, ws, stream=None):
+        _check(lib.lpm_layerwise_backward(self.h, _ptr(x), _ptr(dz), _ptr(w), _ptr(wt), _ptr(dx), _ptr(dw), int(accumulate),
+                                          _ptr(ws), _stream(stream)))
+
+    def time(self, op, x, w, wt, y, dx, dw, ws, warmup=3, iters=20, stream=None):
+        """Average microseconds of one forward (op 0) or backward (op 1) call."""
+        out = C.c_float()
+        _check(lib.lpm_layerwise_time(self.h, op, _ptr(x), _ptr(w), _ptr(wt), _ptr(y), _ptr(dx), _ptr(dw), _ptr(ws), warmup,
+                                      iters, _stream(stream), C.byref(out)))
+        return out.value
+
+    def close(self):
+        if self.h:
+            lib.lpm_layerwise_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        self.close()
 
 
 def _ptr(t):
