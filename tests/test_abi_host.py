@@ -158,6 +158,18 @@ def test_error_codes(lpm):
     with pytest.raises(lpm.LpmError) as e:
         lpm.lpm_conv_ws_bytes(dict(m=1, h=4, w=4, cin=8, cout=8, kh=5, kw=5, stride=1, pad=0), lpm.BF16)
     assert e.value.code == -2
+    # layer-wise partitioning: the shape checks come before any device object is made
+    g = dict(m=2, h=8, w=8, cin=32, cout=64, kh=3, kw=3, stride=1, pad=1)
+    for n, code in ((1, -1), (9, -1), (3, -2)):
+        with pytest.raises(lpm.LpmError) as e:
+            lpm.Layerwise(g, lpm.BF16, n)
+        assert e.value.code == code
+    with pytest.raises(lpm.LpmError) as e:                      # 15 channels per sub-layer
+        lpm.Layerwise(dict(g, cout=60), lpm.BF16, 4)
+    assert e.value.code == -2
+    with pytest.raises(lpm.LpmError) as e:
+        lpm.Layerwise(dict(g, kh=11, kw=11), lpm.BF16, 2)
+    assert e.value.code == -2
 
 
 def test_stage_layout(lpm):
