@@ -96,7 +96,8 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
             gws += align_up(o.elems() * (size_t)microbatch * s->esz, 256);
         }
         lr.wws_off = wws;                        // every layer its own area: the reductions of a pass run in one launch
-        wws += align_up(std::max(wgrad_ws_bytes(dtype, lr.g), wgrad_staged_ws_bytes(dtype, lr.g)), 256);
+        wws += align_up(std::max({wgrad_ws_bytes(dtype, lr.g), wgrad_staged_ws_bytes(dtype, lr.g),
+                                  epi_bwd_ws_bytes(lr.g.rows_out(), l.cout)}), 256);   // (a bias-only reduction runs here too)
         if (wgrad_staged_ok(dtype, lr.g)) {
             lr.fcs_x_off = fcs;  fcs += align_up((size_t)LPM_FC_STAGE_SLOTS * lr.g.rows_in() * lr.g.Cin * 2, 256);
             lr.fcs_dz_off = fcs; fcs += align_up((size_t)LPM_FC_STAGE_SLOTS * lr.g.rows_out() * lr.g.Cout * 2, 256);
@@ -383,7 +384,9 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
     // layer, the point in its stream where that layer's output gradient is final, and the weight phase waits for
     // that point before the layer's weight gradient instead of for the end of the data phase
     const bool by_layer = layer_slot >= 0 && deferred && (do_data != do_weights);
-    struct WgradJob { const LayerRt* lr; const void* xin; const void* dz; float* wdb; const float* sc; };
+    // bias_g != NULL: the layer's bias gradient is a plain column sum of bias_g that nothing in the data phase needs;
+    // it runs in the weight phase, ahead of the layer's weight gradient (scratch: the layer's own area)
+    struct WgradJob { const LayerRt* lr; const void* xin; const void* dz; float* wdb; const float* sc; const void* bias_g; float* bias_db; };
     // One weight gradient on stream q.  fc_slot = j >= 0 (of fc_flush = M micro-batches): a layer with staging areas
     // files its operands under slot j and contracts a group of slots at a time; the first group overwrites the accumulator.
     auto one_wgrad = [&](const WgradJob& j, hipStream_t q, ReduceDesc* d) -> hipError_t {
@@ -447,6 +450,7 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                 float* dbias = lr.b_off != NO ? grads + lr.b_off : nullptr;
                 const bool bias_in_wgrad = dbias && wgrad_fuses_bias(s->dtype, lr.g);
                 const void* dz = g;
+                const void* bias_g = nullptr;
                 if (lr.fused_in) {
                     dz = gw + lr.dz_off;           // written by the consumer's backward kernel
                 } else if (i == s->t_out && (boundary & LPM_DY_IS_DZ)) {
@@ -460,7 +464,9 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                         have[gi(l.add_src)] = 1;
                     }
                     const bool need_dz = relu || sc;
-                    if (need_dz || gadd || (dbias && !bias_in_wgrad)) {
+                    if (!need_dz && !gadd && dbias && !bias_in_wgrad && deferred) {
+                        bias_g = g;
+                    } else if (need_dz || gadd || (dbias && !bias_in_wgrad)) {
                         if (do_data) LPM_HIP(launch_epilogue_bwd(s->dtype, lr.g.rows_out(), l.cout, g, relu ? yout : nullptr, sc,
                                                     need_dz ? (void*)(gw + lr.dz_off) : nullptr, gadd, gadd_acc,
                                                     bias_in_wgrad ? nullptr : dbias, acc, kws, st));
@@ -512,13 +518,13 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                 }
                 const void* xin = tptr(s, l.src, x, y, stash);
                 if (deferred) {
-                    jobs.push_back(WgradJob{&lr, xin, dz, wdb, sc});
+                    jobs.push_back(WgradJob{&lr, xin, dz, wdb, sc, bias_g, bias_g ? dbias : nullptr});
                 } else {
                     std::vector<hipGraphNode_t> before;
                     LPM_HIP(frontier(before));
                     if (!wtail.empty())       // weight gradients share one scratch area: keep them in a chain
                         LPM_HIP(hipStreamUpdateCaptureDependencies(st, wtail.data(), wtail.size(), hipStreamAddCaptureDependencies));
-                    LPM_HIP(one_wgrad(WgradJob{&lr, xin, dz, wdb, sc}, st, nullptr));
+                    LPM_HIP(one_wgrad(WgradJob{&lr, xin, dz, wdb, sc, nullptr, nullptr}, st, nullptr));
                     LPM_HIP(frontier(wtail));
                     LPM_HIP(hipStreamUpdateCaptureDependencies(st, before.data(), before.size(), hipStreamSetCaptureDependencies));
                 }
@@ -578,6 +584,9 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
             ReduceDesc d{};
             if (by_layer)
                 LPM_HIP(hipStreamWaitEvent(wst, s->ev_layer[(size_t)(j.lr - &s->lay[0]) * LPM_MAX_WINDOW + layer_slot], 0));
+            if (j.bias_g)
+                LPM_HIP(launch_epilogue_bwd(s->dtype, j.lr->g.rows_out(), j.lr->d.cout, j.bias_g, nullptr, nullptr, nullptr, nullptr, 0,
+                                            j.bias_db, acc, (char*)wws + j.lr->wws_off, wst));
             LPM_HIP(one_wgrad(j, wst, &d));
             if (d.splits > 0) red.push_back(d);
         }
