@@ -564,4 +564,16 @@ hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t s) {
     return hipGetLastError();
 }
 
+// One wavefront that does nothing for `ticks` periods of the constant 100 MHz device clock (it leaves the loop as soon
+// as the clock has advanced that far): the probe kernel of streams_share_queue.
+__global__ void spin_kernel(long long ticks) {
+    const long long t0 = wall_clock64();
+    while (wall_clock64() - t0 < ticks) __builtin_amdgcn_s_sleep(16);
+}
+
+hipError_t launch_spin(long long ticks, hipStream_t s) {
+    hipLaunchKernelGGL(spin_kernel, dim3(1), dim3(64), 0, s, ticks);
+    return hipGetLastError();
+}
+
 }  // namespace lpm

@@ -23,6 +23,14 @@ constexpr int LPM_POOL_SCHEDULE_STREAMS = 8;    // indices 0..7: forward / backw
 constexpr int LPM_POOL_STREAMS = 12;            // indices 8..11: weight-gradient side streams, handed out round-robin
 hipError_t pooled_stream(int index, hipStream_t* out);
 int next_side_stream_index();
+// The runtime spreads a process's streams over a few hardware queues (four by default), and a hardware queue runs
+// its kernels strictly one after the other -- two streams on one queue never overlap, and a wait at the head of one
+// holds up the other.  Which queue a stream gets is not exposed, so it is measured: a short spin kernel on each of the
+// two streams, started together; *shared = they ran back to back.  Synchronises both streams.
+hipError_t streams_share_queue(hipStream_t a, hipStream_t b, bool* shared);
+// Up to `want` pooled streams that share a hardware queue neither with one of taken[0..n_taken) nor with each other.
+hipError_t pick_concurrent_streams(const hipStream_t* taken, int n_taken, hipStream_t* out, int want, int* found);
+hipError_t launch_spin(long long ticks, hipStream_t st);
 
 // ---- validated network description ---------------------------------------------------------------
 struct Shape { int32_t c, h, w; size_t elems() const { return (size_t)c * h * w; } };

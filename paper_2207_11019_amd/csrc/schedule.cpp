@@ -84,6 +84,9 @@ struct lpm_schedule {
     std::vector<hipEvent_t> ev_w;   // [Z*M]  all of B_{z,j} done (weight phase included)
     hipEvent_t ev_fork = nullptr;
     std::vector<hipStream_t> sf, sb;     // PIPELINED: per-stage forward / backward streams (borrowed from the pool)
+    // OVERLAPPED: the weight phases' streams, picked from the pool so that forward, data phases, weight phases and
+    // stage 0's weight phase each feed a hardware queue of their own; measured once per (sf, sb) pair
+    hipStream_t ov_sf = nullptr, ov_sb = nullptr, ov_w = nullptr, ov_w0 = nullptr;
     std::vector<char> cut_fused;         // [Z] the ReLU backward of stage z-1's last layer runs inside stage z's backward kernel
     std::vector<GraphEntry> graphs;
 
@@ -338,13 +341,29 @@ int32_t pipelined_role(lpm_schedule* s, const RunArgs& a, int32_t z, uint64_t ep
     return LPM_OK;
 }
 
+// Streams of the weight phases for an OVERLAPPED run on (sf, sb): two pooled streams that share a hardware queue
+// neither with sf or sb nor with each other; failing that one such stream for both, failing that stage 0's side
+// stream.  The choice only affects how much overlaps, never the result.
+int32_t pick_weight_streams(lpm_schedule* s, hipStream_t sf, hipStream_t sb) {
+    if (s->ov_w && s->ov_sf == sf && s->ov_sb == sb) return LPM_OK;
+    const hipStream_t taken[2] = {sf, sb};
+    hipStream_t got[2] = {nullptr, nullptr};
+    int found = 0;
+    LPM_HIP(pick_concurrent_streams(taken, 2, got, 2, &found));
+    s->ov_w = found > 0 ? got[0] : s->st[0]->side;
+    s->ov_w0 = found > 1 ? got[1] : s->ov_w;
+    s->ov_sf = sf;
+    s->ov_sb = sb;
+    return LPM_OK;
+}
+
 // OVERLAPPED, three workers: 0 enqueues the forward chains on sf, 1 the data phases of the backward chains
 // on sb, 2 the weight phases and the updates on the weight stream (stage 0's side stream).
 // ev_f[j*Z+Z-1]: forward chain j done; ev_b[j*Z+z]: data phase of B_{z,j} done; ev_w[j*Z]: micro-batch j done.
 int32_t overlapped_role(lpm_schedule* s, const RunArgs& a, int32_t role, uint64_t epoch) {
     const int32_t Z = s->Z, M = s->M, W = s->window;
     const bool async = (a.mode & LPM_ASYNC_UPDATE) != 0;
-    hipStream_t sw = s->st[0]->side;
+    hipStream_t sw = s->ov_w;
     int32_t rc;
     if (role == 0) {
         for (int32_t j = 0; j < M; ++j) {
@@ -384,8 +403,14 @@ int32_t overlapped_role(lpm_schedule* s, const RunArgs& a, int32_t role, uint64_
             }
         }
     } else {
+        // Stage 0's weight phase closes every micro-batch, and the next forward chain but one waits for it: with a
+        // hardware queue to itself it follows stage 0's data phase from the start instead of queueing behind the other
+        // stages' weight phases.  ev_w[j*Z+1] then marks the end of those on the common weight stream.
+        const bool own0 = !async && Z > 1 && s->ov_w0 != s->ov_w;
+        hipStream_t sw_all = sw, sw_0 = s->ov_w0;
         for (int32_t j = 0; j < M; ++j) {
             for (int32_t z = Z - 1; z >= 0; --z) {
+                sw = (own0 && z == 0) ? sw_0 : sw_all;
                 const size_t i = (size_t)j * Z + z;
                 if ((rc = await_record(s, s->rec_b[i], epoch))) return rc;
                 // Stage 0 closes the micro-batch, and the next forward chain but one waits for it: there the weight
@@ -405,6 +430,10 @@ int32_t overlapped_role(lpm_schedule* s, const RunArgs& a, int32_t role, uint64_
                         publish(s->rec_w[i], epoch);
                     }
                 } else if (j == M - 1 && (rc = upd_op(s, a, z, sw))) return rc;
+            }
+            if (own0) {        // sw is stage 0's stream here: the micro-batch is done when the other stream is, too
+                LPM_HIP(hipEventRecord(s->ev_w[(size_t)j * Z + 1], sw_all));
+                LPM_HIP(hipStreamWaitEvent(sw, s->ev_w[(size_t)j * Z + 1], 0));
             }
             LPM_HIP(hipEventRecord(s->ev_w[(size_t)j * Z], sw));
             publish(s->rec_w[(size_t)j * Z], epoch);
@@ -514,6 +543,7 @@ int32_t enqueue(lpm_schedule* s, const RunArgs& a) {
         return LPM_OK;
     }
     if (!capturing) {
+        if ((rc = pick_weight_streams(s, a.sf, a.sb))) return rc;
         if ((rc = run_roles(s, a, overlapped_role, 3))) return rc;
         LPM_HIP(hipStreamWaitEvent(a.sf, s->ev_w[(size_t)(M - 1) * Z], 0));
         return LPM_OK;

@@ -6,6 +6,7 @@
 // topological order of its dependency graph, so shared streams cannot dead-lock it.
 #include "lpm_internal.h"
 
+#include <algorithm>
 #include <map>
 #include <mutex>
 
@@ -30,6 +31,56 @@ hipError_t pooled_stream(int index, hipStream_t* out) {
         if (e != hipSuccess) { v[(size_t)index] = nullptr; return e; }
     }
     *out = v[(size_t)index];
+    return hipSuccess;
+}
+
+hipError_t streams_share_queue(hipStream_t a, hipStream_t b, bool* shared) {
+    *shared = true;
+    if (a == b) return hipSuccess;
+    constexpr long long SPIN_TICKS = 5000;               // 50 us of the 100 MHz clock
+    hipEvent_t e0 = nullptr, ea = nullptr, eb = nullptr;
+    hipError_t e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&ea);
+    if (e == hipSuccess) e = hipEventCreate(&eb);
+    // b's kernel may start once a's stream has reached the probe, so both time spans start at e0
+    if (e == hipSuccess) e = hipEventRecord(e0, a);
+    if (e == hipSuccess) e = launch_spin(SPIN_TICKS, a);
+    if (e == hipSuccess) e = hipStreamWaitEvent(b, e0, 0);
+    if (e == hipSuccess) e = launch_spin(SPIN_TICKS, b);
+    if (e == hipSuccess) e = hipEventRecord(eb, b);
+    if (e == hipSuccess) e = hipEventRecord(ea, a);
+    if (e == hipSuccess) e = hipEventSynchronize(ea);
+    if (e == hipSuccess) e = hipEventSynchronize(eb);
+    float ta = 0.f, tb = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ta, e0, ea);
+    if (e == hipSuccess) e = hipEventElapsedTime(&tb, e0, eb);
+    if (e0) (void)hipEventDestroy(e0);
+    if (ea) (void)hipEventDestroy(ea);
+    if (eb) (void)hipEventDestroy(eb);
+    if (e != hipSuccess) return e;
+    // side by side both spans are one spin (0.05 ms) plus launch latency; back to back the later one is two spins
+    *shared = std::max(ta, tb) > 0.08f;
+    return hipSuccess;
+}
+
+hipError_t pick_concurrent_streams(const hipStream_t* taken, int n_taken, hipStream_t* out, int want, int* found) {
+    std::vector<hipStream_t> have(taken, taken + n_taken);
+    *found = 0;
+    // the side streams first (they exist anyway), then the per-stage schedule streams
+    for (int k = 0; k < LPM_POOL_STREAMS && *found < want; ++k) {
+        const int index = (k + LPM_POOL_SCHEDULE_STREAMS) % LPM_POOL_STREAMS;
+        hipStream_t c = nullptr;
+        hipError_t e = pooled_stream(index, &c);
+        if (e != hipSuccess) return e;
+        bool clash = false;
+        for (size_t i = 0; i < have.size() && !clash; ++i) {
+            e = streams_share_queue(have[i], c, &clash);
+            if (e != hipSuccess) return e;
+        }
+        if (clash) continue;
+        have.push_back(c);
+        out[(*found)++] = c;
+    }
     return hipSuccess;
 }
 
