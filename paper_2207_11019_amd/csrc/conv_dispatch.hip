@@ -20,8 +20,9 @@ bool mfma_wgrad_ok(const ConvGeom& g);
 size_t mfma_fwd_ws_bytes(const ConvGeom& g);
 size_t mfma_dgrad_ws_bytes(const ConvGeom& g);
 size_t mfma_wgrad_ws_bytes(const ConvGeom& g);
+bool mfma_fwd_pools(const ConvGeom& g);
 hipError_t mfma_conv_fwd(const ConvGeom& g, const void* x, const void* w, const float* scale, const float* bias,
-                         const void* add, int relu, void* y, void* ws, hipStream_t st);
+                         const void* add, int relu, void* y, void* ws, hipStream_t st, void* pool_y);
 hipError_t mfma_conv_dgrad(const ConvGeom& g, const void* dz, const void* wt, void* dx, int accumulate, const void* mask,
                            const float* mscale, void* ws, hipStream_t st, const UnpoolDesc* unpool);
 hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* bscale,
@@ -65,9 +66,12 @@ size_t wgrad_ws_bytes(int dtype, const ConvGeom& g) {
     return wgrad_generic_ws_bytes(g);
 }
 
+bool fwd_can_pool(int dtype, const ConvGeom& g) { return dtype == LPM_BF16 && mfma_fwd_pools(g); }
+
 hipError_t launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, const float* scale,
-                           const float* bias, const void* add, int relu, void* y, void* ws, hipStream_t st) {
-    if (dtype == LPM_BF16 && mfma_fwd_ok(g)) return mfma_conv_fwd(g, x, w, scale, bias, add, relu, y, ws, st);
+                           const float* bias, const void* add, int relu, void* y, void* ws, hipStream_t st, void* pool_y) {
+    if (pool_y && !fwd_can_pool(dtype, g)) return hipErrorInvalidValue;      // callers ask fwd_can_pool first
+    if (dtype == LPM_BF16 && mfma_fwd_ok(g)) return mfma_conv_fwd(g, x, w, scale, bias, add, relu, y, ws, st, pool_y);
     if (dtype == LPM_BF16 && smallk_ok(g)) return smallk_conv_fwd(g, x, w, scale, bias, add, relu, y, st);
     return conv_fwd_generic_launch(dtype, g, x, w, scale, bias, add, relu, y, st);
 }

@@ -73,6 +73,7 @@ struct IgemmArgs {
     const uint16_t* pool_x;      // pooling input [m][2*Hr][2*Wr][N], NULL: plain output
     uint16_t* pool_dst;
     int pool_acc, pool_mask;     // (the per-channel factor is mscale)
+    uint16_t* fwd_pool;          // forward with split K only: also store the 2x2 max-pooling of C, [m][Hr/2][Wr/2][N]
 };
 
 // One element v of the gradient of a 2x2 max-pooling output at pooled pixel `row`, channel `col`: goes to the first
@@ -513,6 +514,40 @@ __global__ void __launch_bounds__(256) splitk_epilogue_unpool(const float* __res
     unpool_store(v, (int)(i / N), (int)(i % N), Hr, Wr, N, pool_x, dst, acc, mask, mscale);
 }
 
+// forward: the same sum and epilogue, and the 2x2 max-pooling of the result as well (of the rounded values, as the
+// pooling kernel would see them): P[m][Hr/2][Wr/2][N].  A block takes one pooling window x 64 channels; wavefront k
+// takes window position k, so every thread sums one element as in splitk_epilogue and the maximum goes through LDS.
+__global__ void __launch_bounds__(256) splitk_epilogue_pool(const float* __restrict__ part, int splits, int64_t MN, int N, int Hr,
+                                                            int Wr, const float* __restrict__ scale,
+                                                            const float* __restrict__ bias, int relu,
+                                                            uint16_t* __restrict__ C, uint16_t* __restrict__ P) {
+    __shared__ float win[4][64];
+    const int lane = threadIdx.x & 63, k = threadIdx.x >> 6;
+    const int cgroups = (N + 63) >> 6;
+    const int col = (int)(blockIdx.x % cgroups) * 64 + lane;
+    int64_t q = blockIdx.x / cgroups;        // pooled pixel (n, py, px)
+    const int64_t pooled = q;
+    const int Wp = Wr >> 1, Hp = Hr >> 1;
+    const int px = (int)(q % Wp); q /= Wp;
+    const int py = (int)(q % Hp);
+    const int64_t n = q / Hp;
+    float r = 0.f;
+    if (col < N) {
+        const int64_t e = ((n * Hr + 2 * py + (k >> 1)) * Wr + 2 * px + (k & 1)) * N + col;
+        float v = part[e];
+        for (int s = 1; s < splits; ++s) v += part[(int64_t)s * MN + e];
+        if (scale) v *= scale[col];
+        if (bias) v += bias[col];
+        if (relu) v = fmaxf(v, 0.f);
+        const uint16_t h = f2bf(v);
+        C[e] = h;
+        r = bf2f(h);
+    }
+    win[k][lane] = r;
+    __syncthreads();
+    if (k == 0 && col < N) P[pooled * N + col] = f2bf(fmaxf(fmaxf(win[0][lane], win[1][lane]), fmaxf(win[2][lane], win[3][lane])));
+}
+
 hipError_t launch_splitk_epilogue(const float* part, int splits, int64_t MN, int N, const float* scale, const float* bias,
                                   const void* add, int relu, int accumulate, const void* mask, const float* mscale,
                                   void* C, hipStream_t st) {
@@ -630,7 +665,10 @@ static hipError_t run_igemm(int mode, IgemmArgs a, void* ws, hipStream_t st) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.splits == 1) return e;
     const int64_t MN = (int64_t)a.M * a.N;
-    if (a.pool_x)
+    if (a.fwd_pool)
+        hipLaunchKernelGGL(splitk_epilogue_pool, dim3((unsigned)((a.M / 4) * ((a.N + 63) / 64))), dim3(256), 0, st, (const float*)ws, pl.splits,
+                           MN, a.N, a.Hr, a.Wr, a.scale, a.bias, a.relu, a.C, a.fwd_pool);
+    else if (a.pool_x)
         hipLaunchKernelGGL(splitk_epilogue_unpool, dim3((unsigned)((MN + 255) / 256)), dim3(256), 0, st, (const float*)ws,
                            pl.splits, MN, a.N, a.Hr, a.Wr, a.pool_x, a.pool_dst, a.pool_acc, a.pool_mask, a.mscale);
     else
@@ -662,9 +700,17 @@ size_t mfma_dgrad_ws_bytes(const ConvGeom& g) {
     return pl.splits > 1 ? (size_t)pl.splits * g.rows_in() * g.Cin * sizeof(float) : 0;
 }
 
+// whether the forward contraction of this layer can also store the 2x2 max-pooling of its output (pool_y below):
+// the split-K form, whose second kernel sees whole pooling windows
+bool mfma_fwd_pools(const ConvGeom& g) {
+    return mfma_fwd_ok(g) && !(g.Ho & 1) && !(g.Wo & 1) && plan_igemm(g.rows_out(), g.Cout, g.K(), g.Cin).splits > 1;
+}
+
 hipError_t mfma_conv_fwd(const ConvGeom& g, const void* x, const void* w, const float* scale, const float* bias,
-                         const void* add, int relu, void* y, void* ws, hipStream_t st) {
+                         const void* add, int relu, void* y, void* ws, hipStream_t st, void* pool_y) {
+    if (pool_y && (add || !mfma_fwd_pools(g))) return hipErrorInvalidValue;
     IgemmArgs a{};
+    a.fwd_pool = (uint16_t*)pool_y;
     a.A = (const uint16_t*)x; a.B = (const uint16_t*)w; a.C = (uint16_t*)y;
     a.scale = scale; a.bias = bias; a.add = (const uint16_t*)add; a.relu = relu; a.accumulate = 0;
     a.M = (int)g.rows_out(); a.N = g.Cout; a.Ktot = g.K();

@@ -55,8 +55,11 @@ struct ConvGeom {
 // activations / activation gradients / low-precision weights (LPM_F32: float everywhere).
 
 // y = relu?( scale_c * conv(x, w) + bias_c + add )      (scale, bias, add may be NULL)
+// pool_y (may be NULL; only when fwd_can_pool and add == NULL): also stores the 2x2 max-pooling of y, [m][Ho/2][Wo/2][Cout]
 hipError_t launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, const float* scale,
-                           const float* bias, const void* add, int relu, void* y, void* ws, hipStream_t st);
+                           const float* bias, const void* add, int relu, void* y, void* ws, hipStream_t st,
+                           void* pool_y = nullptr);
+bool fwd_can_pool(int dtype, const ConvGeom& g);
 // dx (+)= conv_transpose(dz, w);  then, when given, dx = dx * [mask > 0] * mscale_c -- the epilogue backward of
 // the layer that produced the tensor dx belongs to (mask = that tensor, mscale = that layer's scale)
 // unpool (may be NULL; only when dgrad_can_unpool): dx is the gradient of a 2x2 max-pooling output that nothing else

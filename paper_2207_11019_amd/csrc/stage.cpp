@@ -140,6 +140,18 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
         lr.unpool_of = p;
         s->Ly(p).unpooled = true;
     }
+    // Pooling-forward fusion: a convolution whose output feeds a 2x2 max-pooling inside the stage and whose forward
+    // contraction ends in a split reduction: that reduction stores the pooled tensor as well (one kernel less per pool
+    // on the forward chain; the pooling layer's own input stays stored, the backward pass needs it).
+    for (int32_t i = first; i + 1 < last; ++i) {
+        LayerRt& lr = s->Ly(i);
+        const lpm_layer& l = lr.d;
+        const lpm_layer& pl = s->net[(size_t)i + 1];
+        if (!has_weights(l) || l.add_src != LPM_NONE || pl.kind != LPM_MAXPOOL2 || pl.src != i) continue;
+        if ((pl.h_in & 1) || (pl.w_in & 1) || !fwd_can_pool(dtype, lr.g)) continue;
+        lr.pool_fwd = i + 1;
+        s->Ly(i + 1).pooled_fwd = true;
+    }
     s->n_trainable = off;
     if (dtype == LPM_BF16) {                   // transposed copies follow the mirrored region
         const size_t base = align_up(off * 2, 256);
@@ -312,10 +324,12 @@ extern "C" int32_t lpm_stage_forward(lpm_stage* s, const void* x, void* y, const
                 const float* sc = lr.s_off != NO ? params + lr.s_off : nullptr;
                 const float* bi = lr.b_off != NO ? params + lr.b_off : nullptr;
                 const void* add = l.add_src != LPM_NONE ? tptr(s, l.add_src, x, y, stash) : nullptr;
-                LPM_HIP(launch_conv_fwd(s->dtype, lr.g, in, w, sc, bi, add, (l.flags & LPM_RELU) != 0, outp, fwd_ws, st));
+                void* pooled = lr.pool_fwd >= 0 ? const_cast<void*>(tptr(s, lr.pool_fwd, x, y, stash)) : nullptr;
+                LPM_HIP(launch_conv_fwd(s->dtype, lr.g, in, w, sc, bi, add, (l.flags & LPM_RELU) != 0, outp, fwd_ws, st, pooled));
                 break;
             }
             case LPM_MAXPOOL2:
+                if (lr.pooled_fwd) break;        // stored by the producer's forward kernel
                 LPM_HIP(launch_maxpool_fwd(s->dtype, s->m, l.h_in, l.w_in, l.cin, in, outp, st));
                 break;
             case LPM_GAP:
