@@ -339,7 +339,7 @@ def main():
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dt, "data": "synthetic",
         "config": {"workload": args.workload, "global_batch": batch, "n_microbatch": M, "microbatch": m, "partitions": Z,
-                   "plan": starts, "schedule": ("overlapped, 2 HIP streams" if sched == "overlapped" else "pipelined, 2 HIP streams per partition")
+                   "plan": starts, "schedule": ("overlapped, forward / data-phase / weight-phase chains on HIP streams of their own" if sched == "overlapped" else "pipelined, HIP streams per partition")
                    + ", window 2, " + ("graph replay" if best == "graph" else "eager enqueue"),
                    "lr": lr, "momentum": mu},
         "locked_ms_per_step": round(t_locked / args.steps * 1e3, 4),

@@ -253,8 +253,12 @@ int32_t lpm_schedule_cut_fused(const lpm_schedule* s, int32_t z);
  *   dx_wanted  non-zero: stage 0 also produces the gradient w.r.t. x (micro-batch j into
  *              per_stage[0].grad_in[j % window]; for partitions fed by an upstream activation)
  *   loss_out   device float; set to the mini-batch mean loss (loss stage only; may be NULL otherwise)
- *   stream_fwd, stream_bwd  two distinct streams for LPM_OVERLAPPED; LPM_LOCKED and LPM_PIPELINED use
- *              stream_fwd only (PIPELINED forks its own streams from it and joins them back).
+ *   stream_fwd, stream_bwd  two distinct streams for LPM_OVERLAPPED (forward chains and the data phases of the
+ *              backward chains; the weight phases run on streams of the library, forked from and joined back
+ *              into these.  The first such run on a pair of streams launches a few short probe kernels on them
+ *              and synchronises them, to find library streams that do not share a hardware queue with them);
+ *              LPM_LOCKED and LPM_PIPELINED use stream_fwd only (PIPELINED forks its own streams from it and
+ *              joins them back).
  * Micro-batch j uses slot j % window of stash, act_out and grad_in in every mode.
  * mode | LPM_ASYNC_UPDATE (with LPM_LOCKED or LPM_OVERLAPPED, window <= 2, not with LPM_GRAPH): the
  *   asynchronous parameter update.  Every micro-batch is a mini-batch of its own (loss = mean over its m
