@@ -42,6 +42,11 @@ hipError_t streams_share_queue(hipStream_t a, hipStream_t b, bool* shared) {
     hipError_t e = hipEventCreate(&e0);
     if (e == hipSuccess) e = hipEventCreate(&ea);
     if (e == hipSuccess) e = hipEventCreate(&eb);
+    // the first launch on a stream can take far longer than any later one (the runtime sets the stream up): not timed
+    if (e == hipSuccess) e = launch_spin(1, a);
+    if (e == hipSuccess) e = launch_spin(1, b);
+    if (e == hipSuccess) e = hipStreamSynchronize(a);
+    if (e == hipSuccess) e = hipStreamSynchronize(b);
     // b's kernel may start once a's stream has reached the probe, so both time spans start at e0
     if (e == hipSuccess) e = hipEventRecord(e0, a);
     if (e == hipSuccess) e = launch_spin(SPIN_TICKS, a);
