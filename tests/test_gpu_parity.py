@@ -135,6 +135,34 @@ def test_lenet_config_f32(lpm):
         assert nets[lpm.LOCKED].loss_value() == nets[mode].loss_value()
 
 
+def test_overlapped_on_changing_streams(lpm):
+    """OVERLAPPED picks the weight phases' streams for the caller's pair of streams at the first run on that pair:
+    steps on a second pair, on the first pair again and with the two streams swapped must all give LOCKED's bits."""
+    import torch
+    layers = wl.tiny_vgg()
+    starts = _starts(layers, 2)
+    o = oracle_step(layers, starts, 8, 4, True, seed=9, lr=0.05, mu=0.9)
+    ref = gpu_step(lpm, layers, starts, 8, 4, 1, o, 0.05, 0.9, lpm.LOCKED)
+    compare(ref, layers, starts, 4, 1, o)
+    a = ref.read_params()
+    net = lpm.Net(layers, starts, 2, 4, 1)
+    xd = lpm.pack_act(o["x"], 1)
+    ld = torch.from_numpy(o["labels"]).to("cuda:0")
+    first = (net.stream_fwd, net.stream_bwd)
+    second = (torch.cuda.Stream(), torch.cuda.Stream())
+    for k, (sf, sb) in enumerate((first, second, first, (second[1], second[0]))):
+        print("stream pair", k, flush=True)
+        net.stream_fwd, net.stream_bwd = sf, sb
+        net.load_params(o["p0"], o["m0"])
+        net.step(xd, ld, None, 0.05, 0.9, lpm.OVERLAPPED)
+        torch.cuda.synchronize()
+        b = net.read_params()
+        for i in a:
+            for key in a[i]:
+                np.testing.assert_array_equal(a[i][key], b[i][key])
+        assert ref.loss_value() == net.loss_value()
+
+
 def test_two_steps_with_momentum(lpm):
     layers = wl.tiny_vgg()
     starts = _starts(layers, 2)
