@@ -225,7 +225,7 @@ CONFIGS = {
     "lenet":          (lenet, 32, 4, 2, "f32", None),
     "vgg16_cifar":    (vgg16_cifar, 128, 8, 4, "bf16", None),
     "resnet18_cifar": (resnet18_cifar, 256, 8, 4, "bf16", [0, 5, 10, 15, 23]),      # cuts at the stage boundaries
-    "resnet34_cifar": (resnet34_cifar, 256, 8, 4, "bf16", [0, 7, 16, 29, 39]),      # (not a BASELINE config: same shapes, more depth)
+    "resnet34_cifar": (resnet34_cifar, 256, 8, 4, "bf16", [0, 7, 16, 29, 39]),      # (not one of the five benchmark configurations: the same shapes, more depth)
     "r50_conv4x":     (r50_conv4x, 64, 4, 1, "bf16", None),
     "vgg16_224":      (vgg16_224, 32, 8, 4, "bf16", None),
 }
