@@ -9,6 +9,7 @@ What it computes is plain mini-batch backpropagation plus SGD, re-organised in t
   * loss              f(a^L, e), softmax cross-entropy              (Problem Statement, eq. 3; Results section)
   * backward          chain rule for parameter/activation gradients (Problem Statement, eqs. 8-9)
   * update            p <- p - alpha * omega                        (Problem Statement, eq. 6)
+                      (and Adam, which the same passage names as the alternative)
   * partitions        stacks of consecutive layers (sub-modules)    (Layer-wise Partitioning and Merging)
   * cost              additive over the F_{i,j}, B_{i,j} operations (Cost Model, eq. 10)
   * schedules         locked F_1..F_n then B_n..B_1; overlapped F/B of different micro-batches,
@@ -261,6 +262,27 @@ def sgd_momentum(params, grads, momentum, lr, mu, first=0, last=None):
             if k in p:
                 momentum[i][k] = mu * momentum[i][k] + grads[i][k]
                 p[k] = p[k] - lr * momentum[i][k]
+
+
+def adam(params, grads, m1, m2, lr, beta1, beta2, eps, t, first=0, last=None):
+    """The other update rule the Problem Statement names beside SGD (it prints only SGD's formula, eq. 6): Adam as
+    published by Kingma and Ba, step t = 1, 2, ... for the trainable tensors of layers [first,last), in place.
+
+        m1 <- beta1*m1 + (1-beta1)*g          m2 <- beta2*m2 + (1-beta2)*g*g
+        p  <- p - lr * (m1 / (1-beta1^t)) / (sqrt(m2 / (1-beta2^t)) + eps)
+
+    No weight decay, no AMSGrad.  The frozen per-channel scale 's' is never updated.
+    """
+    c1, c2 = 1.0 - beta1 ** t, 1.0 - beta2 ** t
+    for i, p in params.items():
+        if i < first or (last is not None and i >= last):
+            continue
+        for k in ("W", "b"):
+            if k in p:
+                g = grads[i][k]
+                m1[i][k] = beta1 * m1[i][k] + (1.0 - beta1) * g
+                m2[i][k] = beta2 * m2[i][k] + (1.0 - beta2) * g * g
+                p[k] = p[k] - lr * (m1[i][k] / c1) / (np.sqrt(m2[i][k] / c2) + eps)
 
 
 # --------------------------------------------------------------------------- schedules

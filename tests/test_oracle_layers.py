@@ -282,3 +282,39 @@ def test_round_bf16_pins():
     for t, v in stash.items():
         if t != "dlogits":
             assert np.all((np.asarray(v).astype(np.float32).view(np.uint32) & 0xFFFF) == 0), t
+
+
+def test_adam_pins():
+    """Adam against what its definition fixes: the first step from a zero state moves every element by
+    lr * g / (|g| + eps) whatever its size; under a constant gradient the bias-corrected moments are exactly g
+    and g*g at every step, so T steps move by T times that; a zero gradient moves nothing; and a hand-computed
+    second step with a different gradient."""
+    rng_ = np.random.default_rng(3)
+    g = rng_.standard_normal((4, 3, 2, 2)) * np.array([1e-3, 1.0, 50.0])[None, :, None, None]
+    p0 = rng_.standard_normal(g.shape)
+    lr, b1, b2, eps = 0.01, 0.9, 0.999, 1e-8
+    params, m1, m2 = {0: {"W": p0.copy()}}, {0: {"W": np.zeros_like(g)}}, {0: {"W": np.zeros_like(g)}}
+    orc.adam(params, {0: {"W": g}}, m1, m2, lr, b1, b2, eps, 1)
+    step = lr * g / (np.abs(g) + eps)
+    np.testing.assert_allclose(params[0]["W"], p0 - step, rtol=0, atol=1e-15)
+    for t in range(2, 8):                      # constant gradient
+        orc.adam(params, {0: {"W": g}}, m1, m2, lr, b1, b2, eps, t)
+        np.testing.assert_allclose(params[0]["W"], p0 - t * step, rtol=0, atol=1e-12)
+        np.testing.assert_allclose(m1[0]["W"] / (1 - b1 ** t), g, rtol=1e-12)
+        np.testing.assert_allclose(m2[0]["W"] / (1 - b2 ** t), g * g, rtol=1e-12)
+    # a second step with another gradient, written out element by element
+    params, m1, m2 = {0: {"W": np.array([1.0])}}, {0: {"W": np.zeros(1)}}, {0: {"W": np.zeros(1)}}
+    orc.adam(params, {0: {"W": np.array([2.0])}}, m1, m2, 0.1, 0.5, 0.75, 0.0, 1)      # m1 = 1, m2 = 1: p = 1 - 0.1
+    orc.adam(params, {0: {"W": np.array([-4.0])}}, m1, m2, 0.1, 0.5, 0.75, 0.0, 2)
+    # m1 = 0.5*1 + 0.5*(-4) = -1.5 -> /0.75 = -2 ; m2 = 0.75*1 + 0.25*16 = 4.75 -> /0.4375 ; p = 0.9 + 0.1*2/sqrt(4.75/0.4375)
+    np.testing.assert_allclose(params[0]["W"], [0.9 + 0.2 / np.sqrt(4.75 / 0.4375)], rtol=1e-14)
+    # zero gradient from a zero state: nothing moves (0 / (0 + eps)); the frozen scale and other layers are left alone
+    params = {0: {"W": p0.copy(), "s": np.ones(3)}, 1: {"W": p0.copy()}}
+    z = {i: {"W": np.zeros_like(g)} for i in (0, 1)}
+    m1, m2 = {i: {"W": np.zeros_like(g)} for i in (0, 1)}, {i: {"W": np.zeros_like(g)} for i in (0, 1)}
+    orc.adam(params, z, m1, m2, lr, b1, b2, eps, 1)
+    np.testing.assert_array_equal(params[0]["W"], p0)
+    orc.adam(params, {0: {"W": g}, 1: {"W": g}}, m1, m2, lr, b1, b2, eps, 1, first=1, last=2)
+    np.testing.assert_array_equal(params[0]["W"], p0)
+    np.testing.assert_array_equal(params[0]["s"], np.ones(3))
+    assert not np.array_equal(params[1]["W"], p0)
