@@ -214,6 +214,16 @@ int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y, const voi
 int32_t lpm_stage_update(lpm_stage* s, float* params, void* lowp, float* grads, float* momentum,
                          float lr, float mu, int32_t zero_grads, void* stream);
 
+/* U_z with Adam (Kingma and Ba), the update rule the problem statement names beside SGD (it prints only SGD's,
+ * eq. 6):  m1 <- beta1*m1 + (1-beta1)*g;  m2 <- beta2*m2 + (1-beta2)*g*g;
+ *          p <- p - lr * (m1 / (1-beta1^step)) / (sqrt(m2 / (1-beta2^step)) + eps),   step = 1, 2, ...
+ * m1, m2: two device buffers laid out like momentum (momentum_bytes each), zero before the first step.
+ * Refreshes the low-precision copies like lpm_stage_update; the schedules keep calling that one.
+ * Errors: LPM_EINVAL (also step < 1, beta outside [0, 1), eps < 0), LPM_EALIGN, LPM_EHIP. */
+int32_t lpm_stage_update_adam(lpm_stage* s, float* params, void* lowp, float* grads, float* m1, float* m2,
+                              float lr, float beta1, float beta2, float eps, int32_t step, int32_t zero_grads,
+                              void* stream);
+
 /* Device buffers of one stage as used by a schedule. */
 #define LPM_MAX_WINDOW 4
 typedef struct lpm_stage_buffers {

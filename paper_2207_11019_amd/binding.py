@@ -71,6 +71,8 @@ lib.lpm_stage_sync_lowp.argtypes = [_vp, _vp, _vp, _vp]
 lib.lpm_stage_forward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, C.c_float, _vp]
 lib.lpm_stage_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]
 lib.lpm_stage_update.argtypes = [_vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _i32, _vp]
+lib.lpm_stage_update_adam.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, C.c_float, C.c_float, _i32, _i32, _vp]
+lib.lpm_stage_update_adam.restype = C.c_int32
 lib.lpm_schedule_create.argtypes = [C.POINTER(_vp), _i32, _i32, _i32, C.POINTER(_vp)]
 lib.lpm_schedule_destroy.argtypes = [_vp]
 lib.lpm_schedule_cut_fused.argtypes = [_vp, _i32]
@@ -309,6 +311,11 @@ class Stage:
     def update(self, params, lowp, grads, momentum, lr, mu, zero_grads=False, stream=None):
         _check(lib.lpm_stage_update(self.h, _ptr(params), _ptr(lowp), _ptr(grads), _ptr(momentum), lr, mu,
                                     int(zero_grads), _stream(stream)))
+
+
+    def update_adam(self, params, lowp, grads, m1, m2, lr, beta1, beta2, eps, step, zero_grads=False, stream=None):
+        _check(lib.lpm_stage_update_adam(self.h, _ptr(params), _ptr(lowp), _ptr(grads), _ptr(m1), _ptr(m2), lr, beta1, beta2,
+                                         eps, int(step), int(zero_grads), _stream(stream)))
 
 
 class Schedule:

@@ -486,6 +486,39 @@ hipError_t launch_sgd(const float* p_in, float* p, uint16_t* lowp, float* g, flo
     return hipGetLastError();
 }
 
+// Adam update (Kingma & Ba), the alternative to eq. 6 that the paper's problem statement names: the same streaming
+// shape as sgd_kernel with two moment buffers.  inv_c1 = 1 / (1 - beta1^t), inv_c2 = 1 / (1 - beta2^t).
+__global__ void __launch_bounds__(256) adam_kernel(float4* p, uint2* __restrict__ lowp, float4* __restrict__ g, float4* __restrict__ m1,
+                                                   float4* __restrict__ m2, size_t n4, float lr, float beta1, float beta2,
+                                                   float eps, float inv_c1, float inv_c2, int zero_g) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n4) return;
+    const float4 gg = ld_stream(&g[i]);
+    float4 a = ld_stream(&m1[i]), b = ld_stream(&m2[i]), pp = ld_stream(&p[i]);
+    const float gv[4] = {gg.x, gg.y, gg.z, gg.w};
+    float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w}, pv[4] = {pp.x, pp.y, pp.z, pp.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        av[k] = beta1 * av[k] + (1.f - beta1) * gv[k];
+        bv[k] = beta2 * bv[k] + (1.f - beta2) * gv[k] * gv[k];
+        pv[k] -= lr * (av[k] * inv_c1) / (sqrtf(bv[k] * inv_c2) + eps);
+    }
+    st_stream(&m1[i], make_float4(av[0], av[1], av[2], av[3]));
+    st_stream(&m2[i], make_float4(bv[0], bv[1], bv[2], bv[3]));
+    st_stream(&p[i], make_float4(pv[0], pv[1], pv[2], pv[3]));
+    if (lowp) st_stream(&lowp[i], make_uint2(pack_bf16x2(pv[0], pv[1]), pack_bf16x2(pv[2], pv[3])));
+    if (zero_g) st_stream(&g[i], make_float4(0.f, 0.f, 0.f, 0.f));
+}
+
+hipError_t launch_adam(float* p, uint16_t* lowp, float* g, float* m1, float* m2, size_t n, float lr, float beta1, float beta2,
+                       float eps, float inv_c1, float inv_c2, int zero_g, hipStream_t s) {
+    const size_t n4 = n / 4;
+    if (n4 == 0) return hipSuccess;
+    hipLaunchKernelGGL(adam_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, (float4*)p, (uint2*)lowp, (float4*)g, (float4*)m1,
+                       (float4*)m2, n4, lr, beta1, beta2, eps, inv_c1, inv_c2, zero_g);
+    return hipGetLastError();
+}
+
 __global__ void __launch_bounds__(256) f32_to_bf16_kernel(const float4* __restrict__ src, uint2* __restrict__ dst, size_t n4) {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n4) return;

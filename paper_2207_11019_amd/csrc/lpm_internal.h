@@ -125,6 +125,8 @@ hipError_t launch_softmax_ce(int dtype, int32_t m, int32_t C, const void* logits
 // v = mu*v + g; p = p_in - lr*v (p_in may be p); lowp[i] = bf16(p[i]) (lowp may be NULL); optionally g = 0.   n % 4 == 0
 hipError_t launch_sgd(const float* p_in, float* p, uint16_t* lowp, float* g, float* v, size_t n, float lr, float mu, int zero_g,
                       hipStream_t st);
+hipError_t launch_adam(float* p, uint16_t* lowp, float* g, float* m1, float* m2, size_t n, float lr, float beta1, float beta2,
+                       float eps, float inv_c1, float inv_c2, int zero_g, hipStream_t st);
 hipError_t launch_f32_to_bf16(const float* src, uint16_t* dst, size_t n, hipStream_t st);
 // dst[ci][kh][kw][co] = bf16(src[co][kh][kw][ci]) for a list of weight tensors, one launch per LPM_TRANSPOSE_BATCH of them
 struct TransposeDesc { const float* src; uint16_t* dst; int32_t Cout, KK, Cin; };

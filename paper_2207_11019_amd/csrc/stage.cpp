@@ -10,6 +10,7 @@
 #include <new>
 
 #include "stage.h"
+#include <cmath>
 
 using namespace lpm;
 
@@ -657,5 +658,25 @@ int32_t lpm_stage_update_to(lpm_stage* s, const float* params_in, float* params,
     }
     LPM_HIP(launch_sgd(params_in, params, (uint16_t*)lowp, grads, momentum, s->n_trainable, lr_, mu, zero_grads, st));
     LPM_HIP(transpose_copies(s, params, lowp, st));
+    return LPM_OK;
+}
+
+extern "C" int32_t lpm_stage_update_adam(lpm_stage* s, float* params, void* lowp, float* grads, float* m1, float* m2,
+                                         float lr_, float beta1, float beta2, float eps, int32_t step, int32_t zero_grads,
+                                         void* stream) {
+    if (!s || !params || !grads || !m1 || !m2) return fail(LPM_EINVAL, "NULL argument");
+    if (s->dtype == LPM_BF16 && !lowp) return fail(LPM_EINVAL, "lowp is NULL for a bf16 stage");
+    if (step < 1 || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f))
+        return fail(LPM_EINVAL, "Adam needs step >= 1, 0 <= beta < 1 and eps >= 0");
+    if (misaligned(params) || misaligned(grads) || misaligned(m1) || misaligned(m2) || (lowp && misaligned(lowp)))
+        return fail(LPM_EALIGN, "device buffers must be 256-byte aligned");
+    if (s->n_trainable == 0) return LPM_OK;
+    // bias corrections in double on the host: 1 - beta^t loses digits in float for beta close to 1
+    const float inv_c1 = (float)(1.0 / (1.0 - std::pow((double)beta1, (double)step)));
+    const float inv_c2 = (float)(1.0 / (1.0 - std::pow((double)beta2, (double)step)));
+    hipStream_t st = (hipStream_t)stream;
+    LPM_HIP(launch_adam(params, s->dtype == LPM_BF16 ? (uint16_t*)lowp : nullptr, grads, m1, m2, s->n_trainable, lr_, beta1, beta2,
+                        eps, inv_c1, inv_c2, zero_grads, st));
+    if (s->dtype == LPM_BF16) LPM_HIP(transpose_copies(s, params, lowp, st));
     return LPM_OK;
 }

@@ -3,6 +3,8 @@ import numpy as np
 import pytest
 
 import workloads as wl
+from workloads import rng
+from oracle import lpm_oracle as orc
 from harness import oracle_step, gpu_step, compare, rel_err, l2_err, stage_backward_isolated
 
 pytestmark = pytest.mark.gpu
@@ -161,6 +163,58 @@ def test_overlapped_on_changing_streams(lpm):
             for key in a[i]:
                 np.testing.assert_array_equal(a[i][key], b[i][key])
         assert ref.loss_value() == net.loss_value()
+
+
+@pytest.mark.parametrize("dtype", [0, 1], ids=["f32", "bf16"])
+def test_adam_update(lpm, dtype):
+    """lpm_stage_update_adam against the oracle's Adam: three steps with a new gradient each, every stage of a
+    small network; for bf16 the low-precision copy must be the rounded new weights."""
+    import copy
+    import torch
+    layers = wl.tiny_vgg()
+    starts = _starts(layers, 2)
+    params, _ = wl.make_params(layers, 21, bf16=bool(dtype), bias_std=0.05, momentum_std=0.0)
+    net = lpm.Net(layers, starts, 2, 4, dtype)
+    zeros = {i: {k: np.zeros_like(v) for k, v in p.items() if k != "s"} for i, p in params.items()}
+    net.load_params(params, zeros)                      # the momentum buffer serves as the first moment
+    second = [torch.zeros_like(b["momentum"]) for b in net.bufs]
+    ref_p, ref_m1, ref_m2 = copy.deepcopy(params), copy.deepcopy(zeros), copy.deepcopy(zeros)
+    # the C ABI takes the hyper-parameters as floats: both sides get the float values (1 - 0.999 differs from
+    # 1 - float(0.999) by 1.3e-5 of itself, which would show in the second moment)
+    lr, b1, b2, eps = (float(np.float32(v)) for v in (0.01, 0.9, 0.999, 1e-8))
+    for t in (1, 2, 3):
+        grads = {i: {k: rng.normal(100 + t, 10 * i + j, v.shape, 0.0, 10.0 ** (t - 3)).astype(np.float32).astype(np.float64)
+                     for j, (k, v) in enumerate(p.items()) if k != "s"} for i, p in params.items()}
+        net._write("grads", grads, ("W", "b"))
+        for z, st in enumerate(net.stages):
+            b = net.bufs[z]
+            st.update_adam(b["params"], b["lowp"], b["grads"], b["momentum"], second[z], lr, b1, b2, eps, t)
+        torch.cuda.synchronize()
+        orc.adam(ref_p, grads, ref_m1, ref_m2, lr, b1, b2, eps, t)
+        got_p, got_m1 = net.read_params(), net.read_momentum()
+        for i in ref_p:
+            for k in ("W", "b"):
+                if k in ref_p[i]:
+                    assert rel_err(got_p[i][k], ref_p[i][k]) <= 1e-5, (t, i, k)
+                    assert rel_err(got_m1[i][k], ref_m1[i][k]) <= 1e-5, (t, i, k)
+    # second moments: read them through the same unpacking by lending the buffers to the net
+    for z, b in enumerate(net.bufs):
+        b["momentum"], second[z] = second[z], b["momentum"]
+    got_m2 = net.read_momentum()
+    for i in ref_m2:
+        for k in ref_m2[i]:
+            assert rel_err(got_m2[i][k], ref_m2[i][k]) <= 1e-5, (i, k)
+    if dtype == 1:
+        for z, st in enumerate(net.stages):
+            n = st.param_bytes // 4
+            p32 = net.bufs[z]["params"].view(torch.float32)[:n]
+            low = net.bufs[z]["lowp"].view(torch.bfloat16)[:n]
+            # the mirrored region covers the trainable parameters, which come first
+            off, cnt = st.param_offset(st.first, 0)
+            assert torch.equal(low[off:off + cnt], p32[off:off + cnt].to(torch.bfloat16))
+    with pytest.raises(lpm.LpmError):
+        net.stages[0].update_adam(net.bufs[0]["params"], net.bufs[0]["lowp"], net.bufs[0]["grads"], net.bufs[0]["momentum"],
+                                  second[0], lr, b1, b2, eps, 0)
 
 
 def test_two_steps_with_momentum(lpm):
