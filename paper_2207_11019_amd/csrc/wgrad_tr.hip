@@ -275,12 +275,18 @@ static TrPlan plan_wgrad_tr(const ConvGeom& g) {
     const bool s33 = g.Kh == 3 && g.Kw == 3 && g.stride == 1;
     const int64_t out_bytes = ((int64_t)g.Cout * g.K() + g.Cout) * 4;
     // a filter row per block once both channel counts give several tiles (the shared halo tile then cuts the L2
-    // traffic that bounds the single-tap blocks); the patch range is split to about 1.5 blocks per CU, keeping
-    // at least eight patches per block and the partial sums (written and read once) below 64 MiB
+    // traffic that bounds the single-tap blocks); the patch range is split to about one block per CU, keeping
+    // at least eight patches per block and the partial sums (written and read once) below 64 MiB.  (Alone on the
+    // GPU a weight gradient is 3-6 % faster at 1.5 blocks per CU; beside the forward and data-gradient kernels of
+    // an overlapped step the smaller partial sums win: -1 to -2.6 % per step on the five workloads.)
     const int64_t macs = g.rows_out() * g.Cout * g.K();
     int taps = (s33 && g.Cin >= 128 && g.Cout >= 128 && macs >= (int64_t)1000000000) ? 3 : 1;
     const int64_t base = (int64_t)pl.co_tiles * pl.ci_tiles * (KhKw / taps);
-    int64_t sp = std::max<int64_t>(1, 384 / base);
+    int64_t target = 256;
+#ifdef LPM_TUNE
+    if (const char* e = getenv("LPM_T_TRBLOCKS")) target = std::max(1, atoi(e));
+#endif
+    int64_t sp = std::max<int64_t>(1, target / base);
     sp = std::min<int64_t>(sp, std::max(1, pl.kt_total / 8));
     sp = std::min<int64_t>(sp, std::max<int64_t>(1, (64ll << 20) / out_bytes));
     int best_taps = taps, best_s = (int)sp;
