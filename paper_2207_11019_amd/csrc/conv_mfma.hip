@@ -580,7 +580,11 @@ static IgemmPlan plan_igemm(int64_t M, int N, int Ktot, int ci) {
     int s = std::max(1, (kt64 + kpb / 2) / kpb);
     // no more blocks than fill the chip once -- except for a single row of tiles (a small-batch FC layer), which
     // only streams weights and needs many blocks in flight to cover the memory latency
-    const int64_t cap = (M <= 64 ? 1024 : 320) / tiles;
+    int64_t cap_blocks = 320;
+#ifdef LPM_TUNE
+    if (const char* e = getenv("LPM_T_CAP")) cap_blocks = std::max(1, atoi(e));
+#endif
+    const int64_t cap = (M <= 64 ? 1024 : cap_blocks) / tiles;
     s = (int)std::min<int64_t>(s, std::max<int64_t>(1, cap));
     s = std::min(s, pl.kt_total);
     pl.splits = std::max(1, s);

@@ -262,6 +262,37 @@ __global__ void __launch_bounds__(256) epilogue_bwd_bf16x8(int64_t rows, int C, 
     }
 }
 
+// The same without a bias gradient: nothing ties a thread to a channel column, so thread i simply takes the i-th
+// 16-byte chunk of the tensor -- a wavefront covers 1 KiB of consecutive memory, and small tensors still spread over
+// many blocks (ResNet-18/CIFAR: 6.8 -> about 3.5 us per launch, twelve launches per micro-batch on the data-phase chain).
+__global__ void __launch_bounds__(256) epilogue_bwd_flat_bf16x8(unsigned chunks, unsigned C8, const uint4* __restrict__ dy,
+                                                                const uint4* __restrict__ y, const float* __restrict__ scale,
+                                                                uint4* __restrict__ dz, uint4* __restrict__ gadd, int gadd_acc) {
+    const unsigned i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= chunks) return;
+    const uint4 g4 = dy[i];
+    const uint4 y4 = y ? y[i] : make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
+    const uint4 a4 = (gadd && gadd_acc) ? gadd[i] : make_uint4(0, 0, 0, 0);
+    float sc[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
+    if (scale) {                                   // two 16-byte loads: the chunk's first channel is a multiple of 8
+        const float* sp = scale + (i % C8) * 8u;
+        const float4 lo = *reinterpret_cast<const float4*>(sp), hi = *reinterpret_cast<const float4*>(sp + 4);
+        sc[0] = lo.x; sc[1] = lo.y; sc[2] = lo.z; sc[3] = lo.w; sc[4] = hi.x; sc[5] = hi.y; sc[6] = hi.z; sc[7] = hi.w;
+    }
+    const uint32_t gw[4] = {g4.x, g4.y, g4.z, g4.w}, yw[4] = {y4.x, y4.y, y4.z, y4.w}, aw[4] = {a4.x, a4.y, a4.z, a4.w};
+    uint32_t zo[4], go[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        float g0 = bf2f((uint16_t)(gw[k] & 0xffffu)), g1 = bf2f((uint16_t)(gw[k] >> 16));
+        if (!(bf2f((uint16_t)(yw[k] & 0xffffu)) > 0.f)) g0 = 0.f;
+        if (!(bf2f((uint16_t)(yw[k] >> 16)) > 0.f)) g1 = 0.f;
+        zo[k] = pack_bf16x2(g0 * sc[2 * k], g1 * sc[2 * k + 1]);
+        go[k] = pack_bf16x2(g0 + bf2f((uint16_t)(aw[k] & 0xffffu)), g1 + bf2f((uint16_t)(aw[k] >> 16)));
+    }
+    if (dz) dz[i] = make_uint4(zo[0], zo[1], zo[2], zo[3]);
+    if (gadd) gadd[i] = make_uint4(go[0], go[1], go[2], go[3]);
+}
+
 // db[c] (+)= sum over the row blocks' partials, added in block order; 4 lanes per channel
 __global__ void __launch_bounds__(256) bias_reduce(const float* __restrict__ part, float* __restrict__ db, int C,
                                                    int nblocks, int accumulate) {
@@ -288,6 +319,12 @@ hipError_t launch_epilogue_bwd(int dtype, int64_t rows, int32_t C, const void* d
                                void* dz, void* gadd, int gadd_acc, float* dbias, int db_acc, void* ws, hipStream_t s) {
     const unsigned rb = nblk(rows, EPI_ROWS);
     float* part = dbias ? (float*)ws : nullptr;
+    if (dtype == LPM_BF16 && (C & 7) == 0 && !dbias && rows * (C >> 3) < ((int64_t)1 << 31)) {
+        const unsigned chunks = (unsigned)(rows * (C >> 3));
+        hipLaunchKernelGGL(epilogue_bwd_flat_bf16x8, dim3((chunks + 255u) / 256u), dim3(256), 0, s, chunks, (unsigned)(C >> 3),
+                           (const uint4*)dy, (const uint4*)y, scale, (uint4*)dz, (uint4*)gadd, gadd_acc);
+        return hipGetLastError();
+    }
     if (dtype == LPM_BF16 && (C & 7) == 0) {
         hipLaunchKernelGGL(epilogue_bwd_bf16x8, dim3(nblk(C, 64), rb), dim3(256), 0, s, rows, C, (const uint4*)dy,
                            (const uint4*)y, scale, (uint4*)dz, (uint4*)gadd, gadd_acc, part);
