@@ -454,29 +454,57 @@ __device__ inline float wave_sum(float v) {
     return v;
 }
 
+// One block of 16 wavefronts, a wavefront per row at a time; a row of up to 1024 classes is read once and kept in
+// registers (the kernel closes every forward chain, so its latency counts: three dependent passes over global memory
+// per row and four wavefronts made it 13 us for 32 rows of 10 classes).  The loss is summed in row order by one thread.
 template <typename T>
-__global__ void __launch_bounds__(256) softmax_ce_kernel(int m, int C, const T* __restrict__ z,
-                                                         const int32_t* __restrict__ labels, float loss_scale,
-                                                         T* __restrict__ dz, float* __restrict__ loss_accum) {
+__global__ void __launch_bounds__(1024) softmax_ce_kernel(int m, int C, const T* __restrict__ z,
+                                                          const int32_t* __restrict__ labels, float loss_scale,
+                                                          T* __restrict__ dz, float* __restrict__ loss_accum) {
+    constexpr int KEEP = 16;                 // classes per lane held in registers
     __shared__ float rowloss[256];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool cached = C <= 64 * KEEP;
     float total = 0.f;
     for (int base = 0; base < m; base += 256) {
         const int nrow = min(256, m - base);
-        for (int r = wave; r < nrow; r += 4) {
+        for (int r = wave; r < nrow; r += 16) {
             const T* zr = z + (int64_t)(base + r) * C;
             T* dr = dz + (int64_t)(base + r) * C;
+            float v[KEEP];
             float mx = -INFINITY;
-            for (int c = lane; c < C; c += 64) mx = fmaxf(mx, ld(zr, c));
+            if (cached) {
+#pragma unroll
+                for (int k = 0; k < KEEP; ++k) {
+                    const int c = lane + 64 * k;
+                    v[k] = c < C ? ld(zr, c) : -INFINITY;
+                    mx = fmaxf(mx, v[k]);
+                }
+            } else {
+                for (int c = lane; c < C; c += 64) mx = fmaxf(mx, ld(zr, c));
+            }
             mx = wave_max(mx);
             float se = 0.f;
-            for (int c = lane; c < C; c += 64) se += expf(ld(zr, c) - mx);
+            if (cached) {
+#pragma unroll
+                for (int k = 0; k < KEEP; ++k) { v[k] = expf(v[k] - mx); se += v[k]; }      // exp(-inf) = 0 past the end
+            } else {
+                for (int c = lane; c < C; c += 64) se += expf(ld(zr, c) - mx);
+            }
             se = wave_sum(se);
             const int lab = labels[base + r];
             const float inv = 1.f / se;
-            for (int c = lane; c < C; c += 64) {
-                const float p = expf(ld(zr, c) - mx) * inv;
-                st(dr, c, (p - (c == lab ? 1.f : 0.f)) * loss_scale);
+            if (cached) {
+#pragma unroll
+                for (int k = 0; k < KEEP; ++k) {
+                    const int c = lane + 64 * k;
+                    if (c < C) st(dr, c, (v[k] * inv - (c == lab ? 1.f : 0.f)) * loss_scale);
+                }
+            } else {
+                for (int c = lane; c < C; c += 64) {
+                    const float p = expf(ld(zr, c) - mx) * inv;
+                    st(dr, c, (p - (c == lab ? 1.f : 0.f)) * loss_scale);
+                }
             }
             if (lane == 0) rowloss[r] = logf(se) - (ld(zr, lab) - mx);
         }
@@ -490,7 +518,7 @@ __global__ void __launch_bounds__(256) softmax_ce_kernel(int m, int C, const T* 
 
 hipError_t launch_softmax_ce(int dtype, int32_t m, int32_t C, const void* logits, const int32_t* labels, float loss_scale,
                              void* dlogits, float* loss_accum, hipStream_t s) {
-    LPM_DISPATCH(dtype, hipLaunchKernelGGL(softmax_ce_kernel<T>, dim3(1), dim3(256), 0, s, m, C, (const T*)logits, labels,
+    LPM_DISPATCH(dtype, hipLaunchKernelGGL(softmax_ce_kernel<T>, dim3(1), dim3(1024), 0, s, m, C, (const T*)logits, labels,
                                            loss_scale, (T*)dlogits, loss_accum));
     return hipGetLastError();
 }
