@@ -358,7 +358,7 @@ int32_t pick_weight_streams(lpm_schedule* s, hipStream_t sf, hipStream_t sb) {
 }
 
 // OVERLAPPED, three workers: 0 enqueues the forward chains on sf, 1 the data phases of the backward chains
-// on sb, 2 the weight phases and the updates on the weight stream (stage 0's side stream).
+// on sb, 2 the weight phases and the updates on the weight streams (ov_w, and ov_w0 for stage 0; see pick_weight_streams).
 // ev_f[j*Z+Z-1]: forward chain j done; ev_b[j*Z+z]: data phase of B_{z,j} done; ev_w[j*Z]: micro-batch j done.
 int32_t overlapped_role(lpm_schedule* s, const RunArgs& a, int32_t role, uint64_t epoch) {
     const int32_t Z = s->Z, M = s->M, W = s->window;

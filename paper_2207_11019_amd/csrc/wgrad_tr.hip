@@ -1,4 +1,4 @@
-// Weight gradient (eq. 8) of convolutions whose output images are at least 8x8 pixels: bf16 MFMA, fp32 accumulation.
+// Weight gradient (eq. 8) of convolutions whose output images are at least 7x7 pixels: bf16 MFMA, fp32 accumulation.
 //
 //   dW[co][kh][kw][ci] = sum over output pixels q of dz[q][co] * x[pixel(q, kh, kw)][ci]
 //
