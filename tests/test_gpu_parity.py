@@ -37,6 +37,8 @@ CASES = [
     ("tiny_fc_bf16_one_stage", wl.tiny_fc, 6, 3, 1, 1),
     # 64-channel convolutions over 4x4 and 2x2 images: the same for convolutions
     ("tiny_wide_bf16", wl.tiny_wide, 8, 4, 2, 1),
+    # a split forward reduction into 72 channels whose second kernel also pools
+    ("tiny_deep_pool_bf16", wl.tiny_deep_pool, 16, 2, 1, 1),
 ]
 
 

@@ -211,6 +211,15 @@ def tiny_wide():
     return b.finish()
 
 
+def tiny_deep_pool():
+    """A 512 -> 72 channel 3x3 convolution over 4x4 images followed by a pooling: a long reduction (split over blocks)
+    into a channel count that is not a multiple of the 64-channel tile, then the pooling its second kernel performs."""
+    b = _Builder(3, 4, 4)
+    b.conv(512, 3, pad=1); b.conv(72, 3, pad=1); b.pool(); b.conv(40, 3, pad=1); b.gap()
+    b.fc(5, relu=False); b.loss()
+    return b.finish()
+
+
 def tiny_resnet(hw=8, widths=(4, 6), n_classes=5):
     """Stem + one identity block + one strided projection block + GAP + FC."""
     return resnet18_cifar(widths=widths, blocks=1, hw=hw, n_classes=n_classes)
