@@ -67,6 +67,17 @@ def test_other_windows(lpm, window, mode):
         compare(net, layers, starts, M, 0, o, window=window)
 
 
+@pytest.mark.parametrize("mode", [0, 1, 2, 17], ids=["locked", "overlapped", "pipelined", "overlapped_graph"])
+def test_single_microbatch(lpm, mode):
+    """M = 1: nothing to overlap and nothing to accumulate; every schedule is plain backpropagation on the batch."""
+    layers = wl.tiny_vgg()
+    for Z in (1, 3):
+        starts = _starts(layers, Z)
+        o = oracle_step(layers, starts, 4, 1, True, seed=41, lr=0.05, mu=0.9)
+        net = gpu_step(lpm, layers, starts, 4, 1, 1, o, 0.05, 0.9, mode)
+        compare(net, layers, starts, 1, 1, o)
+
+
 def test_stage_without_parameters(lpm):
     """A partition made of a pooling layer alone: nothing to update, no weight gradient, gradients pass through."""
     layers = wl.tiny_vgg()
