@@ -24,7 +24,7 @@ bool mfma_fwd_pools(const ConvGeom& g);
 hipError_t mfma_conv_fwd(const ConvGeom& g, const void* x, const void* w, const float* scale, const float* bias,
                          const void* add, int relu, void* y, void* ws, hipStream_t st, void* pool_y);
 hipError_t mfma_conv_dgrad(const ConvGeom& g, const void* dz, const void* wt, void* dx, int accumulate, const void* mask,
-                           const float* mscale, void* ws, hipStream_t st, const UnpoolDesc* unpool);
+                           const float* mscale, void* ws, hipStream_t st, const UnpoolDesc* unpool, const DgradSide* side);
 hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* bscale,
                            int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred);
 
@@ -89,12 +89,16 @@ bool dgrad_can_unpool(int dtype, const ConvGeom& g) {
            (int64_t)g.rows_in() * g.Cin <= ((int64_t)1 << 20);
 }
 
+// the MFMA data gradient can take over the epilogue backward of a layer with a shortcut (DgradSide)
+bool dgrad_has_side(int dtype, const ConvGeom& g) { return dgrad_uses_wt(dtype, g); }
+
 hipError_t launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dz, const void* w, const void* wt, void* dx,
                              int accumulate, const void* mask, const float* mscale, void* ws, hipStream_t st,
-                             const UnpoolDesc* unpool) {
+                             const UnpoolDesc* unpool, const DgradSide* side) {
     if (unpool && !(dgrad_can_unpool(dtype, g) && wt)) return hipErrorInvalidValue;      // callers ask dgrad_can_unpool first
+    if (side && !(dgrad_has_side(dtype, g) && wt)) return hipErrorInvalidValue;          // ... and dgrad_has_side
     if (dtype == LPM_BF16 && fc_skinny_ok(g)) return fc_dgrad(g, dz, w, dx, accumulate, mask, mscale, ws, st);
-    if (dtype == LPM_BF16 && wt && mfma_dgrad_ok(g)) return mfma_conv_dgrad(g, dz, wt, dx, accumulate, mask, mscale, ws, st, unpool);
+    if (dtype == LPM_BF16 && wt && mfma_dgrad_ok(g)) return mfma_conv_dgrad(g, dz, wt, dx, accumulate, mask, mscale, ws, st, unpool, side);
     return conv_dgrad_generic_launch(dtype, g, dz, w, dx, accumulate, mask, mscale, st);
 }
 

@@ -67,9 +67,15 @@ bool fwd_can_pool(int dtype, const ConvGeom& g);
 // (found in pool_x, the pooling input [m][2H][2W][Cin]) and writes the four window positions of dst (same shape):
 // dst (+)= route(dx) * [max > 0 if mask] * mscale_c.  dx, accumulate, mask, mscale of the plain form are then unused.
 struct UnpoolDesc { const void* pool_x; void* dst; int accumulate; int mask; const float* mscale; };
+// side (may be NULL; only when dgrad_has_side): this data gradient is the last contribution to the gradient of a tensor
+// y = relu(scale*z + bias + shortcut) and performs that layer's epilogue backward on the way:
+//   v = conv_transpose(dz, w) + earlier (the contributions already there, may be NULL);  m = v * [mask > 0];
+//   dx = m * mscale_c (the producer's dz);   shortcut (+)= m (the gradient of the producer's shortcut tensor, may be NULL)
+struct DgradSide { const void* earlier; void* shortcut; int shortcut_acc; };
 hipError_t launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dz, const void* w, const void* wt,
                              void* dx, int accumulate, const void* mask, const float* mscale, void* ws, hipStream_t st,
-                             const UnpoolDesc* unpool = nullptr);
+                             const UnpoolDesc* unpool = nullptr, const DgradSide* side = nullptr);
+bool dgrad_has_side(int dtype, const ConvGeom& g);
 bool dgrad_can_unpool(int dtype, const ConvGeom& g);
 // dw (+)= sum over pixels of dz (x) x         ws: split-reduction partials (wgrad_ws_bytes)
 // dbias (may be NULL, only when wgrad_fuses_bias): dbias (+)= (sum over pixels of dz) / bscale_c

@@ -113,16 +113,26 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
     for (int32_t i = first; i < last; ++i) {
         LayerRt& lr = s->Ly(i);
         const lpm_layer& l = lr.d;
-        if (dtype != LPM_BF16 || !has_weights(l) || !(l.flags & (LPM_RELU | LPM_SCALE)) || l.add_src != LPM_NONE) continue;
+        if (dtype != LPM_BF16 || !has_weights(l) || !(l.flags & (LPM_RELU | LPM_SCALE))) continue;
         if (i == s->t_out) continue;           // its gradient arrives from outside the stage
-        int n_src = 0, n_other = 0;
+        int n_src = 0, n_other = 0, n_add = 0;
+        int32_t consumer = -1, first_add = last;
         for (int32_t j = i + 1; j < last; ++j) {
             const lpm_layer& c = s->net[j];
-            if (c.src == i) (c.kind == LPM_SOFTMAX_CE ? n_other : n_src)++;
-            if (c.add_src == i) ++n_other;
+            if (c.src == i) { (c.kind == LPM_SOFTMAX_CE ? n_other : n_src)++; consumer = j; }
+            if (c.add_src == i) { ++n_add; first_add = std::min(first_add, j); }
         }
         if (n_src != 1 || n_other != 0) continue;
         if ((l.flags & LPM_BIAS) && !wgrad_fuses_bias(dtype, lr.g)) continue;
+        if (l.add_src != LPM_NONE || n_add > 0) {
+            // Residual blocks.  The layer adds a shortcut, and / or later layers use its output as their shortcut: the
+            // single layer that reads it as its input comes first in layer order, so its data gradient is the last
+            // contribution in the backward pass, and an MFMA data gradient can add the earlier ones, mask, and write
+            // both this layer's dz and the shortcut's gradient.
+            const lpm_layer& c = s->net[(size_t)consumer];
+            if (!has_weights(c) || first_add < consumer || !dgrad_has_side(dtype, s->Ly(consumer).g)) continue;
+            lr.fused_side = true;
+        }
         lr.fused_in = true;
     }
     // Pooling-backward fusion: a 2x2 max-pooling (even input extent) whose output feeds exactly one layer, a
@@ -518,12 +528,26 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                         have[gi(q)] = 1;
                     }
                 }
+                DgradSide side{};
+                bool use_side = false;
                 if (want && lr.unpool_of < 0) {
                     if (l.src >= first && s->Ly(l.src).fused_in) {
                         const LayerRt& pr = s->Ly(l.src);
                         gsrc = gw + pr.dz_off;
                         gmask = (pr.d.flags & LPM_RELU) ? tptr(s, l.src, x, y, stash) : nullptr;
                         gmscale = pr.s_off != NO ? params + pr.s_off : nullptr;
+                        if (pr.fused_side) {
+                            // the producer sits in a residual block: what its shortcut users have already put into its output
+                            // gradient is added, and the masked sum is also the gradient of the producer's own shortcut
+                            use_side = true;
+                            side.earlier = have[gi(l.src)] ? G[gi(l.src)] : nullptr;
+                            const int32_t a = pr.d.add_src;
+                            if (a != LPM_NONE && (a >= first || dx != nullptr)) {
+                                side.shortcut = G[gi(a)];
+                                side.shortcut_acc = have[gi(a)];
+                                have[gi(a)] = 1;
+                            }
+                        }
                     } else {
                         gsrc = G[gi(l.src)];
                         gsrc_acc = have[gi(l.src)];
@@ -551,7 +575,8 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                     if (lr.unpool_of >= 0) {
                         if (do_data && unpool.dst) LPM_HIP(launch_conv_dgrad(s->dtype, lr.g, dz, w, wt, nullptr, 0, nullptr, nullptr, kws, st, &unpool));
                     } else if (do_data) {
-                        LPM_HIP(launch_conv_dgrad(s->dtype, lr.g, dz, w, wt, gsrc, gsrc_acc, gmask, gmscale, kws, st));
+                        LPM_HIP(launch_conv_dgrad(s->dtype, lr.g, dz, w, wt, gsrc, gsrc_acc, gmask, gmscale, kws, st, nullptr,
+                                                  use_side ? &side : nullptr));
                     }
                 }
                 break;

@@ -28,6 +28,8 @@ struct LayerRt {
     size_t fcs_x_off = NO, fcs_dz_off = NO;      // staging areas of a layer whose weight gradient a schedule contracts
                                                  // once per mini-batch (byte offsets in the backward scratch)
     int32_t unpool_of = -1;                      // conv/FC: index of the max-pooling layer whose backward its data gradient performs
+    bool fused_side = false;                     // fused_in, and the consumer's data gradient also adds the earlier contributions to this
+                                                 // layer's output gradient and writes the gradient of this layer's shortcut (DgradSide)
     int32_t pool_fwd = -1;                       // conv/FC: index of the max-pooling layer whose forward its own forward kernel performs
     bool pooled_fwd = false;                     // max-pooling: its forward runs inside its producer's forward kernel
     bool unpooled = false;                       // max-pooling: its backward runs inside its consumer's data gradient
