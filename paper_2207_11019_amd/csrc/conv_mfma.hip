@@ -59,6 +59,7 @@ struct IgemmArgs {
     int relu, accumulate;
     uint16_t* C2;           // data gradient: the masked, not yet scaled result also goes here (the producer's shortcut), or NULL
     int acc2;               // ... added to what C2 holds
+    const float* c2scale;   // ... times this per-channel factor (NULL: 1)
     int M, N, Ktot;
     int Hi, Wi, Ci;       // extent of the gathered tensor
     int Hr, Wr;           // extent of the row space
@@ -162,7 +163,10 @@ __device__ __forceinline__ void igemm_store(const IgemmArgs& p, const f32x16 (&a
             const float r = fmaxf(v, 0.f);
             v = relu ? r : v;
             if (MASK) v = bf2f(p.mask[o]) > 0.f ? v : 0.f;
-            if (p.C2) p.C2[o] = f2bf(p.acc2 ? v + bf2f(p.C2[o]) : v);
+            if (p.C2) {
+                const float u = p.c2scale ? v * p.c2scale[col] : v;
+                p.C2[o] = f2bf(p.acc2 ? u + bf2f(p.C2[o]) : u);
+            }
             p.C[o] = f2bf(v * ms);
         }
 }
@@ -489,7 +493,8 @@ __global__ void __launch_bounds__(256) splitk_epilogue(const float* __restrict__
                                                        const float* __restrict__ scale, const float* __restrict__ bias,
                                                        const uint16_t* __restrict__ add, int relu, int accumulate,
                                                        const uint16_t* __restrict__ mask, const float* __restrict__ mscale,
-                                                       uint16_t* __restrict__ C, uint16_t* __restrict__ C2, int acc2) {
+                                                       uint16_t* __restrict__ C, uint16_t* __restrict__ C2, int acc2,
+                                                       const float* __restrict__ c2scale) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= MN) return;
     float v = part[i];
@@ -501,7 +506,10 @@ __global__ void __launch_bounds__(256) splitk_epilogue(const float* __restrict__
     if (accumulate) v += bf2f(C[i]);
     if (relu) v = fmaxf(v, 0.f);
     if (mask && !(bf2f(mask[i]) > 0.f)) v = 0.f;
-    if (C2) C2[i] = f2bf(acc2 ? v + bf2f(C2[i]) : v);
+    if (C2) {
+        const float u = c2scale ? v * c2scale[col] : v;
+        C2[i] = f2bf(acc2 ? u + bf2f(C2[i]) : u);
+    }
     if (mscale) v *= mscale[col];
     C[i] = f2bf(v);
 }
@@ -556,7 +564,7 @@ hipError_t launch_splitk_epilogue(const float* part, int splits, int64_t MN, int
                                   const void* add, int relu, int accumulate, const void* mask, const float* mscale,
                                   void* C, hipStream_t st) {
     hipLaunchKernelGGL(splitk_epilogue, dim3((unsigned)((MN + 255) / 256)), dim3(256), 0, st, part, splits, MN, N, scale, bias,
-                       (const uint16_t*)add, relu, accumulate, (const uint16_t*)mask, mscale, (uint16_t*)C, (uint16_t*)nullptr, 0);
+                       (const uint16_t*)add, relu, accumulate, (const uint16_t*)mask, mscale, (uint16_t*)C, (uint16_t*)nullptr, 0, (const float*)nullptr);
     return hipGetLastError();
 }
 
@@ -681,7 +689,7 @@ static hipError_t run_igemm(int mode, IgemmArgs a, void* ws, hipStream_t st) {
                            pl.splits, MN, a.N, a.Hr, a.Wr, a.pool_x, a.pool_dst, a.pool_acc, a.pool_mask, a.mscale);
     else
         hipLaunchKernelGGL(splitk_epilogue, dim3((unsigned)((MN + 255) / 256)), dim3(256), 0, st, (const float*)ws, pl.splits,
-                           MN, a.N, a.scale, a.bias, a.add, a.relu, a.accumulate, a.mask, a.mscale, a.C, a.C2, a.acc2);
+                           MN, a.N, a.scale, a.bias, a.add, a.relu, a.accumulate, a.mask, a.mscale, a.C, a.C2, a.acc2, a.c2scale);
     return hipGetLastError();
 }
 
@@ -737,7 +745,7 @@ hipError_t mfma_conv_dgrad(const ConvGeom& g, const void* dz, const void* wt, vo
     IgemmArgs a{};
     a.A = (const uint16_t*)dz; a.B = (const uint16_t*)wt; a.C = (uint16_t*)dx;
     a.accumulate = accumulate; a.mask = (const uint16_t*)mask; a.mscale = mscale;
-    if (side) { a.add = (const uint16_t*)side->earlier; a.C2 = (uint16_t*)side->shortcut; a.acc2 = side->shortcut_acc; }
+    if (side) { a.add = (const uint16_t*)side->earlier; a.C2 = (uint16_t*)side->shortcut; a.acc2 = side->shortcut_acc; a.c2scale = side->shortcut_scale; }
     if (unpool) {
         a.C = nullptr; a.accumulate = 0; a.mask = nullptr;
         a.pool_x = (const uint16_t*)unpool->pool_x; a.pool_dst = (uint16_t*)unpool->dst;

@@ -70,8 +70,9 @@ struct UnpoolDesc { const void* pool_x; void* dst; int accumulate; int mask; con
 // side (may be NULL; only when dgrad_has_side): this data gradient is the last contribution to the gradient of a tensor
 // y = relu(scale*z + bias + shortcut) and performs that layer's epilogue backward on the way:
 //   v = conv_transpose(dz, w) + earlier (the contributions already there, may be NULL);  m = v * [mask > 0];
-//   dx = m * mscale_c (the producer's dz);   shortcut (+)= m (the gradient of the producer's shortcut tensor, may be NULL)
-struct DgradSide { const void* earlier; void* shortcut; int shortcut_acc; };
+//   dx = m * mscale_c (the producer's dz);   shortcut (+)= m * shortcut_scale_c (the gradient of the producer's shortcut
+//   tensor, may be NULL; with a scale: the dz of the scale-only layer -- a projection -- that made the shortcut)
+struct DgradSide { const void* earlier; void* shortcut; int shortcut_acc; const float* shortcut_scale; };
 hipError_t launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dz, const void* w, const void* wt,
                              void* dx, int accumulate, const void* mask, const float* mscale, void* ws, hipStream_t st,
                              const UnpoolDesc* unpool = nullptr, const DgradSide* side = nullptr);

@@ -135,6 +135,25 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
         }
         lr.fused_in = true;
     }
+    // ... and a projection shortcut: a scale-only layer (no ReLU, no shortcut of its own) whose output is read by
+    // exactly one layer, as its shortcut, when that layer is fused_side: the shortcut gradient that layer's fused
+    // epilogue writes is this layer's output gradient, and times this layer's scale it is this layer's dz.
+    for (int32_t i = first; i < last; ++i) {
+        LayerRt& lr = s->Ly(i);
+        const lpm_layer& l = lr.d;
+        if (dtype != LPM_BF16 || !has_weights(l) || (l.flags & LPM_RELU) || !(l.flags & LPM_SCALE) || l.add_src != LPM_NONE) continue;
+        if (i == s->t_out) continue;
+        if ((l.flags & LPM_BIAS) && !wgrad_fuses_bias(dtype, lr.g)) continue;
+        int n_src = 0, n_add = 0;
+        int32_t user = -1;
+        for (int32_t j = i + 1; j < last; ++j) {
+            if (s->net[(size_t)j].src == i) ++n_src;
+            if (s->net[(size_t)j].add_src == i) { ++n_add; user = j; }
+        }
+        if (n_src != 0 || n_add != 1 || !s->Ly(user).fused_side) continue;
+        lr.fused_in = true;
+        lr.via_shortcut = true;
+    }
     // Pooling-backward fusion: a 2x2 max-pooling (even input extent) whose output feeds exactly one layer, a
     // convolution whose data gradient runs on the stride-1 MFMA kernel: that kernel routes its result to the
     // window maxima itself and the gradient of the pooling output is never stored.
@@ -542,7 +561,11 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                             use_side = true;
                             side.earlier = have[gi(l.src)] ? G[gi(l.src)] : nullptr;
                             const int32_t a = pr.d.add_src;
-                            if (a != LPM_NONE && (a >= first || dx != nullptr)) {
+                            if (a != LPM_NONE && a >= first && s->Ly(a).via_shortcut) {
+                                side.shortcut = gw + s->Ly(a).dz_off;           // the projection's dz
+                                side.shortcut_scale = params + s->Ly(a).s_off;
+                                have[gi(a)] = 1;
+                            } else if (a != LPM_NONE && (a >= first || dx != nullptr)) {
                                 side.shortcut = G[gi(a)];
                                 side.shortcut_acc = have[gi(a)];
                                 have[gi(a)] = 1;

@@ -30,6 +30,8 @@ struct LayerRt {
     int32_t unpool_of = -1;                      // conv/FC: index of the max-pooling layer whose backward its data gradient performs
     bool fused_side = false;                     // fused_in, and the consumer's data gradient also adds the earlier contributions to this
                                                  // layer's output gradient and writes the gradient of this layer's shortcut (DgradSide)
+    bool via_shortcut = false;                   // fused_in: a scale-only layer read as a shortcut by one fused_side layer; the kernel that
+                                                 // writes that layer's shortcut gradient writes this layer's dz instead
     int32_t pool_fwd = -1;                       // conv/FC: index of the max-pooling layer whose forward its own forward kernel performs
     bool pooled_fwd = false;                     // max-pooling: its forward runs inside its producer's forward kernel
     bool unpooled = false;                       // max-pooling: its backward runs inside its consumer's data gradient
