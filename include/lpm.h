@@ -176,7 +176,11 @@ int32_t lpm_stage_stash_offset(const lpm_stage* s, int32_t t, size_t* offset, si
 /* Byte offset inside the backward scratch of the gradient w.r.t. internal tensor t (first <= t < last-1),
  * valid after lpm_stage_backward has run.  For tests.  The gradient of a max-pooling output that feeds a single
  * convolution may not be stored at all (that layer's data-gradient kernel routes it to the pooling input
- * directly); the offset then names memory the pass leaves untouched.  Errors: LPM_EINVAL. */
+ * directly); the offset then names memory the pass leaves untouched.  Likewise for LPM_BF16 the output of a
+ * conv/FC layer with ReLU or scale whose epilogue backward runs inside its reader's data-gradient kernel: the
+ * area then holds only the contributions that arrived before that kernel's own (those of the layers that use the
+ * tensor as a shortcut), or nothing.  Gradients of pooling inputs and of tensors with several readers are
+ * complete.  Errors: LPM_EINVAL. */
 int32_t lpm_stage_grad_offset(const lpm_stage* s, int32_t t, size_t* offset, size_t* bytes);
 
 /* (Re)build the low-precision weight copies from the float master parameters (LPM_BF16 stages; a
