@@ -407,10 +407,13 @@ int32_t overlapped_role(lpm_schedule* s, const RunArgs& a, int32_t role, uint64_
         // hardware queue to itself it follows stage 0's data phase from the start instead of queueing behind the other
         // stages' weight phases.  ev_w[j*Z+1] then marks the end of those on the common weight stream.
         const bool own0 = !async && Z > 1 && s->ov_w0 != s->ov_w;
+        // Asynchronous update: B_{z,j+1} waits for U_{z,j}, so the weight phases and updates are a chain per stage; odd
+        // stages take the second stream (each stage keeps its stream, which orders its updates).
+        const bool async2 = async && Z > 1 && s->ov_w0 != s->ov_w;
         hipStream_t sw_all = sw, sw_0 = s->ov_w0;
         for (int32_t j = 0; j < M; ++j) {
             for (int32_t z = Z - 1; z >= 0; --z) {
-                sw = (own0 && z == 0) ? sw_0 : sw_all;
+                sw = ((own0 && z == 0) || (async2 && (z & 1))) ? sw_0 : sw_all;
                 const size_t i = (size_t)j * Z + z;
                 if ((rc = await_record(s, s->rec_b[i], epoch))) return rc;
                 // Stage 0 closes the micro-batch, and the next forward chain but one waits for it: there the weight
@@ -435,6 +438,8 @@ int32_t overlapped_role(lpm_schedule* s, const RunArgs& a, int32_t role, uint64_
                 LPM_HIP(hipEventRecord(s->ev_w[(size_t)j * Z + 1], sw_all));
                 LPM_HIP(hipStreamWaitEvent(sw, s->ev_w[(size_t)j * Z + 1], 0));
             }
+            // (asynchronous update on two streams: U_{1,j}, recorded above, is the last operation of the odd stages)
+            if (async2) LPM_HIP(hipStreamWaitEvent(sw, s->ev_w[(size_t)j * Z + 1], 0));
             LPM_HIP(hipEventRecord(s->ev_w[(size_t)j * Z], sw));
             publish(s->rec_w[(size_t)j * Z], epoch);
         }
