@@ -171,11 +171,108 @@ __device__ __forceinline__ void igemm_store(const IgemmArgs& p, const f32x16 (&a
         }
 }
 
+// The same epilogue with 16-byte accesses.  A 32x32 accumulator tile has a column per lane (2-byte stores, 64 bytes
+// per row and instruction; the masked / shortcut forms add as many 2-byte loads); the wavefront passes the tile through
+// a private LDS area and every lane then owns 8 consecutive channels of a row.  tile: 32 rows of 36 floats.
+template <bool ADD, bool ACC, bool MASK>
+__device__ __forceinline__ void igemm_store_vec(const IgemmArgs& p, const f32x16& acc, float* tile, int row0, int col0, int rows, int lane) {
+    const int col_l = lane & 31, rq = (lane >> 5) * 4;
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int i = 0; i < 16; ++i) tile[((i >> 2) * 8 + rq + (i & 3)) * 36 + col_l] = acc[i];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const bool relu = p.relu != 0;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int idx = lane + 64 * c, r = idx >> 2, ch = (idx & 3) * 8;
+        const int row = row0 + r, col = col0 + ch;
+        if (row >= rows || col >= p.N) continue;
+        const float4 lo = *reinterpret_cast<const float4*>(tile + r * 36 + ch), hi = *reinterpret_cast<const float4*>(tile + r * 36 + ch + 4);
+        float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        const size_t o = (size_t)(unsigned)(row * p.N + col);
+        auto vec8 = [&](const float* q, float (&d)[8]) __attribute__((always_inline)) {
+            const float4 a = *reinterpret_cast<const float4*>(q + col), b = *reinterpret_cast<const float4*>(q + col + 4);
+            d[0] = a.x; d[1] = a.y; d[2] = a.z; d[3] = a.w; d[4] = b.x; d[5] = b.y; d[6] = b.z; d[7] = b.w;
+        };
+        auto bf8 = [&](const uint16_t* q, float (&d)[8]) __attribute__((always_inline)) {
+            const uint4 w = *reinterpret_cast<const uint4*>(q + o);
+            const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) { d[2 * k] = bf2f((uint16_t)(ww[k] & 0xffffu)); d[2 * k + 1] = bf2f((uint16_t)(ww[k] >> 16)); }
+        };
+        auto st8 = [&](uint16_t* q, const float (&d)[8]) __attribute__((always_inline)) {
+            *reinterpret_cast<uint4*>(q + o) = make_uint4(pack_bf16x2(d[0], d[1]), pack_bf16x2(d[2], d[3]), pack_bf16x2(d[4], d[5]),
+                                                          pack_bf16x2(d[6], d[7]));
+        };
+        float t[8];
+        if (p.scale) { vec8(p.scale, t);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] *= t[k]; }
+        if (p.bias) { vec8(p.bias, t);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] += t[k]; }
+        if (ADD) { bf8(p.add, t);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] += t[k]; }
+        if (ACC) { bf8(p.C, t);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] += t[k]; }
+        if (relu) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = fmaxf(v[k], 0.f); }
+        if (MASK) { bf8(p.mask, t);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = t[k] > 0.f ? v[k] : 0.f; }
+        if (p.C2) {
+            float u[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) u[k] = v[k];
+            if (p.c2scale) { vec8(p.c2scale, t);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) u[k] *= t[k]; }
+            if (p.acc2) { bf8(p.C2, t);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) u[k] += t[k]; }
+            st8(p.C2, u);
+        }
+        if (p.mscale) { vec8(p.mscale, t);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] *= t[k]; }
+        st8(p.C, v);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();        // the area is written again for the wavefront's next tile
+}
+
+// tile: this wavefront's private LDS area of 32 x 36 floats (NULL: none -- element-wise stores)
 template <int MI, int NI, int WTM, int WTN, int MODE>
 __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& p, f32x16 (&acc)[MI][NI], int m0, int n0, int wm, int wn, int lane,
-                                               int rows, int Hc, int Wc, int ph, int pw) {
+                                               int rows, int Hc, int Wc, int ph, int pw, float* tile = nullptr) {
     const int col_l = lane & 31, rq = (lane >> 5) * 4;
     const int variant = (p.add ? 1 : 0) | (p.accumulate ? 2 : 0) | (p.mask ? 4 : 0);
+    if (tile && MODE != MODE_DGRAD_S && !p.part && !(MODE == MODE_DGRAD && p.pool_x) && (p.N & 7) == 0) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) {
+                const int row0 = m0 + wm * WTM + mi * 32, col0 = n0 + wn * WTN + ni * 32;
+#define LPM_STORE_VEC(A, B, C) igemm_store_vec<A, B, C>(p, acc[mi][ni], tile, row0, col0, rows, lane)
+                switch (variant) {
+                    case 0: LPM_STORE_VEC(false, false, false); break;
+                    case 1: LPM_STORE_VEC(true, false, false); break;
+                    case 2: LPM_STORE_VEC(false, true, false); break;
+                    case 3: LPM_STORE_VEC(true, true, false); break;
+                    case 4: LPM_STORE_VEC(false, false, true); break;
+                    case 5: LPM_STORE_VEC(true, false, true); break;
+                    case 6: LPM_STORE_VEC(false, true, true); break;
+                    default: LPM_STORE_VEC(true, true, true); break;
+                }
+#undef LPM_STORE_VEC
+            }
+        return;
+    }
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
         const int col = n0 + wn * WTN + ni * 32 + col_l;
@@ -374,7 +471,10 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
 #undef LPM_LOAD_TILE
 #undef LPM_STORE_TILE
 
-    igemm_epilogue<Cfg::MI, Cfg::NI, Cfg::WTM, Cfg::WTN, MODE>(p, acc, m0, n0, wm, wn, lane, rows, Hc, Wc, ph, pw);
+    // (every wavefront is past the loop's last barrier: the A tiles are dead and take the epilogue's staging areas)
+    constexpr bool STAGE_FITS = sizeof(As) >= 4 * 32 * 36 * sizeof(float);
+    float* stage = STAGE_FITS ? reinterpret_cast<float*>(&As[0][0]) + wave * (32 * 36) : nullptr;
+    igemm_epilogue<Cfg::MI, Cfg::NI, Cfg::WTM, Cfg::WTN, MODE>(p, acc, m0, n0, wm, wn, lane, rows, Hc, Wc, ph, pw, stage);
 }
 
 #ifdef LPM_TUNE
