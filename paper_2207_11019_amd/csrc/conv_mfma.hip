@@ -174,8 +174,11 @@ __device__ __forceinline__ void igemm_store(const IgemmArgs& p, const f32x16 (&a
 // The same epilogue with 16-byte accesses.  A 32x32 accumulator tile has a column per lane (2-byte stores, 64 bytes
 // per row and instruction; the masked / shortcut forms add as many 2-byte loads); the wavefront passes the tile through
 // a private LDS area and every lane then owns 8 consecutive channels of a row.  tile: 32 rows of 36 floats.
-template <bool ADD, bool ACC, bool MASK>
-__device__ __forceinline__ void igemm_store_vec(const IgemmArgs& p, const f32x16& acc, float* tile, int row0, int col0, int rows, int lane) {
+// (PART: the fp32 split-K partials instead of the epilogue; strided data gradient: a row is a pixel of the block's
+// residue class, Hc x Wc of them per image)
+template <int MODE, bool PART, bool ADD, bool ACC, bool MASK>
+__device__ __forceinline__ void igemm_store_vec(const IgemmArgs& p, const f32x16& acc, float* tile, int row0, int col0, int rows, int lane,
+                                                int Hc, int Wc, int ph, int pw) {
     const int col_l = lane & 31, rq = (lane >> 5) * 4;
     asm volatile("" ::: "memory");
 #pragma unroll
@@ -191,7 +194,17 @@ __device__ __forceinline__ void igemm_store_vec(const IgemmArgs& p, const f32x16
         if (row >= rows || col >= p.N) continue;
         const float4 lo = *reinterpret_cast<const float4*>(tile + r * 36 + ch), hi = *reinterpret_cast<const float4*>(tile + r * 36 + ch + 4);
         float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-        const size_t o = (size_t)(unsigned)(row * p.N + col);
+        size_t o = (size_t)(unsigned)(row * p.N + col);
+        if (MODE == MODE_DGRAD_S) {      // class row -> pixel of the full image
+            const int wq = row % Wc, t_ = row / Wc, hq = t_ % Hc, n = t_ / Hc;
+            o = (size_t)(unsigned)(((n * p.Hr + hq * p.stride + ph) * p.Wr + wq * p.stride + pw) * p.N + col);
+        }
+        if (PART) {
+            float* q = p.part + (size_t)blockIdx.z * p.M * p.N + o;
+            *reinterpret_cast<float4*>(q) = lo;
+            *reinterpret_cast<float4*>(q + 4) = hi;
+            continue;
+        }
         auto vec8 = [&](const float* q, float (&d)[8]) __attribute__((always_inline)) {
             const float4 a = *reinterpret_cast<const float4*>(q + col), b = *reinterpret_cast<const float4*>(q + col + 4);
             d[0] = a.x; d[1] = a.y; d[2] = a.z; d[3] = a.w; d[4] = b.x; d[5] = b.y; d[6] = b.z; d[7] = b.w;
@@ -252,13 +265,17 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& p, f32x16 (&acc)
                                                int rows, int Hc, int Wc, int ph, int pw, float* tile = nullptr) {
     const int col_l = lane & 31, rq = (lane >> 5) * 4;
     const int variant = (p.add ? 1 : 0) | (p.accumulate ? 2 : 0) | (p.mask ? 4 : 0);
-    if (tile && MODE != MODE_DGRAD_S && !p.part && !(MODE == MODE_DGRAD && p.pool_x) && (p.N & 7) == 0) {
+    if (tile && (p.part || !(MODE == MODE_DGRAD && p.pool_x)) && (p.N & 7) == 0) {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) {
                 const int row0 = m0 + wm * WTM + mi * 32, col0 = n0 + wn * WTN + ni * 32;
-#define LPM_STORE_VEC(A, B, C) igemm_store_vec<A, B, C>(p, acc[mi][ni], tile, row0, col0, rows, lane)
+                if (p.part) {
+                    igemm_store_vec<MODE, true, false, false, false>(p, acc[mi][ni], tile, row0, col0, rows, lane, Hc, Wc, ph, pw);
+                    continue;
+                }
+#define LPM_STORE_VEC(A, B, C) igemm_store_vec<MODE, false, A, B, C>(p, acc[mi][ni], tile, row0, col0, rows, lane, Hc, Wc, ph, pw)
                 switch (variant) {
                     case 0: LPM_STORE_VEC(false, false, false); break;
                     case 1: LPM_STORE_VEC(true, false, false); break;
