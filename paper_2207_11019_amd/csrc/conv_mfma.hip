@@ -605,6 +605,20 @@ __global__ void __launch_bounds__(256, 2) igemm_dl_kernel(IgemmArgs p) {
 }
 #endif   // LPM_TUNE
 
+// Sum of one element's split-K partials in split order.  The loads are issued eight at a time before the first add (a
+// plain loop over a run-time split count waits for every load in turn); the additions keep the order.
+__device__ __forceinline__ float sum_partials(const float* __restrict__ part, int splits, int64_t stride, int64_t i) {
+    float v = 0.f;
+    for (int s0 = 0; s0 < splits; s0 += 8) {
+        float t[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) t[k] = s0 + k < splits ? part[(int64_t)(s0 + k) * stride + i] : 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) if (s0 + k < splits) v = (s0 + k == 0) ? t[k] : v + t[k];
+    }
+    return v;
+}
+
 // sums split-K partials in split order and applies the epilogue
 __global__ void __launch_bounds__(256) splitk_epilogue(const float* __restrict__ part, int splits, int64_t MN, int N,
                                                        const float* __restrict__ scale, const float* __restrict__ bias,
@@ -614,8 +628,7 @@ __global__ void __launch_bounds__(256) splitk_epilogue(const float* __restrict__
                                                        const float* __restrict__ c2scale) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= MN) return;
-    float v = part[i];
-    for (int s = 1; s < splits; ++s) v += part[(int64_t)s * MN + i];
+    float v = sum_partials(part, splits, MN, i);
     const int col = (int)(i % N);
     if (scale) v *= scale[col];
     if (bias) v += bias[col];
@@ -638,8 +651,7 @@ __global__ void __launch_bounds__(256) splitk_epilogue_unpool(const float* __res
                                                               const float* __restrict__ mscale) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= MN) return;
-    float v = part[i];
-    for (int s = 1; s < splits; ++s) v += part[(int64_t)s * MN + i];
+    float v = sum_partials(part, splits, MN, i);
     unpool_store(v, (int)(i / N), (int)(i % N), Hr, Wr, N, pool_x, dst, acc, mask, mscale);
 }
 
@@ -663,8 +675,7 @@ __global__ void __launch_bounds__(256) splitk_epilogue_pool(const float* __restr
     float r = 0.f;
     if (col < N) {
         const int64_t e = ((n * Hr + 2 * py + (k >> 1)) * Wr + 2 * px + (k & 1)) * N + col;
-        float v = part[e];
-        for (int s = 1; s < splits; ++s) v += part[(int64_t)s * MN + e];
+        float v = sum_partials(part, splits, MN, e);
         if (scale) v *= scale[col];
         if (bias) v += bias[col];
         if (relu) v = fmaxf(v, 0.f);
