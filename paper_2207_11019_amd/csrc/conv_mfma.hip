@@ -70,6 +70,7 @@ struct IgemmArgs {
     // only meets the filter taps of matching parity.  cls_tile0[c] = first row tile of class c (c = ph*stride+pw).
     int Kh;
     int cls_tile0[17];
+    int wshift, hshift;          // log2 of Wr, Hr when both are powers of two, else -1 (set by run_igemm)
     int m_tiles;                 // host only: row tiles to launch (0: ceil(M / 64)); K the plan is made for (0: Ktot)
     int plan_K;
     // stride-1 data gradient routed through a 2x2 max-pooling (see UnpoolDesc): the rows are pooled pixels
@@ -380,7 +381,18 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
         const int id = tid + c * 256, row = m0 + id / CPR, kc = id % CPR;
         a_ok[c] = (id < BM * CPR) & (row < rows);
         const int rr = a_ok[c] ? row : 0;
-        const int wq = rr % Wc, t = rr / Wc, hq = t % Hc, n = t / Hc;
+        int wq, hq, n;
+        if (MODE != MODE_DGRAD_S && p.wshift >= 0) {       // power-of-two image extents (same for the whole launch): no division
+            wq = rr & (Wc - 1);
+            const int t = rr >> p.wshift;
+            hq = t & (Hc - 1);
+            n = t >> p.hshift;
+        } else {
+            wq = rr % Wc;
+            const int t = rr / Wc;
+            hq = t % Hc;
+            n = t / Hc;
+        }
         if (MODE == MODE_FWD) { a_h0[c] = hq * p.stride - p.pad; a_w0[c] = wq * p.stride - p.pad; }
         else if (MODE == MODE_DGRAD) { a_h0[c] = hq + p.pad; a_w0[c] = wq + p.pad; }
         else { a_h0[c] = hq; a_w0[c] = wq; }
@@ -799,6 +811,11 @@ static void launch_igemm_cfg(const IgemmPlan& pl, const IgemmArgs& a, hipStream_
 }
 
 static hipError_t run_igemm(int mode, IgemmArgs a, void* ws, hipStream_t st) {
+    a.wshift = a.hshift = -1;
+    if (a.Wr > 0 && a.Hr > 0 && !(a.Wr & (a.Wr - 1)) && !(a.Hr & (a.Hr - 1))) {
+        a.wshift = __builtin_ctz((unsigned)a.Wr);
+        a.hshift = __builtin_ctz((unsigned)a.Hr);
+    }
     const IgemmPlan pl = plan_igemm(a.M, a.N, a.plan_K ? a.plan_K : a.Ktot, a.Ci);
     a.kt_total = pl.kt_total;
     a.kt_per_split = pl.kt_per;
