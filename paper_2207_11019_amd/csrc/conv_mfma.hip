@@ -641,7 +641,7 @@ __global__ void __launch_bounds__(256) splitk_epilogue(const float* __restrict__
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= MN) return;
     float v = sum_partials(part, splits, MN, i);
-    const int col = (int)(i % N);
+    const int col = (int)((unsigned)i % (unsigned)N);      // (the output has fewer than 2^31 elements)
     if (scale) v *= scale[col];
     if (bias) v += bias[col];
     if (add) v += bf2f(add[i]);
@@ -664,7 +664,7 @@ __global__ void __launch_bounds__(256) splitk_epilogue_unpool(const float* __res
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= MN) return;
     float v = sum_partials(part, splits, MN, i);
-    unpool_store(v, (int)(i / N), (int)(i % N), Hr, Wr, N, pool_x, dst, acc, mask, mscale);
+    unpool_store(v, (int)((unsigned)i / (unsigned)N), (int)((unsigned)i % (unsigned)N), Hr, Wr, N, pool_x, dst, acc, mask, mscale);
 }
 
 // forward: the same sum and epilogue, and the 2x2 max-pooling of the result as well (of the rounded values, as the
