@@ -16,7 +16,7 @@ __all__ = ["LpmError", "lib", "lpm_conv_geom", "lpm_conv_ws_bytes", "lpm_conv_fo
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = os.path.join(_HERE, "liblpm.so")
 if not os.path.exists(_LIB):
-    raise ImportError("liblpm.so is missing: build it with `python -m paper_2207_11019_amd.build`")
+    raise ImportError("liblpm.so is missing: build it with `python paper_2207_11019_amd/build.py`")
 lib = C.CDLL(_LIB)
 
 F32, BF16 = 0, 1
