@@ -2,7 +2,7 @@
 
 PyTorch is used for device memory and streams; no torch operator takes part in the training step.
 The library is required: importing this module fails if liblpm.so has not been built
-(python -m paper_2207_11019_amd.build or __graft_entry__.build()).
+(python paper_2207_11019_amd/build.py or __graft_entry__.build()).
 """
 import ctypes as C
 import os
