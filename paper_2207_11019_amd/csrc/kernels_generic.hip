@@ -385,8 +385,81 @@ __global__ void __launch_bounds__(256) maxpool_bwd_kernel(int m, int H, int W, i
     }
 }
 
+// bf16 with C a multiple of 8: a thread takes 8 channels of one pooled pixel with 16-byte accesses (the element-wise
+// kernels above issue a 2-byte access per tensor and thread).  Same arithmetic and the same first-maximum rule.
+__device__ __forceinline__ void unpack8x(const uint4 v, float (&f)[8]) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { f[2 * k] = bf2f((uint16_t)(w[k] & 0xffffu)); f[2 * k + 1] = bf2f((uint16_t)(w[k] >> 16)); }
+}
+__device__ __forceinline__ uint4 pack8x(const float (&f)[8]) {
+    return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+}
+
+__global__ void __launch_bounds__(256) maxpool_fwd_bf16x8(unsigned total8, int H, int W, int C8, const uint4* __restrict__ x,
+                                                          uint4* __restrict__ y) {
+    const unsigned idx = blockIdx.x * 256u + threadIdx.x;
+    if (idx >= total8) return;
+    const unsigned Ho = H / 2, Wo = W / 2;
+    const unsigned c = idx % (unsigned)C8, r = idx / (unsigned)C8;
+    const unsigned wo = r % Wo, ho = (r / Wo) % Ho, n = r / (Wo * Ho);
+    const size_t base = ((size_t)(n * H + 2 * ho) * W + 2 * wo) * C8 + c;
+    float a[8], b[8], d[8], e[8], o[8];
+    unpack8x(x[base], a); unpack8x(x[base + C8], b);
+    unpack8x(x[base + (size_t)W * C8], d); unpack8x(x[base + (size_t)W * C8 + C8], e);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) o[k] = fmaxf(fmaxf(a[k], b[k]), fmaxf(d[k], e[k]));
+    y[idx] = pack8x(o);
+}
+
+__global__ void __launch_bounds__(256) maxpool_bwd_bf16x8(unsigned total8, int H, int W, int C8, const uint4* __restrict__ x,
+                                                          const uint4* __restrict__ y, const uint4* __restrict__ dy,
+                                                          uint4* __restrict__ dx, int accumulate, int mask,
+                                                          const float* __restrict__ mscale) {
+    const unsigned idx = blockIdx.x * 256u + threadIdx.x;
+    if (idx >= total8) return;
+    const unsigned Ho = H / 2, Wo = W / 2;
+    const unsigned c = idx % (unsigned)C8, r = idx / (unsigned)C8;
+    const unsigned wo = r % Wo, ho = (r / Wo) % Ho, n = r / (Wo * Ho);
+    const size_t base = ((size_t)(n * H + 2 * ho) * W + 2 * wo) * C8 + c;
+    const size_t off[4] = {0, (size_t)C8, (size_t)W * C8, (size_t)W * C8 + C8};
+    float mx[8], g[8], xin[4][8], old[4][8];
+    unpack8x(y[idx], mx);
+    unpack8x(dy[idx], g);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        unpack8x(x[base + off[k]], xin[k]);
+        if (accumulate) unpack8x(dx[base + off[k]], old[k]);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        if (mask && !(mx[j] > 0.f)) g[j] = 0.f;        // the pooled tensor is a ReLU output: its mask at the maximum
+        if (mscale) g[j] *= mscale[c * 8 + j];
+    }
+    float out[4][8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        bool found = false;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const bool hit = !found && (xin[k][j] == mx[j]);
+            found = found || hit;
+            float v = hit ? g[j] : 0.f;
+            if (accumulate) v += old[k][j];
+            out[k][j] = v;
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) dx[base + off[k]] = pack8x(out[k]);
+}
+
 hipError_t launch_maxpool_fwd(int dtype, int32_t m, int32_t H, int32_t W, int32_t C, const void* x, void* y, hipStream_t s) {
     const int64_t total = (int64_t)m * (H / 2) * (W / 2) * C;
+    if (dtype == LPM_BF16 && (C & 7) == 0 && (int64_t)m * H * W * C < ((int64_t)1 << 31)) {
+        const unsigned total8 = (unsigned)(total / 8);
+        hipLaunchKernelGGL(maxpool_fwd_bf16x8, dim3((total8 + 255u) / 256u), dim3(256), 0, s, total8, H, W, C / 8, (const uint4*)x, (uint4*)y);
+        return hipGetLastError();
+    }
     LPM_DISPATCH(dtype, hipLaunchKernelGGL(maxpool_fwd_kernel<T>, dim3(nblk(total, 256)), dim3(256), 0, s, m, H, W, C,
                                            (const T*)x, (T*)y));
     return hipGetLastError();
@@ -395,6 +468,12 @@ hipError_t launch_maxpool_fwd(int dtype, int32_t m, int32_t H, int32_t W, int32_
 hipError_t launch_maxpool_bwd(int dtype, int32_t m, int32_t H, int32_t W, int32_t C, const void* x, const void* y,
                               const void* dy, void* dx, int accumulate, int mask, const float* mscale, hipStream_t s) {
     const int64_t total = (int64_t)m * (H / 2) * (W / 2) * C;
+    if (dtype == LPM_BF16 && (C & 7) == 0 && (int64_t)m * H * W * C < ((int64_t)1 << 31)) {
+        const unsigned total8 = (unsigned)(total / 8);
+        hipLaunchKernelGGL(maxpool_bwd_bf16x8, dim3((total8 + 255u) / 256u), dim3(256), 0, s, total8, H, W, C / 8, (const uint4*)x,
+                           (const uint4*)y, (const uint4*)dy, (uint4*)dx, accumulate, mask, mscale);
+        return hipGetLastError();
+    }
     LPM_DISPATCH(dtype, hipLaunchKernelGGL(maxpool_bwd_kernel<T>, dim3(nblk(total, 256)), dim3(256), 0, s, m, H, W, C,
                                            (const T*)x, (const T*)y, (const T*)dy, (T*)dx, accumulate, mask, mscale));
     return hipGetLastError();
