@@ -656,6 +656,73 @@ __global__ void __launch_bounds__(256) splitk_epilogue(const float* __restrict__
     C[i] = f2bf(v);
 }
 
+// The same for four consecutive channels per thread (N a multiple of 4): 16-byte partial loads, 8-byte tensor accesses.
+__global__ void __launch_bounds__(256) splitk_epilogue_x4(const float* __restrict__ part, int splits, int64_t MN, int N,
+                                                          const float* __restrict__ scale, const float* __restrict__ bias,
+                                                          const uint16_t* __restrict__ add, int relu, int accumulate,
+                                                          const uint16_t* __restrict__ mask, const float* __restrict__ mscale,
+                                                          uint16_t* __restrict__ C, uint16_t* __restrict__ C2, int acc2,
+                                                          const float* __restrict__ c2scale) {
+    const unsigned i = (blockIdx.x * 256u + threadIdx.x) * 4u;
+    if (i >= (unsigned)MN) return;
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < splits; s0 += 8) {          // eight splits' loads before the first add; the adds keep the split order
+        float4 t[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            t[k] = s0 + k < splits ? *reinterpret_cast<const float4*>(part + (size_t)(s0 + k) * MN + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (s0 + k < splits) {
+                if (s0 + k == 0) { v[0] = t[k].x; v[1] = t[k].y; v[2] = t[k].z; v[3] = t[k].w; }
+                else { v[0] += t[k].x; v[1] += t[k].y; v[2] += t[k].z; v[3] += t[k].w; }
+            }
+    }
+    const unsigned col = i % (unsigned)N;
+    auto f4 = [&](const float* q, float (&d)[4]) __attribute__((always_inline)) {
+        const float4 a = *reinterpret_cast<const float4*>(q + col);
+        d[0] = a.x; d[1] = a.y; d[2] = a.z; d[3] = a.w;
+    };
+    auto b4 = [&](const uint16_t* q, float (&d)[4]) __attribute__((always_inline)) {
+        const uint2 w = *reinterpret_cast<const uint2*>(q + i);
+        d[0] = bf2f((uint16_t)(w.x & 0xffffu)); d[1] = bf2f((uint16_t)(w.x >> 16));
+        d[2] = bf2f((uint16_t)(w.y & 0xffffu)); d[3] = bf2f((uint16_t)(w.y >> 16));
+    };
+    float t[4];
+    if (scale) { f4(scale, t);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] *= t[k]; }
+    if (bias) { f4(bias, t);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] += t[k]; }
+    if (add) { b4(add, t);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] += t[k]; }
+    if (accumulate) { b4(C, t);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] += t[k]; }
+    if (relu) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = fmaxf(v[k], 0.f); }
+    if (mask) { b4(mask, t);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) if (!(t[k] > 0.f)) v[k] = 0.f; }
+    if (C2) {
+        float u[4] = {v[0], v[1], v[2], v[3]};
+        if (c2scale) { f4(c2scale, t);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) u[k] *= t[k]; }
+        if (acc2) { b4(C2, t);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) u[k] += t[k]; }
+        *reinterpret_cast<uint2*>(C2 + i) = make_uint2(pack_bf16x2(u[0], u[1]), pack_bf16x2(u[2], u[3]));
+    }
+    if (mscale) { f4(mscale, t);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] *= t[k]; }
+    *reinterpret_cast<uint2*>(C + i) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+}
+
 // the same sum routed through a 2x2 max-pooling (see unpool_store)
 __global__ void __launch_bounds__(256) splitk_epilogue_unpool(const float* __restrict__ part, int splits, int64_t MN, int N,
                                                               int Hr, int Wr, const uint16_t* __restrict__ pool_x,
@@ -832,6 +899,9 @@ static hipError_t run_igemm(int mode, IgemmArgs a, void* ws, hipStream_t st) {
     else if (a.pool_x)
         hipLaunchKernelGGL(splitk_epilogue_unpool, dim3((unsigned)((MN + 255) / 256)), dim3(256), 0, st, (const float*)ws,
                            pl.splits, MN, a.N, a.Hr, a.Wr, a.pool_x, a.pool_dst, a.pool_acc, a.pool_mask, a.mscale);
+    else if ((a.N & 3) == 0)
+        hipLaunchKernelGGL(splitk_epilogue_x4, dim3((unsigned)((MN / 4 + 255) / 256)), dim3(256), 0, st, (const float*)ws, pl.splits,
+                           MN, a.N, a.scale, a.bias, a.add, a.relu, a.accumulate, a.mask, a.mscale, a.C, a.C2, a.acc2, a.c2scale);
     else
         hipLaunchKernelGGL(splitk_epilogue, dim3((unsigned)((MN + 255) / 256)), dim3(256), 0, st, (const float*)ws, pl.splits,
                            MN, a.N, a.scale, a.bias, a.add, a.relu, a.accumulate, a.mask, a.mscale, a.C, a.C2, a.acc2, a.c2scale);
