@@ -326,8 +326,9 @@ int32_t lpm_conv_time(int32_t op, const lpm_conv_geom* g, int32_t dtype, void* x
 /* ---- layer-wise partitioning of one layer ("Layer-wise Partitioning and Merging" section, fig. 1a) ---- */
 
 /* The un-merged form of the method: a layer's output channels are split into n equal sub-layers (n = the paper's
- * number of devices), each sub-layer is computed by its own launch on its own stream of the library's pool (the
- * stand-in for a device) with its slice of the weights, and the outputs are concatenated for the next layer.
+ * number of devices), each sub-layer is computed by its own launch with its slice of the weights -- on the caller's
+ * stream and up to three streams of the library's pool that were measured to feed other hardware queues (the
+ * stand-ins for devices; further sub-layers share them in turn) -- and the outputs are concatenated for the next layer.
  * Backward, the incoming gradient is re-partitioned by channel, each sub-layer produces its slice of the weight
  * gradient and a full-size partial input gradient, and the partials are added in sub-layer order.  The results are
  * those of the merged layer (lpm_conv_*); the difference in time is the overhead that merging removes.
@@ -343,7 +344,8 @@ int32_t lpm_layerwise_ws_bytes(const lpm_layerwise* lw, size_t* forward, size_t*
 
 /* y = relu?( scale_c * (w (*) x) + bias_c ), computed as n sub-layers and one concatenation (eq. 1 per sub-layer).
  *   x [m][h][w][cin], w [cout][kh][kw][cin] (sub-layer i owns rows i*cout/n ...), y [m][ho][wo][cout]; scale, bias
- *   (float [cout]) may be NULL.  Enqueues on `stream` and on n pooled streams that fork from and join back into it;
+ *   (float [cout]) may be NULL.  Enqueues on `stream` and on pooled streams that fork from and join back into it
+ *   (the first call on a stream runs a few short probe kernels on it and synchronises it);
  *   calls on one handle must not overlap (they share its events and the scratch). */
 int32_t lpm_layerwise_forward(lpm_layerwise* lw, const void* x, const void* w, const float* scale, const float* bias,
                               int32_t relu, void* y, void* ws, void* stream);

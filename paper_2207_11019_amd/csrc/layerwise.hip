@@ -19,6 +19,8 @@ struct lpm_layerwise {
     size_t es;          // bytes per activation element
     size_t y_bytes, dz_bytes, dx_bytes, fwd_ws, bwd_ws;      // per sub-layer, each a multiple of 256
     hipEvent_t fork, join[8];
+    hipStream_t probed_for;   // the caller stream sub[] was chosen for (NULL: not yet)
+    hipStream_t sub[8];       // stream of sub-layer i
 };
 
 namespace {
@@ -62,6 +64,22 @@ __global__ void __launch_bounds__(256) layerwise_sum(const void* __restrict__ pa
         if (BF16) ((uint16_t*)dx)[i] = f32_to_bf16(s);
         else ((float*)dx)[i] = s;
     }
+}
+
+// Streams of the n sub-layers for a caller stream st: the runtime maps streams onto four hardware queues that each run
+// their kernels one after the other, so "n devices" are best imitated by st itself plus up to three pooled streams
+// measured to sit on other queues (streams_share_queue); further sub-layers share them round-robin.
+int32_t choose_streams(lpm_layerwise* L, hipStream_t st) {
+    if (L->probed_for == st && L->sub[0]) return LPM_OK;
+    hipStream_t got[3] = {nullptr, nullptr, nullptr};
+    int found = 0;
+    const hipStream_t taken[1] = {st};
+    LPM_HIP(pick_concurrent_streams(taken, 1, got, std::min(3, L->n - 1), &found));
+    hipStream_t set[4] = {st, got[0], got[1], got[2]};
+    const int have = 1 + found;
+    for (int i = 0; i < L->n; ++i) L->sub[i] = set[(i + 1) % have];      // the caller's stream takes the last of every round
+    L->probed_for = st;
+    return LPM_OK;
 }
 
 unsigned blocks_for(int64_t work) { return (unsigned)std::min<int64_t>((work + 255) / 256, 256 * 8); }
@@ -124,8 +142,10 @@ extern "C" int32_t lpm_layerwise_forward(lpm_layerwise* L, const void* x, const 
                                          int32_t relu, void* y, void* ws, void* stream) {
     if (!L || !x || !w || !y || !ws) return fail(LPM_EINVAL, "NULL argument");
     if (misaligned({x, w, scale, bias, y, ws})) return fail(LPM_EALIGN, "device buffers must be 256-byte aligned");
-    hipStream_t st = (hipStream_t)stream, sub[8];
-    for (int i = 0; i < L->n; ++i) LPM_HIP(pooled_stream(i, &sub[i]));
+    hipStream_t st = (hipStream_t)stream;
+    int32_t src = choose_streams(L, st);
+    if (src) return src;
+    hipStream_t* sub = L->sub;
     const int cn = L->gs.Cout;
     const size_t w_slice = (size_t)cn * L->g.K() * L->es;
     char* yparts = (char*)ws;
@@ -152,8 +172,10 @@ extern "C" int32_t lpm_layerwise_backward(lpm_layerwise* L, const void* x, const
                                           void* dx, float* dw, int32_t accumulate, void* ws, void* stream) {
     if (!L || !x || !dz || !w || !dw || !ws) return fail(LPM_EINVAL, "NULL argument");
     if (misaligned({x, dz, w, wt, dx, dw, ws})) return fail(LPM_EALIGN, "device buffers must be 256-byte aligned");
-    hipStream_t st = (hipStream_t)stream, sub[8];
-    for (int i = 0; i < L->n; ++i) LPM_HIP(pooled_stream(i, &sub[i]));
+    hipStream_t st = (hipStream_t)stream;
+    int32_t src = choose_streams(L, st);
+    if (src) return src;
+    hipStream_t* sub = L->sub;
     const int cn = L->gs.Cout;
     const size_t w_slice = (size_t)cn * L->g.K() * L->es;          // also the size of one sub-layer's transposed weights
     const size_t dw_slice = (size_t)cn * L->g.K();
