@@ -190,7 +190,8 @@ int32_t lpm_stage_sync_lowp(lpm_stage* s, const float* params, void* lowp, void*
 /* F_{z,j}: forward pass of the stage on one micro-batch (eq. 1 applied layer by layer).
  *   x        stage input  [m][H][W][C]            (read)
  *   y        stage output [m][Ho][Wo][Co], or the logits [m][classes] for a loss stage   (written)
- *   labels   loss stage only: int32 [m]; 4-byte aligned is enough
+ *   labels   loss stage only: int32 [m], every value in [0, classes); 4-byte aligned is enough.  A value outside
+ *            that range reads nothing out of bounds: the row gets no one-hot term and the loss becomes NaN
  *   loss_accum loss stage only: one float, += loss_scale * sum_n -log softmax(logits_n)[label_n]
  *   params, lowp   as sized by lpm_stage_sizes (lowp may be NULL for LPM_F32)
  *   stash    one stash slot (written)

@@ -8,7 +8,7 @@ namespace lpm {
 
 hipError_t conv_fwd_generic_launch(int dtype, const ConvGeom& g, const void* x, const void* w, const float* scale,
                                    const float* bias, const void* add, int relu, void* y, hipStream_t s);
-hipError_t conv_dgrad_generic_launch(int dtype, const ConvGeom& g, const void* dz, const void* w, void* dx,
+hipError_t conv_dgrad_generic_launch(int dtype, const ConvGeom& g, const void* dz, const float* dzscale, const void* w, void* dx,
                                      int accumulate, const void* mask, const float* mscale, hipStream_t s);
 hipError_t conv_wgrad_generic_launch(int dtype, const ConvGeom& g, const void* x, const void* dz, float* dw,
                                      int accumulate, void* ws, hipStream_t s);
@@ -25,29 +25,29 @@ hipError_t mfma_conv_fwd(const ConvGeom& g, const void* x, const void* w, const 
                          const void* add, int relu, void* y, void* ws, hipStream_t st, void* pool_y);
 hipError_t mfma_conv_dgrad(const ConvGeom& g, const void* dz, const void* wt, void* dx, int accumulate, const void* mask,
                            const float* mscale, void* ws, hipStream_t st, const UnpoolDesc* unpool, const DgradSide* side);
-hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* bscale,
+hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* rscale,
                            int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred);
 
 bool wgrad_tr_ok(const ConvGeom& g);
 size_t wgrad_tr_ws_bytes(const ConvGeom& g);
-hipError_t wgrad_tr(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* bscale,
+hipError_t wgrad_tr(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* rscale,
                     int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred);
 
 bool fc_skinny_ok(const ConvGeom& g);
 size_t fc_dgrad_ws_bytes(const ConvGeom& g);
-hipError_t fc_dgrad(const ConvGeom& g, const void* dz, const void* w, void* dx, int accumulate, const void* mask,
+hipError_t fc_dgrad(const ConvGeom& g, const void* dz, const float* dzscale, const void* w, void* dx, int accumulate, const void* mask,
                     const float* mscale, void* ws, hipStream_t st);
-hipError_t fc_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* bscale,
+hipError_t fc_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* rscale,
                     int accumulate, hipStream_t st);
 
 bool fc_staged_ok(const ConvGeom& g);
 hipError_t fc_wgrad_staged(const ConvGeom& g, const void* xs, const void* dzs, int slots, float* dw, float* dbias,
-                           const float* bscale, int accumulate, hipStream_t st);
+                           const float* rscale, int accumulate, hipStream_t st);
 
 bool mfma_wgrad_flat_ok(const ConvGeom& g);
 size_t mfma_wgrad_flat_ws_bytes(const ConvGeom& g);
 hipError_t mfma_conv_wgrad_flat(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias,
-                                const float* bscale, int accumulate, void* ws, hipStream_t st);
+                                const float* rscale, int accumulate, void* ws, hipStream_t st);
 
 bool smallk_ok(const ConvGeom& g);
 hipError_t smallk_conv_fwd(const ConvGeom& g, const void* x, const void* w, const float* scale, const float* bias,
@@ -94,22 +94,22 @@ bool dgrad_has_side(int dtype, const ConvGeom& g) { return dgrad_uses_wt(dtype, 
 
 hipError_t launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dz, const void* w, const void* wt, void* dx,
                              int accumulate, const void* mask, const float* mscale, void* ws, hipStream_t st,
-                             const UnpoolDesc* unpool, const DgradSide* side) {
+                             const UnpoolDesc* unpool, const DgradSide* side, const float* dzscale) {
     if (unpool && !(dgrad_can_unpool(dtype, g) && wt)) return hipErrorInvalidValue;      // callers ask dgrad_can_unpool first
     if (side && !(dgrad_has_side(dtype, g) && wt)) return hipErrorInvalidValue;          // ... and dgrad_has_side
-    if (dtype == LPM_BF16 && fc_skinny_ok(g)) return fc_dgrad(g, dz, w, dx, accumulate, mask, mscale, ws, st);
+    if (dtype == LPM_BF16 && fc_skinny_ok(g)) return fc_dgrad(g, dz, dzscale, w, dx, accumulate, mask, mscale, ws, st);
     if (dtype == LPM_BF16 && wt && mfma_dgrad_ok(g)) return mfma_conv_dgrad(g, dz, wt, dx, accumulate, mask, mscale, ws, st, unpool, side);
-    return conv_dgrad_generic_launch(dtype, g, dz, w, dx, accumulate, mask, mscale, st);
+    return conv_dgrad_generic_launch(dtype, g, dz, dzscale, w, dx, accumulate, mask, mscale, st);
 }
 
 hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias,
-                             const float* bscale, int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred) {
+                             const float* rscale, int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred) {
     if (deferred) deferred->splits = 0;
-    if (dtype == LPM_BF16 && fc_skinny_ok(g)) return fc_wgrad(g, x, dz, dw, dbias, bscale, accumulate, st);
-    if (dtype == LPM_BF16 && wgrad_tr_ok(g)) return wgrad_tr(g, x, dz, dw, dbias, bscale, accumulate, ws, st, deferred);
-    if (dtype == LPM_BF16 && mfma_wgrad_ok(g)) return mfma_conv_wgrad(g, x, dz, dw, dbias, bscale, accumulate, ws, st, deferred);
-    if (dtype == LPM_BF16 && mfma_wgrad_flat_ok(g)) return mfma_conv_wgrad_flat(g, x, dz, dw, dbias, bscale, accumulate, ws, st);
-    if (dbias) return hipErrorInvalidValue;      // callers ask wgrad_fuses_bias first
+    if (dtype == LPM_BF16 && fc_skinny_ok(g)) return fc_wgrad(g, x, dz, dw, dbias, rscale, accumulate, st);
+    if (dtype == LPM_BF16 && wgrad_tr_ok(g)) return wgrad_tr(g, x, dz, dw, dbias, rscale, accumulate, ws, st, deferred);
+    if (dtype == LPM_BF16 && mfma_wgrad_ok(g)) return mfma_conv_wgrad(g, x, dz, dw, dbias, rscale, accumulate, ws, st, deferred);
+    if (dtype == LPM_BF16 && mfma_wgrad_flat_ok(g)) return mfma_conv_wgrad_flat(g, x, dz, dw, dbias, rscale, accumulate, ws, st);
+    if (dbias || rscale) return hipErrorInvalidValue;      // callers ask wgrad_fuses_bias first
     return conv_wgrad_generic_launch(dtype, g, x, dz, dw, accumulate, ws, st);
 }
 
@@ -132,11 +132,11 @@ size_t wgrad_staged_ws_bytes(int dtype, const ConvGeom& g) {
 }
 
 hipError_t launch_wgrad_staged(int dtype, const ConvGeom& g, const void* xs, const void* dzs, int slots, float* dw, float* dbias,
-                               const float* bscale, int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred) {
+                               const float* rscale, int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred) {
     if (deferred) deferred->splits = 0;
-    if (fc_staged_ok(g)) return fc_wgrad_staged(g, xs, dzs, slots, dw, dbias, bscale, accumulate, st);
+    if (fc_staged_ok(g)) return fc_wgrad_staged(g, xs, dzs, slots, dw, dbias, rscale, accumulate, st);
     // the staged micro-batches are one larger batch in the same layout
-    return launch_conv_wgrad(dtype, staged_geom(g, slots), xs, dzs, dw, dbias, bscale, accumulate, ws, st, deferred);
+    return launch_conv_wgrad(dtype, staged_geom(g, slots), xs, dzs, dw, dbias, rscale, accumulate, ws, st, deferred);
 }
 
 }  // namespace lpm

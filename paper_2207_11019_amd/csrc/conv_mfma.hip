@@ -14,9 +14,6 @@
 #include "elem.h"
 #include "lds_dma.h"
 #include <algorithm>
-#ifdef LPM_TUNE
-#include <cstdlib>
-#endif
 
 namespace lpm {
 
@@ -506,116 +503,6 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
     igemm_epilogue<Cfg::MI, Cfg::NI, Cfg::WTM, Cfg::WTN, MODE>(p, acc, m0, n0, wm, wn, lane, rows, Hc, Wc, ph, pw, stage);
 }
 
-#ifdef LPM_TUNE
-// Measurement builds only.  On MI355X this variant is behind the register-staged kernel above on the workloads' layer
-// shapes (3x3 filters, K loops of 8 tiles: 12.6 against 11.1 us on 32x32x128->256; a 224x224 VGG-16 step 9.73 against
-// 9.51 ms) and ahead only on long 1x1 contractions with thousands of blocks (38.7 against 42.0 us), so product
-// launches do not use it.
-// The same contraction with the K tiles copied by loads that write LDS directly, through a ring of four stages
-// (three tiles in flight), for forward and stride-1 data gradient when the gathered tensor's channel count is a
-// multiple of 64 and the filter has at most 64 taps.  LDS rows are 64 elements (128 bytes) without padding; chunk c
-// (16 bytes) of tile row r sits at position c ^ ((r >> 1) & 7), which makes the operand fetches (32 rows x one
-// chunk per half-wavefront) conflict-free -- the loader simply asks for the chunk that belongs at its lane's place.
-// Per row, the filter taps that fall inside the image are a 64-bit mask computed once; per K tile a lane spends a
-// shift and a select.  One workgroup barrier per K tile, no staging registers, no LDS stores.
-constexpr int DL_TILE_BYTES = 64 * 128, DL_STAGE = 2 * DL_TILE_BYTES;
-
-template <int MODE, int DL_NST>
-__global__ void __launch_bounds__(256, 2) igemm_dl_kernel(IgemmArgs p) {
-    static_assert(MODE == MODE_FWD || MODE == MODE_DGRAD, "forward or stride-1 data gradient");
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];      // DL_NST stages of A tile + B tile
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int nt = (p.N + 63) / 64;
-    const int tile = xcd_remap(blockIdx.x, gridDim.x);
-    const int m0 = (tile / nt) * 64, n0 = (tile % nt) * 64;
-    const int kt0 = blockIdx.z * p.kt_per_split, nk = min(p.kt_total, kt0 + p.kt_per_split) - kt0;
-    const u32x4_ rsA = buffer_words(p.A, p.a_bytes), rsB = buffer_words(p.B, p.b_bytes);
-    const int taps = p.Kh * p.Kw;
-
-    // loader: load wl (0..7) of an operand fills tile rows wl*8 .. wl*8+7; lane = row * 8 + position; this wavefront takes wl = wave, wave + 4
-    const int l_row = lane >> 3, l_pos = lane & 7;
-    unsigned a_base[2], b_off[2];
-    unsigned long long a_mask[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int row = (wave + 4 * i) * 8 + l_row, c = l_pos ^ ((row >> 1) & 7);
-        const int grow = m0 + row;
-        const bool ok = grow < p.M;
-        const int rr = ok ? grow : 0;
-        const int wq = rr % p.Wr, t = rr / p.Wr, hq = t % p.Hr, n = t / p.Hr;
-        const int h0 = MODE == MODE_FWD ? hq * p.stride - p.pad : hq + p.pad;
-        const int w0 = MODE == MODE_FWD ? wq * p.stride - p.pad : wq + p.pad;
-        a_base[i] = (unsigned)(((n * p.Hi + h0) * p.Wi + w0) * p.Ci + c * 8) * 2u;     // may wrap below zero; used only for taps inside
-        unsigned long long mk = 0;
-        for (int tp = 0; tp < taps; ++tp) {
-            const int kh = tp / p.Kw, kw = tp - kh * p.Kw;
-            const int h = MODE == MODE_FWD ? h0 + kh : h0 - kh, w = MODE == MODE_FWD ? w0 + kw : w0 - kw;
-            if (ok & ((unsigned)h < (unsigned)p.Hi) & ((unsigned)w < (unsigned)p.Wi)) mk |= 1ull << tp;
-        }
-        a_mask[i] = mk;
-        const int nn = n0 + row;
-        b_off[i] = nn < p.N ? (unsigned)(((size_t)nn * p.Ktot + c * 8) * 2) : 0xffffffffu;
-    }
-    // cursor of the next K tile to load: filter tap and channel offset
-    int c_tap, c_c0, c_kh, c_kw;
-    {
-        const int k0 = kt0 * 64;
-        c_tap = k0 / p.Ci; c_c0 = k0 - c_tap * p.Ci;
-        c_kh = c_tap / p.Kw; c_kw = c_tap - c_kh * p.Kw;
-    }
-#define LPM_DL_ISSUE(ST)                                                                                      \
-    {                                                                                                         \
-        unsigned char* st_ = lds + (ST) * DL_STAGE;                                                           \
-        const unsigned tapoff_ = MODE == MODE_FWD ? (unsigned)((c_kh * p.Wi + c_kw) * p.Ci + c_c0) * 2u        \
-                                                  : (unsigned)(c_c0 - (c_kh * p.Wi + c_kw) * p.Ci) * 2u;       \
-        const unsigned kb_ = (unsigned)(c_tap * p.Ci + c_c0) * 2u;                                            \
-        _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                       \
-            const bool in_ = (a_mask[i] >> c_tap) & 1ull;                                                     \
-            load_to_lds16(rsA, st_ + (wave + 4 * i) * 1024, in_ ? a_base[i] + tapoff_ : 0xffffffffu);         \
-        }                                                                                                     \
-        _Pragma("unroll") for (int i = 0; i < 2; ++i)                                                         \
-            load_to_lds16(rsB, st_ + DL_TILE_BYTES + (wave + 4 * i) * 1024,                                   \
-                          b_off[i] == 0xffffffffu ? 0xffffffffu : b_off[i] + kb_);                            \
-        c_c0 += 64;                                                                                           \
-        if (c_c0 >= p.Ci) {                                                                                   \
-            c_c0 = 0; ++c_tap;                                                                                \
-            if (++c_kw == p.Kw) { c_kw = 0; ++c_kh; }                                                         \
-        }                                                                                                     \
-    }
-
-    f32x16 acc[1][1];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[0][0][i] = 0.f;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int r = lane & 31, kq = lane >> 5, sw = (r >> 1) & 7;
-#pragma unroll
-    for (int i = 0; i < DL_NST - 1; ++i)
-        if (i < nk) LPM_DL_ISSUE(i);
-    int st = 0;
-    for (int it = 0; it < nk; ++it) {
-        wait_tiles_behind<4, (DL_NST > 2 ? DL_NST - 2 : 1)>(DL_NST > 2 ? nk - 1 - it : 0);      // tile `it` has landed: only the tiles behind it are outstanding
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_barrier();      // every wavefront's part has landed, and all are done reading the stage loaded next
-        asm volatile("" ::: "memory");
-        if (it + DL_NST - 1 < nk) {
-            const int st2 = st == 0 ? DL_NST - 1 : st - 1;
-            LPM_DL_ISSUE(st2);
-        }
-        const unsigned char* as = lds + st * DL_STAGE + (wm * 32 + r) * 128;
-        const unsigned char* bs = lds + st * DL_STAGE + DL_TILE_BYTES + (wn * 32 + r) * 128;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const int po = ((ks * 2 + kq) ^ sw) * 16;
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(as + po);
-            const bf16x8 b = *reinterpret_cast<const bf16x8*>(bs + po);
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[0][0], 0, 0, 0);
-        }
-        st = st == DL_NST - 1 ? 0 : st + 1;
-    }
-#undef LPM_DL_ISSUE
-    igemm_epilogue<1, 1, 32, 32, MODE>(p, acc, m0, n0, wm, wn, lane, p.M, p.Hr, p.Wr, 0, 0);
-}
-#endif   // LPM_TUNE
 
 // Sum of one element's split-K partials in split order.  The loads are issued eight at a time before the first add (a
 // plain loop over a run-time split count waits for every load in turn); the additions keep the order.
@@ -793,86 +680,24 @@ static IgemmPlan plan_igemm(int64_t M, int N, int Ktot, int ci) {
     // about 8 K tiles per block: timed alone a contraction is fastest at about 14, but inside a step, where two or
     // three kernels share the GPU and a K tile takes longer, shorter loops win (VGG-16/CIFAR: -5 % locked, -2 % overlapped)
     int kpb = 8;
-#ifdef LPM_TUNE
-    if (const char* e = getenv("LPM_T_KPB")) kpb = std::max(1, atoi(e));
-#endif
     int s = std::max(1, (kt64 + kpb / 2) / kpb);
     // no more blocks than fill the chip once -- except for a single row of tiles (a small-batch FC layer), which
     // only streams weights and needs many blocks in flight to cover the memory latency
     int64_t cap_blocks = 320;
-#ifdef LPM_TUNE
-    if (const char* e = getenv("LPM_T_CAP")) cap_blocks = std::max(1, atoi(e));
-#endif
     const int64_t cap = (M <= 64 ? 1024 : cap_blocks) / tiles;
     s = (int)std::min<int64_t>(s, std::max<int64_t>(1, cap));
     s = std::min(s, pl.kt_total);
     pl.splits = std::max(1, s);
-#ifdef LPM_TUNE      // measurement builds only: override the split count from the environment
-    if (const char* e = getenv("LPM_T_SPLITS")) { pl.splits = std::max(1, std::min(atoi(e), pl.kt_total)); }
-#endif
     pl.kt_per = (pl.kt_total + pl.splits - 1) / pl.splits;
     pl.splits = (pl.kt_total + pl.kt_per - 1) / pl.kt_per;
     return pl;
 }
 
-#ifdef LPM_TUNE
-template <int MODE>
-static bool igemm_dl_ok(const IgemmPlan& pl, const IgemmArgs& a) {
-    if (MODE == MODE_DGRAD_S || pl.bk != 64 || a.Kh * a.Kw > 64 || a.Kh * a.Kw < 1) return false;
-    const char* e = getenv("LPM_T_DL");
-    return e && atoi(e) != 0;
-}
-
-template <int MODE, int NST>
-static void launch_igemm_dl_n(const dim3& grid, const IgemmArgs& a, hipStream_t st) {
-    constexpr int M2 = MODE == MODE_DGRAD_S ? MODE_DGRAD : MODE;     // (never launched for the strided form)
-    const int bytes = NST * DL_STAGE;
-    static const hipError_t attr = hipFuncSetAttribute((const void*)igemm_dl_kernel<M2, NST>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    (void)attr;
-    hipLaunchKernelGGL((igemm_dl_kernel<M2, NST>), grid, dim3(256), bytes, st, a);
-}
-template <int MODE>
-static void launch_igemm_dl(const dim3& grid, const IgemmArgs& a, hipStream_t st) {
-    if (const char* e = getenv("LPM_T_NST")) {
-        if (atoi(e) == 3) { launch_igemm_dl_n<MODE, 3>(grid, a, st); return; }
-        if (atoi(e) == 4) { launch_igemm_dl_n<MODE, 4>(grid, a, st); return; }
-    }
-    launch_igemm_dl_n<MODE, 2>(grid, a, st);
-}
-
-#endif   // LPM_TUNE
 
 template <int MODE>
 static void launch_igemm_cfg(const IgemmPlan& pl, const IgemmArgs& a, hipStream_t st) {
-#ifdef LPM_TUNE      // measurement builds only: other block / wavefront tile shapes, chosen from the environment
-    if (MODE != MODE_DGRAD_S && a.Ci % 64 == 0) {
-        const int cfg = getenv("LPM_T_CFG") ? atoi(getenv("LPM_T_CFG")) : 0;
-#define LPM_CFG(ID, BM_, BN_, BK_, WGM_, WGN_)                                                                      \
-        if (cfg == ID) {                                                                                            \
-            const dim3 grid((unsigned)(((a.M + BM_ - 1) / BM_) * ((a.N + BN_ - 1) / BN_)), 1, pl.splits);           \
-            IgemmArgs b = a;                                                                                        \
-            b.kt_total = a.Ktot / BK_;                                                                              \
-            b.kt_per_split = (b.kt_total + pl.splits - 1) / pl.splits;                                              \
-            hipLaunchKernelGGL((igemm_kernel<BM_, BN_, BK_, WGM_, WGN_, MODE>), grid, dim3(256), 0, st, b);          \
-            return;                                                                                                 \
-        }
-        LPM_CFG(1, 128, 64, 64, 4, 1)
-        LPM_CFG(2, 128, 64, 64, 2, 2)
-        LPM_CFG(3, 64, 128, 64, 1, 4)
-        LPM_CFG(4, 128, 128, 64, 2, 2)
-        LPM_CFG(5, 128, 128, 32, 2, 2)
-        LPM_CFG(6, 256, 64, 32, 4, 1)
-        LPM_CFG(7, 128, 128, 64, 4, 1)
-        LPM_CFG(8, 256, 128, 32, 4, 1)
-        LPM_CFG(9, 256, 128, 32, 2, 2)
-#undef LPM_CFG
-    }
-#endif
     const int mt = a.m_tiles ? a.m_tiles : (a.M + 63) / 64;
     const dim3 grid((unsigned)(mt * ((a.N + 63) / 64)), 1, pl.splits);
-#ifdef LPM_TUNE
-    if (igemm_dl_ok<MODE>(pl, a)) { launch_igemm_dl<MODE>(grid, a, st); return; }
-#endif
     if (pl.bk == 64) hipLaunchKernelGGL((igemm_kernel<64, 64, 64, 2, 2, MODE>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((igemm_kernel<64, 64, 32, 2, 2, MODE>), grid, dim3(256), 0, st, a);
 }
@@ -991,8 +816,8 @@ struct WgradArgs {
     const uint16_t* X;
     const uint16_t* DZ;
     float* out;            // dW, or the partials base when splits > 1
-    float* db;             // bias gradient (column sums of dz, divided by bscale), or NULL
-    const float* bscale;   // per-channel scale the layer applied after the bias-free pre-activation, or NULL
+    float* db;             // bias gradient (column sums of dz), or NULL
+    const float* rscale;   // the layer's per-channel scale, or NULL: dz is the gradient before that scale, so row co of dW is multiplied by it
     size_t part_stride;    // floats between the partials of consecutive splits (>= Cout*K + Cout)
     unsigned dz_bytes, x_bytes;   // extents of DZ and X for the buffer resources
     int Cout, Cin, KhKw, Kw;
@@ -1211,8 +1036,7 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
         const int co = co0 + tid;
         if (p.splits > 1) out[total + co] = bsum;
         else {
-            const float v = p.bscale ? bsum / p.bscale[co] : bsum;
-            p.db[co] = p.accumulate ? p.db[co] + v : v;
+            p.db[co] = p.accumulate ? p.db[co] + bsum : bsum;
         }
     }
     const int col_l = lane & 31, rq = (lane >> 5) * 4;
@@ -1228,6 +1052,7 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
                 if (co >= p.Cout) continue;
                 const size_t o = ((size_t)co * p.KhKw + tap) * p.Cin + ci;
                 float v = acc[mi][ni][i];
+                if (p.splits == 1 && p.rscale) v *= p.rscale[co];
                 if (p.splits == 1 && p.accumulate) v += out[o];
                 out[o] = v;
             }
@@ -1256,18 +1081,6 @@ static WgradPlan plan_wgrad(const ConvGeom& g) {
     const int64_t wbytes = (int64_t)g.Cout * g.K() * 4;
     while (s > 1 && wbytes * s > (256ll << 20)) --s;
     if (s < 1) s = 1;
-#ifdef LPM_TUNE
-    if (const char* e = getenv("LPM_T_BIG")) {
-        pl.big = atoi(e);
-        pl.bk = pl.big ? 64 : (R > 64 ? 128 : 64);
-        if (const char* b = getenv("LPM_T_BK")) if (!pl.big) pl.bk = atoi(b) >= 128 ? 128 : 64;
-        pl.rt_total = (int)((R + pl.bk - 1) / pl.bk);
-        const int t2 = pl.big ? 128 : 64;
-        pl.co_tiles = (g.Cout + t2 - 1) / t2;
-        pl.ci_tiles = (g.Cin + t2 - 1) / t2;
-    }
-    if (const char* e = getenv("LPM_T_SPLITS")) s = std::max(1, std::min(atoi(e), pl.rt_total));
-#endif
     pl.rt_per = (pl.rt_total + s - 1) / s;
     pl.splits = (pl.rt_total + pl.rt_per - 1) / pl.rt_per;
     return pl;
@@ -1280,7 +1093,7 @@ size_t mfma_wgrad_ws_bytes(const ConvGeom& g) {
     return pl.splits > 1 ? (size_t)pl.splits * ((size_t)g.Cout * g.K() + g.Cout) * sizeof(float) : 0;
 }
 
-// dbias (may be NULL): also produce the bias gradient, the per-channel sum of dz divided by bscale (may be NULL)
+// dbias (may be NULL): also produce the bias gradient, the per-channel sum of dz; rscale (may be NULL): per-row factor of dW
 struct ReduceBatchArgs {
     ReduceDesc d[LPM_REDUCE_BATCH];
     int64_t first[LPM_REDUCE_BATCH + 1];     // first thread of every reduction (a thread sums four outputs)
@@ -1297,7 +1110,7 @@ __global__ void __launch_bounds__(256) wgrad_reduce_batch(ReduceBatchArgs a) {
     const ReduceDesc& d = a.d[k];
     const int64_t i = (t - a.first[k]) * 4;
     if (i >= d.n + d.nb) return;              // padding up to a whole block
-    if (i + 4 <= d.n && (d.stride & 3) == 0) {
+    if (i + 4 <= d.n && (d.stride & 3) == 0 && (d.row_len & 3) == 0) {
         float4 c[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) c[j] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -1319,6 +1132,10 @@ __global__ void __launch_bounds__(256) wgrad_reduce_batch(ReduceBatchArgs a) {
         }
         float4 r = make_float4((c[0].x + c[1].x) + (c[2].x + c[3].x), (c[0].y + c[1].y) + (c[2].y + c[3].y),
                                (c[0].z + c[1].z) + (c[2].z + c[3].z), (c[0].w + c[1].w) + (c[2].w + c[3].w));
+        if (d.rscale) {                           // (row_len is a multiple of 4 on this path: the four outputs share a row)
+            const float f = d.rscale[i / d.row_len];
+            r.x *= f; r.y *= f; r.z *= f; r.w *= f;
+        }
         float4* o = reinterpret_cast<float4*>(d.dst + i);
         if (d.accumulate) { const float4 q = *o; r.x += q.x; r.y += q.y; r.z += q.z; r.w += q.w; }
         *o = r;
@@ -1327,10 +1144,11 @@ __global__ void __launch_bounds__(256) wgrad_reduce_batch(ReduceBatchArgs a) {
     for (int64_t e = i; e < i + 4 && e < d.n + d.nb; ++e) {
         float acc = d.part[e];
         for (int s = 1; s < d.splits; ++s) acc += d.part[(size_t)s * d.stride + e];
-        if (e < d.n) d.dst[e] = d.accumulate ? d.dst[e] + acc : acc;
-        else {
+        if (e < d.n) {
+            if (d.rscale) acc *= d.rscale[e / d.row_len];
+            d.dst[e] = d.accumulate ? d.dst[e] + acc : acc;
+        } else {
             const int c = (int)(e - d.n);
-            if (d.bscale) acc /= d.bscale[c];
             d.db[c] = d.accumulate ? d.db[c] + acc : acc;
         }
     }
@@ -1358,7 +1176,7 @@ hipError_t launch_reduce_batch(const ReduceDesc* d, int count, hipStream_t st) {
     return hipSuccess;
 }
 
-hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* bscale,
+hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* rscale,
                            int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred) {
     const WgradPlan pl = plan_wgrad(g);
     WgradArgs a{};
@@ -1367,7 +1185,7 @@ hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, flo
     a.Cout = g.Cout; a.Cin = g.Cin; a.KhKw = g.Kh * g.Kw; a.Kw = g.Kw;
     a.H = g.H; a.W = g.W; a.Ho = g.Ho; a.Wo = g.Wo; a.stride = g.stride; a.pad = g.pad;
     a.R = (int)g.rows_out();
-    a.db = dbias; a.bscale = bscale;
+    a.db = dbias; a.rscale = rscale;
     a.part_stride = (size_t)g.Cout * g.K() + g.Cout;
     a.dz_bytes = (unsigned)(g.rows_out() * g.Cout * 2); a.x_bytes = (unsigned)(g.rows_in() * g.Cin * 2);
     a.rt_total = pl.rt_total; a.rt_per_split = pl.rt_per; a.splits = pl.splits;
@@ -1382,7 +1200,7 @@ hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, flo
     const int64_t n = (int64_t)g.Cout * g.K();
     const int nb = dbias ? g.Cout : 0;
     // one reduction kernel whether it runs now or batched with the stage's other layers: the same summation order
-    const ReduceDesc d{(const float*)ws, a.part_stride, pl.splits, dw, n, dbias, nb, bscale, accumulate};
+    const ReduceDesc d{(const float*)ws, a.part_stride, pl.splits, dw, n, dbias, nb, rscale, g.K(), accumulate};
     if (deferred) { *deferred = d; return hipSuccess; }
     return launch_reduce_batch(&d, 1, st);
 }
@@ -1392,7 +1210,7 @@ hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, flo
 // added in lane order -- a fixed order, with 8 loads in flight per output instead of one.
 __global__ void __launch_bounds__(256) wgrad_reduce_short(const float* __restrict__ part, size_t stride, int splits,
                                                           float* __restrict__ dst, int64_t n, float* __restrict__ db, int nb,
-                                                          const float* __restrict__ bscale, int accumulate) {
+                                                          const float* __restrict__ rscale, int row_len, int accumulate) {
     __shared__ float red[8][32];
     const int o = threadIdx.x & 31, l = threadIdx.x >> 5;
     const int64_t i = (int64_t)blockIdx.x * 32 + o;
@@ -1408,10 +1226,11 @@ __global__ void __launch_bounds__(256) wgrad_reduce_short(const float* __restric
     float v = red[0][o];
 #pragma unroll
     for (int k = 1; k < 8; ++k) v += red[k][o];
-    if (i < n) dst[i] = accumulate ? dst[i] + v : v;
-    else {
+    if (i < n) {
+        if (rscale) v *= rscale[i / row_len];
+        dst[i] = accumulate ? dst[i] + v : v;
+    } else {
         const int c = (int)(i - n);
-        if (bscale) v /= bscale[c];
         db[c] = accumulate ? db[c] + v : v;
     }
 }
@@ -1428,10 +1247,6 @@ static WgradPlan plan_wgrad_flat(const ConvGeom& g) {
     pl.ci_tiles = 1;
     // the 2-byte gathers make a pixel tile slow (about 2 us), so blocks take as few as two of them
     int s = std::min(std::min(512 / pl.co_tiles, std::max(1, pl.rt_total / 2)), 256);
-#ifdef LPM_TUNE
-    if (const char* e = getenv("LPM_T_SPLITS")) s = std::max(1, std::min(atoi(e), pl.rt_total));
-    if (const char* e = getenv("LPM_T_BK")) { pl.bk = atoi(e) >= 128 ? 128 : 64; pl.rt_total = (int)((R + pl.bk - 1) / pl.bk); }
-#endif
     pl.rt_per = (pl.rt_total + s - 1) / s;
     pl.splits = (pl.rt_total + pl.rt_per - 1) / pl.rt_per;
     return pl;
@@ -1443,7 +1258,7 @@ size_t mfma_wgrad_flat_ws_bytes(const ConvGeom& g) {
 }
 
 hipError_t mfma_conv_wgrad_flat(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias,
-                                const float* bscale, int accumulate, void* ws, hipStream_t st) {
+                                const float* rscale, int accumulate, void* ws, hipStream_t st) {
     const WgradPlan pl = plan_wgrad_flat(g);
     WgradArgs a{};
     a.X = (const uint16_t*)x; a.DZ = (const uint16_t*)dz;
@@ -1452,7 +1267,7 @@ hipError_t mfma_conv_wgrad_flat(const ConvGeom& g, const void* x, const void* dz
     a.x_cin = g.Cin; a.x_taps = g.Kh * g.Kw;
     a.H = g.H; a.W = g.W; a.Ho = g.Ho; a.Wo = g.Wo; a.stride = g.stride; a.pad = g.pad;
     a.R = (int)g.rows_out();
-    a.db = dbias; a.bscale = bscale;
+    a.db = dbias; a.rscale = rscale;
     a.part_stride = (size_t)g.Cout * g.K() + g.Cout;
     a.dz_bytes = (unsigned)(g.rows_out() * g.Cout * 2); a.x_bytes = (unsigned)(g.rows_in() * g.Cin * 2);
     a.rt_total = pl.rt_total; a.rt_per_split = pl.rt_per; a.splits = pl.splits;
@@ -1466,7 +1281,7 @@ hipError_t mfma_conv_wgrad_flat(const ConvGeom& g, const void* x, const void* dz
     const int64_t n = (int64_t)g.Cout * g.K();
     const int nb = dbias ? g.Cout : 0;
     hipLaunchKernelGGL(wgrad_reduce_short, dim3((unsigned)((n + nb + 31) / 32)), dim3(256), 0, st, (const float*)ws,
-                       a.part_stride, pl.splits, dw, n, dbias, nb, bscale, accumulate);
+                       a.part_stride, pl.splits, dw, n, dbias, nb, rscale, g.K(), accumulate);
     return hipGetLastError();
 }
 

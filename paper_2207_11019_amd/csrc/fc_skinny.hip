@@ -33,8 +33,9 @@ __device__ __forceinline__ void unpack8(const uint4 v, float (&f)[8]) {
 constexpr int FCD_COLS = 512, FCD_MAX_CPS = 256;
 
 template <int MB>
-__global__ void __launch_bounds__(256) fc_dgrad_skinny(const uint16_t* __restrict__ dz, const uint16_t* __restrict__ w,
-                                                       float* __restrict__ part, int m, int Cout, int K, int cps) {
+__global__ void __launch_bounds__(256) fc_dgrad_skinny(const uint16_t* __restrict__ dz, const float* __restrict__ dzscale,
+                                                       const uint16_t* __restrict__ w, float* __restrict__ part, int m, int Cout,
+                                                       int K, int cps) {
     __shared__ float dzs[MB][FCD_MAX_CPS];
     __shared__ float red[MB][FCD_COLS];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -43,7 +44,7 @@ __global__ void __launch_bounds__(256) fc_dgrad_skinny(const uint16_t* __restric
     const int c0 = blockIdx.y * cps, cn = min(cps, Cout - c0);
     for (int i = tid; i < MB * cn; i += 256) {
         const int r = i / cn, c = i - r * cn;
-        dzs[r][c] = r < m ? bf2f(dz[(size_t)r * Cout + c0 + c]) : 0.f;
+        dzs[r][c] = r < m ? bf2f(dz[(size_t)r * Cout + c0 + c]) * (dzscale ? dzscale[c0 + c] : 1.f) : 0.f;
     }
     __syncthreads();
     float acc[MB][8];
@@ -126,12 +127,13 @@ static FcDgradPlan plan_fc_dgrad(const ConvGeom& g) {
 
 size_t fc_dgrad_ws_bytes(const ConvGeom& g) { return (size_t)plan_fc_dgrad(g).splits * g.m * g.K() * sizeof(float); }
 
-hipError_t fc_dgrad(const ConvGeom& g, const void* dz, const void* w, void* dx, int accumulate, const void* mask,
+// dzscale (may be NULL): dz is the gradient before the layer's per-channel scale; channel co is multiplied by dzscale[co]
+hipError_t fc_dgrad(const ConvGeom& g, const void* dz, const float* dzscale, const void* w, void* dx, int accumulate, const void* mask,
                     const float* mscale, void* ws, hipStream_t st) {
     const FcDgradPlan p = plan_fc_dgrad(g);
     const dim3 grid((unsigned)p.colblocks, (unsigned)p.splits);
     const int K = g.K();
-#define LPM_FCD(MB) hipLaunchKernelGGL((fc_dgrad_skinny<MB>), grid, dim3(256), 0, st, (const uint16_t*)dz, (const uint16_t*)w, \
+#define LPM_FCD(MB) hipLaunchKernelGGL((fc_dgrad_skinny<MB>), grid, dim3(256), 0, st, (const uint16_t*)dz, dzscale, (const uint16_t*)w, \
                                        (float*)ws, g.m, g.Cout, K, p.cps)
     if (g.m <= 4) LPM_FCD(4);
     else LPM_FCD(8);
@@ -143,7 +145,8 @@ hipError_t fc_dgrad(const ConvGeom& g, const void* dz, const void* w, void* dx, 
                                   mask, mscale, dx, st);
 }
 
-// ---- weight gradient: dW[co][k] (+)= sum_r dz[r][co] * x[r][k];  db[co] (+)= (sum_r dz[r][co]) / bscale[co] ----
+// ---- weight gradient: dW[co][k] (+)= rscale[co] * sum_r dz[r][co] * x[r][k];  db[co] (+)= sum_r dz[r][co] ----
+// (rscale, may be NULL: the layer's per-channel scale; dz is the gradient before that scale)
 // A thread keeps its 8 columns of every sample in registers and walks the block's output channels, reading
 // (when accumulating) and writing 32 bytes of dW per channel: one pass over the gradient matrix.
 constexpr int FCW_CPB = 16;
@@ -151,7 +154,7 @@ constexpr int FCW_CPB = 16;
 template <int MB>
 __global__ void __launch_bounds__(256) fc_wgrad_skinny(const uint16_t* __restrict__ x, const uint16_t* __restrict__ dz,
                                                        float* __restrict__ dw, float* __restrict__ db,
-                                                       const float* __restrict__ bscale, int m, int Cout, int K,
+                                                       const float* __restrict__ rscale, int m, int Cout, int K,
                                                        int accumulate) {
     __shared__ float dzs[MB][FCW_CPB];
     const int tid = threadIdx.x;
@@ -167,8 +170,15 @@ __global__ void __launch_bounds__(256) fc_wgrad_skinny(const uint16_t* __restric
 #pragma unroll
         for (int r = 0; r < MB; ++r) s += dzs[r][tid];
         const int co = c0 + tid;
-        if (bscale) s /= bscale[co];
         db[co] = accumulate ? db[co] + s : s;
+    }
+    if (rscale) {                                   // from here on the block's dz values carry the layer's scale
+        __syncthreads();
+        for (int i = tid; i < MB * FCW_CPB; i += blockDim.x) {
+            const int c = i % FCW_CPB;
+            if (c < cn) dzs[i / FCW_CPB][c] *= rscale[c0 + c];
+        }
+        __syncthreads();
     }
     if (k0 >= K) return;
     float xr[MB][8];
@@ -206,13 +216,13 @@ __global__ void __launch_bounds__(256) fc_wgrad_skinny(const uint16_t* __restric
     }
 }
 
-hipError_t fc_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* bscale,
+hipError_t fc_wgrad(const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias, const float* rscale,
                     int accumulate, hipStream_t st) {
     const int K = g.K();
     const int threads = std::min(256, ((K / 8 + 63) / 64) * 64);
     const dim3 grid((unsigned)((K / 8 + threads - 1) / threads), (unsigned)((g.Cout + FCW_CPB - 1) / FCW_CPB));
 #define LPM_FCW(MB) hipLaunchKernelGGL((fc_wgrad_skinny<MB>), grid, dim3(threads), 0, st, (const uint16_t*)x, (const uint16_t*)dz, \
-                                       dw, dbias, bscale, g.m, g.Cout, K, accumulate)
+                                       dw, dbias, rscale, g.m, g.Cout, K, accumulate)
     if (g.m <= 4) LPM_FCW(4);
     else LPM_FCW(8);
 #undef LPM_FCW
@@ -249,7 +259,7 @@ hipError_t stage_operands(const ConvGeom& g, const void* x, const void* dz, void
 constexpr int FCR_CPB = 16;
 __global__ void __launch_bounds__(256) fc_wgrad_rows(const uint16_t* __restrict__ x, const uint16_t* __restrict__ dz,
                                                      float* __restrict__ dw, float* __restrict__ db,
-                                                     const float* __restrict__ bscale, int R, int Cout, int K, int accumulate) {
+                                                     const float* __restrict__ rscale, int R, int Cout, int K, int accumulate) {
     extern __shared__ float dzr[];               // [R rounded up to 8][FCR_CPB]
     const int tid = threadIdx.x;
     const int k0 = (blockIdx.x * blockDim.x + tid) * 8;
@@ -264,8 +274,15 @@ __global__ void __launch_bounds__(256) fc_wgrad_rows(const uint16_t* __restrict_
         float sum = 0.f;
         for (int r = 0; r < R; ++r) sum += dzr[r * FCR_CPB + tid];
         const int co = c0 + tid;
-        if (bscale) sum /= bscale[co];
         db[co] = accumulate ? db[co] + sum : sum;
+    }
+    if (rscale) {
+        __syncthreads();
+        for (int i = tid; i < R8 * FCR_CPB; i += blockDim.x) {
+            const int c = i % FCR_CPB;
+            if (c < cn) dzr[i] *= rscale[c0 + c];
+        }
+        __syncthreads();
     }
     if (k0 >= K) return;
     float acc[FCR_CPB][8];
@@ -312,13 +329,13 @@ __global__ void __launch_bounds__(256) fc_wgrad_rows(const uint16_t* __restrict_
 
 // contraction over the first `slots` staged micro-batches
 hipError_t fc_wgrad_staged(const ConvGeom& g, const void* xs, const void* dzs, int slots, float* dw, float* dbias,
-                           const float* bscale, int accumulate, hipStream_t st) {
+                           const float* rscale, int accumulate, hipStream_t st) {
     const int K = g.K(), R = slots * g.m;
     const int threads = std::min(256, ((K / 8 + 63) / 64) * 64);
     const dim3 grid((unsigned)((K / 8 + threads - 1) / threads), (unsigned)((g.Cout + FCR_CPB - 1) / FCR_CPB));
     const size_t lds = (size_t)((R + 7) & ~7) * FCR_CPB * sizeof(float);
     hipLaunchKernelGGL(fc_wgrad_rows, grid, dim3(threads), lds, st, (const uint16_t*)xs, (const uint16_t*)dzs, dw, dbias,
-                       bscale, R, g.Cout, K, accumulate);
+                       rscale, R, g.Cout, K, accumulate);
     return hipGetLastError();
 }
 

@@ -59,9 +59,9 @@ hipError_t conv_fwd_generic_launch(int dtype, const ConvGeom& g, const void* x, 
 // --------------------------------------------------------------------------------------------------
 // data gradient, eq. 9: dx[n,h,w,ci] (+)= sum_{kh,kw,co} dz[n,(h+p-kh)/s,(w+p-kw)/s,co] * w[co,kh,kw,ci]
 template <typename T>
-__global__ void __launch_bounds__(256) conv_dgrad_generic(ConvGeom g, const T* __restrict__ dz, const T* __restrict__ w,
-                                                          T* __restrict__ dx, int accumulate, const T* __restrict__ mask,
-                                                          const float* __restrict__ mscale) {
+__global__ void __launch_bounds__(256) conv_dgrad_generic(ConvGeom g, const T* __restrict__ dz, const float* __restrict__ dzscale,
+                                                          const T* __restrict__ w, T* __restrict__ dx, int accumulate,
+                                                          const T* __restrict__ mask, const float* __restrict__ mscale) {
     const int64_t total = g.rows_in() * g.Cin;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
@@ -82,7 +82,8 @@ __global__ void __launch_bounds__(256) conv_dgrad_generic(ConvGeom g, const T* _
             const T* dp = dz + (((int64_t)n * g.Ho + ho) * g.Wo + wo) * g.Cout;
             const T* wp = w + ((int64_t)kh * g.Kw + kw) * g.Cin + ci;
             const int64_t wstride = (int64_t)g.Kh * g.Kw * g.Cin;
-            for (int co = 0; co < g.Cout; ++co) acc = fmaf(ld(dp, co), ld(wp, co * wstride), acc);
+            if (dzscale) { for (int co = 0; co < g.Cout; ++co) acc = fmaf(ld(dp, co) * dzscale[co], ld(wp, co * wstride), acc); }
+            else { for (int co = 0; co < g.Cout; ++co) acc = fmaf(ld(dp, co), ld(wp, co * wstride), acc); }
         }
     }
     if (accumulate) acc += ld(dx, idx);
@@ -91,11 +92,11 @@ __global__ void __launch_bounds__(256) conv_dgrad_generic(ConvGeom g, const T* _
     st(dx, idx, acc);
 }
 
-hipError_t conv_dgrad_generic_launch(int dtype, const ConvGeom& g, const void* dz, const void* w, void* dx,
+hipError_t conv_dgrad_generic_launch(int dtype, const ConvGeom& g, const void* dz, const float* dzscale, const void* w, void* dx,
                                      int accumulate, const void* mask, const float* mscale, hipStream_t s) {
     const int64_t total = g.rows_in() * g.Cin;
     LPM_DISPATCH(dtype, hipLaunchKernelGGL(conv_dgrad_generic<T>, dim3(nblk(total, 256)), dim3(256), 0, s, g,
-                                           (const T*)dz, (const T*)w, (T*)dx, accumulate, (const T*)mask, mscale));
+                                           (const T*)dz, dzscale, (const T*)w, (T*)dx, accumulate, (const T*)mask, mscale));
     return hipGetLastError();
 }
 
@@ -571,7 +572,9 @@ __global__ void __launch_bounds__(1024) softmax_ce_kernel(int m, int C, const T*
                 for (int c = lane; c < C; c += 64) se += expf(ld(zr, c) - mx);
             }
             se = wave_sum(se);
+            // a label outside [0, C) selects no class: no one-hot term, and the row's loss becomes NaN so the host sees it
             const int lab = labels[base + r];
+            const bool lab_ok = (unsigned)lab < (unsigned)C;
             const float inv = 1.f / se;
             if (cached) {
 #pragma unroll
@@ -585,7 +588,7 @@ __global__ void __launch_bounds__(1024) softmax_ce_kernel(int m, int C, const T*
                     st(dr, c, (p - (c == lab ? 1.f : 0.f)) * loss_scale);
                 }
             }
-            if (lane == 0) rowloss[r] = logf(se) - (ld(zr, lab) - mx);
+            if (lane == 0) rowloss[r] = lab_ok ? logf(se) - (ld(zr, lab) - mx) : __builtin_nanf("");
         }
         __syncthreads();
         if (threadIdx.x == 0)
@@ -677,7 +680,8 @@ hipError_t launch_f32_to_bf16(const float* src, uint16_t* dst, size_t n, hipStre
     return hipGetLastError();
 }
 
-// dst[ci][k][co] = bf16(src[co][k][ci])   (k = kh*Kw+kw), for up to LPM_TRANSPOSE_BATCH weight tensors in one launch.
+// dst[ci][k][co] = bf16(src[co][k][ci] * scale[co])   (k = kh*Kw+kw; scale may be NULL), for up to LPM_TRANSPOSE_BATCH weight
+// tensors in one launch.
 // A block moves a 32 (co) x 32 (ci) tile of one filter tap through LDS: reads run along ci, writes along co.
 struct TransposeBatchArgs {
     TransposeDesc d[LPM_TRANSPOSE_BATCH];
@@ -699,7 +703,7 @@ __global__ void __launch_bounds__(256) weight_transpose_batch(TransposeBatchArgs
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int co = co0 + ly + r * 8, ci = ci0 + lx;
-        tile[ly + r * 8][lx] = (co < d.Cout && ci < d.Cin) ? d.src[((size_t)co * d.KK + kk) * d.Cin + ci] : 0.f;
+        tile[ly + r * 8][lx] = (co < d.Cout && ci < d.Cin) ? d.src[((size_t)co * d.KK + kk) * d.Cin + ci] * (d.scale ? d.scale[co] : 1.f) : 0.f;
     }
     __syncthreads();
 #pragma unroll

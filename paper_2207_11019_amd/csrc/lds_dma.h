@@ -25,7 +25,12 @@ __device__ __forceinline__ void load_to_lds16(u32x4_ rs, const unsigned char* ds
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :
                  : "s"(d), "v"(off), "s"(rs)
-                 : "memory");      // (M0 is a reserved register: the compiler sets it immediately before each of its own uses)
+                 : "memory");
+    // M0 is not on the clobber list on purpose: the compiler treats it as a reserved register (it rejects the entry with
+    // "clobber list contains reserved registers: m0"), which means it never keeps a value in M0 across statements and
+    // writes M0 itself immediately before each instruction of its own that reads it.  Were that to change, the weight
+    // gradients of the patch-based kernel would land in the wrong LDS stage: its layer-level parity tests compare every
+    // output element with the fp64 result and would fail.
 }
 
 // wait until at most min(rem, MAXT) * LPT of this wavefront's loads are outstanding (the count is an immediate)

@@ -73,23 +73,27 @@ struct UnpoolDesc { const void* pool_x; void* dst; int accumulate; int mask; con
 //   dx = m * mscale_c (the producer's dz);   shortcut (+)= m * shortcut_scale_c (the gradient of the producer's shortcut
 //   tensor, may be NULL; with a scale: the dz of the scale-only layer -- a projection -- that made the shortcut)
 struct DgradSide { const void* earlier; void* shortcut; int shortcut_acc; const float* shortcut_scale; };
+// dzscale (may be NULL): dz is the gradient before the layer's own per-channel scale.  The kernels that read w multiply
+// channel co of dz by dzscale[co]; wt, when given, must then already carry the factor (wt[ci][kh][kw][co] = w[co][kh][kw][ci] * dzscale[co]).
 hipError_t launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dz, const void* w, const void* wt,
                              void* dx, int accumulate, const void* mask, const float* mscale, void* ws, hipStream_t st,
-                             const UnpoolDesc* unpool = nullptr, const DgradSide* side = nullptr);
+                             const UnpoolDesc* unpool = nullptr, const DgradSide* side = nullptr, const float* dzscale = nullptr);
 bool dgrad_has_side(int dtype, const ConvGeom& g);
 bool dgrad_can_unpool(int dtype, const ConvGeom& g);
 // dw (+)= sum over pixels of dz (x) x         ws: split-reduction partials (wgrad_ws_bytes)
-// dbias (may be NULL, only when wgrad_fuses_bias): dbias (+)= (sum over pixels of dz) / bscale_c
+// dbias (may be NULL, only when wgrad_fuses_bias): dbias (+)= sum over pixels of dz
+// rscale (may be NULL): dz is the gradient before the layer's per-channel scale; row co of dw is multiplied by rscale[co]
 // deferred (may be NULL): when the kernel leaves split partials, describe their reduction there instead of launching
 // it (deferred->splits stays 0 when nothing is left to do); the caller runs launch_reduce_batch later on the stream.
 struct ReduceDesc {
     const float* part; size_t stride; int splits;      // partial s of output i at part[s*stride + i]
     float* dst; int64_t n;                              // dst[i] (+)= sum_s part, i < n
-    float* db; int nb; const float* bscale;             // db[c] (+)= (sum_s part[s*stride + n + c]) / bscale[c], c < nb
+    float* db; int nb;                                  // db[c] (+)= sum_s part[s*stride + n + c], c < nb
+    const float* rscale; int row_len;                   // (may be NULL) the sum of output i is multiplied by rscale[i / row_len]
     int accumulate;
 };
 hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const void* dz, float* dw, float* dbias,
-                             const float* bscale, int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred = nullptr);
+                             const float* rscale, int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred = nullptr);
 constexpr int LPM_REDUCE_BATCH = 24;
 // the reductions of up to LPM_REDUCE_BATCH weight gradients in one launch (each in its fixed split order)
 hipError_t launch_reduce_batch(const ReduceDesc* d, int count, hipStream_t st);
@@ -103,7 +107,7 @@ size_t wgrad_staged_ws_bytes(int dtype, const ConvGeom& g);      // split partia
 hipError_t stage_operands(const ConvGeom& g, const void* x, const void* dz, void* xs, void* dzs, int slot, hipStream_t st);
 // dw (+)= the gradient over `slots` staged micro-batches starting at xs / dzs; `deferred` as for launch_conv_wgrad
 hipError_t launch_wgrad_staged(int dtype, const ConvGeom& g, const void* xs, const void* dzs, int slots, float* dw, float* dbias,
-                               const float* bscale, int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred);
+                               const float* rscale, int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred);
 bool wgrad_fuses_bias(int dtype, const ConvGeom& g);
 bool dgrad_uses_wt(int dtype, const ConvGeom& g);
 size_t wgrad_ws_bytes(int dtype, const ConvGeom& g);
@@ -135,8 +139,9 @@ hipError_t launch_sgd(const float* p_in, float* p, uint16_t* lowp, float* g, flo
 hipError_t launch_adam(float* p, uint16_t* lowp, float* g, float* m1, float* m2, size_t n, float lr, float beta1, float beta2,
                        float eps, float inv_c1, float inv_c2, int zero_g, hipStream_t st);
 hipError_t launch_f32_to_bf16(const float* src, uint16_t* dst, size_t n, hipStream_t st);
-// dst[ci][kh][kw][co] = bf16(src[co][kh][kw][ci]) for a list of weight tensors, one launch per LPM_TRANSPOSE_BATCH of them
-struct TransposeDesc { const float* src; uint16_t* dst; int32_t Cout, KK, Cin; };
+// dst[ci][kh][kw][co] = bf16(src[co][kh][kw][ci] * scale[co]) for a list of weight tensors (scale may be NULL), one launch per
+// LPM_TRANSPOSE_BATCH of them
+struct TransposeDesc { const float* src; uint16_t* dst; int32_t Cout, KK, Cin; const float* scale; };
 constexpr int LPM_TRANSPOSE_BATCH = 24;
 hipError_t launch_weight_transpose_batch(const TransposeDesc* d, int count, hipStream_t st);
 hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t st);

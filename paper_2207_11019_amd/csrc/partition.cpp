@@ -183,6 +183,8 @@ static int32_t plan(const lpm_layer* layers, int32_t L, int32_t Z, const lpm_cos
         if (fixed_starts[0] != 0 || fixed_starts[Z] != L) return fail(LPM_ENOPLAN, "fixed plan must start at 0 and end at L");
         for (int32_t z = 1; z <= Z; ++z) {
             if (fixed_starts[z] <= fixed_starts[z - 1]) return fail(LPM_ENOPLAN, "fixed plan has an empty or reversed stage");
+            if (fixed_starts[z] > L || (z < Z && fixed_starts[z] >= L))          // (before the value indexes anything)
+                return fail(LPM_ENOPLAN, "fixed plan: stage %d would start at layer %d of %d", z, fixed_starts[z], L);
             if (z < Z && !P.allowed[fixed_starts[z] - 1])
                 return fail(LPM_ENOPLAN, "fixed plan cuts after layer %d, where no cut is allowed", fixed_starts[z] - 1);
         }

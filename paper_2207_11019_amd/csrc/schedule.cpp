@@ -31,39 +31,6 @@
 
 using namespace lpm;
 
-#ifdef LPM_TUNE      // measurement builds only: GPU time stamps of the chains of one step (LPM_T_TRACE=1), printed by lpm_trace_dump
-#include <cstdlib>
-#include <cstdio>
-#include <mutex>
-namespace {
-struct TraceEv { hipEvent_t e; const char* what; int z, j; };
-std::vector<TraceEv> g_trace;
-std::mutex g_trace_mu;
-void trace_mark(hipStream_t st, const char* what, int z, int j) {
-    if (!getenv("LPM_T_TRACE")) return;
-    hipEvent_t e;
-    if (hipEventCreate(&e) != hipSuccess) return;
-    (void)hipEventRecord(e, st);
-    std::lock_guard<std::mutex> lk(g_trace_mu);
-    g_trace.push_back(TraceEv{e, what, z, j});
-}
-}  // namespace
-extern "C" void lpm_trace_dump() {
-    (void)hipDeviceSynchronize();
-    std::lock_guard<std::mutex> lk(g_trace_mu);
-    if (g_trace.empty()) return;
-    for (const TraceEv& t : g_trace) {
-        float ms = 0.f;
-        (void)hipEventElapsedTime(&ms, g_trace[0].e, t.e);
-        printf("trace %-10s z%d j%d %9.1f us\n", t.what, t.z, t.j, ms * 1000.f);
-    }
-    for (const TraceEv& t : g_trace) (void)hipEventDestroy(t.e);
-    g_trace.clear();
-}
-#define LPM_TRACE(st, what, z, j) trace_mark(st, what, z, j)
-#else
-#define LPM_TRACE(st, what, z, j) ((void)0)
-#endif
 
 
 int32_t lpm_stage_prepare(lpm_stage* s);
@@ -373,9 +340,7 @@ int32_t overlapped_role(lpm_schedule* s, const RunArgs& a, int32_t role, uint64_
                 if ((rc = await_record(s, s->rec_w[i], epoch))) return rc;
                 LPM_HIP(hipStreamWaitEvent(a.sf, s->ev_w[i], 0));
             }
-            LPM_TRACE(a.sf, "F start", 0, j);
             for (int32_t z = 0; z < Z; ++z) if ((rc = fwd_op(s, a, z, j, a.sf, async ? forward_version(j, W) : -1))) return rc;
-            LPM_TRACE(a.sf, "F end", Z - 1, j);
             LPM_HIP(hipEventRecord(s->ev_f[(size_t)j * Z + Z - 1], a.sf));
             publish(s->rec_f[(size_t)j * Z + Z - 1], epoch);
         }
@@ -395,9 +360,7 @@ int32_t overlapped_role(lpm_schedule* s, const RunArgs& a, int32_t role, uint64_
                     if ((rc = await_record(s, s->rec_w[u], epoch))) return rc;
                     LPM_HIP(hipStreamWaitEvent(a.sb, s->ev_w[u], 0));
                 }
-                if (z == Z - 1) LPM_TRACE(a.sb, "Bd start", z, j);
                 if ((rc = bwd_op(s, a, z, j, a.sb, sw, LPM_PHASE_DATA, async ? j : -1, z == 0 && !async))) return rc;
-                LPM_TRACE(a.sb, "Bd end", z, j);
                 LPM_HIP(hipEventRecord(s->ev_b[(size_t)j * Z + z], a.sb));
                 publish(s->rec_b[(size_t)j * Z + z], epoch);
             }
@@ -424,7 +387,6 @@ int32_t overlapped_role(lpm_schedule* s, const RunArgs& a, int32_t role, uint64_
                 // whatever follows on this stream (the update, the record that closes the micro-batch) is still ordered
                 // after the whole data phase
                 if (by_layer) LPM_HIP(hipStreamWaitEvent(sw, s->ev_b[i], 0));
-                LPM_TRACE(sw, "W end", z, j);
                 if (async) {
                     if ((rc = upd_op(s, a, z, sw, j))) return rc;
                     if (j == M - 1 && (rc = copy_final_version(s, a, z, sw))) return rc;

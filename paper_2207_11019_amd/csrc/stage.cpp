@@ -92,6 +92,9 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
             lr.lowp_w_off = lr.w_off * 2;      // the bf16 copies mirror the float layout element for element
             if (dgrad_uses_wt(dtype, lr.g)) { lr.lowp_wt_off = lowp; lowp += align_up(lr.w_count * 2, 256); }   // rebased below
         }
+        // A scaled layer whose weight-gradient kernel also sums the bias gradient keeps dz free of the scale: the bias
+        // gradient is then the plain column sum of dz (eq. 8 for the bias), whatever the scale's value -- zero included.
+        lr.dz_unscaled = dtype == LPM_BF16 && (l.flags & LPM_SCALE) && wgrad_fuses_bias(dtype, lr.g);
         if (l.flags & (LPM_RELU | LPM_SCALE)) {          // needs its own dz buffer (it outlives the layer's turn)
             lr.dz_off = gws;
             gws += align_up(o.elems() * (size_t)microbatch * s->esz, 256);
@@ -304,7 +307,8 @@ static hipError_t transpose_copies(const lpm_stage* s, const float* params, void
     for (int32_t i = s->first; i < s->last; ++i) {
         const LayerRt& lr = s->Ly(i);
         if (lr.lowp_wt_off != NO)
-            d.push_back(TransposeDesc{params + lr.w_off, (uint16_t*)((char*)lowp + lr.lowp_wt_off), lr.d.cout, lr.d.kh * lr.d.kw, lr.d.cin});
+            d.push_back(TransposeDesc{params + lr.w_off, (uint16_t*)((char*)lowp + lr.lowp_wt_off), lr.d.cout, lr.d.kh * lr.d.kw, lr.d.cin,
+                                      lr.dz_unscaled ? params + lr.s_off : nullptr});
     }
     return d.empty() ? hipSuccess : launch_weight_transpose_batch(d.data(), (int)d.size(), st);
 }
@@ -511,7 +515,7 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                     if (!need_dz && !gadd && dbias && !bias_in_wgrad && deferred) {
                         bias_g = g;
                     } else if (need_dz || gadd || (dbias && !bias_in_wgrad)) {
-                        if (do_data) LPM_HIP(launch_epilogue_bwd(s->dtype, lr.g.rows_out(), l.cout, g, relu ? yout : nullptr, sc,
+                        if (do_data) LPM_HIP(launch_epilogue_bwd(s->dtype, lr.g.rows_out(), l.cout, g, relu ? yout : nullptr, lr.dz_unscaled ? nullptr : sc,
                                                     need_dz ? (void*)(gw + lr.dz_off) : nullptr, gadd, gadd_acc,
                                                     bias_in_wgrad ? nullptr : dbias, acc, kws, st));
                         if (need_dz) dz = gw + lr.dz_off;
@@ -540,7 +544,7 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                             unpool.dst = gw + pr.dz_off;
                             unpool.accumulate = 0;
                             unpool.mask = (pr.d.flags & LPM_RELU) != 0;
-                            unpool.mscale = pr.s_off != NO ? params + pr.s_off : nullptr;
+                            unpool.mscale = (pr.s_off != NO && !pr.dz_unscaled) ? params + pr.s_off : nullptr;
                         } else if (q == first - 1 && (boundary & LPM_MASK_DX)) {
                             unpool.mask = 1;
                         }
@@ -554,7 +558,7 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                         const LayerRt& pr = s->Ly(l.src);
                         gsrc = gw + pr.dz_off;
                         gmask = (pr.d.flags & LPM_RELU) ? tptr(s, l.src, x, y, stash) : nullptr;
-                        gmscale = pr.s_off != NO ? params + pr.s_off : nullptr;
+                        gmscale = (pr.s_off != NO && !pr.dz_unscaled) ? params + pr.s_off : nullptr;
                         if (pr.fused_side) {
                             // the producer sits in a residual block: what its shortcut users have already put into its output
                             // gradient is added, and the masked sum is also the gradient of the producer's own shortcut
@@ -563,7 +567,7 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                             const int32_t a = pr.d.add_src;
                             if (a != LPM_NONE && a >= first && s->Ly(a).via_shortcut) {
                                 side.shortcut = gw + s->Ly(a).dz_off;           // the projection's dz
-                                side.shortcut_scale = params + s->Ly(a).s_off;
+                                side.shortcut_scale = s->Ly(a).dz_unscaled ? nullptr : params + s->Ly(a).s_off;
                                 have[gi(a)] = 1;
                             } else if (a != LPM_NONE && (a >= first || dx != nullptr)) {
                                 side.shortcut = G[gi(a)];
@@ -580,13 +584,13 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                 }
                 const void* xin = tptr(s, l.src, x, y, stash);
                 if (deferred) {
-                    jobs.push_back(WgradJob{&lr, xin, dz, wdb, sc, bias_g, bias_g ? dbias : nullptr});
+                    jobs.push_back(WgradJob{&lr, xin, dz, wdb, lr.dz_unscaled ? sc : nullptr, bias_g, bias_g ? dbias : nullptr});
                 } else {
                     std::vector<hipGraphNode_t> before;
                     LPM_HIP(frontier(before));
                     if (!wtail.empty())       // weight gradients share one scratch area: keep them in a chain
                         LPM_HIP(hipStreamUpdateCaptureDependencies(st, wtail.data(), wtail.size(), hipStreamAddCaptureDependencies));
-                    LPM_HIP(one_wgrad(WgradJob{&lr, xin, dz, wdb, sc, nullptr, nullptr}, st, nullptr));
+                    LPM_HIP(one_wgrad(WgradJob{&lr, xin, dz, wdb, lr.dz_unscaled ? sc : nullptr, nullptr, nullptr}, st, nullptr));
                     LPM_HIP(frontier(wtail));
                     LPM_HIP(hipStreamUpdateCaptureDependencies(st, before.data(), before.size(), hipStreamSetCaptureDependencies));
                 }
@@ -596,10 +600,11 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                     const void* wt = (s->dtype == LPM_BF16 && lr.lowp_wt_off != NO)
                                          ? (const void*)((const char*)lowp + lr.lowp_wt_off) : nullptr;
                     if (lr.unpool_of >= 0) {
-                        if (do_data && unpool.dst) LPM_HIP(launch_conv_dgrad(s->dtype, lr.g, dz, w, wt, nullptr, 0, nullptr, nullptr, kws, st, &unpool));
+                        if (do_data && unpool.dst) LPM_HIP(launch_conv_dgrad(s->dtype, lr.g, dz, w, wt, nullptr, 0, nullptr, nullptr, kws, st, &unpool,
+                                                                             nullptr, lr.dz_unscaled ? sc : nullptr));
                     } else if (do_data) {
                         LPM_HIP(launch_conv_dgrad(s->dtype, lr.g, dz, w, wt, gsrc, gsrc_acc, gmask, gmscale, kws, st, nullptr,
-                                                  use_side ? &side : nullptr));
+                                                  use_side ? &side : nullptr, lr.dz_unscaled ? sc : nullptr));
                     }
                 }
                 break;
@@ -617,7 +622,7 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                         gsrc = gw + pr.dz_off;
                         gsrc_acc = 0;
                         gmask = (pr.d.flags & LPM_RELU) ? tptr(s, l.src, x, y, stash) : nullptr;
-                        gmscale = pr.s_off != NO ? params + pr.s_off : nullptr;
+                        gmscale = (pr.s_off != NO && !pr.dz_unscaled) ? params + pr.s_off : nullptr;
                     } else if (l.src == first - 1 && (boundary & LPM_MASK_DX)) {
                         gmask = x;
                     }

@@ -36,6 +36,9 @@ struct LayerRt {
     bool pooled_fwd = false;                     // max-pooling: its forward runs inside its producer's forward kernel
     bool unpooled = false;                       // max-pooling: its backward runs inside its consumer's data gradient
     bool fused_in = false;                       // its consumer's backward kernel writes dz directly (mask and scale fused)
+    bool dz_unscaled = false;                    // its dz buffer holds the gradient BEFORE the layer's per-channel scale: the weight-gradient
+                                                 // kernel multiplies row co of dW by scale[co] and sums dz for the bias gradient as it is, the
+                                                 // data gradient reads transposed weights that carry the scale (or scales dz as it loads it)
 };
 
 }  // namespace lpm

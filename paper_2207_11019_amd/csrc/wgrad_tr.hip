@@ -18,9 +18,6 @@
 #include "elem.h"
 #include "lds_dma.h"
 #include <algorithm>
-#ifdef LPM_TUNE
-#include <cstdlib>
-#endif
 
 namespace lpm {
 
@@ -33,8 +30,8 @@ struct WgradTrArgs {
     const uint16_t* X;
     const uint16_t* DZ;
     float* out;            // dW, or the partials base when splits > 1
-    float* db;             // bias gradient (sum of dz over the pixels, divided by bscale), or NULL
-    const float* bscale;
+    float* db;             // bias gradient (sum of dz over the pixels), or NULL
+    const float* rscale;   // the layer's per-channel scale, or NULL: row co of dW is multiplied by it (dz is the gradient before the scale)
     size_t part_stride;    // floats between the partials of consecutive splits (>= Cout*K + Cout)
     unsigned dz_bytes, x_bytes;
     int Cout, Cin, Kh, Kw, H, W, Ho, Wo, stride, pad;
@@ -214,8 +211,7 @@ __global__ void __launch_bounds__(256, 2) wgrad_tr_kernel(WgradTrArgs p) {
             if (co >= p.Cout) continue;
             if (p.splits > 1) out[total + co] = accb[i];
             else {
-                const float v = p.bscale ? accb[i] / p.bscale[co] : accb[i];
-                p.db[co] = p.accumulate ? p.db[co] + v : v;
+                p.db[co] = p.accumulate ? p.db[co] + accb[i] : accb[i];
             }
         }
     }
@@ -230,6 +226,7 @@ __global__ void __launch_bounds__(256, 2) wgrad_tr_kernel(WgradTrArgs p) {
                 if (co >= p.Cout) continue;
                 const size_t o = ((size_t)co * KhKw + tap) * p.Cin + ci;
                 float v = acc[t][i];
+                if (p.splits == 1 && p.rscale) v *= p.rscale[co];
                 if (p.splits == 1 && p.accumulate) v += out[o];
                 out[o] = v;
             }
@@ -272,9 +269,6 @@ static ConvGeom tr_view(const ConvGeom& g) {
 // m16 32x32x64->64), which adds up over a training step (ResNet-18/CIFAR: 5.34 -> 5.10 ms).  It takes every
 // shape whose patches are mostly inside the image.
 bool wgrad_tr_ok(const ConvGeom& g) {
-#ifdef LPM_TUNE
-    if (getenv("LPM_T_NOTR")) return false;
-#endif
     return tr_shape_ok(tr_view(g));
 }
 
@@ -296,17 +290,10 @@ static TrPlan plan_wgrad_tr(const ConvGeom& g) {
     int taps = (s33 && g.Cin >= 128 && g.Cout >= 128 && macs >= (int64_t)1000000000) ? 3 : 1;
     const int64_t base = (int64_t)pl.co_tiles * pl.ci_tiles * (KhKw / taps);
     int64_t target = 256;
-#ifdef LPM_TUNE
-    if (const char* e = getenv("LPM_T_TRBLOCKS")) target = std::max(1, atoi(e));
-#endif
     int64_t sp = std::max<int64_t>(1, target / base);
     sp = std::min<int64_t>(sp, std::max(1, pl.kt_total / 8));
     sp = std::min<int64_t>(sp, std::max<int64_t>(1, (64ll << 20) / out_bytes));
     int best_taps = taps, best_s = (int)sp;
-#ifdef LPM_TUNE
-    if (const char* e = getenv("LPM_T_TAPS")) { const int t = atoi(e); if (t == 1 || (s33 && (t == 3 || t == 9))) best_taps = t; }
-    if (const char* e = getenv("LPM_T_SPLITS")) best_s = std::max(1, std::min(atoi(e), pl.kt_total));
-#endif
     pl.taps = best_taps;
     pl.groups = KhKw / best_taps;
     pl.kt_per = (pl.kt_total + best_s - 1) / best_s;
@@ -320,14 +307,14 @@ size_t wgrad_tr_ws_bytes(const ConvGeom& g_) {
     return pl.splits > 1 ? (size_t)pl.splits * ((size_t)g.Cout * g.K() + g.Cout) * sizeof(float) : 0;
 }
 
-hipError_t wgrad_tr(const ConvGeom& g_, const void* x, const void* dz, float* dw, float* dbias, const float* bscale,
+hipError_t wgrad_tr(const ConvGeom& g_, const void* x, const void* dz, float* dw, float* dbias, const float* rscale,
                     int accumulate, void* ws, hipStream_t st, ReduceDesc* deferred) {
     const ConvGeom g = tr_view(g_);
     const TrPlan pl = plan_wgrad_tr(g);
     WgradTrArgs a{};
     a.X = (const uint16_t*)x; a.DZ = (const uint16_t*)dz;
     a.out = pl.splits > 1 ? (float*)ws : dw;
-    a.db = dbias; a.bscale = bscale;
+    a.db = dbias; a.rscale = rscale;
     a.part_stride = (size_t)g.Cout * g.K() + g.Cout;
     a.dz_bytes = (unsigned)(g.rows_out() * g.Cout * 2); a.x_bytes = (unsigned)(g.rows_in() * g.Cin * 2);
     a.Cout = g.Cout; a.Cin = g.Cin; a.Kh = g.Kh; a.Kw = g.Kw;
@@ -346,9 +333,6 @@ hipError_t wgrad_tr(const ConvGeom& g_, const void* x, const void* dz, float* dw
         if (attr != hipSuccess) return attr;                                                                  \
         hipLaunchKernelGGL((wgrad_tr_kernel<TAPS, NST>), grid, dim3(256), bytes, st, a);                      \
     }
-#ifdef LPM_TUNE      // all nine taps per block: measured slower than a filter row per block on every shape tried
-    if (pl.taps == 9) LPM_TR_LAUNCH(9, 3) else
-#endif
     if (pl.taps == 3) LPM_TR_LAUNCH(3, 4)
     else LPM_TR_LAUNCH(1, 4)
 #undef LPM_TR_LAUNCH
@@ -356,7 +340,7 @@ hipError_t wgrad_tr(const ConvGeom& g_, const void* x, const void* dz, float* dw
     if (e != hipSuccess || pl.splits == 1) return e;
     const int64_t n = (int64_t)g.Cout * g.K();
     const int nb = dbias ? g.Cout : 0;
-    const ReduceDesc d{(const float*)ws, a.part_stride, pl.splits, dw, n, dbias, nb, bscale, accumulate};
+    const ReduceDesc d{(const float*)ws, a.part_stride, pl.splits, dw, n, dbias, nb, rscale, g.K(), accumulate};
     if (deferred) { *deferred = d; return hipSuccess; }
     return launch_reduce_batch(&d, 1, st);
 }

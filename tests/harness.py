@@ -21,8 +21,20 @@ def rel_err(got, ref):
     return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
 
 
-def oracle_step(layers, starts, batch, M, bf16, seed, lr, mu, dx_wanted=False, bias_std=0.05, momentum_std=1e-3, steps=1):
+def read_tensor(net, z, t, slot):
+    """Tensor t of stage z for the micro-batch in `slot`: the stage's output lives in the boundary ring, every other
+    tensor of the stage in its stash slot."""
+    if t == net._out_tensor(z):
+        return net.read_act_out(z, slot)
+    return net.read_stash(t, slot)
+
+
+def oracle_step(layers, starts, batch, M, bf16, seed, lr, mu, dx_wanted=False, bias_std=0.05, momentum_std=1e-3, steps=1,
+                mutate=None):
+    """mutate: optional function applied to the freshly made parameter dict (both sides then start from its result)."""
     params, mom = wl.make_params(layers, seed, bf16=bf16, bias_std=bias_std, momentum_std=momentum_std)
+    if mutate is not None:
+        mutate(params)
     x, labels, g = wl.make_batch(layers, batch, seed, bf16=bf16)
     p0, m0 = copy.deepcopy(params), copy.deepcopy(mom)
     ref = None
@@ -100,11 +112,7 @@ def compare(net, layers, starts, M, dtype, o, dx_wanted=False, window=2, report=
         for t in range(starts[z], starts[z + 1]):
             if layers[t]["kind"] == "softmax_ce":
                 continue
-            try:
-                got = net.read_stash(t, slot)
-            except Exception:
-                got = net.read_act_out(z, slot)
-            errs["act%d" % t] = rel_err(got, stash[t])
+            errs["act%d" % t] = rel_err(read_tensor(net, z, t, slot), stash[t])
         if backward and (z > 0 or dx_wanted):
             want = ref["gin"][(z, j)]
             if z > 0 and net.schedule.cut_fused(z):
@@ -171,11 +179,7 @@ def stage_backward_isolated(lpm, layers, starts, m, batch_total, dtype, seed, dx
             for t in range(starts[z], starts[z + 1]):
                 if layers[t]["kind"] == "softmax_ce":
                     continue
-                try:
-                    got = net.read_stash(t, 0)
-                except Exception:
-                    got = net.read_act_out(z, 0)
-                errs["act%d" % t] = rel_err(got, stashes[z][t])
+                errs["act%d" % t] = rel_err(read_tensor(net, z, t, 0), stashes[z][t])
     g_out = g_up
     for z in range(Z - 1, -1, -1):
         s0, s1 = starts[z], starts[z + 1]

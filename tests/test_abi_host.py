@@ -111,6 +111,26 @@ def test_plans_from_supplied_costs(lpm):
         lpm.lpm_partition_costs(L, 3, cp, [1, 2, 3])
 
 
+def test_layer_cost_residual_bf16_hand_value(lpm):
+    """The library's cost of a bf16 ResNet-18 layer with a shortcut equals the value worked by hand in
+    tests/test_oracle_plan.py::test_layer_cost_hand_computed_residual_bf16 (shortcut bytes, 22-byte update)."""
+    L = wl.resnet18_cifar()
+    assert lpm.lpm_layer_cost(L, 2, _cp("bf16", 32, 8)) == 3_738_006
+
+
+def test_fixed_plan_out_of_range_is_rejected(lpm):
+    """A fixed plan whose entries point past the layer list is refused before any entry is used as an index."""
+    L = wl.lenet()
+    cp = _cp("f32", 8, 4)
+    for plan in ([0, 1000, 8], [0, 8, 8], [0, 9, 8], [0, 4, 2000]):
+        with pytest.raises(lpm.LpmError) as e:
+            lpm.lpm_partition(L, 2, cp, fixed_starts=plan)
+        assert e.value.code == -6, plan
+    with pytest.raises(lpm.LpmError) as e:
+        lpm.lpm_partition(L, 3, cp, fixed_starts=[0, 4, 100000, 8])
+    assert e.value.code == -6
+
+
 def test_error_codes(lpm):
     L = wl.lenet()
     cp = _cp("f32", 8, 4)

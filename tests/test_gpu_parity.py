@@ -248,6 +248,41 @@ def test_partition_with_upstream_gradient(lpm, dtype):
     compare(net, layers, starts, 1, dtype, o, dx_wanted=True)
 
 
+@pytest.mark.parametrize("dtype", [0, 1], ids=["f32", "bf16"])
+@pytest.mark.parametrize("net", ["bottleneck32", "tiny_resnet"])
+def test_zero_and_tiny_scales(lpm, net, dtype):
+    """Frozen per-channel scales of exactly 0 and of 1e-20 (a zero-initialised folded normalisation is a legal value):
+    the bias gradient is the sum of the masked output gradient whatever the scale (eq. 8 for the bias), the weight
+    gradient of a zero-scale channel is 0, and nothing is divided by a scale.  bottleneck32: 32- and 64-channel
+    bottleneck blocks (matrix-core kernels, fused epilogue backward); tiny_resnet: 4 and 6 channels (generic kernels)."""
+    if net == "bottleneck32":
+        layers = wl.r50_conv4x(cin=64, hw=8, mid=32, cout=64, blocks=2)
+        batch, M, dx = 8, 2, True
+    else:
+        layers = wl.tiny_resnet()
+        batch, M, dx = 6, 3, False
+    starts = [0, len(layers)]
+
+    def mutate(params):
+        for i, p in params.items():
+            if "s" in p:
+                p["s"][0::3] = 0.0
+                p["s"][1::3] = 1e-20
+
+    o = oracle_step(layers, starts, batch, M, dtype == 1, seed=29, lr=0.05, mu=0.9, dx_wanted=dx, mutate=mutate)
+    for mode in (lpm.LOCKED, lpm.OVERLAPPED):
+        net_ = gpu_step(lpm, layers, starts, batch, M, dtype, o, 0.05, 0.9, mode, dx_wanted=dx)
+        errs = compare(net_, layers, starts, M, dtype, o, dx_wanted=dx)
+        g = net_.read_grads()
+        for i in g:
+            for k in g[i]:
+                assert np.isfinite(g[i][k]).all(), (i, k)
+        # the bias gradient of zero-scale channels is generally not zero, and must match the oracle's
+        i0 = [i for i in o["params"] if "s" in o["params"][i]][0]
+        assert np.abs(o["ref"]["grads"][i0]["b"][0::3]).max() > 0
+        print(net, dtype, mode, "worst", sorted(errs.items(), key=lambda kv: -kv[1])[:3], flush=True)
+
+
 def test_vgg16_cifar_config_bf16(lpm):
     """The VGG-16/CIFAR workload at full size (batch 128, 8 micro-batches of 16, 4 planned partitions).
 

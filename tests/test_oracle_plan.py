@@ -36,6 +36,25 @@ def test_layer_cost_hand_computed_lenet():
     assert orc.layer_cost(L, 4, 8, 4, 4, 157_286_400, 8_000_000) == expect
 
 
+def test_layer_cost_hand_computed_residual_bf16():
+    """A ResNet-18 layer with a shortcut in the bf16 element type (m = 32, M = 8), worked by hand: the second 3x3
+    convolution of the first basic block, 64 -> 64 channels over 32x32 pixels, which adds the stem's output.  The
+    shortcut is one more tensor read forward and one more written backward, and the update moves 22 bytes per
+    parameter (20 in float plus the 2-byte weight copy).  Every number below is written out, not computed."""
+    L = wl.resnet18_cifar()
+    assert L[2]["add_src"] == 0 and L[2]["cin"] == L[2]["cout"] == 64 and L[2]["h_in"] == 32
+    # multiply-adds 64*32*32 * 64*9 = 37 748 736;  flop = 2 * mac * 32 images * 3 passes = 7 247 757 312
+    # arithmetic time = 7 247 757 312 * 1e6 // 2 516 582 400 = 2 880 000 ps
+    # elements per image: in = out = shortcut = 65 536;  weights 36 864, parameters 36 864 + 64 = 36 928
+    # forward bytes  = (in + out + shortcut) * 32 * 2 + weights * 2            = 12 582 912 + 73 728      = 12 656 640
+    # backward bytes = (dout + in + din + dshortcut) * 32 * 2 + weights*2 + 8*weights = 16 777 216 + 73 728 + 294 912 = 17 145 856
+    # update bytes   = 36 928 * 22                                                                         =    812 416
+    # traffic time = ((12 656 640 + 17 145 856) * 8 + 812 416) * 1e6 // (8 * 8 000 000) = 239 232 384 // 64 = 3 738 006 ps
+    assert orc.layer_cost(L, 2, 32, 8, 2, 2_516_582_400, 8_000_000) == 3_738_006
+    # without the shortcut terms the layer would be arithmetic-bound (2 689 430 < 2 880 000); with 20-byte updates 3 736 852
+    assert 3_738_006 not in (2_880_000, 3_736_852)
+
+
 def test_stage_cost_is_additive():
     L = wl.vgg16_cifar()
     c = [orc.layer_cost(L, i, 16, 8, 2, CP["flop_per_us"], CP["hbm_byte_per_us"]) for i in range(len(L))]
