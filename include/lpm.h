@@ -316,6 +316,19 @@ int32_t lpm_conv_dgrad(const lpm_conv_geom* g, int32_t dtype, const void* dz, co
 int32_t lpm_conv_wgrad(const lpm_conv_geom* g, int32_t dtype, const void* x, const void* dz, float* dw,
                        int32_t accumulate, void* ws, void* stream);
 
+/* lpm_conv_wgrad for callers that cannot allocate device memory and have none to lend: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same operation, same kernels and the same bits as
+ * lpm_conv_wgrad, but the split partials go to a fixed area of LPM_STATIC_SCRATCH_BYTES inside the library's device
+ * image instead of a caller buffer; the call allocates and frees nothing, on the host side of the runtime or on the
+ * device.  x, dz, dw as for lpm_conv_wgrad (caller-owned device memory, 256-byte aligned).
+ * All calls on one GPU share that GPU's area: calls that may overlap on one GPU (two streams, two threads) race and
+ * must be serialised by the caller; consecutive calls on one stream are ordered by the stream.
+ * Errors: as lpm_conv_wgrad; LPM_EINVAL when the geometry needs more scratch than the area holds (lpm_conv_ws_bytes
+ * tells how much), before anything is enqueued. */
+#define LPM_STATIC_SCRATCH_BYTES (8u << 20)
+int32_t lpm_conv_wgrad_static(const lpm_conv_geom* g, int32_t dtype, const void* x, const void* dz, float* dw,
+                              int32_t accumulate, void* stream);
+
 /* Measurement helper: enqueues one of the three contractions `iters` times back to back on `stream`
  * between two HIP events (after `warmup` untimed launches), waits for them, and returns the average
  * duration of one launch in microseconds.  op: 0 = forward (x, w -> y, ReLU epilogue), 1 = data gradient

@@ -9,7 +9,7 @@ import os
 
 import numpy as np
 
-__all__ = ["LpmError", "lib", "lpm_conv_geom", "lpm_conv_ws_bytes", "lpm_conv_forward", "lpm_conv_dgrad", "lpm_conv_wgrad", "lpm_conv_time", "Layerwise", "lpm_layer", "lpm_cost_params", "lpm_stage_buffers", "layers_from_dicts",
+__all__ = ["LpmError", "lib", "lpm_conv_geom", "lpm_conv_ws_bytes", "lpm_conv_forward", "lpm_conv_dgrad", "lpm_conv_wgrad", "lpm_conv_wgrad_static", "STATIC_SCRATCH_BYTES", "lpm_conv_time", "Layerwise", "lpm_layer", "lpm_cost_params", "lpm_stage_buffers", "layers_from_dicts",
            "lpm_layer_cost", "lpm_partition", "lpm_partition_costs", "Stage", "Schedule", "Net", "F32", "BF16", "LOCKED", "OVERLAPPED", "PIPELINED", "ASYNC_UPDATE",
            "GRAPH", "pack_act", "unpack_act", "pack_weight", "unpack_weight", "MI355X_COST"]
 
@@ -82,6 +82,7 @@ lib.lpm_conv_ws_bytes.argtypes = [C.POINTER(lpm_conv_geom), _i32, _psz, _psz, _p
 lib.lpm_conv_forward.argtypes = [C.POINTER(lpm_conv_geom), _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]
 lib.lpm_conv_dgrad.argtypes = [C.POINTER(lpm_conv_geom), _i32, _vp, _vp, _vp, _vp, _i32, _vp, _vp]
 lib.lpm_conv_wgrad.argtypes = [C.POINTER(lpm_conv_geom), _i32, _vp, _vp, _vp, _i32, _vp, _vp]
+lib.lpm_conv_wgrad_static.argtypes = [C.POINTER(lpm_conv_geom), _i32, _vp, _vp, _vp, _i32, _vp]
 lib.lpm_conv_time.argtypes = [_i32, C.POINTER(lpm_conv_geom), _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp,
                               C.POINTER(C.c_float)]
 lib.lpm_layerwise_create.argtypes = [C.POINTER(lpm_conv_geom), _i32, _i32, C.POINTER(_vp)]
@@ -91,7 +92,7 @@ lib.lpm_layerwise_forward.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _
 lib.lpm_layerwise_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]
 lib.lpm_layerwise_time.argtypes = [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, C.POINTER(C.c_float)]
 for _f in ("lpm_layerwise_create", "lpm_layerwise_destroy", "lpm_layerwise_ws_bytes", "lpm_layerwise_forward",
-           "lpm_layerwise_backward", "lpm_layerwise_time", "lpm_conv_time", "lpm_conv_ws_bytes", "lpm_conv_forward", "lpm_conv_dgrad", "lpm_conv_wgrad", "lpm_layer_cost", "lpm_partition", "lpm_partition_costs", "lpm_stage_create", "lpm_stage_destroy", "lpm_stage_sizes",
+           "lpm_layerwise_backward", "lpm_layerwise_time", "lpm_conv_time", "lpm_conv_ws_bytes", "lpm_conv_forward", "lpm_conv_dgrad", "lpm_conv_wgrad", "lpm_conv_wgrad_static", "lpm_layer_cost", "lpm_partition", "lpm_partition_costs", "lpm_stage_create", "lpm_stage_destroy", "lpm_stage_sizes",
            "lpm_stage_param_offset", "lpm_stage_stash_offset", "lpm_stage_grad_offset", "lpm_stage_sync_lowp",
            "lpm_stage_forward", "lpm_stage_backward", "lpm_stage_update", "lpm_schedule_create",
            "lpm_schedule_destroy", "lpm_schedule_cut_fused", "lpm_schedule_run"):
@@ -195,6 +196,15 @@ def lpm_conv_dgrad(g, dtype, dz, w, wt, dx, accumulate=False, ws=None, stream=No
 def lpm_conv_wgrad(g, dtype, x, dz, dw, accumulate=False, ws=None, stream=None):
     gg = _geom(g)
     _check(lib.lpm_conv_wgrad(C.byref(gg), dtype, _ptr(x), _ptr(dz), _ptr(dw), int(accumulate), _ptr(ws), _stream(stream)))
+
+
+STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def lpm_conv_wgrad_static(g, dtype, x, dz, dw, accumulate=False, stream=None):
+    """lpm_conv_wgrad with the library's built-in scratch area: no workspace argument, nothing allocated."""
+    gg = _geom(g)
+    _check(lib.lpm_conv_wgrad_static(C.byref(gg), dtype, _ptr(x), _ptr(dz), _ptr(dw), int(accumulate), _stream(stream)))
 
 
 def lpm_conv_time(op, g, dtype, x, w, wt, y, dw, ws, warmup=3, iters=20, stream=None):

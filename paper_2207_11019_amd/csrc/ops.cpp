@@ -1,6 +1,7 @@
 // Single-layer entry points: the contractions of eq. 1 (forward), eq. 9 (data gradient) and eq. 8
 // (weight gradient) on their own, for layer-level tests and per-kernel measurement.
 #include "lpm_internal.h"
+#include <mutex>
 
 using namespace lpm;
 
@@ -63,6 +64,52 @@ extern "C" int32_t lpm_conv_wgrad(const lpm_conv_geom* g, int32_t dtype, const v
     if (!x || !dz || !dw) return fail(LPM_EINVAL, "NULL argument");
     if (wgrad_ws_bytes(dtype, cg) && !ws) return fail(LPM_EINVAL, "scratch required");
     if (bad_align({x, dz, dw, ws})) return fail(LPM_EALIGN, "device buffers must be 256-byte aligned");
+    LPM_HIP(launch_conv_wgrad(dtype, cg, x, dz, dw, nullptr, nullptr, accumulate != 0, ws, (hipStream_t)stream));
+    return LPM_OK;
+}
+
+// ---- the weight gradient for callers that cannot allocate -----------------------------------------------------------
+// Scratch of lpm_conv_wgrad_static: a fixed area in the library's own device image (every GPU the library runs on holds
+// its copy until the process ends).  In host code the array's name is only a handle for hipGetSymbolAddress; the
+// device address it yields is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[LPM_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[MAX_DEVICES];      // per device: address of that device's copy of `scratch`, NULL until asked for
+}  // namespace
+
+// Address of the current device's copy (looked up once per device, with that device current).
+static int32_t static_scratch(void** out) {
+    int dev = 0;
+    LPM_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(LPM_EINVAL, "device index %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        LPM_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(LPM_EHIP, "hipGetSymbolAddress returned NULL");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return LPM_OK;
+}
+
+extern "C" int32_t lpm_conv_wgrad_static(const lpm_conv_geom* g, int32_t dtype, const void* x, const void* dz, float* dw,
+                                         int32_t accumulate, void* stream) {
+    ConvGeom cg;
+    int32_t rc = to_geom(g, dtype, cg);
+    if (rc) return rc;
+    if (!x || !dz || !dw) return fail(LPM_EINVAL, "NULL argument");
+    if (bad_align({x, dz, dw})) return fail(LPM_EALIGN, "device buffers must be 256-byte aligned");
+    const size_t need = wgrad_ws_bytes(dtype, cg);
+    if (need > (size_t)LPM_STATIC_SCRATCH_BYTES)
+        return fail(LPM_EINVAL, "this geometry needs %zu bytes of scratch, the built-in area holds %zu: use lpm_conv_wgrad",
+                    need, (size_t)LPM_STATIC_SCRATCH_BYTES);
+    void* ws = nullptr;
+    if ((rc = static_scratch(&ws))) return rc;
+    // (every partial sum a reduction reads is written by the contraction of the same call: nothing has to start at zero)
     LPM_HIP(launch_conv_wgrad(dtype, cg, x, dz, dw, nullptr, nullptr, accumulate != 0, ws, (hipStream_t)stream));
     return LPM_OK;
 }
