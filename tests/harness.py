@@ -11,6 +11,7 @@ import numpy as np
 
 import workloads as wl
 from oracle import lpm_oracle as orc
+import flipnoise as fn
 
 TOL = {0: 1e-4, 1: 2e-2}
 
@@ -30,32 +31,52 @@ def read_tensor(net, z, t, slot):
 
 
 def oracle_step(layers, starts, batch, M, bf16, seed, lr, mu, dx_wanted=False, bias_std=0.05, momentum_std=1e-3, steps=1,
-                mutate=None):
-    """mutate: optional function applied to the freshly made parameter dict (both sides then start from its result)."""
-    params, mom = wl.make_params(layers, seed, bf16=bf16, bias_std=bias_std, momentum_std=momentum_std)
-    if mutate is not None:
-        mutate(params)
-    x, labels, g = wl.make_batch(layers, batch, seed, bf16=bf16)
-    p0, m0 = copy.deepcopy(params), copy.deepcopy(mom)
-    ref = None
-    for _ in range(steps):
-        ref = orc.run_schedule(layers, starts, params, mom, x, labels, g, M, lr, mu, orc.LOCKED, keep=True,
-                               input_grad=dx_wanted, store=orc.round_bf16 if bf16 else None)
-    return dict(p0=p0, m0=m0, x=x, labels=labels, g=g, ref=ref, params=params, mom=mom)
+                mutate=None, plain=True):
+    """One (or `steps`) mini-batch step(s) by the oracle.
+
+    For the bf16 element type two results are returned: `ref` takes the backward pass's decisions (ReLU mask,
+    pooling maximum) in the kernel's storage precision -- every stored activation rounded to bfloat16 once, all
+    arithmetic fp64 -- and is what a bf16 implementation is held to element by element; `plain` (plain=True) is the
+    unrounded fp64 computation from the same inputs, against which forward quantities are held to the same bar and
+    backward quantities are reported (and asserted when the two oracle runs agree on every decision).
+    mutate: optional function applied to the freshly made parameter dict (both sides then start from its result)."""
+    def one(store):
+        params, mom = wl.make_params(layers, seed, bf16=bf16, bias_std=bias_std, momentum_std=momentum_std)
+        if mutate is not None:
+            mutate(params)
+        x, labels, g = wl.make_batch(layers, batch, seed, bf16=bf16)
+        p0, m0 = copy.deepcopy(params), copy.deepcopy(mom)
+        ref = None
+        for _ in range(steps):
+            ref = orc.run_schedule(layers, starts, params, mom, x, labels, g, M, lr, mu, orc.LOCKED, keep=True,
+                                   input_grad=dx_wanted, store=store)
+        return dict(p0=p0, m0=m0, x=x, labels=labels, g=g, ref=ref, params=params, mom=mom)
+
+    o = one(orc.round_bf16 if bf16 else None)
+    if bf16 and plain:
+        o["plain"] = one(None)
+    return o
 
 
-def oracle_step_async(layers, starts, batch, M, bf16, seed, lr, mu, window, locked, bias_std=0.05, momentum_std=1e-3):
-    """One pass with an update per micro-batch (oracle.run_schedule_async)."""
+def oracle_step_async(layers, starts, batch, M, bf16, seed, lr, mu, window, locked, bias_std=0.05, momentum_std=1e-3,
+                      store="default", wstore="default"):
+    """One pass with an update per micro-batch (oracle.run_schedule_async).  store / wstore: how stored activations and
+    the weight copies the layers compute with are rounded (default: to bfloat16 for the bf16 element type)."""
     params, mom = wl.make_params(layers, seed, bf16=bf16, bias_std=bias_std, momentum_std=momentum_std)
     x, labels, g = wl.make_batch(layers, batch, seed, bf16=bf16)
     p0, m0 = copy.deepcopy(params), copy.deepcopy(mom)
+    if store == "default":
+        store = orc.round_bf16 if bf16 else None
+    if wstore == "default":
+        wstore = orc.round_bf16 if bf16 else None
     ref = orc.run_schedule_async(layers, starts, params, mom, x, labels, g, M, lr, mu, window=window, locked=locked,
-                                 store=orc.round_bf16 if bf16 else None, wstore=orc.round_bf16 if bf16 else None)
+                                 store=store, wstore=wstore)
     return dict(p0=p0, m0=m0, x=x, labels=labels, g=g, ref=ref, params=params, mom=mom)
 
 
-def compare_async(net, dtype, o, tol=None):
-    """Loss, last micro-batch's gradient, final weights and momentum against the oracle."""
+def compare_async(net, dtype, o, tol=None, floors=None):
+    """Loss, last micro-batch's gradient, final weights and momentum against the oracle.
+    floors: optional {name: decision-flip noise floor}; a tensor's bound is then tol + 2 * floor."""
     tol = TOL[dtype] if tol is None else tol
     ref = o["ref"]
     errs = {"loss": abs(net.loss_value() - ref["loss"]) / max(abs(ref["loss"]), 1e-30)}
@@ -66,9 +87,29 @@ def compare_async(net, dtype, o, tol=None):
                 errs["grad%d.%s" % (i, k)] = rel_err(g[i][k], ref["grads"][i][k])
                 errs["param%d.%s" % (i, k)] = rel_err(p[i][k], o["params"][i][k])
                 errs["mom%d.%s" % (i, k)] = rel_err(v[i][k], o["mom"][i][k])
-    bad = {k: e for k, e in errs.items() if not (e <= tol)}
+    bad = {k: e for k, e in errs.items() if not (e <= tol + 2 * (floors or {}).get(k, 0.0))}
     assert not bad, "over the %g bar: %s" % (tol, sorted(bad.items(), key=lambda kv: -kv[1])[:8])
     return errs
+
+
+def async_floors(layers, starts, batch, M, seed, lr, mu, window, locked, o, realisations=8):
+    """Decision-flip noise floor of a bf16 asynchronous-update pass: the largest distance, over a few realisations, between
+    the oracle's result and the same oracle arithmetic with accumulation-order noise (flipnoise.order_noise_store) on the
+    stored activations and on the weight copies -- per compared tensor, in the harness's error measure."""
+    fl = {}
+    for r in range(realisations):
+        q = oracle_step_async(layers, starts, batch, M, True, seed, lr, mu, window, locked,
+                              store=fn.order_noise_store(100 + r), wstore=fn.order_noise_store(200 + r))
+        cand = {"loss": abs(q["ref"]["loss"] - o["ref"]["loss"]) / max(abs(o["ref"]["loss"]), 1e-30)}
+        for i in o["params"]:
+            for k in ("W", "b"):
+                if k in o["params"][i]:
+                    cand["grad%d.%s" % (i, k)] = rel_err(q["ref"]["grads"][i][k], o["ref"]["grads"][i][k])
+                    cand["param%d.%s" % (i, k)] = rel_err(q["params"][i][k], o["params"][i][k])
+                    cand["mom%d.%s" % (i, k)] = rel_err(q["mom"][i][k], o["mom"][i][k])
+        for k, e in cand.items():
+            fl[k] = max(fl.get(k, 0.0), e)
+    return fl
 
 
 def gpu_step(lpm, layers, starts, batch, M, dtype, o, lr, mu, mode, window=2, dx_wanted=False, steps=1):
@@ -85,10 +126,32 @@ def gpu_step(lpm, layers, starts, batch, M, dtype, o, lr, mu, mode, window=2, dx
     return net
 
 
+def all_tensors(stash_by_stage, Z, j):
+    """{tensor index: value} over all stages for micro-batch j, from the oracle's per-stage stashes."""
+    out = {}
+    for z in range(Z):
+        out.update({t: v for t, v in stash_by_stage[(z, j)].items() if isinstance(t, int)})
+    return out
+
+
+def device_tensors(net, layers, starts, slot):
+    out = {}
+    for z in range(len(starts) - 1):
+        for t in range(starts[z], starts[z + 1]):
+            if layers[t]["kind"] != "softmax_ce":
+                out[t] = read_tensor(net, z, t, slot)
+    return out
+
+
 def compare(net, layers, starts, M, dtype, o, dx_wanted=False, window=2, report=None, backward=True):
     """Compares loss, gradients, updated weights, momentum, and the last micro-batch's activations
     and boundary gradients.  Returns {name: error}; asserts every error is under the bar.
-    backward=False restricts the comparison to the forward quantities (activations and loss)."""
+    backward=False restricts the comparison to the forward quantities (activations and loss).
+
+    bf16: the element-wise bar is applied against the oracle run that decides in storage precision (o["ref"]); the
+    count of decisions on which the device's stored activations differ from that run's is printed, and a failure
+    names it.  Against the unrounded fp64 run (o["plain"]) the forward quantities must meet the same bar; the
+    backward quantities are printed, and must meet it too whenever the two oracle runs agree on every decision."""
     tol = TOL[dtype]
     ref = o["ref"]
     errs = {}
@@ -106,23 +169,63 @@ def compare(net, layers, starts, M, dtype, o, dx_wanted=False, window=2, report=
     Z = len(starts) - 1
     j = M - 1
     slot = j % window
+    dev = device_tensors(net, layers, starts, slot)
+    want_t = all_tensors(ref["stash"], Z, j)
+    for t, got in dev.items():
+        errs["act%d" % t] = rel_err(got, want_t[t])
+    gins = {}
     for z in range(Z):
-        stash = ref["stash"][(z, j)]
-        s = net.stages[z]
-        for t in range(starts[z], starts[z + 1]):
-            if layers[t]["kind"] == "softmax_ce":
-                continue
-            errs["act%d" % t] = rel_err(read_tensor(net, z, t, slot), stash[t])
         if backward and (z > 0 or dx_wanted):
+            gins[z] = net.read_grad_in(z, slot)
             want = ref["gin"][(z, j)]
             if z > 0 and net.schedule.cut_fused(z):
                 # the cut hands down the previous stage's pre-activation gradient: ReLU derivative of the stage input applied
                 want = want * (ref["stash"][(z - 1, j)][starts[z] - 1] > 0)
-            errs["gin%d" % z] = rel_err(net.read_grad_in(z, slot), want)
+            errs["gin%d" % z] = rel_err(gins[z], want)
+    flips = None
+    if dtype == 1:
+        dev[-1] = want_t[-1] = o["x"][j * (len(o["x"]) // M):(j + 1) * (len(o["x"]) // M)]
+        flips = fn.decision_disagreements(layers, 0, len(layers), dev, want_t)
+        print("decisions differing from the storage-precision oracle run (relu, of, pool, of):", flips, flush=True)
     bad = {k: e for k, e in errs.items() if not (e <= tol)}
     if report is not None:
         report.update(errs)
-    assert not bad, "over the %g bar: %s" % (tol, sorted(bad.items(), key=lambda kv: -kv[1])[:8])
+    assert not bad, "over the %g bar (decision disagreements %s): %s" % (tol, flips, sorted(bad.items(), key=lambda kv: -kv[1])[:8])
+    if dtype == 1 and "plain" in o:
+        # against the unrounded fp64 computation
+        pl = o["plain"]
+        pr = pl["ref"]
+        plain_t = all_tensors(pr["stash"], Z, j)
+        plain_t[-1] = dev[-1]
+        perr = {}
+        if o["labels"] is not None:
+            perr["loss"] = abs(net.loss_value() - pr["loss"]) / max(abs(pr["loss"]), 1e-30)
+        for t, got in dev.items():
+            if t >= 0:
+                perr["act%d" % t] = rel_err(got, plain_t[t])
+        fwd_bad = {k: e for k, e in perr.items() if not (e <= tol)}
+        berr = {}
+        for i in (pl["params"] if backward else []):
+            for k in ("W", "b"):
+                if k in pl["params"][i]:
+                    berr["grad%d.%s" % (i, k)] = rel_err(g[i][k], pr["grads"][i][k])
+                    berr["param%d.%s" % (i, k)] = rel_err(p[i][k], pl["params"][i][k])
+        for z, got in gins.items():
+            want = pr["gin"][(z, j)]
+            if z > 0 and net.schedule.cut_fused(z):
+                want = want * (pr["stash"][(z - 1, j)][starts[z] - 1] > 0)
+            berr["gin%d" % z] = rel_err(got, want)
+        oracle_flips = fn.decision_disagreements(layers, 0, len(layers), plain_t, want_t)
+        worst_f = max(perr.values()) if perr else 0.0
+        worst_b = max(berr.values()) if berr else 0.0
+        print("against the unrounded fp64 oracle: worst forward error %.4g, worst backward error %.4g; the two oracle runs "
+              "differ on decisions (relu, of, pool, of) %s" % (worst_f, worst_b, oracle_flips), flush=True)
+        if report is not None:
+            report.update({"plain." + k: e for k, e in list(perr.items()) + list(berr.items())})
+        assert not fwd_bad, "forward quantities over the %g bar against the unrounded oracle: %s" % (tol, sorted(fwd_bad.items(), key=lambda kv: -kv[1])[:8])
+        if oracle_flips[0] == 0 and oracle_flips[2] == 0:
+            bbad = {k: e for k, e in berr.items() if not (e <= tol)}
+            assert not bbad, "backward quantities over the %g bar against the unrounded oracle (no decision depends on the storage precision here): %s" % (tol, sorted(bbad.items(), key=lambda kv: -kv[1])[:8])
     return errs
 
 

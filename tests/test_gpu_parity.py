@@ -6,6 +6,7 @@ import workloads as wl
 from workloads import rng
 from oracle import lpm_oracle as orc
 from harness import oracle_step, gpu_step, compare, rel_err, l2_err, stage_backward_isolated
+import flipnoise as fn
 
 pytestmark = pytest.mark.gpu
 
@@ -90,6 +91,33 @@ def test_stage_without_parameters(lpm):
             compare(net, layers, starts, 2, dtype, o)
 
 
+def test_maxpool_backward_full_size_with_ties(lpm):
+    """Pooling backward at the 224x224 VGG-16's first pooling size (4 x 64 x 224 x 224) as a stage of its own, on an input
+    quantised to multiples of 1/4 so that many windows hold their maximum twice or more: the gradient must land on the
+    first maximum in row-major window order, bit for bit; the 2x2 window sums of the result equal the incoming gradient
+    whichever element received it.  The count of tie windows is printed."""
+    import torch
+    import flipnoise as fn
+    layers = [dict(kind="maxpool2", cin=64, cout=64, kh=2, kw=2, stride=2, pad=0, h_in=224, w_in=224, relu=False, bias=False,
+                   scale=False, src=-1, add_src=None, cut_after=False)]
+    m = 4
+    x = np.round(rng.normal(3, 1, (m, 64, 224, 224)) * 4.0) / 4.0
+    dy = rng.round_to_bf16(rng.normal(3, 2, (m, 64, 112, 112)))
+    win = x.reshape(m, 64, 112, 2, 112, 2).transpose(0, 1, 2, 4, 3, 5).reshape(m, 64, 112, 112, 4)
+    ties = int(((win == win.max(axis=-1, keepdims=True)).sum(axis=-1) > 1).sum())
+    print("windows whose maximum occurs more than once: %d of %d" % (ties, win.shape[0] * 64 * 112 * 112), flush=True)
+    assert ties > 100000
+    want = orc.maxpool2_bwd(x, dy)
+    net = lpm.Net(layers, [0, 1], m, 1, lpm.BF16, dx_wanted=True)
+    for mode in (lpm.LOCKED, lpm.OVERLAPPED):
+        net.step(lpm.pack_act(x, lpm.BF16), None, lpm.pack_act(dy, lpm.BF16), 0.0, 0.0, mode)
+        torch.cuda.synchronize()
+        got = net.read_grad_in(0, 0)
+        np.testing.assert_array_equal(fn.window_sums(got), dy)
+        np.testing.assert_array_equal(got, want)
+    np.testing.assert_array_equal(net.read_act_out(0, 0), orc.maxpool2_fwd(x))
+
+
 def test_pipelined_graph_is_refused(lpm):
     """Stage-parallel streams are not captured into a graph: the call fails before anything is enqueued."""
     layers = wl.tiny_lenet()
@@ -126,6 +154,25 @@ def test_async_update(lpm, name, builder, batch, M, Z, dtype, sched):
     o = oracle_step_async(layers, starts, batch, M, dtype == 1, seed=23, lr=0.05, mu=0.9, window=window, locked=sched == "locked")
     net = gpu_step(lpm, layers, starts, batch, M, dtype, o, 0.05, 0.9, mode, window=window)
     compare_async(net, dtype, o)
+
+
+@pytest.mark.parametrize("sched", ["locked", "overlapped_w2"])
+def test_async_update_bf16_relu_network(lpm, sched):
+    """The per-micro-batch update in bf16 on a network WITH ReLU and max-pooling (tiny_vgg, 4 micro-batches of 2).
+    After the first update the two sides' bf16 weight copies differ in a few last bits, which can flip decisions of
+    later micro-batches; each tensor is therefore held to the bar plus twice the decision-flip noise floor of this
+    very case, measured on the oracle (eight realisations of accumulation-order noise, harness.async_floors)."""
+    from harness import oracle_step_async, compare_async, async_floors
+    layers = wl.tiny_vgg()
+    starts = _starts(layers, 2)
+    window, locked = (2, False) if sched == "overlapped_w2" else (2, True)
+    mode = (lpm.LOCKED if locked else lpm.OVERLAPPED) | lpm.ASYNC_UPDATE
+    o = oracle_step_async(layers, starts, 8, 4, True, seed=23, lr=0.05, mu=0.9, window=window, locked=locked)
+    floors = async_floors(layers, starts, 8, 4, 23, 0.05, 0.9, window, locked, o)
+    print("largest floors", sorted(floors.items(), key=lambda kv: -kv[1])[:5], flush=True)
+    net = gpu_step(lpm, layers, starts, 8, 4, 1, o, 0.05, 0.9, mode, window=window)
+    errs = compare_async(net, 1, o, floors=floors)
+    print("largest errors", sorted(errs.items(), key=lambda kv: -kv[1])[:5], flush=True)
 
 
 def test_lenet_config_f32(lpm):
@@ -286,9 +333,12 @@ def test_zero_and_tiny_scales(lpm, net, dtype):
 def test_vgg16_cifar_config_bf16(lpm):
     """The VGG-16/CIFAR workload at full size (batch 128, 8 micro-batches of 16, 4 planned partitions).
 
-    Forward quantities are compared end to end.  The backward pass is compared stage by stage from a
-    forward state prepared by the oracle (see harness.stage_backward_isolated): over 13 bf16 layers the
-    ReLU / pooling decisions are not stable against last-bit differences, on either side."""
+    Forward quantities are compared end to end, against the storage-precision oracle run and against the unrounded
+    one.  Backward: (a) end to end against the unrounded fp64 step, each gradient tensor held to the bar plus twice the
+    decision-flip noise floor of this workload (the distance between the two oracle runs; mechanism pinned by
+    tests/test_oracle_flip_noise.py: over 13 bf16 layers ReLU / pooling decisions are not stable against last-bit
+    differences, on either side); (b) element-wise at the bar, stage by stage from a forward state prepared by the
+    oracle (harness.stage_backward_isolated), where both sides decide on identical stored values."""
     layers = wl.vgg16_cifar()
     cp = dict(lpm.MI355X_COST["bf16"], link_byte_per_us=0, microbatch=16, n_microbatch=8)
     starts, _ = lpm.lpm_partition(layers, 4, cp)
@@ -307,11 +357,20 @@ def test_vgg16_cifar_config_bf16(lpm):
         for i in a:
             for k in a[i]:
                 np.testing.assert_array_equal(a[i][k], b[i][k])
-    # end-to-end gradients: sanity only (2-norm), the element-wise bar is applied per stage below
+    # End-to-end gradients against the unrounded fp64 step.  The bound per tensor is the bar plus twice the distance between
+    # the two oracle runs (stored activations rounded to bf16, or not): a second valid bf16 result is that far from the
+    # unrounded one (tests/test_oracle_flip_noise.py); the element-wise bar itself is applied per stage below.
     g = nets[lpm.LOCKED].read_grads()
-    worst = max(l2_err(g[i]["W"], o["ref"]["grads"][i]["W"]) for i in g)
-    print("end-to-end gradient 2-norm error, worst layer: %.4f" % worst, flush=True)
-    assert worst < 0.5
+    A, B = o["plain"]["ref"]["grads"], o["ref"]["grads"]
+    over = []
+    for i in g:
+        for k in g[i]:
+            f_inf, f_l2 = fn.inf_err(B[i][k], A[i][k]), fn.l2_err(B[i][k], A[i][k])
+            e_inf, e_l2 = fn.inf_err(g[i][k], A[i][k]), fn.l2_err(g[i][k], A[i][k])
+            print("end-to-end grad%d.%s: error %.4f (floor %.4f), 2-norm %.4f (floor %.4f)" % (i, k, e_inf, f_inf, e_l2, f_l2), flush=True)
+            if not (e_inf <= 2e-2 + 2 * f_inf and e_l2 <= 2e-2 + 2 * f_l2):
+                over.append((i, k, e_inf, f_inf, e_l2, f_l2))
+    assert not over, over
     del nets
     rep = {}
     stage_backward_isolated(lpm, layers, starts, 16, 128, 1, seed=11, report=rep)
