@@ -472,16 +472,21 @@ def pmc_probe(args, torch, wl, lpm):
     dtype = lpm.BF16 if dt == "bf16" else lpm.F32
     dx_wanted = layers[-1]["kind"] != "softmax_ce"
     st = torch.cuda.Stream()
+    class V:          # what pool_stage needs of a workload, without its parameters (the kernels probed here do not read them)
+        pass
+    V.torch, V.layers, V.m, V.dtype = torch, layers, m, dtype
     if what == "update":
-        V = Workload(torch, wl, lpm, args.workload)
+        cp = dict(lpm.MI355X_COST[dt], link_byte_per_us=0, microbatch=m, n_microbatch=M)
+        starts, _ = lpm.lpm_partition(layers, Z, cp, list(fixed) if fixed is not None else None)
         z = int(arg)
-        s, b = V.net.stages[z], V.net.bufs[z]
+        s = lpm.Stage(layers, starts[z], starts[z + 1], m, dtype)
+        zb = lambda n: torch.zeros(max(n, 256), dtype=torch.uint8, device="cuda")      # noqa: E731
+        b = dict(params=zb(s.param_bytes), lowp=zb(s.lowp_bytes), grads=zb(s.grad_bytes), momentum=zb(s.grad_bytes))
         torch.cuda.synchronize()
         for _ in range(5):
-            s.update(b["params"], b["lowp"], b["grads"], b["momentum"], 0.0, 0.9, False, st)
-        info.update(parameters=s.grad_bytes // 4, algorithmic_bytes=22 * (s.grad_bytes // 4))
+            s.update(b["params"], b["lowp"] if dtype == lpm.BF16 else None, b["grads"], b["momentum"], 0.0, 0.9, False, st)
+        info.update(stage_layers=[starts[z], starts[z + 1]], parameters=s.grad_bytes // 4, algorithmic_bytes=22 * (s.grad_bytes // 4))
     elif what == "pool":
-        V = Workload(torch, wl, lpm, args.workload)
         ps, x, y, par, stash, ws = pool_stage(lpm, V, int(arg))
         torch.cuda.synchronize()
         for _ in range(20):

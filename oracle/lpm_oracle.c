@@ -157,3 +157,99 @@ void orc_maxpool2_bwd(const double *x, const double *dy, double *dx, int N, int 
             }
     }
 }
+
+/* ---- three-dimensional convolution (the 3x3x3 layers of the volumetric use case) ------------------------------
+ * Same definition with one more spatial index: activations [N][C][D][H][W], weights [Cout][Cin][Kd][Kh][Kw],
+ * one stride for all three axes, padding pd along the depth and p along height and width.
+ *   z[n,co,do,ho,wo] = sum_{ci,kd,kh,kw} Wt[co,ci,kd,kh,kw] * x[n,ci,do*s+kd-pd,ho*s+kh-p,wo*s+kw-p], zero outside. */
+#define IDX5(n, c, d, h, w, C, D, H, W) (((((size_t)(n) * (C) + (c)) * (D) + (d)) * (H) + (h)) * (W) + (w))
+
+void orc_conv3d_fwd(const double *x, const double *wt, double *z, int N, int Cin, int D, int H, int W,
+                    int Cout, int Kd, int Kh, int Kw, int stride, int pad_d, int pad)
+{
+    const int Do = (D + 2 * pad_d - Kd) / stride + 1, Ho = (H + 2 * pad - Kh) / stride + 1, Wo = (W + 2 * pad - Kw) / stride + 1;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int n = 0; n < N; ++n)
+        for (int co = 0; co < Cout; ++co)
+            for (int dq = 0; dq < Do; ++dq)
+                for (int ho = 0; ho < Ho; ++ho)
+                    for (int wo = 0; wo < Wo; ++wo) {
+                        double acc = 0.0;
+                        for (int ci = 0; ci < Cin; ++ci)
+                            for (int kd = 0; kd < Kd; ++kd) {
+                                const int d = dq * stride + kd - pad_d;
+                                if (d < 0 || d >= D) continue;
+                                for (int kh = 0; kh < Kh; ++kh) {
+                                    const int h = ho * stride + kh - pad;
+                                    if (h < 0 || h >= H) continue;
+                                    for (int kw = 0; kw < Kw; ++kw) {
+                                        const int w = wo * stride + kw - pad;
+                                        if (w < 0 || w >= W) continue;
+                                        acc += wt[IDX5(co, ci, kd, kh, kw, Cin, Kd, Kh, Kw)] * x[IDX5(n, ci, d, h, w, Cin, D, H, W)];
+                                    }
+                                }
+                            }
+                        z[IDX5(n, co, dq, ho, wo, Cout, Do, Ho, Wo)] = acc;
+                    }
+}
+
+/* dx[n,ci,d,h,w] = sum over (co,kd,kh,kw) and the output positions (do,ho,wo) that read (d,h,w) through that tap. */
+void orc_conv3d_bwd_data(const double *dz, const double *wt, double *dx, int N, int Cin, int D, int H, int W,
+                         int Cout, int Kd, int Kh, int Kw, int stride, int pad_d, int pad)
+{
+    const int Do = (D + 2 * pad_d - Kd) / stride + 1, Ho = (H + 2 * pad - Kh) / stride + 1, Wo = (W + 2 * pad - Kw) / stride + 1;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int n = 0; n < N; ++n)
+        for (int ci = 0; ci < Cin; ++ci)
+            for (int d = 0; d < D; ++d)
+                for (int h = 0; h < H; ++h)
+                    for (int w = 0; w < W; ++w) {
+                        double acc = 0.0;
+                        for (int co = 0; co < Cout; ++co)
+                            for (int kd = 0; kd < Kd; ++kd) {
+                                const int td = d + pad_d - kd;
+                                if (td < 0 || td % stride || td / stride >= Do) continue;
+                                for (int kh = 0; kh < Kh; ++kh) {
+                                    const int th = h + pad - kh;
+                                    if (th < 0 || th % stride || th / stride >= Ho) continue;
+                                    for (int kw = 0; kw < Kw; ++kw) {
+                                        const int tw = w + pad - kw;
+                                        if (tw < 0 || tw % stride || tw / stride >= Wo) continue;
+                                        acc += wt[IDX5(co, ci, kd, kh, kw, Cin, Kd, Kh, Kw)] *
+                                               dz[IDX5(n, co, td / stride, th / stride, tw / stride, Cout, Do, Ho, Wo)];
+                                    }
+                                }
+                            }
+                        dx[IDX5(n, ci, d, h, w, Cin, D, H, W)] = acc;
+                    }
+}
+
+/* dW[co,ci,kd,kh,kw] = sum_{n,do,ho,wo} dz[n,co,do,ho,wo] * x[n,ci,do*s+kd-pd,ho*s+kh-p,wo*s+kw-p]. */
+void orc_conv3d_bwd_weight(const double *x, const double *dz, double *dwt, int N, int Cin, int D, int H, int W,
+                           int Cout, int Kd, int Kh, int Kw, int stride, int pad_d, int pad)
+{
+    const int Do = (D + 2 * pad_d - Kd) / stride + 1, Ho = (H + 2 * pad - Kh) / stride + 1, Wo = (W + 2 * pad - Kw) / stride + 1;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int co = 0; co < Cout; ++co)
+        for (int ci = 0; ci < Cin; ++ci)
+            for (int kd = 0; kd < Kd; ++kd)
+                for (int kh = 0; kh < Kh; ++kh)
+                    for (int kw = 0; kw < Kw; ++kw) {
+                        double acc = 0.0;
+                        for (int n = 0; n < N; ++n)
+                            for (int dq = 0; dq < Do; ++dq) {
+                                const int d = dq * stride + kd - pad_d;
+                                if (d < 0 || d >= D) continue;
+                                for (int ho = 0; ho < Ho; ++ho) {
+                                    const int h = ho * stride + kh - pad;
+                                    if (h < 0 || h >= H) continue;
+                                    for (int wo = 0; wo < Wo; ++wo) {
+                                        const int w = wo * stride + kw - pad;
+                                        if (w < 0 || w >= W) continue;
+                                        acc += dz[IDX5(n, co, dq, ho, wo, Cout, Do, Ho, Wo)] * x[IDX5(n, ci, d, h, w, Cin, D, H, W)];
+                                    }
+                                }
+                            }
+                        dwt[IDX5(co, ci, kd, kh, kw, Cin, Kd, Kh, Kw)] = acc;
+                    }
+}

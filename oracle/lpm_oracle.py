@@ -19,6 +19,8 @@ What it computes is plain mini-batch backpropagation plus SGD, re-organised in t
 Convolution and pooling loops are the C routines of lpm_oracle.c (direct fp64 loops);
 everything else is numpy in float64.  Layouts are logical: activations [N][C][H][W],
 weights [Cout][Cin][Kh][Kw].  Layers are the plain dicts of workloads.configs.
+A volumetric (3-D) convolution keeps its tensors as [N][C][D*H][W] and its weights as [Cout][Cin][Kd*Kh][Kw]:
+only the convolution routines unfold the depth (keys d_in, kd, pad_d of the layer dict).
 
 Readings taken where the paper is silent are listed next to each function.
 """
@@ -61,15 +63,29 @@ def _f64(a):
 
 # --------------------------------------------------------------------------- layers
 
+def _depth(l):
+    """(D, Kd, pad_d) of a convolution: 1, 1, 0 for a two-dimensional layer.  A volumetric layer reads its input
+    [N][C][D][H][W] stored as [N][C][D*H][W] (depth folded into the height axis), so that every other routine of this
+    file -- epilogue, pooling-free residual sums, global average pooling -- sees an ordinary 4-index tensor."""
+    D = l.get("d_in", 1)
+    if l["kind"] == "fc":
+        return D, D, 0
+    return D, l.get("kd", 1), l.get("pad_d", 0)
+
+
 def _oshape(l):
     k = l["kind"]
     if k == "conv":
-        return (l["cout"], (l["h_in"] + 2 * l["pad"] - l["kh"]) // l["stride"] + 1,
+        D, Kd, pd = _depth(l)
+        Do = (D + 2 * pd - Kd) // l["stride"] + 1
+        return (l["cout"], Do * ((l["h_in"] + 2 * l["pad"] - l["kh"]) // l["stride"] + 1),
                 (l["w_in"] + 2 * l["pad"] - l["kw"]) // l["stride"] + 1)
     if k in ("fc",):
         return (l["cout"], 1, 1)
     if k == "maxpool2":
         return (l["cin"], l["h_in"] // 2, l["w_in"] // 2)
+    if k == "attn":
+        return (l["cout"], l["h_in"], l["w_in"])
     return (l["cin"], 1, 1)          # gap, softmax_ce
 
 
@@ -80,8 +96,20 @@ def _geom(l):
     return l["cin"], l["h_in"], l["w_in"], l["cout"], l["kh"], l["kw"], l["stride"], l["pad"]
 
 
+def _is3d(l):
+    D, Kd, _ = _depth(l)
+    return D > 1 or Kd > 1
+
+
 def conv_fwd(x, W, l):
     Cin, H, Wd, Cout, Kh, Kw, s, p = _geom(l)
+    if _is3d(l):
+        D, Kd, pd = _depth(l)
+        x = _f64(x).reshape(-1, Cin, D, H, Wd)
+        N = x.shape[0]
+        z = np.empty((N,) + _oshape(l))
+        _c().orc_conv3d_fwd(_p(x), _p(_f64(W)), _p(z), N, Cin, D, H, Wd, Cout, Kd, Kh, Kw, s, pd, p)
+        return z
     x = _f64(x).reshape(-1, Cin, H, Wd)
     N = x.shape[0]
     z = np.empty((N,) + _oshape(l))
@@ -93,6 +121,11 @@ def conv_bwd_data(dz, W, l):
     Cin, H, Wd, Cout, Kh, Kw, s, p = _geom(l)
     dz = _f64(dz)
     N = dz.shape[0]
+    if _is3d(l):
+        D, Kd, pd = _depth(l)
+        dx = np.empty((N, Cin, D * H, Wd))
+        _c().orc_conv3d_bwd_data(_p(dz), _p(_f64(W)), _p(dx), N, Cin, D, H, Wd, Cout, Kd, Kh, Kw, s, pd, p)
+        return dx
     dx = np.empty((N, Cin, H, Wd))
     _c().orc_conv_bwd_data(_p(dz), _p(_f64(W)), _p(dx), N, Cin, H, Wd, Cout, Kh, Kw, s, p)
     return dx
@@ -100,11 +133,56 @@ def conv_bwd_data(dz, W, l):
 
 def conv_bwd_weight(x, dz, l):
     Cin, H, Wd, Cout, Kh, Kw, s, p = _geom(l)
-    x = _f64(x).reshape(-1, Cin, H, Wd)
     dz = _f64(dz)
+    if _is3d(l):
+        D, Kd, pd = _depth(l)
+        x = _f64(x).reshape(-1, Cin, D, H, Wd)
+        dW = np.empty((Cout, Cin, Kd * Kh, Kw))          # [Cout][Cin][Kd][Kh][Kw] with (Kd, Kh) folded, like the activations
+        _c().orc_conv3d_bwd_weight(_p(x), _p(dz), _p(dW), x.shape[0], Cin, D, H, Wd, Cout, Kd, Kh, Kw, s, pd, p)
+        return dW
+    x = _f64(x).reshape(-1, Cin, H, Wd)
     dW = np.empty((Cout, Cin, Kh, Kw))
     _c().orc_conv_bwd_weight(_p(x), _p(dz), _p(dW), x.shape[0], Cin, H, Wd, Cout, Kh, Kw, s, p)
     return dW
+
+
+def attn_fwd(x):
+    """Self-attention over the positions of one sample (reading of the use case's "self-attention layer": scaled
+    dot-product attention, one head).  x [N][3C][H][W] holds queries, keys and values as three groups of C channels
+    (made by the 1x1 convolution in front of this layer); with P = H*W positions
+        S[i][j] = sum_c q[c][i] k[c][j] / sqrt(C),   A = softmax over j of S,   y[c][i] = sum_j A[i][j] v[c][j].
+    Returns y [N][C][H][W]."""
+    x = _f64(x)
+    N, C3, H, W = x.shape
+    C = C3 // 3
+    q, k, v = (x[:, g * C:(g + 1) * C].reshape(N, C, H * W) for g in range(3))
+    S = np.einsum("nci,ncj->nij", q, k) / np.sqrt(C)
+    S = S - S.max(axis=2, keepdims=True)
+    A = np.exp(S)
+    A /= A.sum(axis=2, keepdims=True)
+    return np.einsum("nij,ncj->nci", A, v).reshape(N, C, H, W)
+
+
+def attn_bwd(x, dy):
+    """Gradient of attn_fwd w.r.t. x, by the chain rule through y = A v, A = softmax(S), S = q^T k / sqrt(C):
+        dv[c][j] = sum_i A[i][j] dy[c][i];   dA[i][j] = sum_c dy[c][i] v[c][j];
+        dS[i][j] = A[i][j] (dA[i][j] - sum_j' A[i][j'] dA[i][j']);
+        dq[c][i] = sum_j dS[i][j] k[c][j] / sqrt(C);   dk[c][j] = sum_i dS[i][j] q[c][i] / sqrt(C)."""
+    x, dy = _f64(x), _f64(dy)
+    N, C3, H, W = x.shape
+    C = C3 // 3
+    q, k, v = (x[:, g * C:(g + 1) * C].reshape(N, C, H * W) for g in range(3))
+    g = dy.reshape(N, C, H * W)
+    S = np.einsum("nci,ncj->nij", q, k) / np.sqrt(C)
+    S = S - S.max(axis=2, keepdims=True)
+    A = np.exp(S)
+    A /= A.sum(axis=2, keepdims=True)
+    dv = np.einsum("nij,nci->ncj", A, g)
+    dA = np.einsum("nci,ncj->nij", g, v)
+    dS = A * (dA - (A * dA).sum(axis=2, keepdims=True))
+    dq = np.einsum("nij,ncj->nci", dS, k) / np.sqrt(C)
+    dk = np.einsum("nij,nci->ncj", dS, q) / np.sqrt(C)
+    return np.concatenate([dq, dk, dv], axis=1).reshape(N, C3, H, W)
 
 
 def maxpool2_fwd(x):
@@ -188,6 +266,8 @@ def stage_forward(layers, first, last, params, a_in, labels=None, batch_total=No
             T[i] = maxpool2_fwd(x)
         elif k == "gap":
             T[i] = x.mean(axis=(2, 3), keepdims=True)
+        elif k == "attn":
+            T[i] = attn_fwd(x)
         elif k == "softmax_ce":
             loss, T["dlogits"] = softmax_ce(x, labels, batch_total)
             T[i] = x
@@ -239,6 +319,8 @@ def stage_backward(layers, first, last, params, stash, g_out, grads, input_grad=
         elif k == "gap":
             x = stash[src]
             acc(src, np.broadcast_to(g / (x.shape[2] * x.shape[3]), x.shape).copy())
+        elif k == "attn":
+            acc(src, attn_bwd(stash[src], g))
         elif k == "softmax_ce":
             acc(src, g)
     return G.get(first - 1) if input_grad else None
@@ -551,9 +633,13 @@ def layer_cost(layers, i, m, M, elem_bytes, flop_per_us, hbm_byte_per_us):
     in_el, out_el = cin * h * w, co * ho * wo
     has_w = l["kind"] in ("conv", "fc")
     kh, kw = (l["h_in"], l["w_in"]) if l["kind"] == "fc" else (l["kh"], l["kw"])
-    w_el = co * cin * kh * kw if has_w else 0
+    D, Kd, _ = _depth(l) if has_w else (1, 1, 0)
+    in_el *= D                                     # a volumetric layer's input has D slices of h x w
+    w_el = co * cin * Kd * kh * kw if has_w else 0
     p_el = w_el + (co if (has_w and l["bias"]) else 0)
-    mac = out_el * cin * kh * kw if has_w else 0
+    mac = out_el * cin * Kd * kh * kw if has_w else 0
+    if l["kind"] == "attn":                        # the two products S = q^T k and y = A v: 2 * P * P * C multiply-adds
+        mac = 2 * (h * w) * (h * w) * co
     first = l["src"] < 0
     flop = 2 * mac * m * (2 if first else 3)
     sc = out_el if l.get("add_src") is not None else 0
