@@ -1,8 +1,9 @@
 """Layer lists of the benchmark workloads, as plain dicts, and their seeded tensors.
 
 A layer dict has the keys
-  kind      'conv' | 'fc' | 'maxpool2' | 'gap' | 'softmax_ce'
+  kind      'conv' | 'fc' | 'maxpool2' | 'gap' | 'softmax_ce' | 'attn'
   cin, cout, kh, kw, stride, pad, h_in, w_in
+  d_in, kd, pad_d       volumetric convolutions only (defaults 1, 1, 0): input depth, filter depth, depth padding
   relu, bias, scale     booleans (scale = frozen per-channel multiplier, i.e. a folded BatchNorm)
   src       index of the layer whose output is this layer's input (-1 = network input)
   add_src   index of the layer whose output is added before the ReLU, or None
@@ -20,18 +21,33 @@ BASE_SEED = 20220711
 
 
 def _layer(kind, cin, cout, k, stride, pad, h, w, relu=False, bias=False, scale=False,
-           src=None, add_src=None):
+           src=None, add_src=None, d=1, kd=1, pad_d=0):
     return dict(kind=kind, cin=cin, cout=cout, kh=k[0], kw=k[1], stride=stride, pad=pad, h_in=h, w_in=w,
-                relu=relu, bias=bias, scale=scale, src=src, add_src=add_src, cut_after=False)
+                relu=relu, bias=bias, scale=scale, src=src, add_src=add_src, cut_after=False, d_in=d, kd=kd, pad_d=pad_d)
+
+
+def out_dhw(l):
+    """(D, H, W) of a layer's output for one sample (D = 1 for everything that is not a volumetric convolution)."""
+    k = l["kind"]
+    if k == "conv":
+        s = l["stride"]
+        return ((l.get("d_in", 1) + 2 * l.get("pad_d", 0) - l.get("kd", 1)) // s + 1,
+                (l["h_in"] + 2 * l["pad"] - l["kh"]) // s + 1, (l["w_in"] + 2 * l["pad"] - l["kw"]) // s + 1)
+    if k == "maxpool2":
+        return (1, l["h_in"] // 2, l["w_in"] // 2)
+    if k == "attn":
+        return (1, l["h_in"], l["w_in"])
+    return (1, 1, 1)
 
 
 def out_shape(l):
-    """(C, H, W) of a layer's output for one image."""
+    """(C, H, W) of a layer's output for one image; the depth of a volume is folded into H (tensor [C][D*H][W])."""
     k = l["kind"]
     if k == "conv":
-        ho = (l["h_in"] + 2 * l["pad"] - l["kh"]) // l["stride"] + 1
-        wo = (l["w_in"] + 2 * l["pad"] - l["kw"]) // l["stride"] + 1
-        return (l["cout"], ho, wo)
+        do, ho, wo = out_dhw(l)
+        return (l["cout"], do * ho, wo)
+    if k == "attn":
+        return (l["cout"], l["h_in"], l["w_in"])
     if k == "fc":
         return (l["cout"], 1, 1)
     if k == "maxpool2":
@@ -44,13 +60,13 @@ def out_shape(l):
 
 
 def in_shape(l):
-    return (l["cin"], l["h_in"], l["w_in"])
+    return (l["cin"], (l.get("d_in", 1) if l["kind"] in ("conv", "fc") else 1) * l["h_in"], l["w_in"])
 
 
 class _Builder:
-    def __init__(self, c, h, w):
+    def __init__(self, c, h, w, d=1):
         self.layers = []
-        self.c, self.h, self.w = c, h, w
+        self.c, self.h, self.w, self.d = c, h, w, d          # h, w, d: true extents (a tensor is stored [C][D*H][W])
 
     @property
     def last(self):
@@ -59,7 +75,8 @@ class _Builder:
     def _push(self, l, src):
         l["src"] = self.last if src is None else src
         self.layers.append(l)
-        self.c, self.h, self.w = out_shape(l)
+        self.c = out_shape(l)[0]
+        self.d, self.h, self.w = out_dhw(l)
         return self.last
 
     def conv(self, cout, k, stride=1, pad=0, relu=True, bias=True, scale=False, src=None, add_src=None,
@@ -67,14 +84,30 @@ class _Builder:
         c, h, w = in_chw if in_chw else (self.c, self.h, self.w)
         return self._push(_layer("conv", c, cout, (k, k), stride, pad, h, w, relu, bias, scale, None, add_src), src)
 
+    def conv3d(self, cout, k, stride=1, pad=0, relu=True, bias=True, scale=False, src=None, add_src=None, in_cdhw=None):
+        """k x k x k filter over the volume [C][D][H][W]."""
+        c, d, h, w = in_cdhw if in_cdhw else (self.c, self.d, self.h, self.w)
+        return self._push(_layer("conv", c, cout, (k, k), stride, pad, h, w, relu, bias, scale, None, add_src, d=d, kd=k, pad_d=pad), src)
+
     def fc(self, cout, relu=True, bias=True):
-        return self._push(_layer("fc", self.c, cout, (self.h, self.w), 1, 0, self.h, self.w, relu, bias), None)
+        l = _layer("fc", self.c, cout, (self.h, self.w), 1, 0, self.h, self.w, relu, bias, d=self.d, kd=self.d)
+        return self._push(l, None)
 
     def pool(self):
+        assert self.d == 1
         return self._push(_layer("maxpool2", self.c, self.c, (2, 2), 2, 0, self.h, self.w), None)
 
     def gap(self):
-        return self._push(_layer("gap", self.c, self.c, (self.h, self.w), 1, 0, self.h, self.w), None)
+        h = self.d * self.h
+        return self._push(_layer("gap", self.c, self.c, (h, self.w), 1, 0, h, self.w), None)
+
+    def attn(self, src=None):
+        """Self-attention over all positions of the current tensor, whose 3*C channels are queries | keys | values."""
+        assert self.c % 3 == 0
+        d, h, w = self.d, self.h, self.w
+        i = self._push(_layer("attn", self.c, self.c // 3, (1, 1), 1, 0, d * h, w), src)
+        self.d, self.h, self.w = d, h, w          # the layer keeps the volume's extents (it sees them folded)
+        return i
 
     def loss(self):
         return self._push(_layer("softmax_ce", self.c, self.c, (1, 1), 1, 0, 1, 1), None)
@@ -84,7 +117,7 @@ class _Builder:
         layer is not a pooling layer (a pool stays with its conv) and not the loss."""
         L = self.layers
         for i, l in enumerate(L[:-1]):
-            ok = L[i + 1]["kind"] not in ("maxpool2", "softmax_ce", "gap")
+            ok = L[i + 1]["kind"] not in ("maxpool2", "softmax_ce", "gap", "attn")
             for j in range(i + 1, len(L)):
                 for ref in (L[j]["src"], L[j]["add_src"]):
                     if ref is not None and ref < i:
@@ -179,6 +212,69 @@ def r50_conv4x(cin=512, hw=28, mid=256, cout=1024, blocks=6):
     return b.finish()
 
 
+def _basic_block3d(b, cout, stride):
+    """The residual network layer of the volumetric use case: two 3x3x3 convolutions with folded normalisation and ReLU,
+    plus the shortcut (a 1x1x1 projection when the block down-samples)."""
+    x = b.last
+    cdhw = (b.c, b.d, b.h, b.w)
+    a = b.conv3d(cout, 3, stride=stride, pad=1, relu=True, scale=True, src=x)
+    after = (b.c, b.d, b.h, b.w)
+    if stride != 1 or cdhw[0] != cout:
+        sc = b.conv3d(cout, 1, stride=stride, pad=0, relu=False, scale=True, src=x, in_cdhw=cdhw)
+    else:
+        sc = x
+    b.conv3d(cout, 3, pad=1, relu=True, scale=True, src=a, add_src=sc, in_cdhw=after)
+
+
+def _attention_block(b):
+    """Residual self-attention: a 1x1x1 convolution makes queries | keys | values, the attention layer mixes the positions,
+    a 1x1x1 convolution projects back and the block input is added before the ReLU."""
+    x, c = b.last, b.c
+    b.conv3d(3 * c, 1, relu=False, src=x)
+    b.attn()
+    b.conv3d(c, 1, relu=True, src=b.last, add_src=x)
+
+
+def resattnet18_3d(widths=(32, 64, 128, 256), blocks=2, vol=32, n_classes=2, attention_from=2):
+    """A 3D-ResAttNet18-shaped network on synthetic one-channel volumes (stand-in for the structural-MRI scans of the
+    paper's first use case; two classes as in its AD-vs-NC task): 3x3x3 stem, four stages of `blocks` residual blocks
+    (stride 2 from the second stage on), a residual self-attention block after every stage from `attention_from` on
+    (where the volume is small enough for all-pairs attention), global average pooling, classifier."""
+    b = _Builder(1, vol, vol, vol)
+    b.conv3d(widths[0], 3, pad=1, scale=True)
+    for i, wd in enumerate(widths):
+        for j in range(blocks):
+            _basic_block3d(b, wd, 2 if (i > 0 and j == 0) else 1)
+        if i >= attention_from:
+            _attention_block(b)
+    b.gap()
+    b.fc(n_classes, relu=False)
+    b.loss()
+    return b.finish()
+
+
+def tiny_conv3d():
+    """Small volumetric network: 3x3x3 stem on 2 channels, one residual block, one strided block, attention, head."""
+    b = _Builder(2, 6, 6, 6)
+    b.conv3d(8, 3, pad=1, scale=True)
+    _basic_block3d(b, 8, 1)
+    _basic_block3d(b, 16, 2)
+    _attention_block(b)
+    b.gap(); b.fc(5, relu=False); b.loss()
+    return b.finish()
+
+
+def tiny_conv3d_mfma():
+    """The same shape with 32 / 64 channels, so that the matrix-core kernels take the volumetric layers."""
+    b = _Builder(2, 6, 6, 6)
+    b.conv3d(32, 3, pad=1, scale=True)
+    _basic_block3d(b, 32, 1)
+    _basic_block3d(b, 64, 2)
+    _attention_block(b)
+    b.gap(); b.fc(5, relu=False); b.loss()
+    return b.finish()
+
+
 def tiny_lenet():
     """2-conv, 2-FC net on 1x8x8 inputs for finite-difference checks."""
     b = _Builder(1, 8, 8)
@@ -238,6 +334,11 @@ CONFIGS = {
     "r50_conv4x":     (r50_conv4x, 64, 4, 1, "bf16", None),
     "vgg16_224":      (vgg16_224, 32, 8, 4, "bf16", None),
 }
+# the volumetric use case (not one of the five benchmark configurations): batch of six volumes as in the paper's runs,
+# three micro-batches of two, four partitions by the cost model
+EXTRA_CONFIGS = {
+    "resattnet18_3d": (resattnet18_3d, 6, 3, 4, "bf16", None),
+}
 
 
 def tensor_shapes(layers):
@@ -249,7 +350,7 @@ def param_shapes(l):
     """{'W': shape, 'b': shape, 's': shape} of a layer's parameters (only the ones it has)."""
     if l["kind"] not in ("conv", "fc"):
         return {}
-    p = {"W": (l["cout"], l["cin"], l["kh"], l["kw"])}
+    p = {"W": (l["cout"], l["cin"], l.get("kd", 1) * l["kh"], l["kw"])}          # [Cout][Cin][Kd*Kh][Kw]
     if l["bias"]:
         p["b"] = (l["cout"],)
     if l["scale"]:
@@ -269,7 +370,7 @@ def make_params(layers, seed=BASE_SEED, bf16=False, bias_std=0.0, momentum_std=0
         sh = param_shapes(l)
         if not sh:
             continue
-        fan_in = l["cin"] * l["kh"] * l["kw"]
+        fan_in = l["cin"] * l.get("kd", 1) * l["kh"] * l["kw"]
         p = {"W": rng.normal(seed, i * 8 + 0, sh["W"], 0.0, np.sqrt(2.0 / fan_in))}
         if bf16:
             p["W"] = rng.round_to_bf16(p["W"])
