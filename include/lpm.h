@@ -59,6 +59,9 @@ extern "C" {
 #define LPM_MAXPOOL2    2   /* 2x2 window, stride 2 (H, W even); gradient to the first maximum */
 #define LPM_GAP         3   /* global average pool over H x W                                  */
 #define LPM_SOFTMAX_CE  4   /* softmax cross-entropy on the logits; must be the last layer     */
+#define LPM_ATTN        5   /* one-head self-attention over the positions of a sample (the "self-attention layer" of
+                               the volumetric use case): the input's 3*cout channels are queries | keys | values,
+                               y_i = sum_j softmax_j(q_i.k_j / sqrt(cout)) v_j; no parameters                  */
 
 /* ---- layer flags (CONV / FC): y = relu( scale_c * z + bias_c + T[add_src] ) ---- */
 #define LPM_RELU   1
@@ -90,6 +93,11 @@ typedef struct lpm_layer {
     int32_t src;                /* tensor read as input (normally l-1)                              */
     int32_t add_src;            /* tensor added before the ReLU, or LPM_NONE                        */
     int32_t cut_allowed_after;  /* non-zero: a partition boundary may follow this layer             */
+    /* Volumetric (3-D) convolutions, the 3x3x3 layers of the method's first use case.  A tensor [C][D][H][W] is handled
+     * as [C][D*H][W] by every other layer kind (depth folded into the height); a CONV / FC layer with d_in > 1 unfolds
+     * it: its input tensor must have height d_in * h_in, its kernel is kd x kh x kw (weights [Cout][Kd][Kh][Kw][Cin]),
+     * the one stride applies to all three axes, pad_d pads the depth.  0 in d_in / kd means 1 (a 2-D layer). */
+    int32_t d_in, kd, pad_d;
 } lpm_layer;
 
 /* Machine and workload parameters of the cost model (all integers: plans are reproducible). */
@@ -297,6 +305,7 @@ int32_t lpm_schedule_run(lpm_schedule* s, int32_t mode, const void* x_batch, con
  * A fully connected layer is kh = h, kw = w, stride 1, pad 0. */
 typedef struct lpm_conv_geom {
     int32_t m, h, w, cin, cout, kh, kw, stride, pad;
+    int32_t d, kd, pad_d;      /* volumetric form: input [m][d][h][w][cin], weights [cout][kd][kh][kw][cin]; 0 = 1 (2-D) */
 } lpm_conv_geom;
 
 /* Scratch bytes the three contractions need for this geometry (host out-pointers, any may be NULL). */

@@ -21,7 +21,7 @@ lib = C.CDLL(_LIB)
 
 F32, BF16 = 0, 1
 LOCKED, OVERLAPPED, PIPELINED, GRAPH, ASYNC_UPDATE = 0, 1, 2, 16, 32
-KINDS = {"conv": 0, "fc": 1, "maxpool2": 2, "gap": 3, "softmax_ce": 4}
+KINDS = {"conv": 0, "fc": 1, "maxpool2": 2, "gap": 3, "softmax_ce": 4, "attn": 5}
 RELU, BIAS, SCALE = 1, 2, 4
 NONE = -2
 MAX_WINDOW = 4
@@ -35,7 +35,7 @@ class LpmError(RuntimeError):
 
 class lpm_layer(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("kind", "cin", "cout", "kh", "kw", "stride", "pad", "h_in", "w_in", "flags",
-                                         "src", "add_src", "cut_allowed_after")]
+                                         "src", "add_src", "cut_allowed_after", "d_in", "kd", "pad_d")]
 
 
 class lpm_cost_params(C.Structure):
@@ -50,7 +50,7 @@ class lpm_stage_buffers(C.Structure):
 
 
 class lpm_conv_geom(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("m", "h", "w", "cin", "cout", "kh", "kw", "stride", "pad")]
+    _fields_ = [(n, C.c_int32) for n in ("m", "h", "w", "cin", "cout", "kh", "kw", "stride", "pad", "d", "kd", "pad_d")]
 
 
 lib.lpm_last_error.restype = C.c_char_p
@@ -115,7 +115,8 @@ def layers_from_dicts(layers):
         flags = (RELU if l.get("relu") else 0) | (BIAS if l.get("bias") else 0) | (SCALE if l.get("scale") else 0)
         add = l.get("add_src")
         arr[i] = lpm_layer(KINDS[l["kind"]], l["cin"], l["cout"], l["kh"], l["kw"], l["stride"], l["pad"], l["h_in"],
-                           l["w_in"], flags, l["src"], NONE if add is None else add, 1 if l.get("cut_after") else 0)
+                           l["w_in"], flags, l["src"], NONE if add is None else add, 1 if l.get("cut_after") else 0,
+                           l.get("d_in", 1), l.get("kd", 1), l.get("pad_d", 0))
     return arr
 
 
@@ -170,7 +171,10 @@ def lpm_partition_costs(layers, Z, cp, layer_cost_ps, fixed_starts=None):
 
 
 def _geom(g):
-    return g if isinstance(g, lpm_conv_geom) else lpm_conv_geom(*[g[k] for k in ("m", "h", "w", "cin", "cout", "kh", "kw", "stride", "pad")])
+    if isinstance(g, lpm_conv_geom):
+        return g
+    return lpm_conv_geom(*([g[k] for k in ("m", "h", "w", "cin", "cout", "kh", "kw", "stride", "pad")] +
+                           [g.get("d", 1), g.get("kd", 1), g.get("pad_d", 0)]))
 
 
 def lpm_conv_ws_bytes(g, dtype):
@@ -387,21 +391,26 @@ def unpack_weight(flat, shape_oihw):
 
 
 def _oshape(l):
+    """(C, H, W) of a layer's output for one sample; a volumetric layer's depth is folded into H."""
     k = l["kind"]
     if k == "conv":
-        return (l["cout"], (l["h_in"] + 2 * l["pad"] - l["kh"]) // l["stride"] + 1,
+        d, kd, pd = l.get("d_in", 1), l.get("kd", 1), l.get("pad_d", 0)
+        return (l["cout"], ((d + 2 * pd - kd) // l["stride"] + 1) * ((l["h_in"] + 2 * l["pad"] - l["kh"]) // l["stride"] + 1),
                 (l["w_in"] + 2 * l["pad"] - l["kw"]) // l["stride"] + 1)
     if k == "fc":
         return (l["cout"], 1, 1)
     if k == "maxpool2":
         return (l["cin"], l["h_in"] // 2, l["w_in"] // 2)
+    if k == "attn":
+        return (l["cout"], l["h_in"], l["w_in"])
     return (l["cin"], 1, 1)
 
 
 def _wshape(l):
+    """Logical weight shape [Cout][Cin][Kd*Kh][Kw] (the filter depth folded into its height, like the activations)."""
     if l["kind"] == "fc":
-        return (l["cout"], l["cin"], l["h_in"], l["w_in"])
-    return (l["cout"], l["cin"], l["kh"], l["kw"])
+        return (l["cout"], l["cin"], l.get("d_in", 1) * l["h_in"], l["w_in"])
+    return (l["cout"], l["cin"], l.get("kd", 1) * l["kh"], l["kw"])
 
 
 _NET_STREAMS = {}
@@ -526,7 +535,8 @@ class Net:
 
     # ---- tensors
     def tensor_shape(self, t):
-        return _oshape(self.layers[t]) if t >= 0 else (self.layers[0]["cin"], self.layers[0]["h_in"], self.layers[0]["w_in"])
+        l0 = self.layers[0]
+        return _oshape(self.layers[t]) if t >= 0 else (l0["cin"], l0.get("d_in", 1) * l0["h_in"], l0["w_in"])
 
     def read_stash(self, t, slot):
         """Logical [m][C][H][W] value of internal tensor t from a stash slot."""

@@ -85,7 +85,7 @@ bool dgrad_uses_wt(int dtype, const ConvGeom& g) { return dtype == LPM_BF16 && !
 // (worth it while the kernel is bound by its launch: measured on the 224x224 VGG layers the scattered 2-byte stores
 // in the contraction's epilogue cost more than the separate pooling kernel, so large gradients keep that kernel)
 bool dgrad_can_unpool(int dtype, const ConvGeom& g) {
-    return dtype == LPM_BF16 && !fc_skinny_ok(g) && mfma_dgrad_ok(g) && g.stride == 1 &&
+    return dtype == LPM_BF16 && !g.is3d() && !fc_skinny_ok(g) && mfma_dgrad_ok(g) && g.stride == 1 &&
            (int64_t)g.rows_in() * g.Cin <= ((int64_t)1 << 20);
 }
 

@@ -71,6 +71,9 @@ struct IgemmArgs {
     int m_tiles;                 // host only: row tiles to launch (0: ceil(M / 64)); K the plan is made for (0: Ktot)
     int plan_K;
     // stride-1 data gradient routed through a 2x2 max-pooling (see UnpoolDesc): the rows are pooled pixels
+    // volumetric layers (forward and stride-1 data gradient): depth of the gathered tensor and of the row space, filter
+    // depth and depth padding; a row space image index is then sample * Dr + slice.  2-D layers: 1, 1, 1, 0.
+    int Di, Dr, Kd, pad_d;
     const uint16_t* pool_x;      // pooling input [m][2*Hr][2*Wr][N], NULL: plain output
     uint16_t* pool_dst;
     int pool_acc, pool_mask;     // (the per-channel factor is mscale)
@@ -369,7 +372,7 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
     // that start in the padding; it is only used when the tap lands inside the image) and the pixel's
     // coordinates at tap (0,0).  Per K tile only a wave-uniform tap offset is added.
     // (Strided data gradient: the row's coordinates inside its residue class and the image's base offset.)
-    int a_h0[A_CH], a_w0[A_CH];
+    int a_h0[A_CH], a_w0[A_CH], a_d0[A_CH];
     unsigned a_base[A_CH];
     bool a_ok[A_CH];
     unsigned b_off[B_CH];
@@ -390,11 +393,13 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
             hq = t % Hc;
             n = t / Hc;
         }
-        if (MODE == MODE_FWD) { a_h0[c] = hq * p.stride - p.pad; a_w0[c] = wq * p.stride - p.pad; }
-        else if (MODE == MODE_DGRAD) { a_h0[c] = hq + p.pad; a_w0[c] = wq + p.pad; }
-        else { a_h0[c] = hq; a_w0[c] = wq; }
+        int dq = 0;
+        if (MODE != MODE_DGRAD_S && p.Dr > 1) { const int ns = n / p.Dr; dq = n - ns * p.Dr; n = ns; }      // sample, slice
+        if (MODE == MODE_FWD) { a_h0[c] = hq * p.stride - p.pad; a_w0[c] = wq * p.stride - p.pad; a_d0[c] = dq * p.stride - p.pad_d; }
+        else if (MODE == MODE_DGRAD) { a_h0[c] = hq + p.pad; a_w0[c] = wq + p.pad; a_d0[c] = dq + p.pad_d; }
+        else { a_h0[c] = hq; a_w0[c] = wq; a_d0[c] = 0; }
         if (MODE == MODE_DGRAD_S) a_base[c] = (unsigned)(n * p.Hi * p.Wi * p.Ci + kc * 8) * 2u;
-        else a_base[c] = (unsigned)(((n * p.Hi + a_h0[c]) * p.Wi + a_w0[c]) * p.Ci + kc * 8) * 2u;
+        else a_base[c] = (unsigned)((((n * p.Di + a_d0[c]) * p.Hi + a_h0[c]) * p.Wi + a_w0[c]) * p.Ci + kc * 8) * 2u;
     }
 #pragma unroll
     for (int c = 0; c < B_CH; ++c) {
@@ -402,14 +407,19 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
         b_off[c] = ((id < BN * CPR) & (n < p.N)) ? (unsigned)(((size_t)n * p.Ktot + (id % CPR) * 8) * 2) : OOB;
     }
     // cursor of the next K tile to load (tiles are loaded strictly in order): filter tap and channel offset
-    int cur_kt = kt0, cur_c0, cur_kh, cur_kw;
+    int cur_kt = kt0, cur_c0, cur_kh, cur_kw, cur_kd = 0;
     {
         const int k0 = kt0 * BK, tap = k0 / p.Ci;
         cur_c0 = k0 - tap * p.Ci;
         if (MODE == MODE_DGRAD_S) {
             const int nkw = kw_first < p.Kw ? (p.Kw - kw_first + kstep - 1) / kstep : 1;
             cur_kh = kh_first + (tap / nkw) * kstep; cur_kw = kw_first + (tap % nkw) * kstep;
-        } else { cur_kh = tap / p.Kw; cur_kw = tap - cur_kh * p.Kw; }
+        } else {
+            const int hw = p.Kh * p.Kw;
+            cur_kd = tap / hw;
+            const int r = tap - cur_kd * hw;
+            cur_kh = r / p.Kw; cur_kw = r - cur_kh * p.Kw;
+        }
     }
     // two K tiles in flight in registers
     uint4 ra0[A_CH], rb0[B_CH], ra1[A_CH], rb1[B_CH];
@@ -417,10 +427,10 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
 #define LPM_LOAD_TILE(RA, RB)                                                                                \
     {                                                                                                        \
         const bool live_ = cur_kt < kt1;                                                                     \
-        const int kh_ = cur_kh, kw_ = cur_kw;                                                                \
+        const int kh_ = cur_kh, kw_ = cur_kw, kd_ = cur_kd;                                                  \
         const unsigned tapoff_ = (MODE == MODE_FWD)                                                          \
-                                     ? (unsigned)((kh_ * p.Wi + kw_) * p.Ci + cur_c0) * 2u                   \
-                                     : (unsigned)(cur_c0 - (kh_ * p.Wi + kw_) * p.Ci) * 2u;                  \
+                                     ? (unsigned)(((kd_ * p.Hi + kh_) * p.Wi + kw_) * p.Ci + cur_c0) * 2u    \
+                                     : (unsigned)(cur_c0 - ((kd_ * p.Hi + kh_) * p.Wi + kw_) * p.Ci) * 2u;   \
         /* strided data gradient: output pixel = class coordinate + (ph + pad - kh) / stride, an exact quotient */ \
         const int dh_ = (MODE == MODE_DGRAD_S) ? (ph + p.pad - kh_) / kstep : 0;                             \
         const int dw_ = (MODE == MODE_DGRAD_S) ? (pw + p.pad - kw_) / kstep : 0;                             \
@@ -428,8 +438,13 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
             int h_, w_;                                                                                      \
             bool ok_ = a_ok[c] & live_;                                                                      \
             unsigned off_;                                                                                   \
-            if (MODE == MODE_FWD) { h_ = a_h0[c] + kh_; w_ = a_w0[c] + kw_; off_ = a_base[c] + tapoff_; }    \
-            else if (MODE == MODE_DGRAD) { h_ = a_h0[c] - kh_; w_ = a_w0[c] - kw_; off_ = a_base[c] + tapoff_; } \
+            if (MODE == MODE_FWD) {                                                                          \
+                h_ = a_h0[c] + kh_; w_ = a_w0[c] + kw_; off_ = a_base[c] + tapoff_;                          \
+                ok_ = ok_ & ((unsigned)(a_d0[c] + kd_) < (unsigned)p.Di);                                    \
+            } else if (MODE == MODE_DGRAD) {                                                                 \
+                h_ = a_h0[c] - kh_; w_ = a_w0[c] - kw_; off_ = a_base[c] + tapoff_;                          \
+                ok_ = ok_ & ((unsigned)(a_d0[c] - kd_) < (unsigned)p.Di);                                    \
+            }                                                                                                \
             else {                                                                                           \
                 h_ = a_h0[c] + dh_; w_ = a_w0[c] + dw_;                                                      \
                 off_ = a_base[c] + (unsigned)((h_ * p.Wi + w_) * p.Ci + cur_c0) * 2u;                        \
@@ -437,7 +452,7 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
             ok_ = ok_ & ((unsigned)h_ < (unsigned)p.Hi) & ((unsigned)w_ < (unsigned)p.Wi);                   \
             RA[c] = buf_load16(rsA, ok_ ? off_ : OOB);                                                       \
         }                                                                                                    \
-        const unsigned k0b_ = (unsigned)((kh_ * p.Kw + kw_) * p.Ci + cur_c0) * 2u;                           \
+        const unsigned k0b_ = (unsigned)(((kd_ * p.Kh + kh_) * p.Kw + kw_) * p.Ci + cur_c0) * 2u;            \
         _Pragma("unroll") for (int c = 0; c < B_CH; ++c)                                                     \
             RB[c] = buf_load16(rsB, ((b_off[c] == OOB) | !live_) ? OOB : b_off[c] + k0b_);                   \
         ++cur_kt;                                                                                            \
@@ -445,7 +460,10 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
         if (cur_c0 >= p.Ci) {                                                                                \
             cur_c0 = 0;                                                                                      \
             cur_kw += kstep;                                                                                 \
-            if (cur_kw >= p.Kw) { cur_kw = kw_first; cur_kh += kstep; }                                      \
+            if (cur_kw >= p.Kw) {                                                                            \
+                cur_kw = kw_first; cur_kh += kstep;                                                          \
+                if (MODE != MODE_DGRAD_S && cur_kh >= p.Kh) { cur_kh = 0; ++cur_kd; }                        \
+            }                                                                                                \
         }                                                                                                    \
     }
 #define LPM_STORE_TILE(BUF, RA, RB)                                                                          \
@@ -704,6 +722,9 @@ static void launch_igemm_cfg(const IgemmPlan& pl, const IgemmArgs& a, hipStream_
 
 static hipError_t run_igemm(int mode, IgemmArgs a, void* ws, hipStream_t st) {
     a.wshift = a.hshift = -1;
+    if (a.Di < 1) a.Di = 1;
+    if (a.Dr < 1) a.Dr = 1;
+    if (a.Kd < 1) a.Kd = 1;
     if (a.Wr > 0 && a.Hr > 0 && !(a.Wr & (a.Wr - 1)) && !(a.Hr & (a.Hr - 1))) {
         a.wshift = __builtin_ctz((unsigned)a.Wr);
         a.hshift = __builtin_ctz((unsigned)a.Hr);
@@ -739,7 +760,8 @@ static bool fits32(const ConvGeom& g) {
     return g.rows_in() * g.Cin < lim && g.rows_out() * g.Cout < lim && (int64_t)g.Cout * g.K() < lim;
 }
 bool mfma_fwd_ok(const ConvGeom& g) { return g.Cin % 32 == 0 && fits32(g); }
-bool mfma_dgrad_ok(const ConvGeom& g) { return g.Cout % 32 == 0 && g.stride <= 4 && fits32(g); }
+// (a strided data gradient goes by residue classes of the two image axes: two-dimensional layers only)
+bool mfma_dgrad_ok(const ConvGeom& g) { return g.Cout % 32 == 0 && g.stride <= 4 && (g.stride == 1 || !g.is3d()) && fits32(g); }
 
 size_t mfma_fwd_ws_bytes(const ConvGeom& g) {
     const IgemmPlan pl = plan_igemm(g.rows_out(), g.Cout, g.K(), g.Cin);
@@ -748,7 +770,7 @@ size_t mfma_fwd_ws_bytes(const ConvGeom& g) {
 // K a residue class of a strided data gradient runs over at most: the taps of matching parity
 static int dgrad_plan_K(const ConvGeom& g) {
     const int s = g.stride;
-    return ((g.Kh + s - 1) / s) * ((g.Kw + s - 1) / s) * g.Cout;
+    return g.Kd * ((g.Kh + s - 1) / s) * ((g.Kw + s - 1) / s) * g.Cout;
 }
 
 size_t mfma_dgrad_ws_bytes(const ConvGeom& g) {
@@ -759,7 +781,7 @@ size_t mfma_dgrad_ws_bytes(const ConvGeom& g) {
 // whether the forward contraction of this layer can also store the 2x2 max-pooling of its output (pool_y below):
 // the split-K form, whose second kernel sees whole pooling windows
 bool mfma_fwd_pools(const ConvGeom& g) {
-    return mfma_fwd_ok(g) && !(g.Ho & 1) && !(g.Wo & 1) && plan_igemm(g.rows_out(), g.Cout, g.K(), g.Cin).splits > 1;
+    return mfma_fwd_ok(g) && !g.is3d() && !(g.Ho & 1) && !(g.Wo & 1) && plan_igemm(g.rows_out(), g.Cout, g.K(), g.Cin).splits > 1;
 }
 
 hipError_t mfma_conv_fwd(const ConvGeom& g, const void* x, const void* w, const float* scale, const float* bias,
@@ -772,6 +794,7 @@ hipError_t mfma_conv_fwd(const ConvGeom& g, const void* x, const void* w, const 
     a.M = (int)g.rows_out(); a.N = g.Cout; a.Ktot = g.K();
     a.Hi = g.H; a.Wi = g.W; a.Ci = g.Cin; a.Hr = g.Ho; a.Wr = g.Wo; a.Kw = g.Kw; a.stride = g.stride; a.pad = g.pad;
     a.Kh = g.Kh;
+    a.Di = g.D; a.Dr = g.Do; a.Kd = g.Kd; a.pad_d = g.pad_d;
     a.a_bytes = (unsigned)(g.rows_in() * g.Cin * 2); a.b_bytes = (unsigned)((int64_t)g.Cout * g.K() * 2);
     return run_igemm(MODE_FWD, a, ws, st);
 }
@@ -791,7 +814,8 @@ hipError_t mfma_conv_dgrad(const ConvGeom& g, const void* dz, const void* wt, vo
         a.pool_x = (const uint16_t*)unpool->pool_x; a.pool_dst = (uint16_t*)unpool->dst;
         a.pool_acc = unpool->accumulate; a.pool_mask = unpool->mask; a.mscale = unpool->mscale;
     }
-    a.M = (int)g.rows_in(); a.N = g.Cin; a.Ktot = g.Kh * g.Kw * g.Cout;
+    a.M = (int)g.rows_in(); a.N = g.Cin; a.Ktot = g.taps() * g.Cout;
+    a.Di = g.Do; a.Dr = g.D; a.Kd = g.Kd; a.pad_d = g.pad_d;
     a.Hi = g.Ho; a.Wi = g.Wo; a.Ci = g.Cout; a.Hr = g.H; a.Wr = g.W; a.Kw = g.Kw; a.stride = g.stride; a.pad = g.pad;
     a.a_bytes = (unsigned)(g.rows_out() * g.Cout * 2); a.b_bytes = (unsigned)((int64_t)g.Cout * g.K() * 2);
     a.Kh = g.Kh;
@@ -827,6 +851,7 @@ struct WgradArgs {
     int accumulate;
     int co_tiles, ci_tiles;
     int x_cin, x_taps;     // flattened mode (see wgrad_kernel): channels and filter taps of the real input
+    int Kh, D, Do, pad_d;  // volumetric layers: filter height (KhKw then counts Kd*Kh*Kw taps), slices in / out, depth padding
 };
 
 template <int LDK>
@@ -872,7 +897,8 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
     const int tap = tile % p.KhKw;
     const int co_t = tile / p.KhKw;
     const int co0 = co_t * BM, ci0 = ci_t * BN;
-    const int kh = tap / p.Kw, kw = tap - kh * p.Kw;
+    const int kd = tap / (p.Kh * p.Kw), tap2 = tap - kd * (p.Kh * p.Kw);
+    const int kh = tap2 / p.Kw, kw = tap2 - kh * p.Kw;
     const int rt0 = split * p.rt_per_split, rt1 = min(p.rt_total, rt0 + p.rt_per_split);
 
     // Two pixel tiles in flight in registers; out-of-range items (ragged channels, pixels past the end, taps
@@ -951,9 +977,11 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
                     }                                                                                        \
                 } else {                                                                                     \
                     const int h_ = ho_ * p.stride + kh - p.pad, w_ = wo_ * p.stride + kw - p.pad;            \
+                    int img_ = n_, d_ = 0;        /* n_ counts (sample, output slice) pairs */                   \
+                    if (p.Do > 1 || p.D > 1) { const int ns_ = n_ / p.Do; d_ = (n_ - ns_ * p.Do) * p.stride + kd - p.pad_d; img_ = ns_ * p.D + d_; } \
                     const bool ok_ = b_chok[t] & live_ & (b_r[t] + j < p.R) & ((unsigned)h_ < (unsigned)p.H) & \
-                                     ((unsigned)w_ < (unsigned)p.W);                                         \
-                    QB[t][j] = buf_load16(rsX, ok_ ? (unsigned)(((n_ * p.H + h_) * p.W + w_) * p.Cin) * 2u + b_choff[t] : OOB); \
+                                     ((unsigned)w_ < (unsigned)p.W) & ((unsigned)d_ < (unsigned)p.D);        \
+                    QB[t][j] = buf_load16(rsX, ok_ ? (unsigned)(((img_ * p.H + h_) * p.W + w_) * p.Cin) * 2u + b_choff[t] : OOB); \
                 }                                                                                            \
                 ++wo_;                                                                                       \
                 if (wo_ == p.Wo) { wo_ = 0; ++ho_; if (ho_ == p.Ho) { ho_ = 0; ++n_; } }                     \
@@ -1074,7 +1102,7 @@ static WgradPlan plan_wgrad(const ConvGeom& g) {
     const int t = pl.big ? 128 : 64;
     pl.co_tiles = (g.Cout + t - 1) / t;
     pl.ci_tiles = (g.Cin + t - 1) / t;
-    const int64_t tiles = (int64_t)pl.co_tiles * pl.ci_tiles * g.Kh * g.Kw;
+    const int64_t tiles = (int64_t)pl.co_tiles * pl.ci_tiles * g.taps();
     int s = (int)std::min<int64_t>(512 / std::max<int64_t>(tiles, 1), std::max(1, pl.rt_total / 4));
     if (s > 24) s = 24;          // beyond this the partial sums cost more than the shorter pixel loops save
     // the partials must stay modest for very large weight tensors
@@ -1182,7 +1210,8 @@ hipError_t mfma_conv_wgrad(const ConvGeom& g, const void* x, const void* dz, flo
     WgradArgs a{};
     a.X = (const uint16_t*)x; a.DZ = (const uint16_t*)dz;
     a.out = pl.splits > 1 ? (float*)ws : dw;
-    a.Cout = g.Cout; a.Cin = g.Cin; a.KhKw = g.Kh * g.Kw; a.Kw = g.Kw;
+    a.Cout = g.Cout; a.Cin = g.Cin; a.KhKw = g.taps(); a.Kw = g.Kw;
+    a.Kh = g.Kh; a.D = g.D; a.Do = g.Do; a.pad_d = g.pad_d;
     a.H = g.H; a.W = g.W; a.Ho = g.Ho; a.Wo = g.Wo; a.stride = g.stride; a.pad = g.pad;
     a.R = (int)g.rows_out();
     a.db = dbias; a.rscale = rscale;
@@ -1236,7 +1265,7 @@ __global__ void __launch_bounds__(256) wgrad_reduce_short(const float* __restric
 }
 
 // Weight gradient of an image-input layer (Cin*Kh*Kw <= 64): one N tile holds every (tap, channel) index.
-bool mfma_wgrad_flat_ok(const ConvGeom& g) { return g.K() <= 64 && g.Cout % 8 == 0 && fits32(g); }
+bool mfma_wgrad_flat_ok(const ConvGeom& g) { return !g.is3d() && g.K() <= 64 && g.Cout % 8 == 0 && fits32(g); }
 
 static WgradPlan plan_wgrad_flat(const ConvGeom& g) {
     WgradPlan pl{};
@@ -1264,6 +1293,7 @@ hipError_t mfma_conv_wgrad_flat(const ConvGeom& g, const void* x, const void* dz
     a.X = (const uint16_t*)x; a.DZ = (const uint16_t*)dz;
     a.out = pl.splits > 1 ? (float*)ws : dw;
     a.Cout = g.Cout; a.Cin = g.K(); a.KhKw = 1; a.Kw = g.Kw;
+    a.Kh = 1; a.D = 1; a.Do = 1; a.pad_d = 0;
     a.x_cin = g.Cin; a.x_taps = g.Kh * g.Kw;
     a.H = g.H; a.W = g.W; a.Ho = g.Ho; a.Wo = g.Wo; a.stride = g.stride; a.pad = g.pad;
     a.R = (int)g.rows_out();

@@ -12,7 +12,7 @@ constexpr int SK_MAXK = 32;       // Cin*Kh*Kw
 constexpr int SK_MAXCO = 128;
 
 bool smallk_ok(const ConvGeom& g) {
-    return g.K() <= SK_MAXK && g.Cout <= SK_MAXCO && g.Cout % 8 == 0 && g.rows_out() < (1ll << 31) / SK_MAXCO;
+    return !g.is3d() && g.K() <= SK_MAXK && g.Cout <= SK_MAXCO && g.Cout % 8 == 0 && g.rows_out() < (1ll << 31) / SK_MAXCO;
 }
 
 // one thread = PX output pixels (consecutive rows of the flattened output) x 8 output channels: the filter values

@@ -16,7 +16,7 @@ hipError_t launch_splitk_epilogue(const float* part, int splits, int64_t MN, int
 constexpr int FC_MAX_M = 8;       // beyond this the per-lane accumulators no longer fit the register file
 
 bool fc_skinny_ok(const ConvGeom& g) {
-    return g.Ho == 1 && g.Wo == 1 && g.Kh == g.H && g.Kw == g.W && g.pad == 0 && g.m <= FC_MAX_M && g.K() % 8 == 0 &&
+    return !g.is3d() && g.Ho == 1 && g.Wo == 1 && g.Kh == g.H && g.Kw == g.W && g.pad == 0 && g.m <= FC_MAX_M && g.K() % 8 == 0 &&
            (int64_t)g.m * g.K() < ((int64_t)1 << 31);
 }
 

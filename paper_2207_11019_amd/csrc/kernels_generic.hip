@@ -19,6 +19,7 @@ static inline unsigned nblk(int64_t n, int per) { return (unsigned)((n + per - 1
 
 // --------------------------------------------------------------------------------------------------
 // convolution forward, eq. 1 for a conv/FC layer:  y = relu?(scale*z + bias + add)
+// (two- and three-dimensional: a 2-D layer has D = Do = Kd = 1)
 template <typename T>
 __global__ void __launch_bounds__(256) conv_fwd_generic(ConvGeom g, const T* __restrict__ x, const T* __restrict__ w,
                                                         const float* __restrict__ scale, const float* __restrict__ bias,
@@ -27,18 +28,25 @@ __global__ void __launch_bounds__(256) conv_fwd_generic(ConvGeom g, const T* __r
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
     const int co = (int)(idx % g.Cout);
-    const int64_t row = idx / g.Cout;
-    const int wo = (int)(row % g.Wo), ho = (int)((row / g.Wo) % g.Ho), n = (int)(row / ((int64_t)g.Wo * g.Ho));
+    int64_t row = idx / g.Cout;
+    const int wo = (int)(row % g.Wo); row /= g.Wo;
+    const int ho = (int)(row % g.Ho); row /= g.Ho;
+    const int dq = (int)(row % g.Do);
+    const int n = (int)(row / g.Do);
     float acc = 0.f;
-    for (int kh = 0; kh < g.Kh; ++kh) {
-        const int h = ho * g.stride + kh - g.pad;
-        if (h < 0 || h >= g.H) continue;
-        for (int kw = 0; kw < g.Kw; ++kw) {
-            const int ww = wo * g.stride + kw - g.pad;
-            if (ww < 0 || ww >= g.W) continue;
-            const T* xp = x + (((int64_t)n * g.H + h) * g.W + ww) * g.Cin;
-            const T* wp = w + (((int64_t)co * g.Kh + kh) * g.Kw + kw) * g.Cin;
-            for (int ci = 0; ci < g.Cin; ++ci) acc = fmaf(ld(xp, ci), ld(wp, ci), acc);
+    for (int kd = 0; kd < g.Kd; ++kd) {
+        const int d = dq * g.stride + kd - g.pad_d;
+        if (d < 0 || d >= g.D) continue;
+        for (int kh = 0; kh < g.Kh; ++kh) {
+            const int h = ho * g.stride + kh - g.pad;
+            if (h < 0 || h >= g.H) continue;
+            for (int kw = 0; kw < g.Kw; ++kw) {
+                const int ww = wo * g.stride + kw - g.pad;
+                if (ww < 0 || ww >= g.W) continue;
+                const T* xp = x + ((((int64_t)n * g.D + d) * g.H + h) * g.W + ww) * g.Cin;
+                const T* wp = w + ((((int64_t)co * g.Kd + kd) * g.Kh + kh) * g.Kw + kw) * g.Cin;
+                for (int ci = 0; ci < g.Cin; ++ci) acc = fmaf(ld(xp, ci), ld(wp, ci), acc);
+            }
         }
     }
     if (scale) acc *= scale[co];
@@ -66,24 +74,33 @@ __global__ void __launch_bounds__(256) conv_dgrad_generic(ConvGeom g, const T* _
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
     const int ci = (int)(idx % g.Cin);
-    const int64_t row = idx / g.Cin;
-    const int ww = (int)(row % g.W), h = (int)((row / g.W) % g.H), n = (int)(row / ((int64_t)g.W * g.H));
+    int64_t row = idx / g.Cin;
+    const int ww = (int)(row % g.W); row /= g.W;
+    const int h = (int)(row % g.H); row /= g.H;
+    const int d = (int)(row % g.D);
+    const int n = (int)(row / g.D);
+    const int64_t wstride = (int64_t)g.taps() * g.Cin;
     float acc = 0.f;
-    for (int kh = 0; kh < g.Kh; ++kh) {
-        const int hh = h + g.pad - kh;
-        if (hh < 0 || hh % g.stride) continue;
-        const int ho = hh / g.stride;
-        if (ho >= g.Ho) continue;
-        for (int kw = 0; kw < g.Kw; ++kw) {
-            const int wq = ww + g.pad - kw;
-            if (wq < 0 || wq % g.stride) continue;
-            const int wo = wq / g.stride;
-            if (wo >= g.Wo) continue;
-            const T* dp = dz + (((int64_t)n * g.Ho + ho) * g.Wo + wo) * g.Cout;
-            const T* wp = w + ((int64_t)kh * g.Kw + kw) * g.Cin + ci;
-            const int64_t wstride = (int64_t)g.Kh * g.Kw * g.Cin;
-            if (dzscale) { for (int co = 0; co < g.Cout; ++co) acc = fmaf(ld(dp, co) * dzscale[co], ld(wp, co * wstride), acc); }
-            else { for (int co = 0; co < g.Cout; ++co) acc = fmaf(ld(dp, co), ld(wp, co * wstride), acc); }
+    for (int kd = 0; kd < g.Kd; ++kd) {
+        const int dd = d + g.pad_d - kd;
+        if (dd < 0 || dd % g.stride) continue;
+        const int dq = dd / g.stride;
+        if (dq >= g.Do) continue;
+        for (int kh = 0; kh < g.Kh; ++kh) {
+            const int hh = h + g.pad - kh;
+            if (hh < 0 || hh % g.stride) continue;
+            const int ho = hh / g.stride;
+            if (ho >= g.Ho) continue;
+            for (int kw = 0; kw < g.Kw; ++kw) {
+                const int wq = ww + g.pad - kw;
+                if (wq < 0 || wq % g.stride) continue;
+                const int wo = wq / g.stride;
+                if (wo >= g.Wo) continue;
+                const T* dp = dz + ((((int64_t)n * g.Do + dq) * g.Ho + ho) * g.Wo + wo) * g.Cout;
+                const T* wp = w + (((int64_t)kd * g.Kh + kh) * g.Kw + kw) * g.Cin + ci;
+                if (dzscale) { for (int co = 0; co < g.Cout; ++co) acc = fmaf(ld(dp, co) * dzscale[co], ld(wp, co * wstride), acc); }
+                else { for (int co = 0; co < g.Cout; ++co) acc = fmaf(ld(dp, co), ld(wp, co * wstride), acc); }
+            }
         }
     }
     if (accumulate) acc += ld(dx, idx);
@@ -113,18 +130,21 @@ __global__ void __launch_bounds__(256) conv_wgrad_generic(ConvGeom g, const T* _
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
     const int ci = (int)(idx % g.Cin);
-    const int kw = (int)((idx / g.Cin) % g.Kw), kh = (int)((idx / ((int64_t)g.Cin * g.Kw)) % g.Kh);
-    const int co = (int)(idx / K);
-    const int nho = g.m * g.Ho;
+    int64_t t = idx / g.Cin;
+    const int kw = (int)(t % g.Kw); t /= g.Kw;
+    const int kh = (int)(t % g.Kh); t /= g.Kh;
+    const int kd = (int)(t % g.Kd);
+    const int co = (int)(t / g.Kd);
+    const int nho = g.m * g.Do * g.Ho;                 // lines of Wo output pixels: (n, do, ho)
     const int per = (nho + chunks - 1) / chunks;
     const int r0 = blockIdx.y * per, r1 = min(nho, r0 + per);
     float acc = 0.f;
     for (int r = r0; r < r1; ++r) {
-        const int n = r / g.Ho, ho = r % g.Ho;
-        const int h = ho * g.stride + kh - g.pad;
-        if (h < 0 || h >= g.H) continue;
+        const int ho = r % g.Ho, nd = r / g.Ho, dq = nd % g.Do, n = nd / g.Do;
+        const int h = ho * g.stride + kh - g.pad, d = dq * g.stride + kd - g.pad_d;
+        if (h < 0 || h >= g.H || d < 0 || d >= g.D) continue;
         const T* dp = dz + ((int64_t)r * g.Wo) * g.Cout + co;
-        const T* xp = x + (((int64_t)n * g.H + h) * g.W) * g.Cin + ci;
+        const T* xp = x + ((((int64_t)n * g.D + d) * g.H + h) * g.W) * g.Cin + ci;
         for (int wo = 0; wo < g.Wo; ++wo) {
             const int ww = wo * g.stride + kw - g.pad;
             if (ww < 0 || ww >= g.W) continue;
@@ -152,7 +172,7 @@ hipError_t reduce_partials_launch(const float* part, float* dst, int64_t n, int 
 
 static int wgrad_generic_chunks(const ConvGeom& g) {
     const int64_t total = (int64_t)g.Cout * g.K();
-    const int nho = g.m * g.Ho;
+    const int nho = g.m * g.Do * g.Ho;
     int64_t c = ((int64_t)1 << 22) / total;     // keep the partials within a few MB
     const int64_t want = (nho + 3) / 4;          // a thread walks at most 4 (n,ho) lines
     if (c > want) c = want;

@@ -99,6 +99,7 @@ extern "C" int32_t lpm_layerwise_create(const lpm_conv_geom* g, int32_t dtype, i
         g->pad < 0 || g->pad >= g->kh || g->pad >= g->kw || g->h + 2 * g->pad < g->kh || g->w + 2 * g->pad < g->kw)
         return fail(LPM_ESHAPE, "bad convolution geometry");
     if (g->cout % n || (g->cout / n) % 8) return fail(LPM_ESHAPE, "cout / n must be a whole multiple of 8 channels");
+    if (g->d > 1 || g->kd > 1) return fail(LPM_ESHAPE, "layer-wise partitioning takes two-dimensional layers");
     lpm_layerwise* L = new (std::nothrow) lpm_layerwise{};
     if (!L) return fail(LPM_ENOMEM, "out of host memory");
     const int32_t ho = (g->h + 2 * g->pad - g->kh) / g->stride + 1, wo = (g->w + 2 * g->pad - g->kw) / g->stride + 1;

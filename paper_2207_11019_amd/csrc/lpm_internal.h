@@ -33,7 +33,7 @@ hipError_t pick_concurrent_streams(const hipStream_t* taken, int n_taken, hipStr
 hipError_t launch_spin(long long ticks, hipStream_t st);
 
 // ---- validated network description ---------------------------------------------------------------
-struct Shape { int32_t c, h, w; size_t elems() const { return (size_t)c * h * w; } };
+struct Shape { int32_t c, h, w; size_t elems() const { return (size_t)c * h * w; } };      // (a volume's depth is folded into h)
 
 // Checks the whole list (kinds, extents, references, shapes) and returns per-tensor shapes:
 // shapes[0] is tensor -1 (the network input), shapes[t+1] the output of layer t.
@@ -42,13 +42,19 @@ int32_t validate_network(const lpm_layer* layers, int32_t L, std::vector<lpm_lay
                          std::vector<Shape>& shapes);
 
 inline bool has_weights(const lpm_layer& l) { return l.kind == LPM_CONV || l.kind == LPM_FC; }
+inline int32_t taps_of(const lpm_layer& l) { return (l.kd > 0 ? l.kd : 1) * l.kh * l.kw; }      // after validate_network: kd >= 1
 
 // ---- geometry handed to the kernel launchers -----------------------------------------------------
+// Volumetric layers: D input slices of H x W, kernel Kd x Kh x Kw, Do output slices (2-D layers: D = Do = Kd = 1,
+// pad_d = 0).  Only the kernels that say so handle is3d() geometries; the others are not offered them.
 struct ConvGeom {
     int32_t m, H, W, Cin, Ho, Wo, Cout, Kh, Kw, stride, pad;
-    __host__ __device__ int64_t rows_out() const { return (int64_t)m * Ho * Wo; }
-    __host__ __device__ int64_t rows_in() const { return (int64_t)m * H * W; }
-    __host__ __device__ int32_t K() const { return Kh * Kw * Cin; }
+    int32_t D = 1, Do = 1, Kd = 1, pad_d = 0;
+    __host__ __device__ int64_t rows_out() const { return (int64_t)m * Do * Ho * Wo; }
+    __host__ __device__ int64_t rows_in() const { return (int64_t)m * D * H * W; }
+    __host__ __device__ int32_t K() const { return Kd * Kh * Kw * Cin; }
+    __host__ __device__ int32_t taps() const { return Kd * Kh * Kw; }
+    __host__ __device__ bool is3d() const { return D > 1 || Kd > 1; }
 };
 
 // All launchers enqueue on `st` and return the launch status.  `dtype` selects the element type of
@@ -131,6 +137,13 @@ hipError_t launch_gap_fwd(int dtype, int32_t m, int32_t HW, int32_t C, const voi
 hipError_t launch_gap_bwd(int dtype, int32_t m, int32_t HW, int32_t C, const void* dy, void* dx, int accumulate,
                           const void* mask, const float* mscale, hipStream_t st);
 // dlogits = (softmax(logits) - onehot) * loss_scale;  *loss_accum += loss_scale * sum_n -log p_n[label_n]
+// one-head self-attention over P positions per sample: x [m][P][3C] (queries | keys | values), y [m][P][C]
+hipError_t launch_attn_fwd(int dtype, int32_t m, int32_t P, int32_t C, const void* x, void* y, hipStream_t st);
+// dx (+)= gradient w.r.t. x given dy [m][P][C]; ws: attn_bwd_ws_bytes (row statistics of the recomputed softmax)
+hipError_t launch_attn_bwd(int dtype, int32_t m, int32_t P, int32_t C, const void* x, const void* dy, void* dx, int accumulate,
+                           void* ws, hipStream_t st);
+size_t attn_bwd_ws_bytes(int32_t m, int32_t P);
+bool attn_ok(int32_t P, int32_t C);
 hipError_t launch_softmax_ce(int dtype, int32_t m, int32_t C, const void* logits, const int32_t* labels,
                              float loss_scale, void* dlogits, float* loss_accum, hipStream_t st);
 // v = mu*v + g; p = p_in - lr*v (p_in may be p); lowp[i] = bf16(p[i]) (lowp may be NULL); optionally g = 0.   n % 4 == 0

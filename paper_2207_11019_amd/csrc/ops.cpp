@@ -14,6 +14,10 @@ static int32_t to_geom(const lpm_conv_geom* g, int32_t dtype, ConvGeom& out) {
     const int32_t ho = g->h + 2 * g->pad - g->kh, wo = g->w + 2 * g->pad - g->kw;
     if (ho < 0 || wo < 0) return fail(LPM_ESHAPE, "kernel larger than padded input");
     out = ConvGeom{g->m, g->h, g->w, g->cin, ho / g->stride + 1, wo / g->stride + 1, g->cout, g->kh, g->kw, g->stride, g->pad};
+    // volumetric form (0 in d / kd means 1)
+    const int32_t d = g->d > 0 ? g->d : 1, kd = g->kd > 0 ? g->kd : 1;
+    if (g->d < 0 || g->kd < 0 || g->pad_d < 0 || g->pad_d >= kd || d + 2 * g->pad_d - kd < 0) return fail(LPM_ESHAPE, "bad depth geometry");
+    out.D = d; out.Kd = kd; out.pad_d = g->pad_d; out.Do = (d + 2 * g->pad_d - kd) / g->stride + 1;
     return LPM_OK;
 }
 

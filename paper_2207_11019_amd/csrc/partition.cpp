@@ -35,28 +35,34 @@ int32_t validate_network(const lpm_layer* layers, int32_t L, std::vector<lpm_lay
     norm.assign(layers, layers + L);
     shapes.assign((size_t)L + 1, Shape{0, 0, 0});
     if (layers[0].src != -1) return fail(LPM_ESHAPE, "layer 0 must read tensor -1 (the network input)");
-    shapes[0] = Shape{layers[0].cin, layers[0].h_in, layers[0].w_in};
+    const int32_t d0 = (has_weights(layers[0]) && layers[0].d_in > 1) ? layers[0].d_in : 1;
+    shapes[0] = Shape{layers[0].cin, d0 * layers[0].h_in, layers[0].w_in};
     for (int32_t i = 0; i < L; ++i) {
         lpm_layer& l = norm[i];
-        if (l.kind < LPM_CONV || l.kind > LPM_SOFTMAX_CE) return fail(LPM_EINVAL, "layer %d: unknown kind %d", i, l.kind);
+        if (l.kind < LPM_CONV || l.kind > LPM_ATTN) return fail(LPM_EINVAL, "layer %d: unknown kind %d", i, l.kind);
+        if (l.d_in < 0 || l.kd < 0 || l.pad_d < 0) return fail(LPM_ESHAPE, "layer %d: negative depth field", i);
+        if (!has_weights(l) && (l.d_in > 1 || l.kd > 1 || l.pad_d > 0))
+            return fail(LPM_ESHAPE, "layer %d: only CONV / FC layers take a depth (other kinds see it folded into the height)", i);
+        if (l.d_in == 0) l.d_in = 1;
+        if (l.kd == 0) l.kd = 1;
         if (l.cin <= 0 || l.h_in <= 0 || l.w_in <= 0) return fail(LPM_ESHAPE, "layer %d: non-positive input extent", i);
         if (l.src < -1 || l.src >= i) return fail(LPM_ESHAPE, "layer %d: src %d is not an earlier tensor", i, l.src);
         const Shape in = shapes[(size_t)l.src + 1];
-        if (in.c != l.cin || in.h != l.h_in || in.w != l.w_in)
+        if (in.c != l.cin || in.h != l.d_in * l.h_in || in.w != l.w_in)
             return fail(LPM_ESHAPE, "layer %d: input extent %dx%dx%d does not match tensor %d (%dx%dx%d)", i, l.cin,
                         l.h_in, l.w_in, l.src, in.c, in.h, in.w);
         Shape out{};
         switch (l.kind) {
             case LPM_FC:
-                l.kh = l.h_in; l.kw = l.w_in; l.stride = 1; l.pad = 0;
+                l.kh = l.h_in; l.kw = l.w_in; l.stride = 1; l.pad = 0; l.kd = l.d_in; l.pad_d = 0;
                 [[fallthrough]];
             case LPM_CONV: {
                 if (l.cout <= 0 || l.kh <= 0 || l.kw <= 0 || l.stride <= 0 || l.pad < 0)
                     return fail(LPM_ESHAPE, "layer %d: bad convolution geometry", i);
-                if (l.pad >= l.kh || l.pad >= l.kw) return fail(LPM_ESHAPE, "layer %d: pad must be smaller than the kernel", i);
-                const int32_t ho = (l.h_in + 2 * l.pad - l.kh), wo = (l.w_in + 2 * l.pad - l.kw);
-                if (ho < 0 || wo < 0) return fail(LPM_ESHAPE, "layer %d: kernel larger than padded input", i);
-                out = Shape{l.cout, ho / l.stride + 1, wo / l.stride + 1};
+                if (l.pad >= l.kh || l.pad >= l.kw || l.pad_d >= l.kd) return fail(LPM_ESHAPE, "layer %d: pad must be smaller than the kernel", i);
+                const int32_t ho = (l.h_in + 2 * l.pad - l.kh), wo = (l.w_in + 2 * l.pad - l.kw), dpo = (l.d_in + 2 * l.pad_d - l.kd);
+                if (ho < 0 || wo < 0 || dpo < 0) return fail(LPM_ESHAPE, "layer %d: kernel larger than padded input", i);
+                out = Shape{l.cout, (dpo / l.stride + 1) * (ho / l.stride + 1), wo / l.stride + 1};
                 if (l.flags & ~(LPM_RELU | LPM_BIAS | LPM_SCALE)) return fail(LPM_EINVAL, "layer %d: unknown flags", i);
                 if (l.add_src != LPM_NONE) {
                     if (l.add_src < -1 || l.add_src >= i) return fail(LPM_ESHAPE, "layer %d: add_src %d is not an earlier tensor", i, l.add_src);
@@ -72,6 +78,10 @@ int32_t validate_network(const lpm_layer* layers, int32_t L, std::vector<lpm_lay
                 break;
             case LPM_GAP:
                 out = Shape{l.cin, 1, 1};
+                break;
+            case LPM_ATTN:
+                if (l.cin % 3) return fail(LPM_ESHAPE, "layer %d: attention needs 3*C input channels (queries | keys | values)", i);
+                out = Shape{l.cin / 3, l.h_in, l.w_in};
                 break;
             case LPM_SOFTMAX_CE:
                 if (i != L - 1) return fail(LPM_ESHAPE, "layer %d: the loss must be the last layer", i);
@@ -106,9 +116,10 @@ static uint64_t layer_cost(const std::vector<lpm_layer>& net, const std::vector<
     const u128 e = (u128)cp.elem_bytes, m = (u128)cp.microbatch, M = (u128)cp.n_microbatch;
     const u128 in_el = shapes[(size_t)l.src + 1].elems(), out_el = shapes[(size_t)i + 1].elems();
     const bool hw = has_weights(l);
-    const u128 w_el = hw ? (u128)l.cout * l.cin * l.kh * l.kw : 0;
+    const u128 w_el = hw ? (u128)l.cout * l.cin * taps_of(l) : 0;
     const u128 p_el = w_el + ((hw && (l.flags & LPM_BIAS)) ? (u128)l.cout : 0);
-    const u128 mac = hw ? out_el * (u128)l.cin * l.kh * l.kw : 0;
+    u128 mac = hw ? out_el * (u128)l.cin * taps_of(l) : 0;
+    if (l.kind == LPM_ATTN) mac = 2 * (u128)l.h_in * l.w_in * l.h_in * l.w_in * (u128)(l.cin / 3);      // S = q^T k and y = A v
     const bool first = l.src < 0;
     const u128 flop = 2 * mac * m * (first ? 2 : 3);
     const u128 sc = (l.add_src != LPM_NONE) ? out_el : 0;

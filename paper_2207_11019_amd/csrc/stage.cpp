@@ -83,8 +83,19 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
         const lpm_layer& l = lr.d;
         const Shape o = s->shapes[(size_t)i + 1];
         lr.g = ConvGeom{microbatch, l.h_in, l.w_in, l.cin, o.h, o.w, o.c, l.kh, l.kw, l.stride, l.pad};
-        if (!has_weights(l)) continue;
-        lr.w_count = (size_t)l.cout * l.kh * l.kw * l.cin;
+        if (!has_weights(l)) {
+            if (l.kind == LPM_ATTN) {
+                if (!attn_ok(l.h_in * l.w_in, l.cout)) { delete s; return fail(LPM_ESHAPE, "layer %d: attention over %d positions of %d channels is outside the kernel's limits", i, l.h_in * l.w_in, l.cout); }
+                kws = std::max(kws, align_up(attn_bwd_ws_bytes(microbatch, l.h_in * l.w_in), 256));
+            }
+            continue;
+        }
+        if (l.d_in > 1 || l.kd > 1) {          // a volumetric layer: the tensor heights are slices x rows
+            lr.g.D = l.d_in; lr.g.Kd = l.kd; lr.g.pad_d = l.pad_d;
+            lr.g.Do = (l.d_in + 2 * l.pad_d - l.kd) / l.stride + 1;
+            lr.g.Ho = o.h / lr.g.Do;
+        }
+        lr.w_count = (size_t)l.cout * taps_of(l) * l.cin;
         lr.w_off = off;
         off += align_up(lr.w_count, 64);
         if (l.flags & LPM_BIAS) { lr.b_off = off; off += align_up((size_t)l.cout, 64); }
@@ -122,7 +133,7 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
         int32_t consumer = -1, first_add = last;
         for (int32_t j = i + 1; j < last; ++j) {
             const lpm_layer& c = s->net[j];
-            if (c.src == i) { (c.kind == LPM_SOFTMAX_CE ? n_other : n_src)++; consumer = j; }
+            if (c.src == i) { ((c.kind == LPM_SOFTMAX_CE || c.kind == LPM_ATTN) ? n_other : n_src)++; consumer = j; }
             if (c.add_src == i) { ++n_add; first_add = std::min(first_add, j); }
         }
         if (n_src != 1 || n_other != 0) continue;
@@ -307,7 +318,7 @@ static hipError_t transpose_copies(const lpm_stage* s, const float* params, void
     for (int32_t i = s->first; i < s->last; ++i) {
         const LayerRt& lr = s->Ly(i);
         if (lr.lowp_wt_off != NO)
-            d.push_back(TransposeDesc{params + lr.w_off, (uint16_t*)((char*)lowp + lr.lowp_wt_off), lr.d.cout, lr.d.kh * lr.d.kw, lr.d.cin,
+            d.push_back(TransposeDesc{params + lr.w_off, (uint16_t*)((char*)lowp + lr.lowp_wt_off), lr.d.cout, taps_of(lr.d), lr.d.cin,
                                       lr.dz_unscaled ? params + lr.s_off : nullptr});
     }
     return d.empty() ? hipSuccess : launch_weight_transpose_batch(d.data(), (int)d.size(), st);
@@ -368,6 +379,9 @@ extern "C" int32_t lpm_stage_forward(lpm_stage* s, const void* x, void* y, const
                 break;
             case LPM_GAP:
                 LPM_HIP(launch_gap_fwd(s->dtype, s->m, l.h_in * l.w_in, l.cin, in, outp, st));
+                break;
+            case LPM_ATTN:
+                LPM_HIP(launch_attn_fwd(s->dtype, s->m, l.h_in * l.w_in, l.cout, in, outp, st));
                 break;
             case LPM_SOFTMAX_CE:
                 LPM_HIP(launch_softmax_ce(s->dtype, s->m, l.cin, in, labels, loss_scale, (char*)stash + s->dlogits_off,
@@ -631,6 +645,14 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                                                    tptr(s, i, x, y, stash), g, gsrc, gsrc_acc, gmask != nullptr, gmscale, st));
                     else if (do_data)
                         LPM_HIP(launch_gap_bwd(s->dtype, s->m, l.h_in * l.w_in, l.cin, g, gsrc, gsrc_acc, gmask, gmscale, st));
+                    have[gi(l.src)] = 1;
+                }
+                break;
+            case LPM_ATTN:
+                if (want_src) {
+                    if (do_data)
+                        LPM_HIP(launch_attn_bwd(s->dtype, s->m, l.h_in * l.w_in, l.cout, tptr(s, l.src, x, y, stash), g, G[gi(l.src)],
+                                                have[gi(l.src)], kws, st));
                     have[gi(l.src)] = 1;
                 }
                 break;

@@ -243,7 +243,7 @@ static bool fits32_tr(const ConvGeom& g) {
 }
 
 static bool tr_shape_ok(const ConvGeom& g) {
-    if (g.Cin % 8 != 0 || g.Cout % 8 != 0 || !fits32_tr(g)) return false;
+    if (g.is3d() || g.Cin % 8 != 0 || g.Cout % 8 != 0 || !fits32_tr(g)) return false;
     if (g.Ho < 7 || g.Wo < 7) return false;
     // patches waste the part that hangs over the image edge: at least 3/4 of their pixels must be real
     const int TY = (g.Ho + 7) / 8, TX = (g.Wo + 7) / 8;

@@ -203,7 +203,10 @@ def compare(net, layers, starts, M, dtype, o, dx_wanted=False, window=2, report=
         for t, got in dev.items():
             if t >= 0:
                 perr["act%d" % t] = rel_err(got, plain_t[t])
-        fwd_bad = {k: e for k, e in perr.items() if not (e <= tol)}
+        # (a layer that exponentiates -- attention -- amplifies the storage rounding of its input: the forward bound is the bar
+        #  plus twice the distance between the two oracle runs at that tensor, which is zero to a fraction of the bar elsewhere)
+        ffloor = {"act%d" % t: rel_err(want_t[t], plain_t[t]) for t in dev if t >= 0}
+        fwd_bad = {k: e for k, e in perr.items() if not (e <= tol + 2 * ffloor.get(k, 0.0))}
         berr = {}
         for i in (pl["params"] if backward else []):
             for k in ("W", "b"):

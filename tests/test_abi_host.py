@@ -34,9 +34,9 @@ def _cp(dt, m, M, link=0):
     return dict(base, link_byte_per_us=link, microbatch=m, n_microbatch=M)
 
 
-@pytest.mark.parametrize("name", list(wl.CONFIGS))
+@pytest.mark.parametrize("name", list(wl.CONFIGS) + list(wl.EXTRA_CONFIGS))
 def test_plans_bit_exact_against_oracle(lpm, name):
-    builder, batch, M, Z, dt, _ = wl.CONFIGS[name]
+    builder, batch, M, Z, dt, _ = dict(wl.CONFIGS, **wl.EXTRA_CONFIGS)[name]
     L = builder()
     for link in (0, 153_000):
         cp = _cp(dt, batch // M, M, link)

@@ -21,11 +21,17 @@ def lpm():
 
 def _layer(g):
     return dict(kind="conv", cin=g["cin"], cout=g["cout"], kh=g["kh"], kw=g["kw"], stride=g["stride"], pad=g["pad"],
-                h_in=g["h"], w_in=g["w"], relu=False, bias=False, scale=False, src=-1, add_src=None, cut_after=False)
+                h_in=g["h"], w_in=g["w"], d_in=g.get("d", 1), kd=g.get("kd", 1), pad_d=g.get("pad_d", 0),
+                relu=False, bias=False, scale=False, src=-1, add_src=None, cut_after=False)
 
 
 def G(m, h, w, cin, cout, k, s=1, p=0, kw=None):
     return dict(m=m, h=h, w=w, cin=cin, cout=cout, kh=k, kw=k if kw is None else kw, stride=s, pad=p)
+
+
+def G3(m, d, h, w, cin, cout, k, s=1, p=0):
+    """A volumetric layer: k x k x k filter over [m][d][h][w][cin]."""
+    return dict(m=m, h=h, w=w, cin=cin, cout=cout, kh=k, kw=k, stride=s, pad=p, d=d, kd=k, pad_d=p)
 
 
 SHAPES = [
@@ -60,6 +66,15 @@ SHAPES = [
     G(1, 57, 59, 128, 128, 3, 1, 1),      # a filter row per block, patches over the edge in both directions
     G(4, 64, 64, 128, 128, 3, 1, 0),      # a filter row per block, no padding
     G(1, 60, 60, 72, 136, 3, 1, 1),       # channel counts that are not multiples of the 64-channel tile
+    # volumetric layers (3x3x3 and 1x1x1 filters, the first use case's shapes)
+    G3(2, 6, 6, 6, 32, 64, 3, 1, 1),      # matrix-core kernels for all three contractions
+    G3(1, 5, 7, 6, 64, 40, 3, 1, 1),      # ragged extents and channel tile
+    G3(2, 8, 8, 8, 32, 64, 3, 2, 1),      # stride 2: matrix-core forward / weight gradient, generic data gradient
+    G3(2, 8, 8, 8, 32, 64, 1, 2, 0),      # 1x1x1 stride-2 projection
+    G3(2, 4, 4, 4, 128, 128, 3, 1, 1),    # long reduction: split over blocks
+    G3(3, 4, 4, 4, 64, 192, 1, 1, 0),     # 1x1x1 (queries | keys | values of an attention block)
+    G3(2, 8, 8, 8, 1, 16, 3, 1, 1),       # one-channel input volume (generic kernels)
+    dict(G3(2, 3, 4, 4, 32, 48, 3, 1, 0), kd=3, pad_d=0, kh=4, kw=4),   # filter covers the whole volume: a fully connected layer
 ]
 
 
@@ -67,14 +82,15 @@ def _pack(lpm, torch, a):
     return lpm.pack_act(a, lpm.BF16)
 
 
-@pytest.mark.parametrize("g", SHAPES, ids=lambda g: "m%d_%dx%dx%d_%d_k%dx%d_s%d_p%d" % (g["m"], g["h"], g["w"], g["cin"], g["cout"], g["kh"], g["kw"], g["stride"], g["pad"]))
+@pytest.mark.parametrize("g", SHAPES, ids=lambda g: "m%d_%s%dx%dx%d_%d_k%dx%d_s%d_p%d" % (g["m"], ("d%dk%d_" % (g["d"], g["kd"])) if "d" in g else "", g["h"], g["w"], g["cin"], g["cout"], g["kh"], g["kw"], g["stride"], g["pad"]))
 def test_conv_ops_bf16(lpm, g):
     import torch
     print("geometry", g, flush=True)
     l = _layer(g)
     seed = 3
-    x = rng.round_to_bf16(rng.normal(seed, 1, (g["m"], g["cin"], g["h"], g["w"])))
-    W = rng.round_to_bf16(rng.normal(seed, 2, (g["cout"], g["cin"], g["kh"], g["kw"]), 0.0, (2.0 / (g["cin"] * g["kh"] * g["kw"])) ** 0.5))
+    D, KD = g.get("d", 1), g.get("kd", 1)          # a volume's depth is folded into the height axis of the logical tensors
+    x = rng.round_to_bf16(rng.normal(seed, 1, (g["m"], g["cin"], D * g["h"], g["w"])))
+    W = rng.round_to_bf16(rng.normal(seed, 2, (g["cout"], g["cin"], KD * g["kh"], g["kw"]), 0.0, (2.0 / (g["cin"] * KD * g["kh"] * g["kw"])) ** 0.5))
     z = orc.conv_fwd(x, W, l)
     dz = rng.round_to_bf16(rng.normal(seed, 3, z.shape))
     sc = rng.uniform(seed, 4, (g["cout"],), 0.5, 1.5).astype(np.float32)

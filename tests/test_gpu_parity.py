@@ -40,6 +40,10 @@ CASES = [
     ("tiny_wide_bf16", wl.tiny_wide, 8, 4, 2, 1),
     # a split forward reduction into 72 channels whose second kernel also pools
     ("tiny_deep_pool_bf16", wl.tiny_deep_pool, 16, 2, 1, 1),
+    # the volumetric use case: 3x3x3 residual blocks, a strided block with a 1x1x1 projection, a residual self-attention block
+    ("tiny_conv3d_f32", wl.tiny_conv3d, 4, 2, 3, 0),
+    ("tiny_conv3d_bf16", wl.tiny_conv3d, 4, 2, 3, 1),
+    ("tiny_conv3d_mfma_bf16", wl.tiny_conv3d_mfma, 4, 2, 2, 1),       # 32 / 64 channels: the matrix-core kernels
 ]
 
 
@@ -408,6 +412,8 @@ FULL = [
     ("resnet34_cifar", wl.resnet34_cifar, [0, 7, 16, 29, 39], 32, 256, False),
     ("r50_conv4x", wl.r50_conv4x, [0, 19], 16, 64, True),
     ("vgg16_224", wl.vgg16_224, [0, 10, 18, 19, 22], 4, 32, False),
+    # a 3D-ResAttNet18-shaped network on 32^3 one-channel volumes, two volumes per micro-batch (plan: the cost model's, 4 partitions)
+    ("resattnet18_3d", wl.resattnet18_3d, None, 2, 6, False),
 ]
 
 
@@ -418,6 +424,8 @@ def test_full_size_microbatch_bf16(lpm, name, builder, plan, m, batch, dx):
     infinity norm).  VGG-16/224 uses the described plan (conv1-3 | conv4-5 | FC1 | FC2-3)."""
     layers = builder()
     rep = {}
+    if plan is None:
+        plan, _ = lpm.lpm_partition(layers, 4, dict(lpm.MI355X_COST["bf16"], link_byte_per_us=0, microbatch=m, n_microbatch=batch // m))
     print("workload", name, "plan", plan, flush=True)
     stage_backward_isolated(lpm, layers, plan, m, batch, 1, seed=17, dx_wanted=dx, report=rep, check_forward=True)
     print(name, "worst", sorted(rep.items(), key=lambda kv: -kv[1])[:6], flush=True)

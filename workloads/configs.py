@@ -84,10 +84,14 @@ class _Builder:
         c, h, w = in_chw if in_chw else (self.c, self.h, self.w)
         return self._push(_layer("conv", c, cout, (k, k), stride, pad, h, w, relu, bias, scale, None, add_src), src)
 
-    def conv3d(self, cout, k, stride=1, pad=0, relu=True, bias=True, scale=False, src=None, add_src=None, in_cdhw=None):
-        """k x k x k filter over the volume [C][D][H][W]."""
+    def conv3d(self, cout, k, stride=1, pad=0, relu=True, bias=True, scale=False, src=None, add_src=None, in_cdhw=None,
+               w_gain=1.0):
+        """k x k x k filter over the volume [C][D][H][W].  w_gain: factor on the He-normal standard deviation of its weights."""
         c, d, h, w = in_cdhw if in_cdhw else (self.c, self.d, self.h, self.w)
-        return self._push(_layer("conv", c, cout, (k, k), stride, pad, h, w, relu, bias, scale, None, add_src, d=d, kd=k, pad_d=pad), src)
+        l = _layer("conv", c, cout, (k, k), stride, pad, h, w, relu, bias, scale, None, add_src, d=d, kd=k, pad_d=pad)
+        if w_gain != 1.0:
+            l["w_gain"] = w_gain
+        return self._push(l, src)
 
     def fc(self, cout, relu=True, bias=True):
         l = _layer("fc", self.c, cout, (self.h, self.w), 1, 0, self.h, self.w, relu, bias, d=self.d, kd=self.d)
@@ -223,16 +227,18 @@ def _basic_block3d(b, cout, stride):
         sc = b.conv3d(cout, 1, stride=stride, pad=0, relu=False, scale=True, src=x, in_cdhw=cdhw)
     else:
         sc = x
-    b.conv3d(cout, 3, pad=1, relu=True, scale=True, src=a, add_src=sc, in_cdhw=after)
+    # (the branch's last layer starts small, as a normalisation layer's zero-initialised gain would make it: without batch
+    #  statistics the activations of a He-initialised residual stack otherwise double in variance per block)
+    b.conv3d(cout, 3, pad=1, relu=True, scale=True, src=a, add_src=sc, in_cdhw=after, w_gain=0.25)
 
 
 def _attention_block(b):
     """Residual self-attention: a 1x1x1 convolution makes queries | keys | values, the attention layer mixes the positions,
     a 1x1x1 convolution projects back and the block input is added before the ReLU."""
     x, c = b.last, b.c
-    b.conv3d(3 * c, 1, relu=False, src=x)
+    b.conv3d(3 * c, 1, relu=False, src=x, w_gain=0.5)          # scores of order one on unit-variance activations
     b.attn()
-    b.conv3d(c, 1, relu=True, src=b.last, add_src=x)
+    b.conv3d(c, 1, relu=True, src=b.last, add_src=x, w_gain=0.25)
 
 
 def resattnet18_3d(widths=(32, 64, 128, 256), blocks=2, vol=32, n_classes=2, attention_from=2):
@@ -255,7 +261,7 @@ def resattnet18_3d(widths=(32, 64, 128, 256), blocks=2, vol=32, n_classes=2, att
 
 def tiny_conv3d():
     """Small volumetric network: 3x3x3 stem on 2 channels, one residual block, one strided block, attention, head."""
-    b = _Builder(2, 6, 6, 6)
+    b = _Builder(2, 8, 8, 4)          # 2 channels, 4 slices of 8 x 8 (a sample is a whole number of 256-byte lines)
     b.conv3d(8, 3, pad=1, scale=True)
     _basic_block3d(b, 8, 1)
     _basic_block3d(b, 16, 2)
@@ -266,7 +272,7 @@ def tiny_conv3d():
 
 def tiny_conv3d_mfma():
     """The same shape with 32 / 64 channels, so that the matrix-core kernels take the volumetric layers."""
-    b = _Builder(2, 6, 6, 6)
+    b = _Builder(2, 8, 8, 4)          # 2 channels, 4 slices of 8 x 8 (a sample is a whole number of 256-byte lines)
     b.conv3d(32, 3, pad=1, scale=True)
     _basic_block3d(b, 32, 1)
     _basic_block3d(b, 64, 2)
@@ -362,7 +368,7 @@ _WHICH = {"W": 0, "b": 1, "s": 2, "vW": 3, "vb": 4}
 
 
 def make_params(layers, seed=BASE_SEED, bf16=False, bias_std=0.0, momentum_std=0.0):
-    """He-normal weights N(0, 2/fan_in), bias N(0, bias_std) (zeros when 0), frozen scale U[0.5,1.5),
+    """He-normal weights N(0, 2/fan_in) (standard deviation times the layer's w_gain where it has one), bias N(0, bias_std) (zeros when 0), frozen scale U[0.5,1.5),
     initial momentum N(0, momentum_std) (zeros when 0).  float64, logical layouts.
     With bf16=True weights are rounded to bf16 so that both sides start from representable values."""
     params, momentum = {}, {}
@@ -371,7 +377,7 @@ def make_params(layers, seed=BASE_SEED, bf16=False, bias_std=0.0, momentum_std=0
         if not sh:
             continue
         fan_in = l["cin"] * l.get("kd", 1) * l["kh"] * l["kw"]
-        p = {"W": rng.normal(seed, i * 8 + 0, sh["W"], 0.0, np.sqrt(2.0 / fan_in))}
+        p = {"W": rng.normal(seed, i * 8 + 0, sh["W"], 0.0, l.get("w_gain", 1.0) * np.sqrt(2.0 / fan_in))}
         if bf16:
             p["W"] = rng.round_to_bf16(p["W"])
         if "b" in sh:
