@@ -63,21 +63,21 @@ OPI = {"fwd": 0, "dgrad": 1, "wgrad": 2}
 
 def stored_traffic(workload, kernel):
     """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-    (profiles/hbm_traffic_<workload>.md); None when that file is missing or describes another kernel."""
+    (profiles/hbm_traffic_<workload>.md: pairs of "- kernel: ..." / "- traffic_bytes_per_launch: ..." lines, one pair per
+    measured kernel); None when that file is missing or holds no entry for this kernel."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.md" % workload)
     if not os.path.exists(path):
         return None
-    kv = {}
+    cur = None
     for line in open(path):
-        if line.startswith("- ") and ": " in line:
-            k, v = line[2:].split(": ", 1)
-            kv[k.strip()] = v.strip()
-    if kv.get("kernel") != kernel:
-        return None
-    try:
-        return int(float(kv["traffic_bytes_per_launch"]))
-    except (KeyError, ValueError):
-        return None
+        if line.startswith("- kernel: "):
+            cur = line[len("- kernel: "):].strip()
+        elif line.startswith("- traffic_bytes_per_launch: ") and cur == kernel:
+            try:
+                return int(float(line.split(": ", 1)[1]))
+            except ValueError:
+                return None
+    return None
 
 
 def time_stream(torch, fn, iters, warm=3):

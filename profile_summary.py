@@ -55,19 +55,19 @@ def trace(db, out, cmd):
 
 
 def pmc(dbs):
+    """Per kernel name, launch size (work-items) and counter: dispatches and the average value per dispatch."""
     for db in dbs:
         c = sqlite3.connect(db)
-        try:
-            rows = c.execute("select k.name, p.counter_name, count(*), avg(p.value) from %s p join %s k on k.dispatch_id = p.dispatch_id "
-                             "group by k.name, p.counter_name" % (_table(c, "pmc_events"), _table(c, "kernels"))).fetchall()
-        except sqlite3.Error:
-            rows = c.execute("select kernel_name, counter_name, count(*), avg(value) from %s group by kernel_name, counter_name"
-                             % _table(c, "counters_collection")).fetchall()
-        for name, counter, n, v in rows:
+        view = _table(c, "counters_collection")
+        cols = [r[1] for r in c.execute("pragma table_info(%s)" % view)]
+        size = "grid_size" if "grid_size" in cols else "0"
+        rows = c.execute("select kernel_name, %s, counter_name, count(*), avg(value) from %s group by kernel_name, %s, counter_name"
+                         % (size, view, size)).fetchall()
+        for name, threads, counter, n, v in rows:
             s = _short(name)
             if "at::" in s:
                 continue
-            print("%-62s %-30s n=%5d avg=%.1f" % (s, counter, n, v))
+            print("%-56s work-items=%-10d %-30s n=%5d avg=%.1f" % (s, threads or 0, counter, n, v))
 
 
 if __name__ == "__main__":
