@@ -20,13 +20,34 @@ static inline unsigned nblk(int64_t n, int per) { return (unsigned)((n + per - 1
 // --------------------------------------------------------------------------------------------------
 // convolution forward, eq. 1 for a conv/FC layer:  y = relu?(scale*z + bias + add)
 // (two- and three-dimensional: a 2-D layer has D = Do = Kd = 1)
-template <typename T>
+// R lanes share an output element: lane p of the group takes the channels p, p + R, ... of every filter tap, and the R
+// partial sums are added by a butterfly of lane exchanges, the same order on every run.  (One thread per element walked
+// taps x channels dependent loads alone: 34 us for the 960 outputs of a 256 -> 120 fully connected layer.)
+template <int R>
+__device__ __forceinline__ float group_sum(float v) {
+#pragma unroll
+    for (int off = R / 2; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+// lanes per element for a reduction whose innermost extent is n
+static inline int group_lanes(int n) { return n >= 48 ? 64 : n >= 12 ? 16 : n >= 4 ? 4 : 1; }
+#define LPM_DISPATCH_R(R_, ...)                                    \
+    do {                                                           \
+        if ((R_) == 64) { constexpr int R = 64; __VA_ARGS__; }     \
+        else if ((R_) == 16) { constexpr int R = 16; __VA_ARGS__; } \
+        else if ((R_) == 4) { constexpr int R = 4; __VA_ARGS__; }  \
+        else { constexpr int R = 1; __VA_ARGS__; }                 \
+    } while (0)
+
+template <typename T, int R>
 __global__ void __launch_bounds__(256) conv_fwd_generic(ConvGeom g, const T* __restrict__ x, const T* __restrict__ w,
                                                         const float* __restrict__ scale, const float* __restrict__ bias,
                                                         const T* __restrict__ add, int relu, T* __restrict__ y) {
     const int64_t total = g.rows_out() * g.Cout;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int p = (int)(gid % R);
+    const bool live = gid / R < total;          // (a group is live or idle as a whole; idle groups still take part in the exchange)
+    const int64_t idx = live ? gid / R : 0;
     const int co = (int)(idx % g.Cout);
     int64_t row = idx / g.Cout;
     const int wo = (int)(row % g.Wo); row /= g.Wo;
@@ -45,10 +66,12 @@ __global__ void __launch_bounds__(256) conv_fwd_generic(ConvGeom g, const T* __r
                 if (ww < 0 || ww >= g.W) continue;
                 const T* xp = x + ((((int64_t)n * g.D + d) * g.H + h) * g.W + ww) * g.Cin;
                 const T* wp = w + ((((int64_t)co * g.Kd + kd) * g.Kh + kh) * g.Kw + kw) * g.Cin;
-                for (int ci = 0; ci < g.Cin; ++ci) acc = fmaf(ld(xp, ci), ld(wp, ci), acc);
+                for (int ci = p; ci < g.Cin; ci += R) acc = fmaf(ld(xp, ci), ld(wp, ci), acc);
             }
         }
     }
+    acc = group_sum<R>(acc);
+    if (!live || p) return;
     if (scale) acc *= scale[co];
     if (bias) acc += bias[co];
     if (add) acc += ld(add, idx);
@@ -59,20 +82,24 @@ __global__ void __launch_bounds__(256) conv_fwd_generic(ConvGeom g, const T* __r
 hipError_t conv_fwd_generic_launch(int dtype, const ConvGeom& g, const void* x, const void* w, const float* scale,
                                    const float* bias, const void* add, int relu, void* y, hipStream_t s) {
     const int64_t total = g.rows_out() * g.Cout;
-    LPM_DISPATCH(dtype, hipLaunchKernelGGL(conv_fwd_generic<T>, dim3(nblk(total, 256)), dim3(256), 0, s, g, (const T*)x,
-                                           (const T*)w, scale, bias, (const T*)add, relu, (T*)y));
+    const int lanes = group_lanes(g.Cin);
+    LPM_DISPATCH_R(lanes, LPM_DISPATCH(dtype, hipLaunchKernelGGL((conv_fwd_generic<T, R>), dim3(nblk(total * R, 256)), dim3(256), 0, s, g,
+                                                                 (const T*)x, (const T*)w, scale, bias, (const T*)add, relu, (T*)y)));
     return hipGetLastError();
 }
 
 // --------------------------------------------------------------------------------------------------
 // data gradient, eq. 9: dx[n,h,w,ci] (+)= sum_{kh,kw,co} dz[n,(h+p-kh)/s,(w+p-kw)/s,co] * w[co,kh,kw,ci]
-template <typename T>
+// (R lanes per element, each taking the output channels p, p + R, ... of every tap)
+template <typename T, int R>
 __global__ void __launch_bounds__(256) conv_dgrad_generic(ConvGeom g, const T* __restrict__ dz, const float* __restrict__ dzscale,
                                                           const T* __restrict__ w, T* __restrict__ dx, int accumulate,
                                                           const T* __restrict__ mask, const float* __restrict__ mscale) {
     const int64_t total = g.rows_in() * g.Cin;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int p = (int)(gid % R);
+    const bool live = gid / R < total;
+    const int64_t idx = live ? gid / R : 0;
     const int ci = (int)(idx % g.Cin);
     int64_t row = idx / g.Cin;
     const int ww = (int)(row % g.W); row /= g.W;
@@ -98,11 +125,13 @@ __global__ void __launch_bounds__(256) conv_dgrad_generic(ConvGeom g, const T* _
                 if (wo >= g.Wo) continue;
                 const T* dp = dz + ((((int64_t)n * g.Do + dq) * g.Ho + ho) * g.Wo + wo) * g.Cout;
                 const T* wp = w + (((int64_t)kd * g.Kh + kh) * g.Kw + kw) * g.Cin + ci;
-                if (dzscale) { for (int co = 0; co < g.Cout; ++co) acc = fmaf(ld(dp, co) * dzscale[co], ld(wp, co * wstride), acc); }
-                else { for (int co = 0; co < g.Cout; ++co) acc = fmaf(ld(dp, co), ld(wp, co * wstride), acc); }
+                if (dzscale) { for (int co = p; co < g.Cout; co += R) acc = fmaf(ld(dp, co) * dzscale[co], ld(wp, co * wstride), acc); }
+                else { for (int co = p; co < g.Cout; co += R) acc = fmaf(ld(dp, co), ld(wp, co * wstride), acc); }
             }
         }
     }
+    acc = group_sum<R>(acc);
+    if (!live || p) return;
     if (accumulate) acc += ld(dx, idx);
     if (mask && !(ld(mask, idx) > 0.f)) acc = 0.f;
     if (mscale) acc *= mscale[ci];
@@ -112,8 +141,9 @@ __global__ void __launch_bounds__(256) conv_dgrad_generic(ConvGeom g, const T* _
 hipError_t conv_dgrad_generic_launch(int dtype, const ConvGeom& g, const void* dz, const float* dzscale, const void* w, void* dx,
                                      int accumulate, const void* mask, const float* mscale, hipStream_t s) {
     const int64_t total = g.rows_in() * g.Cin;
-    LPM_DISPATCH(dtype, hipLaunchKernelGGL(conv_dgrad_generic<T>, dim3(nblk(total, 256)), dim3(256), 0, s, g,
-                                           (const T*)dz, dzscale, (const T*)w, (T*)dx, accumulate, (const T*)mask, mscale));
+    const int lanes = group_lanes(g.Cout);
+    LPM_DISPATCH_R(lanes, LPM_DISPATCH(dtype, hipLaunchKernelGGL((conv_dgrad_generic<T, R>), dim3(nblk(total * R, 256)), dim3(256), 0, s, g,
+                                                                 (const T*)dz, dzscale, (const T*)w, (T*)dx, accumulate, (const T*)mask, mscale)));
     return hipGetLastError();
 }
 
@@ -121,14 +151,17 @@ hipError_t conv_dgrad_generic_launch(int dtype, const ConvGeom& g, const void* d
 // weight gradient, eq. 8: dw[co,kh,kw,ci] (+)= sum_{n,ho,wo} dz[n,ho,wo,co] * x[n,ho*s+kh-p,wo*s+kw-p,ci]
 // The (n,ho) range is split into `chunks` slices (blockIdx.y); with more than one slice each writes a
 // partial to ws[chunk][Cout*K] and a second kernel adds the partials in slice order (no float atomics,
-// so the result does not depend on scheduling).
-template <typename T>
+// so the result does not depend on scheduling).  Within a slice R lanes share an element: lane p takes the
+// lines p, p + R, ... and the group adds its partial sums by lane exchanges in a fixed order.
+template <typename T, int R>
 __global__ void __launch_bounds__(256) conv_wgrad_generic(ConvGeom g, const T* __restrict__ x, const T* __restrict__ dz,
                                                           float* __restrict__ out, int chunks, int accumulate) {
     const int K = g.K();
     const int64_t total = (int64_t)g.Cout * K;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int p = (int)(gid % R);
+    const bool live = gid / R < total;
+    const int64_t idx = live ? gid / R : 0;
     const int ci = (int)(idx % g.Cin);
     int64_t t = idx / g.Cin;
     const int kw = (int)(t % g.Kw); t /= g.Kw;
@@ -139,7 +172,7 @@ __global__ void __launch_bounds__(256) conv_wgrad_generic(ConvGeom g, const T* _
     const int per = (nho + chunks - 1) / chunks;
     const int r0 = blockIdx.y * per, r1 = min(nho, r0 + per);
     float acc = 0.f;
-    for (int r = r0; r < r1; ++r) {
+    for (int r = r0 + p; r < r1; r += R) {
         const int ho = r % g.Ho, nd = r / g.Ho, dq = nd % g.Do, n = nd / g.Do;
         const int h = ho * g.stride + kh - g.pad, d = dq * g.stride + kd - g.pad_d;
         if (h < 0 || h >= g.H || d < 0 || d >= g.D) continue;
@@ -151,6 +184,8 @@ __global__ void __launch_bounds__(256) conv_wgrad_generic(ConvGeom g, const T* _
             acc = fmaf(ld(dp, (int64_t)wo * g.Cout), ld(xp, (int64_t)ww * g.Cin), acc);
         }
     }
+    acc = group_sum<R>(acc);
+    if (!live || p) return;
     if (chunks > 1) out[(int64_t)blockIdx.y * total + idx] = acc;
     else out[idx] = accumulate ? out[idx] + acc : acc;
 }
@@ -170,11 +205,13 @@ hipError_t reduce_partials_launch(const float* part, float* dst, int64_t n, int 
     return hipGetLastError();
 }
 
+static int wgrad_generic_lanes(const ConvGeom& g) { return group_lanes(g.m * g.Do * g.Ho); }
+
 static int wgrad_generic_chunks(const ConvGeom& g) {
     const int64_t total = (int64_t)g.Cout * g.K();
     const int nho = g.m * g.Do * g.Ho;
     int64_t c = ((int64_t)1 << 22) / total;     // keep the partials within a few MB
-    const int64_t want = (nho + 3) / 4;          // a thread walks at most 4 (n,ho) lines
+    const int64_t want = (nho + 4 * wgrad_generic_lanes(g) - 1) / (4 * wgrad_generic_lanes(g));      // a lane walks at most 4 (n,ho) lines
     if (c > want) c = want;
     if (c > 256) c = 256;
     if (c > nho) c = nho;
@@ -192,8 +229,9 @@ hipError_t conv_wgrad_generic_launch(int dtype, const ConvGeom& g, const void* x
     const int64_t total = (int64_t)g.Cout * g.K();
     const int chunks = wgrad_generic_chunks(g);
     float* out = chunks > 1 ? (float*)ws : dw;
-    LPM_DISPATCH(dtype, hipLaunchKernelGGL(conv_wgrad_generic<T>, dim3(nblk(total, 256), chunks), dim3(256), 0, s, g,
-                                           (const T*)x, (const T*)dz, out, chunks, accumulate));
+    const int lanes = wgrad_generic_lanes(g);
+    LPM_DISPATCH_R(lanes, LPM_DISPATCH(dtype, hipLaunchKernelGGL((conv_wgrad_generic<T, R>), dim3(nblk(total * R, 256), chunks), dim3(256), 0, s, g,
+                                                                 (const T*)x, (const T*)dz, out, chunks, accumulate)));
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || chunks == 1) return e;
     return reduce_partials_launch((const float*)ws, dw, total, chunks, accumulate, s);
