@@ -33,9 +33,14 @@ def conv_ops(layers, m, first_needs_dgrad=False):
         kh, kw = (l["h_in"], l["w_in"]) if l["kind"] == "fc" else (l["kh"], l["kw"])
         s, p = (1, 0) if l["kind"] == "fc" else (l["stride"], l["pad"])
         g = dict(m=m, h=l["h_in"], w=l["w_in"], cin=l["cin"], cout=l["cout"], kh=kh, kw=kw, stride=s, pad=p)
+        d = l.get("d_in", 1)                      # volumetric layers: depth, filter depth, depth padding
+        kd, pd = (d, 0) if l["kind"] == "fc" else (l.get("kd", 1), l.get("pad_d", 0))
+        if d > 1:
+            g.update(d=d, kd=kd, pad_d=pd)
+        do = (d + 2 * pd - kd) // s + 1
         ho, wo = (g["h"] + 2 * p - kh) // s + 1, (g["w"] + 2 * p - kw) // s + 1
-        flops = 2 * m * ho * wo * l["cout"] * l["cin"] * kh * kw
-        in_el, out_el, w_el = m * g["h"] * g["w"] * l["cin"], m * ho * wo * l["cout"], l["cout"] * kh * kw * l["cin"]
+        flops = 2 * m * do * ho * wo * l["cout"] * l["cin"] * kd * kh * kw
+        in_el, out_el, w_el = m * d * g["h"] * g["w"] * l["cin"], m * do * ho * wo * l["cout"], l["cout"] * kd * kh * kw * l["cin"]
         ops.append((i, "fwd", g, flops, 2 * (in_el + out_el + w_el)))
         if l["src"] >= 0 or first_needs_dgrad:
             ops.append((i, "dgrad", g, flops, 2 * (in_el + out_el + w_el)))
@@ -45,12 +50,14 @@ def conv_ops(layers, m, first_needs_dgrad=False):
 
 def conv_buffers(torch, lpm, g, dtype):
     """Synthetic device operands of one contraction: x, dz-shaped y, w, transposed-shaped wt, dW, scratch."""
+    d, kd, pd = g.get("d", 1), g.get("kd", 1), g.get("pad_d", 0)
+    do = (d + 2 * pd - kd) // g["stride"] + 1
     ho = (g["h"] + 2 * g["pad"] - g["kh"]) // g["stride"] + 1
     wo = (g["w"] + 2 * g["pad"] - g["kw"]) // g["stride"] + 1
     tdt = torch.bfloat16 if dtype == lpm.BF16 else torch.float32
-    K = g["kh"] * g["kw"] * g["cin"]
-    xx = torch.randn(g["m"] * g["h"] * g["w"] * g["cin"], device="cuda").to(tdt)
-    yy = torch.randn(g["m"] * ho * wo * g["cout"], device="cuda").to(tdt) * 1e-2
+    K = kd * g["kh"] * g["kw"] * g["cin"]
+    xx = torch.randn(g["m"] * d * g["h"] * g["w"] * g["cin"], device="cuda").to(tdt)
+    yy = torch.randn(g["m"] * do * ho * wo * g["cout"], device="cuda").to(tdt) * 1e-2
     ww = (torch.randn(g["cout"] * K, device="cuda") * (2.0 / K) ** 0.5).to(tdt)
     wt = ww.clone() if dtype == lpm.BF16 else None
     dw = torch.zeros(g["cout"] * K, device="cuda")
@@ -99,7 +106,7 @@ class Workload:
 
     def __init__(self, torch, wl, lpm, name, plan=None, window=2, async_update=False):
         self.torch, self.lpm, self.name = torch, lpm, name
-        builder, self.batch, self.M, self.Z, self.dt, fixed = wl.CONFIGS[name]
+        builder, self.batch, self.M, self.Z, self.dt, fixed = {**wl.CONFIGS, **wl.EXTRA_CONFIGS}[name]
         self.layers = builder()
         self.m = self.batch // self.M
         self.dtype = lpm.BF16 if self.dt == "bf16" else lpm.F32
@@ -251,8 +258,8 @@ def main():
             t = cache[key]
             ai = flops / byts
             bound = "mfma" if ai >= W.peak / PEAK["hbm"] else "hbm"
-            table.append(dict(layer=i, op=op, shape="m%d %dx%dx%d->%d k%d s%d" % (g["m"], g["h"], g["w"], g["cin"], g["cout"],
-                                                                                    g["kh"], g["stride"]),
+            table.append(dict(layer=i, op=op, shape="m%d %s%dx%dx%d->%d k%d s%d" % (g["m"], "%dx" % g["d"] if "d" in g else "", g["h"], g["w"],
+                                                                                      g["cin"], g["cout"], g["kh"], g["stride"]),
                               us=round(t * 1e6, 2), tflops=round(flops / t / 1e12, 2), gbps=round(byts / t / 1e9, 1),
                               frac_of_mfma_peak=round(flops / t / W.peak, 4),
                               bound=bound, flops=flops, bytes=byts, per_step_us=round(t * 1e6 * M, 1)))
@@ -295,8 +302,8 @@ def main():
             mine = [r for r in table if r["layer"] == i]
             if not mine:
                 continue
-            if l["cout"] % (32 * n_sub):       # slices of fewer than 32 channels would fall to the generic data-gradient kernel
-                skipped += 1
+            if l["cout"] % (32 * n_sub) or l.get("d_in", 1) > 1:       # slices of fewer than 32 channels would fall to the generic
+                skipped += 1                                            # data-gradient kernel; volumetric layers are not sliced
                 continue
             g = next(g for (j, op, g, _, _) in ops if j == i)
             key = tuple(sorted(g.items()))
@@ -352,7 +359,7 @@ def main():
     if not args.no_others:
         by_workload, memory_bound = {}, {}
         n_other = max(5, args.steps // 3)
-        for name in ("vgg16_cifar", "resnet18_cifar", "r50_conv4x", "vgg16_224", "lenet"):
+        for name in ("vgg16_cifar", "resnet18_cifar", "r50_conv4x", "vgg16_224", "lenet", "resattnet18_3d"):
             if name == args.workload:
                 by_workload[name] = dict(plan=starts, global_batch=batch, n_microbatch=M, ms_per_step=round(res["eager"]["overlapped"] / args.steps * 1e3, 4),
                                          locked_ms_per_step=round(res["eager"]["locked"] / args.steps * 1e3, 4),

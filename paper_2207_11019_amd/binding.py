@@ -177,6 +177,27 @@ def _geom(g):
                            [g.get("d", 1), g.get("kd", 1), g.get("pad_d", 0)]))
 
 
+def _conv_sizes(gg, dtype):
+    """Bytes of the operands of one contraction: (x, y or dz, w, dw)."""
+    e = 2 if dtype == BF16 else 4
+    d, kd, pd = max(gg.d, 1), max(gg.kd, 1), gg.pad_d
+    do = (d + 2 * pd - kd) // gg.stride + 1
+    ho = (gg.h + 2 * gg.pad - gg.kh) // gg.stride + 1
+    wo = (gg.w + 2 * gg.pad - gg.kw) // gg.stride + 1
+    wn = gg.cout * kd * gg.kh * gg.kw * gg.cin
+    return gg.m * d * gg.h * gg.w * gg.cin * e, gg.m * do * ho * wo * gg.cout * e, wn * e, wn * 4
+
+
+def _holds(name, t, nbytes):
+    """The library sees plain pointers; a tensor handed over here is checked against the geometry before its kernels run
+    (a buffer that is too small would be read or written past its end on the GPU)."""
+    if t is None or isinstance(t, int):
+        return
+    have = t.numel() * t.element_size()
+    if have < nbytes:
+        raise ValueError("%s holds %d bytes, the geometry needs %d" % (name, have, nbytes))
+
+
 def lpm_conv_ws_bytes(g, dtype):
     """-> (fwd, dgrad, wgrad) scratch bytes"""
     v = [C.c_size_t() for _ in range(3)]
@@ -187,18 +208,24 @@ def lpm_conv_ws_bytes(g, dtype):
 
 def lpm_conv_forward(g, dtype, x, w, scale, bias, add, relu, y, ws=None, stream=None):
     gg = _geom(g)
+    xb, yb, wb, _ = _conv_sizes(gg, dtype)
+    _holds("x", x, xb), _holds("w", w, wb), _holds("add", add, yb), _holds("y", y, yb), _holds("ws", ws, lpm_conv_ws_bytes(gg, dtype)[0])
     _check(lib.lpm_conv_forward(C.byref(gg), dtype, _ptr(x), _ptr(w), _ptr(scale), _ptr(bias), _ptr(add), int(relu), _ptr(y),
                                 _ptr(ws), _stream(stream)))
 
 
 def lpm_conv_dgrad(g, dtype, dz, w, wt, dx, accumulate=False, ws=None, stream=None):
     gg = _geom(g)
+    xb, yb, wb, _ = _conv_sizes(gg, dtype)
+    _holds("dz", dz, yb), _holds("w", w, wb), _holds("wt", wt, wb), _holds("dx", dx, xb), _holds("ws", ws, lpm_conv_ws_bytes(gg, dtype)[1])
     _check(lib.lpm_conv_dgrad(C.byref(gg), dtype, _ptr(dz), _ptr(w), _ptr(wt), _ptr(dx), int(accumulate), _ptr(ws),
                               _stream(stream)))
 
 
 def lpm_conv_wgrad(g, dtype, x, dz, dw, accumulate=False, ws=None, stream=None):
     gg = _geom(g)
+    xb, yb, _, db = _conv_sizes(gg, dtype)
+    _holds("x", x, xb), _holds("dz", dz, yb), _holds("dw", dw, db), _holds("ws", ws, lpm_conv_ws_bytes(gg, dtype)[2])
     _check(lib.lpm_conv_wgrad(C.byref(gg), dtype, _ptr(x), _ptr(dz), _ptr(dw), int(accumulate), _ptr(ws), _stream(stream)))
 
 
@@ -208,12 +235,17 @@ STATIC_SCRATCH_BYTES = 8 << 20
 def lpm_conv_wgrad_static(g, dtype, x, dz, dw, accumulate=False, stream=None):
     """lpm_conv_wgrad with the library's built-in scratch area: no workspace argument, nothing allocated."""
     gg = _geom(g)
+    xb, yb, _, db = _conv_sizes(gg, dtype)
+    _holds("x", x, xb), _holds("dz", dz, yb), _holds("dw", dw, db)
     _check(lib.lpm_conv_wgrad_static(C.byref(gg), dtype, _ptr(x), _ptr(dz), _ptr(dw), int(accumulate), _stream(stream)))
 
 
 def lpm_conv_time(op, g, dtype, x, w, wt, y, dw, ws, warmup=3, iters=20, stream=None):
     """Average microseconds of one launch of contraction op (0 forward, 1 data gradient, 2 weight gradient)."""
     gg = _geom(g)
+    xb, yb, wb, db = _conv_sizes(gg, dtype)
+    _holds("x", x, xb), _holds("w", w, wb), _holds("wt", wt, wb), _holds("y", y, yb), _holds("dw", dw, db)
+    _holds("ws", ws, max(lpm_conv_ws_bytes(gg, dtype)))
     out = C.c_float()
     _check(lib.lpm_conv_time(op, C.byref(gg), dtype, _ptr(x), _ptr(w), _ptr(wt), _ptr(y), _ptr(dw), _ptr(ws), warmup, iters,
                              _stream(stream), C.byref(out)))

@@ -139,12 +139,21 @@ __device__ __forceinline__ void mma_tile(const uint16_t* As, const uint16_t* Bs,
     }
 }
 
+// Strided data gradient: pixel index (in the full tensor) of row `row` of the residue class (pd, ph, pw), whose rows run over
+// (sample, slice of the class, row of the class, column of the class); Dc = 1 and pd = 0 for two-dimensional layers.
+__device__ __forceinline__ int class_pixel(const IgemmArgs& p, int row, int Hc, int Wc, int ph, int pw, int Dc, int pd) {
+    const int wq = row % Wc, t = row / Wc, hq = t % Hc;
+    int n = t / Hc, img = n;
+    if (p.Dr > 1) { const int dq = n % Dc; n /= Dc; img = n * p.Dr + dq * p.stride + pd; }
+    return (img * p.Hr + hq * p.stride + ph) * p.Wr + wq * p.stride + pw;
+}
+
 // Writes a block's accumulators: split-K partials, the max-pooling route of a data gradient, or the fused epilogue.
 // The optional terms of the epilogue (shortcut, accumulation, mask) are the same for the whole launch; each of the
 // eight combinations gets its own straight-line copy of the store loop instead of three branches per element.
 template <int MI, int NI, int WTM, int WTN, int MODE, bool ADD, bool ACC, bool MASK>
 __device__ __forceinline__ void igemm_store(const IgemmArgs& p, const f32x16 (&acc)[MI][NI], int ni, int col, int m0, int wm, int rq,
-                                            int rows, int Hc, int Wc, int ph, int pw) {
+                                            int rows, int Hc, int Wc, int ph, int pw, int Dc, int pd) {
     const float sc = p.scale ? p.scale[col] : 1.f, bi = p.bias ? p.bias[col] : 0.f, ms = p.mscale ? p.mscale[col] : 1.f;
     const bool relu = p.relu != 0;
 #pragma unroll
@@ -155,8 +164,7 @@ __device__ __forceinline__ void igemm_store(const IgemmArgs& p, const f32x16 (&a
             if (row >= rows) continue;
             size_t o = (size_t)(unsigned)(row * p.N + col);            // (the host checked that the output has fewer than 2^31 elements)
             if (MODE == MODE_DGRAD_S) {      // class row -> pixel of the full image
-                const int wq = row % Wc, t = row / Wc, hq = t % Hc, n = t / Hc;
-                o = (size_t)(unsigned)(((n * p.Hr + hq * p.stride + ph) * p.Wr + wq * p.stride + pw) * p.N + col);
+                o = (size_t)(unsigned)(class_pixel(p, row, Hc, Wc, ph, pw, Dc, pd) * p.N + col);
             }
             float v = acc[mi][ni][i] * sc + bi;
             if (ADD) v += bf2f(p.add[o]);
@@ -179,7 +187,7 @@ __device__ __forceinline__ void igemm_store(const IgemmArgs& p, const f32x16 (&a
 // residue class, Hc x Wc of them per image)
 template <int MODE, bool PART, bool ADD, bool ACC, bool MASK>
 __device__ __forceinline__ void igemm_store_vec(const IgemmArgs& p, const f32x16& acc, float* tile, int row0, int col0, int rows, int lane,
-                                                int Hc, int Wc, int ph, int pw) {
+                                                int Hc, int Wc, int ph, int pw, int Dc, int pd) {
     const int col_l = lane & 31, rq = (lane >> 5) * 4;
     asm volatile("" ::: "memory");
 #pragma unroll
@@ -197,8 +205,7 @@ __device__ __forceinline__ void igemm_store_vec(const IgemmArgs& p, const f32x16
         float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
         size_t o = (size_t)(unsigned)(row * p.N + col);
         if (MODE == MODE_DGRAD_S) {      // class row -> pixel of the full image
-            const int wq = row % Wc, t_ = row / Wc, hq = t_ % Hc, n = t_ / Hc;
-            o = (size_t)(unsigned)(((n * p.Hr + hq * p.stride + ph) * p.Wr + wq * p.stride + pw) * p.N + col);
+            o = (size_t)(unsigned)(class_pixel(p, row, Hc, Wc, ph, pw, Dc, pd) * p.N + col);
         }
         if (PART) {
             float* q = p.part + (size_t)blockIdx.z * p.M * p.N + o;
@@ -263,7 +270,7 @@ __device__ __forceinline__ void igemm_store_vec(const IgemmArgs& p, const f32x16
 // tile: this wavefront's private LDS area of 32 x 36 floats (NULL: none -- element-wise stores)
 template <int MI, int NI, int WTM, int WTN, int MODE>
 __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& p, f32x16 (&acc)[MI][NI], int m0, int n0, int wm, int wn, int lane,
-                                               int rows, int Hc, int Wc, int ph, int pw, float* tile = nullptr) {
+                                               int rows, int Hc, int Wc, int ph, int pw, int Dc, int pd, float* tile = nullptr) {
     const int col_l = lane & 31, rq = (lane >> 5) * 4;
     const int variant = (p.add ? 1 : 0) | (p.accumulate ? 2 : 0) | (p.mask ? 4 : 0);
     if (tile && (p.part || !(MODE == MODE_DGRAD && p.pool_x)) && (p.N & 7) == 0) {
@@ -273,10 +280,10 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& p, f32x16 (&acc)
             for (int ni = 0; ni < NI; ++ni) {
                 const int row0 = m0 + wm * WTM + mi * 32, col0 = n0 + wn * WTN + ni * 32;
                 if (p.part) {
-                    igemm_store_vec<MODE, true, false, false, false>(p, acc[mi][ni], tile, row0, col0, rows, lane, Hc, Wc, ph, pw);
+                    igemm_store_vec<MODE, true, false, false, false>(p, acc[mi][ni], tile, row0, col0, rows, lane, Hc, Wc, ph, pw, Dc, pd);
                     continue;
                 }
-#define LPM_STORE_VEC(A, B, C) igemm_store_vec<MODE, false, A, B, C>(p, acc[mi][ni], tile, row0, col0, rows, lane, Hc, Wc, ph, pw)
+#define LPM_STORE_VEC(A, B, C) igemm_store_vec<MODE, false, A, B, C>(p, acc[mi][ni], tile, row0, col0, rows, lane, Hc, Wc, ph, pw, Dc, pd)
                 switch (variant) {
                     case 0: LPM_STORE_VEC(false, false, false); break;
                     case 1: LPM_STORE_VEC(true, false, false); break;
@@ -305,15 +312,14 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& p, f32x16 (&acc)
                     if (row >= rows) continue;
                     size_t o = (size_t)(unsigned)(row * p.N + col);
                     if (MODE == MODE_DGRAD_S) {
-                        const int wq = row % Wc, t = row / Wc, hq = t % Hc, n = t / Hc;
-                        o = (size_t)(unsigned)(((n * p.Hr + hq * p.stride + ph) * p.Wr + wq * p.stride + pw) * p.N + col);
+                        o = (size_t)(unsigned)(class_pixel(p, row, Hc, Wc, ph, pw, Dc, pd) * p.N + col);
                     }
                     if (part) part[o] = acc[mi][ni][i];
                     else unpool_store(acc[mi][ni][i], row, col, p.Hr, p.Wr, p.N, p.pool_x, p.pool_dst, p.pool_acc, p.pool_mask, p.mscale);
                 }
             continue;
         }
-#define LPM_STORE(A, B, C) igemm_store<MI, NI, WTM, WTN, MODE, A, B, C>(p, acc, ni, col, m0, wm, rq, rows, Hc, Wc, ph, pw)
+#define LPM_STORE(A, B, C) igemm_store<MI, NI, WTM, WTN, MODE, A, B, C>(p, acc, ni, col, m0, wm, rq, rows, Hc, Wc, ph, pw, Dc, pd)
         switch (variant) {
             case 0: LPM_STORE(false, false, false); break;
             case 1: LPM_STORE(true, false, false); break;
@@ -346,21 +352,28 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
     int kt0 = blockIdx.z * p.kt_per_split;
     int kt1 = min(p.kt_total, kt0 + p.kt_per_split);
     // filter taps visited: all of them in steps of 1, or (strided data gradient) those of the block's residue class
-    int kstep = 1, kh_first = 0, kw_first = 0;
-    int ph = 0, pw = 0, Hc = p.Hr, Wc = p.Wr, rows = p.M;     // residue class of the block's rows and its extent
+    int kstep = 1, kh_first = 0, kw_first = 0, kd_first = 0;
+    int ph = 0, pw = 0, pd = 0, Hc = p.Hr, Wc = p.Wr, Dc = p.Dr, rows = p.M;     // residue class of the block's rows and its extent
+    int nkh_c = 1, nkw_c = 1;                                                     // filter taps of the class per axis
     if (MODE == MODE_DGRAD_S) {
-        const int s_ = p.stride, mt = tile / nt;
+        // class c = (pd * s + ph) * s + pw; a two-dimensional layer (Dr = 1) has the s * s classes with pd = 0
+        const int s_ = p.stride, mt = tile / nt, ncls = (p.Dr > 1 ? s_ : 1) * s_ * s_;
         int c = 0;
-        while (c + 1 < s_ * s_ && mt >= p.cls_tile0[c + 1]) ++c;
-        ph = c / s_; pw = c - ph * s_;
+        while (c + 1 < ncls && mt >= p.cls_tile0[c + 1]) ++c;
+        pd = c / (s_ * s_);
+        ph = (c - pd * s_ * s_) / s_; pw = c - (pd * s_ + ph) * s_;
         Hc = (p.Hr - ph + s_ - 1) / s_; Wc = (p.Wr - pw + s_ - 1) / s_;
-        rows = (p.M / (p.Hr * p.Wr)) * Hc * Wc;
+        Dc = p.Dr > 1 ? (p.Dr - pd + s_ - 1) / s_ : 1;
+        rows = (p.M / (p.Dr * p.Hr * p.Wr)) * Dc * Hc * Wc;
         m0 = (mt - p.cls_tile0[c]) * BM;
         kstep = s_;
         kh_first = (ph + p.pad) % s_; kw_first = (pw + p.pad) % s_;
+        kd_first = p.Dr > 1 ? (pd + p.pad_d) % s_ : 0;
         const int nkh = kh_first < p.Kh ? (p.Kh - kh_first + s_ - 1) / s_ : 0;
         const int nkw = kw_first < p.Kw ? (p.Kw - kw_first + s_ - 1) / s_ : 0;
-        const int kt_cls = nkh * nkw * (p.Ci / BK);
+        const int nkd = p.Dr > 1 ? (kd_first < p.Kd ? (p.Kd - kd_first + s_ - 1) / s_ : 0) : 1;
+        nkh_c = max(nkh, 1); nkw_c = max(nkw, 1);
+        const int kt_cls = nkd * nkh * nkw * (p.Ci / BK);
         const int per = (kt_cls + (int)gridDim.z - 1) / (int)gridDim.z;
         kt0 = blockIdx.z * per;
         kt1 = min(kt_cls, kt0 + per);
@@ -395,10 +408,11 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
         }
         int dq = 0;
         if (MODE != MODE_DGRAD_S && p.Dr > 1) { const int ns = n / p.Dr; dq = n - ns * p.Dr; n = ns; }      // sample, slice
+        if (MODE == MODE_DGRAD_S && p.Dr > 1) { const int ns = n / Dc; dq = n - ns * Dc; n = ns; }           // sample, slice of the class
         if (MODE == MODE_FWD) { a_h0[c] = hq * p.stride - p.pad; a_w0[c] = wq * p.stride - p.pad; a_d0[c] = dq * p.stride - p.pad_d; }
         else if (MODE == MODE_DGRAD) { a_h0[c] = hq + p.pad; a_w0[c] = wq + p.pad; a_d0[c] = dq + p.pad_d; }
-        else { a_h0[c] = hq; a_w0[c] = wq; a_d0[c] = 0; }
-        if (MODE == MODE_DGRAD_S) a_base[c] = (unsigned)(n * p.Hi * p.Wi * p.Ci + kc * 8) * 2u;
+        else { a_h0[c] = hq; a_w0[c] = wq; a_d0[c] = dq; }
+        if (MODE == MODE_DGRAD_S) a_base[c] = (unsigned)(n * p.Di * p.Hi * p.Wi * p.Ci + kc * 8) * 2u;
         else a_base[c] = (unsigned)((((n * p.Di + a_d0[c]) * p.Hi + a_h0[c]) * p.Wi + a_w0[c]) * p.Ci + kc * 8) * 2u;
     }
 #pragma unroll
@@ -412,8 +426,9 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
         const int k0 = kt0 * BK, tap = k0 / p.Ci;
         cur_c0 = k0 - tap * p.Ci;
         if (MODE == MODE_DGRAD_S) {
-            const int nkw = kw_first < p.Kw ? (p.Kw - kw_first + kstep - 1) / kstep : 1;
-            cur_kh = kh_first + (tap / nkw) * kstep; cur_kw = kw_first + (tap % nkw) * kstep;
+            const int td = tap / (nkh_c * nkw_c), r = tap - td * (nkh_c * nkw_c);
+            cur_kd = kd_first + td * kstep;
+            cur_kh = kh_first + (r / nkw_c) * kstep; cur_kw = kw_first + (r % nkw_c) * kstep;
         } else {
             const int hw = p.Kh * p.Kw;
             cur_kd = tap / hw;
@@ -434,6 +449,7 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
         /* strided data gradient: output pixel = class coordinate + (ph + pad - kh) / stride, an exact quotient */ \
         const int dh_ = (MODE == MODE_DGRAD_S) ? (ph + p.pad - kh_) / kstep : 0;                             \
         const int dw_ = (MODE == MODE_DGRAD_S) ? (pw + p.pad - kw_) / kstep : 0;                             \
+        const int dd_ = (MODE == MODE_DGRAD_S && p.Dr > 1) ? (pd + p.pad_d - kd_) / kstep : 0;               \
         _Pragma("unroll") for (int c = 0; c < A_CH; ++c) {                                                   \
             int h_, w_;                                                                                      \
             bool ok_ = a_ok[c] & live_;                                                                      \
@@ -447,7 +463,9 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
             }                                                                                                \
             else {                                                                                           \
                 h_ = a_h0[c] + dh_; w_ = a_w0[c] + dw_;                                                      \
-                off_ = a_base[c] + (unsigned)((h_ * p.Wi + w_) * p.Ci + cur_c0) * 2u;                        \
+                const int d_ = a_d0[c] + dd_;                                                                \
+                ok_ = ok_ & ((unsigned)d_ < (unsigned)p.Di);                                                 \
+                off_ = a_base[c] + (unsigned)(((d_ * p.Hi + h_) * p.Wi + w_) * p.Ci + cur_c0) * 2u;          \
             }                                                                                                \
             ok_ = ok_ & ((unsigned)h_ < (unsigned)p.Hi) & ((unsigned)w_ < (unsigned)p.Wi);                   \
             RA[c] = buf_load16(rsA, ok_ ? off_ : OOB);                                                       \
@@ -462,7 +480,7 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
             cur_kw += kstep;                                                                                 \
             if (cur_kw >= p.Kw) {                                                                            \
                 cur_kw = kw_first; cur_kh += kstep;                                                          \
-                if (MODE != MODE_DGRAD_S && cur_kh >= p.Kh) { cur_kh = 0; ++cur_kd; }                        \
+                if (cur_kh >= p.Kh) { cur_kh = kh_first; cur_kd += kstep; }                                  \
             }                                                                                                \
         }                                                                                                    \
     }
@@ -518,7 +536,7 @@ __global__ void __launch_bounds__(256, 2) igemm_kernel(IgemmArgs p) {
     // (every wavefront is past the loop's last barrier: the A tiles are dead and take the epilogue's staging areas)
     constexpr bool STAGE_FITS = sizeof(As) >= 4 * 32 * 36 * sizeof(float);
     float* stage = STAGE_FITS ? reinterpret_cast<float*>(&As[0][0]) + wave * (32 * 36) : nullptr;
-    igemm_epilogue<Cfg::MI, Cfg::NI, Cfg::WTM, Cfg::WTN, MODE>(p, acc, m0, n0, wm, wn, lane, rows, Hc, Wc, ph, pw, stage);
+    igemm_epilogue<Cfg::MI, Cfg::NI, Cfg::WTM, Cfg::WTN, MODE>(p, acc, m0, n0, wm, wn, lane, rows, Hc, Wc, ph, pw, Dc, pd, stage);
 }
 
 
@@ -760,8 +778,8 @@ static bool fits32(const ConvGeom& g) {
     return g.rows_in() * g.Cin < lim && g.rows_out() * g.Cout < lim && (int64_t)g.Cout * g.K() < lim;
 }
 bool mfma_fwd_ok(const ConvGeom& g) { return g.Cin % 32 == 0 && fits32(g); }
-// (a strided data gradient goes by residue classes of the two image axes: two-dimensional layers only)
-bool mfma_dgrad_ok(const ConvGeom& g) { return g.Cout % 32 == 0 && g.stride <= 4 && (g.stride == 1 || !g.is3d()) && fits32(g); }
+// (a strided data gradient goes by residue classes of the image axes: stride^2 classes, stride^3 for a volume -- at most 16)
+bool mfma_dgrad_ok(const ConvGeom& g) { return g.Cout % 32 == 0 && g.stride <= 4 && (g.stride <= 2 || !g.is3d()) && fits32(g); }
 
 size_t mfma_fwd_ws_bytes(const ConvGeom& g) {
     const IgemmPlan pl = plan_igemm(g.rows_out(), g.Cout, g.K(), g.Cin);
@@ -770,7 +788,7 @@ size_t mfma_fwd_ws_bytes(const ConvGeom& g) {
 // K a residue class of a strided data gradient runs over at most: the taps of matching parity
 static int dgrad_plan_K(const ConvGeom& g) {
     const int s = g.stride;
-    return g.Kd * ((g.Kh + s - 1) / s) * ((g.Kw + s - 1) / s) * g.Cout;
+    return ((g.Kd + s - 1) / s) * ((g.Kh + s - 1) / s) * ((g.Kw + s - 1) / s) * g.Cout;
 }
 
 size_t mfma_dgrad_ws_bytes(const ConvGeom& g) {
@@ -820,15 +838,16 @@ hipError_t mfma_conv_dgrad(const ConvGeom& g, const void* dz, const void* wt, vo
     a.a_bytes = (unsigned)(g.rows_out() * g.Cout * 2); a.b_bytes = (unsigned)((int64_t)g.Cout * g.K() * 2);
     a.Kh = g.Kh;
     a.plan_K = dgrad_plan_K(g);
-    if (g.stride > 1) {          // row tiles per residue class (h % stride, w % stride)
-        const int s = g.stride;
+    if (g.stride > 1) {          // row tiles per residue class (d % stride, h % stride, w % stride)
+        const int s = g.stride, ncls = (g.D > 1 ? s : 1) * s * s;
         int t = 0;
-        for (int c = 0; c < s * s; ++c) {
+        for (int c = 0; c < ncls; ++c) {
             a.cls_tile0[c] = t;
-            const int64_t Hc = (g.H - c / s + s - 1) / s, Wc = (g.W - c % s + s - 1) / s;
-            t += (int)(((int64_t)g.m * Hc * Wc + 63) / 64);
+            const int pd = c / (s * s), ph = (c / s) % s, pw = c % s;
+            const int64_t Dc = g.D > 1 ? (g.D - pd + s - 1) / s : 1, Hc = (g.H - ph + s - 1) / s, Wc = (g.W - pw + s - 1) / s;
+            t += (int)(((int64_t)g.m * Dc * Hc * Wc + 63) / 64);
         }
-        for (int c = s * s; c <= 16; ++c) a.cls_tile0[c] = t;
+        for (int c = ncls; c <= 16; ++c) a.cls_tile0[c] = t;
         a.m_tiles = t;
     }
     return run_igemm(MODE_DGRAD, a, ws, st);
@@ -936,7 +955,7 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
         b_wo[t] = b_r[t] - q * p.Wo; b_ho[t] = q % p.Ho; b_n[t] = q / p.Ho;
     }
     // FLAT: the 8 (tap, channel) indices of an item -- element offset from the pixel at tap (0,0), and the tap
-    int f_off[B_PT][8], f_hw[B_PT][8];        // f_hw = kh << 16 | kw, or -1 when the index is past Cin*Kh*Kw
+    int f_off[B_PT][8], f_hw[B_PT][8];        // f_hw = kd << 24 | kh << 12 | kw, or -1 when the index is past Cin*Kd*Kh*Kw
     if (FLAT) {
 #pragma unroll
         for (int t = 0; t < B_PT; ++t) {
@@ -944,10 +963,11 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int k = ci0 + cc * 8 + e;
-                const int tp = k / p.x_cin, ci = k - tp * p.x_cin, th = tp / p.Kw, tw = tp - th * p.Kw;
+                const int tp = k / p.x_cin, ci = k - tp * p.x_cin, td = tp / (p.Kh * p.Kw), tr = tp - td * (p.Kh * p.Kw);
+                const int th = tr / p.Kw, tw = tr - th * p.Kw;
                 const bool ok = (item < B_ITEMS) & (k < p.Cin);
-                f_off[t][e] = (th * p.W + tw) * p.x_cin + ci;
-                f_hw[t][e] = ok ? ((th << 16) | tw) : -1;
+                f_off[t][e] = ((td * p.H + th) * p.W + tw) * p.x_cin + ci;      // (a volume's slices are consecutive images)
+                f_hw[t][e] = ok ? ((td << 24) | (th << 12) | tw) : -1;
             }
         }
     }
@@ -967,12 +987,15 @@ __global__ void __launch_bounds__(256, 2) wgrad_kernel(WgradArgs p) {
             _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                  \
                 if (FLAT) {                                                                                  \
                     const int h0_ = ho_ * p.stride - p.pad, w0_ = wo_ * p.stride - p.pad;                    \
-                    const int base_ = ((n_ * p.H + h0_) * p.W + w0_) * p.x_cin;                              \
+                    int img0_ = n_, d0_ = 0;      /* n_ counts (sample, output slice) pairs */                   \
+                    if (p.Do > 1 || p.D > 1) { const int ns_ = n_ / p.Do; d0_ = (n_ - ns_ * p.Do) * p.stride - p.pad_d; img0_ = ns_ * p.D + d0_; } \
+                    const int base_ = ((img0_ * p.H + h0_) * p.W + w0_) * p.x_cin;                           \
                     const bool pix_ = live_ & (b_r[t] + j < p.R);                                            \
                     _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                          \
                         const int hw_ = f_hw[t][e];                                                          \
-                        const bool ok_ = pix_ & (hw_ >= 0) & ((unsigned)(h0_ + (hw_ >> 16)) < (unsigned)p.H) & \
-                                         ((unsigned)(w0_ + (hw_ & 0xffff)) < (unsigned)p.W);                 \
+                        const bool ok_ = pix_ & (hw_ >= 0) & ((unsigned)(h0_ + ((hw_ >> 12) & 0xfff)) < (unsigned)p.H) & \
+                                         ((unsigned)(w0_ + (hw_ & 0xfff)) < (unsigned)p.W) &                 \
+                                         ((unsigned)(d0_ + (hw_ >> 24)) < (unsigned)p.D);                    \
                         QS[t][j][e] = buf_load2(rsX, ok_ ? (unsigned)(base_ + f_off[t][e]) * 2u : OOB);      \
                     }                                                                                        \
                 } else {                                                                                     \
@@ -1265,7 +1288,7 @@ __global__ void __launch_bounds__(256) wgrad_reduce_short(const float* __restric
 }
 
 // Weight gradient of an image-input layer (Cin*Kh*Kw <= 64): one N tile holds every (tap, channel) index.
-bool mfma_wgrad_flat_ok(const ConvGeom& g) { return !g.is3d() && g.K() <= 64 && g.Cout % 8 == 0 && fits32(g); }
+bool mfma_wgrad_flat_ok(const ConvGeom& g) { return g.K() <= 64 && g.Cout % 8 == 0 && fits32(g); }
 
 static WgradPlan plan_wgrad_flat(const ConvGeom& g) {
     WgradPlan pl{};
@@ -1293,8 +1316,8 @@ hipError_t mfma_conv_wgrad_flat(const ConvGeom& g, const void* x, const void* dz
     a.X = (const uint16_t*)x; a.DZ = (const uint16_t*)dz;
     a.out = pl.splits > 1 ? (float*)ws : dw;
     a.Cout = g.Cout; a.Cin = g.K(); a.KhKw = 1; a.Kw = g.Kw;
-    a.Kh = 1; a.D = 1; a.Do = 1; a.pad_d = 0;
-    a.x_cin = g.Cin; a.x_taps = g.Kh * g.Kw;
+    a.Kh = g.Kh; a.D = g.D; a.Do = g.Do; a.pad_d = g.pad_d;
+    a.x_cin = g.Cin; a.x_taps = g.taps();
     a.H = g.H; a.W = g.W; a.Ho = g.Ho; a.Wo = g.Wo; a.stride = g.stride; a.pad = g.pad;
     a.R = (int)g.rows_out();
     a.db = dbias; a.rscale = rscale;

@@ -219,3 +219,24 @@ def test_stage_layout(lpm):
     assert s.has_param(0, 2) and s.param_bytes > s.grad_bytes          # frozen scales sit after the trainable part
     o_s, _ = s.param_offset(0, 2)
     assert o_s * 4 >= s.grad_bytes
+
+
+def test_binding_rejects_undersized_operands(lpm):
+    """The C ABI takes plain pointers, so the binding checks a tensor's size against the geometry before the library's
+    kernels would read or write past its end (CPU tensors: the check comes before any GPU work)."""
+    import torch
+    g3 = dict(m=2, h=8, w=8, cin=32, cout=64, kh=3, kw=3, stride=1, pad=1, d=8, kd=3, pad_d=1)
+    gg = lpm.binding._geom(g3)
+    xb, yb, wb, db = lpm.binding._conv_sizes(gg, lpm.BF16)
+    assert (xb, yb, wb, db) == (2 * 8 * 8 * 8 * 32 * 2, 2 * 8 * 8 * 8 * 64 * 2, 64 * 27 * 32 * 2, 64 * 27 * 32 * 4)
+    flat = dict(g3); del flat["d"], flat["kd"], flat["pad_d"]
+    x2 = torch.zeros(2 * 8 * 8 * 32, dtype=torch.bfloat16)                # sized for one slice: too small for the volume
+    w3 = torch.zeros(64 * 27 * 32, dtype=torch.bfloat16)
+    y3 = torch.zeros(2 * 8 * 8 * 8 * 64, dtype=torch.bfloat16)
+    with pytest.raises(ValueError, match="x holds"):
+        lpm.lpm_conv_forward(g3, lpm.BF16, x2, w3, None, None, None, False, y3)
+    with pytest.raises(ValueError, match="dw holds"):
+        lpm.lpm_conv_wgrad(g3, lpm.BF16, torch.zeros(xb // 2, dtype=torch.bfloat16), y3, torch.zeros(10))
+    with pytest.raises(ValueError, match="holds"):
+        lpm.lpm_conv_time(0, g3, lpm.BF16, x2, w3, w3, y3, torch.zeros(db // 4), torch.zeros(256, dtype=torch.uint8))
+    assert lpm.binding._conv_sizes(lpm.binding._geom(flat), lpm.F32)[0] == 2 * 8 * 8 * 32 * 4

@@ -69,11 +69,16 @@ SHAPES = [
     # volumetric layers (3x3x3 and 1x1x1 filters, the first use case's shapes)
     G3(2, 6, 6, 6, 32, 64, 3, 1, 1),      # matrix-core kernels for all three contractions
     G3(1, 5, 7, 6, 64, 40, 3, 1, 1),      # ragged extents and channel tile
-    G3(2, 8, 8, 8, 32, 64, 3, 2, 1),      # stride 2: matrix-core forward / weight gradient, generic data gradient
+    G3(2, 8, 8, 8, 32, 64, 3, 2, 1),      # stride 2: the data gradient by residue classes of (d, h, w)
+    dict(G3(2, 7, 9, 6, 32, 64, 3, 2, 1), h=9, w=6),      # stride 2, odd extents: eight classes of different sizes
+    G3(1, 12, 12, 12, 64, 64, 3, 2, 1),   # stride 2, several row tiles per class
+    G3(2, 5, 5, 5, 64, 256, 3, 2, 1),     # stride 2, long K: split reduction over the taps of a class
     G3(2, 8, 8, 8, 32, 64, 1, 2, 0),      # 1x1x1 stride-2 projection
     G3(2, 4, 4, 4, 128, 128, 3, 1, 1),    # long reduction: split over blocks
     G3(3, 4, 4, 4, 64, 192, 1, 1, 0),     # 1x1x1 (queries | keys | values of an attention block)
-    G3(2, 8, 8, 8, 1, 16, 3, 1, 1),       # one-channel input volume (generic kernels)
+    G3(2, 8, 8, 8, 1, 16, 3, 1, 1),       # one-channel input volume: flattened (tap, channel) weight gradient
+    dict(G3(1, 9, 7, 10, 2, 24, 3, 1, 1), h=7, w=10),     # two channels x 27 taps, ragged extents
+    G3(2, 9, 9, 9, 1, 32, 3, 2, 1),       # one-channel volume, stride 2
     dict(G3(2, 3, 4, 4, 32, 48, 3, 1, 0), kd=3, pad_d=0, kh=4, kw=4),   # filter covers the whole volume: a fully connected layer
 ]
 

@@ -70,7 +70,8 @@ def test_static_scratch_rejects_oversize(lpm):
     g = dict(m=16, h=14, w=14, cin=256, cout=256, kh=3, kw=3, stride=1, pad=1)
     need = lpm.lpm_conv_ws_bytes(g, lpm.BF16)[2]
     assert need > lpm.STATIC_SCRATCH_BYTES
-    one = torch.zeros(256, dtype=torch.uint8, device="cuda")
+    x = torch.zeros(16 * 14 * 14 * 256, dtype=torch.bfloat16, device="cuda")          # operands of the right size: the call is
+    dw = torch.zeros(256 * 9 * 256, dtype=torch.float32, device="cuda")              # refused for its scratch need alone
     with pytest.raises(lpm.LpmError) as e:
-        lpm.lpm_conv_wgrad_static(g, lpm.BF16, one, one, one, False, None)
+        lpm.lpm_conv_wgrad_static(g, lpm.BF16, x, x, dw, False, None)
     assert e.value.code == -1 and "scratch" in str(e.value)
