@@ -39,6 +39,8 @@ struct WgradTrArgs {
     int kt_total, kt_per_split, splits;
     int accumulate;
     int co_tiles, ci_tiles, tap_groups;
+    int Kd, D, Do, pad_d;  // volumetric layers: filter depth, slices in / out, depth padding (1, 1, 1, 0 otherwise); an "image"
+                           // of the patch cursor is one output slice, and a block's taps all lie in one filter slice kd
 };
 
 template <int TAPS>
@@ -79,7 +81,8 @@ __global__ void __launch_bounds__(256, 2) wgrad_tr_kernel(WgradTrArgs p) {
     const int grp = tile % p.tap_groups;
     const int co_t = tile / p.tap_groups;
     const int co0 = co_t * 64, ci0 = ci_t * 64;
-    const int kh0 = TAPS == 9 ? 0 : (TAPS == 3 ? grp : grp / p.Kw), kw0 = TAPS == 1 ? grp % p.Kw : 0;
+    const int g2d = p.tap_groups / p.Kd, kd = grp / g2d, grp2 = grp - kd * g2d;      // filter slice, tap group inside it
+    const int kh0 = TAPS == 9 ? 0 : (TAPS == 3 ? grp2 : grp2 / p.Kw), kw0 = TAPS == 1 ? grp2 % p.Kw : 0;
     const int kt0 = split * p.kt_per_split, nk = min(p.kt_total, kt0 + p.kt_per_split) - kt0;
 
     const u32x4_ rsD = buffer_words(p.DZ, p.dz_bytes), rsX = buffer_words(p.X, p.x_bytes);
@@ -123,10 +126,17 @@ __global__ void __launch_bounds__(256, 2) wgrad_tr_kernel(WgradTrArgs p) {
             load_to_lds16(rsD, st_ + (wave + 4 * i) * 1024, ok_ ? baseA_ + a_loc[i] : TR_OOB);                \
         }                                                                                                     \
         const int by_ = y0_ * p.stride + kh0 - p.pad, bx_ = x0_ * p.stride + kw0 - p.pad;                     \
-        const unsigned baseB_ = (unsigned)(((c_n * p.H + by_) * p.W + bx_) * p.Cin) * 2u;                     \
+        int imgB_ = c_n;                                                                                      \
+        bool dok_ = true;                                                                                     \
+        if (p.D > 1 || p.Do > 1) {          /* c_n counts (sample, output slice) pairs */                        \
+            const int ns_ = c_n / p.Do, d_ = (c_n - ns_ * p.Do) * p.stride + kd - p.pad_d;                    \
+            dok_ = (unsigned)d_ < (unsigned)p.D;                                                              \
+            imgB_ = ns_ * p.D + d_;                                                                           \
+        }                                                                                                     \
+        const unsigned baseB_ = (unsigned)(((imgB_ * p.H + by_) * p.W + bx_) * p.Cin) * 2u;                   \
         _Pragma("unroll") for (int i = 0; i < C::BMAX; ++i) {                                                 \
             if (wave + 4 * i < C::NB) {                                                                       \
-                const bool ok_ = b_ok[i] & ((unsigned)(by_ + b_dy[i]) < (unsigned)p.H) &                      \
+                const bool ok_ = b_ok[i] & dok_ & ((unsigned)(by_ + b_dy[i]) < (unsigned)p.H) &               \
                                  ((unsigned)(bx_ + b_dx[i]) < (unsigned)p.W);                                 \
                 load_to_lds16(rsX, st_ + C::A_BYTES + (wave + 4 * i) * 1024, ok_ ? baseB_ + b_loc[i] : TR_OOB); \
             }                                                                                                 \
@@ -200,7 +210,7 @@ __global__ void __launch_bounds__(256, 2) wgrad_tr_kernel(WgradTrArgs p) {
 #undef LPM_ISSUE
 
     // accumulator element i of a lane: row (i / 4) * 8 + (lane / 32) * 4 + i % 4, column lane % 32
-    const int KhKw = p.Kh * p.Kw;
+    const int KhKw = p.Kd * p.Kh * p.Kw;             // all taps of the filter
     const size_t total = (size_t)p.Cout * KhKw * p.Cin;
     float* out = p.out + (p.splits > 1 ? (size_t)split * p.part_stride : 0);
     const int rq = (lane >> 5) * 4;
@@ -219,7 +229,7 @@ __global__ void __launch_bounds__(256, 2) wgrad_tr_kernel(WgradTrArgs p) {
     if (ci < p.Cin) {
 #pragma unroll
         for (int t = 0; t < TAPS; ++t) {
-            const int tap = TAPS == 9 ? t : (TAPS == 3 ? grp * 3 + t : grp);
+            const int tap = kd * p.Kh * p.Kw + (TAPS == 9 ? t : (TAPS == 3 ? grp2 * 3 + t : grp2));
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int co = co0 + wm * 32 + (i >> 2) * 8 + rq + (i & 3);
@@ -243,7 +253,7 @@ static bool fits32_tr(const ConvGeom& g) {
 }
 
 static bool tr_shape_ok(const ConvGeom& g) {
-    if (g.is3d() || g.Cin % 8 != 0 || g.Cout % 8 != 0 || !fits32_tr(g)) return false;
+    if (g.Cin % 8 != 0 || g.Cout % 8 != 0 || !fits32_tr(g)) return false;
     if (g.Ho < 7 || g.Wo < 7) return false;
     // patches waste the part that hangs over the image edge: at least 3/4 of their pixels must be real
     const int TY = (g.Ho + 7) / 8, TX = (g.Wo + 7) / 8;
@@ -255,9 +265,11 @@ static bool tr_shape_ok(const ConvGeom& g) {
 // fills them to 77 %), and small images still give long runs of whole patches.
 static ConvGeom tr_view(const ConvGeom& g) {
     const int64_t total = g.rows_out();
-    if (g.Kh != 1 || g.Kw != 1 || g.stride != 1 || g.pad != 0 || (total & 7) || (total >> 3) >= ((int64_t)1 << 30)) return g;
+    if (g.Kd != 1 || g.Kh != 1 || g.Kw != 1 || g.stride != 1 || g.pad != 0 || g.pad_d != 0 || (total & 7) || (total >> 3) >= ((int64_t)1 << 30))
+        return g;
     ConvGeom v = g;
     v.m = 1;
+    v.D = v.Do = 1;
     v.H = v.Ho = (int32_t)(total >> 3);
     v.W = v.Wo = 8;
     return v;
@@ -277,8 +289,8 @@ static TrPlan plan_wgrad_tr(const ConvGeom& g) {
     pl.co_tiles = (g.Cout + 63) / 64;
     pl.ci_tiles = (g.Cin + 63) / 64;
     pl.TY = (g.Ho + 7) / 8; pl.TX = (g.Wo + 7) / 8;
-    pl.kt_total = g.m * pl.TY * pl.TX;
-    const int KhKw = g.Kh * g.Kw;
+    pl.kt_total = g.m * g.Do * pl.TY * pl.TX;
+    const int KhKw = g.taps();
     const bool s33 = g.Kh == 3 && g.Kw == 3 && g.stride == 1;
     const int64_t out_bytes = ((int64_t)g.Cout * g.K() + g.Cout) * 4;
     // a filter row per block once both channel counts give several tiles (the shared halo tile then cuts the L2
@@ -321,6 +333,7 @@ hipError_t wgrad_tr(const ConvGeom& g_, const void* x, const void* dz, float* dw
     a.part_stride = (size_t)g.Cout * g.K() + g.Cout;
     a.dz_bytes = (unsigned)(g.rows_out() * g.Cout * 2); a.x_bytes = (unsigned)(g.rows_in() * g.Cin * 2);
     a.Cout = g.Cout; a.Cin = g.Cin; a.Kh = g.Kh; a.Kw = g.Kw;
+    a.Kd = g.Kd; a.D = g.D; a.Do = g.Do; a.pad_d = g.pad_d;
     a.H = g.H; a.W = g.W; a.Ho = g.Ho; a.Wo = g.Wo; a.stride = g.stride; a.pad = g.pad;
     a.TY = pl.TY; a.TX = pl.TX;
     a.kt_total = pl.kt_total; a.kt_per_split = pl.kt_per; a.splits = pl.splits;

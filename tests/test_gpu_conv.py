@@ -75,6 +75,10 @@ SHAPES = [
     G3(2, 5, 5, 5, 64, 256, 3, 2, 1),     # stride 2, long K: split reduction over the taps of a class
     G3(2, 8, 8, 8, 32, 64, 1, 2, 0),      # 1x1x1 stride-2 projection
     G3(2, 4, 4, 4, 128, 128, 3, 1, 1),    # long reduction: split over blocks
+    G3(1, 4, 9, 8, 32, 64, 3, 1, 1),      # 8x8 patches of the output slices: the patch-based weight gradient, one tap per block
+    G3(2, 6, 16, 16, 128, 128, 3, 1, 1),  # ... a filter row per block (27 taps in 9 groups)
+    G3(1, 7, 15, 15, 32, 64, 3, 2, 1),    # ... stride 2, odd extents
+    G3(2, 3, 8, 8, 64, 64, 1, 1, 0),      # ... 1x1x1: the voxels regrouped as one image of full patches
     G3(3, 4, 4, 4, 64, 192, 1, 1, 0),     # 1x1x1 (queries | keys | values of an attention block)
     G3(2, 8, 8, 8, 1, 16, 3, 1, 1),       # one-channel input volume: flattened (tap, channel) weight gradient
     dict(G3(1, 9, 7, 10, 2, 24, 3, 1, 1), h=7, w=10),     # two channels x 27 taps, ragged extents
