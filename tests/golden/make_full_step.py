@@ -36,6 +36,7 @@ CASES = {
     "resnet18_cifar": ([0, 5, 10, 15, 23], 256, 8, False),
     "r50_conv4x": ([0, 19], 64, 4, True),
     "vgg16_224": ([0, 10, 18, 19, 22], 32, 8, False),      # the described plan: conv1-3 | conv4-5 | FC1 | FC2-3
+    "resattnet18_3d": ([0, 3, 8, 18, 29], 6, 3, False),    # volumetric use case: 3x3x3 residual blocks and self-attention blocks
 }
 SEED, LR, MU, BIAS_STD, MOM_STD, NSAMPLE = 17, 0.01, 0.9, 0.05, 1e-3, 1024
 
@@ -79,7 +80,7 @@ def tensors_of(layers, plan, M, dx, ref, params, mom):
 def main(names):
     for name in names:
         plan, batch, M, dx = CASES[name]
-        layers = wl.CONFIGS[name][0]()
+        layers = {**wl.CONFIGS, **wl.EXTRA_CONFIGS}[name][0]()
         t0 = time.time()
         A = run(layers, plan, batch, M, dx, None)
         print(name, "reference run %.0f s" % (time.time() - t0), flush=True)

@@ -39,7 +39,7 @@ def _run(lpm, torch, layers, plan, batch, M, dx, params, mom, xd, ld, gd, lr, mu
     return net
 
 
-@pytest.mark.parametrize("name", ["r50_conv4x", "resnet18_cifar", "vgg16_224"])
+@pytest.mark.parametrize("name", ["r50_conv4x", "resnet18_cifar", "vgg16_224", "resattnet18_3d"])
 def test_full_step_overlapped_bf16(lpm, name):
     import torch
     path = os.path.join(GOLDEN, "full_step_%s.npz" % name)
@@ -48,7 +48,7 @@ def test_full_step_overlapped_bf16(lpm, name):
     plan = [int(v) for v in d["plan"]]
     batch, M, seed = (int(v) for v in d["batch_M_seed"])
     lr, mu, bias_std, mom_std = (float(v) for v in d["hyper"])
-    layers = wl.CONFIGS[name][0]()
+    layers = {**wl.CONFIGS, **wl.EXTRA_CONFIGS}[name][0]()
     params, mom = wl.make_params(layers, seed, bf16=True, bias_std=bias_std, momentum_std=mom_std)
     x, labels, g = wl.make_batch(layers, batch, seed, bf16=True)
     dx = labels is None
