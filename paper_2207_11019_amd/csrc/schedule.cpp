@@ -190,7 +190,8 @@ int32_t fwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStrea
 // wst: stream of the weight phase (see lpm_stage_backward_on)
 // by_layer: the two phases come as separate calls and the weight phase follows the data phase layer by layer
 int32_t bwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStream_t st, hipStream_t wst,
-               int32_t phases = LPM_PHASE_DATA | LPM_PHASE_WEIGHTS, int32_t ver = -1, bool by_layer = false) {
+               int32_t phases = LPM_PHASE_DATA | LPM_PHASE_WEIGHTS, int32_t ver = -1, bool by_layer = false,
+               hipStream_t wst2 = nullptr) {
     lpm_stage* sg = s->st[(size_t)z];
     const int32_t slot = j % s->window;
     const lpm_stage_buffers& b = a.bufs[z];
@@ -206,7 +207,8 @@ int32_t bwd_op(lpm_schedule* s, const RunArgs& a, int32_t z, int32_t j, hipStrea
     return lpm_stage_backward_on(sg, in, b.act_out[slot], dy, dx, ver_params(b, ver), ver_lowp(b, ver), b.stash[slot], b.grads,
                                  ver < 0 ? j > 0 : 0, b.bwd_ws, st, wst, j & 1, phases, staged ? j : -1,
                                  staged ? s->M : 0, by_layer ? j % LPM_MAX_WINDOW : -1,
-                                 (s->cut_fused[(size_t)z] ? LPM_MASK_DX : 0) | (z + 1 < s->Z && s->cut_fused[(size_t)z + 1] ? LPM_DY_IS_DZ : 0));
+                                 (s->cut_fused[(size_t)z] ? LPM_MASK_DX : 0) | (z + 1 < s->Z && s->cut_fused[(size_t)z + 1] ? LPM_DY_IS_DZ : 0),
+                                 wst2);
 }
 
 // ver < 0: the one update of the synchronous step; else U_{z,ver}: version ver -> version ver + 1
@@ -373,6 +375,9 @@ int32_t overlapped_role(lpm_schedule* s, const RunArgs& a, int32_t role, uint64_
         // Asynchronous update: B_{z,j+1} waits for U_{z,j}, so the weight phases and updates are a chain per stage; odd
         // stages take the second stream (each stage keeps its stream, which orders its updates).
         const bool async2 = async && Z > 1 && s->ov_w0 != s->ov_w;
+        // A single stage has the second stream to spare: its weight gradients alternate between the two (ResNet-50
+        // conv4_x: 2.43 -> 2.34 ms per step; the weight phases are the longest of the three chains there).
+        hipStream_t sw_pair = (!async && Z == 1 && s->ov_w0 != s->ov_w) ? s->ov_w0 : nullptr;
         hipStream_t sw_all = sw, sw_0 = s->ov_w0;
         for (int32_t j = 0; j < M; ++j) {
             for (int32_t z = Z - 1; z >= 0; --z) {
@@ -383,7 +388,7 @@ int32_t overlapped_role(lpm_schedule* s, const RunArgs& a, int32_t role, uint64_
                 // gradients follow the data phase layer by layer (the events were recorded before rec_b was published)
                 const bool by_layer = z == 0 && !async;
                 if (!by_layer) LPM_HIP(hipStreamWaitEvent(sw, s->ev_b[i], 0));
-                if ((rc = bwd_op(s, a, z, j, a.sb, sw, LPM_PHASE_WEIGHTS, async ? j : -1, by_layer))) return rc;
+                if ((rc = bwd_op(s, a, z, j, a.sb, sw, LPM_PHASE_WEIGHTS, async ? j : -1, by_layer, sw_pair))) return rc;
                 // whatever follows on this stream (the update, the record that closes the micro-batch) is still ordered
                 // after the whole data phase
                 if (by_layer) LPM_HIP(hipStreamWaitEvent(sw, s->ev_b[i], 0));

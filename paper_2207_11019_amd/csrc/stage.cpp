@@ -227,6 +227,8 @@ extern "C" int32_t lpm_stage_create(const lpm_layer* layers, int32_t L, int32_t 
 lpm_stage::~lpm_stage() {
     if (ev_fork) (void)hipEventDestroy(ev_fork);
     if (ev_join) (void)hipEventDestroy(ev_join);
+    if (ev_w2_fork) (void)hipEventDestroy(ev_w2_fork);
+    if (ev_w2_join) (void)hipEventDestroy(ev_w2_join);
     for (hipEvent_t v : ev_layer) if (v) (void)hipEventDestroy(v);
 }
 
@@ -235,11 +237,15 @@ int32_t lpm_stage_prepare(lpm_stage* s) {
     if (s->side) return LPM_OK;
     hipStream_t st = nullptr;
     LPM_HIP(pooled_stream(next_side_stream_index(), &st));
-    hipEvent_t ej = nullptr, ef = nullptr;
+    hipEvent_t ej = nullptr, ef = nullptr, e2f = nullptr, e2j = nullptr;
     hipError_t e = hipEventCreateWithFlags(&ej, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&ef, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&e2f, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&e2j, hipEventDisableTiming);
     if (e != hipSuccess) {
         if (ej) (void)hipEventDestroy(ej);
+        if (ef) (void)hipEventDestroy(ef);
+        if (e2f) (void)hipEventDestroy(e2f);
         return hip_fail(e, "hipEventCreateWithFlags");
     }
     std::vector<hipEvent_t> evl((size_t)(s->last - s->first) * LPM_MAX_WINDOW, nullptr);
@@ -250,12 +256,14 @@ int32_t lpm_stage_prepare(lpm_stage* s) {
     }
     if (e != hipSuccess) {
         for (hipEvent_t v : evl) if (v) (void)hipEventDestroy(v);
-        (void)hipEventDestroy(ej); (void)hipEventDestroy(ef);
+        (void)hipEventDestroy(ej); (void)hipEventDestroy(ef); (void)hipEventDestroy(e2f); (void)hipEventDestroy(e2j);
         return hip_fail(e, "hipEventCreateWithFlags");
     }
     s->ev_layer = std::move(evl);
     s->ev_join = ej;
     s->ev_fork = ef;
+    s->ev_w2_fork = e2f;
+    s->ev_w2_join = e2j;
     s->side = st;
     return LPM_OK;
 }
@@ -410,10 +418,13 @@ extern "C" int32_t lpm_stage_backward(lpm_stage* s, const void* x, const void* y
 // parity (0 / 1) selects the copy of the gradient / dz area in bwd_ws this pass uses.
 // While `stream` is being captured the weight gradients stay on it and are taken out of its dependency
 // frontier instead.
+// wstream2 (with wstream, eager only): every other weight gradient of the phase runs on this second stream, forked from
+// wstream at the start of the phase and joined back into it before the reduction of the partial sums -- a weight
+// gradient is some 250 blocks and half fixed cost, so two of them side by side fill what one leaves idle.
 int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const void* dy, void* dx,
                               const float* params, const void* lowp, const void* stash, float* grads,
                               int32_t accumulate, void* bwd_ws, void* stream, void* wstream, int32_t parity,
-                              int32_t phases, int32_t fc_slot, int32_t fc_flush, int32_t layer_slot, int32_t boundary) {
+                              int32_t phases, int32_t fc_slot, int32_t fc_flush, int32_t layer_slot, int32_t boundary, void* wstream2) {
     if ((boundary & LPM_MASK_DX) && !lpm_stage_can_mask_dx(s)) return fail(LPM_EINVAL, "internal: this stage cannot mask its input gradient");
     if ((boundary & LPM_DY_IS_DZ) && !lpm_stage_takes_dz(s)) return fail(LPM_EINVAL, "internal: this stage needs the gradient of its output");
     if (layer_slot >= LPM_MAX_WINDOW) return fail(LPM_EINVAL, "internal: layer event slot out of range");
@@ -670,15 +681,27 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
         }
         std::vector<ReduceDesc> red;
         red.reserve(jobs.size());
+        hipStream_t wst2 = (wstream && wstream2 && deferred && jobs.size() > 1) ? (hipStream_t)wstream2 : nullptr;
+        if (wst2 == wst) wst2 = nullptr;
+        if (wst2) {        // ordered after everything the phase's stream holds (the previous micro-batch's reduction reads the areas written now)
+            LPM_HIP(hipEventRecord(s->ev_w2_fork, wst));
+            LPM_HIP(hipStreamWaitEvent(wst2, s->ev_w2_fork, 0));
+        }
+        size_t k = 0;
         for (const WgradJob& j : jobs) {
             ReduceDesc d{};
+            hipStream_t q = (wst2 && (k++ & 1)) ? wst2 : wst;
             if (by_layer)
-                LPM_HIP(hipStreamWaitEvent(wst, s->ev_layer[(size_t)(j.lr - &s->lay[0]) * LPM_MAX_WINDOW + layer_slot], 0));
+                LPM_HIP(hipStreamWaitEvent(q, s->ev_layer[(size_t)(j.lr - &s->lay[0]) * LPM_MAX_WINDOW + layer_slot], 0));
             if (j.bias_g)
                 LPM_HIP(launch_epilogue_bwd(s->dtype, j.lr->g.rows_out(), j.lr->d.cout, j.bias_g, nullptr, nullptr, nullptr, nullptr, 0,
-                                            j.bias_db, acc, (char*)wws + j.lr->wws_off, wst));
-            LPM_HIP(one_wgrad(j, wst, &d));
+                                            j.bias_db, acc, (char*)wws + j.lr->wws_off, q));
+            LPM_HIP(one_wgrad(j, q, &d));
             if (d.splits > 0) red.push_back(d);
+        }
+        if (wst2) {
+            LPM_HIP(hipEventRecord(s->ev_w2_join, wst2));
+            LPM_HIP(hipStreamWaitEvent(wst, s->ev_w2_join, 0));
         }
         if (!red.empty()) LPM_HIP(launch_reduce_batch(red.data(), (int)red.size(), wst));
         if (!wstream) {      // join: the caller's stream is ordered after every weight gradient

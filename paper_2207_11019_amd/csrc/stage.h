@@ -61,6 +61,7 @@ struct lpm_stage {
     // a side stream (borrowed from the library's pool), forked from and joined back into the caller's stream.
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    hipEvent_t ev_w2_fork = nullptr, ev_w2_join = nullptr;      // a weight phase spread over two streams (lpm_stage_backward_on)
     // per weight layer and micro-batch slot: "this layer's output gradient is final" in the data phase's stream
     // order, for schedules that let the weight phase follow the data phase layer by layer
     std::vector<hipEvent_t> ev_layer;      // [(layer - first) * LPM_MAX_WINDOW + slot]
@@ -77,7 +78,7 @@ int32_t lpm_stage_backward_on(lpm_stage* s, const void* x, const void* y, const 
                               const float* params, const void* lowp, const void* stash, float* grads,
                               int32_t accumulate, void* bwd_ws, void* stream, void* wstream, int32_t parity,
                               int32_t phases, int32_t fc_slot = -1, int32_t fc_flush = 0, int32_t layer_slot = -1,
-                              int32_t boundary = 0);
+                              int32_t boundary = 0, void* wstream2 = nullptr);
 // boundary: a schedule may move the ReLU backward of a stage's last layer into the next stage, whose kernel that
 // writes the gradient w.r.t. its input then masks it with that input (the producer's output) -- one kernel less
 // per cut and micro-batch.  LPM_MASK_DX: this stage masks its dx; LPM_DY_IS_DZ: the gradient this stage receives
