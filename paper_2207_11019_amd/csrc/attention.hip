@@ -32,21 +32,56 @@ __device__ inline float att_wave_sum(float v) {
     return v;
 }
 
-// scores of the block's queries against every key, into sc[QB][P] (LDS); qs[QB][C] holds the queries times 1/sqrt(C)
+// eight consecutive elements of a row (the caller has checked that rows start at multiples of eight elements)
+__device__ __forceinline__ void att_ld8(const float* p, float (&v)[8]) {
+    const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void att_ld8(const bf16_t* p, float (&v)[8]) {
+    const uint4 w = *reinterpret_cast<const uint4*>(p);
+    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { v[2 * k] = bf2f((uint16_t)(ww[k] & 0xffffu)); v[2 * k + 1] = bf2f((uint16_t)(ww[k] >> 16)); }
+}
+
+// acc[i] += sum_c row[c] * mat[i][c] for the ATT_QB rows of mat (LDS, [ATT_QB][C]); the row is read 8 channels at a
+// time where C allows (a thread walking its row two bytes at a time was the slowest part of these kernels)
 template <typename T>
-__device__ __forceinline__ void att_scores(const T* __restrict__ xs, int P, int C, int nq, const float* qs, float* sc) {
+__device__ __forceinline__ void att_row_dots(const T* __restrict__ row, int C, const float* mat, float (&acc)[ATT_QB]) {
+    int c = 0;
+    if ((C & 7) == 0) {
+        for (; c < C; c += 8) {
+            float v[8];
+            att_ld8(row + c, v);
+#pragma unroll
+            for (int i = 0; i < ATT_QB; ++i) {
+                const float4 m0 = *reinterpret_cast<const float4*>(mat + i * C + c), m1 = *reinterpret_cast<const float4*>(mat + i * C + c + 4);
+                acc[i] = fmaf(v[0], m0.x, acc[i]); acc[i] = fmaf(v[1], m0.y, acc[i]); acc[i] = fmaf(v[2], m0.z, acc[i]); acc[i] = fmaf(v[3], m0.w, acc[i]);
+                acc[i] = fmaf(v[4], m1.x, acc[i]); acc[i] = fmaf(v[5], m1.y, acc[i]); acc[i] = fmaf(v[6], m1.z, acc[i]); acc[i] = fmaf(v[7], m1.w, acc[i]);
+            }
+        }
+        return;
+    }
+    for (; c < C; ++c) {
+        const float v = ld(row, c);
+#pragma unroll
+        for (int i = 0; i < ATT_QB; ++i) acc[i] = fmaf(v, mat[i * C + c], acc[i]);
+    }
+}
+
+// The per-block score tiles live in LDS position-major: tile[j * ATT_QB + i] for position j and the block's row i, so the
+// eight values of one position are one 32-byte read.
+
+// scores of the block's queries against every key, into sc[P][QB]; qs[QB][C] holds the queries times 1/sqrt(C)
+template <typename T>
+__device__ __forceinline__ void att_scores(const T* __restrict__ xs, int P, int C, const float* qs, float* sc) {
     for (int j = threadIdx.x; j < P; j += blockDim.x) {
-        const T* kj = xs + (int64_t)j * 3 * C + C;
         float acc[ATT_QB];
 #pragma unroll
         for (int i = 0; i < ATT_QB; ++i) acc[i] = 0.f;
-        for (int c = 0; c < C; ++c) {
-            const float kv = ld(kj, c);
+        att_row_dots(xs + (int64_t)j * 3 * C + C, C, qs, acc);
 #pragma unroll
-            for (int i = 0; i < ATT_QB; ++i) acc[i] = fmaf(qs[i * C + c], kv, acc[i]);
-        }
-#pragma unroll
-        for (int i = 0; i < ATT_QB; ++i) if (i < nq) sc[i * P + j] = acc[i];
+        for (int i = 0; i < ATT_QB; ++i) sc[j * ATT_QB + i] = acc[i];
     }
 }
 
@@ -55,22 +90,43 @@ __device__ __forceinline__ void att_softmax_rows(int P, int nq, float* sc, float
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     for (int i = wave; i < nq; i += nw) {
         float mx = -INFINITY;
-        for (int j = lane; j < P; j += 64) mx = fmaxf(mx, sc[i * P + j]);
+        for (int j = lane; j < P; j += 64) mx = fmaxf(mx, sc[j * ATT_QB + i]);
         mx = att_wave_max(mx);
         float se = 0.f;
-        for (int j = lane; j < P; j += 64) { const float e = expf(sc[i * P + j] - mx); sc[i * P + j] = e; se += e; }
+        for (int j = lane; j < P; j += 64) { const float e = expf(sc[j * ATT_QB + i] - mx); sc[j * ATT_QB + i] = e; se += e; }
         se = att_wave_sum(se);
         const float inv = 1.f / se;
-        for (int j = lane; j < P; j += 64) sc[i * P + j] *= inv;
+        for (int j = lane; j < P; j += 64) sc[j * ATT_QB + i] *= inv;
         if (lane == 0) { rmax[i] = mx; rsum[i] = se; }
     }
 }
 
-template <typename T>
+// out[i][c] = sum_j tile[j][i] * rows[j][c] over all positions j, for the block's rows i < n_rows and all channels c:
+// a thread owns a channel and ATT_QB / NP of the rows (NP parts of the block share a channel when C is small), so one
+// element of rows[j] feeds that many multiply-adds.  f(i, c, value) stores.
+template <int NP, typename T, typename F>
+__device__ __forceinline__ void att_mix(const float* tile, const T* __restrict__ rows, int64_t row_stride, int P, int C, int n_rows, F&& f) {
+    constexpr int QPP = ATT_QB / NP;
+    const int cols = blockDim.x / NP, part = threadIdx.x / cols, i0 = part * QPP;
+    for (int c = threadIdx.x - part * cols; c < C; c += cols) {
+        float acc[QPP];
+#pragma unroll
+        for (int i = 0; i < QPP; ++i) acc[i] = 0.f;
+        for (int j = 0; j < P; ++j) {
+            const float v = ld(rows, (int64_t)j * row_stride + c);
+#pragma unroll
+            for (int i = 0; i < QPP; ++i) acc[i] = fmaf(tile[j * ATT_QB + i0 + i], v, acc[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < QPP; ++i) if (i0 + i < n_rows) f(i0 + i, c, acc[i]);
+    }
+}
+
+template <typename T, int NP>
 __global__ void __launch_bounds__(256) attn_fwd_kernel(int P, int C, const T* __restrict__ x, T* __restrict__ y) {
-    extern __shared__ float lds[];
+    extern __shared__ __attribute__((aligned(16))) float lds[];
     float* qs = lds;                    // [QB][C]
-    float* sc = lds + ATT_QB * C;       // [QB][P]
+    float* sc = lds + ATT_QB * C;       // [P][QB]
     __shared__ float rmax[ATT_QB], rsum[ATT_QB];
     const int n = blockIdx.y, i0 = blockIdx.x * ATT_QB, nq = min(ATT_QB, P - i0);
     const T* xs = x + (int64_t)n * P * 3 * C;
@@ -80,28 +136,23 @@ __global__ void __launch_bounds__(256) attn_fwd_kernel(int P, int C, const T* __
         qs[e] = i < nq ? ld(xs, (int64_t)(i0 + i) * 3 * C + c) * scale : 0.f;
     }
     __syncthreads();
-    att_scores(xs, P, C, nq, qs, sc);
+    att_scores(xs, P, C, qs, sc);
     __syncthreads();
     att_softmax_rows(P, nq, sc, rmax, rsum);
     __syncthreads();
-    for (int e = threadIdx.x; e < nq * C; e += blockDim.x) {
-        const int i = e / C, c = e - i * C;
-        float acc = 0.f;
-        for (int j = 0; j < P; ++j) acc = fmaf(sc[i * P + j], ld(xs, (int64_t)j * 3 * C + 2 * C + c), acc);
-        st(y, ((int64_t)n * P + i0 + i) * C + c, acc);
-    }
+    att_mix<NP>(sc, xs + 2 * C, 3 * C, P, C, nq, [&](int i, int c, float v) { st(y, ((int64_t)n * P + i0 + i) * C + c, v); });
 }
 
 // per block of queries: dq, and per query row (max, sum of exp, sum_j A dA) into stats [m][P][3]
-template <typename T>
+template <typename T, int NP>
 __global__ void __launch_bounds__(256) attn_bwd_q_kernel(int P, int C, const T* __restrict__ x, const T* __restrict__ dy,
                                                          T* __restrict__ dx, int accumulate, float* __restrict__ stats) {
-    extern __shared__ float lds[];
+    extern __shared__ __attribute__((aligned(16))) float lds[];
     float* qs = lds;                           // [QB][C] queries / sqrt(C)
     float* gs = qs + ATT_QB * C;               // [QB][C] dy rows
-    float* sc = gs + ATT_QB * C;               // [QB][P] A, then dS
-    float* da = sc + ATT_QB * P;               // [QB][P] dA
-    __shared__ float rmax[ATT_QB], rsum[ATT_QB], rdot[ATT_QB];
+    float* sc = gs + ATT_QB * C;               // [P][QB] A, then dS
+    float* da = sc + ATT_QB * P;               // [P][QB] dA
+    __shared__ float rmax[ATT_QB], rsum[ATT_QB];
     const int n = blockIdx.y, i0 = blockIdx.x * ATT_QB, nq = min(ATT_QB, P - i0);
     const T* xs = x + (int64_t)n * P * 3 * C;
     const T* gy = dy + (int64_t)n * P * C;
@@ -112,20 +163,15 @@ __global__ void __launch_bounds__(256) attn_bwd_q_kernel(int P, int C, const T* 
         gs[e] = i < nq ? ld(gy, (int64_t)(i0 + i) * C + c) : 0.f;
     }
     __syncthreads();
-    att_scores(xs, P, C, nq, qs, sc);
+    att_scores(xs, P, C, qs, sc);
     // dA[i][j] = dy_i . v_j
     for (int j = threadIdx.x; j < P; j += blockDim.x) {
-        const T* vj = xs + (int64_t)j * 3 * C + 2 * C;
         float acc[ATT_QB];
 #pragma unroll
         for (int i = 0; i < ATT_QB; ++i) acc[i] = 0.f;
-        for (int c = 0; c < C; ++c) {
-            const float vv = ld(vj, c);
+        att_row_dots(xs + (int64_t)j * 3 * C + 2 * C, C, gs, acc);
 #pragma unroll
-            for (int i = 0; i < ATT_QB; ++i) acc[i] = fmaf(gs[i * C + c], vv, acc[i]);
-        }
-#pragma unroll
-        for (int i = 0; i < ATT_QB; ++i) if (i < nq) da[i * P + j] = acc[i];
+        for (int i = 0; i < ATT_QB; ++i) da[j * ATT_QB + i] = acc[i];
     }
     __syncthreads();
     att_softmax_rows(P, nq, sc, rmax, rsum);
@@ -134,36 +180,32 @@ __global__ void __launch_bounds__(256) attn_bwd_q_kernel(int P, int C, const T* 
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
         for (int i = wave; i < nq; i += nw) {
             float r = 0.f;
-            for (int j = lane; j < P; j += 64) r = fmaf(sc[i * P + j], da[i * P + j], r);
+            for (int j = lane; j < P; j += 64) r = fmaf(sc[j * ATT_QB + i], da[j * ATT_QB + i], r);
             r = att_wave_sum(r);
-            for (int j = lane; j < P; j += 64) sc[i * P + j] *= (da[i * P + j] - r);
+            for (int j = lane; j < P; j += 64) sc[j * ATT_QB + i] *= (da[j * ATT_QB + i] - r);
             if (lane == 0) {
-                rdot[i] = r;
                 float* s3 = stats + ((int64_t)n * P + i0 + i) * 3;
                 s3[0] = rmax[i]; s3[1] = rsum[i]; s3[2] = r;
             }
         }
     }
     __syncthreads();
-    for (int e = threadIdx.x; e < nq * C; e += blockDim.x) {
-        const int i = e / C, c = e - i * C;
-        float acc = 0.f;
-        for (int j = 0; j < P; ++j) acc = fmaf(sc[i * P + j], ld(xs, (int64_t)j * 3 * C + C + c), acc);
+    att_mix<NP>(sc, xs + C, 3 * C, P, C, nq, [&](int i, int c, float v) {
         const int64_t o = ((int64_t)n * P + i0 + i) * 3 * C + c;
-        acc *= scale;
-        st(dx, o, accumulate ? acc + ld(dx, o) : acc);
-    }
+        v *= scale;
+        st(dx, o, accumulate ? v + ld(dx, o) : v);
+    });
 }
 
 // per block of keys: dk and dv
-template <typename T>
+template <typename T, int NP>
 __global__ void __launch_bounds__(256) attn_bwd_kv_kernel(int P, int C, const T* __restrict__ x, const T* __restrict__ dy,
                                                           T* __restrict__ dx, int accumulate, const float* __restrict__ stats) {
-    extern __shared__ float lds[];
+    extern __shared__ __attribute__((aligned(16))) float lds[];
     float* ks = lds;                           // [QB][C] keys / sqrt(C)
     float* vs = ks + ATT_QB * C;               // [QB][C] values
-    float* aa = vs + ATT_QB * C;               // [QB][P] A[i][j] for the block's keys j, all queries i
-    float* ds = aa + ATT_QB * P;               // [QB][P] dS[i][j]
+    float* aa = vs + ATT_QB * C;               // [P][QB] A[i][j] for the block's keys j, all queries i
+    float* ds = aa + ATT_QB * P;               // [P][QB] dS[i][j]
     const int n = blockIdx.y, j0 = blockIdx.x * ATT_QB, nk = min(ATT_QB, P - j0);
     const T* xs = x + (int64_t)n * P * 3 * C;
     const T* gy = dy + (int64_t)n * P * C;
@@ -175,46 +217,49 @@ __global__ void __launch_bounds__(256) attn_bwd_kv_kernel(int P, int C, const T*
     }
     __syncthreads();
     for (int i = threadIdx.x; i < P; i += blockDim.x) {
-        const T* qi = xs + (int64_t)i * 3 * C;
-        const T* gi = gy + (int64_t)i * C;
         float s[ATT_QB], d[ATT_QB];
 #pragma unroll
         for (int j = 0; j < ATT_QB; ++j) { s[j] = 0.f; d[j] = 0.f; }
-        for (int c = 0; c < C; ++c) {
-            const float qv = ld(qi, c), gv = ld(gi, c);
-#pragma unroll
-            for (int j = 0; j < ATT_QB; ++j) { s[j] = fmaf(qv, ks[j * C + c], s[j]); d[j] = fmaf(gv, vs[j * C + c], d[j]); }
-        }
+        att_row_dots(xs + (int64_t)i * 3 * C, C, ks, s);
+        att_row_dots(gy + (int64_t)i * C, C, vs, d);
         const float* s3 = stats + ((int64_t)n * P + i) * 3;
         const float mx = s3[0], inv = 1.f / s3[1], r = s3[2];
 #pragma unroll
         for (int j = 0; j < ATT_QB; ++j) {
             const float a = expf(s[j] - mx) * inv;
-            aa[j * P + i] = a;
-            ds[j * P + i] = a * (d[j] - r);
+            aa[i * ATT_QB + j] = a;
+            ds[i * ATT_QB + j] = a * (d[j] - r);
         }
     }
     __syncthreads();
-    for (int e = threadIdx.x; e < nk * C; e += blockDim.x) {
-        const int j = e / C, c = e - j * C;
-        float dv = 0.f, dk = 0.f;
-        for (int i = 0; i < P; ++i) {
-            dv = fmaf(aa[j * P + i], ld(gy, (int64_t)i * C + c), dv);
-            dk = fmaf(ds[j * P + i], ld(xs, (int64_t)i * 3 * C + c), dk);
-        }
-        dk *= scale;
-        const int64_t ok = ((int64_t)n * P + j0 + j) * 3 * C + C + c, ov = ok + C;
-        st(dx, ok, accumulate ? dk + ld(dx, ok) : dk);
-        st(dx, ov, accumulate ? dv + ld(dx, ov) : dv);
-    }
+    att_mix<NP>(aa, gy, C, P, C, nk, [&](int j, int c, float v) {
+        const int64_t o = ((int64_t)n * P + j0 + j) * 3 * C + 2 * C + c;
+        st(dx, o, accumulate ? v + ld(dx, o) : v);
+    });
+    att_mix<NP>(ds, xs, 3 * C, P, C, nk, [&](int j, int c, float v) {
+        const int64_t o = ((int64_t)n * P + j0 + j) * 3 * C + C + c;
+        v *= scale;
+        st(dx, o, accumulate ? v + ld(dx, o) : v);
+    });
 }
+
+// parts of a block that share a channel in att_mix: as many as leave every thread a channel
+static int att_parts(int C) { return C <= 32 ? 8 : C <= 64 ? 4 : C <= 128 ? 2 : 1; }
+#define LPM_ATT_NP(NP_, ...)                                       \
+    do {                                                           \
+        if ((NP_) == 8) { constexpr int NP = 8; __VA_ARGS__; }     \
+        else if ((NP_) == 4) { constexpr int NP = 4; __VA_ARGS__; } \
+        else if ((NP_) == 2) { constexpr int NP = 2; __VA_ARGS__; } \
+        else { constexpr int NP = 1; __VA_ARGS__; }                \
+    } while (0)
 
 hipError_t launch_attn_fwd(int dtype, int32_t m, int32_t P, int32_t C, const void* x, void* y, hipStream_t st) {
     if (!attn_ok(P, C)) return hipErrorInvalidValue;
     const dim3 grid((unsigned)((P + ATT_QB - 1) / ATT_QB), (unsigned)m);
     const size_t lds = (size_t)ATT_QB * (C + P) * sizeof(float);
-    if (dtype == LPM_BF16) hipLaunchKernelGGL(attn_fwd_kernel<bf16_t>, grid, dim3(256), lds, st, P, C, (const bf16_t*)x, (bf16_t*)y);
-    else hipLaunchKernelGGL(attn_fwd_kernel<float>, grid, dim3(256), lds, st, P, C, (const float*)x, (float*)y);
+    const int np = att_parts(C);
+    if (dtype == LPM_BF16) LPM_ATT_NP(np, hipLaunchKernelGGL((attn_fwd_kernel<bf16_t, NP>), grid, dim3(256), lds, st, P, C, (const bf16_t*)x, (bf16_t*)y));
+    else LPM_ATT_NP(np, hipLaunchKernelGGL((attn_fwd_kernel<float, NP>), grid, dim3(256), lds, st, P, C, (const float*)x, (float*)y));
     return hipGetLastError();
 }
 
@@ -223,16 +268,17 @@ hipError_t launch_attn_bwd(int dtype, int32_t m, int32_t P, int32_t C, const voi
     if (!attn_ok(P, C) || !ws) return hipErrorInvalidValue;
     const dim3 grid((unsigned)((P + ATT_QB - 1) / ATT_QB), (unsigned)m);
     const size_t lds = (size_t)ATT_QB * (2 * C + 2 * P) * sizeof(float);
+    const int np = att_parts(C);
     if (dtype == LPM_BF16) {
-        hipLaunchKernelGGL(attn_bwd_q_kernel<bf16_t>, grid, dim3(256), lds, st, P, C, (const bf16_t*)x, (const bf16_t*)dy, (bf16_t*)dx,
-                           accumulate, (float*)ws);
-        hipLaunchKernelGGL(attn_bwd_kv_kernel<bf16_t>, grid, dim3(256), lds, st, P, C, (const bf16_t*)x, (const bf16_t*)dy, (bf16_t*)dx,
-                           accumulate, (const float*)ws);
+        LPM_ATT_NP(np, hipLaunchKernelGGL((attn_bwd_q_kernel<bf16_t, NP>), grid, dim3(256), lds, st, P, C, (const bf16_t*)x, (const bf16_t*)dy,
+                                          (bf16_t*)dx, accumulate, (float*)ws));
+        LPM_ATT_NP(np, hipLaunchKernelGGL((attn_bwd_kv_kernel<bf16_t, NP>), grid, dim3(256), lds, st, P, C, (const bf16_t*)x, (const bf16_t*)dy,
+                                          (bf16_t*)dx, accumulate, (const float*)ws));
     } else {
-        hipLaunchKernelGGL(attn_bwd_q_kernel<float>, grid, dim3(256), lds, st, P, C, (const float*)x, (const float*)dy, (float*)dx,
-                           accumulate, (float*)ws);
-        hipLaunchKernelGGL(attn_bwd_kv_kernel<float>, grid, dim3(256), lds, st, P, C, (const float*)x, (const float*)dy, (float*)dx,
-                           accumulate, (const float*)ws);
+        LPM_ATT_NP(np, hipLaunchKernelGGL((attn_bwd_q_kernel<float, NP>), grid, dim3(256), lds, st, P, C, (const float*)x, (const float*)dy,
+                                          (float*)dx, accumulate, (float*)ws));
+        LPM_ATT_NP(np, hipLaunchKernelGGL((attn_bwd_kv_kernel<float, NP>), grid, dim3(256), lds, st, P, C, (const float*)x, (const float*)dy,
+                                          (float*)dx, accumulate, (const float*)ws));
     }
     return hipGetLastError();
 }
