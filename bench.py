@@ -165,6 +165,7 @@ def main():
     ap.add_argument("--workload", default="r50_conv4x")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-layer-table", action="store_true", help="skip the per-contraction timing table")
+    ap.add_argument("--layer-table", default=None, metavar="FILE", help="also write the per-contraction timing table (JSON) to FILE")
     ap.add_argument("--no-others", action="store_true", help="skip the other workloads (by_workload) and the memory-bound kernels")
     ap.add_argument("--eager", action="store_true", help="enqueue the step kernel by kernel only, no graph replay")
     ap.add_argument("--pmc-probe", default=None, metavar="WHAT",
@@ -425,9 +426,8 @@ def main():
         "roofline": roof,
         "cpu_baseline": cpu,
     }
-    if table:
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "layer_table_%s.json" % args.workload), "w") as f:
+    if table and args.layer_table:
+        with open(args.layer_table, "w") as f:
             json.dump(table, f, indent=1)
     print(json.dumps(out))
     return 0
