@@ -389,7 +389,8 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import lpm_oracle as orc
         import copy
-        n_mb = {"vgg16_cifar": 2, "lenet": M}.get(args.workload, 1)
+        # a sample of 10-30 s of host work: the whole step of the ResNet-50 stage (4 micro-batches, about 18 s on 16 cores)
+        n_mb = {"vgg16_cifar": M, "lenet": M, "r50_conv4x": M, "resnet18_cifar": 2, "resattnet18_3d": M}.get(args.workload, 1)
         xs = W.x[: n_mb * m]
         ls = W.labels[: n_mb * m] if W.labels is not None else None
         gs = W.g_up[: n_mb * m] if W.g_up is not None else None
