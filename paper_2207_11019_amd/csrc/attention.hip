@@ -112,7 +112,23 @@ __device__ __forceinline__ void att_mix(const float* tile, const T* __restrict__
         float acc[QPP];
 #pragma unroll
         for (int i = 0; i < QPP; ++i) acc[i] = 0.f;
-        for (int j = 0; j < P; ++j) {
+        // Sixteen positions per trip, their loads issued together before the first is used: one memory latency per sixteen
+        // positions (left to itself the compiler keeps four loads in flight; asked to unroll further it chains the
+        // 2-byte loads through one register and waits for each).
+        int j = 0;
+        for (; j + 16 <= P; j += 16) {
+            T raw[16];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) raw[k] = rows[(int64_t)(j + k) * row_stride + c];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                const float v = ld(raw, k);
+#pragma unroll
+                for (int i = 0; i < QPP; ++i) acc[i] = fmaf(tile[(j + k) * ATT_QB + i0 + i], v, acc[i]);
+            }
+        }
+        for (; j < P; ++j) {
             const float v = ld(rows, (int64_t)j * row_stride + c);
 #pragma unroll
             for (int i = 0; i < QPP; ++i) acc[i] = fmaf(tile[j * ATT_QB + i0 + i], v, acc[i]);
